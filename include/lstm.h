@@ -1,0 +1,147 @@
+/*
+ * lstm.h -- C ABI of the MI355X (gfx950) stacked-LSTM library.
+ *
+ * The library computes the forward pass and full back-propagation through time
+ * of the network that Section 2 of Appleyard, Kocisky & Blunsom, "Optimizing
+ * Performance of Recurrent Neural Networks on GPUs" (arXiv 1604.01946) studies:
+ * a standard four-gate LSTM without peepholes,
+ *
+ *     i_t = sigma(W_i x_t + R_i h_{t-1} + b_i)      f_t = sigma(W_f x_t + R_f h_{t-1} + b_f)
+ *     o_t = sigma(W_o x_t + R_o h_{t-1} + b_o)      c'_t = tanh(W_c x_t + R_c h_{t-1} + b_c)
+ *     c_t = f_t o c_{t-1} + i_t o c'_t              h_t = o_t o tanh(c_t)
+ *
+ * stacked as Section 2.4 describes (layer l at step t reads h of layer l-1 at
+ * step t).  The two subscript misprints of the printed equations are read the
+ * standard way (x_t in the first line, previous cell state c_{t-1} in the fifth).
+ *
+ * Conventions common to every call
+ *   - all tensors are fp32, contiguous, row-major (last index fastest);
+ *   - every pointer is a DEVICE pointer owned by the caller and 16-byte aligned;
+ *     the library never allocates or frees device memory in lstm_forward /
+ *     lstm_backward (helper streams and events are created on first use and
+ *     released by lstm_shutdown);
+ *   - gate order along every 4H axis (W, R, b, dW, dR, db): i, f, o, c' -- the order
+ *     in which Section 2 lists the equations;
+ *   - one bias vector per gate, as printed;
+ *   - W is the concatenation of layer 0's [4H][I] matrix and the [4H][H] matrices of
+ *     layers 1..L-1; R is [L][4H][H]; b is [L][4H];
+ *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); internal helper streams fork from it and join back to it, and
+ *     no call synchronises the host;
+ *   - return value: LSTM_OK or an LSTM_* error code.  Arguments are validated before
+ *     any GPU work; on error nothing has been launched except for LSTM_HIP_ERROR /
+ *     LSTM_INTERNAL, which can surface after partial execution.
+ */
+#ifndef LSTM_MI355X_H
+#define LSTM_MI355X_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---------------------------------------------------------------- */
+#define LSTM_OK                0
+#define LSTM_INVALID_ARG       1 /* non-positive dimension, required pointer NULL, misaligned pointer, bad flags */
+#define LSTM_BUFFER_TOO_SMALL  2 /* workspace_bytes below lstm_workspace_bytes() */
+#define LSTM_HIP_ERROR         3 /* a HIP runtime call or kernel launch failed */
+#define LSTM_INTERNAL          4 /* a kernel's bounded wait expired (persistent path watchdog) */
+#define LSTM_UNSUPPORTED       5 /* the forced path cannot run this shape on this device */
+
+/* ---- flags: bits 0..3 select the execution path ---------------------------------------
+ * The paths are the rungs of the paper's optimisation ladder (Table 1) rebuilt for
+ * gfx950, plus the on-chip-weights variant that Section 4 names as future work.  */
+#define LSTM_PATH_AUTO        0u /* persistent when the shape fits, else wavefront */
+#define LSTM_PATH_NAIVE       1u /* Section 2.1 starting point: one kernel per operation, eight per-gate GEMMs per cell */
+#define LSTM_PATH_GROUPED     2u /* + the four gates stacked into one GEMM per operand (optimisation 1) */
+#define LSTM_PATH_FUSED       3u /* + one fused point-wise kernel per cell (optimisation 3) */
+#define LSTM_PATH_STEP        4u /* + time-batched input GEMM per layer and a fused recurrent-GEMM+point-wise
+                                    step kernel, layers one after the other (optimisations 4, 5) */
+#define LSTM_PATH_WAVEFRONT   5u /* + layers overlapped on HIP streams in diagonal order (optimisations 2, 6) */
+#define LSTM_PATH_PERSISTENT  6u /* one cooperative kernel for the whole recurrence: weights resident in
+                                    registers, steps ordered by flags in device memory (Section 4) */
+#define LSTM_PATH_MASK        0xFu
+
+/* Bytes of the opaque `reserve` buffer that lstm_forward fills for lstm_backward.
+ * Returns 0 if any dimension is non-positive. */
+size_t lstm_reserve_bytes(int L, int T, int B, int I, int H);
+
+/* Bytes of scratch that lstm_forward / lstm_backward need (the maximum over both and
+ * over all paths).  Contents need not survive between calls.  Returns 0 on invalid
+ * dimensions. */
+size_t lstm_workspace_bytes(int L, int T, int B, int I, int H);
+
+/*
+ * Forward pass (Section 2 equations; execution per Sections 2.2-2.4 and 4).
+ *   x   [T][B][I]  input sequence, time-major
+ *   h0  [L][B][H]  initial hidden state, NULL = zeros
+ *   c0  [L][B][H]  initial cell state,   NULL = zeros
+ *   W, R, b        parameters, layouts above
+ *   y   [T][B][H]  out: hidden state of the top layer at every step
+ *   hT  [L][B][H]  out: hidden state of every layer after the last step, NULL = not written
+ *   cT  [L][B][H]  out: cell state of every layer after the last step,   NULL = not written
+ *   reserve        out: lstm_reserve_bytes() bytes kept for lstm_backward; NULL = inference
+ *                  (the same data then lives in the workspace and is discarded)
+ *   workspace      scratch of at least lstm_workspace_bytes() bytes
+ */
+int lstm_forward(int L, int T, int B, int I, int H,
+                 const float* x, const float* h0, const float* c0,
+                 const float* W, const float* R, const float* b,
+                 float* y, float* hT, float* cT,
+                 void* reserve, void* workspace, size_t workspace_bytes,
+                 void* stream, unsigned flags);
+
+/*
+ * Backward pass: gradients of  <dy,y> + <dhT,hT> + <dcT,cT>  with respect to every input
+ * of lstm_forward.  The paper gives no backward equations; this is the chain rule through
+ * the Section 2 equations, with the data-gradient products grouped over the four gates
+ * (Section 2.1) and the weight gradients formed as one large product per matrix after all
+ * propagation is complete (Section 2.6).
+ *   x, h0, c0, W, R  the arguments given to lstm_forward (h0/c0 may be NULL again)
+ *   reserve          as written by lstm_forward with the same dimensions
+ *   dy   [T][B][H]   gradient with respect to y
+ *   dhT, dcT [L][B][H] gradients with respect to hT, cT; NULL = zeros
+ *   dx   [T][B][I]   out, NULL = skipped
+ *   dh0, dc0 [L][B][H] out, NULL = skipped
+ *   dW, dR, db       out, shaped like W, R, b; OVERWRITTEN (not accumulated into)
+ */
+int lstm_backward(int L, int T, int B, int I, int H,
+                  const float* x, const float* h0, const float* c0,
+                  const float* W, const float* R, const void* reserve,
+                  const float* dy, const float* dhT, const float* dcT,
+                  float* dx, float* dh0, float* dc0,
+                  float* dW, float* dR, float* db,
+                  void* workspace, size_t workspace_bytes,
+                  void* stream, unsigned flags);
+
+/*
+ * C[M][N] (row stride ldc) = A * B, or += when accumulate != 0, on the fp32 matrix cores.
+ * This is the time-batched product of Section 2.3 (input projections of many steps in one
+ * call) and of Section 2.6 (weight gradients); the LSTM calls use it internally and it is
+ * exported so that tests can check it alone.  Element (m,k) of A is A[m*sAm + k*sAk],
+ * element (k,n) of B is B[k*sBk + n*sBn]; one stride of each operand must be 1.
+ */
+int lstm_gemm_f32(int M, int N, int K,
+                  const float* A, long sAm, long sAk,
+                  const float* B, long sBk, long sBn,
+                  float* C, long ldc, int accumulate, void* stream);
+
+/* Which path LSTM_PATH_AUTO resolves to for this shape on the current device
+ * (returns an LSTM_PATH_* value; LSTM_PATH_AUTO on invalid dimensions). */
+unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* lstm_status_string(int status);
+
+/* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
+const char* lstm_last_error(void);
+
+/* Destroys the helper streams and events the library created.  Safe to call repeatedly;
+ * the next call re-creates them. */
+void lstm_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSTM_MI355X_H */

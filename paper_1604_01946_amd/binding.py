@@ -1,0 +1,138 @@
+"""ctypes binding of the C ABI declared in include/lstm.h.
+
+Argument marshalling only: every function here has the name and argument order of
+the C entry point it forwards to, accepts torch tensors (their device pointer is
+passed) or None for optional pointers, and returns the C status code.  No LSTM
+arithmetic happens in Python, and there is no fallback: if the compiled library
+is missing, importing a symbol from it raises.
+"""
+import ctypes
+import os
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "liblstm_mi355x.so")
+
+LSTM_OK = 0
+LSTM_INVALID_ARG = 1
+LSTM_BUFFER_TOO_SMALL = 2
+LSTM_HIP_ERROR = 3
+LSTM_INTERNAL = 4
+LSTM_UNSUPPORTED = 5
+
+LSTM_PATH_AUTO = 0
+LSTM_PATH_NAIVE = 1
+LSTM_PATH_GROUPED = 2
+LSTM_PATH_FUSED = 3
+LSTM_PATH_STEP = 4
+LSTM_PATH_WAVEFRONT = 5
+LSTM_PATH_PERSISTENT = 6
+PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wavefront", 6: "persistent"}
+
+EXPORTS = [
+    "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
+    "lstm_auto_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
+]
+
+_lib = None
+
+
+class LstmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({lstm_status_string(status)}) {lstm_last_error()}")
+
+
+def library():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_1604_01946_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        i, p, z, u, l = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint, ctypes.c_long
+        lib.lstm_reserve_bytes.restype = z
+        lib.lstm_reserve_bytes.argtypes = [i] * 5
+        lib.lstm_workspace_bytes.restype = z
+        lib.lstm_workspace_bytes.argtypes = [i] * 5
+        lib.lstm_forward.restype = i
+        lib.lstm_forward.argtypes = [i] * 5 + [p] * 11 + [z, p, u]
+        lib.lstm_backward.restype = i
+        lib.lstm_backward.argtypes = [i] * 5 + [p] * 16 + [z, p, u]
+        lib.lstm_gemm_f32.restype = i
+        lib.lstm_gemm_f32.argtypes = [i, i, i, p, l, l, p, l, l, p, l, i, p]
+        lib.lstm_auto_path.restype = u
+        lib.lstm_auto_path.argtypes = [i] * 6
+        lib.lstm_status_string.restype = ctypes.c_char_p
+        lib.lstm_status_string.argtypes = [i]
+        lib.lstm_last_error.restype = ctypes.c_char_p
+        lib.lstm_last_error.argtypes = []
+        lib.lstm_shutdown.restype = None
+        lib.lstm_shutdown.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    """Device (or raw) address of a tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def lstm_reserve_bytes(L, T, B, I, H):
+    return library().lstm_reserve_bytes(L, T, B, I, H)
+
+
+def lstm_workspace_bytes(L, T, B, I, H):
+    return library().lstm_workspace_bytes(L, T, B, I, H)
+
+
+def lstm_status_string(status):
+    return library().lstm_status_string(status).decode()
+
+
+def lstm_last_error():
+    return library().lstm_last_error().decode()
+
+
+def lstm_shutdown():
+    library().lstm_shutdown()
+
+
+def lstm_auto_path(L, T, B, I, H, backward):
+    return library().lstm_auto_path(L, T, B, I, H, int(backward))
+
+
+def lstm_forward(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, workspace, workspace_bytes,
+                 stream=None, flags=0):
+    return library().lstm_forward(L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(c0), _ptr(W), _ptr(R), _ptr(b),
+                                  _ptr(y), _ptr(hT), _ptr(cT), _ptr(reserve), _ptr(workspace), workspace_bytes,
+                                  _stream(stream), flags)
+
+
+def lstm_backward(L, T, B, I, H, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db,
+                  workspace, workspace_bytes, stream=None, flags=0):
+    return library().lstm_backward(L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(c0), _ptr(W), _ptr(R), _ptr(reserve),
+                                   _ptr(dy), _ptr(dhT), _ptr(dcT), _ptr(dx), _ptr(dh0), _ptr(dc0),
+                                   _ptr(dW), _ptr(dR), _ptr(db), _ptr(workspace), workspace_bytes,
+                                   _stream(stream), flags)
+
+
+def lstm_gemm_f32(M, N, K, A, sAm, sAk, Bm, sBk, sBn, C, ldc, accumulate, stream=None):
+    return library().lstm_gemm_f32(M, N, K, _ptr(A), sAm, sAk, _ptr(Bm), sBk, sBn, _ptr(C), ldc, int(accumulate),
+                                   _stream(stream))
+
+
+def check(status, where="lstm"):
+    if status != LSTM_OK:
+        raise LstmError(status, where)

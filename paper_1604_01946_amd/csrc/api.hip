@@ -1,0 +1,147 @@
+// C ABI of the LSTM library: argument validation, workspace carving and the host-side
+// schedules of every execution path (see include/lstm.h for the contract).
+#include "../../include/lstm.h"
+#include "internal.h"
+#include "schedule.h"
+
+#include <string.h>
+#include <stdio.h>
+#include <string>
+
+using namespace lstm;
+
+namespace lstm {
+thread_local std::string g_last_error;
+
+hipError_t record(hipError_t e, const char* what) {
+  if (e != hipSuccess) {
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+  }
+  return e;
+}
+}  // namespace lstm
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool dims_ok(int L, int T, int B, int I, int H) { return L > 0 && T > 0 && B > 0 && I > 0 && H > 0; }
+
+}  // namespace
+
+namespace lstm {
+
+size_t reserve_bytes(const Dims& d) { return (size_t)d.L * d.T * d.B * 6 * d.H * sizeof(float); }
+
+WsLayout ws_layout(const Dims& d) {
+  WsLayout w;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, H = d.H, L = d.L;
+  const size_t Bp = align_up((size_t)d.B, 16);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  w.P = take(L * TB * G * 4);
+  w.dx = take(L * TB * H * 4);
+  w.RT = take(L * H * G * 4);
+  w.state = take(4 * L * d.B * H * 4);
+  w.dbpart = take(L * 64 * G * 4);
+  w.scratch = take(8 * (size_t)d.B * G * 4);
+  w.xchg = take(L * (size_t)d.T * G * Bp * 4);
+  w.flags = take((2 * L * ((size_t)d.T + 2) + 64) * 4);
+  w.resv = take(reserve_bytes(d));
+  w.total = off;
+  return w;
+}
+
+}  // namespace lstm
+
+extern "C" {
+
+size_t lstm_reserve_bytes(int L, int T, int B, int I, int H) {
+  if (!dims_ok(L, T, B, I, H)) return 0;
+  return reserve_bytes(Dims{L, T, B, I, H});
+}
+
+size_t lstm_workspace_bytes(int L, int T, int B, int I, int H) {
+  if (!dims_ok(L, T, B, I, H)) return 0;
+  return ws_layout(Dims{L, T, B, I, H}).total;
+}
+
+const char* lstm_status_string(int status) {
+  switch (status) {
+    case LSTM_OK: return "ok";
+    case LSTM_INVALID_ARG: return "invalid argument (non-positive dimension, NULL or misaligned pointer, bad flags)";
+    case LSTM_BUFFER_TOO_SMALL: return "workspace smaller than lstm_workspace_bytes()";
+    case LSTM_HIP_ERROR: return "HIP runtime error (see lstm_last_error())";
+    case LSTM_INTERNAL: return "internal error: a kernel's bounded wait expired";
+    case LSTM_UNSUPPORTED: return "the forced path does not support this shape on this device";
+    default: return "unknown status";
+  }
+}
+
+const char* lstm_last_error(void) { return g_last_error.c_str(); }
+
+void lstm_shutdown(void) { release_helpers(); }
+
+unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward) {
+  if (!dims_ok(L, T, B, I, H)) return LSTM_PATH_AUTO;
+  return resolve_auto_path(Dims{L, T, B, I, H}, backward != 0);
+}
+
+int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const float* B, long sBk, long sBn,
+                  float* C, long ldc, int accumulate, void* stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C || ldc < N) return LSTM_INVALID_ARG;
+  if ((sAm != 1 && sAk != 1) || (sBk != 1 && sBn != 1)) return LSTM_INVALID_ARG;
+  GemmProblem p{A, B, C, M, N, K, sAm, sAk, sBk, sBn, ldc, accumulate};
+  if (record(launch_gemm_group(&p, 1, (hipStream_t)stream), "gemm launch") != hipSuccess) return LSTM_HIP_ERROR;
+  return LSTM_OK;
+}
+
+int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
+                 const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
+                 size_t workspace_bytes, void* stream, unsigned flags) {
+  g_last_error.clear();
+  if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
+  if (!x || !W || !R || !b || !y || !workspace) return LSTM_INVALID_ARG;
+  const void* ptrs[] = {x, h0, c0, W, R, b, y, hT, cT, reserve, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LSTM_INVALID_ARG;
+  if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
+  const Dims d{L, T, B, I, H};
+  const WsLayout w = ws_layout(d);
+  if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
+
+  FwdArgs a{d, x, h0, c0, W, R, b, y, hT, cT,
+            reserve ? (float*)reserve : (float*)((char*)workspace + w.resv), (char*)workspace, w, (hipStream_t)stream};
+  unsigned path = flags & LSTM_PATH_MASK;
+  if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, false);
+  return run_forward(a, path);
+}
+
+int lstm_backward(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0,
+                  const float* W, const float* R, const void* reserve, const float* dy, const float* dhT,
+                  const float* dcT, float* dx, float* dh0, float* dc0, float* dW, float* dR, float* db,
+                  void* workspace, size_t workspace_bytes, void* stream, unsigned flags) {
+  g_last_error.clear();
+  if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
+  if (!x || !W || !R || !reserve || !dy || !dW || !dR || !db || !workspace) return LSTM_INVALID_ARG;
+  const void* ptrs[] = {x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LSTM_INVALID_ARG;
+  if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
+  const Dims d{L, T, B, I, H};
+  const WsLayout w = ws_layout(d);
+  if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
+
+  BwdArgs a{d, x, h0, c0, W, R, (const float*)reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db,
+            (char*)workspace, w, (hipStream_t)stream};
+  unsigned path = flags & LSTM_PATH_MASK;
+  if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, true);
+  return run_backward(a, path);
+}
+
+}  // extern "C"

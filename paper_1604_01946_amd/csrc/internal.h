@@ -1,0 +1,96 @@
+// Internal declarations shared by the HIP translation units of the LSTM library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lstm {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- GEMM (gemm.hip)
+// One dense product C[M][N] (+)= A*B with arbitrary (unit in one dimension) strides.
+struct GemmProblem {
+  const float* A;
+  const float* B;
+  float* C;
+  int M, N, K;
+  long sAm, sAk, sBk, sBn, ldc;
+  int accumulate;
+};
+constexpr int kMaxGemmGroup = 16;
+// A group of independent products executed by one launch (Section 2.6: the weight
+// update products have no dependencies, so they can all be in flight together).
+hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream);
+
+// ---------------------------------------------------------------- point-wise / layout kernels (pointwise.hip)
+enum EwOp : int {
+  EW_ADD = 0,       // out = a + b
+  EW_ADD_BIAS = 1,  // out[r][c] = a[r][c] + b[c]
+  EW_SIGMOID = 2,   // out = sigma(a)
+  EW_TANH = 3,      // out = tanh(a)
+  EW_MUL = 4,       // out = a * b
+  EW_FMA_MUL = 5,   // out = out + a * b
+  EW_COPY = 6,
+};
+// Strided 2-D element-wise op over [rows][cols] (one kernel per operation: the
+// Section 2.1 starting point).
+hipError_t launch_ew(EwOp op, float* out, long ldo, const float* a, long lda, const float* b, long ldb,
+                     int rows, int cols, hipStream_t stream);
+
+// Fused forward point-wise update (Section 2.2.2): gates from pre-activations, cell and hidden update.
+// pre1 (+ pre2 if non-null) [B][4H], bias [4H], c_prev [B][H] (may be null = zeros).
+hipError_t launch_pointwise_fwd(const float* pre1, const float* pre2, const float* bias, const float* c_prev,
+                                float* h_out, float* c_out, float* gates_out, float* h_out2, float* c_out2,
+                                int B, int H, hipStream_t stream);
+// Fused backward point-wise: gate pre-activation gradients dA [B][4H] and dc_{t-1}.
+// dh = dh_a + dh_b (either may be null), dc_in may be null.
+hipError_t launch_pointwise_bwd(const float* gates, const float* c_t, const float* c_prev, const float* dh_a,
+                                const float* dh_b, const float* dc_in, float* dA, float* dc_out, int B, int H,
+                                hipStream_t stream);
+// out[c][r] = in[r][c] for `batch` matrices laid one after the other.
+hipError_t launch_transpose(const float* in, float* out, int rows, int cols, int batch, hipStream_t stream);
+// out[n] = sum_r in[r][n]; partial must hold 64*cols floats.
+hipError_t launch_colsum(const float* in, int rows, int cols, float* partial, float* out, hipStream_t stream);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+
+// ---------------------------------------------------------------- fused step kernels (step.hip)
+struct StepFwdArgs {
+  const float* R;       // [4H][H]
+  const float* h_prev;  // [B][H] or null (zeros)
+  const float* c_prev;  // [B][H] or null (zeros)
+  const float* P;       // [B][4H] input projection of this step
+  const float* bias;    // [4H]
+  float* h_out;         // [B][H]
+  float* c_out;         // [B][H]
+  float* gates_out;     // [B][4H]
+  float* h_out2;        // optional second copy of h (y / hT), may be null
+  float* c_out2;        // optional second copy of c (cT), may be null
+  int B, H;
+};
+hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream);
+
+struct StepBwdArgs {
+  const float* RT;       // [H][4H] transposed recurrent matrix
+  const float* dA_next;  // [B][4H] gate gradients of step t+1, null at the last step
+  const float* dh_extra; // [B][H] added to dh (dhT at the last step), may be null
+  const float* dout;     // [B][H] gradient from above (dy or the upper layer's input gradient); null when !pointwise
+  const float* gates;    // [B][4H] of step t
+  const float* c_t;      // [B][H]
+  const float* c_prev;   // [B][H] c_{t-1} (c0 at t=0), null = zeros
+  const float* dc_in;    // [B][H] carried cell gradient, null = zeros
+  float* dA;             // [B][4H] out
+  float* dc_out;         // [B][H] out
+  float* dh_out;         // [B][H] out when !pointwise (dh0)
+  int pointwise;         // 0: only dh_out = dA_next * R (+dh_extra)
+  int B, H;
+};
+hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream);
+
+// ---------------------------------------------------------------- device math
+__device__ __forceinline__ float sigmoidf_dev(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+}  // namespace lstm

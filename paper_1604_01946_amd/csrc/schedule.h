@@ -1,0 +1,71 @@
+// Host-side plan structures shared by the API and the per-path schedules.
+#pragma once
+#include "internal.h"
+
+namespace lstm {
+
+struct Dims {
+  int L, T, B, I, H;
+};
+
+// Byte offsets of the regions carved out of the caller's workspace.
+struct WsLayout {
+  size_t P;        // [L][T*B][4H]  forward: input projections; backward: gate gradients dA
+  size_t dx;       // [L][T*B][H]   backward: gradient handed from layer l to layer l-1
+  size_t RT;       // [L][H][4H]    backward: transposed recurrent matrices
+  size_t state;    // [4][L][B][H]  carried cell/hidden gradients, zero block
+  size_t dbpart;   // [L][64][4H]   bias-gradient partial sums
+  size_t scratch;  // [8][B][4H]    per-cell temporaries of the unfused paths
+  size_t xchg;     // persistent path: k-major exchange buffers
+  size_t flags;    // persistent path: step counters and the watchdog word
+  size_t resv;     // stand-in for `reserve` when the caller runs inference
+  size_t total;
+};
+
+struct FwdArgs {
+  Dims d;
+  const float *x, *h0, *c0, *W, *R, *b;
+  float *y, *hT, *cT;
+  float* reserve;
+  char* ws;
+  WsLayout w;
+  hipStream_t stream;
+};
+
+struct BwdArgs {
+  Dims d;
+  const float *x, *h0, *c0, *W, *R;
+  const float* reserve;
+  const float *dy, *dhT, *dcT;
+  float *dx, *dh0, *dc0, *dW, *dR, *db;
+  char* ws;
+  WsLayout w;
+  hipStream_t stream;
+};
+
+size_t reserve_bytes(const Dims& d);
+WsLayout ws_layout(const Dims& d);
+unsigned resolve_auto_path(const Dims& d, bool backward);
+int run_forward(const FwdArgs& a, unsigned path);
+int run_backward(const BwdArgs& a, unsigned path);
+void release_helpers();
+hipError_t record(hipError_t e, const char* what);
+
+inline int in_dim(const Dims& d, int l) { return l == 0 ? d.I : d.H; }
+inline size_t w_offset(const Dims& d, int l) {
+  return l == 0 ? 0 : (size_t)4 * d.H * d.I + (size_t)(l - 1) * 4 * d.H * d.H;
+}
+
+// Per-layer views of the reserve buffer: gates [T][B][4H] (activated i,f,o,c'), c and h [T][B][H].
+struct LayerRes {
+  float* gates;
+  float* c;
+  float* h;
+};
+inline LayerRes layer_res(const float* reserve, const Dims& d, int l) {
+  const size_t TB = (size_t)d.T * d.B, H = d.H;
+  float* base = const_cast<float*>(reserve) + (size_t)l * TB * 6 * H;
+  return LayerRes{base, base + TB * 4 * H, base + TB * 5 * H};
+}
+
+}  // namespace lstm

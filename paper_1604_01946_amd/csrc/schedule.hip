@@ -1,0 +1,344 @@
+// Host-side schedules: the order in which each execution path enqueues its kernels.
+//
+// The paths are the rungs of the optimisation ladder of arXiv 1604.01946 (Table 1):
+//   naive    -- Section 2.1 / Listing 1: per-gate GEMMs, one kernel per point-wise operation
+//   grouped  -- Section 2.1: the four gates stacked into one GEMM per operand
+//   fused    -- Section 2.2.2: one fused point-wise kernel per cell
+//   step     -- Section 2.3 / Listing 3: input projections of all steps in one GEMM, weights
+//               re-laid out once per pass, recurrent GEMM + point-wise fused per step
+//   wavefront / persistent -- Section 2.4 and Section 4 (wavefront.hip, persistent.hip)
+// The paper's ladder is forward only; the backward schedules mirror it (Section 2.1 on the
+// backward pass, Section 2.6 on the weight update).
+#include "../../include/lstm.h"
+#include "schedule.h"
+
+namespace lstm {
+
+#define CK(expr, what)                                             \
+  do {                                                             \
+    if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
+  } while (0)
+
+int run_forward_wavefront(const FwdArgs& a);
+int run_backward_wavefront(const BwdArgs& a);
+int run_forward_persistent(const FwdArgs& a);
+int run_backward_persistent(const BwdArgs& a);
+bool persistent_supported(const Dims& d, bool backward);
+
+unsigned resolve_auto_path(const Dims& d, bool backward) {
+  if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
+  return LSTM_PATH_WAVEFRONT;
+}
+
+namespace {
+
+inline float* ws_f(char* ws, size_t off) { return reinterpret_cast<float*>(ws + off); }
+
+int copy_final_states(const FwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t BH = (size_t)d.B * d.H;
+  for (int l = 0; l < d.L; ++l) {
+    const LayerRes r = layer_res(a.reserve, d, l);
+    if (a.hT) CK(launch_ew(EW_COPY, a.hT + l * BH, d.H, r.h + (size_t)(d.T - 1) * BH, d.H, nullptr, 0, d.B, d.H, a.stream), "copy hT");
+    if (a.cT) CK(launch_ew(EW_COPY, a.cT + l * BH, d.H, r.c + (size_t)(d.T - 1) * BH, d.H, nullptr, 0, d.B, d.H, a.stream), "copy cT");
+  }
+  return LSTM_OK;
+}
+
+// ------------------------------------------------------------------ forward: step path
+int fwd_step(const FwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
+  hipStream_t s = a.stream;
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    const LayerRes r = layer_res(a.reserve, d, l);
+    const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
+    const float* Wl = a.W + w_offset(d, l);
+    const float* Rl = a.R + (size_t)l * G * d.H;
+    float* P = ws_f(a.ws, a.w.P) + (size_t)l * TB * G;
+    GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+    CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+    for (int t = 0; t < d.T; ++t) {
+      StepFwdArgs sa;
+      sa.R = Rl;
+      sa.h_prev = t ? r.h + (size_t)(t - 1) * BH : (a.h0 ? a.h0 + l * BH : nullptr);
+      sa.c_prev = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : nullptr);
+      sa.P = P + (size_t)t * d.B * G;
+      sa.bias = a.b + (size_t)l * G;
+      sa.h_out = r.h + (size_t)t * BH;
+      sa.c_out = r.c + (size_t)t * BH;
+      sa.gates_out = r.gates + (size_t)t * d.B * G;
+      sa.h_out2 = (l == d.L - 1) ? a.y + (size_t)t * BH : nullptr;
+      sa.c_out2 = nullptr;
+      sa.B = d.B;
+      sa.H = d.H;
+      CK(launch_step_fwd(sa, s), "forward step kernel");
+    }
+  }
+  return copy_final_states(a);
+}
+
+// ------------------------------------------------------------------ forward: unfused rungs
+// level 0: per-gate GEMMs + one kernel per point-wise op; 1: grouped GEMMs; 2: + fused point-wise.
+int fwd_unfused(const FwdArgs& a, int level) {
+  const Dims& d = a.d;
+  const size_t G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H, BG = (size_t)d.B * G;
+  const int B = d.B, H = d.H;
+  hipStream_t s = a.stream;
+  float* S1 = ws_f(a.ws, a.w.scratch);
+  float* S2 = S1 + BG;
+  float* tmp = S2 + BG;
+  float* zero = ws_f(a.ws, a.w.state) + 2 * (size_t)d.L * BH;
+  CK(launch_fill_zero(zero, BH * 4, s), "zero block");
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    const LayerRes r = layer_res(a.reserve, d, l);
+    const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
+    const float* Wl = a.W + w_offset(d, l);
+    const float* Rl = a.R + (size_t)l * G * H;
+    const float* bl = a.b + (size_t)l * G;
+    for (int t = 0; t < d.T; ++t) {
+      const float* xt = in + (size_t)t * B * Il;
+      const float* hp = t ? r.h + (size_t)(t - 1) * BH : (a.h0 ? a.h0 + l * BH : zero);
+      const float* cp = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : zero);
+      float* ht = r.h + (size_t)t * BH;
+      float* ct = r.c + (size_t)t * BH;
+      float* gt = r.gates + (size_t)t * BG;
+      if (level == 0) {
+        for (int g = 0; g < 4; ++g) {
+          GemmProblem p1{xt, Wl + (size_t)g * H * Il, S1 + g * H, B, H, Il, Il, 1, 1, Il, (long)G, 0};
+          CK(launch_gemm_group(&p1, 1, s), "per-gate input GEMM");
+          GemmProblem p2{hp, Rl + (size_t)g * H * H, S2 + g * H, B, H, H, H, 1, 1, H, (long)G, 0};
+          CK(launch_gemm_group(&p2, 1, s), "per-gate recurrent GEMM");
+        }
+      } else {
+        GemmProblem p1{xt, Wl, S1, B, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+        CK(launch_gemm_group(&p1, 1, s), "grouped input GEMM");
+        GemmProblem p2{hp, Rl, S2, B, (int)G, H, H, 1, 1, H, (long)G, 0};
+        CK(launch_gemm_group(&p2, 1, s), "grouped recurrent GEMM");
+      }
+      if (level >= 2) {
+        CK(launch_pointwise_fwd(S1, S2, bl, cp, ht, ct, gt, (l == d.L - 1) ? a.y + (size_t)t * BH : nullptr, nullptr, B, H, s),
+           "fused point-wise");
+        continue;
+      }
+      if (level == 0) {
+        for (int g = 0; g < 4; ++g) CK(launch_ew(EW_ADD, S1 + g * H, G, S1 + g * H, G, S2 + g * H, G, B, H, s), "add");
+        for (int g = 0; g < 4; ++g) CK(launch_ew(EW_ADD_BIAS, S1 + g * H, G, S1 + g * H, G, bl + g * H, 0, B, H, s), "bias");
+        for (int g = 0; g < 3; ++g) CK(launch_ew(EW_SIGMOID, gt + g * H, G, S1 + g * H, G, nullptr, 0, B, H, s), "sigmoid");
+      } else {
+        CK(launch_ew(EW_ADD, S1, G, S1, G, S2, G, B, (int)G, s), "add");
+        CK(launch_ew(EW_ADD_BIAS, S1, G, S1, G, bl, 0, B, (int)G, s), "bias");
+        CK(launch_ew(EW_SIGMOID, gt, G, S1, G, nullptr, 0, B, 3 * H, s), "sigmoid");
+      }
+      CK(launch_ew(EW_TANH, gt + 3 * H, G, S1 + 3 * H, G, nullptr, 0, B, H, s), "tanh");
+      CK(launch_ew(EW_MUL, ct, H, gt + H, G, cp, H, B, H, s), "f*c");
+      CK(launch_ew(EW_MUL, tmp, H, gt, G, gt + 3 * H, G, B, H, s), "i*g");
+      CK(launch_ew(EW_ADD, ct, H, ct, H, tmp, H, B, H, s), "c");
+      CK(launch_ew(EW_TANH, tmp, H, ct, H, nullptr, 0, B, H, s), "tanh c");
+      CK(launch_ew(EW_MUL, ht, H, gt + 2 * H, G, tmp, H, B, H, s), "h");
+      if (l == d.L - 1) CK(launch_ew(EW_COPY, a.y + (size_t)t * BH, H, ht, H, nullptr, 0, B, H, s), "y");
+    }
+  }
+  return copy_final_states(a);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ weight update (Section 2.6)
+// dW_l = sum_t dA_t^T in_t, dR_l = sum_t dA_t^T h_{t-1}, db_l = sum_t,b dA_t: products over K = T*B
+// with no dependencies between them, so all of them go into grouped launches.
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
+  const int H = d.H, B = d.B;
+  hipStream_t s = a.stream;
+  GemmProblem main_p[kMaxGemmGroup], tail_p[kMaxGemmGroup];
+  int nm = 0, nt = 0;
+  auto flush = [&](GemmProblem* arr, int& n) -> hipError_t {
+    hipError_t e = hipSuccess;
+    if (grouped) {
+      e = launch_gemm_group(arr, n, s);
+    } else {
+      for (int i = 0; i < n && e == hipSuccess; ++i) e = launch_gemm_group(arr + i, 1, s);
+    }
+    n = 0;
+    return e;
+  };
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    const float* dA = dA_all + (size_t)l * TB * G;
+    const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
+    const LayerRes r = layer_res(a.reserve, d, l);
+    float* dWl = a.dW + w_offset(d, l);
+    float* dRl = a.dR + (size_t)l * G * H;
+    if (nm + 2 > kMaxGemmGroup) CK(flush(main_p, nm), "weight-gradient GEMMs");
+    main_p[nm++] = GemmProblem{dA, in, dWl, (int)G, Il, (int)TB, 1, (long)G, Il, 1, Il, 0};
+    if (d.T > 1) {
+      main_p[nm++] = GemmProblem{dA + (size_t)B * G, r.h, dRl, (int)G, H, (int)(TB - B), 1, (long)G, H, 1, H, 0};
+      if (a.h0) {
+        if (nt + 1 > kMaxGemmGroup) {
+          CK(flush(main_p, nm), "weight-gradient GEMMs");
+          CK(flush(tail_p, nt), "weight-gradient GEMMs (initial state term)");
+        }
+        tail_p[nt++] = GemmProblem{dA, a.h0 + (size_t)l * B * H, dRl, (int)G, H, B, 1, (long)G, H, 1, H, 1};
+      }
+    } else if (a.h0) {
+      main_p[nm++] = GemmProblem{dA, a.h0 + (size_t)l * B * H, dRl, (int)G, H, B, 1, (long)G, H, 1, H, 0};
+    } else {
+      CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
+    }
+    CK(launch_colsum(dA, (int)TB, (int)G, reinterpret_cast<float*>(a.ws + a.w.dbpart) + (size_t)l * 64 * G,
+                     a.db + (size_t)l * G, s),
+       "bias gradient");
+  }
+  CK(flush(main_p, nm), "weight-gradient GEMMs");
+  CK(flush(tail_p, nt), "weight-gradient GEMMs (initial state term)");
+  return LSTM_OK;
+}
+
+namespace {
+
+// ------------------------------------------------------------------ backward: step path
+int bwd_step(const BwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H, BG = (size_t)d.B * G;
+  const int H = d.H, B = d.B, T = d.T;
+  hipStream_t s = a.stream;
+  float* dA_all = ws_f(a.ws, a.w.P);
+  float* RT = ws_f(a.ws, a.w.RT);
+  float* dxb = ws_f(a.ws, a.w.dx);
+  float* dcb = ws_f(a.ws, a.w.state);
+  // weights re-laid out once per pass: the backward products read R transposed (Section 2.3)
+  CK(launch_transpose(a.R, RT, (int)G, H, d.L, s), "transpose R");
+  for (int l = d.L - 1; l >= 0; --l) {
+    const int Il = in_dim(d, l);
+    const LayerRes r = layer_res(a.reserve, d, l);
+    float* dA = dA_all + (size_t)l * TB * G;
+    const float* dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * H;
+    float* dc = dcb + (size_t)l * BH;
+    for (int t = T - 1; t >= 0; --t) {
+      StepBwdArgs sa;
+      sa.RT = RT + (size_t)l * H * G;
+      sa.dA_next = (t < T - 1) ? dA + (size_t)(t + 1) * BG : nullptr;
+      sa.dh_extra = (t == T - 1 && a.dhT) ? a.dhT + l * BH : nullptr;
+      sa.dout = dout + (size_t)t * BH;
+      sa.gates = r.gates + (size_t)t * BG;
+      sa.c_t = r.c + (size_t)t * BH;
+      sa.c_prev = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : nullptr);
+      sa.dc_in = (t == T - 1) ? (a.dcT ? a.dcT + l * BH : nullptr) : dc;
+      sa.dA = dA + (size_t)t * BG;
+      sa.dc_out = (t == 0 && a.dc0) ? a.dc0 + l * BH : dc;
+      sa.dh_out = nullptr;
+      sa.pointwise = 1;
+      sa.B = B;
+      sa.H = H;
+      CK(launch_step_bwd(sa, s), "backward step kernel");
+    }
+    if (a.dh0) {
+      StepBwdArgs sa{};
+      sa.RT = RT + (size_t)l * H * G;
+      sa.dA_next = dA;
+      sa.dh_out = a.dh0 + l * BH;
+      sa.pointwise = 0;
+      sa.B = B;
+      sa.H = H;
+      CK(launch_step_bwd(sa, s), "backward step kernel (dh0)");
+    }
+    // gradient for the layer below (or dx): all T steps in one product
+    float* din = l > 0 ? dxb + (size_t)l * TB * H : a.dx;
+    if (din) {
+      GemmProblem p{dA, a.W + w_offset(d, l), din, (int)TB, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
+      CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
+    }
+  }
+  return weight_gradients(a, dA_all, true);
+}
+
+// ------------------------------------------------------------------ backward: unfused rungs
+int bwd_unfused(const BwdArgs& a, bool per_gate) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H, BG = (size_t)d.B * G;
+  const int H = d.H, B = d.B, T = d.T;
+  hipStream_t s = a.stream;
+  float* dA_all = ws_f(a.ws, a.w.P);
+  float* dxb = ws_f(a.ws, a.w.dx);
+  float* dcb = ws_f(a.ws, a.w.state);
+  float* dhb = dcb + (size_t)d.L * BH;
+  for (int l = d.L - 1; l >= 0; --l) {
+    const int Il = in_dim(d, l);
+    const LayerRes r = layer_res(a.reserve, d, l);
+    const float* Wl = a.W + w_offset(d, l);
+    const float* Rl = a.R + (size_t)l * G * H;
+    float* dA = dA_all + (size_t)l * TB * G;
+    const float* dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * H;
+    float* dc = dcb + (size_t)l * BH;
+    float* dh = dhb + (size_t)l * BH;
+    float* din = l > 0 ? dxb + (size_t)l * TB * H : a.dx;
+    for (int t = T - 1; t >= 0; --t) {
+      const float* dh_b = (t == T - 1) ? (a.dhT ? a.dhT + l * BH : nullptr) : dh;
+      const float* dc_in = (t == T - 1) ? (a.dcT ? a.dcT + l * BH : nullptr) : dc;
+      const float* cp = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : nullptr);
+      float* dAt = dA + (size_t)t * BG;
+      CK(launch_pointwise_bwd(r.gates + (size_t)t * BG, r.c + (size_t)t * BH, cp, dout + (size_t)t * BH, dh_b, dc_in,
+                              dAt, (t == 0 && a.dc0) ? a.dc0 + l * BH : dc, B, H, s),
+         "backward point-wise");
+      float* dh_dst = (t == 0) ? (a.dh0 ? a.dh0 + l * BH : nullptr) : dh;
+      if (per_gate) {
+        for (int g = 0; g < 4; ++g) {
+          if (dh_dst) {
+            GemmProblem p{dAt + g * H, Rl + (size_t)g * H * H, dh_dst, B, H, H, (long)G, 1, H, 1, H, g > 0};
+            CK(launch_gemm_group(&p, 1, s), "per-gate recurrent gradient GEMM");
+          }
+          if (din) {
+            GemmProblem p{dAt + g * H, Wl + (size_t)g * H * Il, din + (size_t)t * B * Il, B, Il, H, (long)G, 1, Il, 1, Il, g > 0};
+            CK(launch_gemm_group(&p, 1, s), "per-gate input gradient GEMM");
+          }
+        }
+      } else {
+        if (dh_dst) {
+          GemmProblem p{dAt, Rl, dh_dst, B, H, (int)G, (long)G, 1, H, 1, H, 0};
+          CK(launch_gemm_group(&p, 1, s), "recurrent gradient GEMM");
+        }
+        if (din) {
+          GemmProblem p{dAt, Wl, din + (size_t)t * B * Il, B, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
+          CK(launch_gemm_group(&p, 1, s), "input gradient GEMM");
+        }
+      }
+    }
+  }
+  return weight_gradients(a, dA_all, !per_gate);
+}
+
+}  // namespace
+
+int run_forward(const FwdArgs& a, unsigned path) {
+  switch (path) {
+    case LSTM_PATH_NAIVE: return fwd_unfused(a, 0);
+    case LSTM_PATH_GROUPED: return fwd_unfused(a, 1);
+    case LSTM_PATH_FUSED: return fwd_unfused(a, 2);
+    case LSTM_PATH_STEP: return fwd_step(a);
+    case LSTM_PATH_WAVEFRONT: return run_forward_wavefront(a);
+    case LSTM_PATH_PERSISTENT:
+      if (!persistent_supported(a.d, false)) return LSTM_UNSUPPORTED;
+      return run_forward_persistent(a);
+    default: return LSTM_INVALID_ARG;
+  }
+}
+
+int run_backward(const BwdArgs& a, unsigned path) {
+  switch (path) {
+    case LSTM_PATH_NAIVE: return bwd_unfused(a, true);
+    case LSTM_PATH_GROUPED:
+    case LSTM_PATH_FUSED: return bwd_unfused(a, false);
+    case LSTM_PATH_STEP: return bwd_step(a);
+    case LSTM_PATH_WAVEFRONT: return run_backward_wavefront(a);
+    case LSTM_PATH_PERSISTENT:
+      if (!persistent_supported(a.d, true)) return LSTM_UNSUPPORTED;
+      return run_backward_persistent(a);
+    default: return LSTM_INVALID_ARG;
+  }
+}
+
+}  // namespace lstm

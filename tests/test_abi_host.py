@@ -1,0 +1,81 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, sizes its buffers as documented, and rejects bad arguments before any GPU work."""
+import os
+import re
+import ctypes
+import pytest
+
+from paper_1604_01946_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lstm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lstm_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = B.library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_size_queries():
+    assert B.lstm_reserve_bytes(4, 100, 64, 512, 512) == 4 * 100 * 64 * 6 * 512 * 4
+    assert B.lstm_reserve_bytes(0, 1, 1, 1, 1) == 0 and B.lstm_workspace_bytes(1, 1, -1, 1, 1) == 0
+    assert B.lstm_workspace_bytes(1, 8, 4, 32, 32) > 0
+    assert B.lstm_workspace_bytes(4, 100, 64, 512, 512) % 256 == 0
+
+
+def test_status_strings():
+    for s in range(0, 6):
+        assert B.lstm_status_string(s)
+    assert "unknown" in B.lstm_status_string(99)
+
+
+def _fwd(dims, ptrs, ws_bytes, flags=0):
+    return B.lstm_forward(*dims, *ptrs, ws_bytes, stream=0, flags=flags)
+
+
+def test_forward_rejects_bad_arguments_without_touching_the_gpu():
+    dims = (1, 2, 2, 4, 4)
+    need = B.lstm_workspace_bytes(*dims)
+    ok = 4096  # fake aligned "device addresses": validation must fail before any is dereferenced
+    ptrs = [ok, None, None, ok, ok, ok, ok, None, None, None, ok]
+    assert _fwd((0, 2, 2, 4, 4), ptrs, need) == B.LSTM_INVALID_ARG
+    assert _fwd((1, 2, 2, 4, -4), ptrs, need) == B.LSTM_INVALID_ARG
+    for k in (0, 3, 4, 5, 6, 10):  # x, W, R, b, y, workspace are required
+        bad = list(ptrs); bad[k] = None
+        assert _fwd(dims, bad, need) == B.LSTM_INVALID_ARG, k
+    mis = list(ptrs); mis[0] = ok + 4
+    assert _fwd(dims, mis, need) == B.LSTM_INVALID_ARG
+    assert _fwd(dims, ptrs, need - 1) == B.LSTM_BUFFER_TOO_SMALL
+    assert _fwd(dims, ptrs, need, flags=7) == B.LSTM_INVALID_ARG
+    assert _fwd(dims, ptrs, need, flags=16) == B.LSTM_INVALID_ARG
+
+
+def test_backward_rejects_bad_arguments_without_touching_the_gpu():
+    dims = (1, 2, 2, 4, 4)
+    need = B.lstm_workspace_bytes(*dims)
+    ok = 4096
+    # x h0 c0 W R reserve dy dhT dcT dx dh0 dc0 dW dR db workspace
+    ptrs = [ok, None, None, ok, ok, ok, ok, None, None, None, None, None, ok, ok, ok, ok]
+    call = lambda d, p, n, f=0: B.lstm_backward(*d, *p, n, stream=0, flags=f)
+    assert call((1, 0, 2, 4, 4), ptrs, need) == B.LSTM_INVALID_ARG
+    for k in (0, 3, 4, 5, 6, 12, 13, 14, 15):
+        bad = list(ptrs); bad[k] = None
+        assert call(dims, bad, need) == B.LSTM_INVALID_ARG, k
+    mis = list(ptrs); mis[12] = ok + 8
+    assert call(dims, mis, need) == B.LSTM_INVALID_ARG
+    assert call(dims, ptrs, need - 256) == B.LSTM_BUFFER_TOO_SMALL
+
+
+def test_gemm_rejects_bad_arguments():
+    assert B.lstm_gemm_f32(0, 1, 1, 4096, 1, 1, 4096, 1, 1, 4096, 1, 0, stream=0) == B.LSTM_INVALID_ARG
+    assert B.lstm_gemm_f32(4, 4, 4, 4096, 4, 2, 4096, 4, 1, 4096, 4, 0, stream=0) == B.LSTM_INVALID_ARG
+    assert B.lstm_gemm_f32(4, 4, 4, 4096, 4, 1, 4096, 4, 1, 4096, 2, 0, stream=0) == B.LSTM_INVALID_ARG
+
+
+def test_auto_path_is_a_valid_path():
+    assert B.lstm_auto_path(0, 1, 1, 1, 1, 0) == B.LSTM_PATH_AUTO
+    assert B.lstm_auto_path(1, 8, 4, 32, 32, 1) in (B.LSTM_PATH_STEP, B.LSTM_PATH_WAVEFRONT, B.LSTM_PATH_PERSISTENT)

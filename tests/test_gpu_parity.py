@@ -1,0 +1,176 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances: max|gpu-oracle|/max|oracle| <= 1e-4 for forward outputs and
+<= 1e-3 for every gradient (fp32 arithmetic on the GPU, fp64 in the oracle)."""
+import numpy as np
+import pytest
+
+from paper_1604_01946_amd.inputs import CONFIGS, Config, make_inputs
+from parity import oracle_results, assert_close, FWD_TOL, BWD_TOL
+
+pytestmark = pytest.mark.gpu
+
+FWD = ("y", "hT", "cT")
+BWD = ("dx", "dh0", "dc0", "dW", "dR", "db")
+
+
+def _mods():
+    import torch
+    from paper_1604_01946_amd import binding, runner
+    assert torch.cuda.is_available()
+    return torch, binding, runner
+
+
+def run_case(cfg, seed, flags, backward=True, with_states=True, with_dstates=True, poison=True):
+    torch, binding, runner = _mods()
+    d, ref = oracle_results(cfg, seed, with_states, with_dstates, backward)
+    r = runner.LstmRunner(cfg.dims, d, with_states=with_states, with_dstates=with_dstates)
+    if poison:
+        r.poison()
+    print(f"case {cfg.dims} seed={seed} flags={flags} bwd={backward}", flush=True)
+    binding.check(r.forward(flags=flags), "lstm_forward")
+    torch.cuda.synchronize()
+    e = assert_close(r.fwd_outputs(), ref, FWD, FWD_TOL, f"fwd {cfg.dims} flags={flags}")
+    if backward:
+        binding.check(r.backward(flags=flags), "lstm_backward")
+        torch.cuda.synchronize()
+        e.update(assert_close(r.bwd_outputs(), ref, BWD, BWD_TOL, f"bwd {cfg.dims} flags={flags}"))
+    print("  errors:", {k: f"{v:.2e}" for k, v in e.items()}, flush=True)
+    return r, ref
+
+
+# ------------------------------------------------------------------ GEMM alone
+@pytest.mark.parametrize("M,N,K", [(64, 64, 16), (128, 128, 64), (200, 136, 72), (33, 17, 5), (6400, 2048, 512),
+                                   (1, 1, 1), (257, 129, 130)])
+@pytest.mark.parametrize("layout", ["NT", "NN", "TN"])
+def test_gemm_matches_numpy(M, N, K, layout):
+    torch, binding, _ = _mods()
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((K, N)).astype(np.float32)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    dev = "cuda:0"
+    if layout == "TN":
+        At = torch.from_numpy(np.ascontiguousarray(A.T)).to(dev); sAm, sAk = 1, M
+    else:
+        At = torch.from_numpy(A).to(dev); sAm, sAk = K, 1
+    if layout == "NT":
+        Bt = torch.from_numpy(np.ascontiguousarray(Bm.T)).to(dev); sBk, sBn = 1, K
+    else:
+        Bt = torch.from_numpy(Bm).to(dev); sBk, sBn = N, 1
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    binding.check(binding.lstm_gemm_f32(M, N, K, At, sAm, sAk, Bt, sBk, sBn, C, N, 0), "gemm")
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) < 2e-6
+    binding.check(binding.lstm_gemm_f32(M, N, K, At, sAm, sAk, Bt, sBk, sBn, C, N, 1), "gemm acc")
+    torch.cuda.synchronize()
+    assert np.max(np.abs(C.cpu().numpy() - 2 * ref)) / np.max(np.abs(ref)) < 4e-6
+
+
+# ------------------------------------------------------------------ the five measured shapes
+PATHS_ALL = [0, 1, 2, 3, 4, 5, 6]
+
+
+@pytest.mark.parametrize("flags", PATHS_ALL)
+def test_cfg1_all_paths(flags):
+    _, binding, _ = _mods()
+    cfg = CONFIGS["cfg1"]
+    if flags == 6 and binding.lstm_auto_path(*cfg.dims, 0) != 6:
+        pytest.skip("persistent path does not take this shape")
+    run_case(cfg, 0, flags)
+    run_case(cfg, 1, flags)
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_cfg2_forward(flags):
+    run_case(CONFIGS["cfg2"], 0, flags, backward=False)
+
+
+@pytest.mark.parametrize("flags", [0, 4, 5])
+def test_cfg3_forward_backward(flags):
+    run_case(CONFIGS["cfg3"], 0, flags)
+
+
+def test_cfg4_large_hidden():
+    run_case(CONFIGS["cfg4"], 0, 0)
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_cfg5_small_batch_long_sequence(flags):
+    run_case(CONFIGS["cfg5"], 0, flags, with_states=False, with_dstates=False)
+
+
+# ------------------------------------------------------------------ ragged / odd shapes, several tiles
+ODD = [
+    Config("odd1", L=2, T=3, B=5, I=24, H=40, state_std=0.5, dstate_std=0.5),
+    Config("odd2", L=3, T=4, B=3, I=7, H=30, state_std=0.5, dstate_std=0.5),     # H, I not multiples of 4
+    Config("odd3", L=2, T=5, B=70, I=36, H=100, state_std=0.5, dstate_std=0.5),  # two batch tiles, ragged tail
+    Config("odd4", L=1, T=1, B=1, I=1, H=1, state_std=0.5, dstate_std=0.5),
+    Config("odd5", L=2, T=6, B=33, I=130, H=264, state_std=0.5, dstate_std=0.5),
+]
+
+
+@pytest.mark.parametrize("cfg", ODD, ids=[c.name for c in ODD])
+@pytest.mark.parametrize("flags", [0, 1, 3, 4, 5])
+def test_odd_shapes(cfg, flags):
+    run_case(cfg, 3, flags)
+
+
+# ------------------------------------------------------------------ optional pointers, inference
+def test_null_optionals_and_inference():
+    torch, binding, runner = _mods()
+    cfg = Config("opt", L=2, T=4, B=6, I=16, H=24)
+    for flags in (0, 4):
+        d, ref = oracle_results(cfg, 5, with_states=False, with_dstates=False)
+        r = runner.LstmRunner(cfg.dims, d, with_states=False, with_dstates=False)
+        r.poison()
+        binding.check(r.forward(flags=flags, want_states=False))
+        binding.check(r.backward(flags=flags, want_dx=False, want_dstates=False))
+        torch.cuda.synchronize()
+        assert_close(r.fwd_outputs(), ref, ("y",), FWD_TOL)
+        assert_close(r.bwd_outputs(), ref, ("dW", "dR", "db"), BWD_TOL)
+        assert torch.isnan(r.hT).all() and torch.isnan(r.dx).all() and torch.isnan(r.dh0).all()
+        y_train = r.y.clone()
+        r.y.fill_(float("nan"))
+        binding.check(r.forward(flags=flags, inference=True))
+        torch.cuda.synchronize()
+        assert torch.equal(r.y, y_train)
+
+
+# ------------------------------------------------------------------ determinism (doubles as a race detector)
+@pytest.mark.parametrize("name", ["cfg1", "cfg3"])
+def test_bitwise_repeatable(name):
+    torch, binding, runner = _mods()
+    cfg = CONFIGS[name]
+    d = make_inputs(cfg, 0)
+    r = runner.LstmRunner(cfg.dims, d)
+    outs = []
+    for it in range(3):
+        r.poison()
+        binding.check(r.forward())
+        binding.check(r.backward())
+        torch.cuda.synchronize()
+        outs.append({k: getattr(r, k).clone() for k in FWD + BWD})
+    for k in FWD + BWD:
+        assert torch.equal(outs[0][k], outs[1][k]) and torch.equal(outs[0][k], outs[2][k]), k
+
+
+# ------------------------------------------------------------------ boundary identity on the GPU
+def test_split_T_chaining_on_gpu():
+    torch, binding, runner = _mods()
+    cfg = Config("chain", L=2, T=8, B=16, I=32, H=64, state_std=0.3)
+    d = make_inputs(cfg, 7)
+    full = runner.LstmRunner(cfg.dims, d)
+    binding.check(full.forward())
+    T1 = 3
+    d1 = dict(d, x=d["x"][:T1], dy=d["dy"][:T1])
+    r1 = runner.LstmRunner((cfg.L, T1, cfg.B, cfg.I, cfg.H), d1)
+    binding.check(r1.forward())
+    torch.cuda.synchronize()
+    d2 = dict(d, x=d["x"][T1:], dy=d["dy"][T1:], h0=r1.hT.cpu().numpy(), c0=r1.cT.cpu().numpy())
+    r2 = runner.LstmRunner((cfg.L, cfg.T - T1, cfg.B, cfg.I, cfg.H), d2)
+    binding.check(r2.forward())
+    torch.cuda.synchronize()
+    y12 = torch.cat([r1.y, r2.y])
+    assert float((y12 - full.y).abs().max()) < 1e-5
+    assert float((r2.hT - full.hT).abs().max()) < 1e-5
