@@ -131,6 +131,28 @@ int lstm_gemm_f32(int M, int N, int K,
  * (returns an LSTM_PATH_* value; LSTM_PATH_AUTO on invalid dimensions). */
 unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward);
 
+/*
+ * Phase timing for measurement (Section 2.5 reports time per optimisation stage; this is the
+ * same breakdown taken live).  While enabled, lstm_forward / lstm_backward record HIP events
+ * on the stream each phase is launched on, at the phase's first and last launch.
+ * lstm_profile_read waits for the recorded events, adds the elapsed milliseconds of every
+ * recorded interval to ms[phase] and the interval count to count[phase] (both arrays of
+ * LSTM_PHASE_COUNT entries, host memory, overwritten), and forgets the events.
+ * Returns LSTM_OK or LSTM_HIP_ERROR.  Not thread-safe; intended for benchmarks.
+ */
+#define LSTM_PHASE_FWD_PACK        0 /* weight re-layout / exchange set-up, forward */
+#define LSTM_PHASE_FWD_INPUT_GEMM  1 /* time-batched input projection(s) */
+#define LSTM_PHASE_FWD_RECURRENCE  2 /* per-step recurrent work (step kernels or the persistent kernel) */
+#define LSTM_PHASE_BWD_PACK        3 /* weight re-layout, backward */
+#define LSTM_PHASE_BWD_RECURRENCE  4 /* backward per-step work */
+#define LSTM_PHASE_BWD_INPUT_GEMM  5 /* batched input-gradient product(s) */
+#define LSTM_PHASE_WEIGHT_GRAD     6 /* dW, dR products */
+#define LSTM_PHASE_BIAS_GRAD       7 /* db reductions */
+#define LSTM_PHASE_COUNT           8
+void lstm_profile_enable(int on);
+int lstm_profile_read(float* ms, int* count);
+const char* lstm_phase_name(int phase);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* lstm_status_string(int status);
 

@@ -31,7 +31,9 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
     "lstm_auto_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
+    "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name",
 ]
+LSTM_PHASE_COUNT = 8
 
 _lib = None
 
@@ -67,6 +69,12 @@ def library():
         lib.lstm_last_error.argtypes = []
         lib.lstm_shutdown.restype = None
         lib.lstm_shutdown.argtypes = []
+        lib.lstm_profile_enable.restype = None
+        lib.lstm_profile_enable.argtypes = [i]
+        lib.lstm_profile_read.restype = i
+        lib.lstm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        lib.lstm_phase_name.restype = ctypes.c_char_p
+        lib.lstm_phase_name.argtypes = [i]
         _lib = lib
     return _lib
 
@@ -131,6 +139,22 @@ def lstm_backward(L, T, B, I, H, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0
 def lstm_gemm_f32(M, N, K, A, sAm, sAk, Bm, sBk, sBn, C, ldc, accumulate, stream=None):
     return library().lstm_gemm_f32(M, N, K, _ptr(A), sAm, sAk, _ptr(Bm), sBk, sBn, _ptr(C), ldc, int(accumulate),
                                    _stream(stream))
+
+
+def lstm_profile_enable(on):
+    library().lstm_profile_enable(int(on))
+
+
+def lstm_phase_name(phase):
+    return library().lstm_phase_name(phase).decode()
+
+
+def lstm_profile_read():
+    """Returns (status, {phase name: (milliseconds, intervals)})."""
+    ms = (ctypes.c_float * LSTM_PHASE_COUNT)()
+    cnt = (ctypes.c_int * LSTM_PHASE_COUNT)()
+    st = library().lstm_profile_read(ms, cnt)
+    return st, {lstm_phase_name(k): (float(ms[k]), int(cnt[k])) for k in range(LSTM_PHASE_COUNT)}
 
 
 def check(status, where="lstm"):

@@ -7,6 +7,7 @@
 #include <string.h>
 #include <stdio.h>
 #include <string>
+#include <vector>
 
 using namespace lstm;
 
@@ -19,6 +20,34 @@ hipError_t record(hipError_t e, const char* what) {
     (void)hipGetLastError();
   }
   return e;
+}
+
+namespace {
+struct ProfInterval {
+  int phase;
+  hipEvent_t start, stop;
+  bool open;
+};
+bool g_prof_on = false;
+std::vector<ProfInterval> g_prof;
+}  // namespace
+
+void prof_begin(int phase, hipStream_t s) {
+  if (!g_prof_on) return;
+  ProfInterval iv{phase, nullptr, nullptr, true};
+  if (hipEventCreate(&iv.start) != hipSuccess || hipEventCreate(&iv.stop) != hipSuccess) return;
+  (void)hipEventRecord(iv.start, s);
+  g_prof.push_back(iv);
+}
+void prof_end(int phase, hipStream_t s) {
+  if (!g_prof_on) return;
+  for (size_t i = g_prof.size(); i-- > 0;) {
+    if (g_prof[i].phase == phase && g_prof[i].open) {
+      (void)hipEventRecord(g_prof[i].stop, s);
+      g_prof[i].open = false;
+      return;
+    }
+  }
 }
 }  // namespace lstm
 
@@ -86,6 +115,39 @@ const char* lstm_status_string(int status) {
 const char* lstm_last_error(void) { return g_last_error.c_str(); }
 
 void lstm_shutdown(void) { release_helpers(); }
+
+void lstm_profile_enable(int on) { g_prof_on = on != 0; }
+
+int lstm_profile_read(float* ms, int* count) {
+  if (!ms || !count) return LSTM_INVALID_ARG;
+  for (int i = 0; i < LSTM_PHASE_COUNT; ++i) {
+    ms[i] = 0.f;
+    count[i] = 0;
+  }
+  int status = LSTM_OK;
+  for (auto& iv : g_prof) {
+    float t = 0.f;
+    if (!iv.open && hipEventSynchronize(iv.stop) == hipSuccess && hipEventElapsedTime(&t, iv.start, iv.stop) == hipSuccess) {
+      if (iv.phase >= 0 && iv.phase < LSTM_PHASE_COUNT) {
+        ms[iv.phase] += t;
+        count[iv.phase] += 1;
+      }
+    } else {
+      (void)hipGetLastError();
+      status = LSTM_HIP_ERROR;
+    }
+    (void)hipEventDestroy(iv.start);
+    (void)hipEventDestroy(iv.stop);
+  }
+  g_prof.clear();
+  return status;
+}
+
+const char* lstm_phase_name(int phase) {
+  static const char* names[LSTM_PHASE_COUNT] = {"fwd_pack",       "fwd_input_gemm", "fwd_recurrence", "bwd_pack",
+                                                "bwd_recurrence", "bwd_input_gemm", "weight_grad",    "bias_grad"};
+  return (phase >= 0 && phase < LSTM_PHASE_COUNT) ? names[phase] : "unknown";
+}
 
 unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward) {
   if (!dims_ok(L, T, B, I, H)) return LSTM_PATH_AUTO;

@@ -51,6 +51,16 @@ int run_backward(const BwdArgs& a, unsigned path);
 void release_helpers();
 hipError_t record(hipError_t e, const char* what);
 
+// Phase timing hooks (no-ops unless lstm_profile_enable(1)).
+void prof_begin(int phase, hipStream_t s);
+void prof_end(int phase, hipStream_t s);
+struct ProfScope {
+  int phase;
+  hipStream_t s;
+  ProfScope(int p, hipStream_t st) : phase(p), s(st) { prof_begin(p, st); }
+  ~ProfScope() { prof_end(phase, s); }
+};
+
 inline int in_dim(const Dims& d, int l) { return l == 0 ? d.I : d.H; }
 inline size_t w_offset(const Dims& d, int l) {
   return l == 0 ? 0 : (size_t)4 * d.H * d.I + (size_t)(l - 1) * 4 * d.H * d.H;

@@ -57,8 +57,12 @@ int fwd_step(const FwdArgs& a) {
     const float* Wl = a.W + w_offset(d, l);
     const float* Rl = a.R + (size_t)l * G * d.H;
     float* P = ws_f(a.ws, a.w.P) + (size_t)l * TB * G;
-    GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
-    CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+    {
+      ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
+      GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+      CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+    }
+    ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     for (int t = 0; t < d.T; ++t) {
       StepFwdArgs sa;
       sa.R = Rl;
@@ -166,6 +170,14 @@ int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped) {
     n = 0;
     return e;
   };
+  {
+    ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
+    for (int l = 0; l < d.L; ++l)
+      CK(launch_colsum(dA_all + (size_t)l * TB * G, (int)TB, (int)G,
+                       reinterpret_cast<float*>(a.ws + a.w.dbpart) + (size_t)l * 64 * G, a.db + (size_t)l * G, s),
+         "bias gradient");
+  }
+  ProfScope ps(LSTM_PHASE_WEIGHT_GRAD, s);
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const float* dA = dA_all + (size_t)l * TB * G;
@@ -189,9 +201,6 @@ int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped) {
     } else {
       CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
     }
-    CK(launch_colsum(dA, (int)TB, (int)G, reinterpret_cast<float*>(a.ws + a.w.dbpart) + (size_t)l * 64 * G,
-                     a.db + (size_t)l * G, s),
-       "bias gradient");
   }
   CK(flush(main_p, nm), "weight-gradient GEMMs");
   CK(flush(tail_p, nt), "weight-gradient GEMMs (initial state term)");
@@ -211,13 +220,17 @@ int bwd_step(const BwdArgs& a) {
   float* dxb = ws_f(a.ws, a.w.dx);
   float* dcb = ws_f(a.ws, a.w.state);
   // weights re-laid out once per pass: the backward products read R transposed (Section 2.3)
-  CK(launch_transpose(a.R, RT, (int)G, H, d.L, s), "transpose R");
+  {
+    ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+    CK(launch_transpose(a.R, RT, (int)G, H, d.L, s), "transpose R");
+  }
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
     const LayerRes r = layer_res(a.reserve, d, l);
     float* dA = dA_all + (size_t)l * TB * G;
     const float* dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * H;
     float* dc = dcb + (size_t)l * BH;
+    prof_begin(LSTM_PHASE_BWD_RECURRENCE, s);
     for (int t = T - 1; t >= 0; --t) {
       StepBwdArgs sa;
       sa.RT = RT + (size_t)l * H * G;
@@ -246,9 +259,11 @@ int bwd_step(const BwdArgs& a) {
       sa.H = H;
       CK(launch_step_bwd(sa, s), "backward step kernel (dh0)");
     }
+    prof_end(LSTM_PHASE_BWD_RECURRENCE, s);
     // gradient for the layer below (or dx): all T steps in one product
     float* din = l > 0 ? dxb + (size_t)l * TB * H : a.dx;
     if (din) {
+      ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
       GemmProblem p{dA, a.W + w_offset(d, l), din, (int)TB, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
       CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
     }
