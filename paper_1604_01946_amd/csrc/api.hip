@@ -66,7 +66,7 @@ size_t reserve_bytes(const Dims& d) { return (size_t)d.L * d.T * d.B * 6 * d.H *
 WsLayout ws_layout(const Dims& d) {
   WsLayout w;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, H = d.H, L = d.L;
-  const size_t Bp = align_up((size_t)d.B, 16);
+  const size_t Bp = d.B <= 16 ? 16 : (d.B <= 32 ? 32 : align_up((size_t)d.B, 64));
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;

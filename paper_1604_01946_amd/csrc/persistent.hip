@@ -1,7 +1,686 @@
+// Persistent recurrence kernels: the whole T-step, L-layer recurrence in ONE cooperative
+// launch, with the recurrent (and, for layers >= 1, the input) weights resident in registers.
+//
+// Section 4 of arXiv 1604.01946 names this as unexploited: the parameters are reused by every
+// iteration and could live in a lower level of memory, at the price of a capacity limit and of
+// assumptions outside the usual programming model (all blocks co-resident, blocks waiting on
+// each other).  On gfx950 the register file of one CU is 512 KB, so a workgroup that owns 8
+// hidden units keeps its [32 x 2H] slice of [W;R] (128 KB at H=512) in VGPRs as ready-made
+// MFMA A operands for the whole sequence.  Co-residency comes from a cooperative launch
+// (grid = L * H/8 <= number of CUs); ordering comes from per-(layer, step) counters in device
+// memory, released / acquired at agent scope, so that a layer only waits for the cells it
+// really depends on -- cell (l, t) needs (l, t-1) and (l-1, t) -- and the layers run as the
+// diagonal wavefront of Section 2.4 inside one grid.  Every wait is bounded: when the spin
+// limit expires the waiter raises a host-visible word and stops waiting for the rest of the
+// kernel, so the grid always drains.
+//
+// Forward data flow per step of workgroup (l, s):
+//   input half     acc  = W_l[rows, :] * h_{l-1,t}      (layers >= 1; layer 0 adds the batched P_0)
+//   recurrent half acc += R_l[rows, :] * h_{l,t-1}
+//   epilogue       4-way K-split summed through LDS, gates, c_t, h_t; h_t goes to the reserve
+//                  and, k-major ([H][BP]), to the exchange buffer the other workgroups read.
+// MFMA shape v_mfma_f32_16x16x4_f32: M = 32 weight rows (unit-major, gate-minor; two tiles),
+// N = batch, K split over the four waves.  The exchange buffer is k-major so that one 16-byte
+// load per lane (4 consecutive batch entries of one k) feeds the B operands of the four batch
+// tiles: tile j, column n is batch 4n + j.
 #include "../../include/lstm.h"
 #include "schedule.h"
+
+#include <mutex>
+#include <stdlib.h>
+
 namespace lstm {
-bool persistent_supported(const Dims&, bool) { return false; }
-int run_forward_persistent(const FwdArgs&) { return LSTM_UNSUPPORTED; }
-int run_backward_persistent(const BwdArgs&) { return LSTM_UNSUPPORTED; }
+
+#define CK(expr, what)                                             \
+  do {                                                             \
+    if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
+  } while (0)
+
+namespace {
+
+// ------------------------------------------------------------------ device helpers
+template <int NT>
+struct BVec;
+template <>
+struct BVec<1> {
+  static __device__ __forceinline__ void ld(const float* p, float (&v)[1]) { v[0] = *p; }
+};
+template <>
+struct BVec<2> {
+  static __device__ __forceinline__ void ld(const float* p, float (&v)[2]) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    v[0] = t.x; v[1] = t.y;
+  }
+};
+template <>
+struct BVec<4> {
+  static __device__ __forceinline__ void ld(const float* p, float (&v)[4]) {
+    const floatx4 t = *reinterpret_cast<const floatx4*>(p);
+    v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+  }
+};
+
+// Synchronisation protocol.  Exchange data is written with agent-scope (write-through) stores,
+// so publishing a step needs no L2 write-back: the producer waits for its stores to be
+// acknowledged (vmcnt(0)), the workgroup meets at a barrier, and one thread bumps the step
+// counter with an agent-scope atomic.  A consumer polls the counter with agent-scope loads and
+// only then issues its first-ever loads of that exchange slot; no cache of its CU or XCD can
+// hold those lines (every slot is written once per launch, slots are 128-byte aligned, and
+// every workgroup invalidates its caches once when the kernel starts), so no invalidate is
+// needed per step either.  `full` (LSTM_FULL_FENCES=1) swaps both sides for the compiler's
+// agent-scope release / acquire fences (L2 write-back and invalidate on every step), which is
+// several times slower and exists to cross-check the fast protocol.
+struct Waiter {
+  int* watchdog;  // host-visible word, set when a wait expires
+  int limit;
+  bool dead;
+  int full;
+  // Waits until *flag >= target.
+  __device__ __forceinline__ void wait(int* flag, int target) {
+    if (!dead) {
+      int spins = 0;
+      while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > limit) {
+          dead = true;
+          __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          break;
+        }
+      }
+    }
+    if (full)
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    else
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  }
+};
+
+// Store that other workgroups will read during this launch.
+__device__ __forceinline__ void xstore(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All threads have written; make it visible at agent scope and bump the counter once.
+__device__ __forceinline__ void signal(int* flag, int full) {
+  if (full)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  else
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// blockIdx -> (layer, slice).  Workgroups are dealt round-robin to the 8 XCDs, each with its
+// own L2; keeping a layer on 8/L XCDs lets its exchange reads be served by few L2s.
+__device__ __forceinline__ void map_block(int L, int NS, int& l, int& s) {
+  const int bid = blockIdx.x;
+  if (L <= 8 && 8 % L == 0 && NS % (8 / L) == 0 && (gridDim.x % 8) == 0) {
+    const int per = 8 / L, xcd = bid & 7;
+    l = xcd / per;
+    s = (bid >> 3) * per + (xcd % per);
+  } else {
+    l = bid / NS;
+    s = bid % NS;
+  }
+}
+
+struct PersFwdArgs {
+  const float* W;     // flat input matrices; layers >= 1 are read
+  const float* R;     // [L][4H][H]
+  const float* bias;  // [L][4H]
+  const float* P0;    // [T][B][4H] input projection of layer 0
+  const float* c0;    // [L][B][H] or null
+  float* hx;          // [L][T+1][H][BP] exchange, slot t+1 = h_t, slot 0 = h0
+  int* flags;         // [L][T+1], slot t+1 counts the slices of layer l that finished step t
+  int* watchdog;
+  float* res;         // reserve base
+  float* y;
+  float* hT;
+  float* cT;
+  int L, T, B, I, H;
+  int has_h0;
+  int spin_limit;
+  int full_fences;
+};
+
+// KG: k-groups (of 4) per wave and per operand half = H/16.  NT: batch tiles of 16.
+template <int KG, int NT>
+__global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
+  constexpr int H = 16 * KG, G = 4 * H, BP = 16 * NT, NS = H / 8;
+  constexpr int CPL = (2 * NT + 3) / 4;  // cells finalised per lane
+  __shared__ float part[4][2 * NT * 4][64];
+
+  int l, s;
+  map_block(a.L, NS, l, s);
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = lane >> 4, n = lane & 15;
+  const int u0 = 8 * s;
+  const size_t TB = (size_t)T * B;
+
+  // ---- weights -> registers, as MFMA A operands: lane (q, n) holds row n of tile mt at k = kbase + 4*kg + q
+  float wR[KG][2], wW[KG][2];
+  {
+    const float* Rl = a.R + (size_t)l * G * H;
+    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
+    const int kbase = wave * (H / 4) + q;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      const int unit = u0 + 4 * mt + (n >> 2), gate = n & 3;
+      const size_t row = ((size_t)gate * H + unit) * H;
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg) {
+        wR[kg][mt] = Rl[row + kbase + 4 * kg];
+        wW[kg][mt] = (l > 0) ? Wl[row + kbase + 4 * kg] : 0.f;
+      }
+    }
+  }
+
+  // ---- the cells this lane finalises
+  int c_unit[CPL], c_batch[CPL], c_p[CPL];
+  bool c_valid[CPL];
+  float c_state[CPL], c_bias[CPL][4];
+#pragma unroll
+  for (int ci = 0; ci < CPL; ++ci) {
+    const int p = wave + 4 * ci;
+    c_p[ci] = p;
+    const int mt = p / NT, j = p % NT;
+    c_unit[ci] = u0 + 4 * mt + q;
+    c_batch[ci] = NT * n + j;
+    c_valid[ci] = (p < 2 * NT) && (c_batch[ci] < B);
+    c_state[ci] = (c_valid[ci] && a.c0) ? a.c0[((size_t)l * B + c_batch[ci]) * H + c_unit[ci]] : 0.f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) c_bias[ci][g] = c_valid[ci] ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
+  }
+
+  float* const hx_l = a.hx + (size_t)l * (T + 1) * H * BP;
+  float* const hx_in = (l > 0) ? a.hx + (size_t)(l - 1) * (T + 1) * H * BP : nullptr;
+  int* const fl_l = a.flags + (size_t)l * (T + 1);
+  int* const fl_in = (l > 0) ? a.flags + (size_t)(l - 1) * (T + 1) : nullptr;
+  float* const res_l = a.res + (size_t)l * TB * 6 * H;
+  float* const res_gates = res_l;
+  float* const res_c = res_l + TB * 4 * H;
+  float* const res_h = res_l + TB * 5 * H;
+  const size_t boff = (size_t)(wave * (H / 4) + q) * BP + NT * n;  // this lane's B-operand offset inside a slot
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+
+  for (int t = 0; t < T; ++t) {
+    floatx4 acc[2][NT];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // layer 0: fetch the batched input projection early, it is consumed in the epilogue
+    float pin[CPL][4];
+#pragma unroll
+    for (int ci = 0; ci < CPL; ++ci)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        pin[ci][g] = (l == 0 && c_valid[ci]) ? a.P0[((size_t)t * B + c_batch[ci]) * G + g * H + c_unit[ci]] : 0.f;
+
+    if (l > 0) {  // input half: h of the layer below at this step
+      w.wait(fl_in + (t + 1), NS);
+      const float* src = hx_in + (size_t)(t + 1) * H * BP + boff;
+      float bv[KG][NT];
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg) BVec<NT>::ld(src + (size_t)4 * kg * BP, bv[kg]);
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[kg][mt], bv[kg][j], acc[mt][j], 0, 0, 0);
+    }
+    if (t > 0 || a.has_h0) {  // recurrent half: own layer, previous step
+      if (t > 0) w.wait(fl_l + t, NS);
+      const float* src = hx_l + (size_t)t * H * BP + boff;
+      float bv[KG][NT];
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg) BVec<NT>::ld(src + (size_t)4 * kg * BP, bv[kg]);
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wR[kg][mt], bv[kg][j], acc[mt][j], 0, 0, 0);
+    }
+
+    // ---- 4-way K-split reduction through LDS
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][(mt * NT + j) * 4 + r][lane] = acc[mt][j][r];
+    __syncthreads();
+
+    // ---- epilogue: register r of lane (q, n) in tile (mt, j) is (unit 4*mt+q, gate r, batch NT*n+j)
+    float* const hx_out = hx_l + (size_t)(t + 1) * H * BP;
+    float o_gate[CPL][4], o_c[CPL], o_h[CPL];
+#pragma unroll
+    for (int ci = 0; ci < CPL; ++ci) {
+      if (c_p[ci] < 2 * NT) {
+        float sg[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = c_p[ci] * 4 + r;
+          sg[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]) +
+                  pin[ci][r] + c_bias[ci][r];
+        }
+        o_gate[ci][0] = sigmoidf_dev(sg[0]);
+        o_gate[ci][1] = sigmoidf_dev(sg[1]);
+        o_gate[ci][2] = sigmoidf_dev(sg[2]);
+        o_gate[ci][3] = tanhf(sg[3]);
+        o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
+        o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
+        c_state[ci] = o_c[ci];
+        if (c_valid[ci]) xstore(&hx_out[(size_t)c_unit[ci] * BP + c_batch[ci]], o_h[ci]);
+      }
+    }
+    signal(fl_l + (t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` for the next step)
+    // the reserve and the outputs are not read before the kernel ends: written after the signal
+#pragma unroll
+    for (int ci = 0; ci < CPL; ++ci) {
+      if (c_valid[ci]) {
+        const size_t e = ((size_t)t * B + c_batch[ci]) * H + c_unit[ci];
+        const size_t g0 = ((size_t)t * B + c_batch[ci]) * G + c_unit[ci];
+        res_h[e] = o_h[ci];
+        res_c[e] = o_c[ci];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) res_gates[g0 + (size_t)g * H] = o_gate[ci][g];
+        if (l == a.L - 1) a.y[e] = o_h[ci];
+        if (t == T - 1) {
+          const size_t se = ((size_t)l * B + c_batch[ci]) * H + c_unit[ci];
+          if (a.hT) a.hT[se] = o_h[ci];
+          if (a.cT) a.cT[se] = o_c[ci];
+        }
+      }
+    }
+  }
+}
+
+// h0 [L][B][H] -> exchange slot 0 of every layer, k-major [H][BP].
+__global__ void pack_state_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H,
+                                  int BP) {
+  const long n = (long)L * B * H;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
+    hx[((size_t)l * (T + 1)) * H * BP + (size_t)k * BP + bb] = h0[e];
+  }
+}
+
+
+// ------------------------------------------------------------------ backward
+// Workgroup (l, s) owns hidden units u0..u0+7 of layer l.  Per step t (descending):
+//   point-wise   dh_t = dout_t + dh_rec,  gate gradients dA_t (4 x 8 x B values), dc carry;
+//                dA_t goes to the standard [T][B][4H] array (weight-gradient GEMMs) and, k-major
+//                ([4H][BP]), to the exchange buffer;
+//   GEMM         [dh_rec_{t-1} ; dx_{l,t}] (16 rows) = [R_l[:, units] | W_l[:, units]]^T * dA_t, K = 4H:
+//                rows 0-7 stay in registers for the next point-wise step, rows 8-15 are the gradient
+//                for the same units of layer l-1 at step t (its dout) and go to dxbuf.
+// Section 2.1's remark on the backward pass (four gate gradients map to one output through the
+// stacked matrices) is the K = 4H contraction; wave w takes the K range of gate w.
+// Counters: slot t+1 of layer l = "point-wise of step t published" (which, by program order, also
+// covers dx of step t+1); slot 0 = "dx of step 0 published".
+struct PersBwdArgs {
+  const float* W;      // flat input matrices (layers >= 1 are read here)
+  const float* R;      // [L][4H][H]
+  const float* res;    // reserve written by the forward pass
+  const float* c0;     // [L][B][H] or null
+  const float* dy;     // [T][B][H]
+  const float* dhT;    // [L][B][H] or null
+  const float* dcT;    // [L][B][H] or null
+  float* dA;           // [L][T][B][4H] gate gradients (standard layout)
+  float* dAx;          // [L][T][4H][BP] exchange
+  float* dxbuf;        // [L][T][B][H] gradient for the layer below (slice l written by layer l, l >= 1)
+  float* dh0;          // [L][B][H] or null
+  float* dc0;          // [L][B][H] or null
+  int* flags;          // [L][T+1]
+  int* watchdog;
+  int L, T, B, I, H;
+  int spin_limit;
+  int full_fences;
+};
+
+// KGB: k-groups (of 4) per wave = H/4 (wave w covers the rows of gate w).  NT: batch tiles of 16.
+template <int KGB, int NT>
+__global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
+  constexpr int H = 4 * KGB, G = 4 * H, BP = 16 * NT, NS = H / 8;
+  __shared__ float part[4][NT * 4][64];
+
+  int l, s;
+  map_block(a.L, NS, l, s);
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = lane >> 4, n = lane & 15;
+  const int u0 = 8 * s;
+  const size_t TB = (size_t)T * B;
+
+  // ---- weights -> registers: A operand row n (< 8: column u0+n of R_l, >= 8: column u0+n-8 of W_l),
+  //      k = wave*H + 4*kg + q
+  float wB[KGB];
+  {
+    const float* Rl = a.R + (size_t)l * G * H;
+    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
+    const float* src = (n < 8) ? Rl + u0 + n : Wl + u0 + (n - 8);
+    const bool live = (n < 8) || (l > 0);
+#pragma unroll
+    for (int kg = 0; kg < KGB; ++kg) wB[kg] = live ? src[(size_t)(wave * H + 4 * kg + q) * H] : 0.f;
+  }
+
+  // ---- the cells this lane owns in the point-wise stage: wave j finalises batch tile j;
+  //      lanes q < 2 hold dh_rec of units 4q..4q+3, lanes q >= 2 hold dx of units 4(q-2)..+3
+  const int batch = NT * n + wave;
+  const bool fin = wave < NT;                       // this wave finalises a tile
+  const bool pw = fin && q < 2 && batch < B;        // lane runs the point-wise stage
+  const bool dxl = fin && q >= 2 && batch < B && l > 0;
+  const int unit0 = u0 + 4 * (q & 1);               // first of the lane's four units
+  float dc[4], dh_rec[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const size_t se = ((size_t)l * B + batch) * H + unit0 + r;
+    dc[r] = (pw && a.dcT) ? a.dcT[se] : 0.f;
+    dh_rec[r] = (pw && a.dhT) ? a.dhT[se] : 0.f;
+  }
+
+  const float* const res_l = a.res + (size_t)l * TB * 6 * H;
+  const float* const res_gates = res_l;
+  const float* const res_c = res_l + TB * 4 * H;
+  float* const dA_l = a.dA + (size_t)l * TB * G;
+  float* const dAx_l = a.dAx + (size_t)l * T * G * BP;
+  int* const fl_l = a.flags + (size_t)l * (T + 1);
+  int* const fl_up = (l < a.L - 1) ? a.flags + (size_t)(l + 1) * (T + 1) : nullptr;
+  const float* const dout_base = (l < a.L - 1) ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
+  float* const dx_out = a.dxbuf + (size_t)l * TB * H;
+  const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+
+  for (int t = T - 1; t >= 0; --t) {
+    // ---- point-wise stage of step t
+    floatx4 gi, gf, go, gg, ct, cp, dA4[4];
+    const size_t e = ((size_t)t * B + batch) * H + unit0;
+    const size_t g0 = ((size_t)t * B + batch) * G + unit0;
+    if (pw) {
+      gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
+      gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
+      go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
+      gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
+      ct = *reinterpret_cast<const floatx4*>(res_c + e);
+      if (t > 0)
+        cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
+      else if (a.c0)
+        cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + batch) * H + unit0);
+      else
+        cp = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (fl_up) w.wait(fl_up + t, NS);  // dx of the layer above at step t is published
+    if (pw) {
+      const floatx4 dout = *reinterpret_cast<const floatx4*>(dout_base + e);
+      float* const xo = dAx_l + (size_t)t * G * BP + batch;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float dh = dout[r] + dh_rec[r];
+        const float tc = tanhf(ct[r]);
+        const float dcv = dc[r] + dh * go[r] * (1.f - tc * tc);
+        dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
+        dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
+        dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
+        dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
+        dc[r] = dcv * gf[r];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) xstore(xo + (size_t)(g * H + unit0 + r) * BP, dA4[g][r]);
+      }
+    }
+    signal(fl_l + (t + 1), a.full_fences);
+    if (pw) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
+    }
+
+    // ---- GEMM of step t: needs dA_t of every slice of this layer
+    w.wait(fl_l + (t + 1), NS);
+    floatx4 acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    {
+      const float* src = dAx_l + (size_t)t * G * BP + boff;
+      constexpr int CH = 32;  // k-groups per chunk: bounds the registers held by loads in flight
+#pragma unroll
+      for (int c0 = 0; c0 < KGB; c0 += CH) {
+        float bv[CH][NT];
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+          if (c0 + i < KGB) BVec<NT>::ld(src + (size_t)4 * (c0 + i) * BP, bv[i]);
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+          if (c0 + i < KGB)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wB[c0 + i], bv[i][j], acc[j], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) part[wave][j * 4 + r][lane] = acc[j][r];
+    __syncthreads();
+    if (fin) {
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = wave * 4 + r;
+        v[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]);
+      }
+      if (q < 2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dh_rec[r] = v[r];
+      } else if (dxl) {
+        float* const o = dx_out + ((size_t)t * B + batch) * H + unit0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) xstore(o + r, v[r]);
+      }
+    }
+    // `part` is next written after the barrier inside the next signal()
+  }
+  signal(fl_l, a.full_fences);  // slot 0: dx of step 0 published
+  if (pw) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const size_t se = ((size_t)l * B + batch) * H + unit0 + r;
+      if (a.dh0) a.dh0[se] = dh_rec[r];
+      if (a.dc0) a.dc0[se] = dc[r];
+    }
+  }
+}
+
+// ------------------------------------------------------------------ host state
+struct DeviceInfo {
+  bool ok = false;
+  int cus = 0;
+  int coop = 0;
+};
+std::mutex g_mu;
+DeviceInfo g_dev[64];
+bool g_dev_init[64];
+int* g_watch_host = nullptr;
+int* g_watch_dev = nullptr;
+
+bool device_info(DeviceInfo& out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+    (void)hipGetLastError();
+    return false;
+  }
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_dev_init[dev]) {
+    DeviceInfo di;
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) di.cus = v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess) di.coop = v;
+    (void)hipGetLastError();
+    di.ok = di.cus > 0;
+    g_dev[dev] = di;
+    g_dev_init[dev] = true;
+  }
+  out = g_dev[dev];
+  return out.ok;
+}
+
+bool ensure_watchdog() {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (g_watch_host) return true;
+  void* p = nullptr;
+  if (hipHostMalloc(&p, 64, hipHostMallocMapped) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  g_watch_host = reinterpret_cast<int*>(p);
+  *g_watch_host = 0;
+  void* d = nullptr;
+  if (hipHostGetDevicePointer(&d, p, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipHostFree(p);
+    g_watch_host = nullptr;
+    return false;
+  }
+  g_watch_dev = reinterpret_cast<int*>(d);
+  return true;
+}
+
+int spin_limit() {
+  const char* e = getenv("LSTM_SPIN_LIMIT");
+  if (e && *e) {
+    const long v = atol(e);
+    if (v > 0 && v < (1L << 30)) return (int)v;
+  }
+  return 1 << 21;
+}
+
+int full_fences() {
+  const char* e = getenv("LSTM_FULL_FENCES");
+  return (e && *e && *e != '0') ? 1 : 0;
+}
+
+inline int batch_tiles(int B) { return B <= 16 ? 1 : (B <= 32 ? 2 : 4); }
+
+template <int KG>
+hipError_t launch_fwd(int NT, int grid, const PersFwdArgs& a, hipStream_t s) {
+  void* params[] = {const_cast<PersFwdArgs*>(&a)};
+  const void* fn = NT == 1 ? (const void*)pers_fwd_kernel<KG, 1>
+                           : (NT == 2 ? (const void*)pers_fwd_kernel<KG, 2> : (const void*)pers_fwd_kernel<KG, 4>);
+  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+}
+
+template <int KGB>
+hipError_t launch_bwd(int NT, int grid, const PersBwdArgs& a, hipStream_t s) {
+  void* params[] = {const_cast<PersBwdArgs*>(&a)};
+  const void* fn = NT == 1 ? (const void*)pers_bwd_kernel<KGB, 1>
+                           : (NT == 2 ? (const void*)pers_bwd_kernel<KGB, 2> : (const void*)pers_bwd_kernel<KGB, 4>);
+  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+}
+
+}  // namespace
+
+void release_persistent() {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (g_watch_host) {
+    (void)hipHostFree(g_watch_host);
+    g_watch_host = nullptr;
+    g_watch_dev = nullptr;
+  }
+}
+
+bool persistent_supported(const Dims& d, bool backward) {
+  (void)backward;
+  if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
+  if (d.B > 64) return false;
+  DeviceInfo di;
+  if (!device_info(di) || !di.coop) return false;
+  return (long)d.L * (d.H / 8) <= di.cus;
+}
+
+int run_forward_persistent(const FwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
+  hipStream_t s = a.stream;
+  if (!ensure_watchdog()) return LSTM_HIP_ERROR;
+  if (*g_watch_host) return LSTM_INTERNAL;
+  const int NT = batch_tiles(d.B), BP = 16 * NT;
+  float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
+  int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
+  float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
+  {
+    ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 4, s), "zero step counters");
+    if (a.h0) {
+      const long n = (long)d.L * d.B * d.H;
+      hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
+                         d.H, BP);
+      CK(hipGetLastError(), "pack h0");
+    }
+  }
+  {
+    ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
+    GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
+    CK(launch_gemm_group(&p, 1, s), "input projection GEMM (layer 0)");
+  }
+  PersFwdArgs k;
+  k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
+  k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
+  k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();
+  k.full_fences = full_fences();
+  const int grid = d.L * (d.H / 8);
+  ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+  hipError_t e = hipErrorInvalidValue;
+  if (d.H == 512) e = launch_fwd<32>(NT, grid, k, s);
+  else if (d.H == 256) e = launch_fwd<16>(NT, grid, k, s);
+  else if (d.H == 128) e = launch_fwd<8>(NT, grid, k, s);
+  CK(e, "persistent forward launch");
+  return LSTM_OK;
+}
+
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped);
+
+int run_backward_persistent(const BwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
+  hipStream_t s = a.stream;
+  if (!ensure_watchdog()) return LSTM_HIP_ERROR;
+  if (*g_watch_host) return LSTM_INTERNAL;
+  const int NT = batch_tiles(d.B);
+  int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
+  float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
+  {
+    ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 4, s), "zero step counters");
+  }
+  PersBwdArgs k;
+  k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
+  k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
+  k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
+  k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+  const int grid = d.L * (d.H / 8);
+  {
+    ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+    hipError_t e = hipErrorInvalidValue;
+    if (d.H == 512) e = launch_bwd<128>(NT, grid, k, s);
+    else if (d.H == 256) e = launch_bwd<64>(NT, grid, k, s);
+    else if (d.H == 128) e = launch_bwd<32>(NT, grid, k, s);
+    CK(e, "persistent backward launch");
+  }
+  if (a.dx) {  // layer 0's input gradient: all T steps in one product
+    ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
+    GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)G, (long)G, 1, d.I, 1, d.I, 0};
+    CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");
+  }
+  return weight_gradients(a, dA, true);
+}
+
 }  // namespace lstm

@@ -31,7 +31,10 @@ def run_case(cfg, seed, flags, backward=True, with_states=True, with_dstates=Tru
     torch.cuda.synchronize()
     e = assert_close(r.fwd_outputs(), ref, FWD, FWD_TOL, f"fwd {cfg.dims} flags={flags}")
     if backward:
-        binding.check(r.backward(flags=flags), "lstm_backward")
+        bflags = flags
+        if flags == binding.LSTM_PATH_PERSISTENT and binding.lstm_auto_path(*cfg.dims, 1) != flags:
+            bflags = 0  # the persistent backward does not take this shape: use the automatic choice
+        binding.check(r.backward(flags=bflags), "lstm_backward")
         torch.cuda.synchronize()
         e.update(assert_close(r.bwd_outputs(), ref, BWD, BWD_TOL, f"bwd {cfg.dims} flags={flags}"))
     print("  errors:", {k: f"{v:.2e}" for k, v in e.items()}, flush=True)
@@ -86,7 +89,7 @@ def test_cfg2_forward(flags):
     run_case(CONFIGS["cfg2"], 0, flags, backward=False)
 
 
-@pytest.mark.parametrize("flags", [0, 4, 5])
+@pytest.mark.parametrize("flags", [0, 4, 5, 6])
 def test_cfg3_forward_backward(flags):
     run_case(CONFIGS["cfg3"], 0, flags)
 
@@ -95,9 +98,29 @@ def test_cfg4_large_hidden():
     run_case(CONFIGS["cfg4"], 0, 0)
 
 
-@pytest.mark.parametrize("flags", [0, 4])
+@pytest.mark.parametrize("flags", [0, 4, 6])
 def test_cfg5_small_batch_long_sequence(flags):
     run_case(CONFIGS["cfg5"], 0, flags, with_states=False, with_dstates=False)
+
+
+# ------------------------------------------------------------------ persistent path: every shape class it takes
+PERS = [
+    Config("p128", L=2, T=5, B=16, I=40, H=128, state_std=0.3, dstate_std=0.3),
+    Config("p128L8", L=8, T=4, B=7, I=128, H=128, state_std=0.3, dstate_std=0.3),
+    Config("p256b1", L=2, T=12, B=1, I=256, H=256, state_std=0.3, dstate_std=0.3),
+    Config("p256b20", L=3, T=6, B=20, I=64, H=256, state_std=0.3, dstate_std=0.3),
+    Config("p512b33", L=2, T=5, B=33, I=72, H=512, state_std=0.3, dstate_std=0.3),
+    Config("p512b64", L=4, T=7, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),
+    Config("p512L1", L=1, T=9, B=48, I=512, H=512, state_std=0.3, dstate_std=0.3),
+]
+
+
+@pytest.mark.parametrize("cfg", PERS, ids=[c.name for c in PERS])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_persistent_shapes(cfg, with_states):
+    _, binding, _ = _mods()
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
 # ------------------------------------------------------------------ ragged / odd shapes, several tiles
