@@ -100,6 +100,12 @@ __device__ __forceinline__ void xstore(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// 16-byte variant: the exchange tiles are staged in LDS and written as whole 128-byte lines, which
+// the memory side takes far better than scattered 4-byte write-through stores.
+__device__ __forceinline__ void xstore4(float* p, floatx4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // All threads have written; make it visible at agent scope and bump the counter once.
 __device__ __forceinline__ void signal(int* flag, int full) {
   if (full)
@@ -149,6 +155,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   constexpr int H = 16 * KG, G = 4 * H, BP = 16 * NT, NS = H / 8;
   constexpr int CPL = (2 * NT + 3) / 4;  // cells finalised per lane
   __shared__ float part[4][2 * NT * 4][64];
+  __shared__ __attribute__((aligned(16))) float xs[8 * BP];  // this step's h slice, [unit][batch]
 
   int l, s;
   map_block(a.L, NS, l, s);
@@ -279,10 +286,13 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
         o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
         o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
         c_state[ci] = o_c[ci];
-        if (c_valid[ci]) xstore(&hx_out[(size_t)c_unit[ci] * BP + c_batch[ci]], o_h[ci]);
+        xs[(c_unit[ci] - u0) * BP + c_batch[ci]] = c_valid[ci] ? o_h[ci] : 0.f;
       }
     }
-    signal(fl_l + (t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` for the next step)
+    __syncthreads();
+    if (threadIdx.x < 2 * BP)  // the slice's 8 rows are contiguous in the k-major exchange slot
+      xstore4(hx_out + (size_t)u0 * BP + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
+    signal(fl_l + (t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
     // the reserve and the outputs are not read before the kernel ends: written after the signal
 #pragma unroll
     for (int ci = 0; ci < CPL; ++ci) {
@@ -352,6 +362,7 @@ template <int KGB, int NT>
 __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   constexpr int H = 4 * KGB, G = 4 * H, BP = 16 * NT, NS = H / 8;
   __shared__ float part[4][NT * 4][64];
+  __shared__ __attribute__((aligned(16))) float xs[32 * BP];  // this step's dA slice, [gate][unit][batch]
 
   int l, s;
   map_block(a.L, NS, l, s);
@@ -421,9 +432,14 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         cp = floatx4{0.f, 0.f, 0.f, 0.f};
     }
     if (fl_up) w.wait(fl_up + t, NS);  // dx of the layer above at step t is published
+    if (fin && q < 2 && !pw) {  // padded batch columns of the staged tile
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + batch] = 0.f;
+    }
     if (pw) {
       const floatx4 dout = *reinterpret_cast<const floatx4*>(dout_base + e);
-      float* const xo = dAx_l + (size_t)t * G * BP + batch;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float dh = dout[r] + dh_rec[r];
@@ -435,7 +451,19 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
         dc[r] = dcv * gf[r];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) xstore(xo + (size_t)(g * H + unit0 + r) * BP, dA4[g][r]);
+        for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + batch] = dA4[g][r];
+      }
+    }
+    __syncthreads();
+    {  // per gate the slice's 8 rows are contiguous in the k-major exchange slot
+      float* const xo = dAx_l + (size_t)t * G * BP;
+#pragma unroll
+      for (int i = 0; i < (8 * BP + 255) / 256; ++i) {
+        const int idx = threadIdx.x + 256 * i;
+        if (idx < 8 * BP) {
+          const int g = idx / (2 * BP), rem = idx % (2 * BP);
+          xstore4(xo + (size_t)(g * H + u0) * BP + 4 * rem, *reinterpret_cast<const floatx4*>(xs + 4 * idx));
+        }
       }
     }
     signal(fl_l + (t + 1), a.full_fences);
@@ -482,9 +510,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) dh_rec[r] = v[r];
       } else if (dxl) {
-        float* const o = dx_out + ((size_t)t * B + batch) * H + unit0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) xstore(o + r, v[r]);
+        xstore4(dx_out + ((size_t)t * B + batch) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
       }
     }
     // `part` is next written after the barrier inside the next signal()
