@@ -153,6 +153,14 @@ void lstm_profile_enable(int on);
 int lstm_profile_read(float* ms, int* count);
 const char* lstm_phase_name(int phase);
 
+/*
+ * Diagnostic hook for the persistent path: while a buffer is set, the workgroup with index
+ * `block` of every persistent launch writes a wall-clock time stamp (100 MHz ticks, int64) at
+ * up to 8 points of each step into device_buf[step*8 + point].  The buffer must hold T*8 int64
+ * values for the launches it is used with (smaller buffers are ignored); NULL turns it off.
+ */
+void lstm_debug_set_trace(void* device_buf, size_t bytes, int block);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* lstm_status_string(int status);
 

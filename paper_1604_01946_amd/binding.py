@@ -31,7 +31,7 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
     "lstm_auto_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
-    "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name",
+    "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name", "lstm_debug_set_trace",
 ]
 LSTM_PHASE_COUNT = 8
 
@@ -75,6 +75,8 @@ def library():
         lib.lstm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
         lib.lstm_phase_name.restype = ctypes.c_char_p
         lib.lstm_phase_name.argtypes = [i]
+        lib.lstm_debug_set_trace.restype = None
+        lib.lstm_debug_set_trace.argtypes = [p, z, i]
         _lib = lib
     return _lib
 
@@ -155,6 +157,10 @@ def lstm_profile_read():
     cnt = (ctypes.c_int * LSTM_PHASE_COUNT)()
     st = library().lstm_profile_read(ms, cnt)
     return st, {lstm_phase_name(k): (float(ms[k]), int(cnt[k])) for k in range(LSTM_PHASE_COUNT)}
+
+
+def lstm_debug_set_trace(device_buf, nbytes, block):
+    library().lstm_debug_set_trace(_ptr(device_buf), nbytes, block)
 
 
 def check(status, where="lstm"):

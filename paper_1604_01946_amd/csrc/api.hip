@@ -116,6 +116,8 @@ const char* lstm_last_error(void) { return g_last_error.c_str(); }
 
 void lstm_shutdown(void) { release_helpers(); }
 
+void lstm_debug_set_trace(void* device_buf, size_t bytes, int block) { set_trace(device_buf, bytes, block); }
+
 void lstm_profile_enable(int on) { g_prof_on = on != 0; }
 
 int lstm_profile_read(float* ms, int* count) {

@@ -87,6 +87,7 @@ struct StepBwdArgs {
   float* dh_out;         // [B][H] out when !pointwise (dh0)
   int pointwise;         // 0: only dh_out = dA_next * R (+dh_extra)
   int B, H;
+  int units_per_wg;      // set by the launcher
 };
 hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream);
 

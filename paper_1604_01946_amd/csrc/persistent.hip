@@ -75,9 +75,14 @@ struct Waiter {
   int limit;
   bool dead;
   int full;
-  // Waits until *flag >= target.
-  __device__ __forceinline__ void wait(int* flag, int target) {
-    if (!dead) {
+  // Non-blocking read of a counter; issue it early and hand the value to wait() later so that the
+  // round trip of the first poll overlaps other work.
+  static __device__ __forceinline__ int peek(int* flag) {
+    return __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // Waits until *flag >= target; `seen` is a value peeked earlier (pass 0 if none).
+  __device__ __forceinline__ void wait(int* flag, int target, int seen = 0) {
+    if (!dead && seen < target) {
       int spins = 0;
       while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
         __builtin_amdgcn_s_sleep(1);
@@ -88,10 +93,21 @@ struct Waiter {
         }
       }
     }
+    acquire();
+  }
+  __device__ __forceinline__ void acquire() const {
     if (full)
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     else
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  }
+};
+
+// Optional time-stamping of one workgroup's step phases (diagnostic hook lstm_debug_set_trace).
+struct Tracer {
+  long long* buf;  // [steps][8] wall-clock ticks (100 MHz), null when disabled
+  __device__ __forceinline__ void mark(int step, int slot) const {
+    if (buf && threadIdx.x == 0) buf[(size_t)step * 8 + slot] = wall_clock64();
   }
 };
 
@@ -147,6 +163,8 @@ struct PersFwdArgs {
   int has_h0;
   int spin_limit;
   int full_fences;
+  long long* trace;
+  int trace_block;
 };
 
 // KG: k-groups (of 4) per wave and per operand half = H/16.  NT: batch tiles of 16.
@@ -165,6 +183,9 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   const int u0 = 8 * s;
   const size_t TB = (size_t)T * B;
 
+  // Register i of a wave covers k-group (i + rot) mod KG: workgroups (and waves) that share an L2
+  // walk the exchange slot from different starting points instead of all hitting one channel.
+  const int rot = ((int)(blockIdx.x >> 3) + __builtin_amdgcn_readfirstlane(wave)) & (KG - 1);
   // ---- weights -> registers, as MFMA A operands: lane (q, n) holds row n of tile mt at k = kbase + 4*kg + q
   float wR[KG][2], wW[KG][2];
   {
@@ -176,9 +197,10 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       const int unit = u0 + 4 * mt + (n >> 2), gate = n & 3;
       const size_t row = ((size_t)gate * H + unit) * H;
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg) {
-        wR[kg][mt] = Rl[row + kbase + 4 * kg];
-        wW[kg][mt] = (l > 0) ? Wl[row + kbase + 4 * kg] : 0.f;
+      for (int i = 0; i < KG; ++i) {
+        const int kg = (i + rot) & (KG - 1);
+        wR[i][mt] = Rl[row + kbase + 4 * kg];
+        wW[i][mt] = (l > 0) ? Wl[row + kbase + 4 * kg] : 0.f;
       }
     }
   }
@@ -211,9 +233,11 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   const size_t boff = (size_t)(wave * (H / 4) + q) * BP + NT * n;  // this lane's B-operand offset inside a slot
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
   for (int t = 0; t < T; ++t) {
+    tr.mark(t, 0);
     floatx4 acc[2][NT];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -228,33 +252,55 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       for (int g = 0; g < 4; ++g)
         pin[ci][g] = (l == 0 && c_valid[ci]) ? a.P0[((size_t)t * B + c_batch[ci]) * G + g * H + c_unit[ci]] : 0.f;
 
-    if (l > 0) {  // input half: h of the layer below at this step
-      w.wait(fl_in + (t + 1), NS);
+    // Loads are issued in bulk ahead of the MFMAs that consume them (the scheduling barriers keep
+    // the compiler from re-serialising them): a step is bound by load latency otherwise.
+    const bool do_in = l > 0, do_rec = (t > 0 || a.has_h0);
+    const int seen_in = do_in ? Waiter::peek(fl_in + (t + 1)) : 0;
+    const int seen_rec = (t > 0) ? Waiter::peek(fl_l + t) : 0;
+    float bi[KG][NT], br[KG][NT];
+    if (do_in) {  // input half: h of the layer below at this step
+      w.wait(fl_in + (t + 1), NS, seen_in);
       const float* src = hx_in + (size_t)(t + 1) * H * BP + boff;
-      float bv[KG][NT];
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg) BVec<NT>::ld(src + (size_t)4 * kg * BP, bv[kg]);
+      for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, bi[i]);
+      tr.mark(t, 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg)
+      for (int i = 0; i < KG / 2; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[kg][mt], bv[kg][j], acc[mt][j], 0, 0, 0);
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (t > 0 || a.has_h0) {  // recurrent half: own layer, previous step
-      if (t > 0) w.wait(fl_l + t, NS);
+    if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
+      if (t > 0) w.wait(fl_l + t, NS, seen_rec);
+      tr.mark(t, 2);
       const float* src = hx_l + (size_t)t * H * BP + boff;
-      float bv[KG][NT];
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg) BVec<NT>::ld(src + (size_t)4 * kg * BP, bv[kg]);
+      for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, br[i]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (do_in) {
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg)
+      for (int i = KG / 2; i < KG; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wR[kg][mt], bv[kg][j], acc[mt][j], 0, 0, 0);
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (do_rec) {
+#pragma unroll
+      for (int i = 0; i < KG; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wR[i][mt], br[i][j], acc[mt][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- 4-way K-split reduction through LDS
@@ -264,7 +310,9 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int r = 0; r < 4; ++r) part[wave][(mt * NT + j) * 4 + r][lane] = acc[mt][j][r];
+    tr.mark(t, 3);
     __syncthreads();
+    tr.mark(t, 4);
 
     // ---- epilogue: register r of lane (q, n) in tile (mt, j) is (unit 4*mt+q, gate r, batch NT*n+j)
     float* const hx_out = hx_l + (size_t)(t + 1) * H * BP;
@@ -292,7 +340,9 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
     __syncthreads();
     if (threadIdx.x < 2 * BP)  // the slice's 8 rows are contiguous in the k-major exchange slot
       xstore4(hx_out + (size_t)u0 * BP + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
+    tr.mark(t, 5);
     signal(fl_l + (t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+    tr.mark(t, 6);
     // the reserve and the outputs are not read before the kernel ends: written after the signal
 #pragma unroll
     for (int ci = 0; ci < CPL; ++ci) {
@@ -355,6 +405,8 @@ struct PersBwdArgs {
   int L, T, B, I, H;
   int spin_limit;
   int full_fences;
+  long long* trace;
+  int trace_block;
 };
 
 // KGB: k-groups (of 4) per wave = H/4 (wave w covers the rows of gate w).  NT: batch tiles of 16.
@@ -374,6 +426,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 
   // ---- weights -> registers: A operand row n (< 8: column u0+n of R_l, >= 8: column u0+n-8 of W_l),
   //      k = wave*H + 4*kg + q
+  const int rot = ((int)(blockIdx.x >> 3) * (KGB / 32) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (KGB - 1);
   float wB[KGB];
   {
     const float* Rl = a.R + (size_t)l * G * H;
@@ -381,7 +434,8 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
     const float* src = (n < 8) ? Rl + u0 + n : Wl + u0 + (n - 8);
     const bool live = (n < 8) || (l > 0);
 #pragma unroll
-    for (int kg = 0; kg < KGB; ++kg) wB[kg] = live ? src[(size_t)(wave * H + 4 * kg + q) * H] : 0.f;
+    for (int i = 0; i < KGB; ++i)
+      wB[i] = live ? src[(size_t)(wave * H + 4 * ((i + rot) & (KGB - 1)) + q) * H] : 0.f;
   }
 
   // ---- the cells this lane owns in the point-wise stage: wave j finalises batch tile j;
@@ -411,9 +465,12 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
+  int seen_up = 0;
   for (int t = T - 1; t >= 0; --t) {
+    tr.mark(t, 0);
     // ---- point-wise stage of step t
     floatx4 gi, gf, go, gg, ct, cp, dA4[4];
     const size_t e = ((size_t)t * B + batch) * H + unit0;
@@ -431,7 +488,8 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
       else
         cp = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    if (fl_up) w.wait(fl_up + t, NS);  // dx of the layer above at step t is published
+    if (fl_up) w.wait(fl_up + t, NS, seen_up);  // dx of the layer above at step t is published
+    tr.mark(t, 1);
     if (fin && q < 2 && !pw) {  // padded batch columns of the staged tile
 #pragma unroll
       for (int r = 0; r < 4; ++r)
@@ -466,7 +524,9 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         }
       }
     }
+    tr.mark(t, 2);
     signal(fl_l + (t + 1), a.full_fences);
+    tr.mark(t, 3);
     if (pw) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
@@ -474,31 +534,42 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 
     // ---- GEMM of step t: needs dA_t of every slice of this layer
     w.wait(fl_l + (t + 1), NS);
+    tr.mark(t, 4);
+    seen_up = (fl_up && t > 0) ? Waiter::peek(fl_up + (t - 1)) : 0;  // needed by the next point-wise stage
     floatx4 acc[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     {
       const float* src = dAx_l + (size_t)t * G * BP + boff;
-      constexpr int CH = 32;  // k-groups per chunk: bounds the registers held by loads in flight
+      // double-buffered chunks of CH k-groups: the loads of chunk c+1 are in flight under the MFMAs
+      // of chunk c (the scheduling barriers keep the compiler from re-serialising them)
+      constexpr int CH = (KGB >= 64) ? 32 : 16, NCH = KGB / CH;
+      float bv[2][CH][NT];
 #pragma unroll
-      for (int c0 = 0; c0 < KGB; c0 += CH) {
-        float bv[CH][NT];
+      for (int i = 0; i < CH; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KGB - 1)) * BP, bv[0][i]);
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        if (c + 1 < NCH) {
+#pragma unroll
+          for (int i = 0; i < CH; ++i)
+            BVec<NT>::ld(src + (size_t)4 * (((c + 1) * CH + i + rot) & (KGB - 1)) * BP, bv[(c + 1) & 1][i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < CH; ++i)
-          if (c0 + i < KGB) BVec<NT>::ld(src + (size_t)4 * (c0 + i) * BP, bv[i]);
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-          if (c0 + i < KGB)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wB[c0 + i], bv[i][j], acc[j], 0, 0, 0);
+          for (int j = 0; j < NT; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wB[c * CH + i], bv[c & 1][i][j], acc[j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) part[wave][j * 4 + r][lane] = acc[j][r];
+    tr.mark(t, 5);
     __syncthreads();
+    tr.mark(t, 6);
     if (fin) {
       float v[4];
 #pragma unroll
@@ -589,6 +660,10 @@ int spin_limit() {
   return 1 << 21;
 }
 
+long long* g_trace_buf = nullptr;
+size_t g_trace_bytes = 0;
+int g_trace_block = 0;
+
 int full_fences() {
   const char* e = getenv("LSTM_FULL_FENCES");
   return (e && *e && *e != '0') ? 1 : 0;
@@ -613,6 +688,12 @@ hipError_t launch_bwd(int NT, int grid, const PersBwdArgs& a, hipStream_t s) {
 }
 
 }  // namespace
+
+void set_trace(void* buf, size_t bytes, int block) {
+  g_trace_buf = reinterpret_cast<long long*>(buf);
+  g_trace_bytes = buf ? bytes : 0;
+  g_trace_block = block;
+}
 
 void release_persistent() {
   std::lock_guard<std::mutex> lk(g_mu);
@@ -662,6 +743,8 @@ int run_forward_persistent(const FwdArgs& a) {
   k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();
   k.full_fences = full_fences();
+  k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+  k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
   ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
   hipError_t e = hipErrorInvalidValue;
@@ -692,6 +775,8 @@ int run_backward_persistent(const BwdArgs& a) {
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
   k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+  k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+  k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
   {
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);

@@ -49,6 +49,7 @@ unsigned resolve_auto_path(const Dims& d, bool backward);
 int run_forward(const FwdArgs& a, unsigned path);
 int run_backward(const BwdArgs& a, unsigned path);
 void release_helpers();
+void set_trace(void* buf, size_t bytes, int block);
 hipError_t record(hipError_t e, const char* what);
 
 // Phase timing hooks (no-ops unless lstm_profile_enable(1)).

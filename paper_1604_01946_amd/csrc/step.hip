@@ -66,20 +66,30 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
       bvalid[j] = bb < B;
       brow[j] = a.h_prev + (long)(bvalid[j] ? bb : 0) * H;
     }
-    for (int ks = wave; ks * 16 < H; ks += 4) {
-      const int k = ks * 16 + 4 * q;
-      floatx4 av[2], bv[NT];
+    // U k-steps per trip: all of their loads are issued before the first MFMA so that enough bytes
+    // are in flight to stream the weights at memory speed (k-steps past the end load zeros)
+    constexpr int U = (NT == 4) ? 4 : 8;
+    for (int ks = wave; ks * 16 < H; ks += 4 * U) {
+      floatx4 av[U][2], bv[U][NT];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) av[mt] = load4<VEC>(arow[mt], k, H, avalid[mt]);
+      for (int u = 0; u < U; ++u) {
+        const int k = (ks + 4 * u) * 16 + 4 * q;
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bv[j] = load4<VEC>(brow[j], k, H, bvalid[j]);
+        for (int mt = 0; mt < 2; ++mt) av[u][mt] = load4<VEC>(arow[mt], k, H, avalid[mt]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+        for (int j = 0; j < NT; ++j) bv[u][j] = load4<VEC>(brow[j], k, H, bvalid[j]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][e], bv[j][e], acc[mt][j], 0, 0, 0);
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][mt][e], bv[u][j][e], acc[mt][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 #pragma unroll
@@ -118,7 +128,10 @@ template <int NT, bool VEC>
 __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
   __shared__ float part[4][NT * 4][64];
   const int H = a.H, B = a.B, K = 4 * a.H;
-  const int u0 = blockIdx.x * 16, b0 = blockIdx.y * 16 * NT;
+  // upw = 16 fills the MFMA tile; upw = 8 (rows 8..15 idle) doubles the number of workgroups when
+  // the grid would otherwise leave CUs without work (the step is bound by streaming R, not by MFMA)
+  const int upw = a.units_per_wg;
+  const int u0 = blockIdx.x * upw, b0 = blockIdx.y * 16 * NT;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, n = lane & 15;
 
@@ -127,7 +140,7 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
   for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   if (a.dA_next) {
-    const bool avalid = (u0 + n) < H;
+    const bool avalid = n < upw && (u0 + n) < H;
     const float* arow = a.RT + (long)(avalid ? u0 + n : 0) * K;
     const float* brow[NT];
     bool bvalid[NT];
@@ -137,16 +150,24 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
       bvalid[j] = bb < B;
       brow[j] = a.dA_next + (long)(bvalid[j] ? bb : 0) * K;
     }
-    for (int ks = wave; ks * 16 < K; ks += 4) {
-      const int k = ks * 16 + 4 * q;
-      floatx4 bv[NT];
-      const floatx4 av = load4<VEC>(arow, k, K, avalid);
+    constexpr int U = (NT == 4) ? 4 : 8;
+    for (int ks = wave; ks * 16 < K; ks += 4 * U) {
+      floatx4 av[U], bv[U][NT];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bv[j] = load4<VEC>(brow[j], k, K, bvalid[j]);
+      for (int u = 0; u < U; ++u) {
+        const int k = (ks + 4 * u) * 16 + 4 * q;
+        av[u] = load4<VEC>(arow, k, K, avalid);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+        for (int j = 0; j < NT; ++j) bv[u][j] = load4<VEC>(brow[j], k, K, bvalid[j]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[e], bv[j][e], acc[j], 0, 0, 0);
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][e], bv[u][j][e], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 #pragma unroll
@@ -161,7 +182,7 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int unit = u0 + 4 * q + r;
-      if (unit >= H || bb >= B) continue;
+      if (4 * q + r >= upw || unit >= H || bb >= B) continue;
       const long e = (long)bb * H + unit, g0 = (long)bb * 4 * H + unit;
       float dh = (part[0][j * 4 + r][lane] + part[1][j * 4 + r][lane]) + (part[2][j * 4 + r][lane] + part[3][j * 4 + r][lane]);
       if (a.dh_extra) dh += a.dh_extra[e];
@@ -197,8 +218,11 @@ hipError_t launch_fwd_nt(const StepFwdArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 template <bool VEC>
-hipError_t launch_bwd_nt(const StepBwdArgs& a, hipStream_t s) {
-  const int gx = (a.H + 15) / 16;
+hipError_t launch_bwd_nt(const StepBwdArgs& a0, hipStream_t s) {
+  StepBwdArgs a = a0;
+  const int bt = a.B <= 64 ? 1 : (a.B + 63) / 64;
+  a.units_per_wg = (((a.H + 15) / 16) * bt < 192) ? 8 : 16;
+  const int gx = (a.H + a.units_per_wg - 1) / a.units_per_wg;
   if (a.B <= 16)
     hipLaunchKernelGGL((step_bwd_kernel<1, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
   else if (a.B <= 32)
