@@ -75,7 +75,7 @@ WsLayout ws_layout(const Dims& d) {
   };
   w.P = take(L * TB * G * 4);
   w.dx = take(L * TB * H * 4);
-  w.RT = take(L * H * G * 4);
+  w.RT = take(L * step_pack_floats(d.H) * 4);
   w.state = take(4 * L * d.B * H * 4);
   w.dbpart = take(L * 64 * G * 4);
   w.scratch = take(8 * (size_t)d.B * G * 4);

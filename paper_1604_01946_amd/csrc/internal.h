@@ -59,7 +59,7 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 
 // ---------------------------------------------------------------- fused step kernels (step.hip)
 struct StepFwdArgs {
-  const float* R;       // [4H][H]
+  const float* Rp;      // recurrent matrix of this layer, packed by launch_pack_fwd
   const float* h_prev;  // [B][H] or null (zeros)
   const float* c_prev;  // [B][H] or null (zeros)
   const float* P;       // [B][4H] input projection of this step
@@ -74,7 +74,7 @@ struct StepFwdArgs {
 hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream);
 
 struct StepBwdArgs {
-  const float* RT;       // [H][4H] transposed recurrent matrix
+  const float* RTp;      // recurrent matrix of this layer, packed by launch_pack_bwd
   const float* dA_next;  // [B][4H] gate gradients of step t+1, null at the last step
   const float* dh_extra; // [B][H] added to dh (dhT at the last step), may be null
   const float* dout;     // [B][H] gradient from above (dy or the upper layer's input gradient); null when !pointwise
@@ -90,6 +90,12 @@ struct StepBwdArgs {
   int units_per_wg;      // set by the launcher
 };
 hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream);
+
+// Per-pass weight re-layout for the step kernels (Section 2.3): R [L][4H][H] -> the order in which
+// the forward / backward step kernels stream it.  per_layer_floats = step_pack_floats(H).
+size_t step_pack_floats(int H);
+hipError_t launch_pack_fwd(const float* R, float* Rp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
+hipError_t launch_pack_bwd(const float* R, float* RTp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
 
 // ---------------------------------------------------------------- device math
 __device__ __forceinline__ float sigmoidf_dev(float z) { return 1.0f / (1.0f + expf(-z)); }

@@ -689,6 +689,11 @@ hipError_t launch_bwd(int NT, int grid, const PersBwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
+int device_cu_count() {
+  DeviceInfo di;
+  return device_info(di) ? di.cus : 0;
+}
+
 void set_trace(void* buf, size_t bytes, int block) {
   g_trace_buf = reinterpret_cast<long long*>(buf);
   g_trace_bytes = buf ? bytes : 0;

@@ -12,7 +12,7 @@ struct Dims {
 struct WsLayout {
   size_t P;        // [L][T*B][4H]  forward: input projections; backward: gate gradients dA
   size_t dx;       // [L][T*B][H]   backward: gradient handed from layer l to layer l-1
-  size_t RT;       // [L][H][4H]    backward: transposed recurrent matrices
+  size_t RT;       // [L][step_pack_floats(H)]  recurrent matrices packed for the step kernels
   size_t state;    // [4][L][B][H]  carried cell/hidden gradients, zero block
   size_t dbpart;   // [L][64][4H]   bias-gradient partial sums
   size_t scratch;  // [8][B][4H]    per-cell temporaries of the unfused paths

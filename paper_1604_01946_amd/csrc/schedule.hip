@@ -25,9 +25,16 @@ int run_forward_persistent(const FwdArgs& a);
 int run_backward_persistent(const BwdArgs& a);
 bool persistent_supported(const Dims& d, bool backward);
 
+int device_cu_count();
+
 unsigned resolve_auto_path(const Dims& d, bool backward) {
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
-  return LSTM_PATH_WAVEFRONT;
+  // Overlapping layers on streams pays when one step kernel leaves CUs idle (Section 2.4: the
+  // gain is largest for small layers); a step that already fills the chip runs layer by layer.
+  const int cus = device_cu_count();
+  const long wgs = (long)((d.H + 3) / 4) * ((d.B + 63) / 64);
+  if (d.L > 1 && (cus == 0 || wgs < 2L * cus)) return LSTM_PATH_WAVEFRONT;
+  return LSTM_PATH_STEP;
 }
 
 namespace {
@@ -50,12 +57,18 @@ int fwd_step(const FwdArgs& a) {
   const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
   hipStream_t s = a.stream;
+  float* Rp = ws_f(a.ws, a.w.RT);
+  const size_t pf = step_pack_floats(d.H);
+  {
+    ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+    CK(launch_pack_fwd(a.R, Rp, d.L, d.H, d.B, pf, s), "pack R");
+  }
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const LayerRes r = layer_res(a.reserve, d, l);
     const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
     const float* Wl = a.W + w_offset(d, l);
-    const float* Rl = a.R + (size_t)l * G * d.H;
+    const float* Rl = Rp + (size_t)l * pf;
     float* P = ws_f(a.ws, a.w.P) + (size_t)l * TB * G;
     {
       ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
@@ -65,7 +78,7 @@ int fwd_step(const FwdArgs& a) {
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     for (int t = 0; t < d.T; ++t) {
       StepFwdArgs sa;
-      sa.R = Rl;
+      sa.Rp = Rl;
       sa.h_prev = t ? r.h + (size_t)(t - 1) * BH : (a.h0 ? a.h0 + l * BH : nullptr);
       sa.c_prev = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : nullptr);
       sa.P = P + (size_t)t * d.B * G;
@@ -217,12 +230,13 @@ int bwd_step(const BwdArgs& a) {
   hipStream_t s = a.stream;
   float* dA_all = ws_f(a.ws, a.w.P);
   float* RT = ws_f(a.ws, a.w.RT);
+  const size_t pf = step_pack_floats(H);
   float* dxb = ws_f(a.ws, a.w.dx);
   float* dcb = ws_f(a.ws, a.w.state);
   // weights re-laid out once per pass: the backward products read R transposed (Section 2.3)
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_transpose(a.R, RT, (int)G, H, d.L, s), "transpose R");
+    CK(launch_pack_bwd(a.R, RT, d.L, H, B, pf, s), "pack R (transposed)");
   }
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
@@ -233,7 +247,7 @@ int bwd_step(const BwdArgs& a) {
     prof_begin(LSTM_PHASE_BWD_RECURRENCE, s);
     for (int t = T - 1; t >= 0; --t) {
       StepBwdArgs sa;
-      sa.RT = RT + (size_t)l * H * G;
+      sa.RTp = RT + (size_t)l * pf;
       sa.dA_next = (t < T - 1) ? dA + (size_t)(t + 1) * BG : nullptr;
       sa.dh_extra = (t == T - 1 && a.dhT) ? a.dhT + l * BH : nullptr;
       sa.dout = dout + (size_t)t * BH;
@@ -251,7 +265,7 @@ int bwd_step(const BwdArgs& a) {
     }
     if (a.dh0) {
       StepBwdArgs sa{};
-      sa.RT = RT + (size_t)l * H * G;
+      sa.RTp = RT + (size_t)l * pf;
       sa.dA_next = dA;
       sa.dh_out = a.dh0 + l * BH;
       sa.pointwise = 0;

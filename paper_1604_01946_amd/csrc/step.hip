@@ -1,20 +1,25 @@
 // Fused per-step kernels: recurrent GEMM over the four stacked gates with the point-wise
-// cell update as its epilogue (forward), and the mirrored backward step.
+// cell update as its epilogue (forward), the mirrored backward step, and the weight pack
+// kernels that feed them.
 //
 // Section 2.1 of arXiv 1604.01946 stacks the four gate matrices that share an input into
-// one [4H x H] operand; Section 2.2.2 fuses all point-wise work of a cell into one kernel.
-// Here both live in one kernel: a workgroup owns a slice of hidden units *with all four
-// gate rows of that slice*, so the gate pre-activations never leave the chip.
+// one [4H x H] operand; Section 2.2.2 fuses all point-wise work of a cell into one kernel;
+// Section 2.3 re-lays the weight matrices out once per pass because they are reused by every
+// step.  Here a workgroup owns a slice of hidden units *with all four gate rows of that
+// slice*, so the gate pre-activations never leave the chip, and the per-pass re-layout goes
+// further than a transpose: the recurrent matrix is packed into exactly the order in which
+// the step kernel's waves consume it, so that a step streams it with whole 1 KB loads at
+// consecutive addresses (at large H the step is bound by reading R once, nothing else).
 //
-// Mapping (forward): workgroup = 8 hidden units x (16*NT) batch rows; the 32 weight rows
-// (unit-major, gate-minor) are the M side of v_mfma_f32_16x16x4_f32, the batch is the N
-// side, and K = H is split over the 4 waves (wave w takes the k-steps w, w+4, ...).  Both
-// operands are read straight from memory as 16-byte runs along K -- lane (q = lane/16,
-// n = lane%16) fetches k = 16*ks + 4q .. +3 of row n, and element e of that fetch feeds the
-// e-th MFMA of the k-step -- so no LDS staging is needed.  The four partial sums meet in
-// LDS; in the D layout a lane already holds all four gates of one (unit, batch) cell.
-// Backward: workgroup = 16 hidden units x (16*NT) batch rows, K = 4H over the transposed
-// recurrent matrix; the epilogue is the point-wise gate-gradient computation.
+// Mapping (forward): workgroup = 4*MT hidden units x (16*NT) batch rows; the 16*MT weight rows
+// (unit-major, gate-minor) are the M side of v_mfma_f32_16x16x4_f32, the batch is the N side,
+// and K = H is split into four contiguous quarters, one per wave.  Lane (q = lane/16,
+// n = lane%16) holds k = 16*ks + 4q .. +3 of row n for k-step ks, and element e of that
+// 16-byte value feeds the e-th MFMA of the k-step; the B operand (h_{t-1}, [B][H]) is read
+// straight from memory the same way.  The four partial sums meet in LDS; in the D layout a
+// lane already holds all four gates of one (unit, batch) cell.
+// Backward: workgroup = upw (8 or 16) hidden units x (16*NT) batch rows, K = 4H over the
+// transposed recurrent matrix; the epilogue is the point-wise gate-gradient computation.
 #include "internal.h"
 
 namespace lstm {
@@ -35,29 +40,83 @@ __device__ __forceinline__ floatx4 load4(const float* __restrict__ row, int k, i
   return v;
 }
 
-template <int NT, bool VEC>
+// k-steps (of 16) per wave for a contraction length K
+__host__ __device__ inline int ksteps_per_wave(int K) { return (((K + 15) / 16) + 3) / 4; }
+
+// ------------------------------------------------------------------ weight pack (once per pass)
+// Forward order: [slice][wave][k-step][m-tile][lane][4]; zero where the slice or K runs out.
+__global__ void pack_fwd_kernel(const float* __restrict__ R, floatx4* __restrict__ Rp, int H, int MT, long per_layer) {
+  const int per = ksteps_per_wave(H);
+  const int NS = (H + 4 * MT - 1) / (4 * MT);
+  const long total = (long)NS * 4 * per * MT * 64;
+  const float* Rl = R + (size_t)blockIdx.y * 4 * H * H;
+  floatx4* out = Rp + (size_t)blockIdx.y * per_layer;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int lane = (int)(i & 63);
+    long r = i >> 6;
+    const int mt = (int)(r % MT); r /= MT;
+    const int ksl = (int)(r % per); r /= per;
+    const int w = (int)(r & 3);
+    const int s = (int)(r >> 2);
+    const int q = lane >> 4, n = lane & 15;
+    const int unit = s * 4 * MT + 4 * mt + (n >> 2), gate = n & 3;
+    const int k = (w * per + ksl) * 16 + 4 * q;
+    floatx4 v = {0.f, 0.f, 0.f, 0.f};
+    if (unit < H) {
+      const float* row = Rl + ((size_t)gate * H + unit) * H;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (k + e < H) v[e] = row[k + e];
+    }
+    out[i] = v;
+  }
+}
+
+// Backward order: [slice][wave][k-step][lane][4] over R^T (row = hidden unit, K = 4H).
+__global__ void pack_bwd_kernel(const float* __restrict__ R, floatx4* __restrict__ Rp, int H, int upw, long per_layer) {
+  const int K = 4 * H, per = ksteps_per_wave(K);
+  const int NS = (H + upw - 1) / upw;
+  const long total = (long)NS * 4 * per * 64;
+  const float* Rl = R + (size_t)blockIdx.y * 4 * H * H;
+  floatx4* out = Rp + (size_t)blockIdx.y * per_layer;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    // lanes of one output block differ in n fastest: the source reads run along the unit axis
+    const int lane = (int)(i & 63);
+    long r = i >> 6;
+    const int ksl = (int)(r % per); r /= per;
+    const int w = (int)(r & 3);
+    const int s = (int)(r >> 2);
+    const int q = lane >> 4, n = lane & 15;
+    const int unit = s * upw + n;
+    const int k = (w * per + ksl) * 16 + 4 * q;
+    floatx4 v = {0.f, 0.f, 0.f, 0.f};
+    if (n < upw && unit < H) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (k + e < K) v[e] = Rl[(size_t)(k + e) * H + unit];
+    }
+    out[i] = v;
+  }
+}
+
+// ------------------------------------------------------------------ forward step
+template <int NT, int MT, bool VEC>
 __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
-  __shared__ float part[4][2 * NT * 4][64];
+  __shared__ float part[4][MT * NT * 4][64];
   const int H = a.H, B = a.B;
-  const int u0 = blockIdx.x * 8, b0 = blockIdx.y * 16 * NT;
+  const int u0 = blockIdx.x * 4 * MT, b0 = blockIdx.y * 16 * NT;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, n = lane & 15;
 
-  floatx4 acc[2][NT];
+  floatx4 acc[MT][NT];
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   if (a.h_prev) {
-    const float* arow[2];
-    bool avalid[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int unit = u0 + 4 * mt + (n >> 2), gate = n & 3;
-      avalid[mt] = unit < H;
-      arow[mt] = a.R + ((long)gate * H + (avalid[mt] ? unit : 0)) * H;
-    }
+    const int per = ksteps_per_wave(H);
+    const floatx4* ap = reinterpret_cast<const floatx4*>(a.Rp) + ((size_t)(blockIdx.x * 4 + wave) * per) * MT * 64 + lane;
     const float* brow[NT];
     bool bvalid[NT];
 #pragma unroll
@@ -66,34 +125,50 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
       bvalid[j] = bb < B;
       brow[j] = a.h_prev + (long)(bvalid[j] ? bb : 0) * H;
     }
-    // U k-steps per trip: all of their loads are issued before the first MFMA so that enough bytes
-    // are in flight to stream the weights at memory speed (k-steps past the end load zeros)
-    constexpr int U = (NT == 4) ? 4 : 8;
-    for (int ks = wave; ks * 16 < H; ks += 4 * U) {
-      floatx4 av[U][2], bv[U][NT];
+    // Chunks of U k-steps, double-buffered: the loads of chunk c+1 are issued before the MFMAs of
+    // chunk c, so with one wave per SIMD the weight stream still overlaps the matrix work (the
+    // scheduling barriers keep the compiler from re-serialising loads and MFMAs).
+    constexpr int U = 4;
+    const int klim = min(H, (wave + 1) * per * 16);
+    floatx4 av[2][U][MT], bv[2][U][NT];
+    auto load_chunk = [&](int c, floatx4 (&ava)[U][MT], floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int k = (ks + 4 * u) * 16 + 4 * q;
+        const int ksl = c * U + u;
+        const bool in = ksl < per;
+        const int k = (wave * per + ksl) * 16 + 4 * q;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) av[u][mt] = load4<VEC>(arow[mt], k, H, avalid[mt]);
+        for (int mt = 0; mt < MT; ++mt) ava[u][mt] = in ? ap[(size_t)(ksl * MT + mt) * 64] : floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < NT; ++j) bv[u][j] = load4<VEC>(brow[j], k, H, bvalid[j]);
+        for (int j = 0; j < NT; ++j) bva[u][j] = load4<VEC>(brow[j], k, klim, bvalid[j] && in);
       }
-      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mma_chunk = [&](const floatx4 (&ava)[U][MT], const floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
+          for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][mt][e], bv[u][j][e], acc[mt][j], 0, 0, 0);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ava[u][mt][e], bva[u][j][e], acc[mt][j], 0, 0, 0);
+    };
+    const int nch = (per + U - 1) / U;
+    load_chunk(0, av[0], bv[0]);
+    for (int c = 0; c < nch; c += 2) {
+      load_chunk(c + 1, av[1], bv[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_chunk(av[0], bv[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_chunk(c + 2, av[0], bv[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (c + 1 < nch) mma_chunk(av[1], bv[1]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -101,7 +176,7 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
   __syncthreads();
 
   // D layout: register r of lane (q, n) is row 4q + r = (unit_local q, gate r), column n (batch).
-  for (int p = wave; p < 2 * NT; p += 4) {
+  for (int p = wave; p < MT * NT; p += 4) {
     const int mt = p / NT, j = p % NT;
     const int unit = u0 + 4 * mt + q, bb = b0 + 16 * j + n;
     float s[4];
@@ -124,6 +199,7 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ backward step
 template <int NT, bool VEC>
 __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
   __shared__ float part[4][NT * 4][64];
@@ -140,8 +216,8 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
   for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   if (a.dA_next) {
-    const bool avalid = n < upw && (u0 + n) < H;
-    const float* arow = a.RT + (long)(avalid ? u0 + n : 0) * K;
+    const int per = ksteps_per_wave(K);
+    const floatx4* ap = reinterpret_cast<const floatx4*>(a.RTp) + ((size_t)(blockIdx.x * 4 + wave) * per) * 64 + lane;
     const float* brow[NT];
     bool bvalid[NT];
 #pragma unroll
@@ -150,23 +226,38 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
       bvalid[j] = bb < B;
       brow[j] = a.dA_next + (long)(bvalid[j] ? bb : 0) * K;
     }
-    constexpr int U = (NT == 4) ? 4 : 8;
-    for (int ks = wave; ks * 16 < K; ks += 4 * U) {
-      floatx4 av[U], bv[U][NT];
+    constexpr int U = 4;
+    const int klim = min(K, (wave + 1) * per * 16);
+    floatx4 av[2][U], bv[2][U][NT];
+    auto load_chunk = [&](int c, floatx4 (&ava)[U], floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int k = (ks + 4 * u) * 16 + 4 * q;
-        av[u] = load4<VEC>(arow, k, K, avalid);
+        const int ksl = c * U + u;
+        const bool in = ksl < per;
+        const int k = (wave * per + ksl) * 16 + 4 * q;
+        ava[u] = in ? ap[(size_t)ksl * 64] : floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < NT; ++j) bv[u][j] = load4<VEC>(brow[j], k, K, bvalid[j]);
+        for (int j = 0; j < NT; ++j) bva[u][j] = load4<VEC>(brow[j], k, klim, bvalid[j] && in);
       }
-      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mma_chunk = [&](const floatx4 (&ava)[U], const floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u][e], bv[u][j][e], acc[j], 0, 0, 0);
+          for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ava[u][e], bva[u][j][e], acc[j], 0, 0, 0);
+    };
+    const int nch = (per + U - 1) / U;
+    load_chunk(0, av[0], bv[0]);
+    for (int c = 0; c < nch; c += 2) {
+      load_chunk(c + 1, av[1], bv[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_chunk(av[0], bv[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_chunk(c + 2, av[0], bv[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (c + 1 < nch) mma_chunk(av[1], bv[1]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -205,23 +296,21 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int batch_tiles_y(int B) { return B <= 64 ? 1 : (B + 63) / 64; }
 
-template <bool VEC>
-hipError_t launch_fwd_nt(const StepFwdArgs& a, hipStream_t s) {
-  const int gx = (a.H + 7) / 8;
+template <int MT, bool VEC>
+hipError_t launch_fwd_mt(const StepFwdArgs& a, hipStream_t s) {
+  const int gx = (a.H + 4 * MT - 1) / (4 * MT);
   if (a.B <= 16)
-    hipLaunchKernelGGL((step_fwd_kernel<1, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((step_fwd_kernel<1, MT, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
   else if (a.B <= 32)
-    hipLaunchKernelGGL((step_fwd_kernel<2, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((step_fwd_kernel<2, MT, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL((step_fwd_kernel<4, VEC>), dim3(gx, (a.B + 63) / 64), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((step_fwd_kernel<4, MT, VEC>), dim3(gx, (a.B + 63) / 64), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 template <bool VEC>
-hipError_t launch_bwd_nt(const StepBwdArgs& a0, hipStream_t s) {
-  StepBwdArgs a = a0;
-  const int bt = a.B <= 64 ? 1 : (a.B + 63) / 64;
-  a.units_per_wg = (((a.H + 15) / 16) * bt < 192) ? 8 : 16;
+hipError_t launch_bwd_nt(const StepBwdArgs& a, hipStream_t s) {
   const int gx = (a.H + a.units_per_wg - 1) / a.units_per_wg;
   if (a.B <= 16)
     hipLaunchKernelGGL((step_bwd_kernel<1, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
@@ -234,13 +323,43 @@ hipError_t launch_bwd_nt(const StepBwdArgs& a0, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
-  const bool vec = (a.H % 4 == 0) && aligned16(a.R) && (a.h_prev == nullptr || aligned16(a.h_prev));
-  return vec ? launch_fwd_nt<true>(a, stream) : launch_fwd_nt<false>(a, stream);
+// 8 units per workgroup halve the re-reads of h_{t-1}; 4 units double the workgroup count when 8
+// would leave CUs idle.
+int step_fwd_mtiles(int H, int B) { return (((H + 7) / 8) * batch_tiles_y(B) < 200) ? 1 : 2; }
+int step_bwd_units(int H, int B) { return (((H + 15) / 16) * batch_tiles_y(B) < 192) ? 8 : 16; }
+
+size_t step_pack_floats(int H) {
+  // upper bound of both packed layouts for one layer, in floats
+  const size_t fwd = (size_t)((H + 3) / 4) * 4 * ksteps_per_wave(H) * 2 * 256;
+  const size_t bwd = (size_t)((H + 7) / 8) * 4 * ksteps_per_wave(4 * H) * 256;
+  return fwd > bwd ? fwd : bwd;
 }
 
-hipError_t launch_step_bwd(const StepBwdArgs& a, hipStream_t stream) {
-  const bool vec = aligned16(a.RT) && (a.dA_next == nullptr || aligned16(a.dA_next));  // K = 4H is a multiple of 4
+hipError_t launch_pack_fwd(const float* R, float* Rp, int L, int H, int B, size_t per_layer_floats, hipStream_t s) {
+  const int MT = step_fwd_mtiles(H, B);
+  hipLaunchKernelGGL(pack_fwd_kernel, dim3(512, L), dim3(256), 0, s, R, reinterpret_cast<floatx4*>(Rp), H, MT,
+                     (long)(per_layer_floats / 4));
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_bwd(const float* R, float* RTp, int L, int H, int B, size_t per_layer_floats, hipStream_t s) {
+  const int upw = step_bwd_units(H, B);
+  hipLaunchKernelGGL(pack_bwd_kernel, dim3(512, L), dim3(256), 0, s, R, reinterpret_cast<floatx4*>(RTp), H, upw,
+                     (long)(per_layer_floats / 4));
+  return hipGetLastError();
+}
+
+hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
+  const bool vec = (a.H % 4 == 0) && (a.h_prev == nullptr || aligned16(a.h_prev));
+  if (step_fwd_mtiles(a.H, a.B) == 1)
+    return vec ? launch_fwd_mt<1, true>(a, stream) : launch_fwd_mt<1, false>(a, stream);
+  return vec ? launch_fwd_mt<2, true>(a, stream) : launch_fwd_mt<2, false>(a, stream);
+}
+
+hipError_t launch_step_bwd(const StepBwdArgs& a0, hipStream_t stream) {
+  StepBwdArgs a = a0;
+  a.units_per_wg = step_bwd_units(a.H, a.B);
+  const bool vec = (a.dA_next == nullptr || aligned16(a.dA_next));  // K = 4H is a multiple of 4
   return vec ? launch_bwd_nt<true>(a, stream) : launch_bwd_nt<false>(a, stream);
 }
 

@@ -95,6 +95,12 @@ int run_forward_wavefront(const FwdArgs& a) {
   auto ev_gemm = [&](int l, int j) { return h->events[1 + 2 * ((size_t)l * NCH + j)]; };
   auto ev_steps = [&](int l, int j) { return h->events[2 + 2 * ((size_t)l * NCH + j)]; };
 
+  float* Rp = ws_f(a.ws, a.w.RT);
+  const size_t pf = step_pack_floats(d.H);
+  {
+    ProfScope ps(LSTM_PHASE_FWD_PACK, a.stream);
+    CK(launch_pack_fwd(a.R, Rp, L, d.H, d.B, pf, a.stream), "pack R");
+  }
   CK(hipEventRecord(h->events[0], a.stream), "fork");
   for (int i = 0; i < 2 * L; ++i) CK(hipStreamWaitEvent(h->streams[i], h->events[0], 0), "fork wait");
   prof_begin(LSTM_PHASE_FWD_RECURRENCE, a.stream);
@@ -119,7 +125,7 @@ int run_forward_wavefront(const FwdArgs& a) {
       CK(hipStreamWaitEvent(step_stream(l), ev_gemm(l, j), 0), "wait gemm");
       for (int t = t0; t < t1; ++t) {
         StepFwdArgs sa;
-        sa.R = a.R + (size_t)l * G * d.H;
+        sa.Rp = Rp + (size_t)l * pf;
         sa.h_prev = t ? r.h + (size_t)(t - 1) * BH : (a.h0 ? a.h0 + l * BH : nullptr);
         sa.c_prev = t ? r.c + (size_t)(t - 1) * BH : (a.c0 ? a.c0 + l * BH : nullptr);
         sa.P = P + (size_t)t * d.B * G;
@@ -168,9 +174,10 @@ int run_backward_wavefront(const BwdArgs& a) {
   float* RT = ws_f(a.ws, a.w.RT);
   float* dxb = ws_f(a.ws, a.w.dx);
   float* dcb = ws_f(a.ws, a.w.state);
+  const size_t pf = step_pack_floats(H);
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, a.stream);
-    CK(launch_transpose(a.R, RT, (int)G, H, L, a.stream), "transpose R");
+    CK(launch_pack_bwd(a.R, RT, L, H, B, pf, a.stream), "pack R (transposed)");
   }
   {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -203,7 +210,7 @@ int run_backward_wavefront(const BwdArgs& a) {
         if (l < L - 1) CK(hipStreamWaitEvent(step_stream(l), ev_gemm(l + 1, j), 0), "wait upper layer");
         for (int t = t1 - 1; t >= t0; --t) {
           StepBwdArgs sa;
-          sa.RT = RT + (size_t)l * H * G;
+          sa.RTp = RT + (size_t)l * pf;
           sa.dA_next = (t < T - 1) ? dA + (size_t)(t + 1) * BG : nullptr;
           sa.dh_extra = (t == T - 1 && a.dhT) ? a.dhT + l * BH : nullptr;
           sa.dout = dout + (size_t)t * BH;
@@ -221,7 +228,7 @@ int run_backward_wavefront(const BwdArgs& a) {
         }
         if (t0 == 0 && a.dh0) {
           StepBwdArgs sa{};
-          sa.RT = RT + (size_t)l * H * G;
+          sa.RTp = RT + (size_t)l * pf;
           sa.dA_next = dA;
           sa.dh_out = a.dh0 + l * BH;
           sa.pointwise = 0;
