@@ -310,3 +310,20 @@ def test_fp32_variant_shows_noise_floor():
     assert np.max(np.abs(y32 - y)) / np.max(np.abs(y)) < 1e-5
     for p, q in zip(g32, g):
         assert np.max(np.abs(p - q)) / np.max(np.abs(q)) < 1e-4
+
+
+def test_oracle_digest_unchanged():
+    """Drift guard: the stored digest was written by tests/golden/make_golden.py from the oracle alone."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.digest()
+    for line in open(os.path.join(here, "oracle_cfg1_digest.txt")):
+        if line.startswith("#"):
+            continue
+        name, *vals = line.split()
+        for a, b in zip(now[name], map(float, vals)):
+            assert abs(a - b) <= 1e-12 * max(1.0, abs(b)), name
