@@ -152,8 +152,8 @@ struct PersFwdArgs {
   const float* bias;  // [L][4H]
   const float* P0;    // [T][B][4H] input projection of layer 0
   const float* c0;    // [L][B][H] or null
-  float* hx;          // [L][T+1][H][BP] exchange, slot t+1 = h_t, slot 0 = h0
-  int* flags;         // [L][T+1], slot t+1 counts the slices of layer l that finished step t
+  float* hx;          // [L][T+1][NC][H][BP] exchange, slot t+1 = h_t, slot 0 = h0
+  int* flags;         // [L][T+1][NC], slot t+1 counts the slices of layer l that finished step t
   int* watchdog;
   float* res;         // reserve base
   float* y;
@@ -167,11 +167,15 @@ struct PersFwdArgs {
   int trace_block;
 };
 
-// KG: k-groups (of 4) per wave and per operand half = H/16.  NT: batch tiles of 16.
-template <int KG, int NT>
+// KG: k-groups (of 4) per wave and per operand half = H/16.  NT: batch tiles of 16 per chain.
+// NC: batch chains.  The recurrences of different batch rows are independent, so the batch is cut
+// into NC chains of 16*NT rows that share the resident weights but have their own exchange slots
+// and counters; a workgroup alternates between them, and while one chain's h_t is on its way to
+// the other workgroups the matrix cores work on the other chain.
+template <int KG, int NT, int NC>
 __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   constexpr int H = 16 * KG, G = 4 * H, BP = 16 * NT, NS = H / 8;
-  constexpr int CPL = (2 * NT + 3) / 4;  // cells finalised per lane
+  constexpr int CPL = (2 * NT + 3) / 4;  // cells finalised per lane and chain
   __shared__ float part[4][2 * NT * 4][64];
   __shared__ __attribute__((aligned(16))) float xs[8 * BP];  // this step's h slice, [unit][batch]
 
@@ -205,179 +209,186 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
     }
   }
 
-  // ---- the cells this lane finalises
-  int c_unit[CPL], c_batch[CPL], c_p[CPL];
-  bool c_valid[CPL];
-  float c_state[CPL], c_bias[CPL][4];
+  // ---- the cells this lane finalises: pair p = (tile mt, tile j) -> unit 4*mt+q, chain-local batch NT*n+j
+  int c_unit[CPL], c_lb[CPL], c_p[CPL];
+  float c_bias[CPL][4];
+  bool c_valid[NC][CPL];
+  float c_state[NC][CPL];
 #pragma unroll
   for (int ci = 0; ci < CPL; ++ci) {
     const int p = wave + 4 * ci;
     c_p[ci] = p;
     const int mt = p / NT, j = p % NT;
     c_unit[ci] = u0 + 4 * mt + q;
-    c_batch[ci] = NT * n + j;
-    c_valid[ci] = (p < 2 * NT) && (c_batch[ci] < B);
-    c_state[ci] = (c_valid[ci] && a.c0) ? a.c0[((size_t)l * B + c_batch[ci]) * H + c_unit[ci]] : 0.f;
+    c_lb[ci] = NT * n + j;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) c_bias[ci][g] = c_valid[ci] ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
+    for (int g = 0; g < 4; ++g) c_bias[ci][g] = (p < 2 * NT) ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int bb = c * BP + c_lb[ci];
+      c_valid[c][ci] = (p < 2 * NT) && (bb < B);
+      c_state[c][ci] = (c_valid[c][ci] && a.c0) ? a.c0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
+    }
   }
 
-  float* const hx_l = a.hx + (size_t)l * (T + 1) * H * BP;
-  float* const hx_in = (l > 0) ? a.hx + (size_t)(l - 1) * (T + 1) * H * BP : nullptr;
-  int* const fl_l = a.flags + (size_t)l * (T + 1);
-  int* const fl_in = (l > 0) ? a.flags + (size_t)(l - 1) * (T + 1) : nullptr;
   float* const res_l = a.res + (size_t)l * TB * 6 * H;
   float* const res_gates = res_l;
   float* const res_c = res_l + TB * 4 * H;
   float* const res_h = res_l + TB * 5 * H;
   const size_t boff = (size_t)(wave * (H / 4) + q) * BP + NT * n;  // this lane's B-operand offset inside a slot
+  auto slot = [&](int layer, int sl, int c) { return a.hx + (((size_t)layer * (T + 1) + sl) * NC + c) * H * BP; };
+  auto flag = [&](int layer, int sl, int c) { return a.flags + ((size_t)layer * (T + 1) + sl) * NC + c; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
   for (int t = 0; t < T; ++t) {
-    tr.mark(t, 0);
-    floatx4 acc[2][NT];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int c = 0; c < NC; ++c) {
+      if (c == 0) tr.mark(t, 0);
+      floatx4 acc[2][NT];
 #pragma unroll
-      for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // layer 0: fetch the batched input projection early, it is consumed in the epilogue
-    float pin[CPL][4];
+      // layer 0: fetch the batched input projection early, it is consumed in the epilogue
+      float pin[CPL][4];
 #pragma unroll
-    for (int ci = 0; ci < CPL; ++ci)
+      for (int ci = 0; ci < CPL; ++ci)
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
-        pin[ci][g] = (l == 0 && c_valid[ci]) ? a.P0[((size_t)t * B + c_batch[ci]) * G + g * H + c_unit[ci]] : 0.f;
+        for (int g = 0; g < 4; ++g)
+          pin[ci][g] = (l == 0 && c_valid[c][ci])
+                           ? a.P0[((size_t)t * B + c * BP + c_lb[ci]) * G + g * H + c_unit[ci]] : 0.f;
 
-    // Loads are issued in bulk ahead of the MFMAs that consume them (the scheduling barriers keep
-    // the compiler from re-serialising them): a step is bound by load latency otherwise.
-    const bool do_in = l > 0, do_rec = (t > 0 || a.has_h0);
-    const int seen_in = do_in ? Waiter::peek(fl_in + (t + 1)) : 0;
-    const int seen_rec = (t > 0) ? Waiter::peek(fl_l + t) : 0;
-    float bi[KG][NT], br[KG][NT];
-    if (do_in) {  // input half: h of the layer below at this step
-      w.wait(fl_in + (t + 1), NS, seen_in);
-      const float* src = hx_in + (size_t)(t + 1) * H * BP + boff;
+      // Loads are issued in bulk ahead of the MFMAs that consume them (the scheduling barriers keep
+      // the compiler from re-serialising them): a step is bound by load latency otherwise.
+      const bool do_in = l > 0, do_rec = (t > 0 || a.has_h0);
+      const int seen_in = do_in ? Waiter::peek(flag(l - 1, t + 1, c)) : 0;
+      const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t, c)) : 0;
+      float bi[KG][NT], br[KG][NT];
+      if (do_in) {  // input half: h of the layer below at this step
+        w.wait(flag(l - 1, t + 1, c), NS, seen_in);
+        const float* src = slot(l - 1, t + 1, c) + boff;
 #pragma unroll
-      for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, bi[i]);
-      tr.mark(t, 1);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, bi[i]);
+        if (c == 0) tr.mark(t, 1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < KG / 2; ++i)
+        for (int i = 0; i < KG / 2; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
+          for (int j = 0; j < NT; ++j)
 #pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
-      if (t > 0) w.wait(fl_l + t, NS, seen_rec);
-      tr.mark(t, 2);
-      const float* src = hx_l + (size_t)t * H * BP + boff;
-#pragma unroll
-      for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, br[i]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (do_in) {
-#pragma unroll
-      for (int i = KG / 2; i < KG; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (do_rec) {
-#pragma unroll
-      for (int i = 0; i < KG; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wR[i][mt], br[i][j], acc[mt][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // ---- 4-way K-split reduction through LDS
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) part[wave][(mt * NT + j) * 4 + r][lane] = acc[mt][j][r];
-    tr.mark(t, 3);
-    __syncthreads();
-    tr.mark(t, 4);
-
-    // ---- epilogue: register r of lane (q, n) in tile (mt, j) is (unit 4*mt+q, gate r, batch NT*n+j)
-    float* const hx_out = hx_l + (size_t)(t + 1) * H * BP;
-    float o_gate[CPL][4], o_c[CPL], o_h[CPL];
-#pragma unroll
-    for (int ci = 0; ci < CPL; ++ci) {
-      if (c_p[ci] < 2 * NT) {
-        float sg[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = c_p[ci] * 4 + r;
-          sg[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]) +
-                  pin[ci][r] + c_bias[ci][r];
-        }
-        o_gate[ci][0] = sigmoidf_dev(sg[0]);
-        o_gate[ci][1] = sigmoidf_dev(sg[1]);
-        o_gate[ci][2] = sigmoidf_dev(sg[2]);
-        o_gate[ci][3] = tanhf(sg[3]);
-        o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
-        o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
-        c_state[ci] = o_c[ci];
-        xs[(c_unit[ci] - u0) * BP + c_batch[ci]] = c_valid[ci] ? o_h[ci] : 0.f;
+            for (int mt = 0; mt < 2; ++mt)
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-    }
-    __syncthreads();
-    if (threadIdx.x < 2 * BP)  // the slice's 8 rows are contiguous in the k-major exchange slot
-      xstore4(hx_out + (size_t)u0 * BP + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
-    tr.mark(t, 5);
-    signal(fl_l + (t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
-    tr.mark(t, 6);
-    // the reserve and the outputs are not read before the kernel ends: written after the signal
+      if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
+        if (t > 0) w.wait(flag(l, t, c), NS, seen_rec);
+        if (c == 0) tr.mark(t, 2);
+        const float* src = slot(l, t, c) + boff;
 #pragma unroll
-    for (int ci = 0; ci < CPL; ++ci) {
-      if (c_valid[ci]) {
-        const size_t e = ((size_t)t * B + c_batch[ci]) * H + c_unit[ci];
-        const size_t g0 = ((size_t)t * B + c_batch[ci]) * G + c_unit[ci];
-        res_h[e] = o_h[ci];
-        res_c[e] = o_c[ci];
+        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, br[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (do_in) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) res_gates[g0 + (size_t)g * H] = o_gate[ci][g];
-        if (l == a.L - 1) a.y[e] = o_h[ci];
-        if (t == T - 1) {
-          const size_t se = ((size_t)l * B + c_batch[ci]) * H + c_unit[ci];
-          if (a.hT) a.hT[se] = o_h[ci];
-          if (a.cT) a.cT[se] = o_c[ci];
+        for (int i = KG / 2; i < KG; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wW[i][mt], bi[i][j], acc[mt][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (do_rec) {
+#pragma unroll
+        for (int i = 0; i < KG; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wR[i][mt], br[i][j], acc[mt][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+
+      // ---- 4-way K-split reduction through LDS
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) part[wave][(mt * NT + j) * 4 + r][lane] = acc[mt][j][r];
+      if (c == 0) tr.mark(t, 3);
+      __syncthreads();
+      if (c == 0) tr.mark(t, 4);
+
+      // ---- epilogue: register r of lane (q, n) in tile (mt, j) is (unit 4*mt+q, gate r, batch NT*n+j)
+      float o_gate[CPL][4], o_c[CPL], o_h[CPL];
+#pragma unroll
+      for (int ci = 0; ci < CPL; ++ci) {
+        if (c_p[ci] < 2 * NT) {
+          float sg[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int row = c_p[ci] * 4 + r;
+            sg[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]) +
+                    pin[ci][r] + c_bias[ci][r];
+          }
+          o_gate[ci][0] = sigmoidf_dev(sg[0]);
+          o_gate[ci][1] = sigmoidf_dev(sg[1]);
+          o_gate[ci][2] = sigmoidf_dev(sg[2]);
+          o_gate[ci][3] = tanhf(sg[3]);
+          o_c[ci] = o_gate[ci][1] * c_state[c][ci] + o_gate[ci][0] * o_gate[ci][3];
+          o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
+          c_state[c][ci] = o_c[ci];
+          xs[(c_unit[ci] - u0) * BP + c_lb[ci]] = c_valid[c][ci] ? o_h[ci] : 0.f;
+        }
+      }
+      __syncthreads();
+      if (threadIdx.x < 2 * BP)  // the slice's 8 rows are contiguous in the k-major exchange slot
+        xstore4(slot(l, t + 1, c) + (size_t)u0 * BP + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
+      if (c == 0) tr.mark(t, 5);
+      signal(flag(l, t + 1, c), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+      if (c == 0) tr.mark(t, 6);
+      // the reserve and the outputs are not read before the kernel ends: written after the signal
+#pragma unroll
+      for (int ci = 0; ci < CPL; ++ci) {
+        if (c_valid[c][ci]) {
+          const int bb = c * BP + c_lb[ci];
+          const size_t e = ((size_t)t * B + bb) * H + c_unit[ci];
+          const size_t g0 = ((size_t)t * B + bb) * G + c_unit[ci];
+          res_h[e] = o_h[ci];
+          res_c[e] = o_c[ci];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) res_gates[g0 + (size_t)g * H] = o_gate[ci][g];
+          if (l == a.L - 1) a.y[e] = o_h[ci];
+          if (t == T - 1) {
+            const size_t se = ((size_t)l * B + bb) * H + c_unit[ci];
+            if (a.hT) a.hT[se] = o_h[ci];
+            if (a.cT) a.cT[se] = o_c[ci];
+          }
         }
       }
     }
   }
 }
 
-// h0 [L][B][H] -> exchange slot 0 of every layer, k-major [H][BP].
+// h0 [L][B][H] -> exchange slot 0 of every layer and chain, k-major [H][BP].
 __global__ void pack_state_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H,
-                                  int BP) {
+                                  int BP, int NC) {
   const long n = (long)L * B * H;
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long)gridDim.x * blockDim.x) {
     const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
-    hx[((size_t)l * (T + 1)) * H * BP + (size_t)k * BP + bb] = h0[e];
+    const int c = bb / BP, lb = bb % BP;
+    hx[(((size_t)l * (T + 1)) * NC + c) * H * BP + (size_t)k * BP + lb] = h0[e];
   }
 }
 
-
 // ------------------------------------------------------------------ backward
-// Workgroup (l, s) owns hidden units u0..u0+7 of layer l.  Per step t (descending):
-//   point-wise   dh_t = dout_t + dh_rec,  gate gradients dA_t (4 x 8 x B values), dc carry;
+// Workgroup (l, s) owns hidden units u0..u0+7 of layer l.  Per step t (descending) and batch chain:
+//   point-wise   dh_t = dout_t + dh_rec,  gate gradients dA_t (4 x 8 x BP values), dc carry;
 //                dA_t goes to the standard [T][B][4H] array (weight-gradient GEMMs) and, k-major
 //                ([4H][BP]), to the exchange buffer;
 //   GEMM         [dh_rec_{t-1} ; dx_{l,t}] (16 rows) = [R_l[:, units] | W_l[:, units]]^T * dA_t, K = 4H:
@@ -396,11 +407,11 @@ struct PersBwdArgs {
   const float* dhT;    // [L][B][H] or null
   const float* dcT;    // [L][B][H] or null
   float* dA;           // [L][T][B][4H] gate gradients (standard layout)
-  float* dAx;          // [L][T][4H][BP] exchange
+  float* dAx;          // [L][T][NC][4H][BP] exchange
   float* dxbuf;        // [L][T][B][H] gradient for the layer below (slice l written by layer l, l >= 1)
   float* dh0;          // [L][B][H] or null
   float* dc0;          // [L][B][H] or null
-  int* flags;          // [L][T+1]
+  int* flags;          // [L][T+1][NC]
   int* watchdog;
   int L, T, B, I, H;
   int spin_limit;
@@ -409,8 +420,8 @@ struct PersBwdArgs {
   int trace_block;
 };
 
-// KGB: k-groups (of 4) per wave = H/4 (wave w covers the rows of gate w).  NT: batch tiles of 16.
-template <int KGB, int NT>
+// KGB: k-groups (of 4) per wave = H/4 (wave w covers the rows of gate w).  NT, NC as in the forward kernel.
+template <int KGB, int NT, int NC>
 __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   constexpr int H = 4 * KGB, G = 4 * H, BP = 16 * NT, NS = H / 8;
   __shared__ float part[4][NT * 4][64];
@@ -440,159 +451,172 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 
   // ---- the cells this lane owns in the point-wise stage: wave j finalises batch tile j;
   //      lanes q < 2 hold dh_rec of units 4q..4q+3, lanes q >= 2 hold dx of units 4(q-2)..+3
-  const int batch = NT * n + wave;
+  const int lb = NT * n + wave;                     // chain-local batch row
   const bool fin = wave < NT;                       // this wave finalises a tile
-  const bool pw = fin && q < 2 && batch < B;        // lane runs the point-wise stage
-  const bool dxl = fin && q >= 2 && batch < B && l > 0;
   const int unit0 = u0 + 4 * (q & 1);               // first of the lane's four units
-  float dc[4], dh_rec[4];
+  bool pw[NC], dxl[NC];
+  float dc[NC][4], dh_rec[NC][4];
+  int seen_up[NC];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const size_t se = ((size_t)l * B + batch) * H + unit0 + r;
-    dc[r] = (pw && a.dcT) ? a.dcT[se] : 0.f;
-    dh_rec[r] = (pw && a.dhT) ? a.dhT[se] : 0.f;
+  for (int c = 0; c < NC; ++c) {
+    const int bb = c * BP + lb;
+    pw[c] = fin && q < 2 && bb < B;                 // lane runs the point-wise stage
+    dxl[c] = fin && q >= 2 && bb < B && l > 0;
+    seen_up[c] = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
+      dc[c][r] = (pw[c] && a.dcT) ? a.dcT[se] : 0.f;
+      dh_rec[c][r] = (pw[c] && a.dhT) ? a.dhT[se] : 0.f;
+    }
   }
 
   const float* const res_l = a.res + (size_t)l * TB * 6 * H;
   const float* const res_gates = res_l;
   const float* const res_c = res_l + TB * 4 * H;
   float* const dA_l = a.dA + (size_t)l * TB * G;
-  float* const dAx_l = a.dAx + (size_t)l * T * G * BP;
-  int* const fl_l = a.flags + (size_t)l * (T + 1);
-  int* const fl_up = (l < a.L - 1) ? a.flags + (size_t)(l + 1) * (T + 1) : nullptr;
-  const float* const dout_base = (l < a.L - 1) ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
+  const bool has_up = l < a.L - 1;
+  const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
   float* const dx_out = a.dxbuf + (size_t)l * TB * H;
   const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
+  auto slot = [&](int t, int c) { return a.dAx + (((size_t)l * T + t) * NC + c) * G * BP; };
+  auto flag = [&](int layer, int sl, int c) { return a.flags + ((size_t)layer * (T + 1) + sl) * NC + c; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
-  int seen_up = 0;
   for (int t = T - 1; t >= 0; --t) {
-    tr.mark(t, 0);
-    // ---- point-wise stage of step t
-    floatx4 gi, gf, go, gg, ct, cp, dA4[4];
-    const size_t e = ((size_t)t * B + batch) * H + unit0;
-    const size_t g0 = ((size_t)t * B + batch) * G + unit0;
-    if (pw) {
-      gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
-      gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
-      go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
-      gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
-      ct = *reinterpret_cast<const floatx4*>(res_c + e);
-      if (t > 0)
-        cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
-      else if (a.c0)
-        cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + batch) * H + unit0);
-      else
-        cp = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-    if (fl_up) w.wait(fl_up + t, NS, seen_up);  // dx of the layer above at step t is published
-    tr.mark(t, 1);
-    if (fin && q < 2 && !pw) {  // padded batch columns of the staged tile
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + batch] = 0.f;
-    }
-    if (pw) {
-      const floatx4 dout = *reinterpret_cast<const floatx4*>(dout_base + e);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float dh = dout[r] + dh_rec[r];
-        const float tc = tanhf(ct[r]);
-        const float dcv = dc[r] + dh * go[r] * (1.f - tc * tc);
-        dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
-        dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
-        dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
-        dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
-        dc[r] = dcv * gf[r];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + batch] = dA4[g][r];
+    for (int c = 0; c < NC; ++c) {
+      if (c == 0) tr.mark(t, 0);
+      const int bb = c * BP + lb;
+      // ---- point-wise stage of step t
+      floatx4 gi, gf, go, gg, ct, cp, dA4[4];
+      const size_t e = ((size_t)t * B + bb) * H + unit0;
+      const size_t g0 = ((size_t)t * B + bb) * G + unit0;
+      if (pw[c]) {
+        gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
+        gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
+        go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
+        gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
+        ct = *reinterpret_cast<const floatx4*>(res_c + e);
+        if (t > 0)
+          cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
+        else if (a.c0)
+          cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
+        else
+          cp = floatx4{0.f, 0.f, 0.f, 0.f};
       }
-    }
-    __syncthreads();
-    {  // per gate the slice's 8 rows are contiguous in the k-major exchange slot
-      float* const xo = dAx_l + (size_t)t * G * BP;
+      if (has_up) w.wait(flag(l + 1, t, c), NS, seen_up[c]);  // dx of the layer above at step t is published
+      if (c == 0) tr.mark(t, 1);
+      if (fin && q < 2 && !pw[c]) {  // padded batch columns of the staged tile
 #pragma unroll
-      for (int i = 0; i < (8 * BP + 255) / 256; ++i) {
-        const int idx = threadIdx.x + 256 * i;
-        if (idx < 8 * BP) {
-          const int g = idx / (2 * BP), rem = idx % (2 * BP);
-          xstore4(xo + (size_t)(g * H + u0) * BP + 4 * rem, *reinterpret_cast<const floatx4*>(xs + 4 * idx));
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + lb] = 0.f;
+      }
+      if (pw[c]) {
+        const floatx4 dout = *reinterpret_cast<const floatx4*>(dout_base + e);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float dh = dout[r] + dh_rec[c][r];
+          const float tc = tanhf(ct[r]);
+          const float dcv = dc[c][r] + dh * go[r] * (1.f - tc * tc);
+          dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
+          dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
+          dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
+          dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
+          dc[c][r] = dcv * gf[r];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + lb] = dA4[g][r];
         }
       }
-    }
-    tr.mark(t, 2);
-    signal(fl_l + (t + 1), a.full_fences);
-    tr.mark(t, 3);
-    if (pw) {
+      __syncthreads();
+      {  // per gate the slice's 8 rows are contiguous in the k-major exchange slot
+        float* const xo = slot(t, c);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
-    }
+        for (int i = 0; i < (8 * BP + 255) / 256; ++i) {
+          const int idx = threadIdx.x + 256 * i;
+          if (idx < 8 * BP) {
+            const int g = idx / (2 * BP), rem = idx % (2 * BP);
+            xstore4(xo + (size_t)(g * H + u0) * BP + 4 * rem, *reinterpret_cast<const floatx4*>(xs + 4 * idx));
+          }
+        }
+      }
+      if (c == 0) tr.mark(t, 2);
+      signal(flag(l, t + 1, c), a.full_fences);
+      if (c == 0) tr.mark(t, 3);
+      if (pw[c]) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
+      }
 
-    // ---- GEMM of step t: needs dA_t of every slice of this layer
-    w.wait(fl_l + (t + 1), NS);
-    tr.mark(t, 4);
-    seen_up = (fl_up && t > 0) ? Waiter::peek(fl_up + (t - 1)) : 0;  // needed by the next point-wise stage
-    floatx4 acc[NT];
+      // ---- GEMM of step t: needs dA_t of every slice of this layer
+      w.wait(flag(l, t + 1, c), NS);
+      if (c == 0) tr.mark(t, 4);
+      seen_up[c] = (has_up && t > 0) ? Waiter::peek(flag(l + 1, t - 1, c)) : 0;  // for the next point-wise stage
+      floatx4 acc[NT];
 #pragma unroll
-    for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    {
-      const float* src = dAx_l + (size_t)t * G * BP + boff;
-      // double-buffered chunks of CH k-groups: the loads of chunk c+1 are in flight under the MFMAs
-      // of chunk c (the scheduling barriers keep the compiler from re-serialising them)
-      constexpr int CH = (KGB >= 64) ? 32 : 16, NCH = KGB / CH;
-      float bv[2][CH][NT];
+      for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+      {
+        const float* src = slot(t, c) + boff;
+        // double-buffered chunks of CH k-groups: the loads of chunk i+1 are in flight under the MFMAs
+        // of chunk i (the scheduling barriers keep the compiler from re-serialising them)
+        constexpr int CH = (KGB >= 64) ? 32 : 16, NCH = KGB / CH;
+        float bv[2][CH][NT];
 #pragma unroll
-      for (int i = 0; i < CH; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KGB - 1)) * BP, bv[0][i]);
+        for (int i = 0; i < CH; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KGB - 1)) * BP, bv[0][i]);
 #pragma unroll
-      for (int c = 0; c < NCH; ++c) {
-        if (c + 1 < NCH) {
+        for (int ch = 0; ch < NCH; ++ch) {
+          if (ch + 1 < NCH) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i)
+              BVec<NT>::ld(src + (size_t)4 * (((ch + 1) * CH + i + rot) & (KGB - 1)) * BP, bv[(ch + 1) & 1][i]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int i = 0; i < CH; ++i)
-            BVec<NT>::ld(src + (size_t)4 * (((c + 1) * CH + i + rot) & (KGB - 1)) * BP, bv[(c + 1) & 1][i]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+              acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wB[ch * CH + i], bv[ch & 1][i][j], acc[j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < CH; ++i)
-#pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(wB[c * CH + i], bv[c & 1][i][j], acc[j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
       }
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][j * 4 + r][lane] = acc[j][r];
+      if (c == 0) tr.mark(t, 5);
+      __syncthreads();
+      if (c == 0) tr.mark(t, 6);
+      if (fin) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = wave * 4 + r;
+          v[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]);
+        }
+        if (q < 2) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) dh_rec[c][r] = v[r];
+        } else if (dxl[c]) {
+          xstore4(dx_out + ((size_t)t * B + bb) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
+        }
+      }
+      // `part` is next written after the barriers of the next point-wise stage
     }
+  }
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) part[wave][j * 4 + r][lane] = acc[j][r];
-    tr.mark(t, 5);
-    __syncthreads();
-    tr.mark(t, 6);
-    if (fin) {
-      float v[4];
+  for (int c = 0; c < NC; ++c) {
+    signal(flag(l, 0, c), a.full_fences);  // slot 0: dx of step 0 published
+    if (pw[c]) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int row = wave * 4 + r;
-        v[r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]);
+        const size_t se = ((size_t)l * B + c * BP + lb) * H + unit0 + r;
+        if (a.dh0) a.dh0[se] = dh_rec[c][r];
+        if (a.dc0) a.dc0[se] = dc[c][r];
       }
-      if (q < 2) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) dh_rec[r] = v[r];
-      } else if (dxl) {
-        xstore4(dx_out + ((size_t)t * B + batch) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
-      }
-    }
-    // `part` is next written after the barrier inside the next signal()
-  }
-  signal(fl_l, a.full_fences);  // slot 0: dx of step 0 published
-  if (pw) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const size_t se = ((size_t)l * B + batch) * H + unit0 + r;
-      if (a.dh0) a.dh0[se] = dh_rec[r];
-      if (a.dc0) a.dc0[se] = dc[r];
     }
   }
 }
@@ -669,21 +693,43 @@ int full_fences() {
   return (e && *e && *e != '0') ? 1 : 0;
 }
 
-inline int batch_tiles(int B) { return B <= 16 ? 1 : (B <= 32 ? 2 : 4); }
+// Batch tiles per chain and number of chains.  One chain is the default: on MI355X two chains
+// measured slower at B = 64 (the step is bound by MFMA issue forward and by L2->CU bandwidth
+// backward, and half-width 8-byte exchange loads are less efficient); LSTM_CHAINS=2 selects two.
+struct BatchPlan {
+  int NT, NC;
+};
+BatchPlan batch_plan(int B) {
+  const char* e = getenv("LSTM_CHAINS");
+  const bool two = e && *e == '2';
+  if (B <= 16) return {1, 1};
+  if (B <= 32) return two ? BatchPlan{1, 2} : BatchPlan{2, 1};
+  return two ? BatchPlan{2, 2} : BatchPlan{4, 1};
+}
 
 template <int KG>
-hipError_t launch_fwd(int NT, int grid, const PersFwdArgs& a, hipStream_t s) {
+hipError_t launch_fwd(BatchPlan bp, int grid, const PersFwdArgs& a, hipStream_t s) {
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
-  const void* fn = NT == 1 ? (const void*)pers_fwd_kernel<KG, 1>
-                           : (NT == 2 ? (const void*)pers_fwd_kernel<KG, 2> : (const void*)pers_fwd_kernel<KG, 4>);
+  const void* fn = nullptr;
+  if (bp.NT == 1 && bp.NC == 1) fn = (const void*)pers_fwd_kernel<KG, 1, 1>;
+  if (bp.NT == 1 && bp.NC == 2) fn = (const void*)pers_fwd_kernel<KG, 1, 2>;
+  if (bp.NT == 2 && bp.NC == 2) fn = (const void*)pers_fwd_kernel<KG, 2, 2>;
+  if (bp.NT == 2 && bp.NC == 1) fn = (const void*)pers_fwd_kernel<KG, 2, 1>;
+  if (bp.NT == 4 && bp.NC == 1) fn = (const void*)pers_fwd_kernel<KG, 4, 1>;
+  if (!fn) return hipErrorInvalidValue;
   return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
 }
 
 template <int KGB>
-hipError_t launch_bwd(int NT, int grid, const PersBwdArgs& a, hipStream_t s) {
+hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t s) {
   void* params[] = {const_cast<PersBwdArgs*>(&a)};
-  const void* fn = NT == 1 ? (const void*)pers_bwd_kernel<KGB, 1>
-                           : (NT == 2 ? (const void*)pers_bwd_kernel<KGB, 2> : (const void*)pers_bwd_kernel<KGB, 4>);
+  const void* fn = nullptr;
+  if (bp.NT == 1 && bp.NC == 1) fn = (const void*)pers_bwd_kernel<KGB, 1, 1>;
+  if (bp.NT == 1 && bp.NC == 2) fn = (const void*)pers_bwd_kernel<KGB, 1, 2>;
+  if (bp.NT == 2 && bp.NC == 2) fn = (const void*)pers_bwd_kernel<KGB, 2, 2>;
+  if (bp.NT == 2 && bp.NC == 1) fn = (const void*)pers_bwd_kernel<KGB, 2, 1>;
+  if (bp.NT == 4 && bp.NC == 1) fn = (const void*)pers_bwd_kernel<KGB, 4, 1>;
+  if (!fn) return hipErrorInvalidValue;
   return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
 }
 
@@ -724,17 +770,18 @@ int run_forward_persistent(const FwdArgs& a) {
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
-  const int NT = batch_tiles(d.B), BP = 16 * NT;
+  const BatchPlan bp = batch_plan(d.B);
+  const int BP = 16 * bp.NT;
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 4, s), "zero step counters");
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
     if (a.h0) {
       const long n = (long)d.L * d.B * d.H;
       hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
-                         d.H, BP);
+                         d.H, BP, bp.NC);
       CK(hipGetLastError(), "pack h0");
     }
   }
@@ -753,9 +800,9 @@ int run_forward_persistent(const FwdArgs& a) {
   const int grid = d.L * (d.H / 8);
   ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
   hipError_t e = hipErrorInvalidValue;
-  if (d.H == 512) e = launch_fwd<32>(NT, grid, k, s);
-  else if (d.H == 256) e = launch_fwd<16>(NT, grid, k, s);
-  else if (d.H == 128) e = launch_fwd<8>(NT, grid, k, s);
+  if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
+  else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
+  else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
   CK(e, "persistent forward launch");
   return LSTM_OK;
 }
@@ -768,12 +815,12 @@ int run_backward_persistent(const BwdArgs& a) {
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
-  const int NT = batch_tiles(d.B);
+  const BatchPlan bp = batch_plan(d.B);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 4, s), "zero step counters");
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
   }
   PersBwdArgs k;
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
@@ -786,9 +833,9 @@ int run_backward_persistent(const BwdArgs& a) {
   {
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (d.H == 512) e = launch_bwd<128>(NT, grid, k, s);
-    else if (d.H == 256) e = launch_bwd<64>(NT, grid, k, s);
-    else if (d.H == 128) e = launch_bwd<32>(NT, grid, k, s);
+    if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
+    else if (d.H == 256) e = launch_bwd<64>(bp, grid, k, s);
+    else if (d.H == 128) e = launch_bwd<32>(bp, grid, k, s);
     CK(e, "persistent backward launch");
   }
   if (a.dx) {  // layer 0's input gradient: all T steps in one product
