@@ -97,7 +97,8 @@ struct TileIO {
   }
 };
 
-template <int WM, int WN>
+// MA / MB: load mode of the A / B operand, fixed at compile time (LM_SCALAR handles anything).
+template <int WM, int WN, int MA, int MB>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
   constexpr int MT = 64 * WM, NT = 64 * WN;
   using IOA = TileIO<MT>;
@@ -116,8 +117,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int modeA = pick_mode(P.A, P.sAm, P.sAk, P.M, P.K);
-  const int modeB = pick_mode(P.B, P.sBn, P.sBk, P.N, P.K);
 
   floatx16 acc[WM][WN];
 #pragma unroll
@@ -129,35 +128,42 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
 
   float ra[IOA::PER_THREAD], rb[IOB::PER_THREAD];
   const int nk = (P.K + KT - 1) / KT;
-  IOA::load(ra, P.A, P.sAm, P.sAk, m0, 0, P.M, P.K, modeA, tid);
-  IOB::load(rb, P.B, P.sBn, P.sBk, n0, 0, P.N, P.K, modeB, tid);
-  IOA::store(ra, As[0], modeA, tid);
-  IOB::store(rb, Bs[0], modeB, tid);
+  IOA::load(ra, P.A, P.sAm, P.sAk, m0, 0, P.M, P.K, MA, tid);
+  IOB::load(rb, P.B, P.sBn, P.sBk, n0, 0, P.N, P.K, MB, tid);
+  IOA::store(ra, As[0], MA, tid);
+  IOB::store(rb, Bs[0], MB, tid);
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
-      IOA::load(ra, P.A, P.sAm, P.sAk, m0, (kt + 1) * KT, P.M, P.K, modeA, tid);
-      IOB::load(rb, P.B, P.sBn, P.sBk, n0, (kt + 1) * KT, P.N, P.K, modeB, tid);
+      IOA::load(ra, P.A, P.sAm, P.sAk, m0, (kt + 1) * KT, P.M, P.K, MA, tid);
+      IOB::load(rb, P.B, P.sBn, P.sBk, n0, (kt + 1) * KT, P.N, P.K, MB, tid);
     }
     const float* as = As[cur] + (lane >> 5) * IOA::LDS_STRIDE + wm * 32 * WM + (lane & 31);
     const float* bs = Bs[cur] + (lane >> 5) * IOB::LDS_STRIDE + wn * 32 * WN + (lane & 31);
+    // all operand fragments of the k-tile are fetched from LDS first; the MFMAs then start as soon as
+    // the first fragments arrive and the remaining LDS latency hides under them
+    float a[KT / 2][WM], b[KT / 2][WN];
 #pragma unroll
-    for (int kk = 0; kk < KT; kk += 2) {
-      float a[WM], b[WN];
+    for (int kk = 0; kk < KT / 2; ++kk) {
 #pragma unroll
-      for (int i = 0; i < WM; ++i) a[i] = as[kk * IOA::LDS_STRIDE + 32 * i];
+      for (int i = 0; i < WM; ++i) a[kk][i] = as[2 * kk * IOA::LDS_STRIDE + 32 * i];
 #pragma unroll
-      for (int j = 0; j < WN; ++j) b[j] = bs[kk * IOB::LDS_STRIDE + 32 * j];
+      for (int j = 0; j < WN; ++j) b[kk][j] = bs[2 * kk * IOB::LDS_STRIDE + 32 * j];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KT / 2; ++kk)
 #pragma unroll
       for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk][i], b[kk][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     if (kt + 1 < nk) {
-      IOA::store(ra, As[cur ^ 1], modeA, tid);
-      IOB::store(rb, Bs[cur ^ 1], modeB, tid);
+      IOA::store(ra, As[cur ^ 1], MA, tid);
+      IOB::store(rb, Bs[cur ^ 1], MB, tid);
     }
     __syncthreads();
   }
@@ -179,6 +185,21 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
     }
 }
 
+template <int WM, int WN>
+void launch_tile(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s) {
+#define LSTM_GEMM_CASE(A_, B_)                                                                        \
+  if (ma == A_ && mb == B_) {                                                                         \
+    hipLaunchKernelGGL((gemm_f32_kernel<WM, WN, A_, B_>), dim3(grid), dim3(256), 0, s, g);            \
+    return;                                                                                           \
+  }
+  LSTM_GEMM_CASE(LM_KCONTIG, LM_KCONTIG)
+  LSTM_GEMM_CASE(LM_KCONTIG, LM_RCONTIG)
+  LSTM_GEMM_CASE(LM_RCONTIG, LM_RCONTIG)
+  LSTM_GEMM_CASE(LM_RCONTIG, LM_KCONTIG)
+#undef LSTM_GEMM_CASE
+  hipLaunchKernelGGL((gemm_f32_kernel<WM, WN, LM_SCALAR, LM_SCALAR>), dim3(grid), dim3(256), 0, s, g);
+}
+
 }  // namespace
 
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream) {
@@ -187,11 +208,19 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   GemmGroupArgs g;
   bool big = true;
   long total_big = 0;
+  // one kernel instance serves the whole group: operands that cannot all take the same vector
+  // loader fall back to the scalar one
+  int ma = -1, mb = -1;
   for (int i = 0; i < nprob; ++i) {
     g.p[i] = probs[i];
     if (probs[i].M < 96 || probs[i].N < 96) big = false;
     total_big += (long)((probs[i].M + 127) / 128) * ((probs[i].N + 127) / 128);
+    const int a = pick_mode(probs[i].A, probs[i].sAm, probs[i].sAk, probs[i].M, probs[i].K);
+    const int b = pick_mode(probs[i].B, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);
+    ma = (i == 0 || ma == a) ? a : LM_SCALAR;
+    mb = (i == 0 || mb == b) ? b : LM_SCALAR;
   }
+  if (ma == LM_SCALAR || mb == LM_SCALAR) ma = mb = LM_SCALAR;
   // Few large tiles leave most of the 256 CUs idle; fall back to 64x64 tiles then.
   if (total_big < 128) big = false;
   const int mt = big ? 128 : 64;
@@ -204,9 +233,9 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   g.nprob = nprob;
   if (start == 0) return hipSuccess;
   if (big)
-    hipLaunchKernelGGL((gemm_f32_kernel<2, 2>), dim3(start), dim3(256), 0, stream, g);
+    launch_tile<2, 2>(ma, mb, start, g, stream);
   else
-    hipLaunchKernelGGL((gemm_f32_kernel<1, 1>), dim3(start), dim3(256), 0, stream, g);
+    launch_tile<1, 1>(ma, mb, start, g, stream);
   return hipGetLastError();
 }
 
