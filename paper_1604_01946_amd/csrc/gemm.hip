@@ -46,7 +46,7 @@ struct TileIO {
 #pragma unroll
       for (int v = 0; v < NVEC; ++v) {
         const int idx = tid + 256 * v;
-        const int row = r0 + idx / 4, k = k0 + 4 * (idx % 4);
+        const int row = r0 + idx / (KT / 4), k = k0 + 4 * (idx % (KT / 4));
         float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row < R && k < K) val = *reinterpret_cast<const float4*>(base + (long)row * s_r + k);
         reg[4 * v + 0] = val.x; reg[4 * v + 1] = val.y; reg[4 * v + 2] = val.z; reg[4 * v + 3] = val.w;
@@ -75,7 +75,7 @@ struct TileIO {
 #pragma unroll
       for (int v = 0; v < NVEC; ++v) {
         const int idx = tid + 256 * v;
-        const int row = idx / 4, k = 4 * (idx % 4);
+        const int row = idx / (KT / 4), k = 4 * (idx % (KT / 4));
 #pragma unroll
         for (int j = 0; j < 4; ++j) S[(k + j) * LDS_STRIDE + row] = reg[4 * v + j];
       }
@@ -107,8 +107,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
   __shared__ __attribute__((aligned(16))) float Bs[2][KT * IOB::LDS_STRIDE];
 
   // which problem, which tile
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): remap so that one XCD
+  // works on a contiguous run of tiles, which share operand panels.
   int pi = 0;
-  const int bid = blockIdx.x;
+  int bid = blockIdx.x;
+  if ((gridDim.x & 7) == 0) bid = (bid & 7) * (gridDim.x >> 3) + (bid >> 3);
   while (pi + 1 < g.nprob && bid >= g.tile_start[pi + 1]) ++pi;
   const GemmProblem& P = g.p[pi];
   const int local = bid - g.tile_start[pi];
