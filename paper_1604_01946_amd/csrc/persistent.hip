@@ -621,6 +621,232 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ backward, wide-batch variant
+// For 32 < B <= 64 the kernel above is bound by L2->CU bandwidth: every workgroup reads the whole
+// dA_t (4H x 64 values per step).  This variant halves that traffic by giving a workgroup 16 hidden
+// units of ONE half of the batch: M = 32 rows (16 dh_rec + 16 dx), N = 32 batch rows, which is one
+// v_mfma_f32_32x32x2_f32 tile (the fp32 MFMA shape that issues at full rate with one wave per
+// SIMD).  Its weight slice is [32 x 4H] = 256 KB at H = 512: the first 128 k-pairs of every wave
+// stay in VGPRs, the rest sit in LDS (152 KB of the CU's 160 KB are used).  The two batch halves
+// never exchange data, so they are placed on different XCDs.
+// Exchange layout of one (layer, step, half) slot: for k = 8*k8 + 2*m + kk and batch row n,
+// element ((k8*2 + kk)*32 + n)*4 + m -- lane (kk, n) of a wave fetches the four k-pairs of an
+// 8-k group with one 16-byte load, 1 KB per wave and instruction.
+template <int HH>
+__global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, const int NBH) {
+  constexpr int H = HH, G = 4 * H, NS2 = H / 16;
+  constexpr int NB8 = H / 8;                 // 8-k groups per wave (wave w covers the rows of gate w)
+  constexpr int KPW = H / 2;                 // k-pairs per wave
+  constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
+  constexpr int LP = KPW - RP;               // k-pairs whose weights live in LDS
+  constexpr int CH8 = 16;                    // 8-k groups per chunk of the load pipeline
+  constexpr int NCH = NB8 / CH8;
+  static_assert(NB8 % CH8 == 0 && (RP / 4) % CH8 == 0, "chunks must not straddle the register/LDS split");
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* const part = smem;         // [4 waves][16 regs][64 lanes]
+  float* const xs = smem + 4096;    // [8 blocks of 8 k][256]: this step's dA slice in exchange order
+  float* const wl = smem + 6144;    // [4 waves][LP][64 lanes]
+
+  // blockIdx -> (layer, batch half, slice): one (layer, half) group per 8/(L*NBH) XCDs when that divides
+  int l, bh, s2;
+  {
+    const int bid = blockIdx.x, groups = a.L * NBH;
+    if (groups <= 8 && 8 % groups == 0 && NS2 % (8 / groups) == 0 && (gridDim.x % 8) == 0) {
+      const int per = 8 / groups, xcd = bid & 7, grp = xcd / per;
+      l = grp / NBH;
+      bh = grp % NBH;
+      s2 = (bid >> 3) * per + (xcd % per);
+    } else {
+      l = bid / (NS2 * NBH);
+      bh = (bid / NS2) % NBH;
+      s2 = bid % NS2;
+    }
+  }
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kk = lane >> 5, n = lane & 31;
+  const int u0 = 16 * s2;
+  const size_t TB = (size_t)T * B;
+  const int rot = ((int)(blockIdx.x >> 3) * (NB8 / 32 > 0 ? NB8 / 32 : 1) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (NB8 - 1);
+
+  // ---- weights: A operand row rho = lane%32 (< 16: column u0+rho of R_l, >= 16: column u0+rho-16 of W_l)
+  float wreg[RP];
+  {
+    const float* Rl = a.R + (size_t)l * G * H;
+    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
+    const float* src = (n < 16) ? Rl + u0 + n : Wl + u0 + (n - 16);
+    const bool live = (n < 16) || (l > 0);
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) {
+      const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
+      const float v = live ? src[(size_t)(wave * H + 8 * k8 + 2 * m + kk) * H] : 0.f;
+      if (i < RP)
+        wreg[i < RP ? i : 0] = v;
+      else
+        wl[((size_t)wave * LP + (i - RP)) * 64 + lane] = v;
+    }
+  }
+
+  // ---- roles: waves 0,1 run the point-wise stage on units u0 + 8*wave + 4*kk + {0..3};
+  //      waves 2,3 publish dx of units u0 + 8*(wave-2) + 4*kk + {0..3}; batch row bh*32 + n
+  const int bb = bh * 32 + n;
+  const bool pwv = wave < 2 && bb < B;
+  const bool dxl = wave >= 2 && bb < B && l > 0;
+  const int unit0 = u0 + 8 * (wave & 1) + 4 * kk;
+  float dc[4], dh_rec[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
+    dc[r] = (pwv && a.dcT) ? a.dcT[se] : 0.f;
+    dh_rec[r] = (pwv && a.dhT) ? a.dhT[se] : 0.f;
+  }
+
+  const float* const res_l = a.res + (size_t)l * TB * 6 * H;
+  const float* const res_gates = res_l;
+  const float* const res_c = res_l + TB * 4 * H;
+  float* const dA_l = a.dA + (size_t)l * TB * G;
+  const bool has_up = l < a.L - 1;
+  const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
+  float* const dx_out = a.dxbuf + (size_t)l * TB * H;
+  auto slot = [&](int t) { return a.dAx + (((size_t)l * T + t) * NBH + bh) * G * 32; };
+  auto flag = [&](int layer, int sl) { return a.flags + ((size_t)layer * (T + 1) + sl) * NBH + bh; };
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+  __syncthreads();                                    // LDS weights are in place
+
+  int seen_up = 0;
+  for (int t = T - 1; t >= 0; --t) {
+    tr.mark(t, 0);
+    // ---- point-wise stage of step t
+    floatx4 gi, gf, go, gg, ct, cp, dA4[4];
+    const size_t e = ((size_t)t * B + bb) * H + unit0;
+    const size_t g0 = ((size_t)t * B + bb) * G + unit0;
+    if (pwv) {
+      gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
+      gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
+      go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
+      gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
+      ct = *reinterpret_cast<const floatx4*>(res_c + e);
+      if (t > 0)
+        cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
+      else if (a.c0)
+        cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
+      else
+        cp = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (has_up) w.wait(flag(l + 1, t), NS2, seen_up);  // dx of the layer above at step t is published
+    tr.mark(t, 1);
+    if (wave < 2) {
+      floatx4 dout = {0.f, 0.f, 0.f, 0.f};
+      if (pwv) dout = *reinterpret_cast<const floatx4*>(dout_base + e);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (pwv) {
+          const float dh = dout[r] + dh_rec[r];
+          const float tc = tanhf(ct[r]);
+          const float dcv = dc[r] + dh * go[r] * (1.f - tc * tc);
+          dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
+          dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
+          dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
+          dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
+          dc[r] = dcv * gf[r];
+        }
+        // unit u0 + 8*wave + 4*kk + r sits at k%8 = 4*kk + r of block (gate, wave): m = 2*kk + r/2, parity r%2
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          xs[(g * 2 + wave) * 256 + ((r & 1) * 32 + n) * 4 + 2 * kk + (r >> 1)] = pwv ? dA4[g][r] : 0.f;
+      }
+    }
+    __syncthreads();
+    {  // eight 1 KB blocks (gate x unit-octet), each contiguous in the exchange slot
+      float* const xo = slot(t);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int idx = threadIdx.x + 256 * i, blk = idx >> 6, off = idx & 63;
+        const int g = blk >> 1, o8 = blk & 1;
+        xstore4(xo + ((size_t)(g * H + u0) / 8 + o8) * 256 + off * 4, *reinterpret_cast<const floatx4*>(xs + blk * 256 + off * 4));
+      }
+    }
+    tr.mark(t, 2);
+    signal(flag(l, t + 1), a.full_fences);
+    tr.mark(t, 3);
+    if (pwv) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
+    }
+
+    // ---- GEMM of step t: needs dA_t of every slice of this layer and batch half
+    w.wait(flag(l, t + 1), NS2);
+    tr.mark(t, 4);
+    seen_up = (has_up && t > 0) ? Waiter::peek(flag(l + 1, t - 1)) : 0;  // for the next point-wise stage
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    {
+      const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
+      floatx4 bv[2][CH8];
+#pragma unroll
+      for (int i = 0; i < CH8; ++i) bv[0][i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NB8 - 1)) * 256);
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        if (ch + 1 < NCH) {
+#pragma unroll
+          for (int i = 0; i < CH8; ++i)
+            bv[(ch + 1) & 1][i] = *reinterpret_cast<const floatx4*>(src + (size_t)(((ch + 1) * CH8 + i + rot) & (NB8 - 1)) * 256);
+        }
+        float al[CH8 * 4];
+        if (ch * CH8 * 4 >= RP) {  // this chunk's weights come from LDS
+#pragma unroll
+          for (int p = 0; p < CH8 * 4; ++p) al[p] = wl[((size_t)wave * LP + (ch * CH8 * 4 + p - RP)) * 64 + lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < CH8; ++i)
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            const int pr = (ch * CH8 + i) * 4 + m;
+            const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[i * 4 + m];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[ch & 1][i][m], acc, 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = acc[r];
+    tr.mark(t, 5);
+    __syncthreads();
+    tr.mark(t, 6);
+    {
+      // register r of a lane is row 8*(r/4) + 4*kk + r%4: wave w sums registers 4w..4w+3 = rows 8w+4kk+{0..3}
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = 4 * wave + r;
+        v[r] = (part[(0 * 16 + row) * 64 + lane] + part[(1 * 16 + row) * 64 + lane]) +
+               (part[(2 * 16 + row) * 64 + lane] + part[(3 * 16 + row) * 64 + lane]);
+      }
+      if (wave < 2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dh_rec[r] = v[r];
+      } else if (dxl) {
+        xstore4(dx_out + ((size_t)t * B + bb) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
+      }
+    }
+    // `part` and `xs` are next written after the barriers of the next point-wise stage
+  }
+  signal(flag(l, 0), a.full_fences);  // slot 0: dx of step 0 published
+  if (pwv) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
+      if (a.dh0) a.dh0[se] = dh_rec[r];
+      if (a.dc0) a.dc0[se] = dc[r];
+    }
+  }
+}
+
 // ------------------------------------------------------------------ host state
 struct DeviceInfo {
   bool ok = false;
@@ -733,6 +959,30 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
   return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
 }
 
+// The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
+bool bwd_wide(const Dims& d) {
+  const char* e = getenv("LSTM_BWD_NARROW");
+  if (e && *e == '1') return false;
+  return d.B > 32 && d.B <= 64;
+}
+
+template <int HH>
+hipError_t launch_bwd32(const PersBwdArgs& a, hipStream_t s) {
+  constexpr int KPW = HH / 2, LP = KPW > 128 ? KPW - 128 : 0;
+  const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
+  const void* fn = (const void*)pers_bwd32_kernel<HH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  int nbh = 2;
+  void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
+  const int grid = a.L * (HH / 16) * nbh;
+  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, (unsigned)smem, s);
+}
+
 }  // namespace
 
 int device_cu_count() {
@@ -816,11 +1066,12 @@ int run_backward_persistent(const BwdArgs& a) {
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
+  const bool wide = bwd_wide(d);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 2 * 4, s), "zero step counters");
   }
   PersBwdArgs k;
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
@@ -833,7 +1084,10 @@ int run_backward_persistent(const BwdArgs& a) {
   {
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
+    if (wide && d.H == 512) e = launch_bwd32<512>(k, s);
+    else if (wide && d.H == 256) e = launch_bwd32<256>(k, s);
+    else if (wide && d.H == 128) e = launch_bwd32<128>(k, s);
+    else if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
     else if (d.H == 256) e = launch_bwd<64>(bp, grid, k, s);
     else if (d.H == 128) e = launch_bwd<32>(bp, grid, k, s);
     CK(e, "persistent backward launch");
