@@ -178,6 +178,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   constexpr int CPL = (2 * NT + 3) / 4;  // cells finalised per lane and chain
   __shared__ float part[4][2 * NT * 4][64];
   __shared__ __attribute__((aligned(16))) float xs[8 * BP];  // this step's h slice, [unit][batch]
+  __shared__ __attribute__((aligned(16))) float ro[6 * BP * 8];  // gates, c, h of the slice: [array][batch][unit]
 
   int l, s;
   map_block(a.L, NS, l, s);
@@ -352,22 +353,37 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       if (c == 0) tr.mark(t, 5);
       signal(flag(l, t + 1, c), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
       if (c == 0) tr.mark(t, 6);
-      // the reserve and the outputs are not read before the kernel ends: written after the signal
+      // The reserve and the outputs are not read before the kernel ends, so they are written after
+      // the signal -- staged through LDS so that each store instruction writes 16-byte runs
+      // (scattered 4-byte stores keep the address unit busy for longer than the whole epilogue).
 #pragma unroll
       for (int ci = 0; ci < CPL; ++ci) {
-        if (c_valid[c][ci]) {
-          const int bb = c * BP + c_lb[ci];
-          const size_t e = ((size_t)t * B + bb) * H + c_unit[ci];
-          const size_t g0 = ((size_t)t * B + bb) * G + c_unit[ci];
-          res_h[e] = o_h[ci];
-          res_c[e] = o_c[ci];
+        if (c_p[ci] < 2 * NT) {
+          const int ul = c_unit[ci] - u0;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) res_gates[g0 + (size_t)g * H] = o_gate[ci][g];
-          if (l == a.L - 1) a.y[e] = o_h[ci];
-          if (t == T - 1) {
-            const size_t se = ((size_t)l * B + bb) * H + c_unit[ci];
-            if (a.hT) a.hT[se] = o_h[ci];
-            if (a.cT) a.cT[se] = o_c[ci];
+          for (int g = 0; g < 4; ++g) ro[(g * BP + c_lb[ci]) * 8 + ul] = o_gate[ci][g];
+          ro[(4 * BP + c_lb[ci]) * 8 + ul] = o_c[ci];
+          ro[(5 * BP + c_lb[ci]) * 8 + ul] = o_h[ci];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < (12 * BP + 255) / 256; ++i) {
+        const int idx = threadIdx.x + 256 * i;  // (array 0..5, chain-local batch row, half of the 8 units)
+        const int arr = idx / (2 * BP), lb = (idx >> 1) % BP, hf = idx & 1;
+        const int b2 = c * BP + lb;
+        if (idx < 12 * BP && b2 < B) {
+          const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * BP + lb) * 8 + 4 * hf);
+          const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
+          if (arr < 4) {
+            *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
+          } else if (arr == 4) {
+            *reinterpret_cast<floatx4*>(res_c + e) = v;
+            if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
+          } else {
+            *reinterpret_cast<floatx4*>(res_h + e) = v;
+            if (l == a.L - 1) *reinterpret_cast<floatx4*>(a.y + e) = v;
+            if (t == T - 1 && a.hT) *reinterpret_cast<floatx4*>(a.hT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
           }
         }
       }
@@ -383,6 +399,225 @@ __global__ void pack_state_kernel(const float* __restrict__ h0, float* __restric
     const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
     const int c = bb / BP, lb = bb % BP;
     hx[(((size_t)l * (T + 1)) * NC + c) * H * BP + (size_t)k * BP + lb] = h0[e];
+  }
+}
+
+// ------------------------------------------------------------------ forward, wide-batch variant
+// Same decomposition as pers_fwd_kernel (8 hidden units x all batch rows per workgroup) for
+// 32 < B <= 64, on v_mfma_f32_32x32x2_f32: with one wave per SIMD the 16x16x4 shape issues at about
+// three quarters of the fp32 matrix rate, the 32x32 shape at nearly all of it.  M = 32 weight rows
+// ordered gate-major (row = 8*gate + unit) so that, in the D layout, a lane holds all four gates of
+// four units; N = two tiles of 32 batch rows (tile j, column n = batch 2n + j).
+// Exchange layout of one (layer, step) slot: for k = 4*k4 + 2*m + kk and batch b = 2n + j, element
+// ((k4*2 + kk)*32 + n)*4 + 2*m + j -- lane (kk, n) fetches two k-pairs of both tiles with one
+// 16-byte load, 1 KB per wave and instruction.
+template <int HH>
+__global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
+  constexpr int H = HH, G = 4 * H, NS = H / 8;
+  constexpr int NK4 = H / 16;  // 4-k groups per wave and operand half
+  __shared__ float part[4][32][64];
+  __shared__ __attribute__((aligned(16))) float xs[512];  // this step's h slice in exchange order
+  __shared__ __attribute__((aligned(16))) float ro[6 * 64 * 8];  // gates, c, h of the slice: [array][batch][unit]
+
+  int l, s;
+  map_block(a.L, NS, l, s);
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kk = lane >> 5, n = lane & 31;
+  const int u0 = 8 * s;
+  const size_t TB = (size_t)T * B;
+  const int rot = ((int)(blockIdx.x >> 3) + __builtin_amdgcn_readfirstlane(wave)) & (NK4 - 1);
+
+  // ---- weights -> registers: A operand row rho = lane%32 = (gate rho/8, unit rho%8), k = wave*H/4 + 4*k4 + 2*m + kk
+  float wR[NK4][2], wW[NK4][2];
+  {
+    const float* Rl = a.R + (size_t)l * G * H;
+    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
+    const size_t row = ((size_t)(n >> 3) * H + u0 + (n & 7)) * H;
+#pragma unroll
+    for (int i = 0; i < NK4; ++i) {
+      const int k4 = (i + rot) & (NK4 - 1);
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        const int k = wave * (H / 4) + 4 * k4 + 2 * m + kk;
+        wR[i][m] = Rl[row + k];
+        wW[i][m] = (l > 0) ? Wl[row + k] : 0.f;
+      }
+    }
+  }
+
+  // ---- the two cells this lane finalises: wave w takes batch tile j = w%2 and unit pair up = w/2;
+  //      D register r of a lane is row 8*(r/4) + 4*kk + r%4 = (gate r/4, unit 4*kk + r%4)
+  const int tj = wave & 1, up = wave >> 1;
+  const int bb = 2 * n + tj;
+  const bool valid = bb < B;
+  int c_unit[2];
+  float c_state[2], c_bias[2][4];
+#pragma unroll
+  for (int ci = 0; ci < 2; ++ci) {
+    c_unit[ci] = u0 + 4 * kk + 2 * up + ci;
+    c_state[ci] = (valid && a.c0) ? a.c0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) c_bias[ci][g] = a.bias[(size_t)l * G + g * H + c_unit[ci]];
+  }
+
+  float* const res_l = a.res + (size_t)l * TB * 6 * H;
+  float* const res_gates = res_l;
+  float* const res_c = res_l + TB * 4 * H;
+  float* const res_h = res_l + TB * 5 * H;
+  auto slot = [&](int layer, int sl) { return a.hx + ((size_t)layer * (T + 1) + sl) * H * 64; };
+  auto flag = [&](int layer, int sl) { return a.flags + (size_t)layer * (T + 1) + sl; };
+  const size_t boff = (size_t)wave * NK4 * 256 + lane * 4;  // this lane's offset inside a slot
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+
+  const bool do_in = l > 0;
+  int seen_in = do_in ? Waiter::peek(flag(l - 1, 1)) : 0;
+  for (int t = 0; t < T; ++t) {
+    tr.mark(t, 0);
+    floatx16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+    // layer 0: fetch the batched input projection early, it is consumed in the epilogue
+    float pin[2][4];
+#pragma unroll
+    for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        pin[ci][g] = (l == 0 && valid) ? a.P0[((size_t)t * B + bb) * G + g * H + c_unit[ci]] : 0.f;
+
+    const bool do_rec = (t > 0 || a.has_h0);
+    const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t)) : 0;
+    floatx4 bi[NK4], br[NK4];
+    if (do_in) {  // input half: h of the layer below at this step
+      w.wait(flag(l - 1, t + 1), NS, seen_in);
+      const float* src = slot(l - 1, t + 1) + boff;
+#pragma unroll
+      for (int i = 0; i < NK4; ++i) bi[i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
+      tr.mark(t, 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NK4 / 2; ++i)
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wW[i][m], bi[i][2 * m + j], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
+      if (t > 0) w.wait(flag(l, t), NS, seen_rec);
+      tr.mark(t, 2);
+      const float* src = slot(l, t) + boff;
+#pragma unroll
+      for (int i = 0; i < NK4; ++i) br[i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the next step's input flag: the answer arrives under the MFMAs below
+    seen_in = (do_in && t + 1 < T) ? Waiter::peek(flag(l - 1, t + 2)) : 0;
+    if (do_in) {
+#pragma unroll
+      for (int i = NK4 / 2; i < NK4; ++i)
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wW[i][m], bi[i][2 * m + j], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (do_rec) {
+#pragma unroll
+      for (int i = 0; i < NK4; ++i)
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wR[i][m], br[i][2 * m + j], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- 4-way K-split reduction through LDS
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) part[wave][j * 16 + r][lane] = acc[j][r];
+    tr.mark(t, 3);
+    __syncthreads();
+    tr.mark(t, 4);
+
+    // ---- epilogue
+    float o_gate[2][4], o_c[2], o_h[2];
+#pragma unroll
+    for (int ci = 0; ci < 2; ++ci) {
+      float sg[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int row = tj * 16 + 4 * g + 2 * up + ci;
+        sg[g] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]) +
+                pin[ci][g] + c_bias[ci][g];
+      }
+      o_gate[ci][0] = sigmoidf_dev(sg[0]);
+      o_gate[ci][1] = sigmoidf_dev(sg[1]);
+      o_gate[ci][2] = sigmoidf_dev(sg[2]);
+      o_gate[ci][3] = tanhf(sg[3]);
+      o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
+      o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
+      c_state[ci] = o_c[ci];
+      // unit offset ul = 4*kk + 2*up + ci: k4 block ul/4 = kk, m = up, parity ci; batch (n, tj)
+      xs[kk * 256 + (ci * 32 + n) * 4 + 2 * up + tj] = valid ? o_h[ci] : 0.f;
+    }
+    __syncthreads();
+    if (threadIdx.x < 128)  // the slice's 8 units are two contiguous 1 KB blocks of the exchange slot
+      xstore4(slot(l, t + 1) + (size_t)(u0 / 4) * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
+    tr.mark(t, 5);
+    signal(flag(l, t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+    tr.mark(t, 6);
+    // The reserve and the outputs are not read before the kernel ends, so they are written after the
+    // signal -- staged through LDS so that each store instruction writes 16-byte runs (scattered
+    // 4-byte stores keep the address unit busy for longer than the whole epilogue).
+#pragma unroll
+    for (int ci = 0; ci < 2; ++ci) {
+      const int ul = 4 * kk + 2 * up + ci;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) ro[(g * 64 + bb) * 8 + ul] = o_gate[ci][g];
+      ro[(4 * 64 + bb) * 8 + ul] = o_c[ci];
+      ro[(5 * 64 + bb) * 8 + ul] = o_h[ci];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      const int idx = threadIdx.x + 256 * i;  // (array 0..5, batch row, half of the 8 units)
+      const int arr = idx >> 7, b2 = (idx >> 1) & 63, hf = idx & 1;
+      if (b2 < B) {
+        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + b2) * 8 + 4 * hf);
+        const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
+        if (arr < 4) {
+          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
+        } else if (arr == 4) {
+          *reinterpret_cast<floatx4*>(res_c + e) = v;
+          if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
+        } else {
+          *reinterpret_cast<floatx4*>(res_h + e) = v;
+          if (l == a.L - 1) *reinterpret_cast<floatx4*>(a.y + e) = v;
+          if (t == T - 1 && a.hT) *reinterpret_cast<floatx4*>(a.hT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
+        }
+      }
+    }
+  }
+}
+
+// h0 [L][B][H] -> exchange slot 0 of every layer in the layout of pers_fwd32_kernel.
+__global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H) {
+  const long cnt = (long)L * B * H;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
+    const int k4 = k >> 2, m = (k >> 1) & 1, kk = k & 1, n = bb >> 1, j = bb & 1;
+    hx[((size_t)l * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] = h0[e];
   }
 }
 
@@ -959,6 +1194,20 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
   return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
 }
 
+// The wide-batch forward kernel (32x32x2 MFMA, two batch tiles of 32).
+bool fwd_wide(const Dims& d) {
+  const char* e = getenv("LSTM_FWD_NARROW");
+  if (e && *e == '1') return false;
+  return d.B > 32 && d.B <= 64;
+}
+
+hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
+  void* params[] = {const_cast<PersFwdArgs*>(&a)};
+  const void* fn = H == 512 ? (const void*)pers_fwd32_kernel<512>
+                            : (H == 256 ? (const void*)pers_fwd32_kernel<256> : (const void*)pers_fwd32_kernel<128>);
+  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+}
+
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
 bool bwd_wide(const Dims& d) {
   const char* e = getenv("LSTM_BWD_NARROW");
@@ -1022,13 +1271,19 @@ int run_forward_persistent(const FwdArgs& a) {
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
   const int BP = 16 * bp.NT;
+  const bool wide = fwd_wide(d);
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, s);
     CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
-    if (a.h0) {
+    if (a.h0 && wide) {
+      const long n = (long)d.L * d.B * d.H;
+      hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
+                         d.H);
+      CK(hipGetLastError(), "pack h0");
+    } else if (a.h0) {
       const long n = (long)d.L * d.B * d.H;
       hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
                          d.H, BP, bp.NC);
@@ -1050,7 +1305,8 @@ int run_forward_persistent(const FwdArgs& a) {
   const int grid = d.L * (d.H / 8);
   ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
   hipError_t e = hipErrorInvalidValue;
-  if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
+  if (wide) e = launch_fwd32(d.H, grid, k, s);
+  else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
   else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
   else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
   CK(e, "persistent forward launch");
