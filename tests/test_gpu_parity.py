@@ -123,6 +123,58 @@ def test_persistent_shapes(cfg, with_states):
     run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
+# ------------------------------------------------------------------ persistent path: kernel variants and the slow protocol
+VARIANTS = [
+    {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1"},                      # 16x16x4 kernels at B > 32
+    {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1", "LSTM_CHAINS": "2"},  # two independent batch chains
+    {"LSTM_FULL_FENCES": "1"},                                             # release/acquire fences on every step
+]
+
+
+@pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences"])
+@pytest.mark.parametrize("cfg", [PERS[3], PERS[4], PERS[5]], ids=["p256b20", "p512b33", "p512b64"])
+def test_persistent_variants(cfg, env, monkeypatch):
+    """The alternative kernels and the fence-based protocol must give the oracle's answer too; the
+    default path must give bit-identical results to the fence-based one (same arithmetic, only the
+    synchronisation differs), which cross-checks the fast flag protocol."""
+    torch, binding, runner = _mods()
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    r, ref = run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT)
+    if "LSTM_FULL_FENCES" in env:
+        slow = {k: getattr(r, k).clone() for k in FWD + BWD}
+        monkeypatch.delenv("LSTM_FULL_FENCES")
+        r.poison()
+        binding.check(r.forward(flags=binding.LSTM_PATH_PERSISTENT))
+        binding.check(r.backward(flags=binding.LSTM_PATH_PERSISTENT))
+        torch.cuda.synchronize()
+        for k in FWD + BWD:
+            assert torch.equal(slow[k], getattr(r, k)), k
+
+
+def test_watchdog_expires_and_reports(monkeypatch):
+    """A spin limit of 1 makes the waits of the persistent kernels give up at once (forced from the
+    host; the kernels still run to completion).  The library must report LSTM_INTERNAL on the next
+    call and work again after lstm_shutdown()."""
+    torch, binding, runner = _mods()
+    cfg = PERS[5]
+    d, ref = oracle_results(cfg, 11)
+    r = runner.LstmRunner(cfg.dims, d)
+    monkeypatch.setenv("LSTM_SPIN_LIMIT", "1")
+    st = r.forward(flags=binding.LSTM_PATH_PERSISTENT)
+    torch.cuda.synchronize()          # the kernel drained
+    assert st == binding.LSTM_OK      # the expiry is seen by the host only afterwards
+    monkeypatch.delenv("LSTM_SPIN_LIMIT")
+    st2 = r.forward(flags=binding.LSTM_PATH_PERSISTENT)
+    if st2 == binding.LSTM_OK:
+        pytest.skip("no wait expired with a spin limit of 1 (every flag was already set when polled)")
+    assert st2 == binding.LSTM_INTERNAL
+    binding.lstm_shutdown()
+    binding.check(r.forward(flags=binding.LSTM_PATH_PERSISTENT))
+    torch.cuda.synchronize()
+    assert_close(r.fwd_outputs(), ref, FWD, FWD_TOL)
+
+
 # ------------------------------------------------------------------ ragged / odd shapes, several tiles
 ODD = [
     Config("odd1", L=2, T=3, B=5, I=24, H=40, state_std=0.5, dstate_std=0.5),
