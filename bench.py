@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the dominant kernels at cfg3, from two rocprofv3 --pmc passes (FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/cfg3_hbm_traffic_pmc.md
+PMC_TRAFFIC_BYTES = {("cfg3", "bwd_recurrence"): int((561.1 + 439.3) * 2**20),
+                     ("cfg3", "fwd_recurrence"): int((305.0 + 364.3) * 2**20),
+                     ("cfg3", "weight_grad"): int((289.1 + 24.0 + 19.2 + 0.0) * 2**20)}
 
 
 def parse():
@@ -34,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-naive", action="store_true")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run one 1 GiB device-to-device copy first (reference point for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -95,6 +102,13 @@ def main():
         if do_bwd:
             B_.check(r.backward(flags=flags), "lstm_backward")
 
+    if args.copy_calibration:
+        src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -143,7 +157,8 @@ def main():
         if fl is not None:
             ach = fl / (dom_ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(ach / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+                        "frac": round(ach / PEAK_FP32_MFMA_TFLOPS, 4),
+                        "traffic": PMC_TRAFFIC_BYTES.get((cfg.name, dom)) if flags == 0 else None,
                         "kernel_phase": dom, "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
         else:
             by = phase_bytes(cfg, dom)
