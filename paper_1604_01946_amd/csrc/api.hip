@@ -75,12 +75,14 @@ WsLayout ws_layout(const Dims& d) {
   };
   w.P = take(L * TB * G * 4);
   w.dx = take(L * TB * H * 4);
-  w.RT = take(L * step_pack_floats(d.H) * 4);
+  w.RT = take(L * step_plan(d).pack_floats * 4);
   w.state = take(4 * L * d.B * H * 4);
   w.dbpart = take(L * 64 * G * 4);
   w.scratch = take(8 * (size_t)d.B * G * 4);
   w.xchg = take(L * (size_t)d.T * G * Bp * 4);
   w.flags = take((2 * L * ((size_t)d.T + 2) + 64) * 4);
+  w.skpart = take(splitk_supported(d.H) ? L * splitk_partial_floats(d.H, d.B) * 4 : 0);
+  w.skcnt = take(splitk_supported(d.H) ? L * ((size_t)d.T + 1) * splitk_counter_ints(d.H, d.B) * 4 : 0);
   w.resv = take(reserve_bytes(d));
   w.total = off;
   return w;

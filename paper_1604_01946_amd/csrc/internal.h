@@ -97,6 +97,20 @@ size_t step_pack_floats(int H);
 hipError_t launch_pack_fwd(const float* R, float* Rp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
 hipError_t launch_pack_bwd(const float* R, float* RTp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
 
+// ---------------------------------------------------------------- split-K step kernels (step_splitk.hip)
+struct SplitK {
+  float* partial;  // partial sums of this layer
+  int* counters;   // arrival counters of this (layer, step), zeroed once per pass
+  int KS;          // K slices
+  int per;         // k-steps (of 16) per K slice
+};
+bool splitk_supported(int H);
+size_t splitk_pack_floats(int H);
+size_t splitk_partial_floats(int H, int B);
+size_t splitk_counter_ints(int H, int B);
+hipError_t launch_pack_bwd_sk(const float* R, float* RTp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
+hipError_t launch_step_bwd_sk(const StepBwdArgs& a, float* partial, int* counters, hipStream_t s);
+
 // ---------------------------------------------------------------- device math
 __device__ __forceinline__ float sigmoidf_dev(float z) { return 1.0f / (1.0f + expf(-z)); }
 

@@ -18,6 +18,8 @@ struct WsLayout {
   size_t scratch;  // [8][B][4H]    per-cell temporaries of the unfused paths
   size_t xchg;     // persistent path: k-major exchange buffers
   size_t flags;    // persistent path: step counters and the watchdog word
+  size_t skpart;   // [L][splitk_partial_floats]  split-K partial sums
+  size_t skcnt;    // [L][T+1][splitk_counter_ints] split-K arrival counters
   size_t resv;     // stand-in for `reserve` when the caller runs inference
   size_t total;
 };
@@ -61,6 +63,24 @@ struct ProfScope {
   ProfScope(int p, hipStream_t st) : phase(p), s(st) { prof_begin(p, st); }
   ~ProfScope() { prof_end(phase, s); }
 };
+
+// Recurrent weights packed once per pass for the step kernels, and one step launch; both pick the
+// split-K kernels when the hidden size calls for them.
+struct StepPlan {
+  bool sk;               // backward steps use the split-K kernel
+  size_t pack_floats;    // per layer (room for either packed layout)
+  size_t part_floats;    // per layer
+  size_t counter_ints;   // per (layer, step)
+};
+inline StepPlan step_plan(const Dims& d) {
+  StepPlan p;
+  p.sk = splitk_supported(d.H);
+  const size_t a = step_pack_floats(d.H), b = p.sk ? splitk_pack_floats(d.H) : 0;
+  p.pack_floats = a > b ? a : b;
+  p.part_floats = splitk_partial_floats(d.H, d.B);
+  p.counter_ints = splitk_counter_ints(d.H, d.B);
+  return p;
+}
 
 inline int in_dim(const Dims& d, int l) { return l == 0 ? d.I : d.H; }
 inline size_t w_offset(const Dims& d, int l) {

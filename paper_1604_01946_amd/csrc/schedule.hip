@@ -58,7 +58,7 @@ int fwd_step(const FwdArgs& a) {
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
   hipStream_t s = a.stream;
   float* Rp = ws_f(a.ws, a.w.RT);
-  const size_t pf = step_pack_floats(d.H);
+  const size_t pf = step_plan(d).pack_floats;
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, s);
     CK(launch_pack_fwd(a.R, Rp, d.L, d.H, d.B, pf, s), "pack R");
@@ -230,14 +230,28 @@ int bwd_step(const BwdArgs& a) {
   hipStream_t s = a.stream;
   float* dA_all = ws_f(a.ws, a.w.P);
   float* RT = ws_f(a.ws, a.w.RT);
-  const size_t pf = step_pack_floats(H);
+  const StepPlan sp = step_plan(d);
+  const size_t pf = sp.pack_floats;
+  float* skpart = ws_f(a.ws, a.w.skpart);
+  int* skcnt = reinterpret_cast<int*>(a.ws + a.w.skcnt);
   float* dxb = ws_f(a.ws, a.w.dx);
   float* dcb = ws_f(a.ws, a.w.state);
   // weights re-laid out once per pass: the backward products read R transposed (Section 2.3)
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_pack_bwd(a.R, RT, d.L, H, B, pf, s), "pack R (transposed)");
+    if (sp.sk) {
+      CK(launch_pack_bwd_sk(a.R, RT, d.L, H, B, pf, s), "pack R (transposed, split-K)");
+      CK(launch_fill_zero(skcnt, (size_t)d.L * (T + 1) * sp.counter_ints * 4, s), "zero arrival counters");
+    } else {
+      CK(launch_pack_bwd(a.R, RT, d.L, H, B, pf, s), "pack R (transposed)");
+    }
   }
+  auto bwd_launch = [&](const StepBwdArgs& sa, int l, int slot) -> hipError_t {
+    if (sp.sk)
+      return launch_step_bwd_sk(sa, skpart + (size_t)l * sp.part_floats,
+                                skcnt + ((size_t)l * (T + 1) + slot) * sp.counter_ints, s);
+    return launch_step_bwd(sa, s);
+  };
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
     const LayerRes r = layer_res(a.reserve, d, l);
@@ -261,7 +275,7 @@ int bwd_step(const BwdArgs& a) {
       sa.pointwise = 1;
       sa.B = B;
       sa.H = H;
-      CK(launch_step_bwd(sa, s), "backward step kernel");
+      CK(bwd_launch(sa, l, t + 1), "backward step kernel");
     }
     if (a.dh0) {
       StepBwdArgs sa{};
@@ -271,7 +285,7 @@ int bwd_step(const BwdArgs& a) {
       sa.pointwise = 0;
       sa.B = B;
       sa.H = H;
-      CK(launch_step_bwd(sa, s), "backward step kernel (dh0)");
+      CK(bwd_launch(sa, l, 0), "backward step kernel (dh0)");
     }
     prof_end(LSTM_PHASE_BWD_RECURRENCE, s);
     // gradient for the layer below (or dx): all T steps in one product

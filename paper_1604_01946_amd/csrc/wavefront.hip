@@ -96,7 +96,7 @@ int run_forward_wavefront(const FwdArgs& a) {
   auto ev_steps = [&](int l, int j) { return h->events[2 + 2 * ((size_t)l * NCH + j)]; };
 
   float* Rp = ws_f(a.ws, a.w.RT);
-  const size_t pf = step_pack_floats(d.H);
+  const size_t pf = step_plan(d).pack_floats;
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, a.stream);
     CK(launch_pack_fwd(a.R, Rp, L, d.H, d.B, pf, a.stream), "pack R");
@@ -174,11 +174,25 @@ int run_backward_wavefront(const BwdArgs& a) {
   float* RT = ws_f(a.ws, a.w.RT);
   float* dxb = ws_f(a.ws, a.w.dx);
   float* dcb = ws_f(a.ws, a.w.state);
-  const size_t pf = step_pack_floats(H);
+  const StepPlan sp = step_plan(d);
+  const size_t pf = sp.pack_floats;
+  float* skpart = ws_f(a.ws, a.w.skpart);
+  int* skcnt = reinterpret_cast<int*>(a.ws + a.w.skcnt);
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, a.stream);
-    CK(launch_pack_bwd(a.R, RT, L, H, B, pf, a.stream), "pack R (transposed)");
+    if (sp.sk) {
+      CK(launch_pack_bwd_sk(a.R, RT, L, H, B, pf, a.stream), "pack R (transposed, split-K)");
+      CK(launch_fill_zero(skcnt, (size_t)L * (T + 1) * sp.counter_ints * 4, a.stream), "zero arrival counters");
+    } else {
+      CK(launch_pack_bwd(a.R, RT, L, H, B, pf, a.stream), "pack R (transposed)");
+    }
   }
+  auto bwd_launch = [&](const StepBwdArgs& sa, int l, int slot, hipStream_t st) -> hipError_t {
+    if (sp.sk)
+      return launch_step_bwd_sk(sa, skpart + (size_t)l * sp.part_floats,
+                                skcnt + ((size_t)l * (T + 1) + slot) * sp.counter_ints, st);
+    return launch_step_bwd(sa, st);
+  };
   {
     std::lock_guard<std::mutex> lk(g_mu);
     Helpers* h = helpers();
@@ -224,7 +238,7 @@ int run_backward_wavefront(const BwdArgs& a) {
           sa.pointwise = 1;
           sa.B = B;
           sa.H = H;
-          CK(launch_step_bwd(sa, step_stream(l)), "backward step kernel");
+          CK(bwd_launch(sa, l, t + 1, step_stream(l)), "backward step kernel");
         }
         if (t0 == 0 && a.dh0) {
           StepBwdArgs sa{};
@@ -234,7 +248,7 @@ int run_backward_wavefront(const BwdArgs& a) {
           sa.pointwise = 0;
           sa.B = B;
           sa.H = H;
-          CK(launch_step_bwd(sa, step_stream(l)), "backward step kernel (dh0)");
+          CK(bwd_launch(sa, l, 0, step_stream(l)), "backward step kernel (dh0)");
         }
         CK(hipEventRecord(ev_steps(l, j), step_stream(l)), "record steps");
         // the chunk's input gradient: dout of the layer below, or dx

@@ -182,6 +182,9 @@ ODD = [
     Config("odd3", L=2, T=5, B=70, I=36, H=100, state_std=0.5, dstate_std=0.5),  # two batch tiles, ragged tail
     Config("odd4", L=1, T=1, B=1, I=1, H=1, state_std=0.5, dstate_std=0.5),
     Config("odd5", L=2, T=6, B=33, I=130, H=264, state_std=0.5, dstate_std=0.5),
+    # hidden sizes that take the split-K step kernels (H >= 1024, multiple of 64)
+    Config("sk1", L=2, T=3, B=5, I=40, H=1024, state_std=0.5, dstate_std=0.5),
+    Config("sk2", L=2, T=2, B=70, I=24, H=1088, state_std=0.5, dstate_std=0.5),
 ]
 
 
