@@ -149,7 +149,11 @@ def main():
 
     # roofline of the phase that takes the most time
     dom = max(phases.items(), key=lambda kv: kv[1][0])[0] if phases else None
-    roofline = None
+    if dom and phases[dom][0] <= 0.0:
+        dom = None  # the unfused baseline paths record no phases
+    roofline = {"bound": "mfma", "achieved": round(tflops, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None, "kernel_phase": "whole_step",
+                "launch_intervals": 0, "avg_ms": round(ms, 4)}
     if dom:
         dom_ms, dom_n = phases[dom]
         persistent = (path_b if dom.startswith("bwd") or dom == "weight_grad" else path_f) == B_.LSTM_PATH_PERSISTENT
