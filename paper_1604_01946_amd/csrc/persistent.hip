@@ -107,7 +107,10 @@ struct Waiter {
 struct Tracer {
   long long* buf;  // [steps][8] wall-clock ticks (100 MHz), null when disabled
   __device__ __forceinline__ void mark(int step, int slot) const {
-    if (buf && threadIdx.x == 0) buf[(size_t)step * 8 + slot] = wall_clock64();
+    if (buf && threadIdx.x == 0) {
+      buf[(size_t)step * 8 + slot] = wall_clock64();
+      if (slot == 0) buf[(size_t)step * 8 + 7] = clock64();  // shader clock, for the core frequency
+    }
   }
 };
 
@@ -874,9 +877,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   constexpr int KPW = H / 2;                 // k-pairs per wave
   constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
   constexpr int LP = KPW - RP;               // k-pairs whose weights live in LDS
-  constexpr int CH8 = 16;                    // 8-k groups per chunk of the load pipeline
-  constexpr int NCH = NB8 / CH8;
-  static_assert(NB8 % CH8 == 0 && (RP / 4) % CH8 == 0, "chunks must not straddle the register/LDS split");
+  constexpr int DEPTH = NB8 < 16 ? NB8 : 16;  // 8-k groups whose exchange loads are in flight ahead of the MFMAs
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float* const part = smem;         // [4 waves][16 regs][64 lanes]
   float* const xs = smem + 4096;    // [8 blocks of 8 k][256]: this step's dA slice in exchange order
@@ -951,14 +952,15 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
   __syncthreads();                                    // LDS weights are in place
 
-  int seen_up = 0;
-  for (int t = T - 1; t >= 0; --t) {
-    tr.mark(t, 0);
-    // ---- point-wise stage of step t
-    floatx4 gi, gf, go, gg, ct, cp, dA4[4];
-    const size_t e = ((size_t)t * B + bb) * H + unit0;
-    const size_t g0 = ((size_t)t * B + bb) * G + unit0;
+  // Reserve values (and, for the top layer, dy) of the step the point-wise stage handles next.  They do
+  // not depend on any counter, so they are fetched one step ahead, under the MFMAs of the previous
+  // step: loads return in order, and a miss to HBM in front of the counter polls would otherwise
+  // stall every poll behind it.
+  floatx4 gi, gf, go, gg, ct, cp, dpre;
+  auto fetch_step = [&](int t) {
     if (pwv) {
+      const size_t e = ((size_t)t * B + bb) * H + unit0;
+      const size_t g0 = ((size_t)t * B + bb) * G + unit0;
       gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
       gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
       go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
@@ -970,12 +972,23 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
         cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
       else
         cp = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (!has_up) dpre = *reinterpret_cast<const floatx4*>(a.dy + e);
     }
+  };
+  fetch_step(T - 1);
+
+  int seen_up = 0;
+  for (int t = T - 1; t >= 0; --t) {
+    tr.mark(t, 0);
+    // ---- point-wise stage of step t
+    floatx4 dA4[4];
+    const size_t e = ((size_t)t * B + bb) * H + unit0;
+    const size_t g0 = ((size_t)t * B + bb) * G + unit0;
     if (has_up) w.wait(flag(l + 1, t), NS2, seen_up);  // dx of the layer above at step t is published
     tr.mark(t, 1);
     if (wave < 2) {
       floatx4 dout = {0.f, 0.f, 0.f, 0.f};
-      if (pwv) dout = *reinterpret_cast<const floatx4*>(dout_base + e);
+      if (pwv) dout = has_up ? *reinterpret_cast<const floatx4*>(dout_base + e) : dpre;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         if (pwv) {
@@ -1020,31 +1033,44 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     {
+      // One 16-byte exchange load feeds the four MFMAs of an 8-k group.  The loads run DEPTH groups
+      // ahead of the MFMAs and are issued between them (so is the LDS part of the weights, two groups
+      // ahead): issued in bulk they would hold the wave in the address unit while the matrix cores
+      // idle.  The scheduling barrier after every group keeps this order.
       const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
-      floatx4 bv[2][CH8];
+      floatx4 bv[NB8];
+      float al[NB8][4];
+#ifdef DBG_NOLOAD
+      auto ldb = [&](int g) { bv[g] = floatx4{(float)g, (float)lane, 1.f, 2.f}; };
+#else
+      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rot) & (NB8 - 1)) * 256); };
+#endif
+      auto ldw = [&](int g) {
+        if (g * 4 >= RP) {
 #pragma unroll
-      for (int i = 0; i < CH8; ++i) bv[0][i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NB8 - 1)) * 256);
-#pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) {
-        if (ch + 1 < NCH) {
-#pragma unroll
-          for (int i = 0; i < CH8; ++i)
-            bv[(ch + 1) & 1][i] = *reinterpret_cast<const floatx4*>(src + (size_t)(((ch + 1) * CH8 + i + rot) & (NB8 - 1)) * 256);
+          for (int m = 0; m < 4; ++m) al[g][m] = wl[((size_t)wave * LP + (g * 4 + m - RP)) * 64 + lane];
         }
-        float al[CH8 * 4];
-        if (ch * CH8 * 4 >= RP) {  // this chunk's weights come from LDS
+      };
 #pragma unroll
-          for (int p = 0; p < CH8 * 4; ++p) al[p] = wl[((size_t)wave * LP + (ch * CH8 * 4 + p - RP)) * 64 + lane];
+      for (int g = 0; g < DEPTH; ++g) ldb(g);
+      ldw(0);
+      if (NB8 > 1) ldw(1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < NB8; ++g) {
+        if (g + DEPTH < NB8) ldb(g + DEPTH);
+        if (g + 2 < NB8) ldw(g + 2);
+        if (g == NB8 - DEPTH && t > 0) fetch_step(t - 1);  // behind the last exchange load of this step
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int pr = g * 4 + m;
+          const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[g][m];
+#ifdef DBG_NOMFMA
+          acc[m] += av * bv[g][m];
+#else
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[g][m], acc, 0, 0, 0);
+#endif
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < CH8; ++i)
-#pragma unroll
-          for (int m = 0; m < 4; ++m) {
-            const int pr = (ch * CH8 + i) * 4 + m;
-            const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[i * 4 + m];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[ch & 1][i][m], acc, 0, 0, 0);
-          }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
