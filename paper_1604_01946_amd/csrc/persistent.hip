@@ -476,75 +476,13 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
-  const bool do_in = l > 0;
-  int seen_in = do_in ? Waiter::peek(flag(l - 1, 1)) : 0;
-  for (int t = 0; t < T; ++t) {
-    tr.mark(t, 0);
-    floatx16 acc[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  // One 16-byte load of a lane feeds four MFMAs (two k-pairs x two batch tiles).
+  auto ldx = [&](const float* src, int i) {
+    return *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
+  };
 
-    // layer 0: fetch the batched input projection early, it is consumed in the epilogue
-    float pin[2][4];
-#pragma unroll
-    for (int ci = 0; ci < 2; ++ci)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        pin[ci][g] = (l == 0 && valid) ? a.P0[((size_t)t * B + bb) * G + g * H + c_unit[ci]] : 0.f;
-
-    const bool do_rec = (t > 0 || a.has_h0);
-    const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t)) : 0;
-    floatx4 bi[NK4], br[NK4];
-    if (do_in) {  // input half: h of the layer below at this step
-      w.wait(flag(l - 1, t + 1), NS, seen_in);
-      const float* src = slot(l - 1, t + 1) + boff;
-#pragma unroll
-      for (int i = 0; i < NK4; ++i) bi[i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
-      tr.mark(t, 1);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < NK4 / 2; ++i)
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wW[i][m], bi[i][2 * m + j], acc[j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
-      if (t > 0) w.wait(flag(l, t), NS, seen_rec);
-      tr.mark(t, 2);
-      const float* src = slot(l, t) + boff;
-#pragma unroll
-      for (int i = 0; i < NK4; ++i) br[i] = *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // the next step's input flag: the answer arrives under the MFMAs below
-    seen_in = (do_in && t + 1 < T) ? Waiter::peek(flag(l - 1, t + 2)) : 0;
-    if (do_in) {
-#pragma unroll
-      for (int i = NK4 / 2; i < NK4; ++i)
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wW[i][m], bi[i][2 * m + j], acc[j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (do_rec) {
-#pragma unroll
-      for (int i = 0; i < NK4; ++i)
-#pragma unroll
-        for (int m = 0; m < 2; ++m)
-#pragma unroll
-          for (int j = 0; j < 2; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wR[i][m], br[i][2 * m + j], acc[j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // ---- 4-way K-split reduction through LDS
+  // ---- everything after the MFMAs of step t: K-split reduction, gates, publish h_t, reserve
+  auto finish_step = [&](const floatx16 (&acc)[2], const float (&pin)[2][4], const int t) {
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -552,8 +490,6 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     tr.mark(t, 3);
     __syncthreads();
     tr.mark(t, 4);
-
-    // ---- epilogue
     float o_gate[2][4], o_c[2], o_h[2];
 #pragma unroll
     for (int ci = 0; ci < 2; ++ci) {
@@ -611,16 +547,142 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         }
       }
     }
+  };
+
+  if (l == 0) {
+    // ---- layer 0: the input half is the batched projection P_0 (added in the epilogue); its values
+    //      for the next step are fetched one step ahead, behind the exchange loads, so that a miss to
+    //      HBM never sits in front of a counter poll (loads return in order).
+    float pin[2][4];
+#pragma unroll
+    for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) pin[ci][g] = valid ? a.P0[(size_t)bb * G + g * H + c_unit[ci]] : 0.f;
+    for (int t = 0; t < T; ++t) {
+      tr.mark(t, 0);
+      floatx16 acc[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+      if (t > 0) w.wait(flag(0, t), NS);  // slot 0 (h0 or zeros) was written before the launch
+      tr.mark(t, 2);
+      const float* src = slot(0, t) + boff;
+      floatx4 br[NK4];
+#pragma unroll
+      for (int i = 0; i < NK4; ++i) br[i] = ldx(src, i);
+      float pnx[2][4];
+#pragma unroll
+      for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          pnx[ci][g] = (valid && t + 1 < T) ? a.P0[((size_t)(t + 1) * B + bb) * G + g * H + c_unit[ci]] : 0.f;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NK4; ++i)
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wR[i][m], br[i][2 * m + j], acc[j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      finish_step(acc, pin, t);
+#pragma unroll
+      for (int ci = 0; ci < 2; ++ci)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) pin[ci][g] = pnx[ci][g];
+    }
+    return;
+  }
+
+  // ---- layers >= 1.  Order of one step, in k-groups of 4:
+  //   1. input MFMAs on the first half of h_{l-1,t}, already in registers; the second half is fetched
+  //      between them.  This part also covers the time the own layer's h_{t-1} needs to become visible.
+  //   2. wait for h_{l,t-1}; input MFMAs on the second half, the recurrent operand fetched between them.
+  //   3. recurrent MFMAs; between the first of them the first half of h_{l-1,t+1} is fetched if the
+  //      layer below (which normally runs ahead) has published it.  If it has not, the same loads
+  //      re-read the current step's slot -- valid memory, values unused -- so that the step is one
+  //      straight line of code, and the operand is fetched after a wait at the end of the step.
+  // Loads are issued between MFMAs rather than in bulk (a bulk of 32 16-byte loads per wave holds the
+  // wave in the address unit for about a microsecond while the matrix cores idle); the scheduling
+  // barriers pin that order.  Only half an operand is carried from step to step, which keeps the
+  // kernel inside the register file.
+  constexpr int HK = NK4 / 2;
+  const float zero_pin[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  floatx4 bl[HK];
+  w.wait(flag(l - 1, 1), NS);
+  {
+    const float* src = slot(l - 1, 1) + boff;
+#pragma unroll
+    for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
+  }
+  for (int t = 0; t < T; ++t) {
+    tr.mark(t, 0);
+    floatx16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    auto mma4 = [&](const float (&wgt)[2], const floatx4& bv) {
+#pragma unroll
+      for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wgt[m], bv[2 * m + j], acc[j], 0, 0, 0);
+    };
+    // both counters are read now; the answers arrive under the MFMAs of part 1
+    const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t)) : NS;
+    const int seen_in = (t + 1 < T) ? Waiter::peek(flag(l - 1, t + 2)) : 0;
+    floatx4 bh[HK], br[NK4];
+    {
+      const float* src = slot(l - 1, t + 1) + boff;
+      tr.mark(t, 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < HK; ++i) {
+        bh[i] = ldx(src, HK + i);
+        mma4(wW[i], bl[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    w.wait(flag(l, t), NS, seen_rec);  // h_{l,t-1}; slot 0 (h0 or zeros) was written before the launch
+    tr.mark(t, 2);
+    {
+      const float* src = slot(l, t) + boff;
+#pragma unroll
+      for (int i = 0; i < HK; ++i) {
+        br[2 * i] = ldx(src, 2 * i);
+        br[2 * i + 1] = ldx(src, 2 * i + 1);
+        mma4(wW[HK + i], bh[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    const bool more = t + 1 < T;
+    const bool pre = more && seen_in >= NS && !w.dead;
+    {
+      const float* nsrc = slot(l - 1, pre ? t + 2 : t + 1) + boff;
+#pragma unroll
+      for (int i = 0; i < NK4; ++i) {
+        if (i < HK) bl[i] = ldx(nsrc, i);
+        mma4(wR[i], br[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    finish_step(acc, zero_pin, t);
+    if (more && !pre) {  // the layer below was late: wait for it now, after this step is published
+      w.wait(flag(l - 1, t + 2), NS);
+      const float* src = slot(l - 1, t + 2) + boff;
+#pragma unroll
+      for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
+    }
   }
 }
 
-// h0 [L][B][H] -> exchange slot 0 of every layer in the layout of pers_fwd32_kernel.
+// h0 [L][B][H] (zeros if null) -> exchange slot 0 of every layer in the layout of pers_fwd32_kernel.
 __global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H) {
   const long cnt = (long)L * B * H;
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
     const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
     const int k4 = k >> 2, m = (k >> 1) & 1, kk = k & 1, n = bb >> 1, j = bb & 1;
-    hx[((size_t)l * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] = h0[e];
+    hx[((size_t)l * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] = h0 ? h0[e] : 0.f;
   }
 }
 
@@ -1304,7 +1366,7 @@ int run_forward_persistent(const FwdArgs& a) {
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, s);
     CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
-    if (a.h0 && wide) {
+    if (wide) {
       const long n = (long)d.L * d.B * d.H;
       hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
                          d.H);
