@@ -13,6 +13,8 @@
 // guarded loader, so every positive shape works.
 #include "internal.h"
 
+#include <type_traits>
+
 namespace lstm {
 namespace {
 
@@ -34,64 +36,92 @@ __host__ __device__ inline int pick_mode(const float* base, long s_r, long s_k, 
   return LM_SCALAR;
 }
 
-template <int ROWS>
-struct TileIO {
+// Moves one operand's [ROWS x KT] tiles from global memory to LDS (k-major) in slots of four
+// floats per thread.  The k-tiles of a slot are loaded in order 0, 1, 2, ...; `cur` is the address
+// of the next one and advances by one 64-bit add, so that the address arithmetic between the MFMAs
+// of the main loop stays a handful of instructions.  Every load is unconditional and reads a valid
+// address (past the last k-tile it re-reads the last one, a row outside the matrix reads the
+// matrix base) and the value is then replaced by zero where it lies outside: a guarded load would
+// put branches into the main loop, and with them the compiler moves the accumulators between
+// register files on every iteration.
+template <int ROWS, int MODE>
+struct TileMover {
   static constexpr int PER_THREAD = ROWS * KT / 256;
-  static constexpr int NVEC = PER_THREAD / 4;
+  static constexpr int SLOTS = PER_THREAD / 4;
   static constexpr int LDS_STRIDE = ROWS + PAD;
 
-  __device__ static void load(float (&reg)[PER_THREAD], const float* __restrict__ base, long s_r, long s_k, int r0,
-                              int k0, int R, int K, int mode, int tid) {
-    if (mode == LM_KCONTIG) {
+  const float* cur[SLOTS];  // vector modes: address of the slot in the next k-tile to load
+  int ktiles[SLOTS];        // vector modes: k-tiles for which the slot is inside the matrix (0: row outside)
+  int lds[SLOTS];           // vector modes: LDS offset of the slot
+  long step;                // elements between consecutive k-tiles
+  // scalar mode keeps the full description
+  const float* base;
+  long s_r, s_k;
+  int r0, R, K, tid;
+
+  __device__ void init(const float* b, long sr, long sk, int r0_, int R_, int K_, int tid_) {
+    base = b; s_r = sr; s_k = sk; r0 = r0_; R = R_; K = K_; tid = tid_;
+    step = (long)KT * sk;
 #pragma unroll
-      for (int v = 0; v < NVEC; ++v) {
-        const int idx = tid + 256 * v;
-        const int row = r0 + idx / (KT / 4), k = k0 + 4 * (idx % (KT / 4));
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < R && k < K) val = *reinterpret_cast<const float4*>(base + (long)row * s_r + k);
-        reg[4 * v + 0] = val.x; reg[4 * v + 1] = val.y; reg[4 * v + 2] = val.z; reg[4 * v + 3] = val.w;
+    for (int v = 0; v < SLOTS; ++v) {
+      const int idx = tid + 256 * v;
+      int row, k;
+      if (MODE == LM_KCONTIG) {
+        row = idx / (KT / 4); k = 4 * (idx % (KT / 4));
+      } else {
+        k = idx / (ROWS / 4); row = 4 * (idx % (ROWS / 4));
       }
-    } else if (mode == LM_RCONTIG) {
-#pragma unroll
-      for (int v = 0; v < NVEC; ++v) {
-        const int idx = tid + 256 * v;
-        const int k = k0 + idx / (ROWS / 4), row = r0 + 4 * (idx % (ROWS / 4));
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < R && k < K) val = *reinterpret_cast<const float4*>(base + (long)k * s_k + row);
-        reg[4 * v + 0] = val.x; reg[4 * v + 1] = val.y; reg[4 * v + 2] = val.z; reg[4 * v + 3] = val.w;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < PER_THREAD; ++i) {
-        const int e = tid + 256 * i;
-        const int row = r0 + e % ROWS, k = k0 + e / ROWS;
-        reg[i] = (row < R && k < K) ? base[(long)row * s_r + (long)k * s_k] : 0.f;
-      }
+      lds[v] = k * LDS_STRIDE + row;
+      const bool inside = r0 + row < R && k < K;
+      cur[v] = b + (inside ? (long)(r0 + row) * sr + (long)k * sk : 0);
+      ktiles[v] = inside ? (K - k + KT - 1) / KT : 0;
     }
   }
 
-  __device__ static void store(const float (&reg)[PER_THREAD], float* __restrict__ S, int mode, int tid) {
-    if (mode == LM_KCONTIG) {
+  // slot v of k-tile kt -> reg[4v .. 4v+3], raw (store() zeroes what lies outside the matrix: doing
+  // it here would make the wave wait for the data at once); the k-tiles of a slot must be requested
+  // in order from 0
+  __device__ __forceinline__ void load(float (&reg)[PER_THREAD], int v, int kt) {
+    if (MODE == LM_SCALAR) {
 #pragma unroll
-      for (int v = 0; v < NVEC; ++v) {
-        const int idx = tid + 256 * v;
-        const int row = idx / (KT / 4), k = 4 * (idx % (KT / 4));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) S[(k + j) * LDS_STRIDE + row] = reg[4 * v + j];
-      }
-    } else if (mode == LM_RCONTIG) {
-#pragma unroll
-      for (int v = 0; v < NVEC; ++v) {
-        const int idx = tid + 256 * v;
-        const int k = idx / (ROWS / 4), row = 4 * (idx % (ROWS / 4));
-        *reinterpret_cast<float4*>(S + k * LDS_STRIDE + row) =
-            make_float4(reg[4 * v + 0], reg[4 * v + 1], reg[4 * v + 2], reg[4 * v + 3]);
+      for (int i = 4 * v; i < 4 * v + 4; ++i) {
+        const int e = tid + 256 * i;
+        const int row = r0 + e % ROWS, k = kt * KT + e / ROWS;
+        reg[i] = base[(row < R && k < K) ? (long)row * s_r + (long)k * s_k : 0];
       }
     } else {
+#ifdef DBG_NOG
+      const float4 val = make_float4(1.f, 2.f, 3.f, (float)kt);
+#else
+      const float4 val = *reinterpret_cast<const float4*>(cur[v]);
+#endif
+      reg[4 * v + 0] = val.x; reg[4 * v + 1] = val.y; reg[4 * v + 2] = val.z; reg[4 * v + 3] = val.w;
+      cur[v] += (kt + 1 < ktiles[v]) ? step : 0;
+    }
+  }
+
+  // reg[4v .. 4v+3], loaded for k-tile kt -> LDS tile S
+  __device__ __forceinline__ void store(const float (&reg)[PER_THREAD], int v, int kt, float* __restrict__ S) const {
+    if (MODE == LM_SCALAR) {
 #pragma unroll
-      for (int i = 0; i < PER_THREAD; ++i) {
+      for (int i = 4 * v; i < 4 * v + 4; ++i) {
         const int e = tid + 256 * i;
-        S[(e / ROWS) * LDS_STRIDE + (e % ROWS)] = reg[i];
+        const int row = r0 + e % ROWS, k = kt * KT + e / ROWS;
+        S[(e / ROWS) * LDS_STRIDE + (e % ROWS)] = (row < R && k < K) ? reg[i] : 0.f;
+      }
+    } else {
+      const bool inside = kt < ktiles[v];
+      const float4 val = make_float4(inside ? reg[4 * v + 0] : 0.f, inside ? reg[4 * v + 1] : 0.f,
+                                     inside ? reg[4 * v + 2] : 0.f, inside ? reg[4 * v + 3] : 0.f);
+#ifdef DBG_NOS
+      if (val.x == 1234.5f) S[lds[v]] = val.y + val.z + val.w;
+      return;
+#endif
+      if (MODE == LM_KCONTIG) {
+        S[lds[v]] = val.x; S[lds[v] + LDS_STRIDE] = val.y;
+        S[lds[v] + 2 * LDS_STRIDE] = val.z; S[lds[v] + 3 * LDS_STRIDE] = val.w;
+      } else {
+        *reinterpret_cast<float4*>(S + lds[v]) = val;
       }
     }
   }
@@ -101,8 +131,10 @@ struct TileIO {
 template <int WM, int WN, int MA, int MB>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
   constexpr int MT = 64 * WM, NT = 64 * WN;
-  using IOA = TileIO<MT>;
-  using IOB = TileIO<NT>;
+  using IOA = TileMover<MT, MA>;
+  using IOB = TileMover<NT, MB>;
+  constexpr int SA = IOA::SLOTS, SB = IOB::SLOTS, SLOTS = SA + SB, KP = KT / 2;
+  static_assert(SLOTS + 3 <= KP && KP % 4 == 0, "the k-pairs of one tile must have room for the store slots before the barrier");
   __shared__ __attribute__((aligned(16))) float As[2][KT * IOA::LDS_STRIDE];
   __shared__ __attribute__((aligned(16))) float Bs[2][KT * IOB::LDS_STRIDE];
 
@@ -129,46 +161,83 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  float ra[IOA::PER_THREAD], rb[IOB::PER_THREAD];
+  // Software pipeline over k-tiles of KT, all stages in one instruction stream so that a single wave
+  // keeps the matrix pipe busy without relying on other waves to cover its waits:
+  //   G(t)  global -> registers, two tiles ahead (two register sets, so a miss to HBM has two tiles
+  //         of MFMA time to return), one slot per k-pair at the start of a tile;
+  //   S(t)  registers -> LDS, one tile ahead, one slot per k-pair before the barrier;
+  //   F     LDS -> operand fragments, two k-pairs ahead of the MFMAs that use them (a ring of four);
+  //   one barrier per tile, before the last two k-pairs: it publishes S(t+1) and closes the reads of
+  //   tile t (the fragments of its last k-pairs are fetched before it), so the first fragments of
+  //   tile t+1 are fetched under the last MFMAs of tile t.
+  // Spreading G and S over the k-pairs matters: their address arithmetic issued in one clump holds
+  // the wave between two MFMAs for longer than an MFMA lasts.  Loads past K give zeros, so the
+  // stages run unconditionally.
+  IOA ia;
+  IOB ib;
+  ia.init(P.A, P.sAm, P.sAk, m0, P.M, P.K, tid);
+  ib.init(P.B, P.sBn, P.sBk, n0, P.N, P.K, tid);
+  float ra[2][IOA::PER_THREAD], rb[2][IOB::PER_THREAD];
   const int nk = (P.K + KT - 1) / KT;
-  IOA::load(ra, P.A, P.sAm, P.sAk, m0, 0, P.M, P.K, MA, tid);
-  IOB::load(rb, P.B, P.sBn, P.sBk, n0, 0, P.N, P.K, MB, tid);
-  IOA::store(ra, As[0], MA, tid);
-  IOB::store(rb, Bs[0], MB, tid);
+  const int aoff = (lane >> 5) * IOA::LDS_STRIDE + wm * 32 * WM + (lane & 31);
+  const int boff = (lane >> 5) * IOB::LDS_STRIDE + wn * 32 * WN + (lane & 31);
+  constexpr int AHEAD = 2;  // k-pairs between the fetch of a fragment pair and the MFMAs that use it
+  float fa[4][WM], fb[4][WN];
+  auto fetch = [&](int buf, int kk, int slot) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i) fa[slot][i] = As[buf][aoff + 2 * kk * IOA::LDS_STRIDE + 32 * i];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) fb[slot][j] = Bs[buf][boff + 2 * kk * IOB::LDS_STRIDE + 32 * j];
+  };
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+#pragma unroll
+    for (int v = 0; v < SA; ++v) ia.load(ra[t], v, t);
+#pragma unroll
+    for (int v = 0; v < SB; ++v) ib.load(rb[t], v, t);
+  }
+#pragma unroll
+  for (int v = 0; v < SA; ++v) ia.store(ra[0], v, 0, As[0]);
+#pragma unroll
+  for (int v = 0; v < SB; ++v) ib.store(rb[0], v, 0, Bs[0]);
   __syncthreads();
+#pragma unroll
+  for (int kk = 0; kk < AHEAD; ++kk) fetch(0, kk, kk);
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      IOA::load(ra, P.A, P.sAm, P.sAk, m0, (kt + 1) * KT, P.M, P.K, MA, tid);
-      IOB::load(rb, P.B, P.sBn, P.sBk, n0, (kt + 1) * KT, P.N, P.K, MB, tid);
-    }
-    const float* as = As[cur] + (lane >> 5) * IOA::LDS_STRIDE + wm * 32 * WM + (lane & 31);
-    const float* bs = Bs[cur] + (lane >> 5) * IOB::LDS_STRIDE + wn * 32 * WN + (lane & 31);
-    // all operand fragments of the k-tile are fetched from LDS first; the MFMAs then start as soon as
-    // the first fragments arrive and the remaining LDS latency hides under them
-    float a[KT / 2][WM], b[KT / 2][WN];
+  // one k-tile; PAR = parity of kt (LDS buffer and register set), a compile-time constant so that
+  // the register arrays keep static indices
+  auto tile = [&](auto par, int kt) {
+    constexpr int PAR = decltype(par)::value;
+    constexpr int BAR = KP - 1 - AHEAD;  // the barrier follows the MFMAs of this k-pair
 #pragma unroll
-    for (int kk = 0; kk < KT / 2; ++kk) {
-#pragma unroll
-      for (int i = 0; i < WM; ++i) a[kk][i] = as[2 * kk * IOA::LDS_STRIDE + 32 * i];
-#pragma unroll
-      for (int j = 0; j < WN; ++j) b[kk][j] = bs[2 * kk * IOB::LDS_STRIDE + 32 * j];
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = 0; kk < KT / 2; ++kk)
+    for (int kk = 0; kk < KP; ++kk) {
+      if (kk < SLOTS) {  // G(kt + 2), slot kk
+        if (kk < SA) ia.load(ra[PAR], kk < SA ? kk : 0, kt + 2);
+        else ib.load(rb[PAR], kk >= SA ? kk - SA : 0, kt + 2);
+      }
+      constexpr int S0 = BAR + 1 - SLOTS;  // first k-pair of the store stage; the last one is BAR
+      if (kk >= S0 && kk <= BAR) {  // S(kt + 1), slot kk - S0
+        const int v = kk - S0;
+        if (v < SA) ia.store(ra[PAR ^ 1], v < SA ? v : 0, kt + 1, As[PAR ^ 1]);
+        else ib.store(rb[PAR ^ 1], v >= SA ? v - SA : 0, kt + 1, Bs[PAR ^ 1]);
+      }
+      if (kk + AHEAD < KP) fetch(PAR, kk + AHEAD, (kk + AHEAD) & 3);
+      else fetch(PAR ^ 1, kk + AHEAD - KP, (kk + AHEAD) & 3);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk][i], b[kk][j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < nk) {
-      IOA::store(ra, As[cur ^ 1], MA, tid);
-      IOB::store(rb, Bs[cur ^ 1], MB, tid);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[kk & 3][i], fb[kk & 3][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk == BAR) __syncthreads();
     }
-    __syncthreads();
+  };
+  // an odd tile count is rounded up (the extra tile multiplies zeros): the loop body stays one
+  // straight line of code
+  for (int kt = 0; kt < nk; kt += 2) {
+    tile(std::integral_constant<int, 0>{}, kt);
+    tile(std::integral_constant<int, 1>{}, kt + 1);
   }
 
   // D layout of the 32x32 tile: register r of lane holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
