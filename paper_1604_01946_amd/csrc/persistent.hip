@@ -711,6 +711,7 @@ struct PersBwdArgs {
   float* dxbuf;        // [L][T][B][H] gradient for the layer below (slice l written by layer l, l >= 1)
   float* dh0;          // [L][B][H] or null
   float* dc0;          // [L][B][H] or null
+  float* db;           // [L][4H] bias gradient, zeroed before the launch (wide kernel only), or null
   int* flags;          // [L][T+1][NC]
   int* watchdog;
   int L, T, B, I, H;
@@ -992,11 +993,14 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   const bool dxl = wave >= 2 && bb < B && l > 0;
   const int unit0 = u0 + 8 * (wave & 1) + 4 * kk;
   float dc[4], dh_rec[4];
+  float dbsum[4][4];  // this lane's share of the bias gradient: sum over t of dA_t, per (gate, unit)
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
     dc[r] = (pwv && a.dcT) ? a.dcT[se] : 0.f;
     dh_rec[r] = (pwv && a.dhT) ? a.dhT[se] : 0.f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) dbsum[g][r] = 0.f;
   }
 
   const float* const res_l = a.res + (size_t)l * TB * 6 * H;
@@ -1062,6 +1066,8 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
           dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
           dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
           dc[r] = dcv * gf[r];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) dbsum[g][r] += dA4[g][r];
         }
         // unit u0 + 8*wave + 4*kk + r sits at k%8 = 4*kk + r of block (gate, wave): m = 2*kk + r/2, parity r%2
 #pragma unroll
@@ -1166,6 +1172,26 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
       if (a.dh0) a.dh0[se] = dh_rec[r];
       if (a.dc0) a.dc0[se] = dc[r];
+    }
+  }
+  // Bias gradient (Section 2.6 lists it with the weight update): the per-lane sums over t are added
+  // over the 32 batch rows of this workgroup through LDS and then into db.  Each element of db
+  // receives exactly one contribution per batch half, and a + b does not depend on which of the
+  // two arrives first, so the result is reproducible.
+  if (a.db) {
+    if (wave < 2) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) part[(g * 16 + 8 * wave + 4 * kk + r) * 32 + n] = dbsum[g][r];
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      const int g = threadIdx.x >> 4, ul = threadIdx.x & 15;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) sum += part[threadIdx.x * 32 + ((i + threadIdx.x) & 31)];
+      atomicAdd(a.db + (size_t)l * G + g * H + u0 + ul, sum);
     }
   }
 }
@@ -1401,7 +1427,7 @@ int run_forward_persistent(const FwdArgs& a) {
   return LSTM_OK;
 }
 
-int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped);
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done);
 
 int run_backward_persistent(const BwdArgs& a) {
   const Dims& d = a.d;
@@ -1421,6 +1447,12 @@ int run_backward_persistent(const BwdArgs& a) {
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
   k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
+  k.db = nullptr;
+  if (wide && a.db) {  // the wide kernel adds the bias gradient into db itself
+    ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
+    CK(launch_fill_zero(a.db, (size_t)d.L * G * 4, s), "zero db");
+    k.db = a.db;
+  }
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
   k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;
@@ -1441,7 +1473,7 @@ int run_backward_persistent(const BwdArgs& a) {
     GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)G, (long)G, 1, d.I, 1, d.I, 0};
     CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");
   }
-  return weight_gradients(a, dA, true);
+  return weight_gradients(a, dA, true, k.db != nullptr);
 }
 
 }  // namespace lstm

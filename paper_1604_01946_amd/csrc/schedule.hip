@@ -166,7 +166,7 @@ int fwd_unfused(const FwdArgs& a, int level) {
 // ------------------------------------------------------------------ weight update (Section 2.6)
 // dW_l = sum_t dA_t^T in_t, dR_l = sum_t dA_t^T h_{t-1}, db_l = sum_t,b dA_t: products over K = T*B
 // with no dependencies between them, so all of them go into grouped launches.
-int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped) {
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done) {
   const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
   const int H = d.H, B = d.B;
@@ -183,7 +183,7 @@ int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped) {
     n = 0;
     return e;
   };
-  {
+  if (!bias_done) {
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
     for (int l = 0; l < d.L; ++l)
       CK(launch_colsum(dA_all + (size_t)l * TB * G, (int)TB, (int)G,
@@ -296,7 +296,7 @@ int bwd_step(const BwdArgs& a) {
       CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
     }
   }
-  return weight_gradients(a, dA_all, true);
+  return weight_gradients(a, dA_all, true, false);
 }
 
 // ------------------------------------------------------------------ backward: unfused rungs
@@ -351,7 +351,7 @@ int bwd_unfused(const BwdArgs& a, bool per_gate) {
       }
     }
   }
-  return weight_gradients(a, dA_all, !per_gate);
+  return weight_gradients(a, dA_all, !per_gate, false);
 }
 
 }  // namespace

@@ -24,7 +24,7 @@ namespace lstm {
   } while (0)
 
 void release_persistent();
-int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped);
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done);
 
 namespace {
 
@@ -269,7 +269,7 @@ int run_backward_wavefront(const BwdArgs& a) {
     }
     prof_end(LSTM_PHASE_BWD_RECURRENCE, a.stream);
   }
-  return weight_gradients(a, dA_all, true);
+  return weight_gradients(a, dA_all, true, false);
 }
 
 }  // namespace lstm
