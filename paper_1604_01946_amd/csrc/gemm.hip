@@ -13,6 +13,7 @@
 // guarded loader, so every positive shape works.
 #include "internal.h"
 
+#include <stdlib.h>
 #include <type_traits>
 
 namespace lstm {
@@ -90,11 +91,7 @@ struct TileMover {
         reg[i] = base[(row < R && k < K) ? (long)row * s_r + (long)k * s_k : 0];
       }
     } else {
-#ifdef DBG_NOG
-      const float4 val = make_float4(1.f, 2.f, 3.f, (float)kt);
-#else
       const float4 val = *reinterpret_cast<const float4*>(cur[v]);
-#endif
       reg[4 * v + 0] = val.x; reg[4 * v + 1] = val.y; reg[4 * v + 2] = val.z; reg[4 * v + 3] = val.w;
       cur[v] += (kt + 1 < ktiles[v]) ? step : 0;
     }
@@ -113,10 +110,6 @@ struct TileMover {
       const bool inside = kt < ktiles[v];
       const float4 val = make_float4(inside ? reg[4 * v + 0] : 0.f, inside ? reg[4 * v + 1] : 0.f,
                                      inside ? reg[4 * v + 2] : 0.f, inside ? reg[4 * v + 3] : 0.f);
-#ifdef DBG_NOS
-      if (val.x == 1234.5f) S[lds[v]] = val.y + val.z + val.w;
-      return;
-#endif
       if (MODE == LM_KCONTIG) {
         S[lds[v]] = val.x; S[lds[v] + LDS_STRIDE] = val.y;
         S[lds[v] + 2 * LDS_STRIDE] = val.z; S[lds[v] + 3 * LDS_STRIDE] = val.w;
@@ -257,6 +250,225 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
     }
 }
 
+// ------------------------------------------------------------------ direct-to-LDS variant
+// The kernel above spends about a fifth of its time on the instructions that move operand tiles
+// through registers (address arithmetic, zero selects, LDS stores): on this hardware they are not
+// hidden behind the MFMAs of the same wave.  This variant takes them out of the main loop:
+//   * global_load_lds_dwordx4 writes 16 bytes per lane straight into LDS (one instruction per KB,
+//     scalar base + constant per-lane offset, so advancing to the next k-tile is scalar arithmetic);
+//   * three LDS stages, tiles requested two ahead, one barrier per tile;
+//   * an operand with unit stride along K keeps its natural [row][16 k] layout in LDS with the four
+//     16-byte pieces of a row XOR-swizzled by (row/2)%4, and a lane fetches four MFMA steps' worth of
+//     operand with one conflict-free ds_read_b128; an operand with unit stride along the row dimension
+//     lands k-major ([k][row]) and is fetched with ds_read_b32 as before.
+// MFMA step (blk, s) of a k-tile multiplies k = 8*blk + 4*h + s for the lane half h = lane/32, the
+// same pairing for both operands.  Requirements (else the kernel above runs): both operands in a
+// vector mode, K a multiple of KT, byte offsets inside an operand below 2^31.  Rows past the end of
+// an operand re-read its last rows; they only reach outputs that are not stored.
+constexpr int DL_STAGES = 3;
+
+template <int W, int ROWS, int MODE>
+struct DlOperand {
+  static constexpr int TILE = ROWS * KT;           // floats per stage
+  static constexpr int CPW = ROWS / 64;            // 1 KB chunks per wave and tile (4 waves)
+  const char* sb;                                   // scalar: address of the next tile to request
+  long step;                                        // bytes between k-tiles
+  unsigned voff[CPW];                               // per-lane byte offset inside the tile, per chunk
+  int rd[W][2];                                     // per-lane LDS float offset inside a stage (K mode: per blk)
+
+  __device__ void init(const float* base, long s_r, long s_k, int r0, int R, int wave, int lane, int w0) {
+    if (MODE == LM_KCONTIG) {
+      sb = reinterpret_cast<const char*>(base);
+      step = (long)KT * 4;
+#pragma unroll
+      for (int j = 0; j < CPW; ++j) {
+        const int row = 16 * (wave * CPW + j) + (lane >> 2), p = lane & 3;
+        const int kq = p ^ ((row >> 1) & 3);
+        const int ra = min(r0 + row, R - 1);
+        voff[j] = (unsigned)(((long)ra * s_r + 4 * kq) * 4);
+      }
+#pragma unroll
+      for (int i = 0; i < W; ++i) {
+        const int r = w0 + 32 * i + (lane & 31), h = lane >> 5;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) rd[i][blk] = r * KT + 4 * ((2 * blk + h) ^ ((r >> 1) & 3));
+      }
+    } else {
+      sb = reinterpret_cast<const char*>(base);
+      step = (long)KT * s_k * 4;
+      constexpr int KPC = 256 / ROWS;  // k-rows per chunk
+#pragma unroll
+      for (int j = 0; j < CPW; ++j) {
+        const int k = (wave * CPW + j) * KPC + (4 * lane) / ROWS, row = (4 * lane) % ROWS;
+        const int ra = min(r0 + row, R - 4);
+        voff[j] = (unsigned)(((long)k * s_k + ra) * 4);
+      }
+#pragma unroll
+      for (int i = 0; i < W; ++i) rd[i][0] = rd[i][1] = (4 * (lane >> 5)) * ROWS + w0 + 32 * i + (lane & 31);
+    }
+  }
+
+  // request the next tile into stage `st` of this operand's LDS area; `more`: a further tile exists.
+  // Written as inline assembly on purpose: through the compiler's builtin every later LDS read is
+  // made to wait for all outstanding requests (it cannot tell the stages apart), which would undo
+  // the prefetch.  M0 carries the wave's LDS destination; nothing else in this kernel uses M0.  The
+  // caller orders the requests against the reads with its own waits.
+  __device__ __forceinline__ void request(float* lds, int st, int wave, bool more) {
+#pragma unroll
+    for (int j = 0; j < CPW; ++j) {
+      const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lds + st * TILE + (wave * CPW + j) * 256);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(voff[j]), "s"(sb) : "memory");
+    }
+    sb += more ? step : 0;
+  }
+
+  // operand fragments of block blk (4 MFMA steps) of the tile in the stage at float offset `so`;
+  // part q of 4 (so that the reads can be spread over four steps)
+  __device__ __forceinline__ void fetch(float (&f)[W][4], const float* lds, int so, int blk, int q) const {
+    if (MODE == LM_KCONTIG) {
+#pragma unroll
+      for (int i = 0; i < W; ++i)
+        if ((i & 3) == q) {
+          const floatx4 x = *reinterpret_cast<const floatx4*>(lds + so + rd[i][blk]);
+          f[i][0] = x[0]; f[i][1] = x[1]; f[i][2] = x[2]; f[i][3] = x[3];
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < W; ++i) f[i][q] = lds[so + rd[i][0] + (8 * blk + q) * ROWS];
+    }
+  }
+};
+
+template <int WM, int WN, int MA, int MB>
+__global__ __launch_bounds__(256) void gemm_dl_kernel(const GemmGroupArgs g) {
+  constexpr int MT = 64 * WM, NT = 64 * WN;
+  using OA = DlOperand<WM, MT, MA>;
+  using OB = DlOperand<WN, NT, MB>;
+  __shared__ __attribute__((aligned(16))) float As[DL_STAGES * OA::TILE];
+  __shared__ __attribute__((aligned(16))) float Bs[DL_STAGES * OB::TILE];
+
+  int pi = 0;
+  int bid = blockIdx.x;
+  if ((gridDim.x & 7) == 0) bid = (bid & 7) * (gridDim.x >> 3) + (bid >> 3);
+  while (pi + 1 < g.nprob && bid >= g.tile_start[pi + 1]) ++pi;
+  const GemmProblem& P = g.p[pi];
+  const int local = bid - g.tile_start[pi];
+  const int tiles_n = (P.N + NT - 1) / NT;
+  const int m0 = (local / tiles_n) * MT, n0 = (local % tiles_n) * NT;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  OA oa;
+  OB ob;
+  oa.init(P.A, P.sAm, P.sAk, m0, P.M, wave, lane, wm * 32 * WM);
+  ob.init(P.B, P.sBn, P.sBk, n0, P.N, wave, lane, wn * 32 * WN);
+  const int nk = P.K / KT;
+  constexpr int NG = OA::CPW + OB::CPW;  // requests per wave and tile
+  // s_waitcnt with only the vector-memory counter set: at most NG requests (the newest tile) outstanding
+  constexpr int WAIT_NEWEST = (NG & 15) | ((NG >> 4) << 14) | (7 << 4) | (15 << 8);
+  constexpr int WAIT_ALL = (7 << 4) | (15 << 8);
+
+  // tiles 0 and 1 (a tile index past the end re-reads the last tile; it is never multiplied)
+  oa.request(As, 0, wave, 1 < nk);
+  ob.request(Bs, 0, wave, 1 < nk);
+  oa.request(As, 1, wave, 2 < nk);
+  ob.request(Bs, 1, wave, 2 < nk);
+  __builtin_amdgcn_s_waitcnt(WAIT_NEWEST);
+  __syncthreads();
+  float fa[2][WM][4], fb[2][WN][4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    oa.fetch(fa[0], As, 0, 0, q);
+    ob.fetch(fb[0], Bs, 0, 0, q);
+  }
+  int st = 0;  // stage of the tile being multiplied
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st1 = st == DL_STAGES - 1 ? 0 : st + 1;   // stage of tile kt + 1
+    const int st2 = st1 == DL_STAGES - 1 ? 0 : st1 + 1; // stage of tile kt + 2 (last read for tile kt - 1)
+    oa.request(As, st2, wave, kt + 3 < nk);
+    ob.request(Bs, st2, wave, kt + 3 < nk);
+    // block 0 of this tile; the fragments of block 1 are fetched between its steps
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      oa.fetch(fa[1], As, st * OA::TILE, 1, s4);
+      ob.fetch(fb[1], Bs, st * OB::TILE, 1, s4);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0][i][s4], fb[0][j][s4], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // tile kt + 1 has landed (this wave's share; the barrier collects the others') and every wave has
+    // fetched its last fragments of tile kt
+    __builtin_amdgcn_s_waitcnt(WAIT_NEWEST);
+    __syncthreads();
+    // block 1; the fragments of block 0 of the next tile are fetched between its steps
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      oa.fetch(fa[0], As, st1 * OA::TILE, 0, s4);
+      ob.fetch(fb[0], Bs, st1 * OB::TILE, 0, s4);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1][i][s4], fb[1][j][s4], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    st = st1;
+  }
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // no request may still be writing LDS when the workgroup ends
+
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      const int col = n0 + wn * 32 * WN + 32 * j + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < P.M && col < P.N) {
+          float* c = P.C + (long)row * P.ldc + col;
+          *c = P.accumulate ? (*c + acc[i][j][r]) : acc[i][j][r];
+        }
+      }
+    }
+}
+
+template <int WM, int WN>
+bool launch_tile_dl(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s) {
+#define LSTM_GEMM_CASE(A_, B_)                                                                      \
+  if (ma == A_ && mb == B_) {                                                                       \
+    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, A_, B_>), dim3(grid), dim3(256), 0, s, g);           \
+    return true;                                                                                    \
+  }
+  LSTM_GEMM_CASE(LM_KCONTIG, LM_KCONTIG)
+  LSTM_GEMM_CASE(LM_KCONTIG, LM_RCONTIG)
+  LSTM_GEMM_CASE(LM_RCONTIG, LM_RCONTIG)
+  LSTM_GEMM_CASE(LM_RCONTIG, LM_KCONTIG)
+#undef LSTM_GEMM_CASE
+  return false;
+}
+
+// Whether the direct-to-LDS kernel can run one operand of a problem.
+bool dl_operand_ok(int mode, long s_r, long s_k, int R, int K) {
+  if (mode == LM_KCONTIG) return R >= 1 && ((long)R * s_r + K) * 4 < (1L << 31);
+  if (mode == LM_RCONTIG) return R >= 4 && ((long)KT * s_k + R) * 4 < (1L << 31);
+  return false;
+}
+
 template <int WM, int WN>
 void launch_tile(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s) {
 #define LSTM_GEMM_CASE(A_, B_)                                                                        \
@@ -273,6 +485,12 @@ void launch_tile(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s
 }
 
 }  // namespace
+
+// LSTM_GEMM_STAGED=1 keeps every product on the register-staged kernel (for comparison and tests).
+static bool gemm_force_staged() {
+  const char* e = getenv("LSTM_GEMM_STAGED");
+  return e && *e == '1';
+}
 
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream) {
   if (nprob <= 0) return hipSuccess;
@@ -293,6 +511,10 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
     mb = (i == 0 || mb == b) ? b : LM_SCALAR;
   }
   if (ma == LM_SCALAR || mb == LM_SCALAR) ma = mb = LM_SCALAR;
+  bool dl = ma != LM_SCALAR && !gemm_force_staged();
+  for (int i = 0; i < nprob && dl; ++i)
+    dl = probs[i].K % KT == 0 && probs[i].K >= KT && dl_operand_ok(ma, probs[i].sAm, probs[i].sAk, probs[i].M, probs[i].K) &&
+         dl_operand_ok(mb, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);
   // Few large tiles leave most of the 256 CUs idle; fall back to 64x64 tiles then.
   if (total_big < 128) big = false;
   const int mt = big ? 128 : 64;
@@ -304,10 +526,16 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   for (int i = nprob; i <= kMaxGemmGroup; ++i) g.tile_start[i] = start;
   g.nprob = nprob;
   if (start == 0) return hipSuccess;
-  if (big)
+  if (dl) {
+    if (big)
+      launch_tile_dl<2, 2>(ma, mb, start, g, stream);
+    else
+      launch_tile_dl<1, 1>(ma, mb, start, g, stream);
+  } else if (big) {
     launch_tile<2, 2>(ma, mb, start, g, stream);
-  else
+  } else {
     launch_tile<1, 1>(ma, mb, start, g, stream);
+  }
   return hipGetLastError();
 }
 

@@ -1108,11 +1108,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
       floatx4 bv[NB8];
       float al[NB8][4];
-#ifdef DBG_NOLOAD
-      auto ldb = [&](int g) { bv[g] = floatx4{(float)g, (float)lane, 1.f, 2.f}; };
-#else
       auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rot) & (NB8 - 1)) * 256); };
-#endif
       auto ldw = [&](int g) {
         if (g * 4 >= RP) {
 #pragma unroll
@@ -1133,11 +1129,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
         for (int m = 0; m < 4; ++m) {
           const int pr = g * 4 + m;
           const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[g][m];
-#ifdef DBG_NOMFMA
-          acc[m] += av * bv[g][m];
-#else
           acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[g][m], acc, 0, 0, 0);
-#endif
         }
         __builtin_amdgcn_sched_barrier(0);
       }

@@ -42,21 +42,19 @@ def run_case(cfg, seed, flags, backward=True, with_states=True, with_dstates=Tru
 
 
 # ------------------------------------------------------------------ GEMM alone
-@pytest.mark.parametrize("M,N,K", [(64, 64, 16), (128, 128, 64), (200, 136, 72), (33, 17, 5), (6400, 2048, 512),
-                                   (1, 1, 1), (257, 129, 130)])
-@pytest.mark.parametrize("layout", ["NT", "NN", "TN"])
-def test_gemm_matches_numpy(M, N, K, layout):
+def _gemm_case(M, N, K, layout):
+    """layout: first letter A (N: [M][K], T: [K][M]), second letter B (N: [K][N], T: [N][K])."""
     torch, binding, _ = _mods()
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     A = rng.standard_normal((M, K)).astype(np.float32)
     Bm = rng.standard_normal((K, N)).astype(np.float32)
     ref = A.astype(np.float64) @ Bm.astype(np.float64)
     dev = "cuda:0"
-    if layout == "TN":
+    if layout[0] == "T":
         At = torch.from_numpy(np.ascontiguousarray(A.T)).to(dev); sAm, sAk = 1, M
     else:
         At = torch.from_numpy(A).to(dev); sAm, sAk = K, 1
-    if layout == "NT":
+    if layout[1] == "T":
         Bt = torch.from_numpy(np.ascontiguousarray(Bm.T)).to(dev); sBk, sBn = 1, K
     else:
         Bt = torch.from_numpy(Bm).to(dev); sBk, sBn = N, 1
@@ -68,6 +66,22 @@ def test_gemm_matches_numpy(M, N, K, layout):
     binding.check(binding.lstm_gemm_f32(M, N, K, At, sAm, sAk, Bt, sBk, sBn, C, N, 1), "gemm acc")
     torch.cuda.synchronize()
     assert np.max(np.abs(C.cpu().numpy() - 2 * ref)) / np.max(np.abs(ref)) < 4e-6
+
+
+# K a multiple of 16 with 16-byte aligned rows takes the direct-to-LDS kernel (1, 2, 3, 4 and many
+# k-tiles, ragged M and N), everything else the register-staged one
+@pytest.mark.parametrize("M,N,K", [(64, 64, 16), (128, 128, 64), (200, 136, 72), (33, 17, 5), (6400, 2048, 512),
+                                   (1, 1, 1), (257, 129, 130), (256, 384, 48), (100, 260, 32), (96, 68, 16)])
+@pytest.mark.parametrize("layout", ["NT", "NN", "TN", "TT"])
+def test_gemm_matches_numpy(M, N, K, layout):
+    _gemm_case(M, N, K, layout)
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (6400, 2048, 512), (256, 384, 48), (100, 260, 32)])
+@pytest.mark.parametrize("layout", ["NT", "NN", "TN", "TT"])
+def test_gemm_register_staged_kernel(M, N, K, layout, monkeypatch):
+    monkeypatch.setenv("LSTM_GEMM_STAGED", "1")
+    _gemm_case(M, N, K, layout)
 
 
 # ------------------------------------------------------------------ the five measured shapes
