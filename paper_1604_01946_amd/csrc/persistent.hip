@@ -125,6 +125,11 @@ __device__ __forceinline__ void xstore4(float* p, floatx4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 
+// Makes a wave-uniform value opaque to the optimiser.  Offsets derived from a loop-invariant value
+// are otherwise all computed ahead of the time loop, dozens of scalar registers that then live in
+// VGPR lanes and are moved back and forth between the MFMAs of every step.
+__device__ __forceinline__ void hide(int& v) { asm volatile("" : "+s"(v)); }
+
 // All threads have written; make it visible at agent scope and bump the counter once.
 __device__ __forceinline__ void signal(int* flag, int full) {
   if (full)
@@ -476,9 +481,12 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
-  // One 16-byte load of a lane feeds four MFMAs (two k-pairs x two batch tiles).
+  // One 16-byte load of a lane feeds four MFMAs (two k-pairs x two batch tiles).  `rv` is `rot`
+  // made opaque once per step (see hide()), so that the rotated offsets are computed next to their
+  // loads with a few scalar instructions.
+  int rv = rot;
   auto ldx = [&](const float* src, int i) {
-    return *reinterpret_cast<const floatx4*>(src + (size_t)((i + rot) & (NK4 - 1)) * 256);
+    return *reinterpret_cast<const floatx4*>(src + (size_t)((i + rv) & (NK4 - 1)) * 256);
   };
 
   // ---- everything after the MFMAs of step t: K-split reduction, gates, publish h_t, reserve
@@ -560,6 +568,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       for (int g = 0; g < 4; ++g) pin[ci][g] = valid ? a.P0[(size_t)bb * G + g * H + c_unit[ci]] : 0.f;
     for (int t = 0; t < T; ++t) {
       tr.mark(t, 0);
+      hide(rv);
       floatx16 acc[2];
 #pragma unroll
       for (int j = 0; j < 2; ++j)
@@ -617,6 +626,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   }
   for (int t = 0; t < T; ++t) {
     tr.mark(t, 0);
+    hide(rv);
     floatx16 acc[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -1108,7 +1118,9 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
       floatx4 bv[NB8];
       float al[NB8][4];
-      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rot) & (NB8 - 1)) * 256); };
+      int rv = rot;
+      hide(rv);  // keeps the rotated offsets next to their loads
+      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rv) & (NB8 - 1)) * 256); };
       auto ldw = [&](int g) {
         if (g * 4 >= RP) {
 #pragma unroll
