@@ -252,7 +252,9 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
+  int rv = rot;
   for (int t = 0; t < T; ++t) {
+    if (KG >= 32) hide(rv);  // large H: keeps the rotated offsets next to their loads instead of in spilled registers
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c == 0) tr.mark(t, 0);
@@ -281,7 +283,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
         w.wait(flag(l - 1, t + 1, c), NS, seen_in);
         const float* src = slot(l - 1, t + 1, c) + boff;
 #pragma unroll
-        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, bi[i]);
+        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rv) & (KG - 1)) * BP, bi[i]);
         if (c == 0) tr.mark(t, 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
         if (c == 0) tr.mark(t, 2);
         const float* src = slot(l, t, c) + boff;
 #pragma unroll
-        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KG - 1)) * BP, br[i]);
+        for (int i = 0; i < KG; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rv) & (KG - 1)) * BP, br[i]);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (do_in) {
@@ -797,28 +799,44 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
+  // Reserve values (and, for the top layer, dy) of the step the point-wise stage handles next.  They do
+  // not depend on any counter, so they are fetched one step ahead, behind the exchange loads of the
+  // previous step: loads return in order, and a miss to HBM in front of the counter polls would
+  // otherwise stall every poll behind it.
+  floatx4 gi[NC], gf[NC], go[NC], gg[NC], ct[NC], cp[NC], dpre[NC];
+  auto fetch_step = [&](int t, int c) {
+    if (pw[c]) {
+      const int bb = c * BP + lb;
+      const size_t e = ((size_t)t * B + bb) * H + unit0;
+      const size_t g0 = ((size_t)t * B + bb) * G + unit0;
+      gi[c] = *reinterpret_cast<const floatx4*>(res_gates + g0);
+      gf[c] = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
+      go[c] = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
+      gg[c] = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
+      ct[c] = *reinterpret_cast<const floatx4*>(res_c + e);
+      if (t > 0)
+        cp[c] = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
+      else if (a.c0)
+        cp[c] = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
+      else
+        cp[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (!has_up) dpre[c] = *reinterpret_cast<const floatx4*>(a.dy + e);
+    }
+  };
+#pragma unroll
+  for (int c = 0; c < NC; ++c) fetch_step(T - 1, c);
+
+  int rv = rot;
   for (int t = T - 1; t >= 0; --t) {
+    hide(rv);  // keeps the rotated offsets next to their loads
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c == 0) tr.mark(t, 0);
       const int bb = c * BP + lb;
       // ---- point-wise stage of step t
-      floatx4 gi, gf, go, gg, ct, cp, dA4[4];
+      floatx4 dA4[4];
       const size_t e = ((size_t)t * B + bb) * H + unit0;
       const size_t g0 = ((size_t)t * B + bb) * G + unit0;
-      if (pw[c]) {
-        gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
-        gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
-        go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
-        gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
-        ct = *reinterpret_cast<const floatx4*>(res_c + e);
-        if (t > 0)
-          cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
-        else if (a.c0)
-          cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
-        else
-          cp = floatx4{0.f, 0.f, 0.f, 0.f};
-      }
       if (has_up) w.wait(flag(l + 1, t, c), NS, seen_up[c]);  // dx of the layer above at step t is published
       if (c == 0) tr.mark(t, 1);
       if (fin && q < 2 && !pw[c]) {  // padded batch columns of the staged tile
@@ -828,17 +846,17 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
           for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + lb] = 0.f;
       }
       if (pw[c]) {
-        const floatx4 dout = *reinterpret_cast<const floatx4*>(dout_base + e);
+        const floatx4 dout = has_up ? *reinterpret_cast<const floatx4*>(dout_base + e) : dpre[c];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float dh = dout[r] + dh_rec[c][r];
-          const float tc = tanhf(ct[r]);
-          const float dcv = dc[c][r] + dh * go[r] * (1.f - tc * tc);
-          dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
-          dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
-          dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
-          dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
-          dc[c][r] = dcv * gf[r];
+          const float tc = tanhf(ct[c][r]);
+          const float dcv = dc[c][r] + dh * go[c][r] * (1.f - tc * tc);
+          dA4[0][r] = dcv * gg[c][r] * gi[c][r] * (1.f - gi[c][r]);
+          dA4[1][r] = dcv * cp[c][r] * gf[c][r] * (1.f - gf[c][r]);
+          dA4[2][r] = dh * tc * go[c][r] * (1.f - go[c][r]);
+          dA4[3][r] = dcv * gi[c][r] * (1.f - gg[c][r] * gg[c][r]);
+          dc[c][r] = dcv * gf[c][r];
 #pragma unroll
           for (int g = 0; g < 4; ++g) xs[(g * 8 + (unit0 - u0) + r) * BP + lb] = dA4[g][r];
         }
@@ -877,14 +895,15 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         constexpr int CH = (KGB >= 64) ? 32 : 16, NCH = KGB / CH;
         float bv[2][CH][NT];
 #pragma unroll
-        for (int i = 0; i < CH; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rot) & (KGB - 1)) * BP, bv[0][i]);
+        for (int i = 0; i < CH; ++i) BVec<NT>::ld(src + (size_t)4 * ((i + rv) & (KGB - 1)) * BP, bv[0][i]);
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
           if (ch + 1 < NCH) {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
-              BVec<NT>::ld(src + (size_t)4 * (((ch + 1) * CH + i + rot) & (KGB - 1)) * BP, bv[(ch + 1) & 1][i]);
+              BVec<NT>::ld(src + (size_t)4 * (((ch + 1) * CH + i + rv) & (KGB - 1)) * BP, bv[(ch + 1) & 1][i]);
           }
+          if (ch == (NCH > 1 ? NCH - 2 : 0) && t > 0) fetch_step(t - 1, c);  // behind this step's last exchange loads
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int i = 0; i < CH; ++i)
