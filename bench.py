@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/cfg3_hbm_traffic_pmc.md
 PMC_TRAFFIC_BYTES = {("cfg3", "bwd_recurrence"): int((561.1 + 439.3) * 2**20),
                      ("cfg3", "fwd_recurrence"): int((305.0 + 364.3) * 2**20),
-                     ("cfg3", "weight_grad"): int((289.1 + 24.0 + 19.2 + 0.0) * 2**20)}
+                     ("cfg3", "weight_grad"): int((497.8 + 32.0 + 19.2 + 16.0) * 2**20)}
 
 
 def parse():
