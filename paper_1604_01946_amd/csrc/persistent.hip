@@ -1294,6 +1294,16 @@ int full_fences() {
 // Batch tiles per chain and number of chains.  One chain is the default: on MI355X two chains
 // measured slower at B = 64 (the step is bound by MFMA issue forward and by L2->CU bandwidth
 // backward, and half-width 8-byte exchange loads are less efficient); LSTM_CHAINS=2 selects two.
+// All workgroups of a persistent kernel must be resident at once (they wait on each other).  The
+// cooperative launch guarantees that; LSTM_PLAIN_LAUNCH=1 uses an ordinary launch instead, which is
+// resident as well when nothing else holds the CUs for good (the grid never exceeds one workgroup
+// per CU), for comparison.
+hipError_t launch_resident(const void* fn, int grid, void** params, unsigned smem, hipStream_t s) {
+  const char* e = getenv("LSTM_PLAIN_LAUNCH");
+  if (e && *e == '1') return hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);
+  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
+}
+
 struct BatchPlan {
   int NT, NC;
 };
@@ -1315,7 +1325,7 @@ hipError_t launch_fwd(BatchPlan bp, int grid, const PersFwdArgs& a, hipStream_t 
   if (bp.NT == 2 && bp.NC == 1) fn = (const void*)pers_fwd_kernel<KG, 2, 1>;
   if (bp.NT == 4 && bp.NC == 1) fn = (const void*)pers_fwd_kernel<KG, 4, 1>;
   if (!fn) return hipErrorInvalidValue;
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+  return launch_resident(fn, grid, params, 0, s);
 }
 
 template <int KGB>
@@ -1328,7 +1338,7 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
   if (bp.NT == 2 && bp.NC == 1) fn = (const void*)pers_bwd_kernel<KGB, 2, 1>;
   if (bp.NT == 4 && bp.NC == 1) fn = (const void*)pers_bwd_kernel<KGB, 4, 1>;
   if (!fn) return hipErrorInvalidValue;
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+  return launch_resident(fn, grid, params, 0, s);
 }
 
 // The wide-batch forward kernel (32x32x2 MFMA, two batch tiles of 32).
@@ -1342,7 +1352,7 @@ hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
   const void* fn = H == 512 ? (const void*)pers_fwd32_kernel<512>
                             : (H == 256 ? (const void*)pers_fwd32_kernel<256> : (const void*)pers_fwd32_kernel<128>);
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, 0, s);
+  return launch_resident(fn, grid, params, 0, s);
 }
 
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
@@ -1366,7 +1376,7 @@ hipError_t launch_bwd32(const PersBwdArgs& a, hipStream_t s) {
   int nbh = 2;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
   const int grid = a.L * (HH / 16) * nbh;
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, (unsigned)smem, s);
+  return launch_resident(fn, grid, params, (unsigned)smem, s);
 }
 
 }  // namespace
