@@ -70,6 +70,8 @@ struct BVec<4> {
 // needed per step either.  `full` (LSTM_FULL_FENCES=1) swaps both sides for the compiler's
 // agent-scope release / acquire fences (L2 write-back and invalidate on every step), which is
 // several times slower and exists to cross-check the fast protocol.
+constexpr int kFlagStride = 32;  // ints between the words of a split counter: one 128-byte line each
+
 struct Waiter {
   int* watchdog;  // host-visible word, set when a wait expires
   int limit;
@@ -85,6 +87,28 @@ struct Waiter {
     if (!dead && seen < target) {
       int spins = 0;
       while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > limit) {
+          dead = true;
+          __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          break;
+        }
+      }
+    }
+    acquire();
+  }
+  // The same for a counter split into NSUB words, each on a cache line of its own (kFlagStride ints
+  // apart): agent-scope atomics from many workgroups on one line are served one after the other by
+  // the memory side, about 25 ns each (6.4 us for 256 arrivals, measured), so the arrivals are spread
+  // over NSUB lines and a waiter reads them all with one load per lane.
+  template <int NSUB>
+  __device__ __forceinline__ void wait_split(int* flags, int target_each) {
+    if (!dead) {
+      const int lane = threadIdx.x & 63;
+      int spins = 0;
+      while (true) {
+        const int v = lane < NSUB ? __hip_atomic_load(flags + lane * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : target_each;
+        if (__all(v >= target_each)) break;
         __builtin_amdgcn_s_sleep(1);
         if (++spins > limit) {
           dead = true;
@@ -1219,6 +1243,202 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   }
 }
 
+// ------------------------------------------------------------------ one layer, large hidden size
+// Section 4 of arXiv 1604.01946 puts the limit of the persistent approach at the capacity of the
+// on-chip memory.  On MI355X the 256 CUs together hold 128 MB of registers and 40 MB of LDS, so a
+// whole [4H x H] recurrent matrix of H = 2048 (64 MiB) fits: every workgroup keeps the 32 rows of
+// 8 hidden units (4 gates x 8 units x H floats = 256 KB) for all T steps, half of it in VGPRs and half
+// in LDS, exactly the split of pers_bwd32_kernel.  One launch runs one layer (all CUs are needed for
+// it, so the layers cannot overlap); the layer's input projection is a batched GEMM before it, as for
+// layer 0 above.  Per step a workgroup multiplies its [32 x H] slice by h_{t-1} ([H x 32 batch rows],
+// read from the exchange slot), K split over the four waves, and finalises 8 units x 32 batch rows.
+// Exchange layout of a slot (H x 32 floats): for k = wave*H/4 + 8*k8 + 2*m + kk and batch row n,
+// element (wave*H/32 + k8)*256 + ((kk*32 + n)*4 + m) -- the 8 units of slice s are one contiguous KB.
+struct PersFwdLArgs {
+  const float* R;     // [4H][H] of this layer
+  const float* bias;  // [4H]
+  const float* P;     // [T][B][4H] input projection of this layer
+  const float* c0;    // [B][H] or null
+  float* hx;          // [T+1][H*32] exchange, slot t+1 = h_t, slot 0 = h0 (or zeros)
+  int* flags;         // [T+1][16][kFlagStride]: slot t+1 counts the slices that published h_t, spread over 16 lines
+  int* watchdog;
+  float* res;         // reserve of this layer
+  float* y;           // [T][B][H] or null (top layer only)
+  float* hT;          // [B][H] or null
+  float* cT;          // [B][H] or null
+  int T, B;
+  int spin_limit;
+  int full_fences;
+  long long* trace;
+  int trace_block;
+};
+
+template <int HH>
+__global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
+  constexpr int H = HH, G = 4 * H, NS = H / 8;
+  constexpr int NB8 = H / 32;                // 8-k groups per wave
+  constexpr int KPW = H / 8;                 // k-pairs per wave
+  constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
+  constexpr int LP = KPW - RP;               // k-pairs whose weights live in LDS
+  constexpr int DEPTH = NB8 < 16 ? NB8 : 16;
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* const part = smem;         // [4 waves][16 regs][64 lanes]
+  float* const xs = smem + 4096;    // [256]: this step's h slice in exchange order
+  float* const ro = smem + 4352;    // [6 arrays][32 batch rows][8 units]
+  float* const wl = smem + 6144;    // [4 waves][LP][64 lanes]
+
+  const int s = blockIdx.x, u0 = 8 * s;
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kk = lane >> 5, n = lane & 31;
+  const size_t TB = (size_t)T * B;
+  const int rot = ((int)(blockIdx.x >> 3) * (NB8 / 32 > 0 ? NB8 / 32 : 1) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (NB8 - 1);
+
+  // ---- weights: A operand row rho = lane%32 = (gate rho/8, unit rho%8); register / LDS entry i covers
+  //      k = wave*H/4 + 8*((i/4 + rot) mod NB8) + 2*(i%4) + kk
+  float wreg[RP];
+  {
+    const float* src = a.R + ((size_t)(n >> 3) * H + u0 + (n & 7)) * H + (size_t)wave * (H / 4) + kk;
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) {
+      const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
+      const float v = src[8 * k8 + 2 * m];
+      if (i < RP)
+        wreg[i < RP ? i : 0] = v;
+      else
+        wl[((size_t)wave * LP + (i - RP)) * 64 + lane] = v;
+    }
+  }
+
+  // ---- the cell this thread finalises: unit u0 + 4*kk + wave, batch row n (D register 4*gate + wave)
+  const int uj = 4 * kk + wave;
+  const bool valid = n < B;
+  float c_state = (valid && a.c0) ? a.c0[(size_t)n * H + u0 + uj] : 0.f;
+  float c_bias[4], pin[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    c_bias[g] = a.bias[g * H + u0 + uj];
+    pin[g] = valid ? a.P[(size_t)n * G + g * H + u0 + uj] : 0.f;
+  }
+  float* const res_gates = a.res;
+  float* const res_c = a.res + TB * 4 * H;
+  float* const res_h = a.res + TB * 5 * H;
+  auto slot = [&](int sl) { return a.hx + (size_t)sl * H * 32; };
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+  __syncthreads();                                    // LDS weights are in place
+
+  int rv = rot;
+  for (int t = 0; t < T; ++t) {
+    tr.mark(t, 0);
+    hide(rv);  // keeps the rotated offsets next to their loads
+    if (t > 0) w.template wait_split<16>(a.flags + (size_t)16 * kFlagStride * t, NS / 16);  // slot 0 was written before the launch
+    tr.mark(t, 2);
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    float pnx[4];
+    {
+      const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
+      floatx4 bv[NB8];
+      float al[NB8][4];
+      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rv) & (NB8 - 1)) * 256); };
+      auto ldw = [&](int g) {
+        if (g * 4 >= RP) {
+#pragma unroll
+          for (int m = 0; m < 4; ++m) al[g][m] = wl[((size_t)wave * LP + (g * 4 + m - RP)) * 64 + lane];
+        }
+      };
+#pragma unroll
+      for (int g = 0; g < DEPTH; ++g) ldb(g);
+      ldw(0);
+      if (NB8 > 1) ldw(1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < NB8; ++g) {
+        if (g + DEPTH < NB8) ldb(g + DEPTH);
+        if (g + 2 < NB8) ldw(g + 2);
+        if (g == NB8 - DEPTH) {  // next step's input projection, behind the last exchange load of this step
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            pnx[q] = (valid && t + 1 < T) ? a.P[((size_t)(t + 1) * B + n) * G + q * H + u0 + uj] : 0.f;
+        }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int pr = g * 4 + m;
+          const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[g][m];
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[g][m], acc, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[(wave * 16 + r) * 64 + lane] = acc[r];
+    tr.mark(t, 3);
+    __syncthreads();
+    tr.mark(t, 4);
+    float sg[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int r = 4 * g + wave;
+      sg[g] = (part[(0 * 16 + r) * 64 + lane] + part[(1 * 16 + r) * 64 + lane]) +
+              (part[(2 * 16 + r) * 64 + lane] + part[(3 * 16 + r) * 64 + lane]) + pin[g] + c_bias[g];
+    }
+    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gg = tanhf(sg[3]);
+    const float cv = gf * c_state + gi * gg;
+    const float hv = go * tanhf(cv);
+    c_state = cv;
+    xs[((uj & 1) * 32 + n) * 4 + (uj >> 1)] = valid ? hv : 0.f;
+    __syncthreads();
+    if (threadIdx.x < 64)
+      xstore4(slot(t + 1) + (size_t)s * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
+    tr.mark(t, 5);
+    signal(a.flags + ((size_t)16 * (t + 1) + (s & 15)) * kFlagStride, a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+    tr.mark(t, 6);
+    // reserve and outputs: staged through LDS so that every store instruction writes 16-byte runs
+    ro[(0 * 32 + n) * 8 + uj] = gi;
+    ro[(1 * 32 + n) * 8 + uj] = gf;
+    ro[(2 * 32 + n) * 8 + uj] = go;
+    ro[(3 * 32 + n) * 8 + uj] = gg;
+    ro[(4 * 32 + n) * 8 + uj] = cv;
+    ro[(5 * 32 + n) * 8 + uj] = hv;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int idx = threadIdx.x + 256 * i;  // (array 0..5, batch row, half of the 8 units)
+      const int arr = idx >> 6, b2 = (idx >> 1) & 31, hf = idx & 1;
+      if (idx < 384 && b2 < B) {
+        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 32 + b2) * 8 + 4 * hf);
+        const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
+        if (arr < 4) {
+          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
+        } else if (arr == 4) {
+          *reinterpret_cast<floatx4*>(res_c + e) = v;
+          if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + (size_t)b2 * H + u0 + 4 * hf) = v;
+        } else {
+          *reinterpret_cast<floatx4*>(res_h + e) = v;
+          if (a.y) *reinterpret_cast<floatx4*>(a.y + e) = v;
+          if (t == T - 1 && a.hT) *reinterpret_cast<floatx4*>(a.hT + (size_t)b2 * H + u0 + 4 * hf) = v;
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) pin[g] = pnx[g];
+  }
+}
+
+// h0 [B][H] of one layer (zeros if null) -> exchange slot 0 in the layout of pers_fwdL_kernel, all 32 batch columns.
+__global__ void pack_stateL_kernel(const float* __restrict__ h0, float* __restrict__ hx, int B, int H) {
+  const long cnt = (long)32 * H;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(e % H), bb = (int)(e / H);
+    const int wv = k / (H / 4), kr = k % (H / 4), k8 = kr >> 3, m = (kr >> 1) & 3, kk = kr & 1;
+    hx[((size_t)wv * (H / 32) + k8) * 256 + (kk * 32 + bb) * 4 + m] = (h0 && bb < B) ? h0[(size_t)bb * H + k] : 0.f;
+  }
+}
+
 // ------------------------------------------------------------------ host state
 struct DeviceInfo {
   bool ok = false;
@@ -1291,9 +1511,6 @@ int full_fences() {
   return (e && *e && *e != '0') ? 1 : 0;
 }
 
-// Batch tiles per chain and number of chains.  One chain is the default: on MI355X two chains
-// measured slower at B = 64 (the step is bound by MFMA issue forward and by L2->CU bandwidth
-// backward, and half-width 8-byte exchange loads are less efficient); LSTM_CHAINS=2 selects two.
 // All workgroups of a persistent kernel must be resident at once (they wait on each other).  The
 // cooperative launch guarantees that; LSTM_PLAIN_LAUNCH=1 uses an ordinary launch instead, which is
 // resident as well when nothing else holds the CUs for good (the grid never exceeds one workgroup
@@ -1304,6 +1521,9 @@ hipError_t launch_resident(const void* fn, int grid, void** params, unsigned sme
   return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
 }
 
+// Batch tiles per chain and number of chains.  One chain is the default: on MI355X two chains
+// measured slower at B = 64 (the step is bound by MFMA issue forward and by L2->CU bandwidth
+// backward, and half-width 8-byte exchange loads are less efficient); LSTM_CHAINS=2 selects two.
 struct BatchPlan {
   int NT, NC;
 };
@@ -1401,8 +1621,19 @@ void release_persistent() {
   }
 }
 
+// Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
+bool persistent_large(const Dims& d, bool backward) {
+  if (backward) return false;  // the backward pass of these shapes runs on the step path
+  const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");
+  if (e && *e == '1') return false;
+  if (!(d.H == 1024 || d.H == 2048) || d.B > 32) return false;
+  DeviceInfo di;
+  if (!device_info(di) || !di.coop) return false;
+  return d.H / 8 <= di.cus;
+}
+
 bool persistent_supported(const Dims& d, bool backward) {
-  (void)backward;
+  if (persistent_large(d, backward)) return true;
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
   if (d.B > 64) return false;
   DeviceInfo di;
@@ -1410,8 +1641,72 @@ bool persistent_supported(const Dims& d, bool backward) {
   return (long)d.L * (d.H / 8) <= di.cus;
 }
 
+namespace {
+
+template <int HH>
+hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
+  constexpr int KPW = HH / 8, LP = KPW > 128 ? KPW - 128 : 0;
+  const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
+  const void* fn = (const void*)pers_fwdL_kernel<HH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  void* params[] = {const_cast<PersFwdLArgs*>(&a)};
+  return launch_resident(fn, HH / 8, params, (unsigned)smem, s);
+}
+
+// Forward pass of the large-H shapes: per layer the batched input projection, then one persistent launch.
+int run_forward_persistent_large(const FwdArgs& a) {
+  const Dims& d = a.d;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
+  hipStream_t s = a.stream;
+  float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
+  int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
+  float* P = reinterpret_cast<float*>(a.ws + a.w.P);
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
+    {
+      ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+      CK(launch_fill_zero(flags, ((size_t)d.T + 1) * 16 * kFlagStride * 4, s), "zero step counters");
+      hipLaunchKernelGGL(pack_stateL_kernel, dim3((unsigned)((32L * d.H + 255) / 256)), dim3(256), 0, s,
+                         a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.B, d.H);
+      CK(hipGetLastError(), "pack h0");
+    }
+    {
+      ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
+      GemmProblem p{in, a.W + w_offset(d, l), P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+      CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+    }
+    PersFwdLArgs k;
+    k.R = a.R + (size_t)l * G * d.H; k.bias = a.b + (size_t)l * G; k.P = P;
+    k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
+    k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
+    k.res = a.reserve + (size_t)l * TB * 6 * d.H;
+    k.y = l == d.L - 1 ? a.y : nullptr;
+    k.hT = a.hT ? a.hT + (size_t)l * BH : nullptr;
+    k.cT = a.cT ? a.cT + (size_t)l * BH : nullptr;
+    k.T = d.T; k.B = d.B; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+    k.trace_block = g_trace_block;
+    ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    CK(d.H == 2048 ? launch_fwdL<2048>(k, s) : launch_fwdL<1024>(k, s), "persistent forward launch (large H)");
+  }
+  return LSTM_OK;
+}
+
+}  // namespace
+
 int run_forward_persistent(const FwdArgs& a) {
   const Dims& d = a.d;
+  if (persistent_large(d, false)) {
+    if (!ensure_watchdog()) return LSTM_HIP_ERROR;
+    if (*g_watch_host) return LSTM_INTERNAL;
+    return run_forward_persistent_large(a);
+  }
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;

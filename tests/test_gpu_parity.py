@@ -137,6 +137,24 @@ def test_persistent_shapes(cfg, with_states):
     run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
+# Large hidden sizes: forward on the one-layer-per-launch persistent kernel (recurrent matrix spread over all CUs),
+# backward on whatever the automatic choice is
+LARGE = [
+    Config("l1024b32", L=2, T=5, B=32, I=96, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l1024b7", L=1, T=4, B=7, I=1024, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l2048b32", L=2, T=4, B=32, I=256, H=2048, state_std=0.3, dstate_std=0.3),
+    Config("l2048b5", L=1, T=3, B=5, I=64, H=2048, state_std=0.3, dstate_std=0.3),
+]
+
+
+@pytest.mark.parametrize("cfg", LARGE, ids=[c.name for c in LARGE])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_persistent_large_hidden(cfg, with_states):
+    _, binding, _ = _mods()
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
+
+
 # ------------------------------------------------------------------ persistent path: kernel variants and the slow protocol
 VARIANTS = [
     {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1"},                      # 16x16x4 kernels at B > 32
