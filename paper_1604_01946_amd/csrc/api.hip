@@ -80,7 +80,7 @@ WsLayout ws_layout(const Dims& d) {
   w.dbpart = take(L * 64 * G * 4);
   w.scratch = take(8 * (size_t)d.B * G * 4);
   w.xchg = take(L * (size_t)d.T * G * Bp * 4);
-  w.flags = take((2 * L * ((size_t)d.T + 2) + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);
+  w.flags = take((2 * L * ((size_t)d.T + 2) * 256 + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);  // step counters, one KB each
   w.skpart = take(splitk_supported(d.H) ? L * splitk_partial_floats(d.H, d.B) * 4 : 0);
   w.skcnt = take(splitk_supported(d.H) ? L * ((size_t)d.T + 1) * splitk_counter_ints(d.H, d.B) * 4 : 0);
   w.resv = take(reserve_bytes(d));

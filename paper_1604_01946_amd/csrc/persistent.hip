@@ -70,23 +70,33 @@ struct BVec<4> {
 // needed per step either.  `full` (LSTM_FULL_FENCES=1) swaps both sides for the compiler's
 // agent-scope release / acquire fences (L2 write-back and invalidate on every step), which is
 // several times slower and exists to cross-check the fast protocol.
-constexpr int kFlagStride = 32;  // ints between the words of a split counter: one 128-byte line each
+// A step counter is split into kFlagSub words, each on a cache line of its own (kFlagStride ints
+// apart).  Agent-scope atomics from many workgroups on one line are served one after the other by the
+// memory side, about 25 ns each (6.4 us for 256 arrivals on one line, measured), so arrivals are spread
+// over the lines by slice index and a waiter reads all of them with one load (lane i reads word i).
+constexpr int kFlagStride = 32;
+constexpr int kFlagSub = 8;
+constexpr int kFlagInts = kFlagSub * kFlagStride;  // ints per counter
 
 struct Waiter {
   int* watchdog;  // host-visible word, set when a wait expires
   int limit;
   bool dead;
   int full;
-  // Non-blocking read of a counter; issue it early and hand the value to wait() later so that the
-  // round trip of the first poll overlaps other work.
+  // Non-blocking read of a counter (per lane: the arrivals on line lane, lanes >= kFlagSub report
+  // "enough"); issue it early and hand the value to wait() later so that the round trip of the first
+  // poll overlaps other work.
   static __device__ __forceinline__ int peek(int* flag) {
-    return __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int lane = threadIdx.x & 63;
+    return lane < kFlagSub ? __hip_atomic_load(flag + lane * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (1 << 30);
   }
-  // Waits until *flag >= target; `seen` is a value peeked earlier (pass 0 if none).
+  // Waits until `target` workgroups (a multiple of kFlagSub, spread evenly) have arrived; `seen` is a
+  // value peeked earlier (pass 0 if none, anything >= target to skip the wait).
   __device__ __forceinline__ void wait(int* flag, int target, int seen = 0) {
-    if (!dead && seen < target) {
+    const int each = target / kFlagSub;
+    if (!dead && !__all(seen >= each)) {
       int spins = 0;
-      while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      while (!__all(peek(flag) >= each)) {
         __builtin_amdgcn_s_sleep(1);
         if (++spins > limit) {
           dead = true;
@@ -97,10 +107,7 @@ struct Waiter {
     }
     acquire();
   }
-  // The same for a counter split into NSUB words, each on a cache line of its own (kFlagStride ints
-  // apart): agent-scope atomics from many workgroups on one line are served one after the other by
-  // the memory side, about 25 ns each (6.4 us for 256 arrivals, measured), so the arrivals are spread
-  // over NSUB lines and a waiter reads them all with one load per lane.
+  // The same for a counter split into NSUB lines with its own arrival count per line.
   template <int NSUB>
   __device__ __forceinline__ void wait_split(int* flags, int target_each) {
     if (!dead) {
@@ -270,7 +277,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   float* const res_h = res_l + TB * 5 * H;
   const size_t boff = (size_t)(wave * (H / 4) + q) * BP + NT * n;  // this lane's B-operand offset inside a slot
   auto slot = [&](int layer, int sl, int c) { return a.hx + (((size_t)layer * (T + 1) + sl) * NC + c) * H * BP; };
-  auto flag = [&](int layer, int sl, int c) { return a.flags + ((size_t)layer * (T + 1) + sl) * NC + c; };
+  auto flag = [&](int layer, int sl, int c) { return a.flags + (((size_t)layer * (T + 1) + sl) * NC + c) * kFlagInts; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -385,7 +392,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       if (threadIdx.x < 2 * BP)  // the slice's 8 rows are contiguous in the k-major exchange slot
         xstore4(slot(l, t + 1, c) + (size_t)u0 * BP + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
       if (c == 0) tr.mark(t, 5);
-      signal(flag(l, t + 1, c), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+      signal(flag(l, t + 1, c) + (s & (kFlagSub - 1)) * kFlagStride, a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
       if (c == 0) tr.mark(t, 6);
       // The reserve and the outputs are not read before the kernel ends, so they are written after
       // the signal -- staged through LDS so that each store instruction writes 16-byte runs
@@ -500,7 +507,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   float* const res_c = res_l + TB * 4 * H;
   float* const res_h = res_l + TB * 5 * H;
   auto slot = [&](int layer, int sl) { return a.hx + ((size_t)layer * (T + 1) + sl) * H * 64; };
-  auto flag = [&](int layer, int sl) { return a.flags + (size_t)layer * (T + 1) + sl; };
+  auto flag = [&](int layer, int sl) { return a.flags + ((size_t)layer * (T + 1) + sl) * kFlagInts; };
   const size_t boff = (size_t)wave * NK4 * 256 + lane * 4;  // this lane's offset inside a slot
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
@@ -548,7 +555,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     if (threadIdx.x < 128)  // the slice's 8 units are two contiguous 1 KB blocks of the exchange slot
       xstore4(slot(l, t + 1) + (size_t)(u0 / 4) * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
     tr.mark(t, 5);
-    signal(flag(l, t + 1), a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+    signal(flag(l, t + 1) + (s & (kFlagSub - 1)) * kFlagStride, a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
     tr.mark(t, 6);
     // The reserve and the outputs are not read before the kernel ends, so they are written after the
     // signal -- staged through LDS so that each store instruction writes 16-byte runs (scattered
@@ -692,7 +699,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       }
     }
     const bool more = t + 1 < T;
-    const bool pre = more && seen_in >= NS && !w.dead;
+    const bool pre = more && __all(seen_in >= NS / kFlagSub) && !w.dead;
     {
       const float* nsrc = slot(l - 1, pre ? t + 2 : t + 1) + boff;
 #pragma unroll
@@ -817,7 +824,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   float* const dx_out = a.dxbuf + (size_t)l * TB * H;
   const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
   auto slot = [&](int t, int c) { return a.dAx + (((size_t)l * T + t) * NC + c) * G * BP; };
-  auto flag = [&](int layer, int sl, int c) { return a.flags + ((size_t)layer * (T + 1) + sl) * NC + c; };
+  auto flag = [&](int layer, int sl, int c) { return a.flags + (((size_t)layer * (T + 1) + sl) * NC + c) * kFlagInts; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -898,7 +905,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         }
       }
       if (c == 0) tr.mark(t, 2);
-      signal(flag(l, t + 1, c), a.full_fences);
+      signal(flag(l, t + 1, c) + (s & (kFlagSub - 1)) * kFlagStride, a.full_fences);
       if (c == 0) tr.mark(t, 3);
       if (pw[c]) {
 #pragma unroll
@@ -963,7 +970,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   }
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    signal(flag(l, 0, c), a.full_fences);  // slot 0: dx of step 0 published
+    signal(flag(l, 0, c) + (s & (kFlagSub - 1)) * kFlagStride, a.full_fences);  // slot 0: dx of step 0 published
     if (pw[c]) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -1064,7 +1071,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
   float* const dx_out = a.dxbuf + (size_t)l * TB * H;
   auto slot = [&](int t) { return a.dAx + (((size_t)l * T + t) * NBH + bh) * G * 32; };
-  auto flag = [&](int layer, int sl) { return a.flags + ((size_t)layer * (T + 1) + sl) * NBH + bh; };
+  auto flag = [&](int layer, int sl) { return a.flags + (((size_t)layer * (T + 1) + sl) * NBH + bh) * kFlagInts; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -1139,7 +1146,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       }
     }
     tr.mark(t, 2);
-    signal(flag(l, t + 1), a.full_fences);
+    signal(flag(l, t + 1) + (s2 & (kFlagSub - 1)) * kFlagStride, a.full_fences);
     tr.mark(t, 3);
     if (pwv) {
 #pragma unroll
@@ -1212,7 +1219,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     }
     // `part` and `xs` are next written after the barriers of the next point-wise stage
   }
-  signal(flag(l, 0), a.full_fences);  // slot 0: dx of step 0 published
+  signal(flag(l, 0) + (s2 & (kFlagSub - 1)) * kFlagStride, a.full_fences);  // slot 0: dx of step 0 published
   if (pwv) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -1719,7 +1726,7 @@ int run_forward_persistent(const FwdArgs& a) {
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_FWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * 4, s), "zero step counters");
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * kFlagInts * 4, s), "zero step counters");
     if (wide) {
       const long n = (long)d.L * d.B * d.H;
       hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
@@ -1769,7 +1776,7 @@ int run_backward_persistent(const BwdArgs& a) {
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   {
     ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 2 * 4, s), "zero step counters");
+    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
   }
   PersBwdArgs k;
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
