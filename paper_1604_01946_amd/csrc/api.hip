@@ -79,8 +79,15 @@ WsLayout ws_layout(const Dims& d) {
   w.state = take(4 * L * d.B * H * 4);
   w.dbpart = take(L * 64 * G * 4);
   w.scratch = take(8 * (size_t)d.B * G * 4);
-  w.xchg = take(L * (size_t)d.T * G * Bp * 4);
-  w.flags = take((2 * L * ((size_t)d.T + 2) * 256 + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);  // step counters, one KB each
+  // persistent paths: exchange buffers (large-H backward: gate gradients and partial sums of one layer,
+  // 5 MB per step at H = 2048)
+  size_t xchg = L * (size_t)d.T * G * Bp * 4;
+  if (d.H == 2048 && d.B <= 32) {
+    const size_t nbk = d.H / 128, need = (size_t)d.T * (nbk * 4 * 128 * 32 + nbk * nbk * 128 * 32) * 4;
+    if (need > xchg) xchg = need;
+  }
+  w.xchg = take(xchg);
+  w.flags = take((2 * (L > 16 ? L : 16) * ((size_t)d.T + 2) * 256 + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);  // step counters, one KB each
   w.skpart = take(splitk_supported(d.H) ? L * splitk_partial_floats(d.H, d.B) * 4 : 0);
   w.skcnt = take(splitk_supported(d.H) ? L * ((size_t)d.T + 1) * splitk_counter_ints(d.H, d.B) * 4 : 0);
   w.resv = take(reserve_bytes(d));

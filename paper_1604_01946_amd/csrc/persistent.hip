@@ -1446,6 +1446,235 @@ __global__ void pack_stateL_kernel(const float* __restrict__ h0, float* __restri
   }
 }
 
+// ------------------------------------------------------------------ one layer, large hidden size, backward
+// dh_{t-1} = R^T dA_t has K = 4H, four times the forward product: slicing it by output units would make
+// every workgroup read all of dA_t (1 MB per step at H = 2048).  The [4H x H] matrix is therefore cut in
+// two dimensions, NBK x NBK tiles of [4*UB gate rows x UB output units] (UB = 128: 256 tiles of 256 KB,
+// half in VGPRs, half in LDS).  Workgroup (i, j) multiplies the gate gradients of unit block i into a
+// partial sum for the output units of block j; the NBK partial sums of a block are then added -- always
+// in the order of i, so the result does not depend on arrival order -- by the same NBK workgroups, each
+// taking 8 of the block's 128 units, which also run the point-wise stage of the next step for those 8
+// units and publish their gate gradients to the NBK workgroups (j, .) that consume unit block j.
+// Per step: 64 KB of dA read and 16 KB of partial sums written per workgroup, two synchronisation
+// hops of NBK arrivals each.  The gradient for the layer below is a batched GEMM after the launch.
+// Exchange layouts: dA_t of a unit block: [k8][(kk*32 + n)*4 + m] for k = 8*k8 + 2*m + kk, batch row n,
+// where k8 = 4*(unit/8 within the block) + gate and k%8 = unit%8; partial sums: [unit in block][32].
+struct PersBwdLArgs {
+  const float* R;      // [4H][H] of this layer
+  const float* res;    // reserve of this layer
+  const float* c0;     // [B][H] or null
+  const float* dout;   // [T][B][H]: dy (top layer) or the gradient handed down by the layer above
+  const float* dhT;    // [B][H] or null
+  const float* dcT;    // [B][H] or null
+  float* dA;           // [T][B][4H] gate gradients (standard layout)
+  float* X;            // [T][NBK][4*UB*32] exchange
+  float* Pp;           // [T][NBK][NBK][UB*32] partial sums
+  float* dh0;          // [B][H] or null
+  float* dc0;          // [B][H] or null
+  float* db;           // [4H] or null
+  int* flagsA;         // [T][NBK] counters: gate gradients of (step, unit block) published
+  int* flagsP;         // [T][NBK] counters: partial sums of (step, output block) published
+  int* watchdog;
+  int T, B;
+  int spin_limit;
+  int full_fences;
+  long long* trace;
+  int trace_block;
+};
+
+template <int HH>
+__global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
+  constexpr int H = HH, G = 4 * H, UB = 128, NBK = H / UB;
+  constexpr int NG8 = 4 * UB / 8;            // 8-k groups of the tile's K = 4*UB
+  constexpr int KP = 4 * UB / 2;             // k-pairs; every wave runs all of them for its 32 output units
+  constexpr int RP = 128, LP = KP - RP;      // k-pairs with weights in registers / in LDS
+  constexpr int DEPTH = 16;
+  static_assert(NBK % kFlagSub == 0, "arrivals must spread evenly over the counter lines");
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float* const stage = smem;        // [UB][32] partial sums of this step; also the bias-gradient reduction
+  float* const xsA = smem + 4096;   // [4 gates][256] gate gradients of the 8 finalised units, exchange order
+  float* const ro = smem + 5120;    // [4 gates][32 batch rows][8 units] the same in standard order
+  float* const wl = smem + 6144;    // [4 waves][LP][64 lanes]
+
+  const int i = blockIdx.x / NBK, j = blockIdx.x % NBK;
+  const int T = a.T, B = a.B;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kk = lane >> 5, n = lane & 31;
+  const size_t TB = (size_t)T * B;
+  const int rot = (4 * j + 16 * __builtin_amdgcn_readfirstlane(wave)) & (NG8 - 1);
+
+  // ---- weights: A operand row n = output unit UB*j + 32*wave + n; entry p covers
+  //      k = 8*k8 + 2*(p%4) + kk with k8 = (p/4 + rot) mod NG8: gate k8%4, unit UB*i + 8*(k8/4) + k%8
+  float wreg[RP];
+  {
+    const float* col = a.R + UB * j + 32 * wave + n;
+#pragma unroll
+    for (int p = 0; p < KP; ++p) {
+      const int k8 = ((p >> 2) + rot) & (NG8 - 1), m = p & 3;
+      const int unit = UB * i + 8 * (k8 >> 2) + 2 * m + kk;
+      const float v = col[((size_t)(k8 & 3) * H + unit) * H];
+      if (p < RP)
+        wreg[p < RP ? p : 0] = v;
+      else
+        wl[((size_t)wave * LP + (p - RP)) * 64 + lane] = v;
+    }
+  }
+
+  // ---- the cell this thread finalises: unit UB*j + 8*i + 2*wave + kk, batch row n
+  const int j8 = 2 * wave + kk;
+  const int cu = UB * j + 8 * i + j8;
+  const bool valid = n < B;
+  float dc = (valid && a.dcT) ? a.dcT[(size_t)n * H + cu] : 0.f;
+  float dh_rec = (valid && a.dhT) ? a.dhT[(size_t)n * H + cu] : 0.f;
+  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};
+  const float* const res_gates = a.res;
+  const float* const res_c = a.res + TB * 4 * H;
+  auto slotX = [&](int t, int blk) { return a.X + ((size_t)t * NBK + blk) * (4 * UB * 32); };
+  auto slotP = [&](int t, int jb, int ib) { return a.Pp + (((size_t)t * NBK + jb) * NBK + ib) * (UB * 32); };
+  auto flagA = [&](int t, int blk) { return a.flagsA + ((size_t)t * NBK + blk) * kFlagInts; };
+  auto flagP = [&](int t, int blk) { return a.flagsP + ((size_t)t * NBK + blk) * kFlagInts; };
+
+  // reserve values and upstream gradient of the step the point-wise stage handles next: fetched ahead,
+  // under the MFMAs, so that no miss to HBM sits in front of a counter poll (loads return in order)
+  float fg[4], fct, fcp, fdo;
+  auto fetch_step = [&](int t) {
+    if (valid) {
+      const size_t e = ((size_t)t * B + n) * H + cu;
+      const size_t g0 = ((size_t)t * B + n) * G + cu;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) fg[g] = res_gates[g0 + (size_t)g * H];
+      fct = res_c[e];
+      fcp = t > 0 ? res_c[e - (size_t)B * H] : (a.c0 ? a.c0[(size_t)n * H + cu] : 0.f);
+      fdo = a.dout[e];
+    }
+  };
+
+  Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
+  const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
+
+  // point-wise stage of step t for the 8 units of this workgroup, and publication of their gate gradients
+  auto pointwise_publish = [&](int t) {
+    float dA4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (valid) {
+      const float dh = fdo + dh_rec;
+      const float tc = tanhf(fct);
+      const float dcv = dc + dh * fg[2] * (1.f - tc * tc);
+      dA4[0] = dcv * fg[3] * fg[0] * (1.f - fg[0]);
+      dA4[1] = dcv * fcp * fg[1] * (1.f - fg[1]);
+      dA4[2] = dh * tc * fg[2] * (1.f - fg[2]);
+      dA4[3] = dcv * fg[0] * (1.f - fg[3] * fg[3]);
+      dc = dcv * fg[1];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) dbsum[g] += dA4[g];
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      xsA[g * 256 + (kk * 32 + n) * 4 + wave] = dA4[g];  // k%8 = j8 = 2*wave + kk: m = wave
+      ro[(g * 32 + n) * 8 + j8] = dA4[g];
+    }
+    __syncthreads();
+    xstore4(slotX(t, j) + (size_t)(4 * i) * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xsA + 4 * threadIdx.x));
+    signal(flagA(t, j) + (i & (kFlagSub - 1)) * kFlagStride, a.full_fences);
+    {  // standard layout for the weight-gradient products: (gate, batch row, half of the 8 units) per thread
+      const int g = threadIdx.x >> 6, b2 = (threadIdx.x >> 1) & 31, hf = threadIdx.x & 1;
+      if (b2 < B)
+        *reinterpret_cast<floatx4*>(a.dA + ((size_t)t * B + b2) * G + (size_t)g * H + UB * j + 8 * i + 4 * hf) =
+            *reinterpret_cast<const floatx4*>(ro + (g * 32 + b2) * 8 + 4 * hf);
+    }
+  };
+
+  __syncthreads();  // LDS weights are in place
+  fetch_step(T - 1);
+  pointwise_publish(T - 1);
+
+  int rv = rot;
+  for (int t = T - 1; t >= 0; --t) {
+    tr.mark(t, 0);
+    hide(rv);
+    w.wait(flagA(t, i), NBK);
+    tr.mark(t, 1);
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    {
+      const float* src = slotX(t, i) + lane * 4;
+      floatx4 bv[NG8];
+      float al[NG8][4];
+      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rv) & (NG8 - 1)) * 256); };
+      auto ldw = [&](int g) {
+        if (g * 4 >= RP) {
+#pragma unroll
+          for (int m = 0; m < 4; ++m) al[g][m] = wl[((size_t)wave * LP + (g * 4 + m - RP)) * 64 + lane];
+        }
+      };
+#pragma unroll
+      for (int g = 0; g < DEPTH; ++g) ldb(g);
+      ldw(0);
+      ldw(1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < NG8; ++g) {
+        if (g + DEPTH < NG8) ldb(g + DEPTH);
+        if (g + 2 < NG8) ldw(g + 2);
+        if (g == NG8 - DEPTH && t > 0) fetch_step(t - 1);  // behind the last exchange load of this step
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int pr = g * 4 + m;
+          const float av = (pr < RP) ? wreg[pr < RP ? pr : 0] : al[g][m];
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[g][m], acc, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // partial sums -> LDS (rows of the D layout) -> one coalesced, write-through 16 KB block
+#pragma unroll
+    for (int r = 0; r < 16; ++r) stage[(32 * wave + 8 * (r >> 2) + 4 * kk + (r & 3)) * 32 + n] = acc[r];
+    tr.mark(t, 2);
+    __syncthreads();
+    {
+      float* const dst = slotP(t, j, i);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int idx = threadIdx.x + 256 * q;
+        xstore4(dst + 4 * idx, *reinterpret_cast<const floatx4*>(stage + 4 * idx));
+      }
+    }
+    signal(flagP(t, j) + (i & (kFlagSub - 1)) * kFlagStride, a.full_fences);
+    tr.mark(t, 3);
+    w.wait(flagP(t, j), NBK);
+    tr.mark(t, 4);
+    {  // dh_rec of this thread's cell: the NBK partial sums in fixed order
+      float pv[NBK];
+#pragma unroll
+      for (int ib = 0; ib < NBK; ++ib) pv[ib] = slotP(t, j, ib)[(8 * i + j8) * 32 + n];
+      float sum = 0.f;
+#pragma unroll
+      for (int ib = 0; ib < NBK; ++ib) sum += pv[ib];
+      dh_rec = sum;
+    }
+    tr.mark(t, 5);
+    if (t > 0) pointwise_publish(t - 1);
+    tr.mark(t, 6);
+  }
+  if (valid) {
+    if (a.dh0) a.dh0[(size_t)n * H + cu] = dh_rec;
+    if (a.dc0) a.dc0[(size_t)n * H + cu] = dc;
+  }
+  if (a.db) {  // this workgroup owns its 8 units for every batch row: plain sums, no atomics
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < 4; ++g) stage[(g * 8 + j8) * 32 + n] = dbsum[g];
+    __syncthreads();
+    if (threadIdx.x < 32) {
+      float sum = 0.f;
+#pragma unroll
+      for (int q = 0; q < 32; ++q) sum += stage[threadIdx.x * 32 + q];
+      a.db[(size_t)(threadIdx.x >> 3) * H + UB * j + 8 * i + (threadIdx.x & 7)] = sum;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ host state
 struct DeviceInfo {
   bool ok = false;
@@ -1630,13 +1859,13 @@ void release_persistent() {
 
 // Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
 bool persistent_large(const Dims& d, bool backward) {
-  if (backward) return false;  // the backward pass of these shapes runs on the step path
   const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");
   if (e && *e == '1') return false;
-  if (!(d.H == 1024 || d.H == 2048) || d.B > 32) return false;
+  if (d.B > 32) return false;
+  if (backward ? d.H != 2048 : !(d.H == 1024 || d.H == 2048)) return false;  // H = 1024 backward: step / wavefront path
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
-  return d.H / 8 <= di.cus;
+  return (backward ? (d.H / 128) * (d.H / 128) : d.H / 8) <= di.cus;
 }
 
 bool persistent_supported(const Dims& d, bool backward) {
@@ -1705,6 +1934,77 @@ int run_forward_persistent_large(const FwdArgs& a) {
   return LSTM_OK;
 }
 
+template <int HH>
+hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
+  constexpr int NBK = HH / 128, LP = 128;
+  const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
+  const void* fn = (const void*)pers_bwdL_kernel<HH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  void* params[] = {const_cast<PersBwdLArgs*>(&a)};
+  return launch_resident(fn, NBK * NBK, params, (unsigned)smem, s);
+}
+
+}  // namespace
+
+int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done);
+
+namespace {
+
+// Backward pass of the large-H shapes: per layer (top down) one persistent launch for the recurrence, then
+// the batched product that hands the gradient to the layer below; weight gradients at the end.
+int run_backward_persistent_large(const BwdArgs& a) {
+  const Dims& d = a.d;
+  constexpr int UB = 128;
+  const int NBK = d.H / UB;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
+  hipStream_t s = a.stream;
+  float* dA_all = reinterpret_cast<float*>(a.ws + a.w.P);
+  float* dxb = reinterpret_cast<float*>(a.ws + a.w.dx);
+  float* X = reinterpret_cast<float*>(a.ws + a.w.xchg);
+  float* Pp = X + (size_t)d.T * NBK * (4 * UB * 32);
+  int* flagsA = reinterpret_cast<int*>(a.ws + a.w.flags);
+  int* flagsP = flagsA + (size_t)d.T * NBK * kFlagInts;
+  for (int l = d.L - 1; l >= 0; --l) {
+    const int Il = in_dim(d, l);
+    float* dA = dA_all + (size_t)l * TB * G;
+    {
+      ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+      CK(launch_fill_zero(flagsA, (size_t)2 * d.T * NBK * kFlagInts * 4, s), "zero step counters");
+    }
+    PersBwdLArgs k;
+    k.R = a.R + (size_t)l * G * d.H;
+    k.res = a.reserve + (size_t)l * TB * 6 * d.H;
+    k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
+    k.dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * d.H;
+    k.dhT = a.dhT ? a.dhT + (size_t)l * BH : nullptr;
+    k.dcT = a.dcT ? a.dcT + (size_t)l * BH : nullptr;
+    k.dA = dA; k.X = X; k.Pp = Pp;
+    k.dh0 = a.dh0 ? a.dh0 + (size_t)l * BH : nullptr;
+    k.dc0 = a.dc0 ? a.dc0 + (size_t)l * BH : nullptr;
+    k.db = a.db + (size_t)l * G;
+    k.flagsA = flagsA; k.flagsP = flagsP; k.watchdog = g_watch_dev;
+    k.T = d.T; k.B = d.B; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+    k.trace_block = g_trace_block;
+    {
+      ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+      CK(launch_bwdL<2048>(k, s), "persistent backward launch (large H)");
+    }
+    float* din = l > 0 ? dxb + (size_t)l * TB * d.H : a.dx;
+    if (din) {
+      ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
+      GemmProblem p{dA, a.W + w_offset(d, l), din, (int)TB, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
+      CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
+    }
+  }
+  return weight_gradients(a, dA_all, true, true);
+}
+
 }  // namespace
 
 int run_forward_persistent(const FwdArgs& a) {
@@ -1762,10 +2062,13 @@ int run_forward_persistent(const FwdArgs& a) {
   return LSTM_OK;
 }
 
-int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done);
-
 int run_backward_persistent(const BwdArgs& a) {
   const Dims& d = a.d;
+  if (persistent_large(d, true)) {
+    if (!ensure_watchdog()) return LSTM_HIP_ERROR;
+    if (*g_watch_host) return LSTM_INTERNAL;
+    return run_backward_persistent_large(a);
+  }
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
