@@ -248,7 +248,7 @@ def test_null_optionals_and_inference():
 
 
 # ------------------------------------------------------------------ determinism (doubles as a race detector)
-@pytest.mark.parametrize("name", ["cfg1", "cfg3"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg3", "cfg4", "cfg5"])
 def test_bitwise_repeatable(name):
     torch, binding, runner = _mods()
     cfg = CONFIGS[name]
