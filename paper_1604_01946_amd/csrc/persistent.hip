@@ -199,6 +199,8 @@ struct PersFwdArgs {
   float* hT;
   float* cT;
   int L, T, B, I, H;
+  int b0;             // wide kernel: first batch row of this launch (a multiple of 64)
+  int nsl;            // wide kernel: batch slices of 64 rows that run side by side in this launch (grid = nsl * L * H/8)
   int has_h0;
   int spin_limit;
   int full_fences;
@@ -460,8 +462,13 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   __shared__ __attribute__((aligned(16))) float xs[512];  // this step's h slice in exchange order
   __shared__ __attribute__((aligned(16))) float ro[6 * 64 * 8];  // gates, c, h of the slice: [array][batch][unit]
 
+  // The recurrences of different batch rows are independent: slices of 64 rows run side by side as
+  // separate groups of workgroups with their own exchange slots and counters.
   int l, s;
-  map_block(a.L, NS, l, s);
+  map_block(a.L, NS * a.nsl, l, s);
+  const int sl = s / NS;
+  s -= sl * NS;
+  const int b0 = a.b0 + 64 * sl;
   const int T = a.T, B = a.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kk = lane >> 5, n = lane & 31;
@@ -490,7 +497,8 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   // ---- the two cells this lane finalises: wave w takes batch tile j = w%2 and unit pair up = w/2;
   //      D register r of a lane is row 8*(r/4) + 4*kk + r%4 = (gate r/4, unit 4*kk + r%4)
   const int tj = wave & 1, up = wave >> 1;
-  const int bb = 2 * n + tj;
+  const int lb = 2 * n + tj;   // batch row inside this launch's 64
+  const int bb = b0 + lb;      // batch row in the tensors
   const bool valid = bb < B;
   int c_unit[2];
   float c_state[2], c_bias[2][4];
@@ -506,8 +514,10 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   float* const res_gates = res_l;
   float* const res_c = res_l + TB * 4 * H;
   float* const res_h = res_l + TB * 5 * H;
-  auto slot = [&](int layer, int sl) { return a.hx + ((size_t)layer * (T + 1) + sl) * H * 64; };
-  auto flag = [&](int layer, int sl) { return a.flags + ((size_t)layer * (T + 1) + sl) * kFlagInts; };
+  float* const hx = a.hx + (size_t)sl * a.L * (T + 1) * H * 64;
+  int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * kFlagInts;
+  auto slot = [&](int layer, int st) { return hx + ((size_t)layer * (T + 1) + st) * H * 64; };
+  auto flag = [&](int layer, int st) { return flags + ((size_t)layer * (T + 1) + st) * kFlagInts; };
   const size_t boff = (size_t)wave * NK4 * 256 + lane * 4;  // this lane's offset inside a slot
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
@@ -564,17 +574,18 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     for (int ci = 0; ci < 2; ++ci) {
       const int ul = 4 * kk + 2 * up + ci;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) ro[(g * 64 + bb) * 8 + ul] = o_gate[ci][g];
-      ro[(4 * 64 + bb) * 8 + ul] = o_c[ci];
-      ro[(5 * 64 + bb) * 8 + ul] = o_h[ci];
+      for (int g = 0; g < 4; ++g) ro[(g * 64 + lb) * 8 + ul] = o_gate[ci][g];
+      ro[(4 * 64 + lb) * 8 + ul] = o_c[ci];
+      ro[(5 * 64 + lb) * 8 + ul] = o_h[ci];
     }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
       const int idx = threadIdx.x + 256 * i;  // (array 0..5, batch row, half of the 8 units)
-      const int arr = idx >> 7, b2 = (idx >> 1) & 63, hf = idx & 1;
+      const int arr = idx >> 7, l2 = (idx >> 1) & 63, hf = idx & 1;
+      const int b2 = b0 + l2;
       if (b2 < B) {
-        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + b2) * 8 + 4 * hf);
+        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
           *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
@@ -720,12 +731,16 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
 }
 
 // h0 [L][B][H] (zeros if null) -> exchange slot 0 of every layer in the layout of pers_fwd32_kernel.
-__global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H) {
-  const long cnt = (long)L * B * H;
+__global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H, int b0,
+                                    int nsl) {
+  const long cnt = (long)nsl * L * 64 * H;  // all 64 batch columns of every slot: rows past the batch hold zeros
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
-    const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
-    const int k4 = k >> 2, m = (k >> 1) & 1, kk = k & 1, n = bb >> 1, j = bb & 1;
-    hx[((size_t)l * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] = h0 ? h0[e] : 0.f;
+    const int k = (int)(e % H), lb = (int)((e / H) % 64), l = (int)((e / ((long)H * 64)) % L);
+    const int sl = (int)(e / ((long)H * 64 * L));
+    const int k4 = k >> 2, m = (k >> 1) & 1, kk = k & 1, n = lb >> 1, j = lb & 1;
+    const int bb = b0 + 64 * sl + lb;
+    hx[(((size_t)sl * L + l) * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] =
+        (h0 && bb < B) ? h0[((size_t)l * B + bb) * H + k] : 0.f;
   }
 }
 
@@ -758,6 +773,7 @@ struct PersBwdArgs {
   int* flags;          // [L][T+1][NC]
   int* watchdog;
   int L, T, B, I, H;
+  int b0;              // wide kernel: first batch row of this launch (a multiple of 64)
   int spin_limit;
   int full_fences;
   long long* trace;
@@ -1048,7 +1064,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
 
   // ---- roles: waves 0,1 run the point-wise stage on units u0 + 8*wave + 4*kk + {0..3};
   //      waves 2,3 publish dx of units u0 + 8*(wave-2) + 4*kk + {0..3}; batch row bh*32 + n
-  const int bb = bh * 32 + n;
+  const int bb = a.b0 + bh * 32 + n;  // batch row in the tensors; the exchange slots hold this launch's 64 rows
   const bool pwv = wave < 2 && bb < B;
   const bool dxl = wave >= 2 && bb < B && l > 0;
   const int unit0 = u0 + 8 * (wave & 1) + 4 * kk;
@@ -1799,9 +1815,10 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
 
 // The wide-batch forward kernel (32x32x2 MFMA, two batch tiles of 32).
 bool fwd_wide(const Dims& d) {
+  if (d.B > 64) return true;  // batches above 64 run as slices of 64 rows, one launch each
   const char* e = getenv("LSTM_FWD_NARROW");
   if (e && *e == '1') return false;
-  return d.B > 32 && d.B <= 64;
+  return d.B > 32;
 }
 
 hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
@@ -1813,13 +1830,14 @@ hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
 
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
 bool bwd_wide(const Dims& d) {
+  if (d.B > 64) return true;
   const char* e = getenv("LSTM_BWD_NARROW");
   if (e && *e == '1') return false;
-  return d.B > 32 && d.B <= 64;
+  return d.B > 32;
 }
 
 template <int HH>
-hipError_t launch_bwd32(const PersBwdArgs& a, hipStream_t s) {
+hipError_t launch_bwd32(const PersBwdArgs& a, int nbh, hipStream_t s) {
   constexpr int KPW = HH / 2, LP = KPW > 128 ? KPW - 128 : 0;
   const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
   const void* fn = (const void*)pers_bwd32_kernel<HH>;
@@ -1829,7 +1847,6 @@ hipError_t launch_bwd32(const PersBwdArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  int nbh = 2;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
   const int grid = a.L * (HH / 16) * nbh;
   return launch_resident(fn, grid, params, (unsigned)smem, s);
@@ -1871,7 +1888,7 @@ bool persistent_large(const Dims& d, bool backward) {
 bool persistent_supported(const Dims& d, bool backward) {
   if (persistent_large(d, backward)) return true;
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
-  if (d.B > 64) return false;
+  if (d.B > 512) return false;  // above 64 rows the batch is processed in slices of 64, one launch per slice
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return (long)d.L * (d.H / 8) <= di.cus;
@@ -2025,21 +2042,6 @@ int run_forward_persistent(const FwdArgs& a) {
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
   {
-    ProfScope ps(LSTM_PHASE_FWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * bp.NC * kFlagInts * 4, s), "zero step counters");
-    if (wide) {
-      const long n = (long)d.L * d.B * d.H;
-      hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
-                         d.H);
-      CK(hipGetLastError(), "pack h0");
-    } else if (a.h0) {
-      const long n = (long)d.L * d.B * d.H;
-      hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
-                         d.H, BP, bp.NC);
-      CK(hipGetLastError(), "pack h0");
-    }
-  }
-  {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
     GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
     CK(launch_gemm_group(&p, 1, s), "input projection GEMM (layer 0)");
@@ -2052,13 +2054,40 @@ int run_forward_persistent(const FwdArgs& a) {
   k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
-  ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
-  hipError_t e = hipErrorInvalidValue;
-  if (wide) e = launch_fwd32(d.H, grid, k, s);
-  else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
-  else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
-  else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
-  CK(e, "persistent forward launch");
+  // Slices of 64 batch rows run side by side in one launch while the CUs last, the rest in further launches.
+  DeviceInfo di;
+  (void)device_info(di);
+  int cap = wide && grid > 0 ? di.cus / grid : 1;
+  if (cap > 16 / d.L) cap = 16 / d.L;  // the counter region holds 16 (slice, layer) pairs
+  if (cap < 1) cap = 1;
+  const int slices = wide ? (d.B + 63) / 64 : 1;
+  for (int s0 = 0; s0 < slices; s0 += cap) {
+    const int nsl = slices - s0 < cap ? slices - s0 : cap;
+    k.b0 = 64 * s0;
+    k.nsl = nsl;
+    {
+      ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+      CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * bp.NC * kFlagInts * 4, s), "zero step counters");
+      if (wide) {
+        const long n = (long)nsl * d.L * 64 * d.H;
+        hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T,
+                           d.B, d.H, k.b0, nsl);
+        CK(hipGetLastError(), "pack h0");
+      } else if (a.h0) {
+        const long n = (long)d.L * d.B * d.H;
+        hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
+                           d.H, BP, bp.NC);
+        CK(hipGetLastError(), "pack h0");
+      }
+    }
+    ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    hipError_t e = hipErrorInvalidValue;
+    if (wide) e = launch_fwd32(d.H, grid * nsl, k, s);
+    else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
+    else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
+    else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
+    CK(e, "persistent forward launch");
+  }
   return LSTM_OK;
 }
 
@@ -2077,16 +2106,12 @@ int run_backward_persistent(const BwdArgs& a) {
   const bool wide = bwd_wide(d);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
-  {
-    ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-    CK(launch_fill_zero(flags, (size_t)d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
-  }
   PersBwdArgs k;
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
   k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
   k.db = nullptr;
-  if (wide && a.db) {  // the wide kernel adds the bias gradient into db itself
+  if (wide && a.db && d.B <= 64) {  // one launch: the wide kernel adds the bias gradient into db itself (two addends per element)
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
     CK(launch_fill_zero(a.db, (size_t)d.L * G * 4, s), "zero db");
     k.db = a.db;
@@ -2095,12 +2120,26 @@ int run_backward_persistent(const BwdArgs& a) {
   k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
-  {
+  // slices of 64 batch rows side by side while the CUs last (see run_forward_persistent): for the wide kernel a
+  // slice is two more "batch halves" of 32 rows with their own exchange slots and counters
+  DeviceInfo di;
+  (void)device_info(di);
+  int cap = wide && grid > 0 ? di.cus / grid : 1;
+  if (cap > 16 / d.L) cap = 16 / d.L;
+  if (cap < 1) cap = 1;
+  const int slices = wide ? (d.B + 63) / 64 : 1;
+  for (int s0 = 0; s0 < slices; s0 += cap) {
+    const int nsl = slices - s0 < cap ? slices - s0 : cap;
+    k.b0 = 64 * s0;
+    {
+      ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+      CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
+    }
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (wide && d.H == 512) e = launch_bwd32<512>(k, s);
-    else if (wide && d.H == 256) e = launch_bwd32<256>(k, s);
-    else if (wide && d.H == 128) e = launch_bwd32<128>(k, s);
+    if (wide && d.H == 512) e = launch_bwd32<512>(k, 2 * nsl, s);
+    else if (wide && d.H == 256) e = launch_bwd32<256>(k, 2 * nsl, s);
+    else if (wide && d.H == 128) e = launch_bwd32<128>(k, 2 * nsl, s);
     else if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
     else if (d.H == 256) e = launch_bwd<64>(bp, grid, k, s);
     else if (d.H == 128) e = launch_bwd<32>(bp, grid, k, s);

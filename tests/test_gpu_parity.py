@@ -126,6 +126,10 @@ PERS = [
     Config("p512b33", L=2, T=5, B=33, I=72, H=512, state_std=0.3, dstate_std=0.3),
     Config("p512b64", L=4, T=7, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),
     Config("p512L1", L=1, T=9, B=48, I=512, H=512, state_std=0.3, dstate_std=0.3),
+    # batches above 64 rows run as slices of 64, one launch per slice (full, ragged and nearly empty last slice)
+    Config("p512b128", L=2, T=4, B=128, I=64, H=512, state_std=0.3, dstate_std=0.3),
+    Config("p256b130", L=3, T=3, B=130, I=256, H=256, state_std=0.3, dstate_std=0.3),
+    Config("p128b65", L=2, T=3, B=65, I=24, H=128, state_std=0.3, dstate_std=0.3),
 ]
 
 
