@@ -130,6 +130,8 @@ PERS = [
     Config("p512b128", L=2, T=4, B=128, I=64, H=512, state_std=0.3, dstate_std=0.3),
     Config("p256b130", L=3, T=3, B=130, I=256, H=256, state_std=0.3, dstate_std=0.3),
     Config("p128b65", L=2, T=3, B=65, I=24, H=128, state_std=0.3, dstate_std=0.3),
+    Config("p128b512", L=1, T=2, B=512, I=16, H=128, state_std=0.3, dstate_std=0.3),   # 8 slices side by side
+    Config("p512T1", L=4, T=1, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),     # a single step
 ]
 
 
@@ -148,6 +150,8 @@ LARGE = [
     Config("l1024b7", L=1, T=4, B=7, I=1024, H=1024, state_std=0.3, dstate_std=0.3),
     Config("l2048b32", L=2, T=4, B=32, I=256, H=2048, state_std=0.3, dstate_std=0.3),
     Config("l2048b5", L=1, T=3, B=5, I=64, H=2048, state_std=0.3, dstate_std=0.3),
+    Config("l2048T1", L=2, T=1, B=1, I=2048, H=2048, state_std=0.3, dstate_std=0.3),   # a single step, a single row
+    Config("l1024T1", L=1, T=1, B=32, I=16, H=1024, state_std=0.3, dstate_std=0.3),
 ]
 
 
