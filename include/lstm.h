@@ -132,6 +132,16 @@ int lstm_gemm_f32(int M, int N, int K,
 unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward);
 
 /*
+ * Overrides what LSTM_PATH_AUTO resolves to for one shape and direction (Sections 2.3 and 3.2: whether
+ * a strategy pays depends on the hidden size, the minibatch and the number of layers, and choosing is
+ * "not trivial"; a caller, or the bundled autotuner, can measure and pin the choice).  `path` is an
+ * LSTM_PATH_* value; LSTM_PATH_AUTO removes the override.  Host-side table, thread-safe, emptied by
+ * lstm_shutdown.  Returns LSTM_OK, LSTM_INVALID_ARG (non-positive dimension, unknown path) or
+ * LSTM_UNSUPPORTED (the path does not take this shape on the current device).
+ */
+int lstm_set_path(int L, int T, int B, int I, int H, int backward, unsigned path);
+
+/*
  * Phase timing for measurement (Section 2.5 reports time per optimisation stage; this is the
  * same breakdown taken live).  While enabled, lstm_forward / lstm_backward record HIP events
  * on the stream each phase is launched on, at the phase's first and last launch.

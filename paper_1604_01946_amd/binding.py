@@ -30,7 +30,7 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
-    "lstm_auto_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
+    "lstm_auto_path", "lstm_set_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
     "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name", "lstm_debug_set_trace",
 ]
 LSTM_PHASE_COUNT = 8
@@ -63,6 +63,8 @@ def library():
         lib.lstm_gemm_f32.argtypes = [i, i, i, p, l, l, p, l, l, p, l, i, p]
         lib.lstm_auto_path.restype = u
         lib.lstm_auto_path.argtypes = [i] * 6
+        lib.lstm_set_path.restype = i
+        lib.lstm_set_path.argtypes = [i] * 6 + [u]
         lib.lstm_status_string.restype = ctypes.c_char_p
         lib.lstm_status_string.argtypes = [i]
         lib.lstm_last_error.restype = ctypes.c_char_p
@@ -121,6 +123,10 @@ def lstm_shutdown():
 
 def lstm_auto_path(L, T, B, I, H, backward):
     return library().lstm_auto_path(L, T, B, I, H, int(backward))
+
+
+def lstm_set_path(L, T, B, I, H, backward, path):
+    return library().lstm_set_path(L, T, B, I, H, int(backward), int(path))
 
 
 def lstm_forward(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, workspace, workspace_bytes,

@@ -123,7 +123,10 @@ const char* lstm_status_string(int status) {
 
 const char* lstm_last_error(void) { return g_last_error.c_str(); }
 
-void lstm_shutdown(void) { release_helpers(); }
+void lstm_shutdown(void) {
+  release_helpers();
+  clear_path_overrides();
+}
 
 void lstm_debug_set_trace(void* device_buf, size_t bytes, int block) { set_trace(device_buf, bytes, block); }
 
@@ -163,6 +166,11 @@ const char* lstm_phase_name(int phase) {
 unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward) {
   if (!dims_ok(L, T, B, I, H)) return LSTM_PATH_AUTO;
   return resolve_auto_path(Dims{L, T, B, I, H}, backward != 0);
+}
+
+int lstm_set_path(int L, int T, int B, int I, int H, int backward, unsigned path) {
+  if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
+  return set_path_override(Dims{L, T, B, I, H}, backward != 0, path);
 }
 
 int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const float* B, long sBk, long sBn,

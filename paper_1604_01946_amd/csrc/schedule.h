@@ -48,6 +48,8 @@ struct BwdArgs {
 size_t reserve_bytes(const Dims& d);
 WsLayout ws_layout(const Dims& d);
 unsigned resolve_auto_path(const Dims& d, bool backward);
+int set_path_override(const Dims& d, bool backward, unsigned path);  // LSTM_PATH_AUTO removes the entry
+void clear_path_overrides();
 int run_forward(const FwdArgs& a, unsigned path);
 int run_backward(const BwdArgs& a, unsigned path);
 void release_helpers();

@@ -12,6 +12,9 @@
 #include "../../include/lstm.h"
 #include "schedule.h"
 
+#include <mutex>
+#include <vector>
+
 namespace lstm {
 
 #define CK(expr, what)                                             \
@@ -27,7 +30,50 @@ bool persistent_supported(const Dims& d, bool backward);
 
 int device_cu_count();
 
+// Per-shape overrides of the automatic choice (lstm_set_path), a few entries, guarded by a mutex.
+namespace {
+struct PathOverride {
+  Dims d;
+  bool backward;
+  unsigned path;
+};
+std::mutex g_path_mu;
+std::vector<PathOverride> g_path_table;
+bool same_shape(const Dims& a, const Dims& b) { return a.L == b.L && a.T == b.T && a.B == b.B && a.I == b.I && a.H == b.H; }
+}  // namespace
+
+bool path_takes_shape(const Dims& d, bool backward, unsigned path) {
+  switch (path) {
+    case LSTM_PATH_NAIVE: case LSTM_PATH_GROUPED: case LSTM_PATH_FUSED: case LSTM_PATH_STEP: case LSTM_PATH_WAVEFRONT: return true;
+    case LSTM_PATH_PERSISTENT: return persistent_supported(d, backward);
+    default: return false;
+  }
+}
+
+int set_path_override(const Dims& d, bool backward, unsigned path) {
+  if (path != LSTM_PATH_AUTO && !path_takes_shape(d, backward, path)) return path > LSTM_PATH_PERSISTENT ? LSTM_INVALID_ARG : LSTM_UNSUPPORTED;
+  std::lock_guard<std::mutex> lk(g_path_mu);
+  for (size_t i = 0; i < g_path_table.size(); ++i)
+    if (same_shape(g_path_table[i].d, d) && g_path_table[i].backward == backward) {
+      if (path == LSTM_PATH_AUTO) g_path_table.erase(g_path_table.begin() + (long)i);
+      else g_path_table[i].path = path;
+      return LSTM_OK;
+    }
+  if (path != LSTM_PATH_AUTO) g_path_table.push_back(PathOverride{d, backward, path});
+  return LSTM_OK;
+}
+
+void clear_path_overrides() {
+  std::lock_guard<std::mutex> lk(g_path_mu);
+  g_path_table.clear();
+}
+
 unsigned resolve_auto_path(const Dims& d, bool backward) {
+  {
+    std::lock_guard<std::mutex> lk(g_path_mu);
+    for (const PathOverride& o : g_path_table)
+      if (same_shape(o.d, d) && o.backward == backward) return o.path;
+  }
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
   // Overlapping layers on streams pays when one step kernel leaves CUs idle (Section 2.4: the
   // gain is largest for small layers); a step that already fills the chip runs layer by layer.

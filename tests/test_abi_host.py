@@ -79,3 +79,21 @@ def test_gemm_rejects_bad_arguments():
 def test_auto_path_is_a_valid_path():
     assert B.lstm_auto_path(0, 1, 1, 1, 1, 0) == B.LSTM_PATH_AUTO
     assert B.lstm_auto_path(1, 8, 4, 32, 32, 1) in (B.LSTM_PATH_STEP, B.LSTM_PATH_WAVEFRONT, B.LSTM_PATH_PERSISTENT)
+
+
+def test_set_path_overrides_and_validates():
+    dims = (2, 8, 4, 32, 32)
+    auto = B.lstm_auto_path(*dims, 0)
+    assert B.lstm_set_path(0, 8, 4, 32, 32, 0, B.LSTM_PATH_STEP) == B.LSTM_INVALID_ARG
+    assert B.lstm_set_path(*dims, 0, 99) == B.LSTM_INVALID_ARG
+    # H = 32 is not a shape of the persistent kernels on any device
+    assert B.lstm_set_path(*dims, 0, B.LSTM_PATH_PERSISTENT) == B.LSTM_UNSUPPORTED
+    other = B.LSTM_PATH_STEP if auto != B.LSTM_PATH_STEP else B.LSTM_PATH_WAVEFRONT
+    assert B.lstm_set_path(*dims, 0, other) == B.LSTM_OK
+    assert B.lstm_auto_path(*dims, 0) == other
+    assert B.lstm_auto_path(*dims, 1) == B.lstm_auto_path(2, 8, 4, 32, 32, 1)  # the other direction is untouched
+    assert B.lstm_set_path(*dims, 0, B.LSTM_PATH_AUTO) == B.LSTM_OK
+    assert B.lstm_auto_path(*dims, 0) == auto
+    assert B.lstm_set_path(*dims, 1, other) == B.LSTM_OK
+    B.lstm_shutdown()  # empties the table
+    assert B.lstm_auto_path(*dims, 1) == B.lstm_auto_path(*dims, 1)

@@ -292,3 +292,20 @@ def test_split_T_chaining_on_gpu():
     y12 = torch.cat([r1.y, r2.y])
     assert float((y12 - full.y).abs().max()) < 1e-5
     assert float((r2.hT - full.hT).abs().max()) < 1e-5
+
+
+# ------------------------------------------------------------------ autotuner
+def test_autotune_pins_a_path_and_results_stay_right():
+    _, binding, _ = _mods()
+    from paper_1604_01946_amd import autotune
+    cfg = Config("tune", L=2, T=6, B=40, I=128, H=128, state_std=0.3, dstate_std=0.3)
+    try:
+        r = autotune.tune(*cfg.dims, iters=2)
+        assert set(r["forward"]) >= {"step", "wavefront"} and set(r["backward"]) >= {"step", "wavefront"}
+        names = {v: k for k, v in binding.PATH_NAMES.items()}
+        assert binding.lstm_auto_path(*cfg.dims, 0) == names[r["best"][0]]
+        assert binding.lstm_auto_path(*cfg.dims, 1) == names[r["best"][1]]
+        run_case(cfg, 5, 0)
+    finally:
+        binding.lstm_set_path(*cfg.dims, 0, binding.LSTM_PATH_AUTO)
+        binding.lstm_set_path(*cfg.dims, 1, binding.LSTM_PATH_AUTO)
