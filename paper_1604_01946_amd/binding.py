@@ -33,6 +33,9 @@ EXPORTS = [
     "lstm_auto_path", "lstm_set_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
     "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name", "lstm_debug_set_trace",
 ]
+RNN_EXPORTS = ["rnn_reserve_bytes", "rnn_workspace_bytes", "rnn_forward", "rnn_backward"]
+RNN_CELL_RELU, RNN_CELL_TANH, RNN_CELL_GRU = 0, 1, 2
+RNN_CELLS = {"relu": RNN_CELL_RELU, "tanh": RNN_CELL_TANH, "gru": RNN_CELL_GRU}
 LSTM_PHASE_COUNT = 8
 
 _lib = None
@@ -79,6 +82,14 @@ def library():
         lib.lstm_phase_name.argtypes = [i]
         lib.lstm_debug_set_trace.restype = None
         lib.lstm_debug_set_trace.argtypes = [p, z, i]
+        lib.rnn_reserve_bytes.restype = z
+        lib.rnn_reserve_bytes.argtypes = [i] * 6
+        lib.rnn_workspace_bytes.restype = z
+        lib.rnn_workspace_bytes.argtypes = [i] * 6
+        lib.rnn_forward.restype = i
+        lib.rnn_forward.argtypes = [i] * 6 + [p] * 9 + [z, p]
+        lib.rnn_backward.restype = i
+        lib.rnn_backward.argtypes = [i] * 6 + [p] * 13 + [z, p]
         _lib = lib
     return _lib
 
@@ -103,6 +114,26 @@ def _stream(stream):
 
 def lstm_reserve_bytes(L, T, B, I, H):
     return library().lstm_reserve_bytes(L, T, B, I, H)
+
+
+def rnn_reserve_bytes(cell, L, T, B, I, H):
+    return library().rnn_reserve_bytes(cell, L, T, B, I, H)
+
+
+def rnn_workspace_bytes(cell, L, T, B, I, H):
+    return library().rnn_workspace_bytes(cell, L, T, B, I, H)
+
+
+def rnn_forward(cell, L, T, B, I, H, x, h0, W, R, b, y, hT, reserve, workspace, workspace_bytes, stream=None):
+    return library().rnn_forward(cell, L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(W), _ptr(R), _ptr(b), _ptr(y), _ptr(hT),
+                                 _ptr(reserve), _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def rnn_backward(cell, L, T, B, I, H, x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, workspace, workspace_bytes,
+                 stream=None):
+    return library().rnn_backward(cell, L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(W), _ptr(R), _ptr(reserve), _ptr(dy),
+                                  _ptr(dhT), _ptr(dx), _ptr(dh0), _ptr(dW), _ptr(dR), _ptr(db), _ptr(workspace),
+                                  workspace_bytes, _stream(stream))
 
 
 def lstm_workspace_bytes(L, T, B, I, H):

@@ -1,0 +1,263 @@
+// Single-gate RNN (ReLU / tanh) and GRU on the cell-independent rungs of the ladder of
+// arXiv 1604.01946: input products batched over time (Section 2.3), the gates of a step grouped into
+// one recurrent product (Section 2.1; the GRU's three), one fused point-wise kernel per step
+// (Section 2.2.2), weight gradients as large products after propagation (Section 2.6).
+#include "../../include/lstm.h"
+#include "../../include/rnn.h"
+#include "schedule.h"
+
+namespace lstm {
+
+#define CK(expr, what)                                             \
+  do {                                                             \
+    if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
+  } while (0)
+
+namespace {
+
+inline int gates_of(int cell) { return cell == RNN_CELL_GRU ? 3 : ((cell == RNN_CELL_RELU || cell == RNN_CELL_TANH) ? 1 : 0); }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Forward point-wise stage of one step: P = W x_t (without bias), Q = R h_{t-1}, both [B][G].
+// GRU saves r, z, n and Q_n for the backward pass (sv: [B][4H]).
+__global__ void cell_fwd_kernel(int cell, const float* __restrict__ P, const float* __restrict__ Q,
+                                const float* __restrict__ bias, const float* __restrict__ hp, float* __restrict__ h,
+                                float* __restrict__ y, float* __restrict__ sv, int B, int H) {
+  const long cnt = (long)B * H;
+  const int G = (cell == RNN_CELL_GRU ? 3 : 1) * H;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
+    const int u = (int)(e % H);
+    const long row = e / H;
+    const float* p = P + row * G;
+    const float* q = Q + row * G;
+    float out;
+    if (cell == RNN_CELL_GRU) {
+      const float r = sigmoidf_dev(p[u] + bias[u] + q[u]);
+      const float z = sigmoidf_dev(p[H + u] + bias[H + u] + q[H + u]);
+      const float qn = q[2 * H + u];
+      const float n = tanhf(p[2 * H + u] + bias[2 * H + u] + r * qn);
+      out = (1.f - z) * n + z * (hp ? hp[e] : 0.f);
+      float* s4 = sv + row * 4 * H;
+      s4[u] = r; s4[H + u] = z; s4[2 * H + u] = n; s4[3 * H + u] = qn;
+    } else {
+      const float a = p[u] + bias[u] + q[u];
+      out = cell == RNN_CELL_TANH ? tanhf(a) : fmaxf(a, 0.f);
+    }
+    h[e] = out;
+    if (y) y[e] = out;
+  }
+}
+
+// Backward point-wise stage of one step: dh = dout + carry; writes the gradients with respect to
+// W x + b (da, [B][G]) and to R h_{t-1} (dq, [B][G]; the same array for the single-gate cells) and the
+// part of dh_{t-1} that does not pass through R (direct, [B][H]; zero for the single-gate cells).
+__global__ void cell_bwd_kernel(int cell, const float* __restrict__ dout, const float* __restrict__ carry,
+                                const float* __restrict__ h, const float* __restrict__ hp, const float* __restrict__ sv,
+                                float* __restrict__ da, float* __restrict__ dq, float* __restrict__ direct, int B, int H) {
+  const long cnt = (long)B * H;
+  const int G = (cell == RNN_CELL_GRU ? 3 : 1) * H;
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
+    const int u = (int)(e % H);
+    const long row = e / H;
+    const float dh = dout[e] + (carry ? carry[e] : 0.f);
+    if (cell == RNN_CELL_GRU) {
+      const float* s4 = sv + row * 4 * H;
+      const float r = s4[u], z = s4[H + u], n = s4[2 * H + u], qn = s4[3 * H + u];
+      const float hprev = hp ? hp[e] : 0.f;
+      const float dn_pre = dh * (1.f - z) * (1.f - n * n);
+      const float daz = dh * (hprev - n) * z * (1.f - z);
+      const float dar = dn_pre * qn * r * (1.f - r);
+      float* a3 = da + row * G;
+      float* q3 = dq + row * G;
+      a3[u] = dar; a3[H + u] = daz; a3[2 * H + u] = dn_pre;
+      q3[u] = dar; q3[H + u] = daz; q3[2 * H + u] = dn_pre * r;
+      direct[e] = dh * z;
+    } else {
+      const float hv = h[e];
+      da[row * G + u] = dh * (cell == RNN_CELL_TANH ? (1.f - hv * hv) : (hv > 0.f ? 1.f : 0.f));
+      direct[e] = 0.f;
+    }
+  }
+}
+
+struct RnnWs {
+  size_t P, Q, da, dq, dx0, dx1, carry0, carry1, dbpart, total;
+};
+
+RnnWs rnn_ws(int cell, const Dims& d) {
+  const size_t TB = (size_t)d.T * d.B, G = (size_t)gates_of(cell) * d.H, BH = (size_t)d.B * d.H;
+  RnnWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  w.P = take(TB * G * 4);
+  w.Q = take((size_t)d.B * G * 4);
+  w.da = take(TB * G * 4);
+  w.dq = take(TB * G * 4);
+  w.dx0 = take(TB * d.H * 4);
+  w.dx1 = take(TB * d.H * 4);
+  w.carry0 = take(BH * 4);
+  w.carry1 = take(BH * 4);
+  w.dbpart = take(64 * G * 4);
+  w.total = off;
+  return w;
+}
+
+// reserve of layer l: hidden states [T][B][H], then (GRU) r, z, n, R_n h [T][B][4H]
+inline size_t res_layer_floats(int cell, const Dims& d) {
+  return (size_t)d.T * d.B * d.H * (cell == RNN_CELL_GRU ? 5 : 1);
+}
+
+inline int ew_grid(long cnt) { return (int)((cnt + 255) / 256 < 2048 ? (cnt + 255) / 256 : 2048); }
+
+int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const float* W, const float* R, const float* b,
+                 float* y, float* hT, float* reserve, char* ws, hipStream_t s) {
+  const int gates = gates_of(cell), H = d.H, B = d.B;
+  const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
+  const RnnWs w = rnn_ws(cell, d);
+  float* P = reinterpret_cast<float*>(ws + w.P);
+  float* Q = reinterpret_cast<float*>(ws + w.Q);
+  size_t woff = 0;
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    float* hl = reserve + (size_t)l * res_layer_floats(cell, d);
+    float* svl = hl + TB * H;
+    const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(cell, d);
+    const float* Wl = W + woff;
+    const float* Rl = R + (size_t)l * G * H;
+    woff += G * Il;
+    {  // Section 2.3: the layer's input products for all steps in one GEMM
+      GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+      CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+    }
+    for (int t = 0; t < d.T; ++t) {
+      const float* hp = t ? hl + (size_t)(t - 1) * BH : (h0 ? h0 + (size_t)l * BH : nullptr);
+      float* ht = hl + (size_t)t * BH;
+      if (hp) {  // Section 2.1: all gates of the step in one recurrent product
+        GemmProblem p{hp, Rl, Q, B, (int)G, H, H, 1, 1, H, (long)G, 0};
+        CK(launch_gemm_group(&p, 1, s), "recurrent GEMM");
+      } else {
+        CK(launch_fill_zero(Q, (size_t)B * G * 4, s), "zero recurrent term");
+      }
+      hipLaunchKernelGGL(cell_fwd_kernel, dim3(ew_grid((long)BH)), dim3(256), 0, s, cell, P + (size_t)t * B * G, Q,
+                         b + (size_t)l * G, hp, ht, (l == d.L - 1) ? y + (size_t)t * BH : nullptr,
+                         cell == RNN_CELL_GRU ? svl + (size_t)t * B * 4 * H : nullptr, B, H);
+      CK(hipGetLastError(), "point-wise forward");
+    }
+    if (hT) CK(launch_ew(EW_COPY, hT + (size_t)l * BH, H, hl + (size_t)(d.T - 1) * BH, H, nullptr, 0, B, H, s), "copy hT");
+  }
+  return LSTM_OK;
+}
+
+int backward_impl(int cell, const Dims& d, const float* x, const float* h0, const float* W, const float* R,
+                  const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW, float* dR,
+                  float* db, char* ws, hipStream_t s) {
+  const int gates = gates_of(cell), H = d.H, B = d.B;
+  const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
+  const RnnWs w = rnn_ws(cell, d);
+  float* da = reinterpret_cast<float*>(ws + w.da);
+  float* dq = cell == RNN_CELL_GRU ? reinterpret_cast<float*>(ws + w.dq) : da;
+  float* dxb[2] = {reinterpret_cast<float*>(ws + w.dx0), reinterpret_cast<float*>(ws + w.dx1)};
+  float* carry[2] = {reinterpret_cast<float*>(ws + w.carry0), reinterpret_cast<float*>(ws + w.carry1)};
+  float* dbpart = reinterpret_cast<float*>(ws + w.dbpart);
+  for (int l = d.L - 1; l >= 0; --l) {
+    const int Il = in_dim(d, l);
+    const float* hl = reserve + (size_t)l * res_layer_floats(cell, d);
+    const float* svl = hl + TB * H;
+    const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(cell, d);
+    size_t woff = 0;
+    for (int q = 0; q < l; ++q) woff += G * in_dim(d, q);
+    const float* Wl = W + woff;
+    const float* Rl = R + (size_t)l * G * H;
+    const float* dout = (l == d.L - 1) ? dy : dxb[(l + 1) & 1];
+    const float* cin = dhT ? dhT + (size_t)l * BH : nullptr;
+    int cur = 0;
+    for (int t = d.T - 1; t >= 0; --t) {
+      const float* hp = t ? hl + (size_t)(t - 1) * BH : (h0 ? h0 + (size_t)l * BH : nullptr);
+      float* nxt = carry[cur];
+      hipLaunchKernelGGL(cell_bwd_kernel, dim3(ew_grid((long)BH)), dim3(256), 0, s, cell, dout + (size_t)t * BH, cin,
+                         hl + (size_t)t * BH, hp, cell == RNN_CELL_GRU ? svl + (size_t)t * B * 4 * H : nullptr,
+                         da + (size_t)t * B * G, dq + (size_t)t * B * G, nxt, B, H);
+      CK(hipGetLastError(), "point-wise backward");
+      // dh_{t-1} = direct + dq_t R  (the stacked gates map to one output, Section 2.1)
+      GemmProblem p{dq + (size_t)t * B * G, Rl, nxt, B, H, (int)G, (long)G, 1, H, 1, H, 1};
+      CK(launch_gemm_group(&p, 1, s), "recurrent backward GEMM");
+      cin = nxt;
+      cur ^= 1;
+    }
+    if (dh0) CK(launch_ew(EW_COPY, dh0 + (size_t)l * BH, H, cin, H, nullptr, 0, B, H, s), "copy dh0");
+    float* din = l > 0 ? dxb[l & 1] : dx;
+    if (din) {
+      GemmProblem p{da, Wl, din, (int)TB, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
+      CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
+    }
+    // Section 2.6: weight gradients as large products once the layer's propagation is complete
+    float* dWl = dW + woff;
+    float* dRl = dR + (size_t)l * G * H;
+    GemmProblem g[2];
+    int ng = 0;
+    g[ng++] = GemmProblem{da, in, dWl, (int)G, Il, (int)TB, 1, (long)G, Il, 1, Il, 0};
+    if (d.T > 1) g[ng++] = GemmProblem{dq + (size_t)B * G, hl, dRl, (int)G, H, (int)(TB - B), 1, (long)G, H, 1, H, 0};
+    CK(launch_gemm_group(g, ng, s), "weight-gradient GEMMs");
+    if (h0) {
+      GemmProblem p{dq, h0 + (size_t)l * BH, dRl, (int)G, H, B, 1, (long)G, H, 1, H, d.T > 1 ? 1 : 0};
+      CK(launch_gemm_group(&p, 1, s), "weight-gradient GEMM (initial state term)");
+    } else if (d.T == 1) {
+      CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
+    }
+    CK(launch_colsum(da, (int)TB, (int)G, dbpart, db + (size_t)l * G, s), "bias gradient");
+  }
+  return LSTM_OK;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+}  // namespace lstm
+
+using namespace lstm;
+
+extern "C" {
+
+size_t rnn_reserve_bytes(int cell, int L, int T, int B, int I, int H) {
+  if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
+  return (size_t)L * res_layer_floats(cell, Dims{L, T, B, I, H}) * sizeof(float);
+}
+
+size_t rnn_workspace_bytes(int cell, int L, int T, int B, int I, int H) {
+  if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
+  return rnn_ws(cell, Dims{L, T, B, I, H}).total;
+}
+
+int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, const float* h0, const float* W,
+                const float* R, const float* b, float* y, float* hT, void* reserve, void* workspace,
+                size_t workspace_bytes, void* stream) {
+  if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return LSTM_INVALID_ARG;
+  if (!x || !W || !R || !b || !y || !reserve || !workspace) return LSTM_INVALID_ARG;
+  const void* ptrs[] = {x, h0, W, R, b, y, hT, reserve, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LSTM_INVALID_ARG;
+  const Dims d{L, T, B, I, H};
+  if (workspace_bytes < rnn_ws(cell, d).total) return LSTM_BUFFER_TOO_SMALL;
+  return forward_impl(cell, d, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve), reinterpret_cast<char*>(workspace),
+                      (hipStream_t)stream);
+}
+
+int rnn_backward(int cell, int L, int T, int B, int I, int H, const float* x, const float* h0, const float* W,
+                 const float* R, const void* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW,
+                 float* dR, float* db, void* workspace, size_t workspace_bytes, void* stream) {
+  if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return LSTM_INVALID_ARG;
+  if (!x || !W || !R || !reserve || !dy || !dW || !dR || !db || !workspace) return LSTM_INVALID_ARG;
+  const void* ptrs[] = {x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, workspace};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return LSTM_INVALID_ARG;
+  const Dims d{L, T, B, I, H};
+  if (workspace_bytes < rnn_ws(cell, d).total) return LSTM_BUFFER_TOO_SMALL;
+  return backward_impl(cell, d, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
+                       reinterpret_cast<char*>(workspace), (hipStream_t)stream);
+}
+
+}  // extern "C"

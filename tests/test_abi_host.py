@@ -20,6 +20,31 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_library_exports_every_symbol_of_the_rnn_header():
+    hdr = open(os.path.join(ROOT, "include", "rnn.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(rnn_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(B.RNN_EXPORTS), declared ^ set(B.RNN_EXPORTS)
+    lib = B.library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_rnn_size_queries_and_argument_checks():
+    assert B.rnn_reserve_bytes(B.RNN_CELL_TANH, 2, 5, 3, 8, 16) == 2 * 5 * 3 * 16 * 4
+    assert B.rnn_reserve_bytes(B.RNN_CELL_GRU, 2, 5, 3, 8, 16) == 2 * 5 * 3 * 16 * 5 * 4
+    assert B.rnn_reserve_bytes(7, 2, 5, 3, 8, 16) == 0 and B.rnn_workspace_bytes(B.RNN_CELL_GRU, 0, 1, 1, 1, 1) == 0
+    wb = B.rnn_workspace_bytes(B.RNN_CELL_GRU, 1, 2, 2, 4, 4)
+    assert wb > 0 and wb % 256 == 0
+    a = 4096  # any 16-byte aligned non-null address: validation fails before it is touched
+    dims = (B.RNN_CELL_GRU, 1, 2, 2, 4, 4)
+    assert B.rnn_forward(*dims, a, None, a, a, a, a, None, a, a, wb - 1, stream=0) == B.LSTM_BUFFER_TOO_SMALL
+    assert B.rnn_forward(*dims, None, None, a, a, a, a, None, a, a, wb, stream=0) == B.LSTM_INVALID_ARG
+    assert B.rnn_forward(*dims, a + 4, None, a, a, a, a, None, a, a, wb, stream=0) == B.LSTM_INVALID_ARG
+    assert B.rnn_forward(9, 1, 2, 2, 4, 4, a, None, a, a, a, a, None, a, a, wb, stream=0) == B.LSTM_INVALID_ARG
+    assert B.rnn_backward(*dims, a, None, a, a, a, None, None, None, None, a, a, a, a, wb, stream=0) == B.LSTM_INVALID_ARG
+
+
 def test_size_queries():
     assert B.lstm_reserve_bytes(4, 100, 64, 512, 512) == 4 * 100 * 64 * 6 * 512 * 4
     assert B.lstm_reserve_bytes(0, 1, 1, 1, 1) == 0 and B.lstm_workspace_bytes(1, 1, -1, 1, 1) == 0

@@ -1,0 +1,63 @@
+"""GPU parity of the single-gate RNN and GRU cells: rnn_forward / rnn_backward through the C ABI against the CPU
+oracle on the same seeded inputs.  Tolerances as for the LSTM: max|gpu-oracle|/max|oracle| <= 1e-4 forward, <= 1e-3
+for every gradient."""
+import numpy as np
+import pytest
+
+from oracle import rnn_oracle as O
+from parity import assert_close, FWD_TOL, BWD_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def make(cell, L, T, B, I, H, seed, with_h0=True):
+    rng = np.random.default_rng(seed)
+    G = O.CELLS[cell] * H
+    nw = G * I + (L - 1) * G * H
+    a = 1.0 / np.sqrt(H)
+    d = dict(x=rng.standard_normal((T, B, I)), W=rng.uniform(-a, a, nw), R=rng.uniform(-a, a, (L, G, H)),
+             b=rng.uniform(-0.1, 0.1, (L, G)), h0=0.3 * rng.standard_normal((L, B, H)) if with_h0 else None,
+             dy=rng.standard_normal((T, B, H)), dhT=0.3 * rng.standard_normal((L, B, H)) if with_h0 else None)
+    return {k: (None if v is None else v.astype(np.float32)) for k, v in d.items()}
+
+
+def run(cell, L, T, B, I, H, seed, with_h0=True):
+    import torch
+    from paper_1604_01946_amd import binding as Bd
+    d = make(cell, L, T, B, I, H, seed, with_h0)
+    y, hT, saved = O.rnn_forward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    dx, dh0, dW, dR, db = O.rnn_backward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"])
+    ref = dict(y=y, hT=hT, dx=dx, dh0=dh0, dW=dW, dR=dR, db=db)
+    dev = "cuda:0"
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    t = {k: up(v) for k, v in d.items()}
+    c = Bd.RNN_CELLS[cell]
+    f = lambda *s: torch.full(s, float("nan"), dtype=torch.float32, device=dev)
+    out = dict(y=f(T, B, H), hT=f(L, B, H), dx=f(T, B, I), dh0=f(L, B, H), dW=f(d["W"].size), dR=f(*d["R"].shape), db=f(*d["b"].shape))
+    rb, wb = Bd.rnn_reserve_bytes(c, L, T, B, I, H), Bd.rnn_workspace_bytes(c, L, T, B, I, H)
+    res = torch.full((rb // 4,), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.full((wb // 4,), float("nan"), dtype=torch.float32, device=dev)
+    print(f"case {cell} {(L, T, B, I, H)} seed={seed} h0={with_h0}", flush=True)
+    Bd.check(Bd.rnn_forward(c, L, T, B, I, H, t["x"], t["h0"], t["W"], t["R"], t["b"], out["y"], out["hT"], res, ws, wb), "rnn_forward")
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    assert_close(got, ref, ("y", "hT"), FWD_TOL, f"fwd {cell}")
+    Bd.check(Bd.rnn_backward(c, L, T, B, I, H, t["x"], t["h0"], t["W"], t["R"], res, t["dy"], t["dhT"], out["dx"], out["dh0"],
+                             out["dW"], out["dR"], out["db"], ws, wb), "rnn_backward")
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy().reshape(np.asarray(ref[k]).shape) for k, v in out.items()}
+    assert_close(got, ref, ("dx", "dh0", "dW", "dR", "db"), BWD_TOL, f"bwd {cell}")
+
+
+SHAPES = [(1, 8, 4, 32, 32), (3, 5, 7, 24, 40), (2, 6, 64, 128, 256), (4, 12, 33, 512, 512), (1, 1, 1, 16, 16), (2, 3, 3, 5, 7)]
+
+
+@pytest.mark.parametrize("cell", ["relu", "tanh", "gru"])
+@pytest.mark.parametrize("dims", SHAPES, ids=["x".join(map(str, s)) for s in SHAPES])
+def test_cells_match_oracle(cell, dims):
+    run(cell, *dims, seed=3)
+
+
+@pytest.mark.parametrize("cell", ["tanh", "gru"])
+def test_cells_without_initial_state(cell):
+    run(cell, 2, 4, 5, 16, 48, seed=4, with_h0=False)
