@@ -90,6 +90,14 @@ struct Waiter {
     const int lane = threadIdx.x & 63;
     return lane < kFlagSub ? __hip_atomic_load(flag + lane * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : (1 << 30);
   }
+  // The same without any branch or lane mask (lane i reads line i % kFlagSub), for reads issued in the
+  // middle of pinned straight-line code: the value stays in flight until land() is called on it.
+  static __device__ __forceinline__ int peek_all(int* flag) {
+    return __hip_atomic_load(flag + (threadIdx.x & (kFlagSub - 1)) * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // Marks the point where a peeked value is first needed; nothing that depends on it (and so no wait
+  // for it) can be placed earlier.
+  static __device__ __forceinline__ void land(int& v) { asm volatile("" : "+v"(v)); }
   // Waits until `target` workgroups (a multiple of kFlagSub, spread evenly) have arrived; `seen` is a
   // value peeked earlier (pass 0 if none, anything >= target to skip the wait).
   __device__ __forceinline__ void wait(int* flag, int target, int seen = 0) {
@@ -152,8 +160,14 @@ __device__ __forceinline__ void xstore(float* p, float v) {
 
 // 16-byte variant: the exchange tiles are staged in LDS and written as whole 128-byte lines, which
 // the memory side takes far better than scattered 4-byte write-through stores.
+// A store of more than 8 bytes reads its data registers over several cycles after it has issued,
+// and an instruction that overwrites them must keep its distance (two idle cycles on this
+// architecture).  The compiler keeps that distance for its own stores but cannot see one inside
+// inline assembly, so the idle cycles are part of the statement: without them the last lanes of a
+// store were seen to carry the values written by the instructions that followed, once a second
+// workgroup on the CU kept the address unit busy.
 __device__ __forceinline__ void xstore4(float* p, floatx4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
 }
 
 // Makes a wave-uniform value opaque to the optimiser.  Offsets derived from a loop-invariant value
@@ -161,12 +175,21 @@ __device__ __forceinline__ void xstore4(float* p, floatx4 v) {
 // VGPR lanes and are moved back and forth between the MFMAs of every step.
 __device__ __forceinline__ void hide(int& v) { asm volatile("" : "+s"(v)); }
 
+// Waits for every outstanding vector memory operation of the wave.  The counter is shared by loads and
+// stores and decrements in issue order, so a later count-based wait for an old load also waits for
+// every younger store; the second form tells the compiler (which does not read inline assembly) that
+// nothing is outstanding, so registers loaded long ago are not waited for again behind later stores.
+__device__ __forceinline__ void drain_vmem() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+}
+
 // All threads have written; make it visible at agent scope and bump the counter once.
 __device__ __forceinline__ void signal(int* flag, int full) {
   if (full)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   else
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    drain_vmem();
   __syncthreads();
   if (threadIdx.x == 0) __hip_atomic_fetch_add(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -667,6 +690,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     const float* src = slot(l - 1, 1) + boff;
 #pragma unroll
     for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
+    drain_vmem();
   }
   for (int t = 0; t < T; ++t) {
     tr.mark(t, 0);
@@ -683,8 +707,9 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         for (int j = 0; j < 2; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(wgt[m], bv[2 * m + j], acc[j], 0, 0, 0);
     };
     // both counters are read now; the answers arrive under the MFMAs of part 1
-    const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t)) : NS;
-    const int seen_in = (t + 1 < T) ? Waiter::peek(flag(l - 1, t + 2)) : 0;
+    // (slots that do not exist at the ends of the sequence are replaced by ones that do; their values are not used)
+    int seen_rec = Waiter::peek_all(flag(l, t > 0 ? t : 1));
+    int seen_in = Waiter::peek_all(flag(l - 1, t + 1 < T ? t + 2 : t + 1));
     floatx4 bh[HK], br[NK4];
     {
       const float* src = slot(l - 1, t + 1) + boff;
@@ -697,7 +722,8 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    w.wait(flag(l, t), NS, seen_rec);  // h_{l,t-1}; slot 0 (h0 or zeros) was written before the launch
+    Waiter::land(seen_rec);
+    w.wait(flag(l, t), NS, t > 0 ? seen_rec : NS);  // h_{l,t-1}; slot 0 (h0 or zeros) was written before the launch
     tr.mark(t, 2);
     {
       const float* src = slot(l, t) + boff;
@@ -710,6 +736,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       }
     }
     const bool more = t + 1 < T;
+    Waiter::land(seen_in);
     const bool pre = more && __all(seen_in >= NS / kFlagSub) && !w.dead;
     {
       const float* nsrc = slot(l - 1, pre ? t + 2 : t + 1) + boff;
@@ -726,6 +753,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       const float* src = slot(l - 1, t + 2) + boff;
 #pragma unroll
       for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
+      drain_vmem();
     }
   }
 }

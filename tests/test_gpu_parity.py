@@ -273,6 +273,37 @@ def test_bitwise_repeatable(name):
         assert torch.equal(outs[0][k], outs[1][k]) and torch.equal(outs[0][k], outs[2][k]), k
 
 
+@pytest.mark.parametrize("dims", [(4, 100, 16, 256), (8, 60, 32, 256)], ids=["b16", "b32"])
+def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, monkeypatch):
+    """Two calls on two streams whose persistent kernels fit on the same CUs (ordinary launches, small register
+    footprint): each must give exactly what it gives alone.  This caught a 16-byte write-through store issued from
+    inline assembly without the idle cycles a wide store needs before its data registers are overwritten."""
+    torch, binding, runner = _mods()
+    monkeypatch.setenv("LSTM_PLAIN_LAUNCH", "1")
+    L, T, B, H = dims
+    cfg = Config("two", L=L, T=T, B=B, I=H, H=H, state_std=0.1)
+    r1, r2 = runner.LstmRunner(cfg.dims, make_inputs(cfg, 1)), runner.LstmRunner(cfg.dims, make_inputs(cfg, 2))
+    alone = []
+    for r in (r1, r2):
+        binding.check(r.forward())
+        binding.check(r.backward())
+        torch.cuda.synchronize()
+        alone.append({k: getattr(r, k).clone() for k in FWD + BWD})
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for trial in range(4):
+        for first_bwd in (False, True):
+            with torch.cuda.stream(s1):
+                binding.check(r1.backward() if first_bwd else r1.forward())
+            with torch.cuda.stream(s2):
+                binding.check(r2.backward())
+            with torch.cuda.stream(s1):
+                binding.check(r1.backward())
+            torch.cuda.synchronize()
+            for r, ref in ((r1, alone[0]), (r2, alone[1])):
+                for k in FWD + BWD:
+                    assert torch.equal(getattr(r, k), ref[k]), (trial, first_bwd, k)
+
+
 # ------------------------------------------------------------------ boundary identity on the GPU
 def test_split_T_chaining_on_gpu():
     torch, binding, runner = _mods()
