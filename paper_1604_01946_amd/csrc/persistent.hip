@@ -779,13 +779,15 @@ __global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restr
 //                ([4H][BP]), to the exchange buffer;
 //   GEMM         [dh_rec_{t-1} ; dx_{l,t}] (16 rows) = [R_l[:, units] | W_l[:, units]]^T * dA_t, K = 4H:
 //                rows 0-7 stay in registers for the next point-wise step, rows 8-15 are the gradient
-//                for the same units of layer l-1 at step t (its dout) and go to dxbuf.
+//                for the same units of layer l-1 at step t (its dout) and go to dxbuf; for layer 0 they
+//                are the gradient of the network input and go to the caller's dx when I == H (the
+//                tile rows would otherwise multiply zeros), else a batched GEMM follows the launch.
 // Section 2.1's remark on the backward pass (four gate gradients map to one output through the
 // stacked matrices) is the K = 4H contraction; wave w takes the K range of gate w.
 // Counters: slot t+1 of layer l = "point-wise of step t published" (which, by program order, also
 // covers dx of step t+1); slot 0 = "dx of step 0 published".
 struct PersBwdArgs {
-  const float* W;      // flat input matrices (layers >= 1 are read here)
+  const float* W;      // flat input matrices (layer 0's only when dx0 is set)
   const float* R;      // [L][4H][H]
   const float* res;    // reserve written by the forward pass
   const float* c0;     // [L][B][H] or null
@@ -795,6 +797,7 @@ struct PersBwdArgs {
   float* dA;           // [L][T][B][4H] gate gradients (standard layout)
   float* dAx;          // [L][T][NC][4H][BP] exchange
   float* dxbuf;        // [L][T][B][H] gradient for the layer below (slice l written by layer l, l >= 1)
+  float* dx0;          // [T][B][I] gradient of the network input, written by layer 0 when I == H; else null
   float* dh0;          // [L][B][H] or null
   float* dc0;          // [L][B][H] or null
   float* db;           // [L][4H] bias gradient, zeroed before the launch (wide kernel only), or null
@@ -830,8 +833,8 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   {
     const float* Rl = a.R + (size_t)l * G * H;
     const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
-    const float* src = (n < 8) ? Rl + u0 + n : Wl + u0 + (n - 8);
-    const bool live = (n < 8) || (l > 0);
+    const float* src = (n < 8) ? Rl + u0 + n : (l > 0 ? Wl : a.W) + u0 + (n - 8);  // layer 0: its own [4H][I], I == H
+    const bool live = (n < 8) || (l > 0) || a.dx0;
 #pragma unroll
     for (int i = 0; i < KGB; ++i)
       wB[i] = live ? src[(size_t)(wave * H + 4 * ((i + rot) & (KGB - 1)) + q) * H] : 0.f;
@@ -849,7 +852,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   for (int c = 0; c < NC; ++c) {
     const int bb = c * BP + lb;
     pw[c] = fin && q < 2 && bb < B;                 // lane runs the point-wise stage
-    dxl[c] = fin && q >= 2 && bb < B && l > 0;
+    dxl[c] = fin && q >= 2 && bb < B && (l > 0 || a.dx0);
     seen_up[c] = 0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -865,7 +868,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   float* const dA_l = a.dA + (size_t)l * TB * G;
   const bool has_up = l < a.L - 1;
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
-  float* const dx_out = a.dxbuf + (size_t)l * TB * H;
+  float* const dx_out = l > 0 ? a.dxbuf + (size_t)l * TB * H : a.dx0;
   const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
   auto slot = [&](int t, int c) { return a.dAx + (((size_t)l * T + t) * NC + c) * G * BP; };
   auto flag = [&](int layer, int sl, int c) { return a.flags + (((size_t)layer * (T + 1) + sl) * NC + c) * kFlagInts; };
@@ -1077,8 +1080,8 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   {
     const float* Rl = a.R + (size_t)l * G * H;
     const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
-    const float* src = (n < 16) ? Rl + u0 + n : Wl + u0 + (n - 16);
-    const bool live = (n < 16) || (l > 0);
+    const float* src = (n < 16) ? Rl + u0 + n : (l > 0 ? Wl : a.W) + u0 + (n - 16);  // layer 0: its own [4H][I], I == H
+    const bool live = (n < 16) || (l > 0) || a.dx0;
 #pragma unroll
     for (int i = 0; i < KPW; ++i) {
       const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
@@ -1094,7 +1097,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   //      waves 2,3 publish dx of units u0 + 8*(wave-2) + 4*kk + {0..3}; batch row bh*32 + n
   const int bb = a.b0 + bh * 32 + n;  // batch row in the tensors; the exchange slots hold this launch's 64 rows
   const bool pwv = wave < 2 && bb < B;
-  const bool dxl = wave >= 2 && bb < B && l > 0;
+  const bool dxl = wave >= 2 && bb < B && (l > 0 || a.dx0);
   const int unit0 = u0 + 8 * (wave & 1) + 4 * kk;
   float dc[4], dh_rec[4];
   float dbsum[4][4];  // this lane's share of the bias gradient: sum over t of dA_t, per (gate, unit)
@@ -1113,7 +1116,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   float* const dA_l = a.dA + (size_t)l * TB * G;
   const bool has_up = l < a.L - 1;
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
-  float* const dx_out = a.dxbuf + (size_t)l * TB * H;
+  float* const dx_out = l > 0 ? a.dxbuf + (size_t)l * TB * H : a.dx0;
   auto slot = [&](int t) { return a.dAx + (((size_t)l * T + t) * NBH + bh) * G * 32; };
   auto flag = [&](int layer, int sl) { return a.flags + (((size_t)layer * (T + 1) + sl) * NBH + bh) * kFlagInts; };
 
@@ -2138,6 +2141,9 @@ int run_backward_persistent(const BwdArgs& a) {
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
   k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
+  // With I == H layer 0 is like every other layer: its workgroups also multiply by W_0 (the rows of the
+  // MFMA tile that would otherwise hold zeros) and write the gradient of the network input themselves.
+  k.dx0 = (a.dx && d.I == d.H) ? a.dx : nullptr;
   k.db = nullptr;
   if (wide && a.db && d.B <= 64) {  // one launch: the wide kernel adds the bias gradient into db itself (two addends per element)
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
@@ -2173,7 +2179,7 @@ int run_backward_persistent(const BwdArgs& a) {
     else if (d.H == 128) e = launch_bwd<32>(bp, grid, k, s);
     CK(e, "persistent backward launch");
   }
-  if (a.dx) {  // layer 0's input gradient: all T steps in one product
+  if (a.dx && !k.dx0) {  // layer 0's input gradient: all T steps in one product
     ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
     GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)G, (long)G, 1, d.I, 1, d.I, 0};
     CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");

@@ -38,9 +38,11 @@ __device__ __forceinline__ floatx4 ld4(const float* __restrict__ row, int k, int
 // Write-through (agent-scope) 16-byte store.  The data operand must not come straight out of an
 // MFMA: inline assembly is opaque to the compiler's hazard handling, so an accumulator could be
 // read before its last pass has been written.  The partial sums are therefore staged through LDS
-// first (which also turns them into long contiguous runs).
+// first (which also turns them into long contiguous runs).  For the same reason the statement ends in
+// idle cycles: a store of more than 8 bytes still reads its data registers after it has issued, and
+// the compiler, not knowing this is a store, may overwrite them with the very next instruction.
 __device__ __forceinline__ void xstore4(float* p, floatx4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
 }
 
 // True in exactly one workgroup per (row slice, launch): the one whose partial arrived last.
