@@ -212,7 +212,9 @@ struct PersFwdArgs {
   const float* W;     // flat input matrices; layers >= 1 are read
   const float* R;     // [L][4H][H]
   const float* bias;  // [L][4H]
-  const float* P0;    // [T][B][4H] input projection of layer 0
+  const float* P0;    // [T][B][4H] input projection of layer 0 (batched GEMM before the launch), unless xin is set
+  const float* xin;   // wide kernel, I == H: x in exchange layout, [nsl][T+1][H*64] with slot t+1 = x_t; layer 0 then
+                      // multiplies by W_0 itself, step by step, like the layers above it
   const float* c0;    // [L][B][H] or null
   float* hx;          // [L][T+1][NC][H][BP] exchange, slot t+1 = h_t, slot 0 = h0
   int* flags;         // [L][T+1][NC], slot t+1 counts the slices of layer l that finished step t
@@ -503,7 +505,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   float wR[NK4][2], wW[NK4][2];
   {
     const float* Rl = a.R + (size_t)l * G * H;
-    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
+    const float* Wl = l > 0 ? a.W + (size_t)4 * H * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [4H][I], read if I == H
     const size_t row = ((size_t)(n >> 3) * H + u0 + (n & 7)) * H;
 #pragma unroll
     for (int i = 0; i < NK4; ++i) {
@@ -512,7 +514,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       for (int m = 0; m < 2; ++m) {
         const int k = wave * (H / 4) + 4 * k4 + 2 * m + kk;
         wR[i][m] = Rl[row + k];
-        wW[i][m] = (l > 0) ? Wl[row + k] : 0.f;
+        wW[i][m] = (l > 0 || a.xin) ? Wl[row + k] : 0.f;
       }
     }
   }
@@ -624,7 +626,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     }
   };
 
-  if (l == 0) {
+  if (l == 0 && !a.xin) {
     // ---- layer 0: the input half is the batched projection P_0 (added in the epilogue); its values
     //      for the next step are fetched one step ahead, behind the exchange loads, so that a miss to
     //      HBM never sits in front of a counter poll (loads return in order).
@@ -682,12 +684,19 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   // wave in the address unit for about a microsecond while the matrix cores idle); the scheduling
   // barriers pin that order.  Only half an operand is carried from step to step, which keeps the
   // kernel inside the register file.
+  // The layer below is, for layer 0 with I == H, the input sequence itself: x in exchange layout, all
+  // of it there before the launch, with one counter that reads "published" for every step.
   constexpr int HK = NK4 / 2;
   const float zero_pin[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  const float* const in_base = l > 0 ? slot(l - 1, 0) : a.xin + (size_t)sl * (T + 1) * H * 64;
+  int* const in_flag_base = l > 0 ? flag(l - 1, 0) : a.flags + (size_t)a.nsl * a.L * (T + 1) * kFlagInts;
+  const int in_flag_step = l > 0 ? kFlagInts : 0;
+  auto in_slot = [&](int st) { return in_base + (size_t)st * H * 64; };
+  auto in_flag = [&](int st) { return in_flag_base + (size_t)st * in_flag_step; };
   floatx4 bl[HK];
-  w.wait(flag(l - 1, 1), NS);
+  w.wait(in_flag(1), NS);
   {
-    const float* src = slot(l - 1, 1) + boff;
+    const float* src = in_slot(1) + boff;
 #pragma unroll
     for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
     drain_vmem();
@@ -709,10 +718,10 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     // both counters are read now; the answers arrive under the MFMAs of part 1
     // (slots that do not exist at the ends of the sequence are replaced by ones that do; their values are not used)
     int seen_rec = Waiter::peek_all(flag(l, t > 0 ? t : 1));
-    int seen_in = Waiter::peek_all(flag(l - 1, t + 1 < T ? t + 2 : t + 1));
+    int seen_in = Waiter::peek_all(in_flag(t + 1 < T ? t + 2 : t + 1));
     floatx4 bh[HK], br[NK4];
     {
-      const float* src = slot(l - 1, t + 1) + boff;
+      const float* src = in_slot(t + 1) + boff;
       tr.mark(t, 1);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -739,7 +748,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     Waiter::land(seen_in);
     const bool pre = more && __all(seen_in >= NS / kFlagSub) && !w.dead;
     {
-      const float* nsrc = slot(l - 1, pre ? t + 2 : t + 1) + boff;
+      const float* nsrc = in_slot(pre ? t + 2 : t + 1) + boff;
 #pragma unroll
       for (int i = 0; i < NK4; ++i) {
         if (i < HK) bl[i] = ldx(nsrc, i);
@@ -749,8 +758,8 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     }
     finish_step(acc, zero_pin, t);
     if (more && !pre) {  // the layer below was late: wait for it now, after this step is published
-      w.wait(flag(l - 1, t + 2), NS);
-      const float* src = slot(l - 1, t + 2) + boff;
+      w.wait(in_flag(t + 2), NS);
+      const float* src = in_slot(t + 2) + boff;
 #pragma unroll
       for (int i = 0; i < HK; ++i) bl[i] = ldx(src, i);
       drain_vmem();
@@ -769,6 +778,35 @@ __global__ void pack_state32_kernel(const float* __restrict__ h0, float* __restr
     const int bb = b0 + 64 * sl + lb;
     hx[(((size_t)sl * L + l) * (T + 1)) * H * 64 + ((size_t)(k4 * 2 + kk) * 32 + n) * 4 + 2 * m + j] =
         (h0 && bb < B) ? h0[((size_t)l * B + bb) * H + k] : 0.f;
+  }
+}
+
+// x [T][B][H] (I == H) -> exchange layout of pers_fwd32_kernel, slots 1..T of xin [nsl][T+1][H*64], rows past the
+// batch zero; also sets the counter that stands for "every step of the input is published" (nsl*L*(T+1) counters
+// into `flags`).  Block (kb, t, sl) moves the 64 batch rows x 64 inputs [64*kb, 64*kb+64) of one step through LDS:
+// whole rows in, one contiguous 16 KB piece of the slot out.
+__global__ __launch_bounds__(256) void pack_x32_kernel(const float* __restrict__ x, float* __restrict__ xin, int* flags,
+                                                       int L, int T, int B, int H, int b0, int nsl, int ready) {
+  __shared__ float tile[64][65];
+  const int kb = blockIdx.x, t = blockIdx.y, sl = blockIdx.z;
+  if (kb == 0 && t == 0 && sl == 0 && threadIdx.x < kFlagSub)
+    flags[(size_t)nsl * L * (T + 1) * kFlagInts + threadIdx.x * kFlagStride] = ready;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int e = threadIdx.x + 256 * i, lb = e >> 6, kc = e & 63;
+    const int bb = b0 + 64 * sl + lb;
+    tile[lb][kc] = bb < B ? x[((size_t)t * B + bb) * H + 64 * kb + kc] : 0.f;
+  }
+  __syncthreads();
+  float* const dst = xin + ((size_t)sl * (T + 1) + t + 1) * H * 64 + (size_t)kb * 4096;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int o = threadIdx.x + 256 * i;  // 16-byte piece: ((k4*2 + kk)*32 + n), holding (m, j) = (0,0) (0,1) (1,0) (1,1)
+    const int n = o & 31, kk = (o >> 5) & 1, k4 = o >> 6;
+    floatx4 v;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = tile[2 * n + (q & 1)][4 * k4 + 2 * (q >> 1) + kk];
+    *reinterpret_cast<floatx4*>(dst + 4 * o) = v;
   }
 }
 
@@ -2072,12 +2110,23 @@ int run_forward_persistent(const FwdArgs& a) {
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
-  {
+  // Wide kernel with I == H: layer 0 multiplies by W_0 inside the kernel like the layers above it (its workgroups
+  // are otherwise idle half of every step), reading x from a copy in exchange layout that takes the place of the
+  // projection in the workspace.  LSTM_FWD_BATCHED_INPUT=1 keeps the batched product of Section 2.3 instead.
+  bool x_in_kernel = wide && d.I == d.H;
+  if (x_in_kernel) {
+    const char* e = getenv("LSTM_FWD_BATCHED_INPUT");
+    if (e && *e == '1') x_in_kernel = false;
+    const size_t rows = (size_t)(d.B + 63) / 64 * 64;  // the copy of x: T+1 slots of H x 64 per slice
+    if (((size_t)d.T + 1) * rows * d.H > (size_t)d.L * TB * G) x_in_kernel = false;
+  }
+  if (!x_in_kernel) {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
     GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
     CK(launch_gemm_group(&p, 1, s), "input projection GEMM (layer 0)");
   }
   PersFwdArgs k;
+  k.xin = x_in_kernel ? P0 : nullptr;
   k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
   k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();
@@ -2104,6 +2153,11 @@ int run_forward_persistent(const FwdArgs& a) {
         hipLaunchKernelGGL(pack_state32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T,
                            d.B, d.H, k.b0, nsl);
         CK(hipGetLastError(), "pack h0");
+        if (x_in_kernel) {
+          hipLaunchKernelGGL(pack_x32_kernel, dim3(d.H / 64, d.T, nsl), dim3(256), 0, s, a.x, P0, flags, d.L, d.T, d.B, d.H,
+                             k.b0, nsl, d.H / 8);
+          CK(hipGetLastError(), "pack x");
+        }
       } else if (a.h0) {
         const long n = (long)d.L * d.B * d.H;
         hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,

@@ -168,10 +168,11 @@ VARIANTS = [
     {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1"},                      # 16x16x4 kernels at B > 32
     {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1", "LSTM_CHAINS": "2"},  # two independent batch chains
     {"LSTM_FULL_FENCES": "1"},                                             # release/acquire fences on every step
+    {"LSTM_FWD_BATCHED_INPUT": "1"},                                       # layer 0's input product as one GEMM although I == H
 ]
 
 
-@pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences"])
+@pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences", "batched_input"])
 @pytest.mark.parametrize("cfg", [PERS[3], PERS[4], PERS[5]], ids=["p256b20", "p512b33", "p512b64"])
 def test_persistent_variants(cfg, env, monkeypatch):
     """The alternative kernels and the fence-based protocol must give the oracle's answer too; the
