@@ -44,17 +44,19 @@ def parse():
     return ap.parse_args()
 
 
-def phase_flops(cfg, phase, persistent):
-    """Algorithmic FLOPs of one call's worth of each GEMM-type phase."""
+def phase_flops(cfg, phase, persistent, ran=()):
+    """Algorithmic FLOPs of one call's worth of each GEMM-type phase; `ran` = the phases that were recorded."""
     L, T, B, I, H = cfg.dims
     G = 4 * H
     inp = sum(2 * G * (I if l == 0 else H) * B * T for l in range(L))
     rec = sum(2 * G * H * B * T for l in range(L))
     if persistent:
-        # the persistent kernels fold the input products of layers >= 1 into the recurrence
+        # the persistent kernels fold the input products of layers >= 1 into the recurrence, and layer 0's too
+        # when I == H (then no separate input GEMM phase is recorded)
         inp0 = 2 * G * I * B * T
-        table = {"fwd_input_gemm": inp0, "fwd_recurrence": rec + inp - inp0,
-                 "bwd_recurrence": rec + inp - inp0, "bwd_input_gemm": inp0, "weight_grad": inp + rec}
+        table = {"fwd_input_gemm": inp0, "fwd_recurrence": rec + inp - (inp0 if "fwd_input_gemm" in ran else 0),
+                 "bwd_recurrence": rec + inp - (inp0 if "bwd_input_gemm" in ran else 0), "bwd_input_gemm": inp0,
+                 "weight_grad": inp + rec}
     else:
         table = {"fwd_input_gemm": inp, "fwd_recurrence": rec, "bwd_recurrence": rec, "bwd_input_gemm": inp,
                  "weight_grad": inp + rec}
@@ -147,6 +149,7 @@ def main():
     tflops = passes * flop1 / (ms * 1e-3) / 1e12
     tflops_2pass = (2 if do_bwd else 1) * flop1 / (ms * 1e-3) / 1e12
 
+    ran = {k for k, (m, c) in phases.items() if c > 0}
     # roofline of the phase that takes the most time
     dom = max(phases.items(), key=lambda kv: kv[1][0])[0] if phases else None
     if dom and phases[dom][0] <= 0.0:
@@ -157,7 +160,7 @@ def main():
     if dom:
         dom_ms, dom_n = phases[dom]
         persistent = (path_b if dom.startswith("bwd") or dom == "weight_grad" else path_f) == B_.LSTM_PATH_PERSISTENT
-        fl = phase_flops(cfg, dom, persistent)
+        fl = phase_flops(cfg, dom, persistent, ran)
         if fl is not None:
             ach = fl / (dom_ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
@@ -175,7 +178,7 @@ def main():
         if c == 0:
             continue
         persistent = (path_b if k.startswith("bwd") or k == "weight_grad" else path_f) == B_.LSTM_PATH_PERSISTENT
-        fl = phase_flops(cfg, k, persistent)
+        fl = phase_flops(cfg, k, persistent, ran)
         phase_report[k] = {"ms": round(m, 4), "intervals": c}
         if fl:
             phase_report[k]["tflops"] = round(fl / (m * 1e-3) / 1e12, 2)

@@ -3,6 +3,7 @@
 #include "../../include/lstm.h"
 #include "internal.h"
 #include "schedule.h"
+#include <algorithm>
 
 #include <string.h>
 #include <stdio.h>
@@ -82,12 +83,15 @@ WsLayout ws_layout(const Dims& d) {
   // persistent paths: exchange buffers (large-H backward: gate gradients and partial sums of one layer,
   // 5 MB per step at H = 2048)
   size_t xchg = L * (size_t)d.T * G * Bp * 4;
-  if (d.H == 2048 && d.B <= 32) {
-    const size_t nbk = d.H / 128, need = (size_t)d.T * (nbk * 4 * 128 * 32 + nbk * nbk * 128 * 32) * 4;
+  if (d.H == 2048 || d.H == 1024) {  // up to four slices of 32 batch rows side by side (one at H = 2048)
+    const size_t nbk = d.H / 128, sl = std::min<size_t>(((size_t)d.B + 31) / 32, d.H == 2048 ? 1 : 4);
+    const size_t need = sl * d.T * (nbk * 4 * 128 * 32 + nbk * nbk * 128 * 32) * 4;
     if (need > xchg) xchg = need;
+    const size_t fwd = sl * ((size_t)d.T + 1) * d.H * 32 * 4;
+    if (fwd > xchg) xchg = fwd;
   }
   w.xchg = take(xchg);
-  w.flags = take((2 * (L > 16 ? L : 16) * ((size_t)d.T + 2) * 256 + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);  // step counters, one KB each
+  w.flags = take((4 * (L > 16 ? L : 16) * ((size_t)d.T + 2) * 256 + 64 + 16 * 32 * ((size_t)d.T + 2)) * 4);  // step counters, one KB each
   w.skpart = take(splitk_supported(d.H) ? L * splitk_partial_floats(d.H, d.B) * 4 : 0);
   w.skcnt = take(splitk_supported(d.H) ? L * ((size_t)d.T + 1) * splitk_counter_ints(d.H, d.B) * 4 : 0);
   w.resv = take(reserve_bytes(d));

@@ -1359,6 +1359,9 @@ struct PersFwdLArgs {
   float* hT;          // [B][H] or null
   float* cT;          // [B][H] or null
   int T, B;
+  int b0;             // first batch row of this launch (a multiple of 32)
+  int nsl;            // batch slices of 32 rows side by side in this launch (grid = nsl * H/8), each with its own
+                      // exchange slots and counters
   int spin_limit;
   int full_fences;
   long long* trace;
@@ -1379,12 +1382,14 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   float* const ro = smem + 4352;    // [6 arrays][32 batch rows][8 units]
   float* const wl = smem + 6144;    // [4 waves][LP][64 lanes]
 
-  const int s = blockIdx.x, u0 = 8 * s;
-  const int T = a.T, B = a.B;
+  const int sl = blockIdx.x / NS, s = blockIdx.x % NS, u0 = 8 * s;
+  const int T = a.T, B = a.B, b0 = a.b0 + 32 * sl;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kk = lane >> 5, n = lane & 31;
   const size_t TB = (size_t)T * B;
   const int rot = ((int)(blockIdx.x >> 3) * (NB8 / 32 > 0 ? NB8 / 32 : 1) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (NB8 - 1);
+  float* const hx = a.hx + (size_t)sl * (T + 1) * H * 32;
+  int* const flags = a.flags + (size_t)sl * (T + 1) * 16 * kFlagStride;
 
   // ---- weights: A operand row rho = lane%32 = (gate rho/8, unit rho%8); register / LDS entry i covers
   //      k = wave*H/4 + 8*((i/4 + rot) mod NB8) + 2*(i%4) + kk
@@ -1404,18 +1409,19 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
 
   // ---- the cell this thread finalises: unit u0 + 4*kk + wave, batch row n (D register 4*gate + wave)
   const int uj = 4 * kk + wave;
-  const bool valid = n < B;
-  float c_state = (valid && a.c0) ? a.c0[(size_t)n * H + u0 + uj] : 0.f;
+  const int bb = b0 + n;  // batch row in the tensors
+  const bool valid = bb < B;
+  float c_state = (valid && a.c0) ? a.c0[(size_t)bb * H + u0 + uj] : 0.f;
   float c_bias[4], pin[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     c_bias[g] = a.bias[g * H + u0 + uj];
-    pin[g] = valid ? a.P[(size_t)n * G + g * H + u0 + uj] : 0.f;
+    pin[g] = valid ? a.P[(size_t)bb * G + g * H + u0 + uj] : 0.f;
   }
   float* const res_gates = a.res;
   float* const res_c = a.res + TB * 4 * H;
   float* const res_h = a.res + TB * 5 * H;
-  auto slot = [&](int sl) { return a.hx + (size_t)sl * H * 32; };
+  auto slot = [&](int st) { return hx + (size_t)st * H * 32; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -1426,7 +1432,7 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   for (int t = 0; t < T; ++t) {
     tr.mark(t, 0);
     hide(rv);  // keeps the rotated offsets next to their loads
-    if (t > 0) w.template wait_split<16>(a.flags + (size_t)16 * kFlagStride * t, NS / 16);  // slot 0 was written before the launch
+    if (t > 0) w.template wait_split<16>(flags + (size_t)16 * kFlagStride * t, NS / 16);  // slot 0 was written before the launch
     tr.mark(t, 2);
     floatx16 acc;
 #pragma unroll
@@ -1455,7 +1461,7 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
         if (g == NB8 - DEPTH) {  // next step's input projection, behind the last exchange load of this step
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            pnx[q] = (valid && t + 1 < T) ? a.P[((size_t)(t + 1) * B + n) * G + q * H + u0 + uj] : 0.f;
+            pnx[q] = (valid && t + 1 < T) ? a.P[((size_t)(t + 1) * B + bb) * G + q * H + u0 + uj] : 0.f;
         }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
@@ -1487,7 +1493,7 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
     if (threadIdx.x < 64)
       xstore4(slot(t + 1) + (size_t)s * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xs + 4 * threadIdx.x));
     tr.mark(t, 5);
-    signal(a.flags + ((size_t)16 * (t + 1) + (s & 15)) * kFlagStride, a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
+    signal(flags + ((size_t)16 * (t + 1) + (s & 15)) * kFlagStride, a.full_fences);  // publish h_t (the barrier also protects `part` and `xs`)
     tr.mark(t, 6);
     // reserve and outputs: staged through LDS so that every store instruction writes 16-byte runs
     ro[(0 * 32 + n) * 8 + uj] = gi;
@@ -1500,9 +1506,10 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int idx = threadIdx.x + 256 * i;  // (array 0..5, batch row, half of the 8 units)
-      const int arr = idx >> 6, b2 = (idx >> 1) & 31, hf = idx & 1;
+      const int arr = idx >> 6, l2 = (idx >> 1) & 31, hf = idx & 1;
+      const int b2 = b0 + l2;
       if (idx < 384 && b2 < B) {
-        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 32 + b2) * 8 + 4 * hf);
+        const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 32 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
           *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
@@ -1521,27 +1528,33 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   }
 }
 
-// h0 [B][H] of one layer (zeros if null) -> exchange slot 0 in the layout of pers_fwdL_kernel, all 32 batch columns.
-__global__ void pack_stateL_kernel(const float* __restrict__ h0, float* __restrict__ hx, int B, int H) {
-  const long cnt = (long)32 * H;
+// h0 [B][H] of one layer (zeros if null) -> exchange slot 0 of every slice in the layout of pers_fwdL_kernel, all 32 batch columns.
+__global__ void pack_stateL_kernel(const float* __restrict__ h0, float* __restrict__ hx, int T, int B, int H, int b0,
+                                   int nsl) {
+  const long cnt = (long)nsl * 32 * H;
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < cnt; e += (long)gridDim.x * blockDim.x) {
-    const int k = (int)(e % H), bb = (int)(e / H);
+    const int k = (int)(e % H), lb = (int)((e / H) % 32), sl = (int)(e / ((long)H * 32));
+    const int bb = b0 + 32 * sl + lb;
     const int wv = k / (H / 4), kr = k % (H / 4), k8 = kr >> 3, m = (kr >> 1) & 3, kk = kr & 1;
-    hx[((size_t)wv * (H / 32) + k8) * 256 + (kk * 32 + bb) * 4 + m] = (h0 && bb < B) ? h0[(size_t)bb * H + k] : 0.f;
+    hx[(size_t)sl * (T + 1) * H * 32 + ((size_t)wv * (H / 32) + k8) * 256 + (kk * 32 + lb) * 4 + m] =
+        (h0 && bb < B) ? h0[(size_t)bb * H + k] : 0.f;
   }
 }
 
 // ------------------------------------------------------------------ one layer, large hidden size, backward
 // dh_{t-1} = R^T dA_t has K = 4H, four times the forward product: slicing it by output units would make
 // every workgroup read all of dA_t (1 MB per step at H = 2048).  The [4H x H] matrix is therefore cut in
-// two dimensions, NBK x NBK tiles of [4*UB gate rows x UB output units] (UB = 128: 256 tiles of 256 KB,
-// half in VGPRs, half in LDS).  Workgroup (i, j) multiplies the gate gradients of unit block i into a
-// partial sum for the output units of block j; the NBK partial sums of a block are then added -- always
-// in the order of i, so the result does not depend on arrival order -- by the same NBK workgroups, each
-// taking 8 of the block's 128 units, which also run the point-wise stage of the next step for those 8
-// units and publish their gate gradients to the NBK workgroups (j, .) that consume unit block j.
+// two dimensions, NBK x NBK tiles of [4*UB gate rows x UB output units] (UB = 128: tiles of 256 KB, half
+// in VGPRs, half in LDS; 256 tiles at H = 2048, 64 at H = 1024).  Workgroup (i, j) multiplies the gate
+// gradients of unit block i into a partial sum for the output units of block j; the NBK partial sums of a
+// block are then added -- always in the order of i, so the result does not depend on arrival order -- by
+// the same NBK workgroups, each taking UB/NBK of the block's 128 units (8 at H = 2048, 16 at H = 1024: one
+// or two cells per thread), which also run the point-wise stage of the next step for those units and
+// publish their gate gradients to the NBK workgroups (j, .) that consume unit block j.
 // Per step: 64 KB of dA read and 16 KB of partial sums written per workgroup, two synchronisation
 // hops of NBK arrivals each.  The gradient for the layer below is a batched GEMM after the launch.
+// The batch runs in slices of 32 rows, each with its own workgroups, exchange buffers and counters; at
+// H = 1024 four slices fit side by side on 256 CUs.
 // Exchange layouts: dA_t of a unit block: [k8][(kk*32 + n)*4 + m] for k = 8*k8 + 2*m + kk, batch row n,
 // where k8 = 4*(unit/8 within the block) + gate and k%8 = unit%8; partial sums: [unit in block][32].
 struct PersBwdLArgs {
@@ -1552,15 +1565,17 @@ struct PersBwdLArgs {
   const float* dhT;    // [B][H] or null
   const float* dcT;    // [B][H] or null
   float* dA;           // [T][B][4H] gate gradients (standard layout)
-  float* X;            // [T][NBK][4*UB*32] exchange
-  float* Pp;           // [T][NBK][NBK][UB*32] partial sums
+  float* X;            // [nsl][T][NBK][4*UB*32] exchange
+  float* Pp;           // [nsl][T][NBK][NBK][UB*32] partial sums
   float* dh0;          // [B][H] or null
   float* dc0;          // [B][H] or null
-  float* db;           // [4H] or null
-  int* flagsA;         // [T][NBK] counters: gate gradients of (step, unit block) published
-  int* flagsP;         // [T][NBK] counters: partial sums of (step, output block) published
+  float* db;           // [4H] or null (must be null when the batch has more than one slice: column sums follow instead)
+  int* flagsA;         // [nsl][T][NBK] counters: gate gradients of (step, unit block) published
+  int* flagsP;         // [nsl][T][NBK] counters: partial sums of (step, output block) published
   int* watchdog;
   int T, B;
+  int b0;              // first batch row of this launch (a multiple of 32)
+  int nsl;             // batch slices side by side in this launch (grid = nsl * NBK * NBK)
   int spin_limit;
   int full_fences;
   long long* trace;
@@ -1570,18 +1585,23 @@ struct PersBwdLArgs {
 template <int HH>
 __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   constexpr int H = HH, G = 4 * H, UB = 128, NBK = H / UB;
+  constexpr int UF = UB / NBK;               // units a workgroup finalises: 8 or 16
+  constexpr int CPT = UF / 8;                // cells per thread in the point-wise stage
   constexpr int NG8 = 4 * UB / 8;            // 8-k groups of the tile's K = 4*UB
   constexpr int KP = 4 * UB / 2;             // k-pairs; every wave runs all of them for its 32 output units
-  constexpr int RP = 128, LP = KP - RP;      // k-pairs with weights in registers / in LDS
+  constexpr int RP = UF == 16 ? 136 : 128;   // k-pairs with weights in registers (more where the staging arrays are larger)
+  constexpr int LP = KP - RP;                // k-pairs with weights in LDS
   constexpr int DEPTH = 16;
   static_assert(NBK % kFlagSub == 0, "arrivals must spread evenly over the counter lines");
+  static_assert(UF == 8 || UF == 16, "one or two cells per thread");
   extern __shared__ __attribute__((aligned(16))) float smem[];
-  float* const stage = smem;        // [UB][32] partial sums of this step; also the bias-gradient reduction
-  float* const xsA = smem + 4096;   // [4 gates][256] gate gradients of the 8 finalised units, exchange order
-  float* const ro = smem + 5120;    // [4 gates][32 batch rows][8 units] the same in standard order
-  float* const wl = smem + 6144;    // [4 waves][LP][64 lanes]
+  float* const stage = smem;              // [UB][32] partial sums of this step; also the bias-gradient reduction
+  float* const xsA = smem + 4096;         // [UF/8 octets][4 gates][256] gate gradients of the finalised units, exchange order
+  float* const ro = xsA + 1024 * CPT;     // [4 gates][32 batch rows][UF units] the same in standard order
+  float* const wl = ro + 128 * UF;        // [4 waves][LP][64 lanes]; 152 KB in all
 
-  const int i = blockIdx.x / NBK, j = blockIdx.x % NBK;
+  const int sl = blockIdx.x / (NBK * NBK), bid = blockIdx.x % (NBK * NBK);
+  const int i = bid / NBK, j = bid % NBK;
   const int T = a.T, B = a.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kk = lane >> 5, n = lane & 31;
@@ -1605,32 +1625,46 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     }
   }
 
-  // ---- the cell this thread finalises: unit UB*j + 8*i + 2*wave + kk, batch row n
+  // ---- the cells this thread finalises: units UB*j + UF*i + 8*c + 2*wave + kk (c < CPT), batch row b0 + n
   const int j8 = 2 * wave + kk;
-  const int cu = UB * j + 8 * i + j8;
-  const bool valid = n < B;
-  float dc = (valid && a.dcT) ? a.dcT[(size_t)n * H + cu] : 0.f;
-  float dh_rec = (valid && a.dhT) ? a.dhT[(size_t)n * H + cu] : 0.f;
-  float dbsum[4] = {0.f, 0.f, 0.f, 0.f};
+  const int bb = a.b0 + 32 * sl + n;
+  const bool valid = bb < B;
+  int cu[CPT];
+  float dc[CPT], dh_rec[CPT], dbsum[CPT][4];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    cu[c] = UB * j + UF * i + 8 * c + j8;
+    dc[c] = (valid && a.dcT) ? a.dcT[(size_t)bb * H + cu[c]] : 0.f;
+    dh_rec[c] = (valid && a.dhT) ? a.dhT[(size_t)bb * H + cu[c]] : 0.f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) dbsum[c][g] = 0.f;
+  }
   const float* const res_gates = a.res;
   const float* const res_c = a.res + TB * 4 * H;
-  auto slotX = [&](int t, int blk) { return a.X + ((size_t)t * NBK + blk) * (4 * UB * 32); };
-  auto slotP = [&](int t, int jb, int ib) { return a.Pp + (((size_t)t * NBK + jb) * NBK + ib) * (UB * 32); };
-  auto flagA = [&](int t, int blk) { return a.flagsA + ((size_t)t * NBK + blk) * kFlagInts; };
-  auto flagP = [&](int t, int blk) { return a.flagsP + ((size_t)t * NBK + blk) * kFlagInts; };
+  float* const Xs = a.X + (size_t)sl * T * NBK * (4 * UB * 32);
+  float* const Ps = a.Pp + (size_t)sl * T * NBK * NBK * (UB * 32);
+  int* const fA = a.flagsA + (size_t)sl * T * NBK * kFlagInts;
+  int* const fP = a.flagsP + (size_t)sl * T * NBK * kFlagInts;
+  auto slotX = [&](int t, int blk) { return Xs + ((size_t)t * NBK + blk) * (4 * UB * 32); };
+  auto slotP = [&](int t, int jb, int ib) { return Ps + (((size_t)t * NBK + jb) * NBK + ib) * (UB * 32); };
+  auto flagA = [&](int t, int blk) { return fA + ((size_t)t * NBK + blk) * kFlagInts; };
+  auto flagP = [&](int t, int blk) { return fP + ((size_t)t * NBK + blk) * kFlagInts; };
 
   // reserve values and upstream gradient of the step the point-wise stage handles next: fetched ahead,
   // under the MFMAs, so that no miss to HBM sits in front of a counter poll (loads return in order)
-  float fg[4], fct, fcp, fdo;
+  float fg[CPT][4], fct[CPT], fcp[CPT], fdo[CPT];
   auto fetch_step = [&](int t) {
     if (valid) {
-      const size_t e = ((size_t)t * B + n) * H + cu;
-      const size_t g0 = ((size_t)t * B + n) * G + cu;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) fg[g] = res_gates[g0 + (size_t)g * H];
-      fct = res_c[e];
-      fcp = t > 0 ? res_c[e - (size_t)B * H] : (a.c0 ? a.c0[(size_t)n * H + cu] : 0.f);
-      fdo = a.dout[e];
+      for (int c = 0; c < CPT; ++c) {
+        const size_t e = ((size_t)t * B + bb) * H + cu[c];
+        const size_t g0 = ((size_t)t * B + bb) * G + cu[c];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) fg[c][g] = res_gates[g0 + (size_t)g * H];
+        fct[c] = res_c[e];
+        fcp[c] = t > 0 ? res_c[e - (size_t)B * H] : (a.c0 ? a.c0[(size_t)bb * H + cu[c]] : 0.f);
+        fdo[c] = a.dout[e];
+      }
     }
   };
 
@@ -1638,34 +1672,45 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
-  // point-wise stage of step t for the 8 units of this workgroup, and publication of their gate gradients
+  // point-wise stage of step t for the UF units of this workgroup, and publication of their gate gradients
   auto pointwise_publish = [&](int t) {
-    float dA4[4] = {0.f, 0.f, 0.f, 0.f};
-    if (valid) {
-      const float dh = fdo + dh_rec;
-      const float tc = tanhf(fct);
-      const float dcv = dc + dh * fg[2] * (1.f - tc * tc);
-      dA4[0] = dcv * fg[3] * fg[0] * (1.f - fg[0]);
-      dA4[1] = dcv * fcp * fg[1] * (1.f - fg[1]);
-      dA4[2] = dh * tc * fg[2] * (1.f - fg[2]);
-      dA4[3] = dcv * fg[0] * (1.f - fg[3] * fg[3]);
-      dc = dcv * fg[1];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) dbsum[g] += dA4[g];
-    }
+    for (int c = 0; c < CPT; ++c) {
+      float dA4[4] = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
+        const float dh = fdo[c] + dh_rec[c];
+        const float tc = tanhf(fct[c]);
+        const float dcv = dc[c] + dh * fg[c][2] * (1.f - tc * tc);
+        dA4[0] = dcv * fg[c][3] * fg[c][0] * (1.f - fg[c][0]);
+        dA4[1] = dcv * fcp[c] * fg[c][1] * (1.f - fg[c][1]);
+        dA4[2] = dh * tc * fg[c][2] * (1.f - fg[c][2]);
+        dA4[3] = dcv * fg[c][0] * (1.f - fg[c][3] * fg[c][3]);
+        dc[c] = dcv * fg[c][1];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      xsA[g * 256 + (kk * 32 + n) * 4 + wave] = dA4[g];  // k%8 = j8 = 2*wave + kk: m = wave
-      ro[(g * 32 + n) * 8 + j8] = dA4[g];
+        for (int g = 0; g < 4; ++g) dbsum[c][g] += dA4[g];
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        xsA[(c * 4 + g) * 256 + (kk * 32 + n) * 4 + wave] = dA4[g];  // k%8 = j8 = 2*wave + kk: m = wave
+        ro[(g * 32 + n) * UF + 8 * c + j8] = dA4[g];
+      }
     }
     __syncthreads();
-    xstore4(slotX(t, j) + (size_t)(4 * i) * 256 + 4 * threadIdx.x, *reinterpret_cast<const floatx4*>(xsA + 4 * threadIdx.x));
+    // the unit octets of this workgroup are k8 blocks 4*(UF/8*i + c) + gate of the block's slot: contiguous
+#pragma unroll
+    for (int c = 0; c < CPT; ++c)
+      xstore4(slotX(t, j) + (size_t)(4 * (CPT * i + c)) * 256 + 4 * threadIdx.x,
+              *reinterpret_cast<const floatx4*>(xsA + c * 1024 + 4 * threadIdx.x));
     signal(flagA(t, j) + (i & (kFlagSub - 1)) * kFlagStride, a.full_fences);
-    {  // standard layout for the weight-gradient products: (gate, batch row, half of the 8 units) per thread
-      const int g = threadIdx.x >> 6, b2 = (threadIdx.x >> 1) & 31, hf = threadIdx.x & 1;
+    // standard layout for the weight-gradient products: (gate, batch row, four of the UF units) per store
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+      const int idx = threadIdx.x + 256 * q;
+      const int g = idx / (8 * UF), l2 = (idx / (UF / 4)) & 31, hf = idx % (UF / 4);
+      const int b2 = a.b0 + 32 * sl + l2;
       if (b2 < B)
-        *reinterpret_cast<floatx4*>(a.dA + ((size_t)t * B + b2) * G + (size_t)g * H + UB * j + 8 * i + 4 * hf) =
-            *reinterpret_cast<const floatx4*>(ro + (g * 32 + b2) * 8 + 4 * hf);
+        *reinterpret_cast<floatx4*>(a.dA + ((size_t)t * B + b2) * G + (size_t)g * H + UB * j + UF * i + 4 * hf) =
+            *reinterpret_cast<const floatx4*>(ro + (g * 32 + l2) * UF + 4 * hf);
     }
   };
 
@@ -1729,33 +1774,39 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     tr.mark(t, 3);
     w.wait(flagP(t, j), NBK);
     tr.mark(t, 4);
-    {  // dh_rec of this thread's cell: the NBK partial sums in fixed order
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {  // dh_rec of this thread's cells: the NBK partial sums in fixed order
       float pv[NBK];
 #pragma unroll
-      for (int ib = 0; ib < NBK; ++ib) pv[ib] = slotP(t, j, ib)[(8 * i + j8) * 32 + n];
+      for (int ib = 0; ib < NBK; ++ib) pv[ib] = slotP(t, j, ib)[(UF * i + 8 * c + j8) * 32 + n];
       float sum = 0.f;
 #pragma unroll
       for (int ib = 0; ib < NBK; ++ib) sum += pv[ib];
-      dh_rec = sum;
+      dh_rec[c] = sum;
     }
     tr.mark(t, 5);
     if (t > 0) pointwise_publish(t - 1);
     tr.mark(t, 6);
   }
   if (valid) {
-    if (a.dh0) a.dh0[(size_t)n * H + cu] = dh_rec;
-    if (a.dc0) a.dc0[(size_t)n * H + cu] = dc;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      if (a.dh0) a.dh0[(size_t)bb * H + cu[c]] = dh_rec[c];
+      if (a.dc0) a.dc0[(size_t)bb * H + cu[c]] = dc[c];
+    }
   }
-  if (a.db) {  // this workgroup owns its 8 units for every batch row: plain sums, no atomics
+  if (a.db) {  // single slice: this workgroup owns its units for every batch row, plain sums, no atomics
     __syncthreads();
 #pragma unroll
-    for (int g = 0; g < 4; ++g) stage[(g * 8 + j8) * 32 + n] = dbsum[g];
+    for (int c = 0; c < CPT; ++c)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) stage[(g * UF + 8 * c + j8) * 32 + n] = dbsum[c][g];
     __syncthreads();
-    if (threadIdx.x < 32) {
+    if (threadIdx.x < 4 * UF) {
       float sum = 0.f;
 #pragma unroll
-      for (int q = 0; q < 32; ++q) sum += stage[threadIdx.x * 32 + q];
-      a.db[(size_t)(threadIdx.x >> 3) * H + UB * j + 8 * i + (threadIdx.x & 7)] = sum;
+      for (int q = 0; q < 32; ++q) sum += stage[threadIdx.x * 32 + ((q + threadIdx.x) & 31)];
+      a.db[(size_t)(threadIdx.x / UF) * H + UB * j + UF * i + (threadIdx.x % UF)] = sum;
     }
   }
 }
@@ -1944,11 +1995,14 @@ void release_persistent() {
 }
 
 // Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
+// Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward).
+constexpr int kLargeMaxBatch1024 = 256;
+
 bool persistent_large(const Dims& d, bool backward) {
   const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");
   if (e && *e == '1') return false;
-  if (d.B > 32) return false;
-  if (backward ? d.H != 2048 : !(d.H == 1024 || d.H == 2048)) return false;  // H = 1024 backward: step / wavefront path
+  if (!(d.H == 1024 || d.H == 2048)) return false;
+  if (d.B > (d.H == 1024 ? kLargeMaxBatch1024 : 32)) return false;  // H = 2048 fills the chip with one slice of 32 rows
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return (backward ? (d.H / 128) * (d.H / 128) : d.H / 8) <= di.cus;
@@ -1977,7 +2031,7 @@ hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
     attr_set = true;
   }
   void* params[] = {const_cast<PersFwdLArgs*>(&a)};
-  return launch_resident(fn, HH / 8, params, (unsigned)smem, s);
+  return launch_resident(fn, a.nsl * (HH / 8), params, (unsigned)smem, s);
 }
 
 // Forward pass of the large-H shapes: per layer the batched input projection, then one persistent launch.
@@ -1988,22 +2042,32 @@ int run_forward_persistent_large(const FwdArgs& a) {
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P = reinterpret_cast<float*>(a.ws + a.w.P);
+  // slices of 32 batch rows side by side while the CUs last (two at H = 1024), the rest in further launches
+  DeviceInfo di;
+  (void)device_info(di);
+  const int slices = (d.B + 31) / 32;
+  int cap = di.cus / (d.H / 8);
+  if (cap < 1) cap = 1;
+  if (cap > 4) cap = 4;
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
-    {
-      ProfScope ps(LSTM_PHASE_FWD_PACK, s);
-      CK(launch_fill_zero(flags, ((size_t)d.T + 1) * 16 * kFlagStride * 4, s), "zero step counters");
-      hipLaunchKernelGGL(pack_stateL_kernel, dim3((unsigned)((32L * d.H + 255) / 256)), dim3(256), 0, s,
-                         a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.B, d.H);
-      CK(hipGetLastError(), "pack h0");
-    }
     {
       ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
       GemmProblem p{in, a.W + w_offset(d, l), P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
       CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
     }
+   for (int s0 = 0; s0 < slices; s0 += cap) {
+    const int nsl = slices - s0 < cap ? slices - s0 : cap;
+    {
+      ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+      CK(launch_fill_zero(flags, (size_t)nsl * (d.T + 1) * 16 * kFlagStride * 4, s), "zero step counters");
+      hipLaunchKernelGGL(pack_stateL_kernel, dim3((unsigned)((32L * nsl * d.H + 255) / 256)), dim3(256), 0, s,
+                         a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.T, d.B, d.H, 32 * s0, nsl);
+      CK(hipGetLastError(), "pack h0");
+    }
     PersFwdLArgs k;
+    k.b0 = 32 * s0; k.nsl = nsl;
     k.R = a.R + (size_t)l * G * d.H; k.bias = a.b + (size_t)l * G; k.P = P;
     k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
     k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
@@ -2016,14 +2080,15 @@ int run_forward_persistent_large(const FwdArgs& a) {
     k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     CK(d.H == 2048 ? launch_fwdL<2048>(k, s) : launch_fwdL<1024>(k, s), "persistent forward launch (large H)");
+   }
   }
   return LSTM_OK;
 }
 
 template <int HH>
 hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
-  constexpr int NBK = HH / 128, LP = 128;
-  const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
+  constexpr int NBK = HH / 128, UF = 128 / NBK, LP = 256 - (UF == 16 ? 136 : 128);
+  const size_t smem = (4096 + 128 * (size_t)UF + 128 * (size_t)UF + (size_t)4 * LP * 64) * sizeof(float);
   const void* fn = (const void*)pers_bwdL_kernel<HH>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -2032,7 +2097,7 @@ hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
     attr_set = true;
   }
   void* params[] = {const_cast<PersBwdLArgs*>(&a)};
-  return launch_resident(fn, NBK * NBK, params, (unsigned)smem, s);
+  return launch_resident(fn, a.nsl * NBK * NBK, params, (unsigned)smem, s);
 }
 
 }  // namespace
@@ -2049,37 +2114,47 @@ int run_backward_persistent_large(const BwdArgs& a) {
   const int NBK = d.H / UB;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
   hipStream_t s = a.stream;
+  // slices of 32 batch rows side by side while the CUs last (four at H = 1024), the rest in further launches
+  DeviceInfo di;
+  (void)device_info(di);
+  const int slices = (d.B + 31) / 32;
+  int cap = di.cus / (NBK * NBK);
+  if (cap < 1) cap = 1;
+  if (cap > 4) cap = 4;
+  const int maxsl = slices < cap ? slices : cap;
   float* dA_all = reinterpret_cast<float*>(a.ws + a.w.P);
   float* dxb = reinterpret_cast<float*>(a.ws + a.w.dx);
   float* X = reinterpret_cast<float*>(a.ws + a.w.xchg);
-  float* Pp = X + (size_t)d.T * NBK * (4 * UB * 32);
+  float* Pp = X + (size_t)maxsl * d.T * NBK * (4 * UB * 32);
   int* flagsA = reinterpret_cast<int*>(a.ws + a.w.flags);
-  int* flagsP = flagsA + (size_t)d.T * NBK * kFlagInts;
+  int* flagsP = flagsA + (size_t)maxsl * d.T * NBK * kFlagInts;
+  const bool bias_in_kernel = slices == 1;
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
     float* dA = dA_all + (size_t)l * TB * G;
-    {
-      ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-      CK(launch_fill_zero(flagsA, (size_t)2 * d.T * NBK * kFlagInts * 4, s), "zero step counters");
-    }
-    PersBwdLArgs k;
-    k.R = a.R + (size_t)l * G * d.H;
-    k.res = a.reserve + (size_t)l * TB * 6 * d.H;
-    k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
-    k.dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * d.H;
-    k.dhT = a.dhT ? a.dhT + (size_t)l * BH : nullptr;
-    k.dcT = a.dcT ? a.dcT + (size_t)l * BH : nullptr;
-    k.dA = dA; k.X = X; k.Pp = Pp;
-    k.dh0 = a.dh0 ? a.dh0 + (size_t)l * BH : nullptr;
-    k.dc0 = a.dc0 ? a.dc0 + (size_t)l * BH : nullptr;
-    k.db = a.db + (size_t)l * G;
-    k.flagsA = flagsA; k.flagsP = flagsP; k.watchdog = g_watch_dev;
-    k.T = d.T; k.B = d.B; k.spin_limit = spin_limit(); k.full_fences = full_fences();
-    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
-    k.trace_block = g_trace_block;
-    {
+    for (int s0 = 0; s0 < slices; s0 += cap) {
+      const int nsl = slices - s0 < cap ? slices - s0 : cap;
+      {
+        ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+        CK(launch_fill_zero(flagsA, (size_t)2 * maxsl * d.T * NBK * kFlagInts * 4, s), "zero step counters");
+      }
+      PersBwdLArgs k;
+      k.R = a.R + (size_t)l * G * d.H;
+      k.res = a.reserve + (size_t)l * TB * 6 * d.H;
+      k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
+      k.dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * d.H;
+      k.dhT = a.dhT ? a.dhT + (size_t)l * BH : nullptr;
+      k.dcT = a.dcT ? a.dcT + (size_t)l * BH : nullptr;
+      k.dA = dA; k.X = X; k.Pp = Pp;
+      k.dh0 = a.dh0 ? a.dh0 + (size_t)l * BH : nullptr;
+      k.dc0 = a.dc0 ? a.dc0 + (size_t)l * BH : nullptr;
+      k.db = bias_in_kernel ? a.db + (size_t)l * G : nullptr;
+      k.flagsA = flagsA; k.flagsP = flagsP; k.watchdog = g_watch_dev;
+      k.T = d.T; k.B = d.B; k.b0 = 32 * s0; k.nsl = nsl; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+      k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+      k.trace_block = g_trace_block;
       ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
-      CK(launch_bwdL<2048>(k, s), "persistent backward launch (large H)");
+      CK(d.H == 2048 ? launch_bwdL<2048>(k, s) : launch_bwdL<1024>(k, s), "persistent backward launch (large H)");
     }
     float* din = l > 0 ? dxb + (size_t)l * TB * d.H : a.dx;
     if (din) {
@@ -2088,7 +2163,7 @@ int run_backward_persistent_large(const BwdArgs& a) {
       CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
     }
   }
-  return weight_gradients(a, dA_all, true, true);
+  return weight_gradients(a, dA_all, true, bias_in_kernel);
 }
 
 }  // namespace

@@ -143,8 +143,7 @@ def test_persistent_shapes(cfg, with_states):
     run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
-# Large hidden sizes: forward on the one-layer-per-launch persistent kernel (recurrent matrix spread over all CUs),
-# backward on whatever the automatic choice is
+# Large hidden sizes: the one-layer-per-launch persistent kernels (recurrent matrix spread over all CUs)
 LARGE = [
     Config("l1024b32", L=2, T=5, B=32, I=96, H=1024, state_std=0.3, dstate_std=0.3),
     Config("l1024b7", L=1, T=4, B=7, I=1024, H=1024, state_std=0.3, dstate_std=0.3),
@@ -152,6 +151,12 @@ LARGE = [
     Config("l2048b5", L=1, T=3, B=5, I=64, H=2048, state_std=0.3, dstate_std=0.3),
     Config("l2048T1", L=2, T=1, B=1, I=2048, H=2048, state_std=0.3, dstate_std=0.3),   # a single step, a single row
     Config("l1024T1", L=1, T=1, B=32, I=16, H=1024, state_std=0.3, dstate_std=0.3),
+    # H = 1024 above 32 rows: slices of 32 side by side (two forward, four backward) and in further launches
+    Config("l1024b64", L=2, T=4, B=64, I=128, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l1024b33", L=1, T=3, B=33, I=1024, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l1024b100", L=2, T=3, B=100, I=64, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l1024b128", L=1, T=2, B=128, I=32, H=1024, state_std=0.3, dstate_std=0.3),
+    Config("l1024b160", L=1, T=2, B=160, I=48, H=1024, state_std=0.3, dstate_std=0.3),   # five slices: a second backward launch
 ]
 
 
@@ -160,6 +165,7 @@ LARGE = [
 def test_persistent_large_hidden(cfg, with_states):
     _, binding, _ = _mods()
     assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_PERSISTENT
     run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
