@@ -408,9 +408,9 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
           o_gate[ci][0] = sigmoidf_dev(sg[0]);
           o_gate[ci][1] = sigmoidf_dev(sg[1]);
           o_gate[ci][2] = sigmoidf_dev(sg[2]);
-          o_gate[ci][3] = tanhf(sg[3]);
+          o_gate[ci][3] = tanhf_dev(sg[3]);
           o_c[ci] = o_gate[ci][1] * c_state[c][ci] + o_gate[ci][0] * o_gate[ci][3];
-          o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
+          o_h[ci] = o_gate[ci][2] * tanhf_dev(o_c[ci]);
           c_state[c][ci] = o_c[ci];
           xs[(c_unit[ci] - u0) * BP + c_lb[ci]] = c_valid[c][ci] ? o_h[ci] : 0.f;
         }
@@ -579,9 +579,9 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       o_gate[ci][0] = sigmoidf_dev(sg[0]);
       o_gate[ci][1] = sigmoidf_dev(sg[1]);
       o_gate[ci][2] = sigmoidf_dev(sg[2]);
-      o_gate[ci][3] = tanhf(sg[3]);
+      o_gate[ci][3] = tanhf_dev(sg[3]);
       o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
-      o_h[ci] = o_gate[ci][2] * tanhf(o_c[ci]);
+      o_h[ci] = o_gate[ci][2] * tanhf_dev(o_c[ci]);
       c_state[ci] = o_c[ci];
       // unit offset ul = 4*kk + 2*up + ci: k4 block ul/4 = kk, m = up, parity ci; batch (n, tj)
       xs[kk * 256 + (ci * 32 + n) * 4 + 2 * up + tj] = valid ? o_h[ci] : 0.f;
@@ -966,7 +966,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float dh = dout[r] + dh_rec[c][r];
-          const float tc = tanhf(ct[c][r]);
+          const float tc = tanhf_dev(ct[c][r]);
           const float dcv = dc[c][r] + dh * go[c][r] * (1.f - tc * tc);
           dA4[0][r] = dcv * gg[c][r] * gi[c][r] * (1.f - gi[c][r]);
           dA4[1][r] = dcv * cp[c][r] * gf[c][r] * (1.f - gf[c][r]);
@@ -1183,10 +1183,16 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
         cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
       else
         cp = floatx4{0.f, 0.f, 0.f, 0.f};
-      if (!has_up) dpre = *reinterpret_cast<const floatx4*>(a.dy + e);
     }
   };
+  // The upstream gradient of step t (dy, or dx of the layer above) is fetched with them when it is there:
+  // `t_src` is t if it is published, else a step whose row this lane has already read (valid memory, value unused).
+  auto fetch_dout = [&](int t_src) {
+    if (pwv) dpre = *reinterpret_cast<const floatx4*>(dout_base + ((size_t)t_src * B + bb) * H + unit0);
+  };
   fetch_step(T - 1);
+  bool dpre_ok = !has_up;
+  if (dpre_ok) fetch_dout(T - 1);
 
   int seen_up = 0;
   for (int t = T - 1; t >= 0; --t) {
@@ -1199,7 +1205,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     tr.mark(t, 1);
     if (wave < 2) {
       floatx4 dout = {0.f, 0.f, 0.f, 0.f};
-      if (pwv) dout = has_up ? *reinterpret_cast<const floatx4*>(dout_base + e) : dpre;
+      if (pwv) dout = dpre_ok ? dpre : *reinterpret_cast<const floatx4*>(dout_base + e);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         if (pwv) {
@@ -1241,7 +1247,9 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     // ---- GEMM of step t: needs dA_t of every slice of this layer and batch half
     w.wait(flag(l, t + 1), NS2);
     tr.mark(t, 4);
-    seen_up = (has_up && t > 0) ? Waiter::peek(flag(l + 1, t - 1)) : 0;  // for the next point-wise stage
+    // counter of the layer above for the next point-wise stage: read now, looked at under the MFMAs
+    // (the top layer reads its own, already complete counter instead, so that this is one straight line)
+    seen_up = Waiter::peek_all(has_up ? flag(l + 1, t > 0 ? t - 1 : 0) : flag(l, t + 1));
     floatx16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -1271,7 +1279,12 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       for (int g = 0; g < NB8; ++g) {
         if (g + DEPTH < NB8) ldb(g + DEPTH);
         if (g + 2 < NB8) ldw(g + 2);
-        if (g == NB8 - DEPTH && t > 0) fetch_step(t - 1);  // behind the last exchange load of this step
+        if (g == NB8 - DEPTH) {  // behind the last exchange load of this step
+          Waiter::land(seen_up);
+          dpre_ok = t > 0 && (!has_up || (__all(seen_up >= NS2 / kFlagSub) && !w.dead));
+          if (t > 0) fetch_step(t - 1);
+          fetch_dout(dpre_ok ? t - 1 : t);
+        }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           const int pr = g * 4 + m;
@@ -1484,9 +1497,9 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
       sg[g] = (part[(0 * 16 + r) * 64 + lane] + part[(1 * 16 + r) * 64 + lane]) +
               (part[(2 * 16 + r) * 64 + lane] + part[(3 * 16 + r) * 64 + lane]) + pin[g] + c_bias[g];
     }
-    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gg = tanhf(sg[3]);
+    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gg = tanhf_dev(sg[3]);
     const float cv = gf * c_state + gi * gg;
-    const float hv = go * tanhf(cv);
+    const float hv = go * tanhf_dev(cv);
     c_state = cv;
     xs[((uj & 1) * 32 + n) * 4 + (uj >> 1)] = valid ? hv : 0.f;
     __syncthreads();
@@ -1679,7 +1692,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       float dA4[4] = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
         const float dh = fdo[c] + dh_rec[c];
-        const float tc = tanhf(fct[c]);
+        const float tc = tanhf_dev(fct[c]);
         const float dcv = dc[c] + dh * fg[c][2] * (1.f - tc * tc);
         dA4[0] = dcv * fg[c][3] * fg[c][0] * (1.f - fg[c][0]);
         dA4[1] = dcv * fcp[c] * fg[c][1] * (1.f - fg[c][1]);

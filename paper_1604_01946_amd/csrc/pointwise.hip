@@ -23,7 +23,7 @@ __global__ void ew_kernel(int op, float* __restrict__ out, long ldo, const float
       case EW_ADD: v = av + b[r * ldb + c]; break;
       case EW_ADD_BIAS: v = av + b[c]; break;
       case EW_SIGMOID: v = sigmoidf_dev(av); break;
-      case EW_TANH: v = tanhf(av); break;
+      case EW_TANH: v = tanhf_dev(av); break;
       case EW_MUL: v = av * b[r * ldb + c]; break;
       case EW_FMA_MUL: v = out[r * ldo + c] + av * b[r * ldb + c]; break;
       default: v = av; break;
@@ -49,10 +49,10 @@ __global__ void pointwise_fwd_kernel(const float* __restrict__ pre1, const float
       a[q] = pre1[g0 + (long)q * H] + bias[q * H + j];
       if (pre2) a[q] += pre2[g0 + (long)q * H];
     }
-    const float ig = sigmoidf_dev(a[0]), fg = sigmoidf_dev(a[1]), og = sigmoidf_dev(a[2]), gg = tanhf(a[3]);
+    const float ig = sigmoidf_dev(a[0]), fg = sigmoidf_dev(a[1]), og = sigmoidf_dev(a[2]), gg = tanhf_dev(a[3]);
     const float cp = c_prev ? c_prev[e] : 0.f;
     const float c = fg * cp + ig * gg;
-    const float h = og * tanhf(c);
+    const float h = og * tanhf_dev(c);
     gates_out[g0] = ig; gates_out[g0 + H] = fg; gates_out[g0 + 2L * H] = og; gates_out[g0 + 3L * H] = gg;
     c_out[e] = c; h_out[e] = h;
     if (h_out2) h_out2[e] = h;
@@ -69,7 +69,7 @@ __global__ void pointwise_bwd_kernel(const float* __restrict__ gates, const floa
     const int bb = (int)(e / H), j = (int)(e % H);
     const long g0 = (long)bb * 4 * H + j;
     const float ig = gates[g0], fg = gates[g0 + H], og = gates[g0 + 2L * H], gg = gates[g0 + 3L * H];
-    const float tc = tanhf(c_t[e]);
+    const float tc = tanhf_dev(c_t[e]);
     float dh = 0.f;
     if (dh_a) dh += dh_a[e];
     if (dh_b) dh += dh_b[e];

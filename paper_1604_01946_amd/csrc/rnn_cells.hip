@@ -35,13 +35,13 @@ __global__ void cell_fwd_kernel(int cell, const float* __restrict__ P, const flo
       const float r = sigmoidf_dev(p[u] + bias[u] + q[u]);
       const float z = sigmoidf_dev(p[H + u] + bias[H + u] + q[H + u]);
       const float qn = q[2 * H + u];
-      const float n = tanhf(p[2 * H + u] + bias[2 * H + u] + r * qn);
+      const float n = tanhf_dev(p[2 * H + u] + bias[2 * H + u] + r * qn);
       out = (1.f - z) * n + z * (hp ? hp[e] : 0.f);
       float* s4 = sv + row * 4 * H;
       s4[u] = r; s4[H + u] = z; s4[2 * H + u] = n; s4[3 * H + u] = qn;
     } else {
       const float a = p[u] + bias[u] + q[u];
-      out = cell == RNN_CELL_TANH ? tanhf(a) : fmaxf(a, 0.f);
+      out = cell == RNN_CELL_TANH ? tanhf_dev(a) : fmaxf(a, 0.f);
     }
     h[e] = out;
     if (y) y[e] = out;

@@ -187,10 +187,10 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
       const long g0 = (long)bb * 4 * H + unit, e = (long)bb * H + unit;
 #pragma unroll
       for (int r = 0; r < 4; ++r) s[r] += a.P[g0 + (long)r * H] + a.bias[r * H + unit];
-      const float ig = sigmoidf_dev(s[0]), fg = sigmoidf_dev(s[1]), og = sigmoidf_dev(s[2]), gg = tanhf(s[3]);
+      const float ig = sigmoidf_dev(s[0]), fg = sigmoidf_dev(s[1]), og = sigmoidf_dev(s[2]), gg = tanhf_dev(s[3]);
       const float cp = a.c_prev ? a.c_prev[e] : 0.f;
       const float c = fg * cp + ig * gg;
-      const float h = og * tanhf(c);
+      const float h = og * tanhf_dev(c);
       a.gates_out[g0] = ig; a.gates_out[g0 + H] = fg; a.gates_out[g0 + 2L * H] = og; a.gates_out[g0 + 3L * H] = gg;
       a.c_out[e] = c; a.h_out[e] = h;
       if (a.h_out2) a.h_out2[e] = h;
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256) void step_bwd_kernel(const StepBwdArgs a) {
       }
       dh += a.dout[e];
       const float ig = a.gates[g0], fg = a.gates[g0 + H], og = a.gates[g0 + 2L * H], gg = a.gates[g0 + 3L * H];
-      const float tc = tanhf(a.c_t[e]);
+      const float tc = tanhf_dev(a.c_t[e]);
       const float dc = (a.dc_in ? a.dc_in[e] : 0.f) + dh * og * (1.f - tc * tc);
       const float cp = a.c_prev ? a.c_prev[e] : 0.f;
       a.dA[g0] = dc * gg * ig * (1.f - ig);

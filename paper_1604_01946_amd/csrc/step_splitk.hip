@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, c
     floatx4 o0, o1, o2, o3, dco;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float tc = tanhf(ct[r]);
+      const float tc = tanhf_dev(ct[r]);
       const float dc = dci[r] + dh[r] * go[r] * (1.f - tc * tc);
       o0[r] = dc * gg[r] * gi[r] * (1.f - gi[r]);
       o1[r] = dc * cp[r] * gf[r] * (1.f - gf[r]);
