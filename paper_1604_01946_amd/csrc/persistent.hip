@@ -334,10 +334,13 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       // Loads are issued in bulk ahead of the MFMAs that consume them (the scheduling barriers keep
       // the compiler from re-serialising them): a step is bound by load latency otherwise.
       const bool do_in = l > 0, do_rec = (t > 0 || a.has_h0);
-      const int seen_in = do_in ? Waiter::peek(flag(l - 1, t + 1, c)) : 0;
-      const int seen_rec = (t > 0) ? Waiter::peek(flag(l, t, c)) : 0;
+      // both counters are read at once, without branches, so that their round trips overlap (a counter that
+      // does not apply is replaced by one that exists; its value is not used)
+      int seen_in = Waiter::peek_all(do_in ? flag(l - 1, t + 1, c) : flag(l, t > 0 ? t : 1, c));
+      int seen_rec = Waiter::peek_all(flag(l, t > 0 ? t : 1, c));
       float bi[KG][NT], br[KG][NT];
       if (do_in) {  // input half: h of the layer below at this step
+        Waiter::land(seen_in);
         w.wait(flag(l - 1, t + 1, c), NS, seen_in);
         const float* src = slot(l - 1, t + 1, c) + boff;
 #pragma unroll
@@ -354,6 +357,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       }
       if (do_rec) {  // recurrent half: own layer, previous step; its loads fly under the rest of the input half
+        Waiter::land(seen_rec);
         if (t > 0) w.wait(flag(l, t, c), NS, seen_rec);
         if (c == 0) tr.mark(t, 2);
         const float* src = slot(l, t, c) + boff;
@@ -953,6 +957,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
       floatx4 dA4[4];
       const size_t e = ((size_t)t * B + bb) * H + unit0;
       const size_t g0 = ((size_t)t * B + bb) * G + unit0;
+      Waiter::land(seen_up[c]);
       if (has_up) w.wait(flag(l + 1, t, c), NS, seen_up[c]);  // dx of the layer above at step t is published
       if (c == 0) tr.mark(t, 1);
       if (fin && q < 2 && !pw[c]) {  // padded batch columns of the staged tile
@@ -1000,7 +1005,9 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
       // ---- GEMM of step t: needs dA_t of every slice of this layer
       w.wait(flag(l, t + 1, c), NS);
       if (c == 0) tr.mark(t, 4);
-      seen_up[c] = (has_up && t > 0) ? Waiter::peek(flag(l + 1, t - 1, c)) : 0;  // for the next point-wise stage
+      // counter of the layer above for the next point-wise stage, read without a branch and consumed there
+      // (the top layer reads its own, already complete counter instead)
+      seen_up[c] = Waiter::peek_all(has_up ? flag(l + 1, t > 0 ? t - 1 : 0, c) : flag(l, t + 1, c));
       floatx4 acc[NT];
 #pragma unroll
       for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
