@@ -24,9 +24,9 @@ PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernels at cfg3, from two rocprofv3 --pmc passes (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/cfg3_hbm_traffic_pmc.md
-PMC_TRAFFIC_BYTES = {("cfg3", "bwd_recurrence"): int((563.8 + 439.4) * 2**20),
-                     ("cfg3", "fwd_recurrence"): int((306.7 + 364.3) * 2**20),
-                     ("cfg3", "weight_grad"): int((497.8 + 32.0 + 19.2 + 16.0) * 2**20)}
+PMC_TRAFFIC_BYTES = {("cfg3", "bwd_recurrence"): int((572.1 + 451.9) * 2**20),
+                     ("cfg3", "fwd_recurrence"): int((237.0 + 364.3) * 2**20),
+                     ("cfg3", "weight_grad"): int((497.7 + 32.0 + 19.2 + 16.0) * 2**20)}
 
 
 def parse():
