@@ -216,6 +216,7 @@ struct PersFwdArgs {
   const float* xin;   // wide kernel, I == H: x in exchange layout, [nsl][T+1][H*64] with slot t+1 = x_t; layer 0 then
                       // multiplies by W_0 itself, step by step, like the layers above it
   const float* c0;    // [L][B][H] or null
+  const float* h0;    // [L][B][H] or null: read by the GRU variant of the wide kernel (its cell update needs h_{t-1})
   float* hx;          // [L][T+1][NC][H][BP] exchange, slot t+1 = h_t, slot 0 = h0
   int* flags;         // [L][T+1][NC], slot t+1 counts the slices of layer l that finished step t
   int* watchdog;
@@ -483,9 +484,13 @@ __global__ void pack_state_kernel(const float* __restrict__ h0, float* __restric
 // Exchange layout of one (layer, step) slot: for k = 4*k4 + 2*m + kk and batch b = 2n + j, element
 // ((k4*2 + kk)*32 + n)*4 + 2*m + j -- lane (kk, n) fetches two k-pairs of both tiles with one
 // 16-byte load, 1 KB per wave and instruction.
-template <int HH>
+// CELL = 1 runs a GRU on the same machinery (convention of rnn.h: gates r, z, n; the reset gate multiplies the
+// recurrent product): the four row groups of a workgroup's tile are then r, z, the input half of n (W_n x, no
+// recurrent weights) and the recurrent half of n (R_n h, no input weights) -- a quarter of the MFMA work
+// multiplies zeros, everything else is unchanged.  Its reserve is h [T][B][H] followed by r, z, n, R_n h as [T][B][4H].
+template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
-  constexpr int H = HH, G = 4 * H, NS = H / 8;
+  constexpr int H = HH, NG = CELL == 0 ? 4 : 3, G = NG * H, NS = H / 8;  // G: rows of W, R, b and of the projection P0
   constexpr int NK4 = H / 16;  // 4-k groups per wave and operand half
   __shared__ float part[4][32][64];
   __shared__ __attribute__((aligned(16))) float xs[512];  // this step's h slice in exchange order
@@ -509,16 +514,20 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   float wR[NK4][2], wW[NK4][2];
   {
     const float* Rl = a.R + (size_t)l * G * H;
-    const float* Wl = l > 0 ? a.W + (size_t)4 * H * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [4H][I], read if I == H
-    const size_t row = ((size_t)(n >> 3) * H + u0 + (n & 7)) * H;
+    const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I], read if I == H
+    const int grp = n >> 3;
+    // matrix row behind tile row group grp: the gate itself (LSTM); r, z, n (input half), n (recurrent half) for the GRU
+    const int gate = (CELL == 1 && grp == 3) ? 2 : grp;
+    const bool useR = CELL == 0 || grp != 2, useW = (CELL == 0 || grp != 3) && (l > 0 || a.xin);
+    const size_t row = ((size_t)gate * H + u0 + (n & 7)) * H;
 #pragma unroll
     for (int i = 0; i < NK4; ++i) {
       const int k4 = (i + rot) & (NK4 - 1);
 #pragma unroll
       for (int m = 0; m < 2; ++m) {
         const int k = wave * (H / 4) + 4 * k4 + 2 * m + kk;
-        wR[i][m] = Rl[row + k];
-        wW[i][m] = (l > 0 || a.xin) ? Wl[row + k] : 0.f;
+        wR[i][m] = useR ? Rl[row + k] : 0.f;
+        wW[i][m] = useW ? Wl[row + k] : 0.f;
       }
     }
   }
@@ -530,19 +539,20 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
   const int bb = b0 + lb;      // batch row in the tensors
   const bool valid = bb < B;
   int c_unit[2];
-  float c_state[2], c_bias[2][4];
+  float c_state[2], c_bias[2][4];  // c_state: c_{t-1} (LSTM), h_{t-1} (GRU)
 #pragma unroll
   for (int ci = 0; ci < 2; ++ci) {
     c_unit[ci] = u0 + 4 * kk + 2 * up + ci;
-    c_state[ci] = (valid && a.c0) ? a.c0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
+    const float* const s0 = CELL == 0 ? a.c0 : a.h0;
+    c_state[ci] = (valid && s0) ? s0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) c_bias[ci][g] = a.bias[(size_t)l * G + g * H + c_unit[ci]];
+    for (int g = 0; g < 4; ++g) c_bias[ci][g] = g < NG ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
   }
 
-  float* const res_l = a.res + (size_t)l * TB * 6 * H;
-  float* const res_gates = res_l;
-  float* const res_c = res_l + TB * 4 * H;
-  float* const res_h = res_l + TB * 5 * H;
+  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // the four saved arrays, [T][B][4H]
+  float* const res_c = res_l + TB * 4 * H;                       // LSTM only
+  float* const res_h = CELL == 0 ? res_l + TB * 5 * H : res_l;
   float* const hx = a.hx + (size_t)sl * a.L * (T + 1) * H * 64;
   int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * kFlagInts;
   auto slot = [&](int layer, int st) { return hx + ((size_t)layer * (T + 1) + st) * H * 64; };
@@ -580,13 +590,23 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         sg[g] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]) +
                 pin[ci][g] + c_bias[ci][g];
       }
-      o_gate[ci][0] = sigmoidf_dev(sg[0]);
-      o_gate[ci][1] = sigmoidf_dev(sg[1]);
-      o_gate[ci][2] = sigmoidf_dev(sg[2]);
-      o_gate[ci][3] = tanhf_dev(sg[3]);
-      o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
-      o_h[ci] = o_gate[ci][2] * tanhf_dev(o_c[ci]);
-      c_state[ci] = o_c[ci];
+      if (CELL == 0) {
+        o_gate[ci][0] = sigmoidf_dev(sg[0]);
+        o_gate[ci][1] = sigmoidf_dev(sg[1]);
+        o_gate[ci][2] = sigmoidf_dev(sg[2]);
+        o_gate[ci][3] = tanhf_dev(sg[3]);
+        o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
+        o_h[ci] = o_gate[ci][2] * tanhf_dev(o_c[ci]);
+        c_state[ci] = o_c[ci];
+      } else {  // sg: r and z pre-activations, W_n x + b_n, R_n h
+        o_gate[ci][0] = sigmoidf_dev(sg[0]);
+        o_gate[ci][1] = sigmoidf_dev(sg[1]);
+        o_gate[ci][2] = tanhf_dev(sg[2] + o_gate[ci][0] * sg[3]);
+        o_gate[ci][3] = sg[3];
+        o_h[ci] = (1.f - o_gate[ci][1]) * o_gate[ci][2] + o_gate[ci][1] * c_state[ci];
+        o_c[ci] = 0.f;
+        c_state[ci] = o_h[ci];
+      }
       // unit offset ul = 4*kk + 2*up + ci: k4 block ul/4 = kk, m = up, parity ci; batch (n, tj)
       xs[kk * 256 + (ci * 32 + n) * 4 + 2 * up + tj] = valid ? o_h[ci] : 0.f;
     }
@@ -617,10 +637,12 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
-          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
+          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
         } else if (arr == 4) {
-          *reinterpret_cast<floatx4*>(res_c + e) = v;
-          if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
+          if (CELL == 0) {
+            *reinterpret_cast<floatx4*>(res_c + e) = v;
+            if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
+          }
         } else {
           *reinterpret_cast<floatx4*>(res_h + e) = v;
           if (l == a.L - 1) *reinterpret_cast<floatx4*>(a.y + e) = v;
@@ -638,7 +660,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
 #pragma unroll
     for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) pin[ci][g] = valid ? a.P0[(size_t)bb * G + g * H + c_unit[ci]] : 0.f;
+      for (int g = 0; g < 4; ++g) pin[ci][g] = (valid && g < NG) ? a.P0[(size_t)bb * G + g * H + c_unit[ci]] : 0.f;
     for (int t = 0; t < T; ++t) {
       tr.mark(t, 0);
       hide(rv);
@@ -658,7 +680,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
       for (int ci = 0; ci < 2; ++ci)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          pnx[ci][g] = (valid && t + 1 < T) ? a.P0[((size_t)(t + 1) * B + bb) * G + g * H + c_unit[ci]] : 0.f;
+          pnx[ci][g] = (valid && t + 1 < T && g < NG) ? a.P0[((size_t)(t + 1) * B + bb) * G + g * H + c_unit[ci]] : 0.f;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < NK4; ++i)
@@ -851,6 +873,7 @@ struct PersBwdArgs {
   int full_fences;
   long long* trace;
   int trace_block;
+  const float* h0;     // [L][B][H] or null: read by the GRU variant of the wide kernel
 };
 
 // KGB: k-groups (of 4) per wave = H/4 (wave w covers the rows of gate w).  NT, NC as in the forward kernel.
@@ -1085,9 +1108,14 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 // Exchange layout of one (layer, step, half) slot: for k = 8*k8 + 2*m + kk and batch row n,
 // element ((k8*2 + kk)*32 + n)*4 + m -- lane (kk, n) of a wave fetches the four k-pairs of an
 // 8-k group with one 16-byte load, 1 KB per wave and instruction.
-template <int HH>
+// CELL = 1: GRU (see pers_fwd32_kernel).  The four K groups are then the gradients with respect to the r and z
+// pre-activations, to W_n x + b_n, and to R_n h; the recurrent rows of the tile have no weights in the third group,
+// the input rows none in the fourth, and dh_{t-1} also receives dh_t o z_t directly.  The arrays c0 / dcT / dc0 of
+// the arguments are not used; `res` is the GRU reserve, W / R / db have 3H rows.
+template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, const int NBH) {
-  constexpr int H = HH, G = 4 * H, NS2 = H / 16;
+  constexpr int H = HH, G = 4 * H, NS2 = H / 16;  // G: width of the gate-gradient arrays (four groups for both cells)
+  constexpr int NG = CELL == 0 ? 4 : 3, GW = NG * H;  // rows of W, R, db
   constexpr int NB8 = H / 8;                 // 8-k groups per wave (wave w covers the rows of gate w)
   constexpr int KPW = H / 2;                 // k-pairs per wave
   constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
@@ -1123,14 +1151,17 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   // ---- weights: A operand row rho = lane%32 (< 16: column u0+rho of R_l, >= 16: column u0+rho-16 of W_l)
   float wreg[RP];
   {
-    const float* Rl = a.R + (size_t)l * G * H;
-    const float* Wl = a.W + (size_t)4 * H * a.I + (size_t)(l > 0 ? l - 1 : 0) * G * H;
-    const float* src = (n < 16) ? Rl + u0 + n : (l > 0 ? Wl : a.W) + u0 + (n - 16);  // layer 0: its own [4H][I], I == H
-    const bool live = (n < 16) || (l > 0) || a.dx0;
+    const float* Rl = a.R + (size_t)l * GW * H;
+    const float* Wl = a.W + (size_t)GW * a.I + (size_t)(l > 0 ? l - 1 : 0) * GW * H;
+    const float* src = (n < 16) ? Rl + u0 + n : (l > 0 ? Wl : a.W) + u0 + (n - 16);  // layer 0: its own [GW][I], I == H
+    // matrix row block behind K group `wave`: the gate itself (LSTM); GRU: r, z, then n for the input rows only,
+    // then n for the recurrent rows only
+    const int gate = (CELL == 1 && wave == 3) ? 2 : wave;
+    const bool live = ((n < 16) || (l > 0) || a.dx0) && (CELL == 0 || (n < 16 ? wave != 2 : wave != 3));
 #pragma unroll
     for (int i = 0; i < KPW; ++i) {
       const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
-      const float v = live ? src[(size_t)(wave * H + 8 * k8 + 2 * m + kk) * H] : 0.f;
+      const float v = live ? src[(size_t)(gate * H + 8 * k8 + 2 * m + kk) * H] : 0.f;
       if (i < RP)
         wreg[i < RP ? i : 0] = v;
       else
@@ -1144,20 +1175,21 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
   const bool pwv = wave < 2 && bb < B;
   const bool dxl = wave >= 2 && bb < B && (l > 0 || a.dx0);
   const int unit0 = u0 + 8 * (wave & 1) + 4 * kk;
-  float dc[4], dh_rec[4];
+  float dc[4], dh_rec[4];  // dc: carried cell gradient (LSTM); the direct term dh_t o z_t (GRU)
   float dbsum[4][4];  // this lane's share of the bias gradient: sum over t of dA_t, per (gate, unit)
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
-    dc[r] = (pwv && a.dcT) ? a.dcT[se] : 0.f;
+    dc[r] = (CELL == 0 && pwv && a.dcT) ? a.dcT[se] : 0.f;
     dh_rec[r] = (pwv && a.dhT) ? a.dhT[se] : 0.f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) dbsum[g][r] = 0.f;
   }
 
-  const float* const res_l = a.res + (size_t)l * TB * 6 * H;
-  const float* const res_gates = res_l;
-  const float* const res_c = res_l + TB * 4 * H;
+  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  const float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // the four saved arrays, [T][B][4H]
+  const float* const res_c = CELL == 0 ? res_l + TB * 4 * H : res_l;   // c (LSTM) or h (GRU): the state whose previous value the step needs
+  const float* const s0 = CELL == 0 ? a.c0 : a.h0;
   float* const dA_l = a.dA + (size_t)l * TB * G;
   const bool has_up = l < a.L - 1;
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
@@ -1183,11 +1215,11 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
       go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
       gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
-      ct = *reinterpret_cast<const floatx4*>(res_c + e);
+      if (CELL == 0) ct = *reinterpret_cast<const floatx4*>(res_c + e);
       if (t > 0)
         cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
-      else if (a.c0)
-        cp = *reinterpret_cast<const floatx4*>(a.c0 + ((size_t)l * B + bb) * H + unit0);
+      else if (s0)
+        cp = *reinterpret_cast<const floatx4*>(s0 + ((size_t)l * B + bb) * H + unit0);
       else
         cp = floatx4{0.f, 0.f, 0.f, 0.f};
     }
@@ -1217,13 +1249,22 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       for (int r = 0; r < 4; ++r) {
         if (pwv) {
           const float dh = dout[r] + dh_rec[r];
-          const float tc = tanhf(ct[r]);
-          const float dcv = dc[r] + dh * go[r] * (1.f - tc * tc);
-          dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
-          dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
-          dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
-          dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
-          dc[r] = dcv * gf[r];
+          if (CELL == 0) {
+            const float tc = tanhf(ct[r]);
+            const float dcv = dc[r] + dh * go[r] * (1.f - tc * tc);
+            dA4[0][r] = dcv * gg[r] * gi[r] * (1.f - gi[r]);
+            dA4[1][r] = dcv * cp[r] * gf[r] * (1.f - gf[r]);
+            dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
+            dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
+            dc[r] = dcv * gf[r];
+          } else {  // gi, gf, go, gg hold r, z, n, R_n h; cp holds h_{t-1}
+            const float dn = dh * (1.f - gf[r]) * (1.f - go[r] * go[r]);
+            dA4[0][r] = dn * gg[r] * gi[r] * (1.f - gi[r]);
+            dA4[1][r] = dh * (cp[r] - go[r]) * gf[r] * (1.f - gf[r]);
+            dA4[2][r] = dn;
+            dA4[3][r] = dn * gi[r];
+            dc[r] = dh * gf[r];
+          }
 #pragma unroll
           for (int g = 0; g < 4; ++g) dbsum[g][r] += dA4[g][r];
         }
@@ -1317,7 +1358,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       }
       if (wave < 2) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) dh_rec[r] = v[r];
+        for (int r = 0; r < 4; ++r) dh_rec[r] = CELL == 0 ? v[r] : v[r] + dc[r];
       } else if (dxl) {
         xstore4(dx_out + ((size_t)t * B + bb) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
       }
@@ -1330,7 +1371,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     for (int r = 0; r < 4; ++r) {
       const size_t se = ((size_t)l * B + bb) * H + unit0 + r;
       if (a.dh0) a.dh0[se] = dh_rec[r];
-      if (a.dc0) a.dc0[se] = dc[r];
+      if (CELL == 0 && a.dc0) a.dc0[se] = dc[r];
     }
   }
   // Bias gradient (Section 2.6 lists it with the weight update): the per-lane sums over t are added
@@ -1345,12 +1386,12 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
         for (int g = 0; g < 4; ++g) part[(g * 16 + 8 * wave + 4 * kk + r) * 32 + n] = dbsum[g][r];
     }
     __syncthreads();
-    if (threadIdx.x < 64) {
+    if (threadIdx.x < 16 * NG) {
       const int g = threadIdx.x >> 4, ul = threadIdx.x & 15;
       float sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 32; ++i) sum += part[threadIdx.x * 32 + ((i + threadIdx.x) & 31)];
-      atomicAdd(a.db + (size_t)l * G + g * H + u0 + ul, sum);
+      atomicAdd(a.db + (size_t)l * GW + g * H + u0 + ul, sum);
     }
   }
 }
@@ -1961,10 +2002,11 @@ bool fwd_wide(const Dims& d) {
   return d.B > 32;
 }
 
+template <int CELL>
 hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
-  const void* fn = H == 512 ? (const void*)pers_fwd32_kernel<512>
-                            : (H == 256 ? (const void*)pers_fwd32_kernel<256> : (const void*)pers_fwd32_kernel<128>);
+  const void* fn = H == 512 ? (const void*)pers_fwd32_kernel<512, CELL>
+                            : (H == 256 ? (const void*)pers_fwd32_kernel<256, CELL> : (const void*)pers_fwd32_kernel<128, CELL>);
   return launch_resident(fn, grid, params, 0, s);
 }
 
@@ -1976,11 +2018,11 @@ bool bwd_wide(const Dims& d) {
   return d.B > 32;
 }
 
-template <int HH>
+template <int HH, int CELL = 0>
 hipError_t launch_bwd32(const PersBwdArgs& a, int nbh, hipStream_t s) {
   constexpr int KPW = HH / 2, LP = KPW > 128 ? KPW - 128 : 0;
   const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
-  const void* fn = (const void*)pers_bwd32_kernel<HH>;
+  const void* fn = (const void*)pers_bwd32_kernel<HH, CELL>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -2188,20 +2230,32 @@ int run_backward_persistent_large(const BwdArgs& a) {
 
 }  // namespace
 
-int run_forward_persistent(const FwdArgs& a) {
+// Wide persistent kernels for the GRU: hidden sizes and CU budget of the LSTM ones, more than 32 batch rows.
+bool gru_persistent_supported(const Dims& d) {
+  if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
+  if (d.B > 512 || !fwd_wide(d) || !bwd_wide(d)) return false;
+  DeviceInfo di;
+  if (!device_info(di) || !di.coop) return false;
+  return (long)d.L * (d.H / 8) <= di.cus;
+}
+
+// cell: 0 = LSTM; 1 = GRU (wide kernels only: the caller has checked gru_persistent_supported; a.c0 / a.cT are null,
+// W, R, b have 3H rows and a.reserve is the GRU reserve).
+int run_forward_persistent(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
-  if (persistent_large(d, false)) {
+  if (cell == 0 && persistent_large(d, false)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_forward_persistent_large(a);
   }
-  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
+  const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : 3) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
   const int BP = 16 * bp.NT;
   const bool wide = fwd_wide(d);
+  if (cell != 0 && !wide) return LSTM_UNSUPPORTED;
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
@@ -2213,7 +2267,7 @@ int run_forward_persistent(const FwdArgs& a) {
     const char* e = getenv("LSTM_FWD_BATCHED_INPUT");
     if (e && *e == '1') x_in_kernel = false;
     const size_t rows = (size_t)(d.B + 63) / 64 * 64;  // the copy of x: T+1 slots of H x 64 per slice
-    if (((size_t)d.T + 1) * rows * d.H > (size_t)d.L * TB * G) x_in_kernel = false;
+    if (((size_t)d.T + 1) * rows * d.H > (size_t)d.L * TB * 4 * d.H) x_in_kernel = false;
   }
   if (!x_in_kernel) {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
@@ -2222,7 +2276,7 @@ int run_forward_persistent(const FwdArgs& a) {
   }
   PersFwdArgs k;
   k.xin = x_in_kernel ? P0 : nullptr;
-  k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
+  k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.h0 = a.h0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
   k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();
   k.full_fences = full_fences();
@@ -2262,7 +2316,7 @@ int run_forward_persistent(const FwdArgs& a) {
     }
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (wide) e = launch_fwd32(d.H, grid * nsl, k, s);
+    if (wide) e = cell == 0 ? launch_fwd32<0>(d.H, grid * nsl, k, s) : launch_fwd32<1>(d.H, grid * nsl, k, s);
     else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
     else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
     else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
@@ -2271,23 +2325,27 @@ int run_forward_persistent(const FwdArgs& a) {
   return LSTM_OK;
 }
 
-int run_backward_persistent(const BwdArgs& a) {
+// cell as in run_forward_persistent.  For the GRU the function stops after the propagation (gate gradients
+// [L][T*B][4H] at the start of the workspace: r, z, n, and n times r) and reports in *bias_done whether db is complete;
+// the caller forms the weight gradients.
+int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
   const Dims& d = a.d;
-  if (persistent_large(d, true)) {
+  if (cell == 0 && persistent_large(d, true)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_backward_persistent_large(a);
   }
-  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : 3) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
   const bool wide = bwd_wide(d);
+  if (cell != 0 && !wide) return LSTM_UNSUPPORTED;
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   PersBwdArgs k;
-  k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
+  k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.h0 = a.h0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
   k.dh0 = a.dh0; k.dc0 = a.dc0; k.flags = flags; k.watchdog = g_watch_dev;
   // With I == H layer 0 is like every other layer: its workgroups also multiply by W_0 (the rows of the
@@ -2296,7 +2354,7 @@ int run_backward_persistent(const BwdArgs& a) {
   k.db = nullptr;
   if (wide && a.db && d.B <= 64) {  // one launch: the wide kernel adds the bias gradient into db itself (two addends per element)
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
-    CK(launch_fill_zero(a.db, (size_t)d.L * G * 4, s), "zero db");
+    CK(launch_fill_zero(a.db, (size_t)d.L * GW * 4, s), "zero db");
     k.db = a.db;
   }
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
@@ -2320,7 +2378,11 @@ int run_backward_persistent(const BwdArgs& a) {
     }
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (wide && d.H == 512) e = launch_bwd32<512>(k, 2 * nsl, s);
+    if (wide && cell != 0) {
+      e = d.H == 512 ? launch_bwd32<512, 1>(k, 2 * nsl, s)
+                     : (d.H == 256 ? launch_bwd32<256, 1>(k, 2 * nsl, s) : launch_bwd32<128, 1>(k, 2 * nsl, s));
+    }
+    else if (wide && d.H == 512) e = launch_bwd32<512>(k, 2 * nsl, s);
     else if (wide && d.H == 256) e = launch_bwd32<256>(k, 2 * nsl, s);
     else if (wide && d.H == 128) e = launch_bwd32<128>(k, 2 * nsl, s);
     else if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
@@ -2330,9 +2392,11 @@ int run_backward_persistent(const BwdArgs& a) {
   }
   if (a.dx && !k.dx0) {  // layer 0's input gradient: all T steps in one product
     ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
-    GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)G, (long)G, 1, d.I, 1, d.I, 0};
+    GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)GW, (long)G, 1, d.I, 1, d.I, 0};
     CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");
   }
+  if (bias_done) *bias_done = k.db != nullptr;
+  if (cell != 0) return LSTM_OK;
   return weight_gradients(a, dA, true, k.db != nullptr);
 }
 

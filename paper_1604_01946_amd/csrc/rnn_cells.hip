@@ -8,6 +8,11 @@
 
 namespace lstm {
 
+// persistent.hip: the wide persistent kernels also run the GRU (weights on chip for all T steps, Section 4)
+bool gru_persistent_supported(const Dims& d);
+int run_forward_persistent(const FwdArgs& a, int cell);
+int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done);
+
 #define CK(expr, what)                                             \
   do {                                                             \
     if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
@@ -111,12 +116,33 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
   return (size_t)d.T * d.B * d.H * (cell == RNN_CELL_GRU ? 5 : 1);
 }
 
+// Shapes the persistent GRU kernels may take (device limits are checked at run time): their workspace is the LSTM
+// library's, so the buffer must hold either layout.
+inline bool gru_persistent_shape(int cell, const Dims& d) {
+  return cell == RNN_CELL_GRU && (d.H == 128 || d.H == 256 || d.H == 512) && d.B > 32 && d.B <= 512;
+}
+inline size_t ws_total(int cell, const Dims& d) {
+  const size_t own = rnn_ws(cell, d).total;
+  if (!gru_persistent_shape(cell, d)) return own;
+  const size_t pers = ws_layout(d).total;
+  return pers > own ? pers : own;
+}
+inline bool use_persistent(int cell, const Dims& d) {
+  if (!gru_persistent_shape(cell, d) || !gru_persistent_supported(d)) return false;
+  const char* e = getenv("RNN_NO_PERSISTENT");
+  return !(e && *e == '1');
+}
+
 inline int ew_grid(long cnt) { return (int)((cnt + 255) / 256 < 2048 ? (cnt + 255) / 256 : 2048); }
 
 int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const float* W, const float* R, const float* b,
                  float* y, float* hT, float* reserve, char* ws, hipStream_t s) {
   const int gates = gates_of(cell), H = d.H, B = d.B;
   const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
+  if (use_persistent(cell, d)) {
+    const FwdArgs a{d, x, h0, nullptr, W, R, b, y, hT, nullptr, reserve, ws, ws_layout(d), s};
+    return run_forward_persistent(a, 1);
+  }
   const RnnWs w = rnn_ws(cell, d);
   float* P = reinterpret_cast<float*>(ws + w.P);
   float* Q = reinterpret_cast<float*>(ws + w.Q);
@@ -152,11 +178,70 @@ int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const
   return LSTM_OK;
 }
 
+// GRU backward on the persistent kernels: propagation in one launch (per group of batch slices), then the weight
+// gradients as grouped products over all steps (Section 2.6) from the gate gradients it left in the workspace:
+// [L][T*B][4H] holding the gradients with respect to the r and z pre-activations, W_n x + b_n, and R_n h.
+int backward_gru_persistent(const Dims& d, const float* x, const float* h0, const float* W, const float* R,
+                            const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW,
+                            float* dR, float* db, char* ws, hipStream_t s) {
+  const int H = d.H, B = d.B;
+  const size_t TB = (size_t)d.T * B, G = 3 * (size_t)H, G4 = 4 * (size_t)H, BH = (size_t)B * H;
+  const WsLayout w = ws_layout(d);
+  const BwdArgs a{d, x, h0, nullptr, W, R, reserve, dy, dhT, nullptr, dx, dh0, nullptr, dW, dR, db, ws, w, s};
+  bool bias_done = false;
+  const int st = run_backward_persistent(a, 1, &bias_done);
+  if (st != LSTM_OK) return st;
+  const float* dA_all = reinterpret_cast<const float*>(ws + w.P);
+  GemmProblem main_g[kMaxGemmGroup], init_g[kMaxGemmGroup];
+  int nm = 0, ni = 0;
+  auto flush = [&]() -> hipError_t {
+    hipError_t e = hipSuccess;
+    if (nm) e = launch_gemm_group(main_g, nm, s);
+    if (e == hipSuccess && ni) e = launch_gemm_group(init_g, ni, s);
+    nm = ni = 0;
+    return e;
+  };
+  size_t woff = 0;
+  for (int l = 0; l < d.L; ++l) {
+    const int Il = in_dim(d, l);
+    const float* dA = dA_all + (size_t)l * TB * G4;
+    const float* hl = reserve + (size_t)l * res_layer_floats(RNN_CELL_GRU, d);
+    const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(RNN_CELL_GRU, d);
+    float* dWl = dW + woff;
+    float* dRl = dR + (size_t)l * G * H;
+    woff += G * Il;
+    if (nm + 3 > kMaxGemmGroup || ni + 2 > kMaxGemmGroup) CK(flush(), "weight-gradient GEMMs");
+    main_g[nm++] = GemmProblem{dA, in, dWl, (int)G, Il, (int)TB, 1, (long)G4, Il, 1, Il, 0};
+    if (d.T > 1) {  // rows r, z from the first two groups, rows n from the fourth (the gradient of R_n h)
+      main_g[nm++] = GemmProblem{dA + (size_t)B * G4, hl, dRl, 2 * H, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
+      main_g[nm++] = GemmProblem{dA + (size_t)B * G4 + 3 * H, hl, dRl + (size_t)2 * H * H, H, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
+    }
+    if (h0) {
+      const int acc = d.T > 1 ? 1 : 0;
+      init_g[ni++] = GemmProblem{dA, h0 + (size_t)l * BH, dRl, 2 * H, H, B, 1, (long)G4, H, 1, H, acc};
+      init_g[ni++] = GemmProblem{dA + 3 * H, h0 + (size_t)l * BH, dRl + (size_t)2 * H * H, H, H, B, 1, (long)G4, H, 1, H, acc};
+    } else if (d.T == 1) {
+      CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
+    }
+  }
+  CK(flush(), "weight-gradient GEMMs");
+  if (!bias_done) {  // column sums over all four groups, of which db takes the first three
+    float* part = reinterpret_cast<float*>(ws + w.dbpart);
+    float* sums = reinterpret_cast<float*>(ws + w.scratch);
+    for (int l = 0; l < d.L; ++l) {
+      CK(launch_colsum(dA_all + (size_t)l * TB * G4, (int)TB, (int)G4, part, sums, s), "bias gradient");
+      CK(launch_ew(EW_COPY, db + (size_t)l * G, (long)G, sums, (long)G4, nullptr, 0, 1, (int)G, s), "bias gradient");
+    }
+  }
+  return LSTM_OK;
+}
+
 int backward_impl(int cell, const Dims& d, const float* x, const float* h0, const float* W, const float* R,
                   const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW, float* dR,
                   float* db, char* ws, hipStream_t s) {
   const int gates = gates_of(cell), H = d.H, B = d.B;
   const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
+  if (use_persistent(cell, d)) return backward_gru_persistent(d, x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, ws, s);
   const RnnWs w = rnn_ws(cell, d);
   float* da = reinterpret_cast<float*>(ws + w.da);
   float* dq = cell == RNN_CELL_GRU ? reinterpret_cast<float*>(ws + w.dq) : da;
@@ -229,7 +314,7 @@ size_t rnn_reserve_bytes(int cell, int L, int T, int B, int I, int H) {
 
 size_t rnn_workspace_bytes(int cell, int L, int T, int B, int I, int H) {
   if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
-  return rnn_ws(cell, Dims{L, T, B, I, H}).total;
+  return ws_total(cell, Dims{L, T, B, I, H});
 }
 
 int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, const float* h0, const float* W,
@@ -241,7 +326,7 @@ int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, con
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H};
-  if (workspace_bytes < rnn_ws(cell, d).total) return LSTM_BUFFER_TOO_SMALL;
+  if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return forward_impl(cell, d, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve), reinterpret_cast<char*>(workspace),
                       (hipStream_t)stream);
 }
@@ -255,7 +340,7 @@ int rnn_backward(int cell, int L, int T, int B, int I, int H, const float* x, co
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H};
-  if (workspace_bytes < rnn_ws(cell, d).total) return LSTM_BUFFER_TOO_SMALL;
+  if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return backward_impl(cell, d, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
                        reinterpret_cast<char*>(workspace), (hipStream_t)stream);
 }

@@ -61,3 +61,20 @@ def test_cells_match_oracle(cell, dims):
 @pytest.mark.parametrize("cell", ["tanh", "gru"])
 def test_cells_without_initial_state(cell):
     run(cell, 2, 4, 5, 16, 48, seed=4, with_h0=False)
+
+
+# Shapes the persistent GRU kernels take (H in 128/256/512, more than 32 batch rows): x multiplied inside the kernel
+# (I == H) or projected by a batched GEMM (I != H), batch slices side by side and in further launches, a single step.
+PERSISTENT = [(4, 7, 64, 512, 512), (2, 5, 33, 72, 256), (3, 4, 130, 128, 128), (1, 3, 48, 512, 512), (2, 1, 64, 256, 256),
+              (1, 2, 512, 16, 128)]
+
+
+@pytest.mark.parametrize("with_h0", [True, False], ids=["h0", "noh0"])
+@pytest.mark.parametrize("dims", PERSISTENT, ids=["x".join(map(str, s)) for s in PERSISTENT])
+def test_gru_persistent_shapes(dims, with_h0):
+    run("gru", *dims, seed=5, with_h0=with_h0)
+
+
+def test_gru_step_by_step_path_at_a_persistent_shape(monkeypatch):
+    monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
+    run("gru", 2, 5, 40, 64, 128, seed=6)
