@@ -64,10 +64,12 @@ namespace lstm {
 
 size_t reserve_bytes(const Dims& d) { return (size_t)d.L * d.T * d.B * 6 * d.H * sizeof(float); }
 
-WsLayout ws_layout(const Dims& d) {
+// wide_rows: the exchange slots hold 64 batch rows also for batches of 32 rows and fewer (the GRU runs those on the
+// wide persistent kernels).
+WsLayout ws_layout(const Dims& d, bool wide_rows) {
   WsLayout w;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, H = d.H, L = d.L;
-  const size_t Bp = d.B <= 16 ? 16 : (d.B <= 32 ? 32 : align_up((size_t)d.B, 64));
+  const size_t Bp = (d.B > 32 || wide_rows) ? align_up((size_t)d.B, 64) : (d.B <= 16 ? 16 : 32);
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
@@ -82,7 +84,7 @@ WsLayout ws_layout(const Dims& d) {
   w.scratch = take(8 * (size_t)d.B * G * 4);
   // persistent paths: exchange buffers (large-H backward: gate gradients and partial sums of one layer,
   // 5 MB per step at H = 2048)
-  size_t xchg = L * (size_t)d.T * G * Bp * 4;
+  size_t xchg = L * ((size_t)d.T + 1) * G * Bp * 4;
   if (d.H == 2048 || d.H == 1024) {  // up to four slices of 32 batch rows side by side (one at H = 2048)
     const size_t nbk = d.H / 128, sl = std::min<size_t>(((size_t)d.B + 31) / 32, d.H == 2048 ? 1 : 4);
     const size_t need = sl * d.T * (nbk * 4 * 128 * 32 + nbk * nbk * 128 * 32) * 4;

@@ -2230,10 +2230,11 @@ int run_backward_persistent_large(const BwdArgs& a) {
 
 }  // namespace
 
-// Wide persistent kernels for the GRU: hidden sizes and CU budget of the LSTM ones, more than 32 batch rows.
+// Wide persistent kernels for the GRU: hidden sizes and CU budget of the LSTM ones; they also take batches of 32
+// rows and fewer (the rows past the batch are zeros), where the LSTM has kernels of its own.
 bool gru_persistent_supported(const Dims& d) {
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
-  if (d.B > 512 || !fwd_wide(d) || !bwd_wide(d)) return false;
+  if (d.B > 512) return false;
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return (long)d.L * (d.H / 8) <= di.cus;
@@ -2254,8 +2255,7 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
   const int BP = 16 * bp.NT;
-  const bool wide = fwd_wide(d);
-  if (cell != 0 && !wide) return LSTM_UNSUPPORTED;
+  const bool wide = cell != 0 || fwd_wide(d);
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
@@ -2340,8 +2340,7 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
   const BatchPlan bp = batch_plan(d.B);
-  const bool wide = bwd_wide(d);
-  if (cell != 0 && !wide) return LSTM_UNSUPPORTED;
+  const bool wide = cell != 0 || bwd_wide(d);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   PersBwdArgs k;

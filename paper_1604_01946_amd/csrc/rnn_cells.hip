@@ -119,12 +119,12 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
 // Shapes the persistent GRU kernels may take (device limits are checked at run time): their workspace is the LSTM
 // library's, so the buffer must hold either layout.
 inline bool gru_persistent_shape(int cell, const Dims& d) {
-  return cell == RNN_CELL_GRU && (d.H == 128 || d.H == 256 || d.H == 512) && d.B > 32 && d.B <= 512;
+  return cell == RNN_CELL_GRU && (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
 inline size_t ws_total(int cell, const Dims& d) {
   const size_t own = rnn_ws(cell, d).total;
   if (!gru_persistent_shape(cell, d)) return own;
-  const size_t pers = ws_layout(d).total;
+  const size_t pers = ws_layout(d, true).total;
   return pers > own ? pers : own;
 }
 inline bool use_persistent(int cell, const Dims& d) {
@@ -140,7 +140,7 @@ int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const
   const int gates = gates_of(cell), H = d.H, B = d.B;
   const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
   if (use_persistent(cell, d)) {
-    const FwdArgs a{d, x, h0, nullptr, W, R, b, y, hT, nullptr, reserve, ws, ws_layout(d), s};
+    const FwdArgs a{d, x, h0, nullptr, W, R, b, y, hT, nullptr, reserve, ws, ws_layout(d, true), s};
     return run_forward_persistent(a, 1);
   }
   const RnnWs w = rnn_ws(cell, d);
@@ -186,7 +186,7 @@ int backward_gru_persistent(const Dims& d, const float* x, const float* h0, cons
                             float* dR, float* db, char* ws, hipStream_t s) {
   const int H = d.H, B = d.B;
   const size_t TB = (size_t)d.T * B, G = 3 * (size_t)H, G4 = 4 * (size_t)H, BH = (size_t)B * H;
-  const WsLayout w = ws_layout(d);
+  const WsLayout w = ws_layout(d, true);
   const BwdArgs a{d, x, h0, nullptr, W, R, reserve, dy, dhT, nullptr, dx, dh0, nullptr, dW, dR, db, ws, w, s};
   bool bias_done = false;
   const int st = run_backward_persistent(a, 1, &bias_done);

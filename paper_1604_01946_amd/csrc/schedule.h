@@ -46,7 +46,7 @@ struct BwdArgs {
 };
 
 size_t reserve_bytes(const Dims& d);
-WsLayout ws_layout(const Dims& d);
+WsLayout ws_layout(const Dims& d, bool wide_rows = false);
 unsigned resolve_auto_path(const Dims& d, bool backward);
 int set_path_override(const Dims& d, bool backward, unsigned path);  // LSTM_PATH_AUTO removes the entry
 void clear_path_overrides();

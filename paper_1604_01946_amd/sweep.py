@@ -4,6 +4,9 @@ hidden sizes and minibatch sizes, as a Markdown table.  Timing only: inputs are 
 compared (parity at these shapes is the job of the tests).
 
     python -m paper_1604_01946_amd.sweep [--hidden 256,512,1024,2048] [--batch 32,64,128,256] [--layers 1,4] [--T 100]
+                                         [--cell lstm|gru|tanh|relu]
+
+`--cell` times the other recurrent units of Section 3.3 through rnn_forward / rnn_backward instead.
 """
 import argparse
 import math
@@ -49,6 +52,42 @@ def run_shape(L, T, B, H, iters, dev):
     return ms, flop / ms / 1e9, path, bool(torch.isfinite(dW).all().item())
 
 
+def run_shape_rnn(cell, L, T, B, H, iters, dev):
+    I = H
+    gates = 3 if cell == "gru" else 1
+    G = gates * H
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    rnd = lambda *s: torch.randn(*s, device=dev, generator=g, dtype=torch.float32)
+    uni = lambda n, a: (torch.rand(n, device=dev, generator=g, dtype=torch.float32) * 2 - 1) * a
+    x, dy = rnd(T, B, I), rnd(T, B, H)
+    W, R, b = uni(L * G * H, 1 / math.sqrt(H)), uni(L * G * H, 1 / math.sqrt(H)), uni(L * G, 0.1)
+    h0 = rnd(L, B, H) * 0.1
+    f = lambda *s: torch.empty(*s, device=dev, dtype=torch.float32)
+    y, hT, dx, dh0 = f(T, B, H), f(L, B, H), f(T, B, I), f(L, B, H)
+    dW, dR, db = torch.empty_like(W), torch.empty_like(R), torch.empty_like(b)
+    dims = (B_.RNN_CELLS[cell], L, T, B, I, H)
+    rb, wb = B_.rnn_reserve_bytes(*dims), B_.rnn_workspace_bytes(*dims)
+    res = torch.empty(rb, dtype=torch.uint8, device=dev)
+    ws = torch.empty(wb, dtype=torch.uint8, device=dev)
+
+    def step():
+        B_.check(B_.rnn_forward(*dims, x, h0, W, R, b, y, hT, res, ws, wb), "forward")
+        B_.check(B_.rnn_backward(*dims, x, h0, W, R, res, dy, None, dx, dh0, dW, dR, db, ws, wb), "backward")
+
+    step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    flop = 3 * L * 2 * G * (I + H) * B * T
+    return ms, flop / ms / 1e9, None, bool(torch.isfinite(dW).all().item())
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--hidden", default="256,512,1024,2048")
@@ -56,18 +95,25 @@ def main():
     ap.add_argument("--layers", default="1,4")
     ap.add_argument("--T", type=int, default=100)
     ap.add_argument("--iters", type=int, default=3)
+    ap.add_argument("--cell", default="lstm", choices=["lstm", "gru", "tanh", "relu"])
     a = ap.parse_args()
     dev = torch.device("cuda:0")
     names = B_.PATH_NAMES
-    print(f"T = {a.T}, I = H, fp32, forward+backward, TFLOP/s by the 3-pass count (ms per iteration; forward/backward path)\n")
+    what = "forward/backward path" if a.cell == "lstm" else f"cell {a.cell}"
+    print(f"T = {a.T}, I = H, fp32, forward+backward, TFLOP/s by the 3-pass count (ms per iteration; {what})\n")
     for L in [int(v) for v in a.layers.split(",")]:
         Bs = [int(v) for v in a.batch.split(",")]
         print(f"L = {L}\n\n| H | " + " | ".join(f"B={b}" for b in Bs) + " |\n|---|" + "---|" * len(Bs))
         for H in [int(v) for v in a.hidden.split(",")]:
             cells = []
             for B in Bs:
-                ms, tf, path, ok = run_shape(L, a.T, B, H, a.iters, dev)
-                cells.append(f"{tf:.1f} ({ms:.2f}; {names.get(path[0], path[0])}/{names.get(path[1], path[1])}{'' if ok else '; NON-FINITE'})")
+                if a.cell == "lstm":
+                    ms, tf, path, ok = run_shape(L, a.T, B, H, a.iters, dev)
+                    tag = f"; {names.get(path[0], path[0])}/{names.get(path[1], path[1])}"
+                else:
+                    ms, tf, path, ok = run_shape_rnn(a.cell, L, a.T, B, H, a.iters, dev)
+                    tag = ""
+                cells.append(f"{tf:.1f} ({ms:.2f}{tag}{'' if ok else '; NON-FINITE'})")
             print(f"| {H} | " + " | ".join(cells) + " |", flush=True)
         print()
 
