@@ -125,6 +125,7 @@ def main():
     B_.lstm_profile_enable(1)
     nprof = max(3, min(args.steps, 10))
     fwd_ms = bwd_ms = 0.0
+    per_iter = []  # HIP-event time of each of these iterations, synchronised one by one (the paper's protocol, Section 2.1)
     phases = {}
     for _ in range(nprof):
         ev[0].record()
@@ -136,6 +137,7 @@ def main():
         torch.cuda.synchronize()
         fwd_ms += ev[0].elapsed_time(ev[1]) / nprof
         bwd_ms += ev[1].elapsed_time(ev[2]) / nprof
+        per_iter.append(ev[0].elapsed_time(ev[2]))
         st, ph = B_.lstm_profile_read()
         B_.check(st, "lstm_profile_read")
         for k, (m, c) in ph.items():
@@ -235,6 +237,8 @@ def main():
         "tflops_2pass": round(tflops_2pass, 3),
         "us_per_cell": round(ms * 1e3 / (L * T), 3),
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+        "event_ms": {"iterations": len(per_iter), "median": round(sorted(per_iter)[len(per_iter) // 2], 4),
+                     "min": round(min(per_iter), 4), "max": round(max(per_iter), 4)},
         "frac_of_fp32_mfma_peak": round(tflops / PEAK_FP32_MFMA_TFLOPS, 4),
         "phases": phase_report,
         "roofline": roofline,
