@@ -17,15 +17,15 @@
  * layers stacked as Section 2.4 describes.  The reset gate multiplies the recurrent product, so the
  * three recurrent matrices run as one stacked product per step (the grouping of Section 2.1).
  *
- * What runs: for the GRU with H = 128, 256 or 512 (and L*H/8 no more than the CU count, B <= 512)
- * the persistent kernels of lstm.h with the weights on chip for all T steps (Section 4) and the
- * layers as a wavefront inside one launch (2.4): their 32-row tile per workgroup holds r, z and the
- * input and recurrent halves of n for 8 hidden units.  Everything else -- other GRU shapes and the
- * single-gate cells -- runs on the rungs of the paper's ladder that do not depend on the cell: the
- * input products of a layer batched over all steps (Section 2.3), the gates grouped into one
- * recurrent product per step (2.1), one fused point-wise kernel per step (2.2.2).  Weight gradients
- * are large products after propagation (2.6) in both cases, on the library's MFMA GEMM kernels.
- * RNN_NO_PERSISTENT=1 in the environment keeps the GRU on the step-by-step path.
+ * What runs: with H = 128, 256 or 512 (and L*H/8 no more than the CU count, B <= 512) the
+ * persistent kernels of lstm.h with the weights on chip for all T steps (Section 4) and the layers
+ * as a wavefront inside one launch (2.4): their 32-row tile per workgroup holds, for 8 hidden units,
+ * r, z and the input and recurrent halves of n (GRU), or the one gate and three empty groups
+ * (single gate).  Every other shape runs on the rungs of the paper's ladder that do not depend on the
+ * cell: the input products of a layer batched over all steps (Section 2.3), the gates grouped into
+ * one recurrent product per step (2.1), one fused point-wise kernel per step (2.2.2).  Weight
+ * gradients are large products after propagation (2.6) in both cases, on the library's MFMA GEMM
+ * kernels.  RNN_NO_PERSISTENT=1 in the environment keeps every shape on the step-by-step path.
  *
  * Conventions: as in lstm.h (fp32, row-major, device pointers owned by the caller and 16-byte
  * aligned, asynchronous on `stream`, LSTM_* status codes, validation before any GPU work).

@@ -488,9 +488,12 @@ __global__ void pack_state_kernel(const float* __restrict__ h0, float* __restric
 // recurrent product): the four row groups of a workgroup's tile are then r, z, the input half of n (W_n x, no
 // recurrent weights) and the recurrent half of n (R_n h, no input weights) -- a quarter of the MFMA work
 // multiplies zeros, everything else is unchanged.  Its reserve is h [T][B][H] followed by r, z, n, R_n h as [T][B][4H].
+// CELL = 2 / 3: single-gate RNN with ReLU / tanh: only the first row group carries weights (three quarters of the
+// MFMA work multiply zeros -- these small cells are bound by the synchronisation of a step, not by the products);
+// the reserve is h [T][B][H].
 template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
-  constexpr int H = HH, NG = CELL == 0 ? 4 : 3, G = NG * H, NS = H / 8;  // G: rows of W, R, b and of the projection P0
+  constexpr int H = HH, NG = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1), G = NG * H, NS = H / 8;  // G: rows of W, R, b and of the projection P0
   constexpr int NK4 = H / 16;  // 4-k groups per wave and operand half
   __shared__ float part[4][32][64];
   __shared__ __attribute__((aligned(16))) float xs[512];  // this step's h slice in exchange order
@@ -517,8 +520,9 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I], read if I == H
     const int grp = n >> 3;
     // matrix row behind tile row group grp: the gate itself (LSTM); r, z, n (input half), n (recurrent half) for the GRU
-    const int gate = (CELL == 1 && grp == 3) ? 2 : grp;
-    const bool useR = CELL == 0 || grp != 2, useW = (CELL == 0 || grp != 3) && (l > 0 || a.xin);
+    const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);
+    const bool useR = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0);
+    const bool useW = (CELL == 0 || (CELL == 1 ? grp != 3 : grp == 0)) && (l > 0 || a.xin);
     const size_t row = ((size_t)gate * H + u0 + (n & 7)) * H;
 #pragma unroll
     for (int i = 0; i < NK4; ++i) {
@@ -543,13 +547,13 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
 #pragma unroll
   for (int ci = 0; ci < 2; ++ci) {
     c_unit[ci] = u0 + 4 * kk + 2 * up + ci;
-    const float* const s0 = CELL == 0 ? a.c0 : a.h0;
+    const float* const s0 = CELL == 0 ? a.c0 : (CELL == 1 ? a.h0 : nullptr);
     c_state[ci] = (valid && s0) ? s0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) c_bias[ci][g] = g < NG ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
   }
 
-  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : (CELL == 1 ? 5 : 1)) * H;
   float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // the four saved arrays, [T][B][4H]
   float* const res_c = res_l + TB * 4 * H;                       // LSTM only
   float* const res_h = CELL == 0 ? res_l + TB * 5 * H : res_l;
@@ -598,6 +602,11 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         o_c[ci] = o_gate[ci][1] * c_state[ci] + o_gate[ci][0] * o_gate[ci][3];
         o_h[ci] = o_gate[ci][2] * tanhf_dev(o_c[ci]);
         c_state[ci] = o_c[ci];
+      } else if (CELL >= 2) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) o_gate[ci][g] = 0.f;
+        o_h[ci] = CELL == 3 ? tanhf_dev(sg[0]) : fmaxf(sg[0], 0.f);
+        o_c[ci] = 0.f;
       } else {  // sg: r and z pre-activations, W_n x + b_n, R_n h
         o_gate[ci][0] = sigmoidf_dev(sg[0]);
         o_gate[ci][1] = sigmoidf_dev(sg[1]);
@@ -637,7 +646,7 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
-          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
+          if (CELL <= 1) *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
         } else if (arr == 4) {
           if (CELL == 0) {
             *reinterpret_cast<floatx4*>(res_c + e) = v;
@@ -1112,10 +1121,11 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 // pre-activations, to W_n x + b_n, and to R_n h; the recurrent rows of the tile have no weights in the third group,
 // the input rows none in the fourth, and dh_{t-1} also receives dh_t o z_t directly.  The arrays c0 / dcT / dc0 of
 // the arguments are not used; `res` is the GRU reserve, W / R / db have 3H rows.
+// CELL = 2 / 3: single-gate RNN (ReLU / tanh): only the first K group is non-zero; `res` holds h alone.
 template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, const int NBH) {
   constexpr int H = HH, G = 4 * H, NS2 = H / 16;  // G: width of the gate-gradient arrays (four groups for both cells)
-  constexpr int NG = CELL == 0 ? 4 : 3, GW = NG * H;  // rows of W, R, db
+  constexpr int NG = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1), GW = NG * H;  // rows of W, R, db
   constexpr int NB8 = H / 8;                 // 8-k groups per wave (wave w covers the rows of gate w)
   constexpr int KPW = H / 2;                 // k-pairs per wave
   constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
@@ -1156,8 +1166,9 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     const float* src = (n < 16) ? Rl + u0 + n : (l > 0 ? Wl : a.W) + u0 + (n - 16);  // layer 0: its own [GW][I], I == H
     // matrix row block behind K group `wave`: the gate itself (LSTM); GRU: r, z, then n for the input rows only,
     // then n for the recurrent rows only
-    const int gate = (CELL == 1 && wave == 3) ? 2 : wave;
-    const bool live = ((n < 16) || (l > 0) || a.dx0) && (CELL == 0 || (n < 16 ? wave != 2 : wave != 3));
+    const int gate = CELL >= 2 ? 0 : ((CELL == 1 && wave == 3) ? 2 : wave);
+    const bool live = ((n < 16) || (l > 0) || a.dx0) &&
+                      (CELL == 0 || (CELL == 1 ? (n < 16 ? wave != 2 : wave != 3) : wave == 0));
 #pragma unroll
     for (int i = 0; i < KPW; ++i) {
       const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
@@ -1186,9 +1197,9 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     for (int g = 0; g < 4; ++g) dbsum[g][r] = 0.f;
   }
 
-  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
-  const float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // the four saved arrays, [T][B][4H]
-  const float* const res_c = CELL == 0 ? res_l + TB * 4 * H : res_l;   // c (LSTM) or h (GRU): the state whose previous value the step needs
+  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : (CELL == 1 ? 5 : 1)) * H;
+  const float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // the four saved arrays, [T][B][4H] (LSTM, GRU)
+  const float* const res_c = CELL == 0 ? res_l + TB * 4 * H : res_l;   // c (LSTM) or h: the state array the step reads
   const float* const s0 = CELL == 0 ? a.c0 : a.h0;
   float* const dA_l = a.dA + (size_t)l * TB * G;
   const bool has_up = l < a.L - 1;
@@ -1211,17 +1222,21 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
     if (pwv) {
       const size_t e = ((size_t)t * B + bb) * H + unit0;
       const size_t g0 = ((size_t)t * B + bb) * G + unit0;
-      gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
-      gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
-      go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
-      gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
-      if (CELL == 0) ct = *reinterpret_cast<const floatx4*>(res_c + e);
-      if (t > 0)
-        cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
-      else if (s0)
-        cp = *reinterpret_cast<const floatx4*>(s0 + ((size_t)l * B + bb) * H + unit0);
-      else
-        cp = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (CELL <= 1) {
+        gi = *reinterpret_cast<const floatx4*>(res_gates + g0);
+        gf = *reinterpret_cast<const floatx4*>(res_gates + g0 + H);
+        go = *reinterpret_cast<const floatx4*>(res_gates + g0 + 2 * H);
+        gg = *reinterpret_cast<const floatx4*>(res_gates + g0 + 3 * H);
+      }
+      if (CELL != 1) ct = *reinterpret_cast<const floatx4*>(res_c + e);  // c_t (LSTM), h_t (single gate)
+      if (CELL <= 1) {
+        if (t > 0)
+          cp = *reinterpret_cast<const floatx4*>(res_c + e - (size_t)B * H);
+        else if (s0)
+          cp = *reinterpret_cast<const floatx4*>(s0 + ((size_t)l * B + bb) * H + unit0);
+        else
+          cp = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
     }
   };
   // The upstream gradient of step t (dy, or dx of the layer above) is fetched with them when it is there:
@@ -1257,6 +1272,9 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
             dA4[2][r] = dh * tc * go[r] * (1.f - go[r]);
             dA4[3][r] = dcv * gi[r] * (1.f - gg[r] * gg[r]);
             dc[r] = dcv * gf[r];
+          } else if (CELL >= 2) {  // ct holds h_t
+            dA4[0][r] = CELL == 3 ? dh * (1.f - ct[r] * ct[r]) : (ct[r] > 0.f ? dh : 0.f);
+            dA4[1][r] = dA4[2][r] = dA4[3][r] = 0.f;
           } else {  // gi, gf, go, gg hold r, z, n, R_n h; cp holds h_{t-1}
             const float dn = dh * (1.f - gf[r]) * (1.f - go[r] * go[r]);
             dA4[0][r] = dn * gg[r] * gi[r] * (1.f - gi[r]);
@@ -1358,7 +1376,7 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       }
       if (wave < 2) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) dh_rec[r] = CELL == 0 ? v[r] : v[r] + dc[r];
+        for (int r = 0; r < 4; ++r) dh_rec[r] = CELL == 1 ? v[r] + dc[r] : v[r];
       } else if (dxl) {
         xstore4(dx_out + ((size_t)t * B + bb) * H + unit0, floatx4{v[0], v[1], v[2], v[3]});
       }
@@ -2240,8 +2258,8 @@ bool gru_persistent_supported(const Dims& d) {
   return (long)d.L * (d.H / 8) <= di.cus;
 }
 
-// cell: 0 = LSTM; 1 = GRU (wide kernels only: the caller has checked gru_persistent_supported; a.c0 / a.cT are null,
-// W, R, b have 3H rows and a.reserve is the GRU reserve).
+// cell: 0 = LSTM; 1 = GRU, 2 / 3 = single-gate RNN with ReLU / tanh (wide kernels only: the caller has checked
+// gru_persistent_supported; a.c0 / a.cT are null, W, R, b have 3H or H rows and a.reserve is that cell's reserve).
 int run_forward_persistent(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
   if (cell == 0 && persistent_large(d, false)) {
@@ -2249,7 +2267,7 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_forward_persistent_large(a);
   }
-  const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : 3) * (size_t)d.H;
+  const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
@@ -2316,7 +2334,11 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
     }
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (wide) e = cell == 0 ? launch_fwd32<0>(d.H, grid * nsl, k, s) : launch_fwd32<1>(d.H, grid * nsl, k, s);
+    if (wide) {
+      e = cell == 0 ? launch_fwd32<0>(d.H, grid * nsl, k, s)
+                    : (cell == 1 ? launch_fwd32<1>(d.H, grid * nsl, k, s)
+                                 : (cell == 2 ? launch_fwd32<2>(d.H, grid * nsl, k, s) : launch_fwd32<3>(d.H, grid * nsl, k, s)));
+    }
     else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
     else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
     else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
@@ -2325,9 +2347,9 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
   return LSTM_OK;
 }
 
-// cell as in run_forward_persistent.  For the GRU the function stops after the propagation (gate gradients
-// [L][T*B][4H] at the start of the workspace: r, z, n, and n times r) and reports in *bias_done whether db is complete;
-// the caller forms the weight gradients.
+// cell as in run_forward_persistent.  For the other cells the function stops after the propagation (gate gradients
+// [L][T*B][4H] at the start of the workspace: GRU r, z, n, and n times r; single gate: the first H columns) and
+// reports in *bias_done whether db is complete; the caller forms the weight gradients.
 int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
   const Dims& d = a.d;
   if (cell == 0 && persistent_large(d, true)) {
@@ -2335,7 +2357,7 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_backward_persistent_large(a);
   }
-  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : 3) * (size_t)d.H;
+  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
@@ -2377,9 +2399,15 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
     }
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     hipError_t e = hipErrorInvalidValue;
-    if (wide && cell != 0) {
+    if (wide && cell == 1) {
       e = d.H == 512 ? launch_bwd32<512, 1>(k, 2 * nsl, s)
                      : (d.H == 256 ? launch_bwd32<256, 1>(k, 2 * nsl, s) : launch_bwd32<128, 1>(k, 2 * nsl, s));
+    } else if (wide && cell == 2) {
+      e = d.H == 512 ? launch_bwd32<512, 2>(k, 2 * nsl, s)
+                     : (d.H == 256 ? launch_bwd32<256, 2>(k, 2 * nsl, s) : launch_bwd32<128, 2>(k, 2 * nsl, s));
+    } else if (wide && cell == 3) {
+      e = d.H == 512 ? launch_bwd32<512, 3>(k, 2 * nsl, s)
+                     : (d.H == 256 ? launch_bwd32<256, 3>(k, 2 * nsl, s) : launch_bwd32<128, 3>(k, 2 * nsl, s));
     }
     else if (wide && d.H == 512) e = launch_bwd32<512>(k, 2 * nsl, s);
     else if (wide && d.H == 256) e = launch_bwd32<256>(k, 2 * nsl, s);

@@ -119,8 +119,10 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
 // Shapes the persistent GRU kernels may take (device limits are checked at run time): their workspace is the LSTM
 // library's, so the buffer must hold either layout.
 inline bool gru_persistent_shape(int cell, const Dims& d) {
-  return cell == RNN_CELL_GRU && (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
+  return gates_of(cell) != 0 && (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
+// cell selector of the templated persistent kernels
+inline int kernel_cell(int cell) { return cell == RNN_CELL_GRU ? 1 : (cell == RNN_CELL_RELU ? 2 : 3); }
 inline size_t ws_total(int cell, const Dims& d) {
   const size_t own = rnn_ws(cell, d).total;
   if (!gru_persistent_shape(cell, d)) return own;
@@ -141,7 +143,7 @@ int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const
   const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
   if (use_persistent(cell, d)) {
     const FwdArgs a{d, x, h0, nullptr, W, R, b, y, hT, nullptr, reserve, ws, ws_layout(d, true), s};
-    return run_forward_persistent(a, 1);
+    return run_forward_persistent(a, kernel_cell(cell));
   }
   const RnnWs w = rnn_ws(cell, d);
   float* P = reinterpret_cast<float*>(ws + w.P);
@@ -178,18 +180,20 @@ int forward_impl(int cell, const Dims& d, const float* x, const float* h0, const
   return LSTM_OK;
 }
 
-// GRU backward on the persistent kernels: propagation in one launch (per group of batch slices), then the weight
+// Backward on the persistent kernels: propagation in one launch (per group of batch slices), then the weight
 // gradients as grouped products over all steps (Section 2.6) from the gate gradients it left in the workspace:
-// [L][T*B][4H] holding the gradients with respect to the r and z pre-activations, W_n x + b_n, and R_n h.
-int backward_gru_persistent(const Dims& d, const float* x, const float* h0, const float* W, const float* R,
-                            const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW,
-                            float* dR, float* db, char* ws, hipStream_t s) {
+// [L][T*B][4H]; GRU: the gradients with respect to the r and z pre-activations, W_n x + b_n, and R_n h; single gate:
+// the gradient of the pre-activation in the first H columns.
+int backward_persistent(int cell, const Dims& d, const float* x, const float* h0, const float* W, const float* R,
+                        const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW,
+                        float* dR, float* db, char* ws, hipStream_t s) {
   const int H = d.H, B = d.B;
-  const size_t TB = (size_t)d.T * B, G = 3 * (size_t)H, G4 = 4 * (size_t)H, BH = (size_t)B * H;
+  const bool gru = cell == RNN_CELL_GRU;
+  const size_t TB = (size_t)d.T * B, G = (size_t)gates_of(cell) * H, G4 = 4 * (size_t)H, BH = (size_t)B * H;
   const WsLayout w = ws_layout(d, true);
   const BwdArgs a{d, x, h0, nullptr, W, R, reserve, dy, dhT, nullptr, dx, dh0, nullptr, dW, dR, db, ws, w, s};
   bool bias_done = false;
-  const int st = run_backward_persistent(a, 1, &bias_done);
+  const int st = run_backward_persistent(a, kernel_cell(cell), &bias_done);
   if (st != LSTM_OK) return st;
   const float* dA_all = reinterpret_cast<const float*>(ws + w.P);
   GemmProblem main_g[kMaxGemmGroup], init_g[kMaxGemmGroup];
@@ -205,27 +209,31 @@ int backward_gru_persistent(const Dims& d, const float* x, const float* h0, cons
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const float* dA = dA_all + (size_t)l * TB * G4;
-    const float* hl = reserve + (size_t)l * res_layer_floats(RNN_CELL_GRU, d);
-    const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(RNN_CELL_GRU, d);
+    const float* hl = reserve + (size_t)l * res_layer_floats(cell, d);
+    const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(cell, d);
     float* dWl = dW + woff;
     float* dRl = dR + (size_t)l * G * H;
     woff += G * Il;
     if (nm + 3 > kMaxGemmGroup || ni + 2 > kMaxGemmGroup) CK(flush(), "weight-gradient GEMMs");
     main_g[nm++] = GemmProblem{dA, in, dWl, (int)G, Il, (int)TB, 1, (long)G4, Il, 1, Il, 0};
-    if (d.T > 1) {  // rows r, z from the first two groups, rows n from the fourth (the gradient of R_n h)
-      main_g[nm++] = GemmProblem{dA + (size_t)B * G4, hl, dRl, 2 * H, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
-      main_g[nm++] = GemmProblem{dA + (size_t)B * G4 + 3 * H, hl, dRl + (size_t)2 * H * H, H, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
+    // dR: GRU rows r, z from the first two groups, rows n from the fourth (the gradient of R_n h); single gate: the first
+    const int m1 = gru ? 2 * H : H;
+    if (d.T > 1) {
+      main_g[nm++] = GemmProblem{dA + (size_t)B * G4, hl, dRl, m1, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
+      if (gru)
+        main_g[nm++] = GemmProblem{dA + (size_t)B * G4 + 3 * H, hl, dRl + (size_t)2 * H * H, H, H, (int)(TB - B), 1, (long)G4, H, 1, H, 0};
     }
     if (h0) {
       const int acc = d.T > 1 ? 1 : 0;
-      init_g[ni++] = GemmProblem{dA, h0 + (size_t)l * BH, dRl, 2 * H, H, B, 1, (long)G4, H, 1, H, acc};
-      init_g[ni++] = GemmProblem{dA + 3 * H, h0 + (size_t)l * BH, dRl + (size_t)2 * H * H, H, H, B, 1, (long)G4, H, 1, H, acc};
+      init_g[ni++] = GemmProblem{dA, h0 + (size_t)l * BH, dRl, m1, H, B, 1, (long)G4, H, 1, H, acc};
+      if (gru)
+        init_g[ni++] = GemmProblem{dA + 3 * H, h0 + (size_t)l * BH, dRl + (size_t)2 * H * H, H, H, B, 1, (long)G4, H, 1, H, acc};
     } else if (d.T == 1) {
       CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
     }
   }
   CK(flush(), "weight-gradient GEMMs");
-  if (!bias_done) {  // column sums over all four groups, of which db takes the first three
+  if (!bias_done) {  // column sums over all four groups, of which db takes the leading ones
     float* part = reinterpret_cast<float*>(ws + w.dbpart);
     float* sums = reinterpret_cast<float*>(ws + w.scratch);
     for (int l = 0; l < d.L; ++l) {
@@ -241,7 +249,7 @@ int backward_impl(int cell, const Dims& d, const float* x, const float* h0, cons
                   float* db, char* ws, hipStream_t s) {
   const int gates = gates_of(cell), H = d.H, B = d.B;
   const size_t TB = (size_t)d.T * B, G = (size_t)gates * H, BH = (size_t)B * H;
-  if (use_persistent(cell, d)) return backward_gru_persistent(d, x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, ws, s);
+  if (use_persistent(cell, d)) return backward_persistent(cell, d, x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, ws, s);
   const RnnWs w = rnn_ws(cell, d);
   float* da = reinterpret_cast<float*>(ws + w.da);
   float* dq = cell == RNN_CELL_GRU ? reinterpret_cast<float*>(ws + w.dq) : da;

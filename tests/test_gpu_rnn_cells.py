@@ -21,11 +21,31 @@ def make(cell, L, T, B, I, H, seed, with_h0=True):
     return {k: (None if v is None else v.astype(np.float32)) for k, v in d.items()}
 
 
+def relu_margin(L, T, B, I, H, d, saved):
+    """Smallest |pre-activation| of a ReLU network (from the oracle's hidden states).  The backward pass switches on
+    the sign of the pre-activation: an element closer to zero than fp32 rounding of a length-H sum can be decided
+    differently by the two sides, and then a whole gradient term differs -- such inputs test nothing."""
+    Ws, hs, m = O.split_W(d["W"].astype(np.float64), "relu", L, I, H), saved["h"], np.inf
+    for l in range(L):
+        for t in range(T):
+            inp = d["x"][t].astype(np.float64) if l == 0 else hs[l - 1, t]
+            hp = hs[l, t - 1] if t else (d["h0"][l].astype(np.float64) if d["h0"] is not None else np.zeros((B, H)))
+            a = inp @ Ws[l].T + hp @ d["R"][l].astype(np.float64).T + d["b"][l]
+            m = min(m, float(np.abs(a).min()))
+    return m
+
+
 def run(cell, L, T, B, I, H, seed, with_h0=True):
     import torch
     from paper_1604_01946_amd import binding as Bd
-    d = make(cell, L, T, B, I, H, seed, with_h0)
-    y, hT, saved = O.rnn_forward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    for attempt in range(64):  # ReLU: the first seed at or after `seed` whose decisions are unambiguous in fp32 (see relu_margin)
+        d = make(cell, L, T, B, I, H, seed, with_h0)
+        y, hT, saved = O.rnn_forward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+        if cell != "relu" or relu_margin(L, T, B, I, H, d, saved) > 3e-6:  # ten times the fp32 rounding of these sums
+            break
+        seed += 1
+    else:
+        raise AssertionError("no well-conditioned ReLU inputs found: the shape has too many cells for this test")
     dx, dh0, dW, dR, db = O.rnn_backward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"])
     ref = dict(y=y, hT=hT, dx=dx, dh0=dh0, dW=dW, dR=dR, db=db)
     dev = "cuda:0"
@@ -52,9 +72,17 @@ def run(cell, L, T, B, I, H, seed, with_h0=True):
 SHAPES = [(1, 8, 4, 32, 32), (3, 5, 7, 24, 40), (2, 6, 64, 128, 256), (4, 12, 33, 512, 512), (1, 1, 1, 16, 16), (2, 3, 3, 5, 7)]
 
 
+# ReLU runs the shapes with few enough cells that inputs without near-ties exist (see relu_margin)
+def few_cells(dims):
+    L, T, B, I, H = dims
+    return L * T * B * H <= 140000
+
+
 @pytest.mark.parametrize("cell", ["relu", "tanh", "gru"])
 @pytest.mark.parametrize("dims", SHAPES, ids=["x".join(map(str, s)) for s in SHAPES])
 def test_cells_match_oracle(cell, dims):
+    if cell == "relu" and not few_cells(dims):
+        pytest.skip("ReLU: every input of this size has pre-activations within fp32 rounding of zero")
     run(cell, *dims, seed=3)
 
 
@@ -63,18 +91,22 @@ def test_cells_without_initial_state(cell):
     run(cell, 2, 4, 5, 16, 48, seed=4, with_h0=False)
 
 
-# Shapes the persistent GRU kernels take (H in 128/256/512): x multiplied inside the kernel
+# Shapes the persistent kernels take (H in 128/256/512), all three cells: x multiplied inside the kernel
 # (I == H) or projected by a batched GEMM (I != H), batch slices side by side and in further launches, a single step.
 PERSISTENT = [(4, 7, 64, 512, 512), (2, 5, 33, 72, 256), (3, 4, 130, 128, 128), (1, 3, 48, 512, 512), (2, 1, 64, 256, 256),
               (1, 2, 512, 16, 128), (2, 6, 32, 256, 256), (4, 5, 1, 512, 512), (3, 4, 17, 40, 128)]
 
 
 @pytest.mark.parametrize("with_h0", [True, False], ids=["h0", "noh0"])
+@pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
 @pytest.mark.parametrize("dims", PERSISTENT, ids=["x".join(map(str, s)) for s in PERSISTENT])
-def test_gru_persistent_shapes(dims, with_h0):
-    run("gru", *dims, seed=5, with_h0=with_h0)
+def test_persistent_shapes(dims, cell, with_h0):
+    if cell == "relu" and not few_cells(dims):
+        pytest.skip("ReLU: every input of this size has pre-activations within fp32 rounding of zero")
+    run(cell, *dims, seed=5, with_h0=with_h0)
 
 
-def test_gru_step_by_step_path_at_a_persistent_shape(monkeypatch):
+@pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
+def test_step_by_step_path_at_a_persistent_shape(cell, monkeypatch):
     monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
-    run("gru", 2, 5, 40, 64, 128, seed=6)
+    run(cell, 2, 5, 40, 64, 128, seed=6)
