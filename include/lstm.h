@@ -28,6 +28,9 @@
  *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream); internal helper streams fork from it and join back to it, and
  *     no call synchronises the host;
+ *   - calls on different streams may overlap when each has its own `reserve` and
+ *     `workspace` (results do not depend on what else runs on the device); two calls
+ *     must never share a workspace or a reserve while either is in flight;
  *   - return value: LSTM_OK or an LSTM_* error code.  Arguments are validated before
  *     any GPU work; on error nothing has been launched except for LSTM_HIP_ERROR /
  *     LSTM_INTERNAL, which can surface after partial execution.
