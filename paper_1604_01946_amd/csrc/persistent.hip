@@ -2280,7 +2280,9 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
   // Wide kernel with I == H: layer 0 multiplies by W_0 inside the kernel like the layers above it (its workgroups
   // are otherwise idle half of every step), reading x from a copy in exchange layout that takes the place of the
   // projection in the workspace.  LSTM_FWD_BATCHED_INPUT=1 keeps the batched product of Section 2.3 instead.
-  bool x_in_kernel = wide && d.I == d.H;
+  // (Section 2.3 notes that batching the input products pays at some sizes and not at others; here the batched
+  // product only wins where nothing would be idle otherwise: one layer, one slice -- by about 4 %.)
+  bool x_in_kernel = wide && d.I == d.H && !(d.L == 1 && d.B <= 64);
   if (x_in_kernel) {
     const char* e = getenv("LSTM_FWD_BATCHED_INPUT");
     if (e && *e == '1') x_in_kernel = false;
