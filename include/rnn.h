@@ -21,7 +21,8 @@
  * persistent kernels of lstm.h with the weights on chip for all T steps (Section 4) and the layers
  * as a wavefront inside one launch (2.4): their 32-row tile per workgroup holds, for 8 hidden units,
  * r, z and the input and recurrent halves of n (GRU), or the one gate and three empty groups
- * (single gate).  Every other shape runs on the rungs of the paper's ladder that do not depend on the
+ * (single gate); with H = 1024 (B <= 256) or H = 2048 (B <= 32) the one-layer persistent kernels
+ * with the recurrent matrix spread over all CUs.  Every other shape runs on the rungs of the paper's ladder that do not depend on the
  * cell: the input products of a layer batched over all steps (Section 2.3), the gates grouped into
  * one recurrent product per step (2.1), one fused point-wise kernel per step (2.2.2).  Weight
  * gradients are large products after propagation (2.6) in both cases, on the library's MFMA GEMM

@@ -1447,9 +1447,12 @@ struct PersFwdLArgs {
   int trace_block;
 };
 
-template <int HH>
+// CELL as in pers_fwd32_kernel (0 LSTM, 1 GRU, 2 / 3 single gate with ReLU / tanh).  Only recurrent weights live here
+// (the input projection P is a batched product), so the GRU's four row groups are r, z, an empty one and R_n, and P's
+// third block (W_n x) is added in the epilogue; the single gate uses the first group alone.
+template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
-  constexpr int H = HH, G = 4 * H, NS = H / 8;
+  constexpr int H = HH, NG = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1), G = NG * H, NS = H / 8;  // G: rows of R, bias, P
   constexpr int NB8 = H / 32;                // 8-k groups per wave
   constexpr int KPW = H / 8;                 // k-pairs per wave
   constexpr int RP = KPW < 128 ? KPW : 128;  // k-pairs whose weights live in registers
@@ -1474,11 +1477,14 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   //      k = wave*H/4 + 8*((i/4 + rot) mod NB8) + 2*(i%4) + kk
   float wreg[RP];
   {
-    const float* src = a.R + ((size_t)(n >> 3) * H + u0 + (n & 7)) * H + (size_t)wave * (H / 4) + kk;
+    const int grp = n >> 3;
+    const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);
+    const bool live = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0);
+    const float* src = a.R + ((size_t)gate * H + u0 + (n & 7)) * H + (size_t)wave * (H / 4) + kk;
 #pragma unroll
     for (int i = 0; i < KPW; ++i) {
       const int k8 = ((i >> 2) + rot) & (NB8 - 1), m = i & 3;
-      const float v = src[8 * k8 + 2 * m];
+      const float v = live ? src[8 * k8 + 2 * m] : 0.f;
       if (i < RP)
         wreg[i < RP ? i : 0] = v;
       else
@@ -1490,16 +1496,16 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   const int uj = 4 * kk + wave;
   const int bb = b0 + n;  // batch row in the tensors
   const bool valid = bb < B;
-  float c_state = (valid && a.c0) ? a.c0[(size_t)bb * H + u0 + uj] : 0.f;
+  float c_state = (CELL <= 1 && valid && a.c0) ? a.c0[(size_t)bb * H + u0 + uj] : 0.f;  // c_{t-1} (LSTM), h_{t-1} (GRU: a.c0 = h0)
   float c_bias[4], pin[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    c_bias[g] = a.bias[g * H + u0 + uj];
-    pin[g] = valid ? a.P[(size_t)bb * G + g * H + u0 + uj] : 0.f;
+    c_bias[g] = g < NG ? a.bias[g * H + u0 + uj] : 0.f;
+    pin[g] = (valid && g < NG) ? a.P[(size_t)bb * G + g * H + u0 + uj] : 0.f;
   }
-  float* const res_gates = a.res;
-  float* const res_c = a.res + TB * 4 * H;
-  float* const res_h = a.res + TB * 5 * H;
+  float* const res_gates = CELL == 0 ? a.res : a.res + TB * H;  // the four saved arrays [T][B][4H] (LSTM, GRU)
+  float* const res_c = a.res + TB * 4 * H;                       // LSTM only
+  float* const res_h = CELL == 0 ? a.res + TB * 5 * H : a.res;
   auto slot = [&](int st) { return hx + (size_t)st * H * 32; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
@@ -1540,7 +1546,7 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
         if (g == NB8 - DEPTH) {  // next step's input projection, behind the last exchange load of this step
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            pnx[q] = (valid && t + 1 < T) ? a.P[((size_t)(t + 1) * B + bb) * G + q * H + u0 + uj] : 0.f;
+            pnx[q] = (valid && t + 1 < T && q < NG) ? a.P[((size_t)(t + 1) * B + bb) * G + q * H + u0 + uj] : 0.f;
         }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
@@ -1563,10 +1569,23 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
       sg[g] = (part[(0 * 16 + r) * 64 + lane] + part[(1 * 16 + r) * 64 + lane]) +
               (part[(2 * 16 + r) * 64 + lane] + part[(3 * 16 + r) * 64 + lane]) + pin[g] + c_bias[g];
     }
-    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gg = tanhf_dev(sg[3]);
-    const float cv = gf * c_state + gi * gg;
-    const float hv = go * tanhf_dev(cv);
-    c_state = cv;
+    float gi, gf, go, gg, cv, hv;
+    if (CELL == 0) {
+      gi = sigmoidf_dev(sg[0]); gf = sigmoidf_dev(sg[1]); go = sigmoidf_dev(sg[2]); gg = tanhf_dev(sg[3]);
+      cv = gf * c_state + gi * gg;
+      hv = go * tanhf_dev(cv);
+      c_state = cv;
+    } else if (CELL == 1) {  // sg: r, z pre-activations; W_n x + b_n (from P: this group has no weights here); R_n h
+      gi = sigmoidf_dev(sg[0]); gf = sigmoidf_dev(sg[1]);
+      go = tanhf_dev(sg[2] + gi * sg[3]);
+      gg = sg[3];
+      hv = (1.f - gf) * go + gf * c_state;
+      cv = 0.f;
+      c_state = hv;
+    } else {
+      gi = gf = go = gg = cv = 0.f;
+      hv = CELL == 3 ? tanhf_dev(sg[0]) : fmaxf(sg[0], 0.f);
+    }
     xs[((uj & 1) * 32 + n) * 4 + (uj >> 1)] = valid ? hv : 0.f;
     __syncthreads();
     if (threadIdx.x < 64)
@@ -1591,10 +1610,12 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
         const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 32 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
-          *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * G + (size_t)arr * H + u0 + 4 * hf) = v;
+          if (CELL <= 1) *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
         } else if (arr == 4) {
-          *reinterpret_cast<floatx4*>(res_c + e) = v;
-          if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + (size_t)b2 * H + u0 + 4 * hf) = v;
+          if (CELL == 0) {
+            *reinterpret_cast<floatx4*>(res_c + e) = v;
+            if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + (size_t)b2 * H + u0 + 4 * hf) = v;
+          }
         } else {
           *reinterpret_cast<floatx4*>(res_h + e) = v;
           if (a.y) *reinterpret_cast<floatx4*>(a.y + e) = v;
@@ -1661,9 +1682,14 @@ struct PersBwdLArgs {
   int trace_block;
 };
 
-template <int HH>
+// CELL as in pers_bwd32_kernel: the four K groups of a unit octet are the gradients with respect to the four gate
+// pre-activations (LSTM); to the r and z pre-activations, W_n x + b_n and R_n h (GRU: the third has no weights here,
+// dh_{t-1} also receives dh_t o z_t); to the one pre-activation (single gate).  For the other cells `res` is that
+// cell's reserve, c0 carries h0, dcT / dc0 are unused, R and db have 3H or H rows.
+template <int HH, int CELL>
 __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   constexpr int H = HH, G = 4 * H, UB = 128, NBK = H / UB;
+  constexpr int NG = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1);  // gate blocks of R and db
   constexpr int UF = UB / NBK;               // units a workgroup finalises: 8 or 16
   constexpr int CPT = UF / 8;                // cells per thread in the point-wise stage
   constexpr int NG8 = 4 * UB / 8;            // 8-k groups of the tile's K = 4*UB
@@ -1696,7 +1722,10 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     for (int p = 0; p < KP; ++p) {
       const int k8 = ((p >> 2) + rot) & (NG8 - 1), m = p & 3;
       const int unit = UB * i + 8 * (k8 >> 2) + 2 * m + kk;
-      const float v = col[((size_t)(k8 & 3) * H + unit) * H];
+      const int grp = k8 & 3;
+      const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);
+      const bool live = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0);
+      const float v = live ? col[((size_t)gate * H + unit) * H] : 0.f;
       if (p < RP)
         wreg[p < RP ? p : 0] = v;
       else
@@ -1713,13 +1742,13 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
 #pragma unroll
   for (int c = 0; c < CPT; ++c) {
     cu[c] = UB * j + UF * i + 8 * c + j8;
-    dc[c] = (valid && a.dcT) ? a.dcT[(size_t)bb * H + cu[c]] : 0.f;
+    dc[c] = (CELL == 0 && valid && a.dcT) ? a.dcT[(size_t)bb * H + cu[c]] : 0.f;  // GRU: the direct term dh_t o z_t
     dh_rec[c] = (valid && a.dhT) ? a.dhT[(size_t)bb * H + cu[c]] : 0.f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) dbsum[c][g] = 0.f;
   }
-  const float* const res_gates = a.res;
-  const float* const res_c = a.res + TB * 4 * H;
+  const float* const res_gates = CELL == 0 ? a.res : a.res + TB * H;  // the four saved arrays [T][B][4H] (LSTM, GRU)
+  const float* const res_c = CELL == 0 ? a.res + TB * 4 * H : a.res;   // c (LSTM) or h: the state array the step reads
   float* const Xs = a.X + (size_t)sl * T * NBK * (4 * UB * 32);
   float* const Ps = a.Pp + (size_t)sl * T * NBK * NBK * (UB * 32);
   int* const fA = a.flagsA + (size_t)sl * T * NBK * kFlagInts;
@@ -1738,10 +1767,12 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       for (int c = 0; c < CPT; ++c) {
         const size_t e = ((size_t)t * B + bb) * H + cu[c];
         const size_t g0 = ((size_t)t * B + bb) * G + cu[c];
+        if (CELL <= 1) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) fg[c][g] = res_gates[g0 + (size_t)g * H];
-        fct[c] = res_c[e];
-        fcp[c] = t > 0 ? res_c[e - (size_t)B * H] : (a.c0 ? a.c0[(size_t)bb * H + cu[c]] : 0.f);
+          for (int g = 0; g < 4; ++g) fg[c][g] = res_gates[g0 + (size_t)g * H];
+        }
+        if (CELL != 1) fct[c] = res_c[e];  // c_t (LSTM), h_t (single gate)
+        if (CELL <= 1) fcp[c] = t > 0 ? res_c[e - (size_t)B * H] : (a.c0 ? a.c0[(size_t)bb * H + cu[c]] : 0.f);
         fdo[c] = a.dout[e];
       }
     }
@@ -1758,13 +1789,24 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       float dA4[4] = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
         const float dh = fdo[c] + dh_rec[c];
-        const float tc = tanhf_dev(fct[c]);
-        const float dcv = dc[c] + dh * fg[c][2] * (1.f - tc * tc);
-        dA4[0] = dcv * fg[c][3] * fg[c][0] * (1.f - fg[c][0]);
-        dA4[1] = dcv * fcp[c] * fg[c][1] * (1.f - fg[c][1]);
-        dA4[2] = dh * tc * fg[c][2] * (1.f - fg[c][2]);
-        dA4[3] = dcv * fg[c][0] * (1.f - fg[c][3] * fg[c][3]);
-        dc[c] = dcv * fg[c][1];
+        if (CELL == 0) {
+          const float tc = tanhf_dev(fct[c]);
+          const float dcv = dc[c] + dh * fg[c][2] * (1.f - tc * tc);
+          dA4[0] = dcv * fg[c][3] * fg[c][0] * (1.f - fg[c][0]);
+          dA4[1] = dcv * fcp[c] * fg[c][1] * (1.f - fg[c][1]);
+          dA4[2] = dh * tc * fg[c][2] * (1.f - fg[c][2]);
+          dA4[3] = dcv * fg[c][0] * (1.f - fg[c][3] * fg[c][3]);
+          dc[c] = dcv * fg[c][1];
+        } else if (CELL == 1) {  // fg: r, z, n, R_n h; fcp: h_{t-1}
+          const float dn = dh * (1.f - fg[c][1]) * (1.f - fg[c][2] * fg[c][2]);
+          dA4[0] = dn * fg[c][3] * fg[c][0] * (1.f - fg[c][0]);
+          dA4[1] = dh * (fcp[c] - fg[c][2]) * fg[c][1] * (1.f - fg[c][1]);
+          dA4[2] = dn;
+          dA4[3] = dn * fg[c][0];
+          dc[c] = dh * fg[c][1];
+        } else {  // fct: h_t
+          dA4[0] = CELL == 3 ? dh * (1.f - fct[c] * fct[c]) : (fct[c] > 0.f ? dh : 0.f);
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) dbsum[c][g] += dA4[g];
       }
@@ -1861,7 +1903,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       float sum = 0.f;
 #pragma unroll
       for (int ib = 0; ib < NBK; ++ib) sum += pv[ib];
-      dh_rec[c] = sum;
+      dh_rec[c] = CELL == 1 ? sum + dc[c] : sum;
     }
     tr.mark(t, 5);
     if (t > 0) pointwise_publish(t - 1);
@@ -1871,7 +1913,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       if (a.dh0) a.dh0[(size_t)bb * H + cu[c]] = dh_rec[c];
-      if (a.dc0) a.dc0[(size_t)bb * H + cu[c]] = dc[c];
+      if (CELL == 0 && a.dc0) a.dc0[(size_t)bb * H + cu[c]] = dc[c];
     }
   }
   if (a.db) {  // single slice: this workgroup owns its units for every batch row, plain sums, no atomics
@@ -1881,7 +1923,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) stage[(g * UF + 8 * c + j8) * 32 + n] = dbsum[c][g];
     __syncthreads();
-    if (threadIdx.x < 4 * UF) {
+    if (threadIdx.x < NG * UF) {
       float sum = 0.f;
 #pragma unroll
       for (int q = 0; q < 32; ++q) sum += stage[threadIdx.x * 32 + ((q + threadIdx.x) & 31)];
@@ -2099,11 +2141,11 @@ bool persistent_supported(const Dims& d, bool backward) {
 
 namespace {
 
-template <int HH>
+template <int HH, int CELL>
 hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
   constexpr int KPW = HH / 8, LP = KPW > 128 ? KPW - 128 : 0;
   const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
-  const void* fn = (const void*)pers_fwdL_kernel<HH>;
+  const void* fn = (const void*)pers_fwdL_kernel<HH, CELL>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -2115,9 +2157,25 @@ hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
 }
 
 // Forward pass of the large-H shapes: per layer the batched input projection, then one persistent launch.
-int run_forward_persistent_large(const FwdArgs& a) {
+// Dispatch over (hidden size, cell) of the one-layer kernels.
+hipError_t launch_fwdL_any(int H, int cell, const PersFwdLArgs& k, hipStream_t s) {
+  if (H == 2048) {
+    return cell == 0 ? launch_fwdL<2048, 0>(k, s) : (cell == 1 ? launch_fwdL<2048, 1>(k, s)
+                     : (cell == 2 ? launch_fwdL<2048, 2>(k, s) : launch_fwdL<2048, 3>(k, s)));
+  }
+  return cell == 0 ? launch_fwdL<1024, 0>(k, s) : (cell == 1 ? launch_fwdL<1024, 1>(k, s)
+                   : (cell == 2 ? launch_fwdL<1024, 2>(k, s) : launch_fwdL<1024, 3>(k, s)));
+}
+
+// Reserve of one layer in floats per (step, row, unit), and where its hidden states start, for each cell.
+inline size_t res_width(int cell) { return cell == 0 ? 6 : (cell == 1 ? 5 : 1); }
+inline size_t res_h_offset(int cell, size_t TB, int H) { return cell == 0 ? 5 * TB * H : 0; }
+inline int gates_of_cell(int cell) { return cell == 0 ? 4 : (cell == 1 ? 3 : 1); }
+
+int run_forward_persistent_large(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
-  const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
+  const size_t TB = (size_t)d.T * d.B, G = (size_t)gates_of_cell(cell) * d.H, BH = (size_t)d.B * d.H;
+  const size_t rstride = res_width(cell) * TB * d.H;
   hipStream_t s = a.stream;
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
@@ -2131,10 +2189,11 @@ int run_forward_persistent_large(const FwdArgs& a) {
   if (cap > 4) cap = 4;
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
-    const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
+    const float* in = l == 0 ? a.x : a.reserve + (size_t)(l - 1) * rstride + res_h_offset(cell, TB, d.H);
+    const float* Wl = a.W + (l == 0 ? 0 : G * d.I + (size_t)(l - 1) * G * d.H);
     {
       ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
-      GemmProblem p{in, a.W + w_offset(d, l), P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
+      GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
       CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
     }
    for (int s0 = 0; s0 < slices; s0 += cap) {
@@ -2149,9 +2208,10 @@ int run_forward_persistent_large(const FwdArgs& a) {
     PersFwdLArgs k;
     k.b0 = 32 * s0; k.nsl = nsl;
     k.R = a.R + (size_t)l * G * d.H; k.bias = a.b + (size_t)l * G; k.P = P;
-    k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
+    const float* state0 = cell == 0 ? a.c0 : (cell == 1 ? a.h0 : nullptr);  // the GRU's cell update reads h_{t-1}
+    k.c0 = state0 ? state0 + (size_t)l * BH : nullptr;
     k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
-    k.res = a.reserve + (size_t)l * TB * 6 * d.H;
+    k.res = a.reserve + (size_t)l * rstride;
     k.y = l == d.L - 1 ? a.y : nullptr;
     k.hT = a.hT ? a.hT + (size_t)l * BH : nullptr;
     k.cT = a.cT ? a.cT + (size_t)l * BH : nullptr;
@@ -2159,17 +2219,17 @@ int run_forward_persistent_large(const FwdArgs& a) {
     k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
     k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
-    CK(d.H == 2048 ? launch_fwdL<2048>(k, s) : launch_fwdL<1024>(k, s), "persistent forward launch (large H)");
+    CK(launch_fwdL_any(d.H, cell, k, s), "persistent forward launch (large H)");
    }
   }
   return LSTM_OK;
 }
 
-template <int HH>
+template <int HH, int CELL>
 hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
   constexpr int NBK = HH / 128, UF = 128 / NBK, LP = 256 - (UF == 16 ? 136 : 128);
   const size_t smem = (4096 + 128 * (size_t)UF + 128 * (size_t)UF + (size_t)4 * LP * 64) * sizeof(float);
-  const void* fn = (const void*)pers_bwdL_kernel<HH>;
+  const void* fn = (const void*)pers_bwdL_kernel<HH, CELL>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -2188,11 +2248,21 @@ namespace {
 
 // Backward pass of the large-H shapes: per layer (top down) one persistent launch for the recurrence, then
 // the batched product that hands the gradient to the layer below; weight gradients at the end.
-int run_backward_persistent_large(const BwdArgs& a) {
+hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s) {
+  if (H == 2048) {
+    return cell == 0 ? launch_bwdL<2048, 0>(k, s) : (cell == 1 ? launch_bwdL<2048, 1>(k, s)
+                     : (cell == 2 ? launch_bwdL<2048, 2>(k, s) : launch_bwdL<2048, 3>(k, s)));
+  }
+  return cell == 0 ? launch_bwdL<1024, 0>(k, s) : (cell == 1 ? launch_bwdL<1024, 1>(k, s)
+                   : (cell == 2 ? launch_bwdL<1024, 2>(k, s) : launch_bwdL<1024, 3>(k, s)));
+}
+
+int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
   const Dims& d = a.d;
   constexpr int UB = 128;
   const int NBK = d.H / UB;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
+  const size_t GW = (size_t)gates_of_cell(cell) * d.H, rstride = res_width(cell) * TB * d.H;
   hipStream_t s = a.stream;
   // slices of 32 batch rows side by side while the CUs last (four at H = 1024), the rest in further launches
   DeviceInfo di;
@@ -2219,30 +2289,34 @@ int run_backward_persistent_large(const BwdArgs& a) {
         CK(launch_fill_zero(flagsA, (size_t)2 * maxsl * d.T * NBK * kFlagInts * 4, s), "zero step counters");
       }
       PersBwdLArgs k;
-      k.R = a.R + (size_t)l * G * d.H;
-      k.res = a.reserve + (size_t)l * TB * 6 * d.H;
-      k.c0 = a.c0 ? a.c0 + (size_t)l * BH : nullptr;
+      k.R = a.R + (size_t)l * GW * d.H;
+      k.res = a.reserve + (size_t)l * rstride;
+      const float* state0 = cell == 0 ? a.c0 : a.h0;
+      k.c0 = state0 ? state0 + (size_t)l * BH : nullptr;
       k.dout = (l == d.L - 1) ? a.dy : dxb + (size_t)(l + 1) * TB * d.H;
       k.dhT = a.dhT ? a.dhT + (size_t)l * BH : nullptr;
       k.dcT = a.dcT ? a.dcT + (size_t)l * BH : nullptr;
       k.dA = dA; k.X = X; k.Pp = Pp;
       k.dh0 = a.dh0 ? a.dh0 + (size_t)l * BH : nullptr;
       k.dc0 = a.dc0 ? a.dc0 + (size_t)l * BH : nullptr;
-      k.db = bias_in_kernel ? a.db + (size_t)l * G : nullptr;
+      k.db = bias_in_kernel ? a.db + (size_t)l * GW : nullptr;
       k.flagsA = flagsA; k.flagsP = flagsP; k.watchdog = g_watch_dev;
       k.T = d.T; k.B = d.B; k.b0 = 32 * s0; k.nsl = nsl; k.spin_limit = spin_limit(); k.full_fences = full_fences();
       k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
       k.trace_block = g_trace_block;
       ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
-      CK(d.H == 2048 ? launch_bwdL<2048>(k, s) : launch_bwdL<1024>(k, s), "persistent backward launch (large H)");
+      CK(launch_bwdL_any(d.H, cell, k, s), "persistent backward launch (large H)");
     }
     float* din = l > 0 ? dxb + (size_t)l * TB * d.H : a.dx;
-    if (din) {
+    if (din) {  // the GRU's gradient with respect to W_n x is its third group: the first GW columns are the ones W multiplies
       ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
-      GemmProblem p{dA, a.W + w_offset(d, l), din, (int)TB, Il, (int)G, (long)G, 1, Il, 1, Il, 0};
+      const float* Wl = a.W + (l == 0 ? 0 : GW * d.I + (size_t)(l - 1) * GW * d.H);
+      GemmProblem p{dA, Wl, din, (int)TB, Il, (int)GW, (long)G, 1, Il, 1, Il, 0};
       CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
     }
   }
+  if (bias_done) *bias_done = bias_in_kernel;
+  if (cell != 0) return LSTM_OK;
   return weight_gradients(a, dA_all, true, bias_in_kernel);
 }
 
@@ -2251,6 +2325,7 @@ int run_backward_persistent_large(const BwdArgs& a) {
 // Wide persistent kernels for the GRU: hidden sizes and CU budget of the LSTM ones; they also take batches of 32
 // rows and fewer (the rows past the batch are zeros), where the LSTM has kernels of its own.
 bool gru_persistent_supported(const Dims& d) {
+  if (persistent_large(d, false) && persistent_large(d, true)) return true;  // one-layer kernels, H = 1024 / 2048
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
   if (d.B > 512) return false;
   DeviceInfo di;
@@ -2262,10 +2337,10 @@ bool gru_persistent_supported(const Dims& d) {
 // gru_persistent_supported; a.c0 / a.cT are null, W, R, b have 3H or H rows and a.reserve is that cell's reserve).
 int run_forward_persistent(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
-  if (cell == 0 && persistent_large(d, false)) {
+  if (persistent_large(d, false)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
     if (*g_watch_host) return LSTM_INTERNAL;
-    return run_forward_persistent_large(a);
+    return run_forward_persistent_large(a, cell);
   }
   const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
@@ -2354,10 +2429,10 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
 // reports in *bias_done whether db is complete; the caller forms the weight gradients.
 int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
   const Dims& d = a.d;
-  if (cell == 0 && persistent_large(d, true)) {
+  if (persistent_large(d, true)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
     if (*g_watch_host) return LSTM_INTERNAL;
-    return run_backward_persistent_large(a);
+    return run_backward_persistent_large(a, cell, bias_done);
   }
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;

@@ -119,7 +119,10 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
 // Shapes the persistent GRU kernels may take (device limits are checked at run time): their workspace is the LSTM
 // library's, so the buffer must hold either layout.
 inline bool gru_persistent_shape(int cell, const Dims& d) {
-  return gates_of(cell) != 0 && (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
+  if (gates_of(cell) == 0) return false;
+  if (d.H == 1024) return d.B <= 256;   // one-layer kernels
+  if (d.H == 2048) return d.B <= 32;
+  return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
 // cell selector of the templated persistent kernels
 inline int kernel_cell(int cell) { return cell == RNN_CELL_GRU ? 1 : (cell == RNN_CELL_RELU ? 2 : 3); }

@@ -106,6 +106,20 @@ def test_persistent_shapes(dims, cell, with_h0):
     run(cell, *dims, seed=5, with_h0=with_h0)
 
 
+# Large hidden sizes: the one-layer persistent kernels (recurrent matrix spread over all CUs), slices of 32 batch rows
+LARGE = [(2, 4, 32, 96, 1024), (1, 3, 64, 1024, 1024), (1, 3, 100, 64, 1024), (1, 2, 8, 128, 2048), (1, 2, 16, 64, 1024),
+         (2, 1, 5, 2048, 2048)]
+
+
+@pytest.mark.parametrize("with_h0", [True, False], ids=["h0", "noh0"])
+@pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
+@pytest.mark.parametrize("dims", LARGE, ids=["x".join(map(str, s)) for s in LARGE])
+def test_large_hidden_shapes(dims, cell, with_h0):
+    if cell == "relu" and not few_cells(dims):
+        pytest.skip("ReLU: every input of this size has pre-activations within fp32 rounding of zero")
+    run(cell, *dims, seed=8, with_h0=with_h0)
+
+
 @pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
 def test_step_by_step_path_at_a_persistent_shape(cell, monkeypatch):
     monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
