@@ -204,6 +204,7 @@ int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float*
 
   FwdArgs a{d, x, h0, c0, W, R, b, y, hT, cT,
             reserve ? (float*)reserve : (float*)((char*)workspace + w.resv), (char*)workspace, w, (hipStream_t)stream};
+  a.inference = reserve == nullptr;
   unsigned path = flags & LSTM_PATH_MASK;
   if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, false);
   return run_forward(a, path);

@@ -232,6 +232,7 @@ struct PersFwdArgs {
   int full_fences;
   long long* trace;
   int trace_block;
+  int keep;           // wide kernel: 0 = inference call (no reserve wanted): only y, hT, cT are written
 };
 
 // KG: k-groups (of 4) per wave and per operand half = H/16.  NT: batch tiles of 16 per chain.
@@ -627,7 +628,9 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
     tr.mark(t, 6);
     // The reserve and the outputs are not read before the kernel ends, so they are written after the
     // signal -- staged through LDS so that each store instruction writes 16-byte runs (scattered
-    // 4-byte stores keep the address unit busy for longer than the whole epilogue).
+    // 4-byte stores keep the address unit busy for longer than the whole epilogue).  An inference call
+    // has nothing to write for the lower layers except the final states.
+    if (!(a.keep || l == a.L - 1 || t == T - 1)) return;
 #pragma unroll
     for (int ci = 0; ci < 2; ++ci) {
       const int ul = 4 * kk + 2 * up + ci;
@@ -646,14 +649,14 @@ __global__ __launch_bounds__(256) void pers_fwd32_kernel(const PersFwdArgs a) {
         const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * 64 + l2) * 8 + 4 * hf);
         const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
         if (arr < 4) {
-          if (CELL <= 1) *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
+          if (CELL <= 1 && a.keep) *reinterpret_cast<floatx4*>(res_gates + ((size_t)t * B + b2) * 4 * H + (size_t)arr * H + u0 + 4 * hf) = v;
         } else if (arr == 4) {
           if (CELL == 0) {
-            *reinterpret_cast<floatx4*>(res_c + e) = v;
+            if (a.keep) *reinterpret_cast<floatx4*>(res_c + e) = v;
             if (t == T - 1 && a.cT) *reinterpret_cast<floatx4*>(a.cT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
           }
         } else {
-          *reinterpret_cast<floatx4*>(res_h + e) = v;
+          if (a.keep) *reinterpret_cast<floatx4*>(res_h + e) = v;
           if (l == a.L - 1) *reinterpret_cast<floatx4*>(a.y + e) = v;
           if (t == T - 1 && a.hT) *reinterpret_cast<floatx4*>(a.hT + ((size_t)l * B + b2) * H + u0 + 4 * hf) = v;
         }
@@ -2371,6 +2374,7 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
   }
   PersFwdArgs k;
   k.xin = x_in_kernel ? P0 : nullptr;
+  k.keep = a.inference ? 0 : 1;
   k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.h0 = a.h0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
   k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();

@@ -32,6 +32,7 @@ struct FwdArgs {
   char* ws;
   WsLayout w;
   hipStream_t stream;
+  bool inference = false;  // the caller passed no reserve: `reserve` is a stand-in inside the workspace, nobody reads it
 };
 
 struct BwdArgs {
