@@ -15,7 +15,7 @@ import torch
 
 from . import binding as B_
 
-CANDIDATES = (B_.LSTM_PATH_STEP, B_.LSTM_PATH_WAVEFRONT, B_.LSTM_PATH_PERSISTENT)
+CANDIDATES = (B_.LSTM_PATH_FUSED, B_.LSTM_PATH_STEP, B_.LSTM_PATH_WAVEFRONT, B_.LSTM_PATH_PERSISTENT)
 
 
 def tune(L, T, B, I, H, iters=3, device="cuda:0", register=True):

@@ -75,9 +75,14 @@ unsigned resolve_auto_path(const Dims& d, bool backward) {
       if (same_shape(o.d, d) && o.backward == backward) return o.path;
   }
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
+  const int cus = device_cu_count();
+  // Section 3.2 observes that at large minibatches the individual optimisations stop paying.  Here: once the plain
+  // [B x 4H] x [H] product of one step fills every CU with 128 x 128 tiles, the GEMM kernel (grouped gates, fused
+  // point-wise kernel) beats the step kernel, which is built to stream R past a small batch -- forward by 25-30 %
+  // (H = 4096 with B >= 256, H = 2048 with B >= 512); backward the two are within a few per cent either way.
+  if (!backward && cus > 0 && (long)((d.B + 127) / 128) * (4L * d.H / 128) >= cus) return LSTM_PATH_FUSED;
   // Overlapping layers on streams pays when one step kernel leaves CUs idle (Section 2.4: the
   // gain is largest for small layers); a step that already fills the chip runs layer by layer.
-  const int cus = device_cu_count();
   const long wgs = (long)((d.H + 3) / 4) * ((d.B + 63) / 64);
   if (d.L > 1 && (cus == 0 || wgs < 2L * cus)) return LSTM_PATH_WAVEFRONT;
   return LSTM_PATH_STEP;
