@@ -17,9 +17,10 @@
  * layers stacked as Section 2.4 describes.  The reset gate multiplies the recurrent product, so the
  * three recurrent matrices run as one stacked product per step (the grouping of Section 2.1).
  *
- * What runs: with H = 128, 256 or 512 (and L*H/8 no more than the CU count, B <= 512) the
+ * What runs: with H = 128, 256 or 512 (B <= 512) the
  * persistent kernels of lstm.h with the weights on chip for all T steps (Section 4) and the layers
- * as a wavefront inside one launch (2.4): their 32-row tile per workgroup holds, for 8 hidden units,
+ * as a wavefront inside one launch (2.4; as many layers per launch as L*H/8 workgroups fit the CUs,
+ * deeper stacks as consecutive groups of layers): their 32-row tile per workgroup holds, for 8 hidden units,
  * r, z and the input and recurrent halves of n (GRU), or the one gate and three empty groups
  * (single gate); with H = 1024 (B <= 256) or H = 2048 (B <= 32) the one-layer persistent kernels
  * with the recurrent matrix spread over all CUs.  Every other shape runs on the rungs of the paper's ladder that do not depend on the

@@ -2139,7 +2139,7 @@ bool persistent_supported(const Dims& d, bool backward) {
   if (d.B > 512) return false;  // above 64 rows the batch is processed in slices of 64, one launch per slice
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
-  return (long)d.L * (d.H / 8) <= di.cus;
+  return d.H / 8 <= di.cus;  // deeper stacks than the chip holds run as groups of layers (run_forward_persistent)
 }
 
 namespace {
@@ -2333,11 +2333,25 @@ bool gru_persistent_supported(const Dims& d) {
   if (d.B > 512) return false;
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
-  return (long)d.L * (d.H / 8) <= di.cus;
+  return d.H / 8 <= di.cus;  // deeper stacks than the chip holds run as groups of layers
 }
 
 // cell: 0 = LSTM; 1 = GRU, 2 / 3 = single-gate RNN with ReLU / tanh (wide kernels only: the caller has checked
 // gru_persistent_supported; a.c0 / a.cT are null, W, R, b have 3H or H rows and a.reserve is that cell's reserve).
+// Layers that fit on the chip together: L * H/8 workgroups, one per CU.
+int layers_per_launch(const Dims& d) {
+  DeviceInfo di;
+  if (!device_info(di)) return 0;
+  return di.cus / (d.H / 8);
+}
+
+int forward_layers(const FwdArgs& a, int cell);
+int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weight_gradients);
+
+// A stack deeper than the chip holds at once runs as groups of consecutive layers, one group per launch (per batch
+// slice group): the hidden states of a group's top layer, all T steps, are the input sequence of the next group --
+// the same situation as x for layer 0 (Section 2.3) -- and backward the gradient a group's bottom layer produces for
+// its input is the upstream gradient of the group below.
 int run_forward_persistent(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
   if (persistent_large(d, false)) {
@@ -2345,6 +2359,38 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_forward_persistent_large(a, cell);
   }
+  const int per = layers_per_launch(d);
+  if (per <= 0) return LSTM_UNSUPPORTED;
+  if (d.L <= per) return forward_layers(a, cell);
+  const size_t TB = (size_t)d.T * d.B, BH = (size_t)d.B * d.H, G = (size_t)gates_of_cell(cell) * d.H;
+  const size_t rstride = res_width(cell) * TB * d.H;
+  for (int g0 = 0; g0 < d.L; g0 += per) {
+    FwdArgs g = a;
+    g.d.L = d.L - g0 < per ? d.L - g0 : per;
+    const int top = g0 + g.d.L - 1;
+    if (g0 > 0) {
+      g.d.I = d.H;
+      g.x = a.reserve + (size_t)(g0 - 1) * rstride + res_h_offset(cell, TB, d.H);
+      g.W = a.W + G * d.I + (size_t)(g0 - 1) * G * d.H;
+    }
+    g.R = a.R + (size_t)g0 * G * d.H;
+    g.b = a.b + (size_t)g0 * G;
+    g.h0 = a.h0 ? a.h0 + (size_t)g0 * BH : nullptr;
+    g.c0 = a.c0 ? a.c0 + (size_t)g0 * BH : nullptr;
+    g.hT = a.hT ? a.hT + (size_t)g0 * BH : nullptr;
+    g.cT = a.cT ? a.cT + (size_t)g0 * BH : nullptr;
+    g.reserve = a.reserve + (size_t)g0 * rstride;
+    // a group's top layer always leaves its hidden states where the next group reads them (an inference call writes
+    // nothing else of the reserve): y of the group is that array
+    if (top < d.L - 1) g.y = a.reserve + (size_t)top * rstride + res_h_offset(cell, TB, d.H);
+    const int st = forward_layers(g, cell);
+    if (st != LSTM_OK) return st;
+  }
+  return LSTM_OK;
+}
+
+int forward_layers(const FwdArgs& a, int cell) {
+  const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
@@ -2438,6 +2484,50 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
     if (*g_watch_host) return LSTM_INTERNAL;
     return run_backward_persistent_large(a, cell, bias_done);
   }
+  const int per = layers_per_launch(d);
+  if (per <= 0) return LSTM_UNSUPPORTED;
+  if (d.L <= per) return backward_layers(a, cell, bias_done, true);
+  const size_t TB = (size_t)d.T * d.B, BH = (size_t)d.B * d.H, GW = (size_t)gates_of_cell(cell) * d.H;
+  const size_t rstride = res_width(cell) * TB * d.H;
+  const int ngroups = (d.L + per - 1) / per;
+  bool all_bias = true;
+  for (int gi = ngroups - 1; gi >= 0; --gi) {  // top group first
+    const int g0 = gi * per;
+    BwdArgs g = a;
+    g.d.L = d.L - g0 < per ? d.L - g0 : per;
+    const int above = g0 + g.d.L;  // first layer of the group above, if any
+    // the gradient handed from group to group lives in the hand-over array of the workspace, slot = receiving layer + 1
+    float* const handover = reinterpret_cast<float*>(a.ws + a.w.dx);
+    if (g0 > 0) {
+      g.d.I = d.H;
+      g.x = a.reserve + (size_t)(g0 - 1) * rstride + res_h_offset(cell, TB, d.H);
+      g.W = a.W + GW * d.I + (size_t)(g0 - 1) * GW * d.H;
+      g.dx = handover + (size_t)g0 * TB * d.H;
+    }
+    if (above < d.L) g.dy = handover + (size_t)above * TB * d.H;
+    g.R = a.R + (size_t)g0 * GW * d.H;
+    g.h0 = a.h0 ? a.h0 + (size_t)g0 * BH : nullptr;
+    g.c0 = a.c0 ? a.c0 + (size_t)g0 * BH : nullptr;
+    g.dhT = a.dhT ? a.dhT + (size_t)g0 * BH : nullptr;
+    g.dcT = a.dcT ? a.dcT + (size_t)g0 * BH : nullptr;
+    g.dh0 = a.dh0 ? a.dh0 + (size_t)g0 * BH : nullptr;
+    g.dc0 = a.dc0 ? a.dc0 + (size_t)g0 * BH : nullptr;
+    g.db = a.db ? a.db + (size_t)g0 * GW : nullptr;
+    g.reserve = a.reserve + (size_t)g0 * rstride;
+    g.w.P = a.w.P + (size_t)g0 * TB * 4 * d.H * sizeof(float);   // gate gradients of the group's layers, in place
+    g.w.dx = a.w.dx + (size_t)g0 * TB * d.H * sizeof(float);
+    bool done = false;
+    const int st = backward_layers(g, cell, &done, false);
+    if (st != LSTM_OK) return st;
+    all_bias = all_bias && done;
+  }
+  if (bias_done) *bias_done = all_bias;
+  if (cell != 0) return LSTM_OK;
+  return weight_gradients(a, reinterpret_cast<const float*>(a.ws + a.w.P), true, all_bias);
+}
+
+int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weight_gradients) {
+  const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
@@ -2504,7 +2594,7 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
     CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");
   }
   if (bias_done) *bias_done = k.db != nullptr;
-  if (cell != 0) return LSTM_OK;
+  if (cell != 0 || !with_weight_gradients) return LSTM_OK;
   return weight_gradients(a, dA, true, k.db != nullptr);
 }
 

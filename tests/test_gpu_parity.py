@@ -169,6 +169,31 @@ def test_persistent_large_hidden(cfg, with_states):
     run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
+# Stacks deeper than the chip holds at once (L * H/8 workgroups > CUs): groups of consecutive layers, one launch each
+DEEP = [
+    Config("d512L8", L=8, T=5, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),      # 4 + 4, x multiplied in the kernel
+    Config("d512L5", L=5, T=4, B=40, I=72, H=512, state_std=0.3, dstate_std=0.3),       # 4 + 1, x projected by a GEMM
+    Config("d512L6b8", L=6, T=6, B=8, I=512, H=512, state_std=0.3, dstate_std=0.3),     # narrow kernels, 4 + 2
+    Config("d256L9b130", L=9, T=3, B=130, I=256, H=256, state_std=0.3, dstate_std=0.3),  # 8 + 1, three batch slices
+    Config("d128L17", L=17, T=3, B=33, I=24, H=128, state_std=0.3, dstate_std=0.3),     # 16 + 1
+]
+
+
+@pytest.mark.parametrize("cfg", DEEP, ids=[c.name for c in DEEP])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_persistent_layer_groups(cfg, with_states):
+    torch, binding, _ = _mods()
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_PERSISTENT
+    r, ref = run_case(cfg, 13, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
+    # an inference call (no reserve) hands the hidden states from group to group through the workspace
+    y_train = r.y.clone()
+    r.y.fill_(float("nan"))
+    binding.check(r.forward(flags=binding.LSTM_PATH_PERSISTENT, inference=True))
+    torch.cuda.synchronize()
+    assert torch.equal(r.y, y_train)
+
+
 # ------------------------------------------------------------------ persistent path: kernel variants and the slow protocol
 VARIANTS = [
     {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1"},                      # 16x16x4 kernels at B > 32

@@ -107,6 +107,18 @@ def test_persistent_shapes(dims, cell, with_h0):
     run(cell, *dims, seed=5, with_h0=with_h0)
 
 
+# Stacks deeper than the chip holds at once: groups of consecutive layers, one launch per group
+DEEP = [(5, 4, 64, 512, 512), (6, 3, 130, 512, 512), (9, 3, 20, 48, 256), (17, 2, 8, 128, 128)]
+
+
+@pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
+@pytest.mark.parametrize("dims", DEEP, ids=["x".join(map(str, s)) for s in DEEP])
+def test_persistent_layer_groups(dims, cell):
+    if cell == "relu" and not few_cells(dims):
+        pytest.skip("ReLU: every input of this size has pre-activations within fp32 rounding of zero")
+    run(cell, *dims, seed=9)
+
+
 # Large hidden sizes: the one-layer persistent kernels (recurrent matrix spread over all CUs), slices of 32 batch rows
 LARGE = [(2, 4, 32, 96, 1024), (1, 3, 64, 1024, 1024), (1, 3, 100, 64, 1024), (1, 2, 8, 128, 2048), (1, 2, 16, 64, 1024),
          (2, 1, 5, 2048, 2048)]
