@@ -2122,12 +2122,14 @@ void release_persistent() {
 // Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
 // Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward).
 constexpr int kLargeMaxBatch1024 = 256;
+// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice.
+constexpr int kLargeMaxBatch2048 = 256;
 
 bool persistent_large(const Dims& d, bool backward) {
   const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");
   if (e && *e == '1') return false;
   if (!(d.H == 1024 || d.H == 2048)) return false;
-  if (d.B > (d.H == 1024 ? kLargeMaxBatch1024 : 32)) return false;  // H = 2048 fills the chip with one slice of 32 rows
+  if (d.B > (d.H == 1024 ? kLargeMaxBatch1024 : kLargeMaxBatch2048)) return false;
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return (backward ? (d.H / 128) * (d.H / 128) : d.H / 8) <= di.cus;

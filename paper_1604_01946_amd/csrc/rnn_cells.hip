@@ -121,7 +121,7 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
 inline bool gru_persistent_shape(int cell, const Dims& d) {
   if (gates_of(cell) == 0) return false;
   if (d.H == 1024) return d.B <= 256;   // one-layer kernels
-  if (d.H == 2048) return d.B <= 32;
+  if (d.H == 2048) return d.B <= 256;
   return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
 // cell selector of the templated persistent kernels

@@ -121,7 +121,7 @@ def test_persistent_layer_groups(dims, cell):
 
 # Large hidden sizes: the one-layer persistent kernels (recurrent matrix spread over all CUs), slices of 32 batch rows
 LARGE = [(2, 4, 32, 96, 1024), (1, 3, 64, 1024, 1024), (1, 3, 100, 64, 1024), (1, 2, 8, 128, 2048), (1, 2, 16, 64, 1024),
-         (2, 1, 5, 2048, 2048)]
+         (2, 1, 5, 2048, 2048), (1, 2, 40, 64, 2048)]
 
 
 @pytest.mark.parametrize("with_h0", [True, False], ids=["h0", "noh0"])
