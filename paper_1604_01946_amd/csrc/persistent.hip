@@ -2120,10 +2120,12 @@ void release_persistent() {
 }
 
 // Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
-// Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward).
-constexpr int kLargeMaxBatch1024 = 256;
-// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice.
-constexpr int kLargeMaxBatch2048 = 256;
+// Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward):
+// measured faster than the step kernels up to here (108 against 89 TFLOP/s at B = 512).
+constexpr int kLargeMaxBatch1024 = 512;
+// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice.  From 512 rows on one step's
+// product fills the chip as a plain GEMM and that rung is faster (112 against 107 TFLOP/s).
+constexpr int kLargeMaxBatch2048 = 511;
 
 bool persistent_large(const Dims& d, bool backward) {
   const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");

@@ -157,6 +157,7 @@ LARGE = [
     Config("l1024b100", L=2, T=3, B=100, I=64, H=1024, state_std=0.3, dstate_std=0.3),
     Config("l1024b128", L=1, T=2, B=128, I=32, H=1024, state_std=0.3, dstate_std=0.3),
     Config("l1024b160", L=1, T=2, B=160, I=48, H=1024, state_std=0.3, dstate_std=0.3),   # five slices: a second backward launch
+    Config("l1024b300", L=1, T=2, B=300, I=32, H=1024, state_std=0.3, dstate_std=0.3),   # ten slices
     # H = 2048 above 32 rows: one slice fills the chip, the slices run one after the other
     Config("l2048b40", L=1, T=2, B=40, I=64, H=2048, state_std=0.3, dstate_std=0.3),
     Config("l2048b70", L=2, T=2, B=70, I=32, H=2048, state_std=0.3, dstate_std=0.3),
