@@ -153,13 +153,9 @@ struct Tracer {
   }
 };
 
-// Store that other workgroups will read during this launch.
-__device__ __forceinline__ void xstore(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// 16-byte variant: the exchange tiles are staged in LDS and written as whole 128-byte lines, which
-// the memory side takes far better than scattered 4-byte write-through stores.
+// Store that other workgroups will read during this launch (write-through past the CU's cache): the exchange tiles
+// are staged in LDS and written as whole 128-byte lines, 16 bytes per lane, which the memory side takes far better
+// than scattered 4-byte write-through stores.
 // A store of more than 8 bytes reads its data registers over several cycles after it has issued,
 // and an instruction that overwrites them must keep its distance (two idle cycles on this
 // architecture).  The compiler keeps that distance for its own stores but cannot see one inside

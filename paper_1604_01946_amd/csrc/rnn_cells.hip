@@ -120,8 +120,11 @@ inline size_t res_layer_floats(int cell, const Dims& d) {
 // library's, so the buffer must hold either layout.
 inline bool gru_persistent_shape(int cell, const Dims& d) {
   if (gates_of(cell) == 0) return false;
-  if (d.H == 1024) return d.B <= 512;   // one-layer kernels
-  if (d.H == 2048) return d.B <= 256;   // above, the step-by-step path with its large products is faster for these cells
+  // one-layer kernels: up to the batch where the step-by-step path with its large products measured faster (the
+  // single gate leaves three quarters of the persistent kernels' tiles empty, so its break-even comes earlier)
+  const bool gru = cell == RNN_CELL_GRU;
+  if (d.H == 1024) return d.B <= (gru ? 512 : 256);
+  if (d.H == 2048) return d.B <= (gru ? 256 : 96);
   return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
 // cell selector of the templated persistent kernels
