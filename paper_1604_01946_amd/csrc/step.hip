@@ -323,14 +323,21 @@ hipError_t launch_bwd_nt(const StepBwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
-// 8 units per workgroup halve the re-reads of h_{t-1}; 4 units double the workgroup count when 8
-// would leave CUs idle.
-int step_fwd_mtiles(int H, int B) { return (((H + 7) / 8) * batch_tiles_y(B) < 200) ? 1 : 2; }
+// Every workgroup reads all of h_{t-1} for its batch rows: 8 units per workgroup halve those re-reads against 4,
+// 16 halve them again (at H = 4096 they are otherwise twice the stream of R itself); fewer units per workgroup
+// where more would leave CUs idle.
+int step_fwd_mtiles(int H, int B) {
+  const char* e = getenv("LSTM_STEP_MT");
+  if (e && (*e == '1' || *e == '2' || *e == '4')) return *e - '0';
+  if (((H + 15) / 16) * batch_tiles_y(B) >= 200) return 4;
+  return (((H + 7) / 8) * batch_tiles_y(B) < 200) ? 1 : 2;
+}
 int step_bwd_units(int H, int B) { return (((H + 15) / 16) * batch_tiles_y(B) < 192) ? 8 : 16; }
 
 size_t step_pack_floats(int H) {
   // upper bound of both packed layouts for one layer, in floats
-  const size_t fwd = (size_t)((H + 3) / 4) * 4 * ksteps_per_wave(H) * 2 * 256;
+  // forward: ceil(H / (4 MT)) slices of MT m-tiles, MT <= 4: at most (H + 3) / 4 + 3 m-tiles of 4 waves x per x 256 floats
+  const size_t fwd = (size_t)((H + 3) / 4 + 3) * 4 * ksteps_per_wave(H) * 256;
   const size_t bwd = (size_t)((H + 7) / 8) * 4 * ksteps_per_wave(4 * H) * 256;
   return fwd > bwd ? fwd : bwd;
 }
@@ -351,8 +358,9 @@ hipError_t launch_pack_bwd(const float* R, float* RTp, int L, int H, int B, size
 
 hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
   const bool vec = (a.H % 4 == 0) && (a.h_prev == nullptr || aligned16(a.h_prev));
-  if (step_fwd_mtiles(a.H, a.B) == 1)
-    return vec ? launch_fwd_mt<1, true>(a, stream) : launch_fwd_mt<1, false>(a, stream);
+  const int MT = step_fwd_mtiles(a.H, a.B);
+  if (MT == 1) return vec ? launch_fwd_mt<1, true>(a, stream) : launch_fwd_mt<1, false>(a, stream);
+  if (MT == 4) return vec ? launch_fwd_mt<4, true>(a, stream) : launch_fwd_mt<4, false>(a, stream);
   return vec ? launch_fwd_mt<2, true>(a, stream) : launch_fwd_mt<2, false>(a, stream);
 }
 

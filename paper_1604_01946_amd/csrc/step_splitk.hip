@@ -46,42 +46,48 @@ __device__ __forceinline__ void xstore4(float* p, floatx4 v) {
 }
 
 // True in exactly one workgroup per (row slice, launch): the one whose partial arrived last.
-__device__ __forceinline__ bool last_arrival(int* counter, int expected) {
-  __shared__ int s_last;
+// `s_last`: one int of LDS that no thread touches otherwise from here on.
+__device__ __forceinline__ bool last_arrival(int* counter, int expected, int* s_last) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's write-through partial stores are acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
     const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (old == expected - 1);
+    *s_last = (old == expected - 1);
   }
   __syncthreads();
   // The partial sums were written through to memory before each arrival was counted, and this
   // workgroup has not touched those lines since the launch began (a launch starts with clean
   // caches), so its first reads fetch the published values: no cache invalidate is needed.
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
-  return s_last != 0;
+  return *s_last != 0;
 }
 
 // ------------------------------------------------------------------ pack (once per pass)
-// backward: [unit slice of 64][K slice][wave][k-step][lane][4] over R^T (row = hidden unit, K = 4H)
+// k-steps (of 16) of a K slice that one wave takes: the four waves of a workgroup split the slice
+__host__ __device__ inline int sk_per_wave(int per) { return (per + 3) / 4; }
+
+// backward: [unit slice of 64][K slice][wave][k-step of the wave][m-tile of 16 units][lane][4] over R^T
+// (row = hidden unit, K = 4H); zero where the slice, the wave's share or K runs out.
 __global__ void pack_bwd_sk_kernel(const float* __restrict__ R, floatx4* __restrict__ Rp, int H, int KS, int per,
                                    long per_layer) {
-  const int K = 4 * H, NUS = (H + 63) / 64;
-  const long total = (long)NUS * KS * 4 * per * 64;
+  const int K = 4 * H, NUS = (H + 63) / 64, perw = sk_per_wave(per);
+  const long total = (long)NUS * KS * 4 * perw * 4 * 64;
   const float* Rl = R + (size_t)blockIdx.y * 4 * H * H;
   floatx4* out = Rp + (size_t)blockIdx.y * per_layer;
   for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
     const int lane = (int)(i & 63);
     long r = i >> 6;
-    const int ksl = (int)(r % per); r /= per;
+    const int mt = (int)(r & 3); r >>= 2;
+    const int ksl = (int)(r % perw); r /= perw;
     const int w = (int)(r & 3); r >>= 2;
     const int ks = (int)(r % KS);
     const int us = (int)(r / KS);
     const int q = lane >> 4, n = lane & 15;
-    const int unit = us * 64 + 16 * w + n;
-    const int k = (ks * per + ksl) * 16 + 4 * q;
+    const int unit = us * 64 + 16 * mt + n;
+    const int kstep = w * perw + ksl;  // within the K slice
+    const int k = (ks * per + kstep) * 16 + 4 * q;
     floatx4 v = {0.f, 0.f, 0.f, 0.f};
-    if (unit < H) {
+    if (unit < H && kstep < per) {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (k + e < K) v[e] = Rl[(size_t)(k + e) * H + unit];
@@ -91,10 +97,14 @@ __global__ void pack_bwd_sk_kernel(const float* __restrict__ R, floatx4* __restr
 }
 
 // ------------------------------------------------------------------ backward
-// grid.x = NUS * KS (K slice fastest), grid.y = batch tiles.  Wave w owns units u0+16w..u0+16w+15.
+// grid.x = NUS * KS (K slice fastest), grid.y = batch tiles.  A workgroup owns 64 hidden units (four m-tiles of 16)
+// and one K slice; its four waves split the slice, so each wave reads only its quarter of the dA slice (the B operand)
+// and every element of the packed R^T tile exactly once, and the four partial sums meet in LDS.
 template <int NT, bool VEC>
 __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, const SplitK sk) {
-  const int H = a.H, B = a.B, K = 4 * a.H, KS = sk.KS, per = sk.per;
+  constexpr int MT = 4;
+  __shared__ __attribute__((aligned(16))) float part[4][MT * NT * 4][64];
+  const int H = a.H, B = a.B, K = 4 * a.H, KS = sk.KS, per = sk.per, perw = sk_per_wave(per);
   const int us = blockIdx.x / KS, ks = blockIdx.x % KS;
   const int u0 = us * 64, b0 = blockIdx.y * 16 * NT;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -103,12 +113,14 @@ __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, c
   // partial sums: [batch tile][K slice][batch row in tile][H]
   float* const pbase = sk.partial + ((size_t)blockIdx.y * KS) * (16 * NT) * H;
 
-  floatx4 acc[NT];
+  floatx4 acc[MT][NT];
 #pragma unroll
-  for (int j = 0; j < NT; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   if (a.dA_next) {
-    const floatx4* ap = reinterpret_cast<const floatx4*>(a.RTp) + ((size_t)((us * KS + ks) * 4 + wave) * per) * 64 + lane;
+    const floatx4* ap = reinterpret_cast<const floatx4*>(a.RTp) + ((size_t)((us * KS + ks) * 4 + wave) * perw) * MT * 64 + lane;
     const float* brow[NT];
     bool bvalid[NT];
 #pragma unroll
@@ -117,29 +129,35 @@ __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, c
       bvalid[j] = bb < B;
       brow[j] = a.dA_next + (long)(bvalid[j] ? bb : 0) * K;
     }
-    constexpr int U = 4;  // k-steps per chunk of the load pipeline
+    // Chunks of U k-steps, double-buffered: the loads of chunk c+1 are in flight while chunk c feeds the MFMAs.
+    constexpr int U = 4;
     const int klim = min(K, (ks + 1) * per * 16);
-    floatx4 av[2][U], bv[2][U][NT];
-    auto load_chunk = [&](int c, floatx4 (&ava)[U], floatx4 (&bva)[U][NT]) {
+    const int mine = max(0, min(perw, per - wave * perw));  // k-steps of this wave inside the slice
+    floatx4 av[2][U][MT], bv[2][U][NT];
+    auto load_chunk = [&](int c, floatx4 (&ava)[U][MT], floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int ksl = c * U + u;
-        const bool in = ksl < per;
-        const int k = (ks * per + ksl) * 16 + 4 * q;
-        ava[u] = in ? ap[(size_t)ksl * 64] : floatx4{0.f, 0.f, 0.f, 0.f};
+        const bool in = ksl < mine;
+        const int k = (ks * per + wave * perw + ksl) * 16 + 4 * q;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) ava[u][mt] = in ? ap[(size_t)(ksl * MT + mt) * 64] : floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < NT; ++j) bva[u][j] = ld4<VEC>(brow[j], k, klim, bvalid[j] && in);
       }
     };
-    auto mma_chunk = [&](const floatx4 (&ava)[U], const floatx4 (&bva)[U][NT]) {
+    auto mma_chunk = [&](const floatx4 (&ava)[U][MT], const floatx4 (&bva)[U][NT]) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ava[u][e], bva[u][j][e], acc[j], 0, 0, 0);
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(ava[u][mt][e], bva[u][j][e], acc[mt][j], 0, 0, 0);
     };
-    const int nch = (per + U - 1) / U;
+    const int nch = (perw + U - 1) / U;
     load_chunk(0, av[0], bv[0]);
     for (int c = 0; c < nch; c += 2) {
       load_chunk(c + 1, av[1], bv[1]);
@@ -152,18 +170,36 @@ __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, c
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  // D layout: register r of lane (q, n) in tile j is (unit u0+16*wave+4q+r, batch 16j+n); H % 64 == 0 here.
-  // Staged as [batch row][64 units]: 256 contiguous bytes per batch row.
-  __shared__ __attribute__((aligned(16))) float stage[16 * NT * 64];
+  // The waves' partial sums meet in LDS.  D layout: register r of lane (q, n) in tile (mt, j) is
+  // (unit u0 + 16*mt + 4q + r, batch 16j + n); H % 64 == 0 here.
 #pragma unroll
-  for (int j = 0; j < NT; ++j) *reinterpret_cast<floatx4*>(stage + (16 * j + n) * 64 + 16 * wave + 4 * q) = acc[j];
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) part[wave][(mt * NT + j) * 4 + r][lane] = acc[mt][j][r];
+  __syncthreads();
+  floatx4 sum[NT];  // wave w adds up m-tile w
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = (wave * NT + j) * 4 + r;
+      sum[j][r] = (part[0][row][lane] + part[1][row][lane]) + (part[2][row][lane] + part[3][row][lane]);
+    }
+  __syncthreads();
+  // Staged as [batch row][64 units]: 256 contiguous bytes per batch row (the staging area reuses `part`).
+  float* const stage = &part[0][0][0];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) *reinterpret_cast<floatx4*>(stage + (16 * j + n) * 64 + 16 * wave + 4 * q) = sum[j];
   __syncthreads();
   for (int idx = threadIdx.x; idx < 16 * NT * 16; idx += 256) {
     const int lb = idx >> 4, c4 = idx & 15;
     xstore4(pbase + ((size_t)ks * (16 * NT) + lb) * H + u0 + 4 * c4, *reinterpret_cast<const floatx4*>(stage + idx * 4));
   }
 
-  if (!last_arrival(sk.counters + (size_t)blockIdx.y * NUS + us, KS)) return;
+  // (the flag lives in the last quarter of `part`, past the staging area)
+  if (!last_arrival(sk.counters + (size_t)blockIdx.y * NUS + us, KS, reinterpret_cast<int*>(&part[3][0][0]))) return;
 
   // ---- fix-up: sum the K slices in order, then the point-wise gate gradients of this unit slice
   for (int idx = threadIdx.x; idx < 16 * 16 * NT; idx += 256) {
@@ -233,8 +269,8 @@ int splitk_bwd_slices(int H, int B) {
 int splitk_bwd_per(int H, int B) { const int nks = (4 * H + 15) / 16, ks = splitk_bwd_slices(H, B); return (nks + ks - 1) / ks; }
 
 size_t splitk_pack_floats(int H) {
-  // upper bound for any slice count (each K slice pads to whole k-steps)
-  return (size_t)((H + 63) / 64) * 4 * (((4 * H + 15) / 16) + 8) * 256;
+  // upper bound for any slice count: each of up to 8 K slices pads to whole k-steps and then to four equal shares for the waves
+  return (size_t)((H + 63) / 64) * 4 * (((4 * H + 15) / 16) + 32) * 256;
 }
 size_t splitk_partial_floats(int H, int B) { return (size_t)8 * batch_tiles_y(B) * 64 * H; }
 size_t splitk_counter_ints(int H, int B) { return (size_t)((H + 63) / 64) * batch_tiles_y(B); }
