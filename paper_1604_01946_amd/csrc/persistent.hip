@@ -2119,9 +2119,9 @@ void release_persistent() {
 // Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward):
 // measured faster than the step kernels up to here (108 against 89 TFLOP/s at B = 512).
 constexpr int kLargeMaxBatch1024 = 512;
-// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice.  From 512 rows on one step's
-// product fills the chip as a plain GEMM and that rung is faster (112 against 107 TFLOP/s).
-constexpr int kLargeMaxBatch2048 = 511;
+// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice, at a constant 5.8 ms per slice
+// and 100 steps, which the step kernels (streaming R once per step for the whole batch) undercut from about 200 rows on.
+constexpr int kLargeMaxBatch2048 = 192;
 
 bool persistent_large(const Dims& d, bool backward) {
   const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");

@@ -124,7 +124,7 @@ inline bool gru_persistent_shape(int cell, const Dims& d) {
   // single gate leaves three quarters of the persistent kernels' tiles empty, so its break-even comes earlier)
   const bool gru = cell == RNN_CELL_GRU;
   if (d.H == 1024) return d.B <= (gru ? 512 : 256);
-  if (d.H == 2048) return d.B <= (gru ? 256 : 96);
+  if (d.H == 2048) return d.B <= (gru ? 192 : 96);
   return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
 }
 // cell selector of the templated persistent kernels

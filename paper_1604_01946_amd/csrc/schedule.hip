@@ -78,11 +78,10 @@ unsigned resolve_auto_path(const Dims& d, bool backward) {
   const int cus = device_cu_count();
   // Section 3.2 observes that at large minibatches the individual optimisations stop paying.  Here: once the plain
   // [B x 4H] x [H] product of one step fills every CU with 128 x 128 tiles, the GEMM kernel (grouped gates, fused
-  // point-wise kernel) beats the step kernel, which is built to stream R past a small batch -- forward by 25-30 %
-  // (H = 4096 with B >= 256, H = 2048 with B >= 512, H = 1024 with B >= 1024); backward by 3-13 % while one step's gate
-  // gradients stay within 16 MB (measured: H = 2048, B = 1024 is 10 % slower on this rung than on the step kernel).
-  if (cus > 0 && (long)((d.B + 127) / 128) * (4L * d.H / 128) >= cus && (!backward || (long)d.B * 4 * d.H <= (4L << 20)))
-    return LSTM_PATH_FUSED;
+  // point-wise kernel) beats the forward step kernel by 15-20 % (H = 4096 with B >= 256, H = 2048 with B >= 512,
+  // H = 1024 with B >= 1024).  Backward the split-K step kernel stays ahead at every size measured (its contraction
+  // is four times longer, and it fuses the point-wise work that the GEMM rung runs as a second kernel).
+  if (!backward && cus > 0 && (long)((d.B + 127) / 128) * (4L * d.H / 128) >= cus) return LSTM_PATH_FUSED;
   // Overlapping layers on streams pays when one step kernel leaves CUs idle (Section 2.4: the
   // gain is largest for small layers); a step that already fills the chip runs layer by layer.
   const long wgs = (long)((d.H + 3) / 4) * ((d.B + 63) / 64);

@@ -100,8 +100,10 @@ __global__ void pack_bwd_kernel(const float* __restrict__ R, floatx4* __restrict
 }
 
 // ------------------------------------------------------------------ forward step
-template <int NT, int MT, bool VEC>
-__global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
+// TWO: short load chunks and at most 256 registers, so that two waves share a SIMD (the host asks for it where the
+// step is bound by the matrix cores and one workgroup per CU would leave them waiting on its own loads).
+template <int NT, int MT, bool VEC, bool TWO = false>
+__global__ __launch_bounds__(256, TWO ? 2 : 1) void step_fwd_kernel(const StepFwdArgs a) {
   __shared__ float part[4][MT * NT * 4][64];
   const int H = a.H, B = a.B;
   const int u0 = blockIdx.x * 4 * MT, b0 = blockIdx.y * 16 * NT;
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(256) void step_fwd_kernel(const StepFwdArgs a) {
     // Chunks of U k-steps, double-buffered: the loads of chunk c+1 are issued before the MFMAs of
     // chunk c, so with one wave per SIMD the weight stream still overlaps the matrix work (the
     // scheduling barriers keep the compiler from re-serialising loads and MFMAs).
-    constexpr int U = 4;
+    constexpr int U = TWO ? 2 : 4;
     const int klim = min(H, (wave + 1) * per * 16);
     floatx4 av[2][U][MT], bv[2][U][NT];
     auto load_chunk = [&](int c, floatx4 (&ava)[U][MT], floatx4 (&bva)[U][NT]) {
@@ -305,6 +307,8 @@ hipError_t launch_fwd_mt(const StepFwdArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((step_fwd_kernel<1, MT, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
   else if (a.B <= 32)
     hipLaunchKernelGGL((step_fwd_kernel<2, MT, VEC>), dim3(gx, 1), dim3(256), 0, s, a);
+  else if (MT == 4 && a.B <= 64)
+    hipLaunchKernelGGL((step_fwd_kernel<4, MT, VEC, MT == 4>), dim3(gx, 1), dim3(256), 0, s, a);
   else
     hipLaunchKernelGGL((step_fwd_kernel<4, MT, VEC>), dim3(gx, (a.B + 63) / 64), dim3(256), 0, s, a);
   return hipGetLastError();

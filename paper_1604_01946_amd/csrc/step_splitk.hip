@@ -100,8 +100,10 @@ __global__ void pack_bwd_sk_kernel(const float* __restrict__ R, floatx4* __restr
 // grid.x = NUS * KS (K slice fastest), grid.y = batch tiles.  A workgroup owns 64 hidden units (four m-tiles of 16)
 // and one K slice; its four waves split the slice, so each wave reads only its quarter of the dA slice (the B operand)
 // and every element of the packed R^T tile exactly once, and the four partial sums meet in LDS.
-template <int NT, bool VEC>
-__global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, const SplitK sk) {
+// TWO: short load chunks and at most 256 registers, so that two waves share a SIMD (64 batch rows in one tile: the
+// step is bound by the matrix cores, and one wave per SIMD leaves them waiting on its own loads).
+template <int NT, bool VEC, bool TWO = false>
+__global__ __launch_bounds__(256, TWO ? 2 : 1) void step_bwd_sk_kernel(const StepBwdArgs a, const SplitK sk) {
   constexpr int MT = 4;
   __shared__ __attribute__((aligned(16))) float part[4][MT * NT * 4][64];
   const int H = a.H, B = a.B, K = 4 * a.H, KS = sk.KS, per = sk.per, perw = sk_per_wave(per);
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(256) void step_bwd_sk_kernel(const StepBwdArgs a, c
       brow[j] = a.dA_next + (long)(bvalid[j] ? bb : 0) * K;
     }
     // Chunks of U k-steps, double-buffered: the loads of chunk c+1 are in flight while chunk c feeds the MFMAs.
-    constexpr int U = 4;
+    constexpr int U = TWO ? 2 : 4;
     const int klim = min(K, (ks + 1) * per * 16);
     const int mine = max(0, min(perw, per - wave * perw));  // k-steps of this wave inside the slice
     floatx4 av[2][U][MT], bv[2][U][NT];
@@ -290,6 +292,11 @@ hipError_t launch_step_bwd_sk(const StepBwdArgs& a, float* partial, int* counter
   if (nt == NT_) {                                                                                     \
     if (vec) hipLaunchKernelGGL((step_bwd_sk_kernel<NT_, true>), grid, dim3(256), 0, s, a, sk);        \
     else hipLaunchKernelGGL((step_bwd_sk_kernel<NT_, false>), grid, dim3(256), 0, s, a, sk);           \
+  }
+  if (nt == 4 && grid.y == 1) {
+    if (vec) hipLaunchKernelGGL((step_bwd_sk_kernel<4, true, true>), grid, dim3(256), 0, s, a, sk);
+    else hipLaunchKernelGGL((step_bwd_sk_kernel<4, false, true>), grid, dim3(256), 0, s, a, sk);
+    return hipGetLastError();
   }
   LSTM_SK_CASE(1) LSTM_SK_CASE(2) LSTM_SK_CASE(4)
 #undef LSTM_SK_CASE

@@ -291,13 +291,13 @@ def test_null_optionals_and_inference():
         assert torch.equal(r.y, y_train)
 
 
-def test_large_minibatch_takes_the_gemm_rung():
+def test_large_minibatch_takes_the_gemm_rung_forward():
     """Once one step's [B x 4H] x [H] product fills every CU with 128 x 128 tiles the automatic forward path is the
-    grouped-GEMM + fused point-wise rung, in both directions."""
+    grouped-GEMM + fused point-wise rung, the backward path stays the step kernel; the two must work together."""
     _, binding, _ = _mods()
     cfg = Config("bigB", L=2, T=2, B=512, I=64, H=2048, state_std=0.3, dstate_std=0.3)
     assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_FUSED
-    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_FUSED
+    assert binding.lstm_auto_path(*cfg.dims, 1) in (binding.LSTM_PATH_STEP, binding.LSTM_PATH_WAVEFRONT)
     run_case(cfg, 13, 0)
 
 
