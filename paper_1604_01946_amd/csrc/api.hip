@@ -5,6 +5,7 @@
 #include "schedule.h"
 #include <algorithm>
 
+#include <stdlib.h>
 #include <string.h>
 #include <stdio.h>
 #include <string>
@@ -103,16 +104,160 @@ WsLayout ws_layout(const Dims& d, bool wide_rows) {
 
 }  // namespace lstm
 
+namespace lstm {
+
+int padded_hidden(const Dims& d) {
+  const char* e = getenv("LSTM_NO_PAD");
+  if (e && *e == '1') return d.H;
+  if (d.H <= 64 || d.H >= 512 || d.B > 512) return d.H;  // B: the persistent kernels take up to 512 rows
+  return d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);
+}
+
+}  // namespace lstm
+
+namespace {
+
+#define CK(expr, what)                                             \
+  do {                                                             \
+    if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
+  } while (0)
+
+// dst [outer][rd][cd] <- src [outer][rs][cs]: the common corner is copied, the rest of dst is zero.
+__global__ void resize_kernel(float* __restrict__ dst, const float* __restrict__ src, long outer, int rd, int cd, int rs,
+                              int cs) {
+  const long n = outer * rd * cd;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cd);
+    const long t = i / cd;
+    const int r = (int)(t % rd);
+    const long o = t / rd;
+    dst[i] = (r < rs && c < cs) ? src[(o * rs + r) * cs + c] : 0.f;
+  }
+}
+
+hipError_t resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s) {
+  const long n = outer * rd * cd;
+  if (n <= 0) return hipSuccess;
+  const unsigned blocks = (unsigned)std::min<long>((n + 255) / 256, 4096);
+  hipLaunchKernelGGL(resize_kernel, dim3(blocks), dim3(256), 0, s, dst, src, outer, rd, cd, rs, cs);
+  return hipGetLastError();
+}
+
+// Workspace of a padded call: the padded copies of every operand with a hidden axis, then the workspace of the
+// padded problem.  Offsets in bytes.
+struct PadLayout {
+  size_t W, R, b, h0, c0, y, hT, cT, dy, dhT, dcT, dh0, dc0, dW, dR, db, inner, total;
+  WsLayout w;  // of the padded problem, relative to `inner`
+};
+
+PadLayout pad_layout(const Dims& d, const Dims& p) {
+  PadLayout q;
+  size_t off = 0;
+  auto take = [&](size_t floats) {
+    size_t o = off;
+    off = align_up(off + floats * sizeof(float), 256);
+    return o;
+  };
+  const size_t G = 4 * (size_t)p.H, nW = G * d.I + (size_t)(d.L - 1) * G * p.H, nR = (size_t)d.L * G * p.H;
+  const size_t nS = (size_t)d.L * d.B * p.H, nY = (size_t)d.T * d.B * p.H;
+  q.W = take(nW); q.R = take(nR); q.b = take(d.L * G);
+  q.h0 = take(nS); q.c0 = take(nS); q.y = take(nY); q.hT = take(nS); q.cT = take(nS);
+  q.dy = take(nY); q.dhT = take(nS); q.dcT = take(nS); q.dh0 = take(nS); q.dc0 = take(nS);
+  q.dW = take(nW); q.dR = take(nR); q.db = take(d.L * G);
+  q.inner = off;
+  q.w = ws_layout(p);
+  q.total = off + q.w.total;
+  return q;
+}
+
+// Recurrent and input matrices and the bias with every gate block grown from H to Hp rows (and, where the columns
+// run over hidden units, from H to Hp columns).
+int pad_parameters(const Dims& d, int Hp, const float* W, const float* R, const float* b, float* Wp, float* Rp, float* bp,
+                   hipStream_t s) {
+  const size_t G = 4 * (size_t)d.H, Gp = 4 * (size_t)Hp;
+  CK(resize(Wp, W, 4, Hp, d.I, d.H, d.I, s), "pad W (layer 0)");
+  CK(resize(Wp + Gp * d.I, W + G * d.I, 4L * (d.L - 1), Hp, Hp, d.H, d.H, s), "pad W");
+  CK(resize(Rp, R, 4L * d.L, Hp, Hp, d.H, d.H, s), "pad R");
+  if (b) CK(resize(bp, b, 4L * d.L, 1, Hp, 1, d.H, s), "pad b");
+  return LSTM_OK;
+}
+
+int forward_padded(const Dims& d, const Dims& p, const float* x, const float* h0, const float* c0, const float* W,
+                   const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, char* ws,
+                   hipStream_t s, unsigned flags) {
+  const PadLayout q = pad_layout(d, p);
+  auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  const long LB = (long)d.L * d.B, TB = (long)d.T * d.B;
+  {
+    ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+    const int st = pad_parameters(d, p.H, W, R, b, f(q.W), f(q.R), f(q.b), s);
+    if (st != LSTM_OK) return st;
+    if (h0) CK(resize(f(q.h0), h0, 1, (int)LB, p.H, (int)LB, d.H, s), "pad h0");
+    if (c0) CK(resize(f(q.c0), c0, 1, (int)LB, p.H, (int)LB, d.H, s), "pad c0");
+  }
+  char* inner = ws + q.inner;
+  FwdArgs a{p, x, h0 ? f(q.h0) : nullptr, c0 ? f(q.c0) : nullptr, f(q.W), f(q.R), f(q.b), f(q.y), hT ? f(q.hT) : nullptr,
+            cT ? f(q.cT) : nullptr, reserve ? (float*)reserve : (float*)(inner + q.w.resv), inner, q.w, s};
+  a.inference = reserve == nullptr;
+  unsigned path = flags & LSTM_PATH_MASK;
+  if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, false);
+  const int st = run_forward(a, path);
+  if (st != LSTM_OK) return st;
+  ProfScope ps(LSTM_PHASE_FWD_PACK, s);
+  CK(resize(y, f(q.y), 1, (int)TB, d.H, (int)TB, p.H, s), "unpad y");
+  if (hT) CK(resize(hT, f(q.hT), 1, (int)LB, d.H, (int)LB, p.H, s), "unpad hT");
+  if (cT) CK(resize(cT, f(q.cT), 1, (int)LB, d.H, (int)LB, p.H, s), "unpad cT");
+  return LSTM_OK;
+}
+
+int backward_padded(const Dims& d, const Dims& p, const float* x, const float* h0, const float* c0, const float* W,
+                    const float* R, const void* reserve, const float* dy, const float* dhT, const float* dcT, float* dx,
+                    float* dh0, float* dc0, float* dW, float* dR, float* db, char* ws, hipStream_t s, unsigned flags) {
+  const PadLayout q = pad_layout(d, p);
+  auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  const long LB = (long)d.L * d.B, TB = (long)d.T * d.B;
+  const size_t G = 4 * (size_t)d.H, Gp = 4 * (size_t)p.H;
+  {
+    ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+    const int st = pad_parameters(d, p.H, W, R, nullptr, f(q.W), f(q.R), nullptr, s);
+    if (st != LSTM_OK) return st;
+    if (h0) CK(resize(f(q.h0), h0, 1, (int)LB, p.H, (int)LB, d.H, s), "pad h0");
+    if (c0) CK(resize(f(q.c0), c0, 1, (int)LB, p.H, (int)LB, d.H, s), "pad c0");
+    CK(resize(f(q.dy), dy, 1, (int)TB, p.H, (int)TB, d.H, s), "pad dy");
+    if (dhT) CK(resize(f(q.dhT), dhT, 1, (int)LB, p.H, (int)LB, d.H, s), "pad dhT");
+    if (dcT) CK(resize(f(q.dcT), dcT, 1, (int)LB, p.H, (int)LB, d.H, s), "pad dcT");
+  }
+  char* inner = ws + q.inner;
+  BwdArgs a{p, x, h0 ? f(q.h0) : nullptr, c0 ? f(q.c0) : nullptr, f(q.W), f(q.R), (const float*)reserve, f(q.dy),
+            dhT ? f(q.dhT) : nullptr, dcT ? f(q.dcT) : nullptr, dx, dh0 ? f(q.dh0) : nullptr, dc0 ? f(q.dc0) : nullptr,
+            f(q.dW), f(q.dR), f(q.db), inner, q.w, s};
+  unsigned path = flags & LSTM_PATH_MASK;
+  if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, true);
+  const int st = run_backward(a, path);
+  if (st != LSTM_OK) return st;
+  ProfScope ps(LSTM_PHASE_BWD_PACK, s);
+  if (dh0) CK(resize(dh0, f(q.dh0), 1, (int)LB, d.H, (int)LB, p.H, s), "unpad dh0");
+  if (dc0) CK(resize(dc0, f(q.dc0), 1, (int)LB, d.H, (int)LB, p.H, s), "unpad dc0");
+  CK(resize(dW, f(q.dW), 4, d.H, d.I, p.H, d.I, s), "unpad dW (layer 0)");
+  CK(resize(dW + G * d.I, f(q.dW) + Gp * d.I, 4L * (d.L - 1), d.H, d.H, p.H, p.H, s), "unpad dW");
+  CK(resize(dR, f(q.dR), 4L * d.L, d.H, d.H, p.H, p.H, s), "unpad dR");
+  CK(resize(db, f(q.db), 4L * d.L, 1, d.H, 1, p.H, s), "unpad db");
+  return LSTM_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t lstm_reserve_bytes(int L, int T, int B, int I, int H) {
   if (!dims_ok(L, T, B, I, H)) return 0;
-  return reserve_bytes(Dims{L, T, B, I, H});
+  return reserve_bytes(padded_dims(Dims{L, T, B, I, H}));
 }
 
 size_t lstm_workspace_bytes(int L, int T, int B, int I, int H) {
   if (!dims_ok(L, T, B, I, H)) return 0;
-  return ws_layout(Dims{L, T, B, I, H}).total;
+  const Dims d{L, T, B, I, H}, p = padded_dims(d);
+  return p.H == d.H ? ws_layout(d).total : pad_layout(d, p).total;
 }
 
 const char* lstm_status_string(int status) {
@@ -198,7 +343,11 @@ int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float*
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
-  const Dims d{L, T, B, I, H};
+  const Dims d{L, T, B, I, H}, p = padded_dims(d);
+  if (p.H != d.H) {
+    if (workspace_bytes < pad_layout(d, p).total) return LSTM_BUFFER_TOO_SMALL;
+    return forward_padded(d, p, x, h0, c0, W, R, b, y, hT, cT, reserve, (char*)workspace, (hipStream_t)stream, flags);
+  }
   const WsLayout w = ws_layout(d);
   if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
 
@@ -221,7 +370,12 @@ int lstm_backward(int L, int T, int B, int I, int H, const float* x, const float
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
-  const Dims d{L, T, B, I, H};
+  const Dims d{L, T, B, I, H}, p = padded_dims(d);
+  if (p.H != d.H) {
+    if (workspace_bytes < pad_layout(d, p).total) return LSTM_BUFFER_TOO_SMALL;
+    return backward_padded(d, p, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db, (char*)workspace,
+                           (hipStream_t)stream, flags);
+  }
   const WsLayout w = ws_layout(d);
   if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
 

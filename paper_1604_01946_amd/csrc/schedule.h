@@ -46,6 +46,13 @@ struct BwdArgs {
   hipStream_t stream;
 };
 
+// Hidden size the kernels run a shape at.  Hidden units with zero weights, bias and initial state stay at h = c = 0
+// for every step and receive zero gradients, so a network padded that way computes exactly the given one; the
+// persistent kernels exist for H = 128, 256 and 512, and any other hidden size between 64 and 512 runs several times
+// faster padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
+int padded_hidden(const Dims& d);
+inline Dims padded_dims(const Dims& d) { return Dims{d.L, d.T, d.B, d.I, padded_hidden(d)}; }
+
 size_t reserve_bytes(const Dims& d);
 WsLayout ws_layout(const Dims& d, bool wide_rows = false);
 unsigned resolve_auto_path(const Dims& d, bool backward);

@@ -51,7 +51,8 @@ bool path_takes_shape(const Dims& d, bool backward, unsigned path) {
 }
 
 int set_path_override(const Dims& d, bool backward, unsigned path) {
-  if (path != LSTM_PATH_AUTO && !path_takes_shape(d, backward, path)) return path > LSTM_PATH_PERSISTENT ? LSTM_INVALID_ARG : LSTM_UNSUPPORTED;
+  // the kernels see the padded hidden size (padded_hidden), so that is the shape a path has to take
+  if (path != LSTM_PATH_AUTO && !path_takes_shape(padded_dims(d), backward, path)) return path > LSTM_PATH_PERSISTENT ? LSTM_INVALID_ARG : LSTM_UNSUPPORTED;
   std::lock_guard<std::mutex> lk(g_path_mu);
   for (size_t i = 0; i < g_path_table.size(); ++i)
     if (same_shape(g_path_table[i].d, d) && g_path_table[i].backward == backward) {
@@ -68,12 +69,13 @@ void clear_path_overrides() {
   g_path_table.clear();
 }
 
-unsigned resolve_auto_path(const Dims& d, bool backward) {
+unsigned resolve_auto_path(const Dims& user, bool backward) {
   {
     std::lock_guard<std::mutex> lk(g_path_mu);
     for (const PathOverride& o : g_path_table)
-      if (same_shape(o.d, d) && o.backward == backward) return o.path;
+      if (same_shape(o.d, user) && o.backward == backward) return o.path;
   }
+  const Dims d = padded_dims(user);  // what the kernels will run
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
   const int cus = device_cu_count();
   // Section 3.2 observes that at large minibatches the individual optimisations stop paying.  Here: once the plain

@@ -52,6 +52,23 @@ def test_size_queries():
     assert B.lstm_workspace_bytes(4, 100, 64, 512, 512) % 256 == 0
 
 
+def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
+    # 64 < H < 512 runs at the next of 128 / 256 / 512: the reserve holds the padded network
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 100) == 2 * 5 * 3 * 6 * 128 * 4
+    assert B.lstm_reserve_bytes(2, 5, 3, 384, 384) == 2 * 5 * 3 * 6 * 512 * 4
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 64) == 2 * 5 * 3 * 6 * 64 * 4        # small sizes stay as they are
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 640) == 2 * 5 * 3 * 6 * 640 * 4      # and so do sizes above 512
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 100 * 4  # and batches the persistent kernels do not take
+    padded = B.lstm_workspace_bytes(2, 5, 3, 8, 100)
+    assert padded > B.lstm_workspace_bytes(2, 5, 3, 8, 128) and padded % 256 == 0
+    a = 4096
+    ptrs = [a, None, None, a, a, a, a, None, None, None, a]
+    assert B.lstm_forward(2, 5, 3, 8, 100, *ptrs, padded - 1, stream=0, flags=0) == B.LSTM_BUFFER_TOO_SMALL
+    monkeypatch.setenv("LSTM_NO_PAD", "1")
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 100) == 2 * 5 * 3 * 6 * 100 * 4
+    assert B.lstm_workspace_bytes(2, 5, 3, 8, 100) < padded
+
+
 def test_status_strings():
     for s in range(0, 6):
         assert B.lstm_status_string(s)

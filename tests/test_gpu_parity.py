@@ -270,6 +270,39 @@ def test_odd_shapes(cfg, flags):
     run_case(cfg, 3, flags)
 
 
+@pytest.mark.parametrize("cfg", [ODD[2], ODD[4]], ids=["odd3", "odd5"])
+@pytest.mark.parametrize("flags", [0, 4, 5])
+def test_odd_shapes_without_padding(cfg, flags, monkeypatch):
+    """Hidden sizes between 64 and 512 run padded to a size of the persistent kernels unless LSTM_NO_PAD=1: the
+    per-step kernels keep their ragged-shape coverage this way."""
+    monkeypatch.setenv("LSTM_NO_PAD", "1")
+    run_case(cfg, 3, flags)
+
+
+# ------------------------------------------------------------------ hidden sizes padded to the persistent kernels'
+PADDED = [
+    Config("h384", L=2, T=5, B=20, I=384, H=384, state_std=0.3, dstate_std=0.3),      # I == H before padding, not after
+    Config("h200", L=3, T=4, B=64, I=100, H=200, state_std=0.3, dstate_std=0.3),
+    Config("h72", L=1, T=6, B=33, I=72, H=72, state_std=0.3, dstate_std=0.3),
+    Config("h300b130", L=2, T=3, B=130, I=40, H=300, state_std=0.3, dstate_std=0.3),  # three batch slices
+    Config("h511", L=5, T=3, B=7, I=511, H=511, state_std=0.3, dstate_std=0.3),       # odd size, two groups of layers
+]
+
+
+@pytest.mark.parametrize("cfg", PADDED, ids=[c.name for c in PADDED])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_padded_hidden_sizes(cfg, with_states):
+    torch, binding, _ = _mods()
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_PERSISTENT
+    r, ref = run_case(cfg, 17, 0, with_states=with_states, with_dstates=with_states)
+    y_train = r.y.clone()
+    r.y.fill_(float("nan"))
+    binding.check(r.forward(flags=0, inference=True))
+    torch.cuda.synchronize()
+    assert torch.equal(r.y, y_train)
+
+
 # ------------------------------------------------------------------ optional pointers, inference
 def test_null_optionals_and_inference():
     torch, binding, runner = _mods()
