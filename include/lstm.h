@@ -67,7 +67,19 @@ extern "C" {
 #define LSTM_PATH_MASK        0xFu
 
 /* Bytes of the opaque `reserve` buffer that lstm_forward fills for lstm_backward.
- * Returns 0 if any dimension is non-positive. */
+ * Returns 0 if any dimension is non-positive.
+ *
+ * Hidden sizes below 512 other than 128 and 256 (with B <= 512, and more than a few steps of one
+ * layer) are computed at the next of 128, 256, 512: the library copies W, R, b, the initial states
+ * and, backward, the upstream gradients into zero-padded buffers inside the workspace, runs the
+ * padded network on the chosen path and copies the results back.  The result is that of the
+ * given network: a hidden unit whose weights, bias and initial state are zero stays at h = c = 0
+ * at every step and receives zero gradients.  The persistent kernels (Section 4) exist for those
+ * three sizes, and the padded run is faster than the per-step paths at the given size (three to
+ * five times with four layers).  Reserve and workspace sizes are those of the padded network, and
+ * the copies are part of the weight re-layout that Section 2.3 redoes every pass.  LSTM_NO_PAD=1 in the
+ * environment (read at every call: set it the same for size queries, forward and backward) runs
+ * every shape as given. */
 size_t lstm_reserve_bytes(int L, int T, int B, int I, int H);
 
 /* Bytes of scratch that lstm_forward / lstm_backward need (the maximum over both and

@@ -109,7 +109,8 @@ namespace lstm {
 int padded_hidden(const Dims& d) {
   const char* e = getenv("LSTM_NO_PAD");
   if (e && *e == '1') return d.H;
-  if (d.H <= 64 || d.H >= 512 || d.B > 512) return d.H;  // B: the persistent kernels take up to 512 rows
+  if (d.H >= 512 || d.B > 512) return d.H;  // B: the persistent kernels take up to 512 rows
+  if (d.L == 1 && d.T < 32) return d.H;     // a few steps of one layer: the copies would cost more than they save
   return d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);
 }
 

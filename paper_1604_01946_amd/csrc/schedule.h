@@ -48,8 +48,8 @@ struct BwdArgs {
 
 // Hidden size the kernels run a shape at.  Hidden units with zero weights, bias and initial state stay at h = c = 0
 // for every step and receive zero gradients, so a network padded that way computes exactly the given one; the
-// persistent kernels exist for H = 128, 256 and 512, and any other hidden size between 64 and 512 runs several times
-// faster padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
+// persistent kernels exist for H = 128, 256 and 512, and any other hidden size below 512 runs faster (several times,
+// with more than one layer) padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
 int padded_hidden(const Dims& d);
 inline Dims padded_dims(const Dims& d) { return Dims{d.L, d.T, d.B, d.I, padded_hidden(d)}; }
 

@@ -53,10 +53,13 @@ def test_size_queries():
 
 
 def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
-    # 64 < H < 512 runs at the next of 128 / 256 / 512: the reserve holds the padded network
+    # H < 512 runs at the next of 128 / 256 / 512: the reserve holds the padded network
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 100) == 2 * 5 * 3 * 6 * 128 * 4
     assert B.lstm_reserve_bytes(2, 5, 3, 384, 384) == 2 * 5 * 3 * 6 * 512 * 4
-    assert B.lstm_reserve_bytes(2, 5, 3, 8, 64) == 2 * 5 * 3 * 6 * 64 * 4        # small sizes stay as they are
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 1) == 2 * 5 * 3 * 6 * 128 * 4
+    assert B.lstm_reserve_bytes(1, 40, 3, 8, 100) == 40 * 3 * 6 * 128 * 4
+    assert B.lstm_reserve_bytes(1, 8, 3, 8, 100) == 8 * 3 * 6 * 100 * 4          # a few steps of one layer: not worth the copies
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 256) == 2 * 5 * 3 * 6 * 256 * 4      # native sizes stay as they are
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 640) == 2 * 5 * 3 * 6 * 640 * 4      # and so do sizes above 512
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 100 * 4  # and batches the persistent kernels do not take
     padded = B.lstm_workspace_bytes(2, 5, 3, 8, 100)
@@ -124,16 +127,16 @@ def test_auto_path_is_a_valid_path():
 
 
 def test_set_path_overrides_and_validates():
-    dims = (2, 8, 4, 32, 32)
+    dims = (2, 8, 4, 32, 640)
     auto = B.lstm_auto_path(*dims, 0)
-    assert B.lstm_set_path(0, 8, 4, 32, 32, 0, B.LSTM_PATH_STEP) == B.LSTM_INVALID_ARG
+    assert B.lstm_set_path(0, 8, 4, 32, 640, 0, B.LSTM_PATH_STEP) == B.LSTM_INVALID_ARG
     assert B.lstm_set_path(*dims, 0, 99) == B.LSTM_INVALID_ARG
-    # H = 32 is not a shape of the persistent kernels on any device
+    # H = 640 is neither a size of the persistent kernels nor padded to one, on any device
     assert B.lstm_set_path(*dims, 0, B.LSTM_PATH_PERSISTENT) == B.LSTM_UNSUPPORTED
     other = B.LSTM_PATH_STEP if auto != B.LSTM_PATH_STEP else B.LSTM_PATH_WAVEFRONT
     assert B.lstm_set_path(*dims, 0, other) == B.LSTM_OK
     assert B.lstm_auto_path(*dims, 0) == other
-    assert B.lstm_auto_path(*dims, 1) == B.lstm_auto_path(2, 8, 4, 32, 32, 1)  # the other direction is untouched
+    assert B.lstm_auto_path(*dims, 1) == B.lstm_auto_path(2, 8, 4, 32, 640, 1)  # the other direction is untouched
     assert B.lstm_set_path(*dims, 0, B.LSTM_PATH_AUTO) == B.LSTM_OK
     assert B.lstm_auto_path(*dims, 0) == auto
     assert B.lstm_set_path(*dims, 1, other) == B.LSTM_OK
