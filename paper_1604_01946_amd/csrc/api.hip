@@ -104,7 +104,30 @@ WsLayout ws_layout(const Dims& d, bool wide_rows) {
 
 }  // namespace lstm
 
+namespace {
+// dst [outer][rd][cd] <- src [outer][rs][cs]: the common corner is copied, the rest of dst is zero.
+__global__ void resize_kernel(float* __restrict__ dst, const float* __restrict__ src, long outer, int rd, int cd, int rs,
+                              int cs) {
+  const long n = outer * rd * cd;
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cd);
+    const long t = i / cd;
+    const int r = (int)(t % rd);
+    const long o = t / rd;
+    dst[i] = (r < rs && c < cs) ? src[(o * rs + r) * cs + c] : 0.f;
+  }
+}
+}  // namespace
+
 namespace lstm {
+
+hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s) {
+  const long n = outer * rd * cd;
+  if (n <= 0) return hipSuccess;
+  const unsigned blocks = (unsigned)std::min<long>((n + 255) / 256, 4096);
+  hipLaunchKernelGGL(resize_kernel, dim3(blocks), dim3(256), 0, s, dst, src, outer, rd, cd, rs, cs);
+  return hipGetLastError();
+}
 
 int padded_hidden(const Dims& d) {
   const char* e = getenv("LSTM_NO_PAD");
@@ -123,25 +146,8 @@ namespace {
     if (record((expr), what) != hipSuccess) return LSTM_HIP_ERROR; \
   } while (0)
 
-// dst [outer][rd][cd] <- src [outer][rs][cs]: the common corner is copied, the rest of dst is zero.
-__global__ void resize_kernel(float* __restrict__ dst, const float* __restrict__ src, long outer, int rd, int cd, int rs,
-                              int cs) {
-  const long n = outer * rd * cd;
-  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-    const int c = (int)(i % cd);
-    const long t = i / cd;
-    const int r = (int)(t % rd);
-    const long o = t / rd;
-    dst[i] = (r < rs && c < cs) ? src[(o * rs + r) * cs + c] : 0.f;
-  }
-}
-
-hipError_t resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s) {
-  const long n = outer * rd * cd;
-  if (n <= 0) return hipSuccess;
-  const unsigned blocks = (unsigned)std::min<long>((n + 255) / 256, 4096);
-  hipLaunchKernelGGL(resize_kernel, dim3(blocks), dim3(256), 0, s, dst, src, outer, rd, cd, rs, cs);
-  return hipGetLastError();
+inline hipError_t resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s) {
+  return launch_resize(dst, src, outer, rd, cd, rs, cs, s);
 }
 
 // Workspace of a padded call: the padded copies of every operand with a hidden axis, then the workspace of the

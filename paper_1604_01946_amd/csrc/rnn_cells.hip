@@ -314,6 +314,88 @@ int backward_impl(int cell, const Dims& d, const float* x, const float* h0, cons
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Hidden sizes without persistent kernels run zero-padded to the next size that has them, as for the LSTM
+// (padded_hidden): a padded unit has pre-activations 0 and initial state 0, so the GRU keeps it at
+// h = (1 - 1/2) tanh(0) + 1/2 * 0 = 0 and the single gate at act(0) = 0, nothing reads it, and its gradients are 0.
+inline Dims rnn_padded_dims(int cell, const Dims& d) {
+  const char* e = getenv("RNN_NO_PERSISTENT");
+  if (e && *e == '1') return d;
+  return padded_dims(d);
+}
+
+struct RnnPad {
+  size_t W, R, b, h0, y, hT, dy, dhT, dh0, dW, dR, db, inner, total;  // byte offsets
+};
+RnnPad rnn_pad_layout(int cell, const Dims& d, const Dims& p) {
+  RnnPad q;
+  size_t off = 0;
+  auto take = [&](size_t floats) {
+    size_t o = off;
+    off = (off + floats * sizeof(float) + 255) / 256 * 256;
+    return o;
+  };
+  const size_t G = (size_t)gates_of(cell) * p.H, nW = G * d.I + (size_t)(d.L - 1) * G * p.H, nR = (size_t)d.L * G * p.H;
+  const size_t nS = (size_t)d.L * d.B * p.H, nY = (size_t)d.T * d.B * p.H;
+  q.W = take(nW); q.R = take(nR); q.b = take(d.L * G);
+  q.h0 = take(nS); q.y = take(nY); q.hT = take(nS);
+  q.dy = take(nY); q.dhT = take(nS); q.dh0 = take(nS);
+  q.dW = take(nW); q.dR = take(nR); q.db = take(d.L * G);
+  q.inner = off;
+  q.total = off + ws_total(cell, p);
+  return q;
+}
+
+int pad_rnn_parameters(int cell, const Dims& d, int Hp, const float* W, const float* R, const float* b, float* Wp, float* Rp,
+                       float* bp, hipStream_t s) {
+  const long ng = gates_of(cell);
+  const size_t G = (size_t)ng * d.H, Gp = (size_t)ng * Hp;
+  CK(launch_resize(Wp, W, ng, Hp, d.I, d.H, d.I, s), "pad W (layer 0)");
+  CK(launch_resize(Wp + Gp * d.I, W + G * d.I, ng * (d.L - 1), Hp, Hp, d.H, d.H, s), "pad W");
+  CK(launch_resize(Rp, R, ng * d.L, Hp, Hp, d.H, d.H, s), "pad R");
+  if (b) CK(launch_resize(bp, b, ng * d.L, 1, Hp, 1, d.H, s), "pad b");
+  return LSTM_OK;
+}
+
+int forward_padded(int cell, const Dims& d, const Dims& p, const float* x, const float* h0, const float* W, const float* R,
+                   const float* b, float* y, float* hT, float* reserve, char* ws, hipStream_t s) {
+  const RnnPad q = rnn_pad_layout(cell, d, p);
+  auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  const int LB = d.L * d.B, TB = d.T * d.B;
+  int st = pad_rnn_parameters(cell, d, p.H, W, R, b, f(q.W), f(q.R), f(q.b), s);
+  if (st != LSTM_OK) return st;
+  if (h0) CK(launch_resize(f(q.h0), h0, 1, LB, p.H, LB, d.H, s), "pad h0");
+  st = forward_impl(cell, p, x, h0 ? f(q.h0) : nullptr, f(q.W), f(q.R), f(q.b), f(q.y), hT ? f(q.hT) : nullptr, reserve,
+                    ws + q.inner, s);
+  if (st != LSTM_OK) return st;
+  CK(launch_resize(y, f(q.y), 1, TB, d.H, TB, p.H, s), "unpad y");
+  if (hT) CK(launch_resize(hT, f(q.hT), 1, LB, d.H, LB, p.H, s), "unpad hT");
+  return LSTM_OK;
+}
+
+int backward_padded(int cell, const Dims& d, const Dims& p, const float* x, const float* h0, const float* W, const float* R,
+                    const float* reserve, const float* dy, const float* dhT, float* dx, float* dh0, float* dW, float* dR,
+                    float* db, char* ws, hipStream_t s) {
+  const RnnPad q = rnn_pad_layout(cell, d, p);
+  auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  const int LB = d.L * d.B, TB = d.T * d.B;
+  const long ng = gates_of(cell);
+  const size_t G = (size_t)ng * d.H, Gp = (size_t)ng * p.H;
+  int st = pad_rnn_parameters(cell, d, p.H, W, R, nullptr, f(q.W), f(q.R), nullptr, s);
+  if (st != LSTM_OK) return st;
+  if (h0) CK(launch_resize(f(q.h0), h0, 1, LB, p.H, LB, d.H, s), "pad h0");
+  CK(launch_resize(f(q.dy), dy, 1, TB, p.H, TB, d.H, s), "pad dy");
+  if (dhT) CK(launch_resize(f(q.dhT), dhT, 1, LB, p.H, LB, d.H, s), "pad dhT");
+  st = backward_impl(cell, p, x, h0 ? f(q.h0) : nullptr, f(q.W), f(q.R), reserve, f(q.dy), dhT ? f(q.dhT) : nullptr, dx,
+                     dh0 ? f(q.dh0) : nullptr, f(q.dW), f(q.dR), f(q.db), ws + q.inner, s);
+  if (st != LSTM_OK) return st;
+  if (dh0) CK(launch_resize(dh0, f(q.dh0), 1, LB, d.H, LB, p.H, s), "unpad dh0");
+  CK(launch_resize(dW, f(q.dW), ng, d.H, d.I, p.H, d.I, s), "unpad dW (layer 0)");
+  CK(launch_resize(dW + G * d.I, f(q.dW) + Gp * d.I, ng * (d.L - 1), d.H, d.H, p.H, p.H, s), "unpad dW");
+  CK(launch_resize(dR, f(q.dR), ng * d.L, d.H, d.H, p.H, p.H, s), "unpad dR");
+  CK(launch_resize(db, f(q.db), ng * d.L, 1, d.H, 1, p.H, s), "unpad db");
+  return LSTM_OK;
+}
+
 }  // namespace
 }  // namespace lstm
 
@@ -323,12 +405,13 @@ extern "C" {
 
 size_t rnn_reserve_bytes(int cell, int L, int T, int B, int I, int H) {
   if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
-  return (size_t)L * res_layer_floats(cell, Dims{L, T, B, I, H}) * sizeof(float);
+  return (size_t)L * res_layer_floats(cell, rnn_padded_dims(cell, Dims{L, T, B, I, H})) * sizeof(float);
 }
 
 size_t rnn_workspace_bytes(int cell, int L, int T, int B, int I, int H) {
   if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
-  return ws_total(cell, Dims{L, T, B, I, H});
+  const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
+  return p.H == d.H ? ws_total(cell, d) : rnn_pad_layout(cell, d, p).total;
 }
 
 int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, const float* h0, const float* W,
@@ -339,7 +422,12 @@ int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, con
   const void* ptrs[] = {x, h0, W, R, b, y, hT, reserve, workspace};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
-  const Dims d{L, T, B, I, H};
+  const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
+  if (p.H != d.H) {
+    if (workspace_bytes < rnn_pad_layout(cell, d, p).total) return LSTM_BUFFER_TOO_SMALL;
+    return forward_padded(cell, d, p, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve),
+                          reinterpret_cast<char*>(workspace), (hipStream_t)stream);
+  }
   if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return forward_impl(cell, d, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve), reinterpret_cast<char*>(workspace),
                       (hipStream_t)stream);
@@ -353,7 +441,12 @@ int rnn_backward(int cell, int L, int T, int B, int I, int H, const float* x, co
   const void* ptrs[] = {x, h0, W, R, reserve, dy, dhT, dx, dh0, dW, dR, db, workspace};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
-  const Dims d{L, T, B, I, H};
+  const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
+  if (p.H != d.H) {
+    if (workspace_bytes < rnn_pad_layout(cell, d, p).total) return LSTM_BUFFER_TOO_SMALL;
+    return backward_padded(cell, d, p, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
+                           reinterpret_cast<char*>(workspace), (hipStream_t)stream);
+  }
   if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return backward_impl(cell, d, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
                        reinterpret_cast<char*>(workspace), (hipStream_t)stream);

@@ -52,6 +52,8 @@ struct BwdArgs {
 // with more than one layer) padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
 int padded_hidden(const Dims& d);
 inline Dims padded_dims(const Dims& d) { return Dims{d.L, d.T, d.B, d.I, padded_hidden(d)}; }
+// dst [outer][rd][cd] <- src [outer][rs][cs]: the common corner is copied, the rest of dst is zero (pads and crops).
+hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s);
 
 size_t reserve_bytes(const Dims& d);
 WsLayout ws_layout(const Dims& d, bool wide_rows = false);

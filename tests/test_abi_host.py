@@ -31,8 +31,10 @@ def test_library_exports_every_symbol_of_the_rnn_header():
 
 
 def test_rnn_size_queries_and_argument_checks():
-    assert B.rnn_reserve_bytes(B.RNN_CELL_TANH, 2, 5, 3, 8, 16) == 2 * 5 * 3 * 16 * 4
-    assert B.rnn_reserve_bytes(B.RNN_CELL_GRU, 2, 5, 3, 8, 16) == 2 * 5 * 3 * 16 * 5 * 4
+    assert B.rnn_reserve_bytes(B.RNN_CELL_TANH, 2, 5, 3, 8, 128) == 2 * 5 * 3 * 128 * 4
+    assert B.rnn_reserve_bytes(B.RNN_CELL_GRU, 2, 5, 3, 8, 128) == 2 * 5 * 3 * 128 * 5 * 4
+    assert B.rnn_reserve_bytes(B.RNN_CELL_GRU, 2, 5, 3, 8, 16) == 2 * 5 * 3 * 128 * 5 * 4   # padded like the LSTM's sizes
+    assert B.rnn_reserve_bytes(B.RNN_CELL_GRU, 1, 5, 3, 8, 16) == 5 * 3 * 16 * 5 * 4        # a few steps of one layer: as given
     assert B.rnn_reserve_bytes(7, 2, 5, 3, 8, 16) == 0 and B.rnn_workspace_bytes(B.RNN_CELL_GRU, 0, 1, 1, 1, 1) == 0
     wb = B.rnn_workspace_bytes(B.RNN_CELL_GRU, 1, 2, 2, 4, 4)
     assert wb > 0 and wb % 256 == 0

@@ -86,6 +86,22 @@ def test_cells_match_oracle(cell, dims):
     run(cell, *dims, seed=3)
 
 
+# Hidden sizes below 512 without persistent kernels run zero-padded to 128 / 256 / 512 (as the LSTM's do);
+# RNN_NO_PERSISTENT=1 runs them as given on the step-by-step path, which keeps its ragged tiles covered.
+RAGGED = [(3, 5, 7, 24, 40), (2, 3, 3, 5, 7), (2, 4, 70, 36, 100), (2, 40, 9, 300, 300)]
+
+
+@pytest.mark.parametrize("step_by_step", [False, True], ids=["padded", "as_given"])
+@pytest.mark.parametrize("cell", ["relu", "tanh", "gru"])
+@pytest.mark.parametrize("dims", RAGGED, ids=["x".join(map(str, s)) for s in RAGGED])
+def test_ragged_hidden_sizes(cell, dims, step_by_step, monkeypatch):
+    if cell == "relu" and not few_cells(dims):
+        pytest.skip("ReLU: every input of this size has pre-activations within fp32 rounding of zero")
+    if step_by_step:
+        monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
+    run(cell, *dims, seed=11)
+
+
 @pytest.mark.parametrize("cell", ["tanh", "gru"])
 def test_cells_without_initial_state(cell):
     run(cell, 2, 4, 5, 16, 48, seed=4, with_h0=False)
