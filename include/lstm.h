@@ -70,12 +70,13 @@ extern "C" {
  * Returns 0 if any dimension is non-positive.
  *
  * Hidden sizes below 512 other than 128 and 256 (with B <= 512, and more than a few steps of one
- * layer) are computed at the next of 128, 256, 512: the library copies W, R, b, the initial states
+ * layer) are computed at the next of 128, 256, 512, and sizes from 704 to 1023 (with B <= 128) at
+ * 1024: the library copies W, R, b, the initial states
  * and, backward, the upstream gradients into zero-padded buffers inside the workspace, runs the
  * padded network on the chosen path and copies the results back.  The result is that of the
  * given network: a hidden unit whose weights, bias and initial state are zero stays at h = c = 0
  * at every step and receives zero gradients.  The persistent kernels (Section 4) exist for those
- * three sizes, and the padded run is faster than the per-step paths at the given size (three to
+ * sizes, and the padded run is faster than the per-step paths at the given size (three to
  * five times with four layers).  Reserve and workspace sizes are those of the padded network, and
  * the copies are part of the weight re-layout that Section 2.3 redoes every pass.  LSTM_NO_PAD=1 in the
  * environment (read at every call: set it the same for size queries, forward and backward) runs

@@ -62,7 +62,10 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_reserve_bytes(1, 40, 3, 8, 100) == 40 * 3 * 6 * 128 * 4
     assert B.lstm_reserve_bytes(1, 8, 3, 8, 100) == 8 * 3 * 6 * 100 * 4          # a few steps of one layer: not worth the copies
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 256) == 2 * 5 * 3 * 6 * 256 * 4      # native sizes stay as they are
-    assert B.lstm_reserve_bytes(2, 5, 3, 8, 640) == 2 * 5 * 3 * 6 * 640 * 4      # and so do sizes above 512
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 640) == 2 * 5 * 3 * 6 * 640 * 4      # and so do sizes just above 512
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 800) == 2 * 5 * 3 * 6 * 1024 * 4     # nearer 1024: the one-layer kernels
+    assert B.lstm_reserve_bytes(2, 5, 200, 8, 800) == 2 * 5 * 200 * 6 * 800 * 4  # but only for small batches
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 1100) == 2 * 5 * 3 * 6 * 1100 * 4
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 100 * 4  # and batches the persistent kernels do not take
     padded = B.lstm_workspace_bytes(2, 5, 3, 8, 100)
     assert padded > B.lstm_workspace_bytes(2, 5, 3, 8, 128) and padded % 256 == 0

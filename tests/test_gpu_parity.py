@@ -287,6 +287,7 @@ PADDED = [
     Config("h72", L=1, T=40, B=33, I=72, H=72, state_std=0.3, dstate_std=0.3),
     Config("h300b130", L=2, T=3, B=130, I=40, H=300, state_std=0.3, dstate_std=0.3),  # three batch slices
     Config("h511", L=5, T=3, B=7, I=511, H=511, state_std=0.3, dstate_std=0.3),       # odd size, two groups of layers
+    Config("h800", L=2, T=3, B=40, I=800, H=800, state_std=0.3, dstate_std=0.3),      # to 1024: the one-layer kernels
 ]
 
 
