@@ -2136,7 +2136,7 @@ bool persistent_large(const Dims& d, bool backward) {
 bool persistent_supported(const Dims& d, bool backward) {
   if (persistent_large(d, backward)) return true;
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
-  if (d.B > 512) return false;  // above 64 rows the batch is processed in slices of 64, one launch per slice
+  if (d.B > 2048) return false;  // slices of 64 rows; beyond 2048 rows the GEMM rungs are as fast or faster
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return d.H / 8 <= di.cus;  // deeper stacks than the chip holds run as groups of layers (run_forward_persistent)

@@ -136,6 +136,7 @@ PERS = [
     Config("p256b130", L=3, T=3, B=130, I=256, H=256, state_std=0.3, dstate_std=0.3),
     Config("p128b65", L=2, T=3, B=65, I=24, H=128, state_std=0.3, dstate_std=0.3),
     Config("p128b512", L=1, T=2, B=512, I=16, H=128, state_std=0.3, dstate_std=0.3),   # 8 slices side by side
+    Config("p128b1100", L=1, T=2, B=1100, I=16, H=128, state_std=0.3, dstate_std=0.3),  # 18 slices: 16 side by side, then 2
     Config("p512T1", L=4, T=1, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),     # a single step
 ]
 
