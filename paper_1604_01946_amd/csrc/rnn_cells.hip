@@ -125,7 +125,7 @@ inline bool gru_persistent_shape(int cell, const Dims& d) {
   const bool gru = cell == RNN_CELL_GRU;
   if (d.H == 1024) return d.B <= (gru ? 512 : 256);
   if (d.H == 2048) return d.B <= (gru ? 192 : 96);
-  return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= 512;
+  return (d.H == 128 || d.H == 256 || d.H == 512) && d.B <= (gru ? 1024 : 512);  // measured break-even with the step-by-step path
 }
 // cell selector of the templated persistent kernels
 inline int kernel_cell(int cell) { return cell == RNN_CELL_GRU ? 1 : (cell == RNN_CELL_RELU ? 2 : 3); }

@@ -111,7 +111,8 @@ def test_cells_without_initial_state(cell):
 # (I == H) or projected by a batched GEMM (I != H), batch slices side by side and in further launches, a single step.
 PERSISTENT = [(4, 7, 64, 512, 512), (2, 5, 33, 72, 256), (3, 4, 130, 128, 128), (1, 3, 48, 512, 512), (2, 1, 64, 256, 256),
               (1, 2, 512, 16, 128), (2, 6, 32, 256, 256), (4, 5, 1, 512, 512), (3, 4, 17, 40, 128),
-              (3, 3, 130, 256, 256)]   # the last: three slices of 64 rows, two side by side and one in a second launch
+              (3, 3, 130, 256, 256),   # three slices of 64 rows, two side by side and one in a second launch
+              (1, 2, 600, 16, 128)]    # ten slices (GRU; the single gate runs this batch step by step)
 
 
 @pytest.mark.parametrize("with_h0", [True, False], ids=["h0", "noh0"])
