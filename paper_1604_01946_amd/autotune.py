@@ -77,6 +77,8 @@ def tune(L, T, B, I, H, iters=3, device="cuda:0", register=True):
 
 
 if __name__ == "__main__":
+    if len(sys.argv) != 6 or not all(v.isdigit() for v in sys.argv[1:6]):
+        sys.exit("usage: python -m paper_1604_01946_amd.autotune L T B I H")
     dims = [int(v) for v in sys.argv[1:6]]
     r = tune(*dims)
     for k in ("forward", "backward"):

@@ -281,6 +281,22 @@ def test_odd_shapes(cfg, flags, nopad, monkeypatch):
     run_case(cfg, 3, flags)
 
 
+# The forward step kernel with 4, 8 and 16 hidden units per workgroup (the automatic choice depends on the hidden
+# size: 16 only from H = 3200 on), ragged shapes as given; B = 50 takes the variants built for two waves per SIMD.
+STEPK = [ODD[2], ODD[4], ODD[6],
+         Config("odd6", L=1, T=3, B=50, I=20, H=72, state_std=0.5, dstate_std=0.5),
+         Config("sk3", L=1, T=2, B=50, I=24, H=1024, state_std=0.5, dstate_std=0.5)]
+
+
+@pytest.mark.parametrize("mt", ["1", "2", "4"])
+@pytest.mark.parametrize("cfg", STEPK, ids=[c.name for c in STEPK])
+def test_step_kernel_units_per_workgroup(cfg, mt, monkeypatch):
+    _, binding, _ = _mods()
+    monkeypatch.setenv("LSTM_NO_PAD", "1")
+    monkeypatch.setenv("LSTM_STEP_MT", mt)
+    run_case(cfg, 19, binding.LSTM_PATH_STEP)
+
+
 # ------------------------------------------------------------------ hidden sizes padded to the persistent kernels'
 PADDED = [
     Config("h384", L=2, T=5, B=20, I=384, H=384, state_std=0.3, dstate_std=0.3),      # I == H before padding, not after
