@@ -274,6 +274,45 @@ def test_split_batch_and_row_permutation():
     assert np.allclose(yp, y[:, p], atol=1e-14)
 
 
+def test_zero_padded_hidden_units_change_nothing():
+    """Hidden units with zero weight rows and columns, zero bias and zero initial state stay at h = c = 0 and take
+    zero gradients: the network padded from H to Hp gives the given network's outputs and gradients exactly (the
+    library computes some hidden sizes this way)."""
+    cfg, d = rand_case(3, 5, 4, 6, 5, seed=21)
+    L, T, B, I, H = cfg.dims
+    Hp = 8
+    y, hT, cT, res = fwd(cfg, d)
+    g = bwd(cfg, d, res)
+    Ws = O.split_W(d["W"], L, I, H)
+    Wp = []
+    for l, Wl in enumerate(Ws):
+        Il = Wl.shape[1]
+        blk = np.zeros((4, Hp, Il if l == 0 else Hp))
+        blk[:, :H, :Il] = Wl.reshape(4, H, Il)
+        Wp.append(blk.ravel())
+    Rp = np.zeros((L, 4, Hp, Hp)); Rp[:, :, :H, :H] = d["R"].reshape(L, 4, H, H)
+    bp = np.zeros((L, 4, Hp)); bp[:, :, :H] = d["b"].reshape(L, 4, H)
+    pad = lambda a: np.concatenate([a, np.zeros(a.shape[:-1] + (Hp - H,))], axis=-1)
+    a = dict(x=d["x"], h0=pad(d["h0"]), c0=pad(d["c0"]), W=np.concatenate(Wp), R=Rp.reshape(L, 4 * Hp, Hp), b=bp.reshape(L, 4 * Hp))
+    yp, hTp, cTp, resp = O.lstm_forward(L, T, B, I, Hp, a["x"], a["h0"], a["c0"], a["W"], a["R"], a["b"])
+    assert np.array_equal(yp[..., :H], y) and np.array_equal(hTp[..., :H], hT) and np.array_equal(cTp[..., :H], cT)
+    assert not yp[..., H:].any() and not hTp[..., H:].any() and not cTp[..., H:].any()
+    gp = O.lstm_backward(L, T, B, I, Hp, a["x"], a["h0"], a["c0"], a["W"], a["R"], resp, pad(d["dy"]), pad(d["dhT"]), pad(d["dcT"]))
+    dx, dh0, dc0, dW, dR, db = gp
+    assert np.allclose(dx, g[0], atol=1e-15) and np.allclose(dh0[..., :H], g[1], atol=1e-15) and np.allclose(dc0[..., :H], g[2], atol=1e-15)
+    assert not dh0[..., H:].any() and not dc0[..., H:].any()
+    dWs = O.split_W(dW, L, I, Hp)
+    for l, (full, ref) in enumerate(zip(dWs, O.split_W(g[3], L, I, H))):
+        Il = ref.shape[1]
+        blk = full.reshape(4, Hp, -1)
+        assert np.allclose(blk[:, :H, :Il].reshape(4 * H, Il), ref, atol=1e-14)
+        assert not blk[:, H:, :].any() and not blk[:, :, Il:].any() if l else not blk[:, H:, :].any()
+    dRb = dR.reshape(L, 4, Hp, Hp)
+    assert np.allclose(dRb[:, :, :H, :H].reshape(L, 4 * H, H), g[4], atol=1e-14) and not dRb[:, :, H:, :].any() and not dRb[:, :, :, H:].any()
+    dbb = db.reshape(L, 4, Hp)
+    assert np.allclose(dbb[:, :, :H].reshape(L, 4 * H), g[5], atol=1e-14) and not dbb[:, :, H:].any()
+
+
 def test_backward_is_linear_in_upstream_gradients():
     cfg, d = rand_case(2, 5, 2, 3, 4, seed=12)
     _, _, _, res = fwd(cfg, d)

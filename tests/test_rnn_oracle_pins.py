@@ -119,3 +119,38 @@ def test_split_T_and_layer_stack(cell):
     ya, ha, _ = O.rnn_forward(cell, 1, T, B, I, H, d["x"], d["h0"][:1], Ws[0].ravel(), d["R"][:1], d["b"][:1])
     yb, hb, _ = O.rnn_forward(cell, 1, T, B, H, H, ya, d["h0"][1:], Ws[1].ravel(), d["R"][1:], d["b"][1:])
     assert np.allclose(yb, y, atol=1e-14) and np.allclose(np.stack([ha[0], hb[0]]), hT, atol=1e-14)
+
+
+@pytest.mark.parametrize("cell", ["relu", "tanh", "gru"])
+def test_zero_padded_hidden_units_change_nothing(cell):
+    """A hidden unit with zero weights, bias and initial state stays at h = 0 (GRU: r = z = 1/2, n = tanh(0)) and
+    takes zero gradients, so the network padded from H to Hp gives the given network's results (the library computes
+    some hidden sizes this way)."""
+    L, T, B, I, H, Hp = 3, 4, 3, 5, 6, 8
+    d = rand_case(cell, L, T, B, I, H, seed=31)
+    ng = O.CELLS[cell]
+    y, hT, saved = O.rnn_forward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    g = O.rnn_backward(cell, L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"])
+    Wp = []
+    for l, Wl in enumerate(O.split_W(d["W"], cell, L, I, H)):
+        Il = Wl.shape[1]
+        blk = np.zeros((ng, Hp, Il if l == 0 else Hp))
+        blk[:, :H, :Il] = Wl.reshape(ng, H, Il)
+        Wp.append(blk.ravel())
+    Rp = np.zeros((L, ng, Hp, Hp)); Rp[:, :, :H, :H] = d["R"].reshape(L, ng, H, H)
+    bp = np.zeros((L, ng, Hp)); bp[:, :, :H] = d["b"].reshape(L, ng, H)
+    pad = lambda a: np.concatenate([a, np.zeros(a.shape[:-1] + (Hp - H,))], axis=-1)
+    W2, R2, b2 = np.concatenate(Wp), Rp.reshape(L, ng * Hp, Hp), bp.reshape(L, ng * Hp)
+    yp, hTp, savedp = O.rnn_forward(cell, L, T, B, I, Hp, d["x"], pad(d["h0"]), W2, R2, b2)
+    assert np.array_equal(yp[..., :H], y) and np.array_equal(hTp[..., :H], hT)
+    assert not yp[..., H:].any() and not hTp[..., H:].any()
+    dx, dh0, dW, dR, db = O.rnn_backward(cell, L, T, B, I, Hp, d["x"], pad(d["h0"]), W2, R2, savedp, pad(d["dy"]), pad(d["dhT"]))
+    assert np.allclose(dx, g[0], atol=1e-14) and np.allclose(dh0[..., :H], g[1], atol=1e-14) and not dh0[..., H:].any()
+    for l, (full, ref) in enumerate(zip(O.split_W(dW, cell, L, I, Hp), O.split_W(g[2], cell, L, I, H))):
+        Il = ref.shape[1]
+        blk = full.reshape(ng, Hp, -1)
+        assert np.allclose(blk[:, :H, :Il].reshape(ng * H, Il), ref, atol=1e-13) and not blk[:, H:, :].any()
+    dRb = dR.reshape(L, ng, Hp, Hp)
+    assert np.allclose(dRb[:, :, :H, :H].reshape(L, ng * H, H), g[3], atol=1e-13) and not dRb[:, :, H:, :].any() and not dRb[:, :, :, H:].any()
+    dbb = db.reshape(L, ng, Hp)
+    assert np.allclose(dbb[:, :, :H].reshape(L, ng * H), g[4], atol=1e-13) and not dbb[:, :, H:].any()
