@@ -244,8 +244,13 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   __shared__ __attribute__((aligned(16))) float xs[8 * BP];  // this step's h slice, [unit][batch]
   __shared__ __attribute__((aligned(16))) float ro[6 * BP * 8];  // gates, c, h of the slice: [array][batch][unit]
 
+  // The recurrences of different batch rows are independent: slices of NC*BP rows run side by side as separate groups
+  // of workgroups with their own exchange slots and counters (a.nsl of them, the first at batch row a.b0).
   int l, s;
-  map_block(a.L, NS, l, s);
+  map_block(a.L, NS * a.nsl, l, s);
+  const int sl = s / NS;
+  s -= sl * NS;
+  const int brow0 = a.b0 + NC * BP * sl;
   const int T = a.T, B = a.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, n = lane & 15;
@@ -290,7 +295,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
     for (int g = 0; g < 4; ++g) c_bias[ci][g] = (p < 2 * NT) ? a.bias[(size_t)l * G + g * H + c_unit[ci]] : 0.f;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      const int bb = c * BP + c_lb[ci];
+      const int bb = brow0 + c * BP + c_lb[ci];
       c_valid[c][ci] = (p < 2 * NT) && (bb < B);
       c_state[c][ci] = (c_valid[c][ci] && a.c0) ? a.c0[((size_t)l * B + bb) * H + c_unit[ci]] : 0.f;
     }
@@ -301,8 +306,10 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   float* const res_c = res_l + TB * 4 * H;
   float* const res_h = res_l + TB * 5 * H;
   const size_t boff = (size_t)(wave * (H / 4) + q) * BP + NT * n;  // this lane's B-operand offset inside a slot
-  auto slot = [&](int layer, int sl, int c) { return a.hx + (((size_t)layer * (T + 1) + sl) * NC + c) * H * BP; };
-  auto flag = [&](int layer, int sl, int c) { return a.flags + (((size_t)layer * (T + 1) + sl) * NC + c) * kFlagInts; };
+  float* const hx = a.hx + (size_t)sl * a.L * (T + 1) * NC * H * BP;
+  int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * NC * kFlagInts;
+  auto slot = [&](int layer, int st, int c) { return hx + (((size_t)layer * (T + 1) + st) * NC + c) * H * BP; };
+  auto flag = [&](int layer, int st, int c) { return flags + (((size_t)layer * (T + 1) + st) * NC + c) * kFlagInts; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -327,7 +334,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
 #pragma unroll
         for (int g = 0; g < 4; ++g)
           pin[ci][g] = (l == 0 && c_valid[c][ci])
-                           ? a.P0[((size_t)t * B + c * BP + c_lb[ci]) * G + g * H + c_unit[ci]] : 0.f;
+                           ? a.P0[((size_t)t * B + brow0 + c * BP + c_lb[ci]) * G + g * H + c_unit[ci]] : 0.f;
 
       // Loads are issued in bulk ahead of the MFMAs that consume them (the scheduling barriers keep
       // the compiler from re-serialising them): a step is bound by load latency otherwise.
@@ -441,7 +448,7 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
       for (int i = 0; i < (12 * BP + 255) / 256; ++i) {
         const int idx = threadIdx.x + 256 * i;  // (array 0..5, chain-local batch row, half of the 8 units)
         const int arr = idx / (2 * BP), lb = (idx >> 1) % BP, hf = idx & 1;
-        const int b2 = c * BP + lb;
+        const int b2 = brow0 + c * BP + lb;
         if (idx < 12 * BP && b2 < B) {
           const floatx4 v = *reinterpret_cast<const floatx4*>(ro + (arr * BP + lb) * 8 + 4 * hf);
           const size_t e = ((size_t)t * B + b2) * H + u0 + 4 * hf;
@@ -461,14 +468,20 @@ __global__ __launch_bounds__(256) void pers_fwd_kernel(const PersFwdArgs a) {
   }
 }
 
-// h0 [L][B][H] -> exchange slot 0 of every layer and chain, k-major [H][BP].
+// h0 [L][B][H] -> exchange slot 0 of every slice, layer and chain, k-major [H][BP]; rows past the batch are zero.
 __global__ void pack_state_kernel(const float* __restrict__ h0, float* __restrict__ hx, int L, int T, int B, int H,
-                                  int BP, int NC) {
-  const long n = (long)L * B * H;
+                                  int BP, int NC, int b0, int nsl) {
+  const long n = (long)nsl * L * NC * BP * H;
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long)gridDim.x * blockDim.x) {
-    const int k = (int)(e % H), bb = (int)((e / H) % B), l = (int)(e / ((long)H * B));
-    const int c = bb / BP, lb = bb % BP;
-    hx[(((size_t)l * (T + 1)) * NC + c) * H * BP + (size_t)k * BP + lb] = h0[e];
+    const int lb = (int)(e % BP);
+    long r = e / BP;
+    const int k = (int)(r % H); r /= H;
+    const int c = (int)(r % NC); r /= NC;
+    const int l = (int)(r % L);
+    const int sl = (int)(r / L);
+    const int bb = b0 + (sl * NC + c) * BP + lb;
+    hx[((((size_t)sl * L + l) * (T + 1)) * NC + c) * H * BP + (size_t)k * BP + lb] =
+        bb < B ? h0[((size_t)l * B + bb) * H + k] : 0.f;
   }
 }
 
@@ -2395,9 +2408,20 @@ int forward_layers(const FwdArgs& a, int cell) {
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
-  const BatchPlan bp = batch_plan(d.B);
+  DeviceInfo di;
+  (void)device_info(di);
+  // 32 < B: the wide kernel takes slices of 64 rows (32x32x2 tiles).  While all of them fit the chip side by side as
+  // slices of 32 rows on the narrow kernel, that one is faster: half the matrix work per workgroup and step, on twice
+  // as many CUs (one or two layers at H = 512, up to four at H = 256: 0.49 against 0.74 ms at L = 1, H = 512, B = 64).
+  bool narrow_slices = false;
+  if (cell == 0 && d.B > 32 && (long)d.L * (d.H / 8) * ((d.B + 31) / 32) <= di.cus && (d.B + 31) / 32 <= 16 / d.L) {
+    const char* e = getenv("LSTM_FWD_NARROW");
+    const char* c2 = getenv("LSTM_CHAINS");
+    narrow_slices = !(e && (*e == '1' || *e == '0')) && !(c2 && *c2 == '2');  // 1: one slice of 64 rows, 0: wide kernel
+  }
+  const BatchPlan bp = narrow_slices ? BatchPlan{2, 1} : batch_plan(d.B);
   const int BP = 16 * bp.NT;
-  const bool wide = cell != 0 || fwd_wide(d);
+  const bool wide = cell != 0 || (!narrow_slices && fwd_wide(d));
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
@@ -2429,15 +2453,14 @@ int forward_layers(const FwdArgs& a, int cell) {
   k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
   // Slices of 64 batch rows run side by side in one launch while the CUs last, the rest in further launches.
-  DeviceInfo di;
-  (void)device_info(di);
-  int cap = wide && grid > 0 ? di.cus / grid : 1;
+  int cap = (wide || narrow_slices) && grid > 0 ? di.cus / grid : 1;
   if (cap > 16 / d.L) cap = 16 / d.L;  // the counter region holds 16 (slice, layer) pairs
   if (cap < 1) cap = 1;
-  const int slices = wide ? (d.B + 63) / 64 : 1;
+  const int slice_rows = narrow_slices ? 32 : 64;
+  const int slices = wide ? (d.B + 63) / 64 : (narrow_slices ? (d.B + 31) / 32 : 1);
   for (int s0 = 0; s0 < slices; s0 += cap) {
     const int nsl = slices - s0 < cap ? slices - s0 : cap;
-    k.b0 = 64 * s0;
+    k.b0 = slice_rows * s0;
     k.nsl = nsl;
     {
       ProfScope ps(LSTM_PHASE_FWD_PACK, s);
@@ -2453,9 +2476,9 @@ int forward_layers(const FwdArgs& a, int cell) {
           CK(hipGetLastError(), "pack x");
         }
       } else if (a.h0) {
-        const long n = (long)d.L * d.B * d.H;
+        const long n = (long)nsl * d.L * bp.NC * BP * d.H;
         hipLaunchKernelGGL(pack_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a.h0, hx, d.L, d.T, d.B,
-                           d.H, BP, bp.NC);
+                           d.H, BP, bp.NC, k.b0, nsl);
         CK(hipGetLastError(), "pack h0");
       }
     }
@@ -2466,9 +2489,9 @@ int forward_layers(const FwdArgs& a, int cell) {
                     : (cell == 1 ? launch_fwd32<1>(d.H, grid * nsl, k, s)
                                  : (cell == 2 ? launch_fwd32<2>(d.H, grid * nsl, k, s) : launch_fwd32<3>(d.H, grid * nsl, k, s)));
     }
-    else if (d.H == 512) e = launch_fwd<32>(bp, grid, k, s);
-    else if (d.H == 256) e = launch_fwd<16>(bp, grid, k, s);
-    else if (d.H == 128) e = launch_fwd<8>(bp, grid, k, s);
+    else if (d.H == 512) e = launch_fwd<32>(bp, grid * nsl, k, s);
+    else if (d.H == 256) e = launch_fwd<16>(bp, grid * nsl, k, s);
+    else if (d.H == 128) e = launch_fwd<8>(bp, grid * nsl, k, s);
     CK(e, "persistent forward launch");
   }
   return LSTM_OK;
