@@ -55,6 +55,8 @@ hipError_t launch_pointwise_bwd(const float* gates, const float* c_t, const floa
 hipError_t launch_transpose(const float* in, float* out, int rows, int cols, int batch, hipStream_t stream);
 // out[n] = sum_r in[r][n]; partial must hold 64*cols floats.
 hipError_t launch_colsum(const float* in, int rows, int cols, float* partial, float* out, hipStream_t stream);
+hipError_t launch_colsum_batched(const float* in, int rows, int cols, int count, float* partial, float* out,
+                                 hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 
 // ---------------------------------------------------------------- fused step kernels (step.hip)

@@ -889,7 +889,7 @@ struct PersBwdArgs {
   int* flags;          // [L][T+1][NC]
   int* watchdog;
   int L, T, B, I, H;
-  int b0;              // wide kernel: first batch row of this launch (a multiple of 64)
+  int b0;              // first batch row of this launch (a multiple of the slice height)
   int spin_limit;
   int full_fences;
   long long* trace;
@@ -904,8 +904,14 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   __shared__ float part[4][NT * 4][64];
   __shared__ __attribute__((aligned(16))) float xs[32 * BP];  // this step's dA slice, [gate][unit][batch]
 
+  // Slices of NC*BP batch rows side by side, as in the forward kernel: the grid holds one group of L*NS workgroups
+  // per slice, the first slice starts at batch row a.b0.
+  const int nsl = (int)gridDim.x / (a.L * NS);
   int l, s;
-  map_block(a.L, NS, l, s);
+  map_block(a.L, NS * nsl, l, s);
+  const int sl = s / NS;
+  s -= sl * NS;
+  const int brow0 = a.b0 + NC * BP * sl;
   const int T = a.T, B = a.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int q = lane >> 4, n = lane & 15;
@@ -936,7 +942,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   int seen_up[NC];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int bb = c * BP + lb;
+    const int bb = brow0 + c * BP + lb;
     pw[c] = fin && q < 2 && bb < B;                 // lane runs the point-wise stage
     dxl[c] = fin && q >= 2 && bb < B && (l > 0 || a.dx0);
     seen_up[c] = 0;
@@ -956,8 +962,10 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
   float* const dx_out = l > 0 ? a.dxbuf + (size_t)l * TB * H : a.dx0;
   const size_t boff = (size_t)(wave * H + q) * BP + NT * n;
-  auto slot = [&](int t, int c) { return a.dAx + (((size_t)l * T + t) * NC + c) * G * BP; };
-  auto flag = [&](int layer, int sl, int c) { return a.flags + (((size_t)layer * (T + 1) + sl) * NC + c) * kFlagInts; };
+  float* const dAx = a.dAx + (size_t)sl * a.L * T * NC * G * BP;
+  int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * NC * kFlagInts;
+  auto slot = [&](int t, int c) { return dAx + (((size_t)l * T + t) * NC + c) * G * BP; };
+  auto flag = [&](int layer, int st, int c) { return flags + (((size_t)layer * (T + 1) + st) * NC + c) * kFlagInts; };
 
   Waiter w{a.watchdog, a.spin_limit, false, a.full_fences};
   const Tracer tr{((int)blockIdx.x == a.trace_block) ? a.trace : nullptr};
@@ -970,7 +978,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
   floatx4 gi[NC], gf[NC], go[NC], gg[NC], ct[NC], cp[NC], dpre[NC];
   auto fetch_step = [&](int t, int c) {
     if (pw[c]) {
-      const int bb = c * BP + lb;
+      const int bb = brow0 + c * BP + lb;
       const size_t e = ((size_t)t * B + bb) * H + unit0;
       const size_t g0 = ((size_t)t * B + bb) * G + unit0;
       gi[c] = *reinterpret_cast<const floatx4*>(res_gates + g0);
@@ -996,7 +1004,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c == 0) tr.mark(t, 0);
-      const int bb = c * BP + lb;
+      const int bb = brow0 + c * BP + lb;
       // ---- point-wise stage of step t
       floatx4 dA4[4];
       const size_t e = ((size_t)t * B + bb) * H + unit0;
@@ -1110,7 +1118,7 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
     if (pw[c]) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const size_t se = ((size_t)l * B + c * BP + lb) * H + unit0 + r;
+        const size_t se = ((size_t)l * B + brow0 + c * BP + lb) * H + unit0 + r;
         if (a.dh0) a.dh0[se] = dh_rec[c][r];
         if (a.dc0) a.dc0[se] = dc[c][r];
       }
@@ -2067,6 +2075,27 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
 }
 
 // The wide-batch forward kernel (32x32x2 MFMA, two batch tiles of 32).
+// Height of the batch slices (16 or 32 rows) that run side by side on the narrow kernels, or 0 where the batch is
+// taken whole (B <= 16, or no room) or by the wide kernels.  While all slices fit the chip in one launch the narrow
+// kernels are the faster ones: a step's matrix work per workgroup shrinks with the slice and more CUs share it (one or
+// two layers at H = 512, up to four at H = 256; L = 1, H = 512, B = 64, T = 100: forward recurrence 0.40 ms on four
+// slices of 16 rows, 0.53 on two of 32, 0.74 on the wide kernel; backward 0.65 against 1.14).  `env` names the
+// variable that pins the choice: 1 = one slice on the narrow kernel (B <= 64), 0 = never slices.
+int narrow_slice_rows(const Dims& d, int cell, const char* env) {
+  if (cell != 0) return 0;  // the narrow kernels are LSTM kernels
+  const char* e = getenv(env);
+  if (e && (*e == '0' || *e == '1')) return 0;
+  const char* c2 = getenv("LSTM_CHAINS");
+  if (c2 && *c2 == '2') return 0;
+  DeviceInfo di;
+  if (!device_info(di)) return 0;
+  for (int rows = 16; rows <= 32; rows *= 2) {
+    const int n = (d.B + rows - 1) / rows;
+    if (d.B > rows && (long)d.L * (d.H / 8) * n <= di.cus && n <= 16 / d.L) return rows;  // 16 (slice, layer) counter blocks
+  }
+  return 0;
+}
+
 bool fwd_wide(const Dims& d) {
   if (d.B > 64) return true;  // batches above 64 run as slices of 64 rows, one launch each
   const char* e = getenv("LSTM_FWD_NARROW");
@@ -2410,16 +2439,9 @@ int forward_layers(const FwdArgs& a, int cell) {
   if (*g_watch_host) return LSTM_INTERNAL;
   DeviceInfo di;
   (void)device_info(di);
-  // 32 < B: the wide kernel takes slices of 64 rows (32x32x2 tiles).  While all of them fit the chip side by side as
-  // slices of 32 rows on the narrow kernel, that one is faster: half the matrix work per workgroup and step, on twice
-  // as many CUs (one or two layers at H = 512, up to four at H = 256: 0.49 against 0.74 ms at L = 1, H = 512, B = 64).
-  bool narrow_slices = false;
-  if (cell == 0 && d.B > 32 && (long)d.L * (d.H / 8) * ((d.B + 31) / 32) <= di.cus && (d.B + 31) / 32 <= 16 / d.L) {
-    const char* e = getenv("LSTM_FWD_NARROW");
-    const char* c2 = getenv("LSTM_CHAINS");
-    narrow_slices = !(e && (*e == '1' || *e == '0')) && !(c2 && *c2 == '2');  // 1: one slice of 64 rows, 0: wide kernel
-  }
-  const BatchPlan bp = narrow_slices ? BatchPlan{2, 1} : batch_plan(d.B);
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, "LSTM_FWD_NARROW");
+  const bool narrow_slices = slice_rows_narrow > 0;
+  const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
   const int BP = 16 * bp.NT;
   const bool wide = cell != 0 || (!narrow_slices && fwd_wide(d));
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
@@ -2456,8 +2478,8 @@ int forward_layers(const FwdArgs& a, int cell) {
   int cap = (wide || narrow_slices) && grid > 0 ? di.cus / grid : 1;
   if (cap > 16 / d.L) cap = 16 / d.L;  // the counter region holds 16 (slice, layer) pairs
   if (cap < 1) cap = 1;
-  const int slice_rows = narrow_slices ? 32 : 64;
-  const int slices = wide ? (d.B + 63) / 64 : (narrow_slices ? (d.B + 31) / 32 : 1);
+  const int slice_rows = narrow_slices ? slice_rows_narrow : 64;
+  const int slices = wide ? (d.B + 63) / 64 : (narrow_slices ? (d.B + slice_rows - 1) / slice_rows : 1);
   for (int s0 = 0; s0 < slices; s0 += cap) {
     const int nsl = slices - s0 < cap ? slices - s0 : cap;
     k.b0 = slice_rows * s0;
@@ -2555,8 +2577,10 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   if (*g_watch_host) return LSTM_INTERNAL;
-  const BatchPlan bp = batch_plan(d.B);
-  const bool wide = cell != 0 || bwd_wide(d);
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, "LSTM_BWD_NARROW");
+  const bool narrow_slices = slice_rows_narrow > 0;
+  const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
+  const bool wide = cell != 0 || (!narrow_slices && bwd_wide(d));
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
   PersBwdArgs k;
@@ -2580,13 +2604,14 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   // slice is two more "batch halves" of 32 rows with their own exchange slots and counters
   DeviceInfo di;
   (void)device_info(di);
-  int cap = wide && grid > 0 ? di.cus / grid : 1;
+  int cap = (wide || narrow_slices) && grid > 0 ? di.cus / grid : 1;
   if (cap > 16 / d.L) cap = 16 / d.L;
   if (cap < 1) cap = 1;
-  const int slices = wide ? (d.B + 63) / 64 : 1;
+  const int slice_rows = narrow_slices ? slice_rows_narrow : 64;
+  const int slices = wide ? (d.B + 63) / 64 : (narrow_slices ? (d.B + slice_rows - 1) / slice_rows : 1);
   for (int s0 = 0; s0 < slices; s0 += cap) {
     const int nsl = slices - s0 < cap ? slices - s0 : cap;
-    k.b0 = 64 * s0;
+    k.b0 = slice_rows * s0;
     {
       ProfScope ps(LSTM_PHASE_BWD_PACK, s);
       CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
@@ -2606,9 +2631,9 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
     else if (wide && d.H == 512) e = launch_bwd32<512>(k, 2 * nsl, s);
     else if (wide && d.H == 256) e = launch_bwd32<256>(k, 2 * nsl, s);
     else if (wide && d.H == 128) e = launch_bwd32<128>(k, 2 * nsl, s);
-    else if (d.H == 512) e = launch_bwd<128>(bp, grid, k, s);
-    else if (d.H == 256) e = launch_bwd<64>(bp, grid, k, s);
-    else if (d.H == 128) e = launch_bwd<32>(bp, grid, k, s);
+    else if (d.H == 512) e = launch_bwd<128>(bp, grid * nsl, k, s);
+    else if (d.H == 256) e = launch_bwd<64>(bp, grid * nsl, k, s);
+    else if (d.H == 128) e = launch_bwd<32>(bp, grid * nsl, k, s);
     CK(e, "persistent backward launch");
   }
   if (a.dx && !k.dx0) {  // layer 0's input gradient: all T steps in one product

@@ -100,9 +100,12 @@ __global__ void transpose_kernel(const float* __restrict__ in, float* __restrict
 }
 
 constexpr int kColsumChunks = 64;
-// grid (ceil(cols/64), kColsumChunks); 256 threads = 64 columns x 4 row lanes.
+// grid (ceil(cols/64), kColsumChunks, matrices); 256 threads = 64 columns x 4 row lanes.  Matrix z is in + z*rows*cols,
+// its partial sums partial + z*kColsumChunks*cols.
 __global__ void colsum_partial_kernel(const float* __restrict__ in, int rows, int cols, float* __restrict__ partial) {
   __shared__ float red[4][64];
+  in += (size_t)blockIdx.z * rows * cols;
+  partial += (size_t)blockIdx.z * kColsumChunks * cols;
   const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
   const int per = (rows + kColsumChunks - 1) / kColsumChunks;
@@ -117,6 +120,8 @@ __global__ void colsum_partial_kernel(const float* __restrict__ in, int rows, in
 __global__ void colsum_final_kernel(const float* __restrict__ partial, int cols, float* __restrict__ out) {
   const int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= cols) return;
+  partial += (size_t)blockIdx.y * kColsumChunks * cols;
+  out += (size_t)blockIdx.y * cols;
   float s = 0.f;
   for (int k = 0; k < kColsumChunks; ++k) s += partial[(long)k * cols + col];
   out[col] = s;
@@ -165,11 +170,17 @@ hipError_t launch_transpose(const float* in, float* out, int rows, int cols, int
 }
 
 hipError_t launch_colsum(const float* in, int rows, int cols, float* partial, float* out, hipStream_t stream) {
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3((cols + 63) / 64, kColsumChunks), dim3(256), 0, stream, in, rows,
+  return launch_colsum_batched(in, rows, cols, 1, partial, out, stream);
+}
+
+// `count` matrices [rows][cols] one after the other -> out [count][cols]; partial: count * 64 * cols floats.
+hipError_t launch_colsum_batched(const float* in, int rows, int cols, int count, float* partial, float* out,
+                                 hipStream_t stream) {
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((cols + 63) / 64, kColsumChunks, count), dim3(256), 0, stream, in, rows,
                      cols, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, stream, partial, cols, out);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256, count), dim3(256), 0, stream, partial, cols, out);
   return hipGetLastError();
 }
 

@@ -239,10 +239,9 @@ int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool b
   };
   if (!bias_done) {
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
-    for (int l = 0; l < d.L; ++l)
-      CK(launch_colsum(dA_all + (size_t)l * TB * G, (int)TB, (int)G,
-                       reinterpret_cast<float*>(a.ws + a.w.dbpart) + (size_t)l * 64 * G, a.db + (size_t)l * G, s),
-         "bias gradient");
+    // all layers in one pair of launches: dA [L][T*B][4H] -> db [L][4H]
+    CK(launch_colsum_batched(dA_all, (int)TB, (int)G, d.L, reinterpret_cast<float*>(a.ws + a.w.dbpart), a.db, s),
+       "bias gradient");
   }
   ProfScope ps(LSTM_PHASE_WEIGHT_GRAD, s);
   for (int l = 0; l < d.L; ++l) {

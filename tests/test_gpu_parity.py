@@ -210,11 +210,11 @@ VARIANTS = [
     {"LSTM_FWD_NARROW": "1", "LSTM_BWD_NARROW": "1", "LSTM_CHAINS": "2"},  # two independent batch chains
     {"LSTM_FULL_FENCES": "1"},                                             # release/acquire fences on every step
     {"LSTM_FWD_BATCHED_INPUT": "1"},                                       # layer 0's input product as one GEMM although I == H
-    {"LSTM_FWD_NARROW": "0"},                                              # wide forward kernel also where slices of 32 rows on the narrow one would fit
+    {"LSTM_FWD_NARROW": "0", "LSTM_BWD_NARROW": "0"},                      # wide kernels also where slices of 16 / 32 rows on the narrow ones would fit
 ]
 
 
-@pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences", "batched_input", "wide_forward"])
+@pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences", "batched_input", "wide"])
 @pytest.mark.parametrize("cfg", [PERS[3], PERS[4], PERS[5]], ids=["p256b20", "p512b33", "p512b64"])
 def test_persistent_variants(cfg, env, monkeypatch):
     """The alternative kernels and the fence-based protocol must give the oracle's answer too; the
