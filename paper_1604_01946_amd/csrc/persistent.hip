@@ -23,6 +23,13 @@
 // N = batch, K split over the four waves.  The exchange buffer is k-major so that one 16-byte
 // load per lane (4 consecutive batch entries of one k) feeds the B operands of the four batch
 // tiles: tile j, column n is batch 4n + j.
+//
+// Contents, in order: device helpers (waits, signals, write-through stores); pers_fwd_kernel (tiles of 16 batch rows:
+// B <= 32, and slices of 16 / 32 rows side by side); pers_fwd32_kernel (slices of 64 rows, 32x32x2 tiles; templated on
+// the cell: LSTM, GRU, single gate) with its pack kernels; pers_bwd_kernel and pers_bwd32_kernel, the same pair for
+// the backward recurrence; pers_fwdL_kernel / pers_bwdL_kernel (one layer per launch, H = 1024 / 2048, the recurrent
+// matrix spread over all CUs); host side: residency checks and launches, which shapes run where, groups of layers
+// for stacks deeper than the chip holds, batch slices.
 #include "../../include/lstm.h"
 #include "schedule.h"
 
