@@ -29,8 +29,10 @@
  *     default stream); internal helper streams fork from it and join back to it, and
  *     no call synchronises the host;
  *   - calls on different streams may overlap when each has its own `reserve` and
- *     `workspace` (results do not depend on what else runs on the device); two calls
- *     must never share a workspace or a reserve while either is in flight;
+ *     `workspace` (results do not depend on what else runs on the device; the
+ *     persistent kernels of one process run one after the other, chained through an
+ *     event, because each needs all its workgroups resident at once); two calls must
+ *     never share a workspace or a reserve while either is in flight;
  *   - return value: LSTM_OK or an LSTM_* error code.  Arguments are validated before
  *     any GPU work; on error nothing has been launched except for LSTM_HIP_ERROR /
  *     LSTM_INTERNAL, which can surface after partial execution.
@@ -62,7 +64,7 @@ extern "C" {
 #define LSTM_PATH_STEP        4u /* + time-batched input GEMM per layer and a fused recurrent-GEMM+point-wise
                                     step kernel, layers one after the other (optimisations 4, 5) */
 #define LSTM_PATH_WAVEFRONT   5u /* + layers overlapped on HIP streams in diagonal order (optimisations 2, 6) */
-#define LSTM_PATH_PERSISTENT  6u /* one cooperative kernel for the whole recurrence: weights resident in
+#define LSTM_PATH_PERSISTENT  6u /* one kernel for the whole recurrence, all workgroups resident: weights in
                                     registers, steps ordered by flags in device memory (Section 4) */
 #define LSTM_PATH_MASK        0xFu
 

@@ -1,4 +1,4 @@
-// Persistent recurrence kernels: the whole T-step, L-layer recurrence in ONE cooperative
+// Persistent recurrence kernels: the whole T-step, L-layer recurrence in ONE
 // launch, with the recurrent (and, for layers >= 1, the input) weights resident in registers.
 //
 // Section 4 of arXiv 1604.01946 names this as unexploited: the parameters are reused by every
@@ -6,8 +6,8 @@
 // assumptions outside the usual programming model (all blocks co-resident, blocks waiting on
 // each other).  On gfx950 the register file of one CU is 512 KB, so a workgroup that owns 8
 // hidden units keeps its [32 x 2H] slice of [W;R] (128 KB at H=512) in VGPRs as ready-made
-// MFMA A operands for the whole sequence.  Co-residency comes from a cooperative launch
-// (grid = L * H/8 <= number of CUs); ordering comes from per-(layer, step) counters in device
+// MFMA A operands for the whole sequence.  Co-residency comes from the grid never exceeding the
+// number of CUs and from never having two such kernels in flight (see launch_resident); ordering comes from per-(layer, step) counters in device
 // memory, released / acquired at agent scope, so that a layer only waits for the cells it
 // really depends on -- cell (l, t) needs (l, t-1) and (l-1, t) -- and the layers run as the
 // diagonal wavefront of Section 2.4 inside one grid.  Every wait is bounded: when the spin
@@ -2031,14 +2031,41 @@ int full_fences() {
   return (e && *e && *e != '0') ? 1 : 0;
 }
 
-// All workgroups of a persistent kernel must be resident at once (they wait on each other).  The
-// cooperative launch guarantees that; LSTM_PLAIN_LAUNCH=1 uses an ordinary launch instead, which is
-// resident as well when nothing else holds the CUs for good (the grid never exceeds one workgroup
-// per CU), for comparison.
+// All workgroups of a persistent kernel must be resident at once (they wait on each other).  The grid never exceeds
+// the number of CUs and every workgroup fits a CU on its own, so an ordinary launch is resident as soon as the CUs it
+// needs are free, and every other kernel on the device ends without waiting for anything.  What must not happen is
+// two persistent kernels each holding part of the CUs and waiting for the rest: the persistent launches of this
+// process are therefore chained, each waits (on the GPU, through an event) for the one before it, whatever their
+// streams.  This costs nothing on one stream.  A cooperative launch gives the same guarantee device-wide, also
+// against other processes, but measured 0.05-0.15 ms slower per launch on this stack and slows later multi-stream
+// work of the process down: LSTM_COOP_LAUNCH=1 selects it.  LSTM_PLAIN_LAUNCH=1 launches without the chain (two
+// persistent kernels may then share the CUs when both fit; diagnostics and tests).  A wait that never ends is, in
+// every mode, turned into LSTM_INTERNAL by the watchdog.
+std::mutex g_launch_mu;
+hipEvent_t g_last_launch[16] = {};  // per device: completion of the most recent persistent launch
+
 hipError_t launch_resident(const void* fn, int grid, void** params, unsigned smem, hipStream_t s) {
+  const char* c = getenv("LSTM_COOP_LAUNCH");
+  if (c && *c == '1') return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
   const char* e = getenv("LSTM_PLAIN_LAUNCH");
-  if (e && *e == '1') return hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);
-  return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
+  int dev = 0;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if ((e && *e == '1') || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16 ||
+      hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);  // (a stream under capture is ordered by its graph)
+  }
+  std::lock_guard<std::mutex> lk(g_launch_mu);
+  hipError_t st = hipSuccess;
+  if (g_last_launch[dev]) {
+    st = hipStreamWaitEvent(s, g_last_launch[dev], 0);
+  } else {
+    st = hipEventCreateWithFlags(&g_last_launch[dev], hipEventDisableTiming);
+  }
+  if (st != hipSuccess) return st;
+  st = hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);
+  if (st != hipSuccess) return st;
+  return hipEventRecord(g_last_launch[dev], s);
 }
 
 // Batch tiles per chain and number of chains.  One chain is the default: on MI355X two chains
@@ -2156,6 +2183,14 @@ void set_trace(void* buf, size_t bytes, int block) {
 }
 
 void release_persistent() {
+  {
+    std::lock_guard<std::mutex> lk(g_launch_mu);
+    for (hipEvent_t& ev : g_last_launch)
+      if (ev) {
+        (void)hipEventDestroy(ev);
+        ev = nullptr;
+      }
+  }
   std::lock_guard<std::mutex> lk(g_mu);
   if (g_watch_host) {
     (void)hipHostFree(g_watch_host);

@@ -375,13 +375,17 @@ def test_bitwise_repeatable(name):
         assert torch.equal(outs[0][k], outs[1][k]) and torch.equal(outs[0][k], outs[2][k]), k
 
 
+@pytest.mark.parametrize("launch", ["unchained", "chained", "cooperative"])
 @pytest.mark.parametrize("dims", [(4, 100, 16, 256), (8, 60, 32, 256)], ids=["b16", "b32"])
-def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, monkeypatch):
-    """Two calls on two streams whose persistent kernels fit on the same CUs (ordinary launches, small register
-    footprint): each must give exactly what it gives alone.  This caught a 16-byte write-through store issued from
-    inline assembly without the idle cycles a wide store needs before its data registers are overwritten."""
+def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, launch, monkeypatch):
+    """Two calls on two streams: each must give exactly what it gives alone.  Unchained ordinary launches let the two
+    persistent kernels run on the same CUs at once where both fit (small register footprint): this caught a 16-byte
+    write-through store issued from inline assembly without the idle cycles a wide store needs before its data
+    registers are overwritten.  The default chains the persistent launches of the process; cooperative launches are
+    the third mode."""
     torch, binding, runner = _mods()
-    monkeypatch.setenv("LSTM_PLAIN_LAUNCH", "1")
+    if launch != "chained":
+        monkeypatch.setenv("LSTM_PLAIN_LAUNCH" if launch == "unchained" else "LSTM_COOP_LAUNCH", "1")
     L, T, B, H = dims
     cfg = Config("two", L=L, T=T, B=B, I=H, H=H, state_std=0.1)
     r1, r2 = runner.LstmRunner(cfg.dims, make_inputs(cfg, 1)), runner.LstmRunner(cfg.dims, make_inputs(cfg, 2))
