@@ -113,8 +113,11 @@ def test_cfg3_forward_backward(flags):
     run_case(CONFIGS["cfg3"], 0, flags)
 
 
-def test_cfg4_large_hidden():
-    run_case(CONFIGS["cfg4"], 0, 0)
+@pytest.mark.parametrize("flags", [0, 4], ids=["auto", "step"])
+def test_cfg4_large_hidden(flags):
+    """Full size: the one-layer persistent kernels (automatic path), and the step kernels that stream R every step
+    (split-K backward) at the size they were built for."""
+    run_case(CONFIGS["cfg4"], 0, flags)
 
 
 @pytest.mark.parametrize("flags", [0, 4, 6])
