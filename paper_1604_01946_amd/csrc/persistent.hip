@@ -2044,6 +2044,25 @@ int full_fences() {
 std::mutex g_launch_mu;
 hipEvent_t g_last_launch[16] = {};  // per device: completion of the most recent persistent launch
 
+// Side stream (default priority) and two events for work that overlaps a persistent launch which leaves CUs idle.
+hipStream_t g_side_stream = nullptr;
+hipEvent_t g_side_ev[2] = {};
+bool ensure_side_stream() {
+  std::lock_guard<std::mutex> lk(g_launch_mu);
+  if (g_side_stream) return true;
+  if (hipStreamCreateWithFlags(&g_side_stream, hipStreamNonBlocking) != hipSuccess) {
+    g_side_stream = nullptr;
+    (void)hipGetLastError();
+    return false;
+  }
+  for (hipEvent_t& ev : g_side_ev)
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+  return true;
+}
+
 hipError_t launch_resident(const void* fn, int grid, void** params, unsigned smem, hipStream_t s) {
   const char* c = getenv("LSTM_COOP_LAUNCH");
   if (c && *c == '1') return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
@@ -2190,6 +2209,15 @@ void release_persistent() {
         (void)hipEventDestroy(ev);
         ev = nullptr;
       }
+    for (hipEvent_t& ev : g_side_ev)
+      if (ev) {
+        (void)hipEventDestroy(ev);
+        ev = nullptr;
+      }
+    if (g_side_stream) {
+      (void)hipStreamDestroy(g_side_stream);
+      g_side_stream = nullptr;
+    }
   }
   std::lock_guard<std::mutex> lk(g_mu);
   if (g_watch_host) {
@@ -2366,6 +2394,21 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
   int* flagsA = reinterpret_cast<int*>(a.ws + a.w.flags);
   int* flagsP = flagsA + (size_t)maxsl * d.T * NBK * kFlagInts;
   const bool bias_in_kernel = slices == 1;
+  // A launch that occupies at most half of the CUs (H = 1024 with one or two slices) leaves room for the weight
+  // gradients of the layer above, which are complete once that layer's recurrence is: they run on a side stream
+  // while this layer's recurrence runs (Section 2.6 wants them after the propagation of *their* layer, not of all
+  // layers).  The side stream starts them behind the counter reset that precedes the persistent launch, so that the
+  // launch gets its CUs first and the products fill the rest.  LSTM_NO_WGRAD_OVERLAP=1 keeps one stream.
+  bool overlap = cell == 0 && d.L > 1 && 2 * maxsl * NBK * NBK <= di.cus && slices <= cap;
+  {
+    const char* e = getenv("LSTM_NO_WGRAD_OVERLAP");
+    hipStreamCaptureStatus cst = hipStreamCaptureStatusNone;
+    if ((e && *e == '1') || hipStreamIsCapturing(s, &cst) != hipSuccess || cst != hipStreamCaptureStatusNone ||
+        !ensure_side_stream())
+      overlap = false;
+    (void)hipGetLastError();
+  }
+  int pending = -1;  // layer whose weight gradients wait for the side stream
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
     float* dA = dA_all + (size_t)l * TB * G;
@@ -2374,6 +2417,13 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
       {
         ProfScope ps(LSTM_PHASE_BWD_PACK, s);
         CK(launch_fill_zero(flagsA, (size_t)2 * maxsl * d.T * NBK * kFlagInts * 4, s), "zero step counters");
+      }
+      if (overlap && pending >= 0) {
+        CK(hipEventRecord(g_side_ev[0], s), "fork to the side stream");
+        CK(hipStreamWaitEvent(g_side_stream, g_side_ev[0], 0), "side stream wait");
+        const int st = weight_gradients_layers(a, dA_all, pending, pending + 1, g_side_stream, true, bias_in_kernel);
+        if (st != LSTM_OK) return st;
+        pending = -1;
       }
       PersBwdLArgs k;
       k.R = a.R + (size_t)l * GW * d.H;
@@ -2401,10 +2451,17 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
       GemmProblem p{dA, Wl, din, (int)TB, Il, (int)GW, (long)G, 1, Il, 1, Il, 0};
       CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
     }
+    if (overlap) pending = l;
   }
   if (bias_done) *bias_done = bias_in_kernel;
   if (cell != 0) return LSTM_OK;
-  return weight_gradients(a, dA_all, true, bias_in_kernel);
+  if (!overlap) return weight_gradients(a, dA_all, true, bias_in_kernel);
+  // the bottom layer's weight gradients have nothing left to hide behind; then the side stream joins
+  const int st = weight_gradients_layers(a, dA_all, 0, 1, s, true, bias_in_kernel);
+  if (st != LSTM_OK) return st;
+  CK(hipEventRecord(g_side_ev[1], g_side_stream), "join record");
+  CK(hipStreamWaitEvent(s, g_side_ev[1], 0), "join wait");
+  return LSTM_OK;
 }
 
 }  // namespace

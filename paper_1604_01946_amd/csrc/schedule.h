@@ -60,6 +60,8 @@ WsLayout ws_layout(const Dims& d, bool wide_rows = false);
 unsigned resolve_auto_path(const Dims& d, bool backward);
 int set_path_override(const Dims& d, bool backward, unsigned path);  // LSTM_PATH_AUTO removes the entry
 void clear_path_overrides();
+int weight_gradients_layers(const BwdArgs& a, const float* dA_all, int l0, int l1, hipStream_t s, bool grouped,
+                            bool bias_done);
 int run_forward(const FwdArgs& a, unsigned path);
 int run_backward(const BwdArgs& a, unsigned path);
 void release_helpers();

@@ -221,10 +221,15 @@ int fwd_unfused(const FwdArgs& a, int level) {
 // dW_l = sum_t dA_t^T in_t, dR_l = sum_t dA_t^T h_{t-1}, db_l = sum_t,b dA_t: products over K = T*B
 // with no dependencies between them, so all of them go into grouped launches.
 int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool bias_done) {
+  return weight_gradients_layers(a, dA_all, 0, a.d.L, a.stream, grouped, bias_done);
+}
+
+// Layers l0 .. l1-1, on stream s (which may be another stream than the call's: the caller orders it).
+int weight_gradients_layers(const BwdArgs& a, const float* dA_all, int l0, int l1, hipStream_t s, bool grouped,
+                            bool bias_done) {
   const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H;
   const int H = d.H, B = d.B;
-  hipStream_t s = a.stream;
   GemmProblem main_p[kMaxGemmGroup], tail_p[kMaxGemmGroup];
   int nm = 0, nt = 0;
   auto flush = [&](GemmProblem* arr, int& n) -> hipError_t {
@@ -240,11 +245,12 @@ int weight_gradients(const BwdArgs& a, const float* dA_all, bool grouped, bool b
   if (!bias_done) {
     ProfScope ps(LSTM_PHASE_BIAS_GRAD, s);
     // all layers in one pair of launches: dA [L][T*B][4H] -> db [L][4H]
-    CK(launch_colsum_batched(dA_all, (int)TB, (int)G, d.L, reinterpret_cast<float*>(a.ws + a.w.dbpart), a.db, s),
+    CK(launch_colsum_batched(dA_all + (size_t)l0 * TB * G, (int)TB, (int)G, l1 - l0,
+                             reinterpret_cast<float*>(a.ws + a.w.dbpart) + (size_t)l0 * 64 * G, a.db + (size_t)l0 * G, s),
        "bias gradient");
   }
   ProfScope ps(LSTM_PHASE_WEIGHT_GRAD, s);
-  for (int l = 0; l < d.L; ++l) {
+  for (int l = l0; l < l1; ++l) {
     const int Il = in_dim(d, l);
     const float* dA = dA_all + (size_t)l * TB * G;
     const float* in = l == 0 ? a.x : layer_res(a.reserve, d, l - 1).h;
