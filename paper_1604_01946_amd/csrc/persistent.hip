@@ -2372,7 +2372,7 @@ hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s
                    : (cell == 2 ? launch_bwdL<1024, 2>(k, s) : launch_bwdL<1024, 3>(k, s)));
 }
 
-int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
+int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, LayerGradients* lg) {
   const Dims& d = a.d;
   constexpr int UB = 128;
   const int NBK = d.H / UB;
@@ -2399,7 +2399,7 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
   // while this layer's recurrence runs (Section 2.6 wants them after the propagation of *their* layer, not of all
   // layers).  The side stream starts them behind the counter reset that precedes the persistent launch, so that the
   // launch gets its CUs first and the products fill the rest.  LSTM_NO_WGRAD_OVERLAP=1 keeps one stream.
-  bool overlap = cell == 0 && d.L > 1 && 2 * maxsl * NBK * NBK <= di.cus && slices <= cap;
+  bool overlap = (cell == 0 || lg) && d.L > 1 && 2 * maxsl * NBK * NBK <= di.cus && slices <= cap;
   {
     const char* e = getenv("LSTM_NO_WGRAD_OVERLAP");
     hipStreamCaptureStatus cst = hipStreamCaptureStatusNone;
@@ -2421,7 +2421,8 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
       if (overlap && pending >= 0) {
         CK(hipEventRecord(g_side_ev[0], s), "fork to the side stream");
         CK(hipStreamWaitEvent(g_side_stream, g_side_ev[0], 0), "side stream wait");
-        const int st = weight_gradients_layers(a, dA_all, pending, pending + 1, g_side_stream, true, bias_in_kernel);
+        const int st = cell == 0 ? weight_gradients_layers(a, dA_all, pending, pending + 1, g_side_stream, true, bias_in_kernel)
+                                 : lg->fn(lg->ctx, pending, g_side_stream);
         if (st != LSTM_OK) return st;
         pending = -1;
       }
@@ -2454,11 +2455,11 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done) {
     if (overlap) pending = l;
   }
   if (bias_done) *bias_done = bias_in_kernel;
-  if (cell != 0) return LSTM_OK;
-  if (!overlap) return weight_gradients(a, dA_all, true, bias_in_kernel);
+  if (!overlap) return cell != 0 ? LSTM_OK : weight_gradients(a, dA_all, true, bias_in_kernel);
   // the bottom layer's weight gradients have nothing left to hide behind; then the side stream joins
-  const int st = weight_gradients_layers(a, dA_all, 0, 1, s, true, bias_in_kernel);
+  const int st = cell == 0 ? weight_gradients_layers(a, dA_all, 0, 1, s, true, bias_in_kernel) : lg->fn(lg->ctx, 0, s);
   if (st != LSTM_OK) return st;
+  if (lg) lg->used = true;
   CK(hipEventRecord(g_side_ev[1], g_side_stream), "join record");
   CK(hipStreamWaitEvent(s, g_side_ev[1], 0), "join wait");
   return LSTM_OK;
@@ -2621,12 +2622,12 @@ int forward_layers(const FwdArgs& a, int cell) {
 // cell as in run_forward_persistent.  For the other cells the function stops after the propagation (gate gradients
 // [L][T*B][4H] at the start of the workspace: GRU r, z, n, and n times r; single gate: the first H columns) and
 // reports in *bias_done whether db is complete; the caller forms the weight gradients.
-int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done) {
+int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done, LayerGradients* lg) {
   const Dims& d = a.d;
   if (persistent_large(d, true)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
     if (*g_watch_host) return LSTM_INTERNAL;
-    return run_backward_persistent_large(a, cell, bias_done);
+    return run_backward_persistent_large(a, cell, bias_done, lg);
   }
   const int per = layers_per_launch(d);
   if (per <= 0) return LSTM_UNSUPPORTED;

@@ -11,7 +11,7 @@ namespace lstm {
 // persistent.hip: the wide persistent kernels also run the GRU (weights on chip for all T steps, Section 4)
 bool gru_persistent_supported(const Dims& d);
 int run_forward_persistent(const FwdArgs& a, int cell);
-int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done);
+int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done, LayerGradients* lg);
 
 #define CK(expr, what)                                             \
   do {                                                             \
@@ -198,29 +198,16 @@ int backward_persistent(int cell, const Dims& d, const float* x, const float* h0
   const size_t TB = (size_t)d.T * B, G = (size_t)gates_of(cell) * H, G4 = 4 * (size_t)H, BH = (size_t)B * H;
   const WsLayout w = ws_layout(d, true);
   const BwdArgs a{d, x, h0, nullptr, W, R, reserve, dy, dhT, nullptr, dx, dh0, nullptr, dW, dR, db, ws, w, s};
-  bool bias_done = false;
-  const int st = run_backward_persistent(a, kernel_cell(cell), &bias_done);
-  if (st != LSTM_OK) return st;
   const float* dA_all = reinterpret_cast<const float*>(ws + w.P);
-  GemmProblem main_g[kMaxGemmGroup], init_g[kMaxGemmGroup];
-  int nm = 0, ni = 0;
-  auto flush = [&]() -> hipError_t {
-    hipError_t e = hipSuccess;
-    if (nm) e = launch_gemm_group(main_g, nm, s);
-    if (e == hipSuccess && ni) e = launch_gemm_group(init_g, ni, s);
-    nm = ni = 0;
-    return e;
-  };
-  size_t woff = 0;
-  for (int l = 0; l < d.L; ++l) {
+  // The gradient products of layer l (Section 2.6: large products once the layer's propagation is complete) are
+  // appended to two groups: the sums over steps, and the initial-state terms that accumulate onto them.
+  auto add_layer = [&](int l, GemmProblem* main_g, int& nm, GemmProblem* init_g, int& ni, hipStream_t st) -> int {
     const int Il = in_dim(d, l);
     const float* dA = dA_all + (size_t)l * TB * G4;
     const float* hl = reserve + (size_t)l * res_layer_floats(cell, d);
     const float* in = l == 0 ? x : reserve + (size_t)(l - 1) * res_layer_floats(cell, d);
-    float* dWl = dW + woff;
+    float* dWl = dW + (l == 0 ? 0 : G * d.I + (size_t)(l - 1) * G * H);
     float* dRl = dR + (size_t)l * G * H;
-    woff += G * Il;
-    if (nm + 3 > kMaxGemmGroup || ni + 2 > kMaxGemmGroup) CK(flush(), "weight-gradient GEMMs");
     main_g[nm++] = GemmProblem{dA, in, dWl, (int)G, Il, (int)TB, 1, (long)G4, Il, 1, Il, 0};
     // dR: GRU rows r, z from the first two groups, rows n from the fourth (the gradient of R_n h); single gate: the first
     const int m1 = gru ? 2 * H : H;
@@ -235,10 +222,43 @@ int backward_persistent(int cell, const Dims& d, const float* x, const float* h0
       if (gru)
         init_g[ni++] = GemmProblem{dA + 3 * H, h0 + (size_t)l * BH, dRl + (size_t)2 * H * H, H, H, B, 1, (long)G4, H, 1, H, acc};
     } else if (d.T == 1) {
-      CK(launch_fill_zero(dRl, G * H * 4, s), "zero dR");
+      CK(launch_fill_zero(dRl, G * H * 4, st), "zero dR");
     }
+    return LSTM_OK;
+  };
+  auto flush = [&](GemmProblem* main_g, int& nm, GemmProblem* init_g, int& ni, hipStream_t st) -> int {
+    if (nm) CK(launch_gemm_group(main_g, nm, st), "weight-gradient GEMMs");
+    if (ni) CK(launch_gemm_group(init_g, ni, st), "weight-gradient GEMMs (initial state term)");
+    nm = ni = 0;
+    return LSTM_OK;
+  };
+  // One layer on a stream of the caller's choice: the one-layer kernels run it under the next layer's recurrence
+  // where CUs are idle.
+  auto layer_products = [&](int l, hipStream_t st) -> int {
+    GemmProblem main_g[3], init_g[2];
+    int nm = 0, ni = 0;
+    const int rc = add_layer(l, main_g, nm, init_g, ni, st);
+    return rc != LSTM_OK ? rc : flush(main_g, nm, init_g, ni, st);
+  };
+  using Fn = decltype(layer_products);
+  LayerGradients lg{[](void* ctx, int l, hipStream_t st) { return (*static_cast<Fn*>(ctx))(l, st); }, &layer_products, false};
+  bool bias_done = false;
+  const int st = run_backward_persistent(a, kernel_cell(cell), &bias_done, &lg);
+  if (st != LSTM_OK) return st;
+  if (!lg.used) {  // all layers in grouped launches
+    GemmProblem main_g[kMaxGemmGroup], init_g[kMaxGemmGroup];
+    int nm = 0, ni = 0;
+    for (int l = 0; l < d.L; ++l) {
+      if (nm + 3 > kMaxGemmGroup || ni + 2 > kMaxGemmGroup) {
+        const int rc = flush(main_g, nm, init_g, ni, s);
+        if (rc != LSTM_OK) return rc;
+      }
+      const int rc = add_layer(l, main_g, nm, init_g, ni, s);
+      if (rc != LSTM_OK) return rc;
+    }
+    const int rc = flush(main_g, nm, init_g, ni, s);
+    if (rc != LSTM_OK) return rc;
   }
-  CK(flush(), "weight-gradient GEMMs");
   if (!bias_done) {  // column sums over all four groups, of which db takes the leading ones
     float* part = reinterpret_cast<float*>(ws + w.dbpart);
     float* sums = reinterpret_cast<float*>(ws + w.scratch);

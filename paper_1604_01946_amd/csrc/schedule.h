@@ -60,6 +60,14 @@ WsLayout ws_layout(const Dims& d, bool wide_rows = false);
 unsigned resolve_auto_path(const Dims& d, bool backward);
 int set_path_override(const Dims& d, bool backward, unsigned path);  // LSTM_PATH_AUTO removes the entry
 void clear_path_overrides();
+// Weight gradients of one layer on a given stream, supplied by the caller of the persistent backward pass for the
+// cells whose gradient products it forms itself; *used is set when the pass has called it for every layer.
+struct LayerGradients {
+  int (*fn)(void* ctx, int layer, hipStream_t s);
+  void* ctx;
+  bool used;
+};
+
 int weight_gradients_layers(const BwdArgs& a, const float* dA_all, int l0, int l1, hipStream_t s, bool grouped,
                             bool bias_done);
 int run_forward(const FwdArgs& a, unsigned path);

@@ -25,7 +25,7 @@ namespace lstm {
 int run_forward_wavefront(const FwdArgs& a);
 int run_backward_wavefront(const BwdArgs& a);
 int run_forward_persistent(const FwdArgs& a, int cell = 0);
-int run_backward_persistent(const BwdArgs& a, int cell = 0, bool* bias_done = nullptr);
+int run_backward_persistent(const BwdArgs& a, int cell = 0, bool* bias_done = nullptr, LayerGradients* lg = nullptr);
 bool persistent_supported(const Dims& d, bool backward);
 
 int device_cu_count();
