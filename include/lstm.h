@@ -160,6 +160,16 @@ unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward);
 int lstm_set_path(int L, int T, int B, int I, int H, int backward, unsigned path);
 
 /*
+ * Number of chunks the stream-wavefront path cuts the sequence into for one shape (both directions).
+ * Section 2.3: batching the input products of s steps makes them more efficient but makes the layer
+ * above wait longer, and the best s depends on the hardware and the shape; the default is about 2L
+ * chunks.  `chunks` = 0 removes the setting; values above T or 64 are clamped.  Host-side table,
+ * thread-safe, emptied by lstm_shutdown.  Returns LSTM_OK or LSTM_INVALID_ARG (non-positive
+ * dimension, negative count).  The bundled autotuner measures a few counts and pins the best.
+ */
+int lstm_set_wavefront_chunks(int L, int T, int B, int I, int H, int chunks);
+
+/*
  * Phase timing for measurement (Section 2.5 reports time per optimisation stage; this is the
  * same breakdown taken live).  While enabled, lstm_forward / lstm_backward record HIP events
  * on the stream each phase is launched on, at the phase's first and last launch.

@@ -58,6 +58,19 @@ def tune(L, T, B, I, H, iters=3, device="cuda:0", register=True):
         return e0.elapsed_time(e1) / iters
 
     out = {"forward": {}, "backward": {}}
+    # Section 2.3: how many steps to batch in one input product is "not trivial" to choose -- measure a few chunk
+    # counts of the stream wavefront (forward + backward, one setting for both) and keep the best
+    if L > 1:
+        B_.check(fwd(B_.LSTM_PATH_STEP), "autotune")
+        per_chunks = {}
+        for c in sorted({0, 1, 2, 4, 8, 16} & set(range(0, T + 1))):
+            B_.check(B_.lstm_set_wavefront_chunks(*dims, c), "lstm_set_wavefront_chunks")
+            tf, tb = time_it(fwd, B_.LSTM_PATH_WAVEFRONT), time_it(bwd, B_.LSTM_PATH_WAVEFRONT)
+            per_chunks[c] = tf + tb
+        best_c = min(per_chunks, key=per_chunks.get)
+        B_.check(B_.lstm_set_wavefront_chunks(*dims, best_c if register else 0), "lstm_set_wavefront_chunks")
+        out["wavefront_chunks"] = {("default" if c == 0 else c): ms for c, ms in per_chunks.items()}
+        out["best_chunks"] = "default" if best_c == 0 else best_c
     for p in CANDIDATES:
         ms = time_it(fwd, p)
         if ms is not None:
@@ -83,4 +96,6 @@ if __name__ == "__main__":
     r = tune(*dims)
     for k in ("forward", "backward"):
         print(k, {n: round(v, 3) for n, v in r[k].items()})
+    if "wavefront_chunks" in r:
+        print("wavefront chunks (fwd+bwd ms)", {n: round(v, 3) for n, v in r["wavefront_chunks"].items()}, "best", r["best_chunks"])
     print("best", r["best"])

@@ -30,7 +30,7 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
-    "lstm_auto_path", "lstm_set_path", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
+    "lstm_auto_path", "lstm_set_path", "lstm_set_wavefront_chunks", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
     "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name", "lstm_debug_set_trace",
 ]
 RNN_EXPORTS = ["rnn_reserve_bytes", "rnn_workspace_bytes", "rnn_forward", "rnn_backward"]
@@ -68,6 +68,8 @@ def library():
         lib.lstm_auto_path.argtypes = [i] * 6
         lib.lstm_set_path.restype = i
         lib.lstm_set_path.argtypes = [i] * 6 + [u]
+        lib.lstm_set_wavefront_chunks.restype = i
+        lib.lstm_set_wavefront_chunks.argtypes = [i] * 6
         lib.lstm_status_string.restype = ctypes.c_char_p
         lib.lstm_status_string.argtypes = [i]
         lib.lstm_last_error.restype = ctypes.c_char_p
@@ -158,6 +160,10 @@ def lstm_auto_path(L, T, B, I, H, backward):
 
 def lstm_set_path(L, T, B, I, H, backward, path):
     return library().lstm_set_path(L, T, B, I, H, int(backward), int(path))
+
+
+def lstm_set_wavefront_chunks(L, T, B, I, H, chunks):
+    return library().lstm_set_wavefront_chunks(L, T, B, I, H, int(chunks))
 
 
 def lstm_forward(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, workspace, workspace_bytes,

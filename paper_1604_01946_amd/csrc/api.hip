@@ -334,6 +334,11 @@ int lstm_set_path(int L, int T, int B, int I, int H, int backward, unsigned path
   return set_path_override(Dims{L, T, B, I, H}, backward != 0, path);
 }
 
+int lstm_set_wavefront_chunks(int L, int T, int B, int I, int H, int chunks) {
+  if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
+  return set_wavefront_chunks(Dims{L, T, B, I, H}, chunks);
+}
+
 int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const float* B, long sBk, long sBn,
                   float* C, long ldc, int accumulate, void* stream) {
   if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C || ldc < N) return LSTM_INVALID_ARG;

@@ -59,6 +59,8 @@ size_t reserve_bytes(const Dims& d);
 WsLayout ws_layout(const Dims& d, bool wide_rows = false);
 unsigned resolve_auto_path(const Dims& d, bool backward);
 int set_path_override(const Dims& d, bool backward, unsigned path);  // LSTM_PATH_AUTO removes the entry
+int set_wavefront_chunks(const Dims& d, int chunks);                 // 0 removes the entry
+int wavefront_chunks(const Dims& d);                                 // 0: no entry (d as the kernels see it)
 void clear_path_overrides();
 // Weight gradients of one layer on a given stream, supplied by the caller of the persistent backward pass for the
 // cells whose gradient products it forms itself; *used is set when the pass has called it for every layer.

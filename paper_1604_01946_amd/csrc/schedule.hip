@@ -64,9 +64,39 @@ int set_path_override(const Dims& d, bool backward, unsigned path) {
   return LSTM_OK;
 }
 
+namespace {
+struct ChunkOverride {
+  Dims d;
+  int chunks;
+};
+std::vector<ChunkOverride> g_chunk_table;
+}  // namespace
+
+int set_wavefront_chunks(const Dims& user, int chunks) {
+  if (chunks < 0) return LSTM_INVALID_ARG;
+  const Dims d = padded_dims(user);  // the shape the paths run at
+  std::lock_guard<std::mutex> lk(g_path_mu);
+  for (size_t i = 0; i < g_chunk_table.size(); ++i)
+    if (same_shape(g_chunk_table[i].d, d)) {
+      if (chunks == 0) g_chunk_table.erase(g_chunk_table.begin() + (long)i);
+      else g_chunk_table[i].chunks = chunks;
+      return LSTM_OK;
+    }
+  if (chunks > 0) g_chunk_table.push_back(ChunkOverride{d, chunks});
+  return LSTM_OK;
+}
+
+int wavefront_chunks(const Dims& d) {
+  std::lock_guard<std::mutex> lk(g_path_mu);
+  for (const ChunkOverride& o : g_chunk_table)
+    if (same_shape(o.d, d)) return o.chunks;
+  return 0;
+}
+
 void clear_path_overrides() {
   std::lock_guard<std::mutex> lk(g_path_mu);
   g_path_table.clear();
+  g_chunk_table.clear();
 }
 
 unsigned resolve_auto_path(const Dims& user, bool backward) {

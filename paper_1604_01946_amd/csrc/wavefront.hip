@@ -58,9 +58,13 @@ hipError_t ensure(Helpers& h, size_t nstreams, size_t nevents) {
 }
 
 inline int chunk_count(const Dims& d) {
-  int n = 2 * d.L;
-  if (n < 4) n = 4;
+  int n = wavefront_chunks(d);  // lstm_set_wavefront_chunks
+  if (n <= 0) {
+    n = 2 * d.L;
+    if (n < 4) n = 4;
+  }
   if (n > d.T) n = d.T;
+  if (n > 64) n = 64;  // two events per (layer, chunk)
   return n;
 }
 

@@ -77,6 +77,16 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_workspace_bytes(2, 5, 3, 8, 100) < padded
 
 
+def test_wavefront_chunks_setting_validates():
+    dims = (2, 8, 4, 32, 640)
+    assert B.lstm_set_wavefront_chunks(0, 8, 4, 32, 640, 2) == B.LSTM_INVALID_ARG
+    assert B.lstm_set_wavefront_chunks(*dims, -1) == B.LSTM_INVALID_ARG
+    assert B.lstm_set_wavefront_chunks(*dims, 3) == B.LSTM_OK
+    assert B.lstm_set_wavefront_chunks(*dims, 1000) == B.LSTM_OK   # clamped when used
+    assert B.lstm_set_wavefront_chunks(*dims, 0) == B.LSTM_OK      # removes the entry
+    assert B.lstm_set_wavefront_chunks(*dims, 0) == B.LSTM_OK
+
+
 def test_status_strings():
     for s in range(0, 6):
         assert B.lstm_status_string(s)

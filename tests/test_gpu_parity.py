@@ -437,6 +437,20 @@ def test_split_T_chaining_on_gpu(nopad, monkeypatch):
     assert float((r2.hT - full.hT).abs().max()) < 1e-5
 
 
+# ------------------------------------------------------------------ chunk length of the stream wavefront
+@pytest.mark.parametrize("chunks", [1, 2, 3, 7, 100])
+def test_wavefront_chunk_counts(chunks):
+    """Section 2.3's s (steps per batched input product) is a per-shape setting of the wavefront path: any count gives
+    the same results."""
+    _, binding, _ = _mods()
+    cfg = Config("chunks", L=3, T=7, B=20, I=48, H=640, state_std=0.3, dstate_std=0.3)
+    try:
+        binding.check(binding.lstm_set_wavefront_chunks(*cfg.dims, chunks))
+        run_case(cfg, 23, binding.LSTM_PATH_WAVEFRONT)
+    finally:
+        binding.lstm_set_wavefront_chunks(*cfg.dims, 0)
+
+
 # ------------------------------------------------------------------ autotuner
 def test_autotune_pins_a_path_and_results_stay_right():
     _, binding, _ = _mods()
@@ -448,7 +462,10 @@ def test_autotune_pins_a_path_and_results_stay_right():
         names = {v: k for k, v in binding.PATH_NAMES.items()}
         assert binding.lstm_auto_path(*cfg.dims, 0) == names[r["best"][0]]
         assert binding.lstm_auto_path(*cfg.dims, 1) == names[r["best"][1]]
+        assert r["best_chunks"] in ("default", 1, 2, 4) and set(r["wavefront_chunks"]) == {"default", 1, 2, 4}
         run_case(cfg, 5, 0)
+        run_case(cfg, 5, binding.LSTM_PATH_WAVEFRONT)   # with the chunk count the tuner pinned
     finally:
         binding.lstm_set_path(*cfg.dims, 0, binding.LSTM_PATH_AUTO)
         binding.lstm_set_path(*cfg.dims, 1, binding.LSTM_PATH_AUTO)
+        binding.lstm_set_wavefront_chunks(*cfg.dims, 0)
