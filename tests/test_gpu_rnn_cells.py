@@ -103,6 +103,13 @@ def test_ragged_hidden_sizes(cell, dims, step_by_step, monkeypatch):
 
 
 @pytest.mark.parametrize("cell", ["tanh", "gru"])
+def test_measured_shape_at_full_size(cell):
+    """The shape the cells are timed at (four layers, H = 512, minibatch 64, 100 steps: the paper's LSTM shape),
+    compared element by element."""
+    run(cell, 4, 100, 64, 512, 512, seed=1)
+
+
+@pytest.mark.parametrize("cell", ["tanh", "gru"])
 def test_cells_without_initial_state(cell):
     run(cell, 2, 4, 5, 16, 48, seed=4, with_h0=False)
 
