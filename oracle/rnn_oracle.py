@@ -28,7 +28,7 @@ otherwise; one numpy matmul per matrix product and time step, no blocking, fusio
 
 Pins (tests/test_rnn_oracle_pins.py): closed forms for W = R = 0, a scalar GRU step expanded by hand, central
 finite differences for every gradient, torch.nn.RNN / torch.nn.GRU in float64 as independent library routines,
-split-T and layer-stack identities.  Nothing here is "parity unpinned".
+split-T and layer-stack identities, one-sided differences at a pre-activation of exactly 0 for the ReLU slope argument.  Nothing here is "parity unpinned".
 """
 import numpy as np
 
@@ -89,8 +89,30 @@ def rnn_forward(cell, L, T, B, I, H, x, h0, W, R, b, dtype=np.float64):
     return hs[L - 1].copy(), hs[:, T - 1].copy(), saved
 
 
-def rnn_backward(cell, L, T, B, I, H, x, h0, W, R, saved, dy, dhT, dtype=np.float64):
-    """Returns dx [T][B][I], dh0 [L][B][H], dW (flat, like W), dR [L][G][H], db [L][G]."""
+def relu_preactivations(L, T, B, I, H, x, h0, W, R, b, saved, dtype=np.float64):
+    """Pre-activations a [L][T][B][H] of a ReLU network, recomputed from the saved hidden states."""
+    x = np.asarray(x, dtype).reshape(T, B, I)
+    R = np.asarray(R, dtype).reshape(L, H, H)
+    b = np.asarray(b, dtype).reshape(L, H)
+    Ws = split_W(np.asarray(W, dtype), "relu", L, I, H)
+    h0 = np.zeros((L, B, H), dtype) if h0 is None else np.asarray(h0, dtype).reshape(L, B, H)
+    hs = saved["h"]
+    a = np.zeros((L, T, B, H), dtype)
+    for l in range(L):
+        for t in range(T):
+            inp = x[t] if l == 0 else hs[l - 1, t]
+            hp = hs[l, t - 1] if t > 0 else h0[l]
+            a[l, t] = inp @ Ws[l].T + hp @ R[l].T + b[l]
+    return a
+
+
+def rnn_backward(cell, L, T, B, I, H, x, h0, W, R, saved, dy, dhT, dtype=np.float64, relu_slope=None):
+    """Returns dx [T][B][I], dh0 [L][B][H], dW (flat, like W), dR [L][G][H], db [L][G].
+
+    relu_slope (ReLU only): [L][T][B][H] values used as the derivative of the activation in place of (h > 0).
+    max(0, a) has no derivative at a = 0: 0 is its slope from the left and 1 from the right, and an evaluation in
+    finite precision cannot tell which side a pre-activation within rounding of 0 is on.  A test that meets such
+    elements passes the slope it wants for them (and (h > 0) everywhere else) to obtain each of the valid results."""
     G = CELLS[cell] * H
     x = np.asarray(x, dtype).reshape(T, B, I)
     R = np.asarray(R, dtype).reshape(L, G, H)
@@ -122,7 +144,10 @@ def rnn_backward(cell, L, T, B, I, H, x, h0, W, R, saved, dy, dhT, dtype=np.floa
                 direct = dh * z
             else:
                 h = hs[l, t]
-                da = dh * ((1.0 - h * h) if cell == "tanh" else (h > 0).astype(dtype))
+                if cell == "tanh":
+                    da = dh * (1.0 - h * h)
+                else:
+                    da = dh * ((h > 0).astype(dtype) if relu_slope is None else np.asarray(relu_slope, dtype)[l, t])
                 dq = da
                 direct = 0.0
             din[t] = da @ Ws[l]

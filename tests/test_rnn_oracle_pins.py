@@ -154,3 +154,53 @@ def test_zero_padded_hidden_units_change_nothing(cell):
     assert np.allclose(dRb[:, :, :H, :H].reshape(L, ng * H, H), g[3], atol=1e-13) and not dRb[:, :, H:, :].any() and not dRb[:, :, :, H:].any()
     dbb = db.reshape(L, ng, Hp)
     assert np.allclose(dbb[:, :, :H].reshape(L, ng * H), g[4], atol=1e-13) and not dbb[:, :, H:].any()
+
+
+def test_relu_slope_argument_reproduces_default_and_one_sided_derivatives():
+    """The optional ReLU slope of rnn_backward: (1) given the network's own decisions (h > 0) it changes nothing;
+    (2) at a pre-activation of exactly 0 the two admissible slopes are the one-sided derivatives of the loss: a
+    two-layer, two-step network whose unit (layer 0, step 0, row 0, unit 1) sits exactly on the kink (zero input row,
+    zero initial state, zero bias), differentiated with respect to that bias from the right and from the left."""
+    L, T, B, I, H = 2, 2, 2, 3, 3
+    d = rand_case("relu", L, T, B, I, H, 21)
+    d["b"] += 0.2
+    y, hT, saved = O.rnn_forward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    ref = O.rnn_backward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"])
+    same = O.rnn_backward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"],
+                          relu_slope=(saved["h"] > 0).astype(np.float64))
+    for a, b in zip(ref, same):
+        assert np.array_equal(a, b)
+
+    d["x"][0, 0, :] = 0.0
+    d["h0"][0, 0, :] = 0.0
+    d["b"][0, 1] = 0.0
+    # every other pre-activation must be well away from 0 so that the finite step crosses no second kink
+    y, hT, saved = O.rnn_forward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    a = O.relu_preactivations(L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"], saved)
+    assert a[0, 0, 0, 1] == 0.0
+    others = np.abs(a).reshape(-1)
+    assert np.sort(others)[1] > 1e-3
+    eps = 1e-7
+
+    def loss_at(delta):
+        bb = d["b"].copy()
+        bb[0, 1] += delta
+        yy, hh, _ = O.rnn_forward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], bb)
+        return O.loss(yy, hh, d["dy"], d["dhT"])
+
+    right = (loss_at(eps) - loss_at(0.0)) / eps
+    left = (loss_at(0.0) - loss_at(-eps)) / eps
+    assert abs(right - left) > 1e-3  # the kink really is one for this loss
+    for slope, want in ((1.0, right), (0.0, left)):
+        m = (saved["h"] > 0).astype(np.float64)
+        m[0, 0, 0, 1] = slope
+        db = O.rnn_backward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], saved, d["dy"], d["dhT"], relu_slope=m)[4]
+        assert abs(db[0, 1] - want) < 1e-6 * max(1.0, abs(want)), (slope, db[0, 1], want)
+
+
+def test_relu_preactivations_reproduce_hidden_states():
+    L, T, B, I, H = 3, 4, 2, 5, 4
+    d = rand_case("relu", L, T, B, I, H, 5)
+    y, hT, saved = O.rnn_forward("relu", L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"])
+    a = O.relu_preactivations(L, T, B, I, H, d["x"], d["h0"], d["W"], d["R"], d["b"], saved)
+    assert np.allclose(np.maximum(a, 0.0), saved["h"], rtol=0, atol=1e-13)
