@@ -22,11 +22,21 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3   # 256 CU x 256 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch of the dominant kernels at cfg3, from two rocprofv3 --pmc passes (FETCH_SIZE x 2.0,
-# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/cfg3_hbm_traffic_pmc.md
-PMC_TRAFFIC_BYTES = {("cfg3", "bwd_recurrence"): int((572.1 + 451.9) * 2**20),
-                     ("cfg3", "fwd_recurrence"): int((237.0 + 364.3) * 2**20),
-                     ("cfg3", "weight_grad"): int((497.7 + 32.0 + 19.2 + 16.0) * 2**20)}
+
+
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter passes whose summary is kept under profiles/
+    (written by `python -m paper_1604_01946_amd.profile_summary traffic`), or None when no such file names this
+    workload and this kernel: a figure recorded for other kernels is never reported."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic_pmc.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    k = rec.get("kernels", {}).get(kernel)
+    if rec.get("workload") != workload or not k:
+        return None
+    return int(k["read_bytes"]) + int(k["write_bytes"])
 
 
 def parse():
@@ -42,25 +52,6 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference point for rocprofv3 byte counters)")
     return ap.parse_args()
-
-
-def phase_flops(cfg, phase, persistent, ran=()):
-    """Algorithmic FLOPs of one call's worth of each GEMM-type phase; `ran` = the phases that were recorded."""
-    L, T, B, I, H = cfg.dims
-    G = 4 * H
-    inp = sum(2 * G * (I if l == 0 else H) * B * T for l in range(L))
-    rec = sum(2 * G * H * B * T for l in range(L))
-    if persistent:
-        # the persistent kernels fold the input products of layers >= 1 into the recurrence, and layer 0's too
-        # when I == H (then no separate input GEMM phase is recorded)
-        inp0 = 2 * G * I * B * T
-        table = {"fwd_input_gemm": inp0, "fwd_recurrence": rec + inp - (inp0 if "fwd_input_gemm" in ran else 0),
-                 "bwd_recurrence": rec + inp - (inp0 if "bwd_input_gemm" in ran else 0), "bwd_input_gemm": inp0,
-                 "weight_grad": inp + rec}
-    else:
-        table = {"fwd_input_gemm": inp, "fwd_recurrence": rec, "bwd_recurrence": rec, "bwd_input_gemm": inp,
-                 "weight_grad": inp + rec}
-    return table.get(phase)
 
 
 def phase_bytes(cfg, phase):
@@ -140,10 +131,10 @@ def main():
         per_iter.append(ev[0].elapsed_time(ev[2]))
         st, ph = B_.lstm_profile_read()
         B_.check(st, "lstm_profile_read")
-        for k, (m, c) in ph.items():
-            a = phases.setdefault(k, [0.0, 0])
+        for k, (m, c, fl, kern) in ph.items():
+            a = phases.setdefault(k, [0.0, 0, 0.0, ""])
             a[0] += m / nprof
-            a[1] = c
+            a[1], a[2], a[3] = c, fl, kern   # FLOPs as the library counts them for the products the phase really carried
     B_.lstm_profile_enable(0)
 
     passes = 3 if do_bwd else 1
@@ -151,7 +142,6 @@ def main():
     tflops = passes * flop1 / (ms * 1e-3) / 1e12
     tflops_2pass = (2 if do_bwd else 1) * flop1 / (ms * 1e-3) / 1e12
 
-    ran = {k for k, (m, c) in phases.items() if c > 0}
     # roofline of the phase that takes the most time
     dom = max(phases.items(), key=lambda kv: kv[1][0])[0] if phases else None
     if dom and phases[dom][0] <= 0.0:
@@ -160,30 +150,40 @@ def main():
                 "frac": round(tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None, "kernel_phase": "whole_step",
                 "launch_intervals": 0, "avg_ms": round(ms, 4)}
     if dom:
-        dom_ms, dom_n = phases[dom]
-        persistent = (path_b if dom.startswith("bwd") or dom == "weight_grad" else path_f) == B_.LSTM_PATH_PERSISTENT
-        fl = phase_flops(cfg, dom, persistent, ran)
-        if fl is not None:
+        dom_ms, dom_n, fl, kern = phases[dom]
+        traffic = recorded_traffic(cfg.name, kern) if flags == 0 else None
+        # dependent steps of the recurrence: the layers of one persistent launch advance as a wavefront (T + L - 1
+        # steps in a row), every other recurrence runs its L*T cells one after the other
+        wave = kern.startswith("pers_") and "L_kernel" not in kern
+        dep_steps = (T + L - 1) if wave else L * T
+        mfma_us_per_step = fl / (PEAK_FP32_MFMA_TFLOPS * 1e12) * 1e6 / dep_steps if fl else 0.0
+        if fl and not (dom.endswith("recurrence") and mfma_us_per_step < 0.5):
             ach = fl / (dom_ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(ach / PEAK_FP32_MFMA_TFLOPS, 4),
-                        "traffic": PMC_TRAFFIC_BYTES.get((cfg.name, dom)) if flags == 0 else None,
-                        "kernel_phase": dom, "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
+                        "frac": round(ach / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": traffic, "kernel_phase": dom, "kernel": kern,
+                        "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
+        elif fl:
+            # a chain of dependent steps whose matrix work takes well under a microsecond each: bound by the hop from
+            # step to step, neither by the matrix cores nor by memory bandwidth -- reported as time per dependent step
+            us = dom_ms * 1e3 / dep_steps
+            roofline = {"bound": "latency", "achieved": round(us, 3), "peak": None, "unit": "us/step", "frac": None,
+                        "traffic": traffic, "kernel_phase": dom, "kernel": kern, "dependent_steps": dep_steps,
+                        "hbm_gbs": round(traffic / (dom_ms * 1e-3) / 1e9, 1) if traffic else None,
+                        "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
         else:
             by = phase_bytes(cfg, dom)
-            ach = by / (dom_ms * 1e-3) / 1e9
-            roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None, "kernel_phase": dom,
-                        "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
+            if by:
+                ach = by / (dom_ms * 1e-3) / 1e9
+                roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None, "kernel_phase": dom,
+                            "launch_intervals": dom_n, "avg_ms": round(dom_ms, 4)}
     phase_report = {}
-    for k, (m, c) in phases.items():
+    for k, (m, c, fl, kern) in phases.items():
         if c == 0:
             continue
-        persistent = (path_b if k.startswith("bwd") or k == "weight_grad" else path_f) == B_.LSTM_PATH_PERSISTENT
-        fl = phase_flops(cfg, k, persistent, ran)
         phase_report[k] = {"ms": round(m, 4), "intervals": c}
         if fl:
-            phase_report[k]["tflops"] = round(fl / (m * 1e-3) / 1e12, 2)
+            phase_report[k].update(kernel=kern, gflop=round(fl / 1e9, 2), tflops=round(fl / (m * 1e-3) / 1e12, 2))
 
     # in-repo unfused baseline: one kernel per operation, per-gate GEMMs (Section 2.1 starting point)
     naive = None
@@ -245,7 +245,10 @@ def main():
         "unfused_baseline": naive,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    del r
+    torch.cuda.synchronize()
+    B_.lstm_shutdown()   # helper streams, events and the mapped watchdog page are released before the process ends
 
 
 if __name__ == "__main__":

@@ -28,14 +28,31 @@
  *   - calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream); internal helper streams fork from it and join back to it, and
  *     no call synchronises the host;
- *   - calls on different streams may overlap when each has its own `reserve` and
- *     `workspace` (results do not depend on what else runs on the device; the
- *     persistent kernels of one process run one after the other, chained through an
- *     event, because each needs all its workgroups resident at once); two calls must
- *     never share a workspace or a reserve while either is in flight;
+ *   - calls on different streams, also from different host threads, may overlap when
+ *     each has its own `reserve` and `workspace`; two calls must never share a
+ *     workspace or a reserve while either is in flight.  The library's own helper
+ *     streams and events are shared by the process: calls that use them take turns
+ *     while they enqueue (a mutex), their GPU work overlaps as the streams allow;
+ *   - the persistent kernels (Section 4's idea: weights on chip, workgroups that wait
+ *     on each other) need all their workgroups resident at once.  Those of one process
+ *     are chained through an event and never share the device, so their results do not
+ *     depend on the process's other work.  Nothing orders them against OTHER processes
+ *     or against long kernels of the caller that hold compute units for longer than
+ *     the kernels' bounded waits (about a second): LSTM_COOP_LAUNCH=1 in the
+ *     environment selects cooperative launches, which give the device-wide guarantee
+ *     at a small cost per launch;
+ *   - a persistent kernel whose bounded wait expires stops waiting, finishes and raises
+ *     a host-visible word.  The call that launched it has returned LSTM_OK long before
+ *     and ITS OUTPUTS ARE INVALID; the next lstm_* / rnn_* forward or backward call on
+ *     any path returns LSTM_INTERNAL without launching anything and clears the word,
+ *     the call after that runs normally (lstm_shutdown clears it too).  A caller that
+ *     needs certainty about one call synchronises its stream and makes a second call;
  *   - return value: LSTM_OK or an LSTM_* error code.  Arguments are validated before
- *     any GPU work; on error nothing has been launched except for LSTM_HIP_ERROR /
- *     LSTM_INTERNAL, which can surface after partial execution.
+ *     any GPU work; on error nothing has been launched except for LSTM_HIP_ERROR,
+ *     which can surface after partial execution;
+ *   - diagnostic settings come from environment variables (LSTM_NO_PAD, LSTM_COOP_LAUNCH,
+ *     ...); they are read once, at the first call that needs one, and again after
+ *     lstm_shutdown(), never in between.
  */
 #ifndef LSTM_MI355X_H
 #define LSTM_MI355X_H
@@ -51,7 +68,7 @@ extern "C" {
 #define LSTM_INVALID_ARG       1 /* non-positive dimension, required pointer NULL, misaligned pointer, bad flags */
 #define LSTM_BUFFER_TOO_SMALL  2 /* workspace_bytes below lstm_workspace_bytes() */
 #define LSTM_HIP_ERROR         3 /* a HIP runtime call or kernel launch failed */
-#define LSTM_INTERNAL          4 /* a kernel's bounded wait expired (persistent path watchdog) */
+#define LSTM_INTERNAL          4 /* a bounded wait of a persistent kernel of an EARLIER call expired; reported once */
 #define LSTM_UNSUPPORTED       5 /* the forced path cannot run this shape on this device */
 
 /* ---- flags: bits 0..3 select the execution path ---------------------------------------
@@ -81,8 +98,10 @@ extern "C" {
  * sizes, and the padded run is faster than the per-step paths at the given size (three to
  * five times with four layers).  Reserve and workspace sizes are those of the padded network, and
  * the copies are part of the weight re-layout that Section 2.3 redoes every pass.  LSTM_NO_PAD=1 in the
- * environment (read at every call: set it the same for size queries, forward and backward) runs
- * every shape as given. */
+ * environment runs every shape as given; both size queries return the larger of the padded and the
+ * as-given requirement, so a buffer sized under one setting is never too small under the other (the
+ * reserve's layout still differs: forward and backward of one reserve must run under one setting, which
+ * holds by itself because settings are only read again after lstm_shutdown). */
 size_t lstm_reserve_bytes(int L, int T, int B, int I, int H);
 
 /* Bytes of scratch that lstm_forward / lstm_backward need (the maximum over both and
@@ -174,8 +193,12 @@ int lstm_set_wavefront_chunks(int L, int T, int B, int I, int H, int chunks);
  * same breakdown taken live).  While enabled, lstm_forward / lstm_backward record HIP events
  * on the stream each phase is launched on, at the phase's first and last launch.
  * lstm_profile_read waits for the recorded events, adds the elapsed milliseconds of every
- * recorded interval to ms[phase] and the interval count to count[phase] (both arrays of
- * LSTM_PHASE_COUNT entries, host memory, overwritten), and forgets the events.
+ * recorded interval to ms[phase], the interval count to count[phase] and, when `flops` is not
+ * NULL, the algorithmic FLOPs (2*M*N*K of every matrix product launched inside the interval,
+ * whichever kernel carried it: a product folded into a persistent kernel counts in that
+ * kernel's phase) to flops[phase] (arrays of LSTM_PHASE_COUNT entries, host memory,
+ * overwritten), and forgets the events.  lstm_profile_kernel names the kernel that carried the
+ * matrix products of a phase in the most recent profiled call ("" if none; static storage).
  * Returns LSTM_OK or LSTM_HIP_ERROR.  Not thread-safe; intended for benchmarks.
  */
 #define LSTM_PHASE_FWD_PACK        0 /* weight re-layout / exchange set-up, forward */
@@ -188,7 +211,8 @@ int lstm_set_wavefront_chunks(int L, int T, int B, int I, int H, int chunks);
 #define LSTM_PHASE_BIAS_GRAD       7 /* db reductions */
 #define LSTM_PHASE_COUNT           8
 void lstm_profile_enable(int on);
-int lstm_profile_read(float* ms, int* count);
+int lstm_profile_read(float* ms, int* count, double* flops);
+const char* lstm_profile_kernel(int phase);
 const char* lstm_phase_name(int phase);
 
 /*
@@ -205,8 +229,9 @@ const char* lstm_status_string(int status);
 /* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
 const char* lstm_last_error(void);
 
-/* Destroys the helper streams and events the library created.  Safe to call repeatedly;
- * the next call re-creates them. */
+/* Destroys the helper streams and events the library created, empties the per-shape tables, clears a
+ * pending watchdog report and forgets the settings read from the environment.  Safe to call
+ * repeatedly (not while a call is in flight); the next call re-creates what it needs. */
 void lstm_shutdown(void);
 
 #ifdef __cplusplus

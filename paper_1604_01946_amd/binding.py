@@ -31,7 +31,7 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
     "lstm_auto_path", "lstm_set_path", "lstm_set_wavefront_chunks", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
-    "lstm_profile_enable", "lstm_profile_read", "lstm_phase_name", "lstm_debug_set_trace",
+    "lstm_profile_enable", "lstm_profile_read", "lstm_profile_kernel", "lstm_phase_name", "lstm_debug_set_trace",
 ]
 RNN_EXPORTS = ["rnn_reserve_bytes", "rnn_workspace_bytes", "rnn_forward", "rnn_backward"]
 RNN_CELL_RELU, RNN_CELL_TANH, RNN_CELL_GRU = 0, 1, 2
@@ -79,7 +79,10 @@ def library():
         lib.lstm_profile_enable.restype = None
         lib.lstm_profile_enable.argtypes = [i]
         lib.lstm_profile_read.restype = i
-        lib.lstm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        lib.lstm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int),
+                                          ctypes.POINTER(ctypes.c_double)]
+        lib.lstm_profile_kernel.restype = ctypes.c_char_p
+        lib.lstm_profile_kernel.argtypes = [i]
         lib.lstm_phase_name.restype = ctypes.c_char_p
         lib.lstm_phase_name.argtypes = [i]
         lib.lstm_debug_set_trace.restype = None
@@ -195,11 +198,13 @@ def lstm_phase_name(phase):
 
 
 def lstm_profile_read():
-    """Returns (status, {phase name: (milliseconds, intervals)})."""
+    """Returns (status, {phase name: (milliseconds, intervals, algorithmic FLOPs, kernel name)})."""
     ms = (ctypes.c_float * LSTM_PHASE_COUNT)()
     cnt = (ctypes.c_int * LSTM_PHASE_COUNT)()
-    st = library().lstm_profile_read(ms, cnt)
-    return st, {lstm_phase_name(k): (float(ms[k]), int(cnt[k])) for k in range(LSTM_PHASE_COUNT)}
+    fl = (ctypes.c_double * LSTM_PHASE_COUNT)()
+    st = library().lstm_profile_read(ms, cnt, fl)
+    return st, {lstm_phase_name(k): (float(ms[k]), int(cnt[k]), float(fl[k]), library().lstm_profile_kernel(k).decode())
+                for k in range(LSTM_PHASE_COUNT)}
 
 
 def lstm_debug_set_trace(device_buf, nbytes, block):

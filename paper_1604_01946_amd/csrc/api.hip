@@ -3,7 +3,9 @@
 #include "../../include/lstm.h"
 #include "internal.h"
 #include "schedule.h"
+#include "knobs.h"
 #include <algorithm>
+#include <mutex>
 
 #include <stdlib.h>
 #include <string.h>
@@ -25,18 +27,80 @@ hipError_t record(hipError_t e, const char* what) {
 }
 
 namespace {
+std::mutex g_knob_mu;
+Knobs g_knobs;
+bool g_knobs_read = false;
+
+bool env_is(const char* name, char c) {
+  const char* e = getenv(name);
+  return e && *e == c;
+}
+int env_int(const char* name, long lo, long hi, int unset) {
+  const char* e = getenv(name);
+  if (!e || !*e) return unset;
+  const long v = atol(e);
+  return (v >= lo && v <= hi) ? (int)v : unset;
+}
+}  // namespace
+
+const Knobs& knobs() {
+  std::lock_guard<std::mutex> lk(g_knob_mu);
+  if (!g_knobs_read) {
+    Knobs k;
+    k.no_pad = env_is("LSTM_NO_PAD", '1');
+    k.gemm_staged = env_is("LSTM_GEMM_STAGED", '1');
+    k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
+    const char* ff = getenv("LSTM_FULL_FENCES");
+    k.full_fences = ff && *ff && *ff != '0';
+    k.coop_launch = env_is("LSTM_COOP_LAUNCH", '1');
+    k.plain_launch = env_is("LSTM_PLAIN_LAUNCH", '1');
+    k.two_chains = env_is("LSTM_CHAINS", '2');
+    k.fwd_narrow = env_int("LSTM_FWD_NARROW", 0, 1, -1);
+    k.bwd_narrow = env_int("LSTM_BWD_NARROW", 0, 1, -1);
+    k.no_large_persistent = env_is("LSTM_NO_LARGE_PERSISTENT", '1');
+    k.no_wgrad_overlap = env_is("LSTM_NO_WGRAD_OVERLAP", '1');
+    k.fwd_batched_input = env_is("LSTM_FWD_BATCHED_INPUT", '1');
+    k.rnn_no_persistent = env_is("RNN_NO_PERSISTENT", '1');
+    k.step_mt = env_int("LSTM_STEP_MT", 1, 4, 0);
+    k.splitk_min_h = env_int("LSTM_SPLITK_MIN_H", 1, 1 << 20, 0);
+    k.pingpong = env_int("LSTM_PINGPONG", 0, 1, -1);
+    g_knobs = k;
+    g_knobs_read = true;
+  }
+  return g_knobs;
+}
+
+void reset_knobs() {
+  std::lock_guard<std::mutex> lk(g_knob_mu);
+  g_knobs_read = false;
+}
+
+namespace {
 struct ProfInterval {
   int phase;
   hipEvent_t start, stop;
   bool open;
+  double flops;  // algorithmic FLOPs of the matrix products launched inside the interval
 };
 bool g_prof_on = false;
 std::vector<ProfInterval> g_prof;
+const char* g_prof_kernel[LSTM_PHASE_COUNT] = {};
 }  // namespace
+
+void prof_flops(double flops, const char* kernel) {
+  if (!g_prof_on) return;
+  for (size_t i = g_prof.size(); i-- > 0;) {
+    if (g_prof[i].open) {
+      g_prof[i].flops += flops;
+      if (kernel && g_prof[i].phase >= 0 && g_prof[i].phase < LSTM_PHASE_COUNT) g_prof_kernel[g_prof[i].phase] = kernel;
+      return;
+    }
+  }
+}
 
 void prof_begin(int phase, hipStream_t s) {
   if (!g_prof_on) return;
-  ProfInterval iv{phase, nullptr, nullptr, true};
+  ProfInterval iv{phase, nullptr, nullptr, true, 0.0};
   if (hipEventCreate(&iv.start) != hipSuccess || hipEventCreate(&iv.stop) != hipSuccess) return;
   (void)hipEventRecord(iv.start, s);
   g_prof.push_back(iv);
@@ -129,9 +193,9 @@ hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int c
   return hipGetLastError();
 }
 
-int padded_hidden(const Dims& d) {
-  const char* e = getenv("LSTM_NO_PAD");
-  if (e && *e == '1') return d.H;
+int padded_hidden(const Dims& d) { return knobs().no_pad ? d.H : padded_hidden_rule(d); }
+
+int padded_hidden_rule(const Dims& d) {
   // 704 <= H < 1024 with up to 128 rows: the one-layer persistent kernels of H = 1024 are 5-40 % faster than the step
   // kernels at the given size (with more rows, or sizes nearer 512, the extra arithmetic costs more than it saves)
   if (d.H >= 704 && d.H < 1024 && d.B <= 128) return 1024;
@@ -194,7 +258,7 @@ int pad_parameters(const Dims& d, int Hp, const float* W, const float* R, const 
 
 int forward_padded(const Dims& d, const Dims& p, const float* x, const float* h0, const float* c0, const float* W,
                    const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, char* ws,
-                   hipStream_t s, unsigned flags) {
+                   hipStream_t s, unsigned flags, bool no_new_resources) {
   const PadLayout q = pad_layout(d, p);
   auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
   const long LB = (long)d.L * d.B, TB = (long)d.T * d.B;
@@ -211,6 +275,7 @@ int forward_padded(const Dims& d, const Dims& p, const float* x, const float* h0
   a.inference = reserve == nullptr;
   unsigned path = flags & LSTM_PATH_MASK;
   if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, false);
+  if (no_new_resources && path == LSTM_PATH_WAVEFRONT) path = LSTM_PATH_STEP;
   const int st = run_forward(a, path);
   if (st != LSTM_OK) return st;
   ProfScope ps(LSTM_PHASE_FWD_PACK, s);
@@ -257,17 +322,27 @@ int backward_padded(const Dims& d, const Dims& p, const float* x, const float* h
 
 }  // namespace
 
+namespace {
+int forward_call(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
+                 const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
+                 size_t workspace_bytes, void* stream, unsigned flags, bool no_new_resources);
+}  // namespace
+
 extern "C" {
 
+// Both size queries answer for the padded and for the as-given run, whichever needs more, so that the answer does
+// not depend on LSTM_NO_PAD: a buffer sized under one setting is large enough under the other.
 size_t lstm_reserve_bytes(int L, int T, int B, int I, int H) {
   if (!dims_ok(L, T, B, I, H)) return 0;
-  return reserve_bytes(padded_dims(Dims{L, T, B, I, H}));
+  const Dims d{L, T, B, I, H};
+  return reserve_bytes(Dims{L, T, B, I, padded_hidden_rule(d)});  // never below the as-given size: padding only grows H
 }
 
 size_t lstm_workspace_bytes(int L, int T, int B, int I, int H) {
   if (!dims_ok(L, T, B, I, H)) return 0;
-  const Dims d{L, T, B, I, H}, p = padded_dims(d);
-  return p.H == d.H ? ws_layout(d).total : pad_layout(d, p).total;
+  const Dims d{L, T, B, I, H}, p{L, T, B, I, padded_hidden_rule(d)};
+  const size_t given = ws_layout(d).total;
+  return p.H == d.H ? given : std::max(given, pad_layout(d, p).total);
 }
 
 const char* lstm_status_string(int status) {
@@ -287,17 +362,23 @@ const char* lstm_last_error(void) { return g_last_error.c_str(); }
 void lstm_shutdown(void) {
   release_helpers();
   clear_path_overrides();
+  reset_knobs();
 }
 
 void lstm_debug_set_trace(void* device_buf, size_t bytes, int block) { set_trace(device_buf, bytes, block); }
 
 void lstm_profile_enable(int on) { g_prof_on = on != 0; }
 
-int lstm_profile_read(float* ms, int* count) {
+const char* lstm_profile_kernel(int phase) {
+  return (phase >= 0 && phase < LSTM_PHASE_COUNT && g_prof_kernel[phase]) ? g_prof_kernel[phase] : "";
+}
+
+int lstm_profile_read(float* ms, int* count, double* flops) {
   if (!ms || !count) return LSTM_INVALID_ARG;
   for (int i = 0; i < LSTM_PHASE_COUNT; ++i) {
     ms[i] = 0.f;
     count[i] = 0;
+    if (flops) flops[i] = 0.0;
   }
   int status = LSTM_OK;
   for (auto& iv : g_prof) {
@@ -306,6 +387,7 @@ int lstm_profile_read(float* ms, int* count) {
       if (iv.phase >= 0 && iv.phase < LSTM_PHASE_COUNT) {
         ms[iv.phase] += t;
         count[iv.phase] += 1;
+        if (flops) flops[iv.phase] += iv.flops;
       }
     } else {
       (void)hipGetLastError();
@@ -351,6 +433,17 @@ int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const
 int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
                  const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
                  size_t workspace_bytes, void* stream, unsigned flags) {
+  return forward_call(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, workspace, workspace_bytes, stream, flags, false);
+}
+
+}  // extern "C"
+
+namespace {
+// no_new_resources: the caller may create nothing; the stream wavefront, whose helper streams
+// and events are created to the size of the shape, is then replaced by the step path.
+int forward_call(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
+                 const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
+                 size_t workspace_bytes, void* stream, unsigned flags, bool no_new_resources) {
   g_last_error.clear();
   if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
   if (!x || !W || !R || !b || !y || !workspace) return LSTM_INVALID_ARG;
@@ -359,20 +452,25 @@ int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float*
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H}, p = padded_dims(d);
+  if (workspace_bytes < lstm_workspace_bytes(L, T, B, I, H)) return LSTM_BUFFER_TOO_SMALL;
+  if (take_watchdog()) return LSTM_INTERNAL;  // an earlier call's persistent kernel gave up waiting: reported once, here
   if (p.H != d.H) {
-    if (workspace_bytes < pad_layout(d, p).total) return LSTM_BUFFER_TOO_SMALL;
-    return forward_padded(d, p, x, h0, c0, W, R, b, y, hT, cT, reserve, (char*)workspace, (hipStream_t)stream, flags);
+    return forward_padded(d, p, x, h0, c0, W, R, b, y, hT, cT, reserve, (char*)workspace, (hipStream_t)stream, flags,
+                          no_new_resources);
   }
   const WsLayout w = ws_layout(d);
-  if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
 
   FwdArgs a{d, x, h0, c0, W, R, b, y, hT, cT,
             reserve ? (float*)reserve : (float*)((char*)workspace + w.resv), (char*)workspace, w, (hipStream_t)stream};
   a.inference = reserve == nullptr;
   unsigned path = flags & LSTM_PATH_MASK;
   if (path == LSTM_PATH_AUTO) path = resolve_auto_path(d, false);
+  if (no_new_resources && path == LSTM_PATH_WAVEFRONT) path = LSTM_PATH_STEP;
   return run_forward(a, path);
 }
+}  // namespace
+
+extern "C" {
 
 int lstm_backward(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0,
                   const float* W, const float* R, const void* reserve, const float* dy, const float* dhT,
@@ -386,13 +484,13 @@ int lstm_backward(int L, int T, int B, int I, int H, const float* x, const float
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   if ((flags & ~LSTM_PATH_MASK) != 0 || (flags & LSTM_PATH_MASK) > LSTM_PATH_PERSISTENT) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H}, p = padded_dims(d);
+  if (workspace_bytes < lstm_workspace_bytes(L, T, B, I, H)) return LSTM_BUFFER_TOO_SMALL;
+  if (take_watchdog()) return LSTM_INTERNAL;  // an earlier call's persistent kernel gave up waiting: reported once, here
   if (p.H != d.H) {
-    if (workspace_bytes < pad_layout(d, p).total) return LSTM_BUFFER_TOO_SMALL;
     return backward_padded(d, p, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db, (char*)workspace,
                            (hipStream_t)stream, flags);
   }
   const WsLayout w = ws_layout(d);
-  if (workspace_bytes < w.total) return LSTM_BUFFER_TOO_SMALL;
 
   BwdArgs a{d, x, h0, c0, W, R, (const float*)reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db,
             (char*)workspace, w, (hipStream_t)stream};

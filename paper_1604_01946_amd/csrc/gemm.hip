@@ -12,6 +12,7 @@
 // unit stride along K or along the row dimension; unaligned / odd shapes take a scalar
 // guarded loader, so every positive shape works.
 #include "internal.h"
+#include "knobs.h"
 
 #include <stdlib.h>
 #include <type_traits>
@@ -487,10 +488,7 @@ void launch_tile(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s
 }  // namespace
 
 // LSTM_GEMM_STAGED=1 keeps every product on the register-staged kernel (for comparison and tests).
-static bool gemm_force_staged() {
-  const char* e = getenv("LSTM_GEMM_STAGED");
-  return e && *e == '1';
-}
+static bool gemm_force_staged() { return knobs().gemm_staged; }
 
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream) {
   if (nprob <= 0) return hipSuccess;
@@ -512,6 +510,11 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   }
   if (ma == LM_SCALAR || mb == LM_SCALAR) ma = mb = LM_SCALAR;
   bool dl = ma != LM_SCALAR && !gemm_force_staged();
+  {
+    double fl = 0.0;
+    for (int i = 0; i < nprob; ++i) fl += 2.0 * probs[i].M * probs[i].N * probs[i].K;
+    prof_flops(fl, "gemm");
+  }
   for (int i = 0; i < nprob && dl; ++i)
     dl = probs[i].K % KT == 0 && probs[i].K >= KT && dl_operand_ok(ma, probs[i].sAm, probs[i].sAk, probs[i].M, probs[i].K) &&
          dl_operand_ok(mb, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);

@@ -113,6 +113,11 @@ size_t splitk_counter_ints(int H, int B);
 hipError_t launch_pack_bwd_sk(const float* R, float* RTp, int L, int H, int B, size_t per_layer_floats, hipStream_t s);
 hipError_t launch_step_bwd_sk(const StepBwdArgs& a, float* partial, int* counters, hipStream_t s);
 
+// ---------------------------------------------------------------- measurement hook (api.hip)
+// Adds the algorithmic FLOPs of a matrix product that is being launched to the innermost open timing interval
+// and, when `kernel` is given, names the kernel that carries that phase (no-ops unless lstm_profile_enable(1)).
+void prof_flops(double flops, const char* kernel = nullptr);
+
 // ---------------------------------------------------------------- device math
 // sigma and tanh on the hardware's exp2 and reciprocal instructions (about 1 ulp each): absolute error of
 // a few 1e-7 over the whole range, exact limits at +-infinity (exp2 overflows to inf, 1/inf = 0).  The

@@ -32,7 +32,9 @@
 // for stacks deeper than the chip holds, batch slices.
 #include "../../include/lstm.h"
 #include "schedule.h"
+#include "knobs.h"
 
+#include <algorithm>
 #include <mutex>
 #include <stdlib.h>
 
@@ -2013,23 +2015,13 @@ bool ensure_watchdog() {
   return true;
 }
 
-int spin_limit() {
-  const char* e = getenv("LSTM_SPIN_LIMIT");
-  if (e && *e) {
-    const long v = atol(e);
-    if (v > 0 && v < (1L << 30)) return (int)v;
-  }
-  return 1 << 21;
-}
+int spin_limit() { return knobs().spin_limit; }
 
 long long* g_trace_buf = nullptr;
 size_t g_trace_bytes = 0;
 int g_trace_block = 0;
 
-int full_fences() {
-  const char* e = getenv("LSTM_FULL_FENCES");
-  return (e && *e && *e != '0') ? 1 : 0;
-}
+int full_fences() { return knobs().full_fences ? 1 : 0; }
 
 // All workgroups of a persistent kernel must be resident at once (they wait on each other).  The grid never exceeds
 // the number of CUs and every workgroup fits a CU on its own, so an ordinary launch is resident as soon as the CUs it
@@ -2043,10 +2035,12 @@ int full_fences() {
 // every mode, turned into LSTM_INTERNAL by the watchdog.
 std::mutex g_launch_mu;
 hipEvent_t g_last_launch[16] = {};  // per device: completion of the most recent persistent launch
+bool g_last_launch_recorded[16] = {};
 
 // Side stream (default priority) and two events for work that overlaps a persistent launch which leaves CUs idle.
 hipStream_t g_side_stream = nullptr;
 hipEvent_t g_side_ev[2] = {};
+std::mutex g_side_mu;  // held by the call that is using them
 bool ensure_side_stream() {
   std::lock_guard<std::mutex> lk(g_launch_mu);
   if (g_side_stream) return true;
@@ -2063,27 +2057,37 @@ bool ensure_side_stream() {
   return true;
 }
 
+// Raises a kernel's dynamic LDS limit once per process (`done` is the caller's flag for that kernel); callers on
+// several host threads are serialised.
+hipError_t allow_dynamic_lds(const void* fn, size_t smem, bool& done) {
+  std::lock_guard<std::mutex> lk(g_launch_mu);
+  if (done) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
 hipError_t launch_resident(const void* fn, int grid, void** params, unsigned smem, hipStream_t s) {
-  const char* c = getenv("LSTM_COOP_LAUNCH");
-  if (c && *c == '1') return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
-  const char* e = getenv("LSTM_PLAIN_LAUNCH");
+  if (knobs().coop_launch) return hipLaunchCooperativeKernel(fn, dim3(grid), dim3(256), params, smem, s);
   int dev = 0;
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-  if ((e && *e == '1') || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16 ||
+  if (knobs().plain_launch || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16 ||
       hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
     (void)hipGetLastError();
     return hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);  // (a stream under capture is ordered by its graph)
   }
   std::lock_guard<std::mutex> lk(g_launch_mu);
   hipError_t st = hipSuccess;
-  if (g_last_launch[dev]) {
-    st = hipStreamWaitEvent(s, g_last_launch[dev], 0);
-  } else {
+  if (!g_last_launch[dev]) {
     st = hipEventCreateWithFlags(&g_last_launch[dev], hipEventDisableTiming);
+    g_last_launch_recorded[dev] = false;
+  } else if (g_last_launch_recorded[dev]) {
+    st = hipStreamWaitEvent(s, g_last_launch[dev], 0);
   }
   if (st != hipSuccess) return st;
   st = hipLaunchKernel(fn, dim3(grid), dim3(256), params, smem, s);
   if (st != hipSuccess) return st;
+  g_last_launch_recorded[dev] = true;
   return hipEventRecord(g_last_launch[dev], s);
 }
 
@@ -2094,8 +2098,7 @@ struct BatchPlan {
   int NT, NC;
 };
 BatchPlan batch_plan(int B) {
-  const char* e = getenv("LSTM_CHAINS");
-  const bool two = e && *e == '2';
+  const bool two = knobs().two_chains;
   if (B <= 16) return {1, 1};
   if (B <= 32) return two ? BatchPlan{1, 2} : BatchPlan{2, 1};
   return two ? BatchPlan{2, 2} : BatchPlan{4, 1};
@@ -2133,13 +2136,10 @@ hipError_t launch_bwd(BatchPlan bp, int grid, const PersBwdArgs& a, hipStream_t 
 // kernels are the faster ones: a step's matrix work per workgroup shrinks with the slice and more CUs share it (one or
 // two layers at H = 512, up to four at H = 256; L = 1, H = 512, B = 64, T = 100: forward recurrence 0.40 ms on four
 // slices of 16 rows, 0.53 on two of 32, 0.74 on the wide kernel; backward 0.65 against 1.14).  `env` names the
-// variable that pins the choice: 1 = one slice on the narrow kernel (B <= 64), 0 = never slices.
-int narrow_slice_rows(const Dims& d, int cell, const char* env) {
+// setting that pins the choice (LSTM_FWD_NARROW / LSTM_BWD_NARROW): 1 = one slice on the narrow kernel (B <= 64), 0 = never slices.
+int narrow_slice_rows(const Dims& d, int cell, int pinned) {
   if (cell != 0) return 0;  // the narrow kernels are LSTM kernels
-  const char* e = getenv(env);
-  if (e && (*e == '0' || *e == '1')) return 0;
-  const char* c2 = getenv("LSTM_CHAINS");
-  if (c2 && *c2 == '2') return 0;
+  if (pinned >= 0 || knobs().two_chains) return 0;
   DeviceInfo di;
   if (!device_info(di)) return 0;
   for (int rows = 16; rows <= 32; rows *= 2) {
@@ -2151,8 +2151,7 @@ int narrow_slice_rows(const Dims& d, int cell, const char* env) {
 
 bool fwd_wide(const Dims& d) {
   if (d.B > 64) return true;  // batches above 64 run as slices of 64 rows, one launch each
-  const char* e = getenv("LSTM_FWD_NARROW");
-  if (e && *e == '1') return false;
+  if (knobs().fwd_narrow == 1) return false;
   return d.B > 32;
 }
 
@@ -2167,8 +2166,7 @@ hipError_t launch_fwd32(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
 bool bwd_wide(const Dims& d) {
   if (d.B > 64) return true;
-  const char* e = getenv("LSTM_BWD_NARROW");
-  if (e && *e == '1') return false;
+  if (knobs().bwd_narrow == 1) return false;
   return d.B > 32;
 }
 
@@ -2178,11 +2176,7 @@ hipError_t launch_bwd32(const PersBwdArgs& a, int nbh, hipStream_t s) {
   const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
   const void* fn = (const void*)pers_bwd32_kernel<HH, CELL>;
   static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
   const int grid = a.L * (HH / 16) * nbh;
   return launch_resident(fn, grid, params, (unsigned)smem, s);
@@ -2199,6 +2193,34 @@ void set_trace(void* buf, size_t bytes, int block) {
   g_trace_buf = reinterpret_cast<long long*>(buf);
   g_trace_bytes = buf ? bytes : 0;
   g_trace_block = block;
+}
+
+// True once after a persistent kernel's bounded wait has expired: the word is cleared by the report, so the
+// call after the one that reports LSTM_INTERNAL runs normally again.
+bool take_watchdog() {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_watch_host || !*g_watch_host) return false;
+  *g_watch_host = 0;
+  return true;
+}
+
+// Everything the persistent path creates lazily, created now for the current device: the host-visible watchdog
+// word and the event that chains the persistent launches.  After it no persistent forward call creates anything.
+hipError_t setup_persistent() {
+  DeviceInfo di;
+  (void)device_info(di);
+  if (!ensure_watchdog()) return hipErrorOutOfMemory;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipSuccess;  // launches on such a device are not chained
+  std::lock_guard<std::mutex> lk(g_launch_mu);
+  if (!g_last_launch[dev]) {
+    e = hipEventCreateWithFlags(&g_last_launch[dev], hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+    g_last_launch_recorded[dev] = false;
+  }
+  return hipSuccess;
 }
 
 void release_persistent() {
@@ -2236,8 +2258,7 @@ constexpr int kLargeMaxBatch1024 = 512;
 constexpr int kLargeMaxBatch2048 = 192;
 
 bool persistent_large(const Dims& d, bool backward) {
-  const char* e = getenv("LSTM_NO_LARGE_PERSISTENT");
-  if (e && *e == '1') return false;
+  if (knobs().no_large_persistent) return false;
   if (!(d.H == 1024 || d.H == 2048)) return false;
   if (d.B > (d.H == 1024 ? kLargeMaxBatch1024 : kLargeMaxBatch2048)) return false;
   DeviceInfo di;
@@ -2262,11 +2283,7 @@ hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
   const size_t smem = (6144 + (size_t)4 * LP * 64) * sizeof(float);
   const void* fn = (const void*)pers_fwdL_kernel<HH, CELL>;
   static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set); e != hipSuccess) return e;
   void* params[] = {const_cast<PersFwdLArgs*>(&a)};
   return launch_resident(fn, a.nsl * (HH / 8), params, (unsigned)smem, s);
 }
@@ -2334,6 +2351,7 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
     k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
     k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    prof_flops(2.0 * G * d.H * std::min(32 * nsl, d.B - 32 * s0) * d.T, "pers_fwdL_kernel");
     CK(launch_fwdL_any(d.H, cell, k, s), "persistent forward launch (large H)");
    }
   }
@@ -2346,11 +2364,7 @@ hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
   const size_t smem = (4096 + 128 * (size_t)UF + 128 * (size_t)UF + (size_t)4 * LP * 64) * sizeof(float);
   const void* fn = (const void*)pers_bwdL_kernel<HH, CELL>;
   static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdLArgs*>(&a)};
   return launch_resident(fn, a.nsl * NBK * NBK, params, (unsigned)smem, s);
 }
@@ -2400,14 +2414,17 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
   // layers).  The side stream starts them behind the counter reset that precedes the persistent launch, so that the
   // launch gets its CUs first and the products fill the rest.  LSTM_NO_WGRAD_OVERLAP=1 keeps one stream.
   bool overlap = (cell == 0 || lg) && d.L > 1 && 2 * maxsl * NBK * NBK <= di.cus && slices <= cap;
+  // The side stream and its two events are process-wide: calls from several host threads take turns from the first
+  // fork to the join (the enqueue only; the GPU work of different calls still overlaps as their streams allow).
+  std::unique_lock<std::mutex> side_turn(g_side_mu, std::defer_lock);
   {
-    const char* e = getenv("LSTM_NO_WGRAD_OVERLAP");
     hipStreamCaptureStatus cst = hipStreamCaptureStatusNone;
-    if ((e && *e == '1') || hipStreamIsCapturing(s, &cst) != hipSuccess || cst != hipStreamCaptureStatusNone ||
+    if (knobs().no_wgrad_overlap || hipStreamIsCapturing(s, &cst) != hipSuccess || cst != hipStreamCaptureStatusNone ||
         !ensure_side_stream())
       overlap = false;
     (void)hipGetLastError();
   }
+  if (overlap) side_turn.lock();
   int pending = -1;  // layer whose weight gradients wait for the side stream
   for (int l = d.L - 1; l >= 0; --l) {
     const int Il = in_dim(d, l);
@@ -2443,6 +2460,7 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
       k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
       k.trace_block = g_trace_block;
       ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+      prof_flops(2.0 * GW * d.H * std::min(32 * nsl, d.B - 32 * s0) * d.T, "pers_bwdL_kernel");
       CK(launch_bwdL_any(d.H, cell, k, s), "persistent backward launch (large H)");
     }
     float* din = l > 0 ? dxb + (size_t)l * TB * d.H : a.dx;
@@ -2498,7 +2516,6 @@ int run_forward_persistent(const FwdArgs& a, int cell) {
   const Dims& d = a.d;
   if (persistent_large(d, false)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
-    if (*g_watch_host) return LSTM_INTERNAL;
     return run_forward_persistent_large(a, cell);
   }
   const int per = layers_per_launch(d);
@@ -2536,10 +2553,9 @@ int forward_layers(const FwdArgs& a, int cell) {
   const size_t TB = (size_t)d.T * d.B, G = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
-  if (*g_watch_host) return LSTM_INTERNAL;
   DeviceInfo di;
   (void)device_info(di);
-  const int slice_rows_narrow = narrow_slice_rows(d, cell, "LSTM_FWD_NARROW");
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().fwd_narrow);
   const bool narrow_slices = slice_rows_narrow > 0;
   const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
   const int BP = 16 * bp.NT;
@@ -2554,8 +2570,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   // product only wins where nothing would be idle otherwise: one layer, one slice -- by about 4 %.)
   bool x_in_kernel = wide && d.I == d.H && !(d.L == 1 && d.B <= 64);
   if (x_in_kernel) {
-    const char* e = getenv("LSTM_FWD_BATCHED_INPUT");
-    if (e && *e == '1') x_in_kernel = false;
+    if (knobs().fwd_batched_input) x_in_kernel = false;
     const size_t rows = (size_t)(d.B + 63) / 64 * 64;  // the copy of x: T+1 slots of H x 64 per slice
     if (((size_t)d.T + 1) * rows * d.H > (size_t)d.L * TB * 4 * d.H) x_in_kernel = false;
   }
@@ -2605,6 +2620,10 @@ int forward_layers(const FwdArgs& a, int cell) {
       }
     }
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    {  // recurrent products of every layer, input products of the layers above the first, and layer 0's when x is multiplied in the kernel
+      const double rows = std::min(slice_rows * nsl, d.B - k.b0), per = 2.0 * G * rows * d.T;
+      prof_flops(per * d.H * (2 * d.L - 1) + (x_in_kernel ? per * d.I : 0.0), wide ? "pers_fwd32_kernel" : "pers_fwd_kernel");
+    }
     hipError_t e = hipErrorInvalidValue;
     if (wide) {
       e = cell == 0 ? launch_fwd32<0>(d.H, grid * nsl, k, s)
@@ -2626,7 +2645,6 @@ int run_backward_persistent(const BwdArgs& a, int cell, bool* bias_done, LayerGr
   const Dims& d = a.d;
   if (persistent_large(d, true)) {
     if (!ensure_watchdog()) return LSTM_HIP_ERROR;
-    if (*g_watch_host) return LSTM_INTERNAL;
     return run_backward_persistent_large(a, cell, bias_done, lg);
   }
   const int per = layers_per_launch(d);
@@ -2676,8 +2694,7 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
-  if (*g_watch_host) return LSTM_INTERNAL;
-  const int slice_rows_narrow = narrow_slice_rows(d, cell, "LSTM_BWD_NARROW");
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().bwd_narrow);
   const bool narrow_slices = slice_rows_narrow > 0;
   const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
   const bool wide = cell != 0 || (!narrow_slices && bwd_wide(d));
@@ -2717,6 +2734,10 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
       CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
     }
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+    {  // dh products of every layer, dx products of the layers above the first, and layer 0's when the kernel writes dx itself
+      const double rows = std::min(slice_rows * nsl, d.B - k.b0), per = 2.0 * GW * rows * d.T;
+      prof_flops(per * d.H * (2 * d.L - 1) + (k.dx0 ? per * d.I : 0.0), wide ? "pers_bwd32_kernel" : "pers_bwd_kernel");
+    }
     hipError_t e = hipErrorInvalidValue;
     if (wide && cell == 1) {
       e = d.H == 512 ? launch_bwd32<512, 1>(k, 2 * nsl, s)

@@ -5,6 +5,8 @@
 #include "../../include/lstm.h"
 #include "../../include/rnn.h"
 #include "schedule.h"
+#include "knobs.h"
+#include <algorithm>
 
 namespace lstm {
 
@@ -137,8 +139,7 @@ inline size_t ws_total(int cell, const Dims& d) {
 }
 inline bool use_persistent(int cell, const Dims& d) {
   if (!gru_persistent_shape(cell, d) || !gru_persistent_supported(d)) return false;
-  const char* e = getenv("RNN_NO_PERSISTENT");
-  return !(e && *e == '1');
+  return !knobs().rnn_no_persistent;
 }
 
 inline int ew_grid(long cnt) { return (int)((cnt + 255) / 256 < 2048 ? (cnt + 255) / 256 : 2048); }
@@ -337,15 +338,15 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Hidden sizes without persistent kernels run zero-padded to the next size that has them, as for the LSTM
 // (padded_hidden): a padded unit has pre-activations 0 and initial state 0, so the GRU keeps it at
 // h = (1 - 1/2) tanh(0) + 1/2 * 0 = 0 and the single gate at act(0) = 0, nothing reads it, and its gradients are 0.
-inline Dims rnn_padded_dims(int cell, const Dims& d) {
-  const char* e = getenv("RNN_NO_PERSISTENT");
-  if (e && *e == '1') return d;
+inline Dims rnn_padded_rule(int cell, const Dims& d) {  // what the environment does not switch off
   // between 512 and 1024 these cells gain more than the LSTM does (their step-by-step path is one GEMM and one
   // point-wise kernel per step): 2.5-3 times at every size measured
-  const char* np = getenv("LSTM_NO_PAD");
-  if (!(np && *np == '1') && d.H > 512 && d.H < 1024 && gru_persistent_shape(cell, Dims{d.L, d.T, d.B, d.I, 1024}))
+  if (d.H > 512 && d.H < 1024 && gru_persistent_shape(cell, Dims{d.L, d.T, d.B, d.I, 1024}))
     return Dims{d.L, d.T, d.B, d.I, 1024};
-  return padded_dims(d);
+  return Dims{d.L, d.T, d.B, d.I, padded_hidden_rule(d)};
+}
+inline Dims rnn_padded_dims(int cell, const Dims& d) {
+  return (knobs().rnn_no_persistent || knobs().no_pad) ? d : rnn_padded_rule(cell, d);
 }
 
 struct RnnPad {
@@ -430,13 +431,15 @@ extern "C" {
 
 size_t rnn_reserve_bytes(int cell, int L, int T, int B, int I, int H) {
   if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
-  return (size_t)L * res_layer_floats(cell, rnn_padded_dims(cell, Dims{L, T, B, I, H})) * sizeof(float);
+  // (padded or as given, whichever is larger -- padding only grows H -- so that the answer does not depend on the environment)
+  return (size_t)L * res_layer_floats(cell, rnn_padded_rule(cell, Dims{L, T, B, I, H})) * sizeof(float);
 }
 
 size_t rnn_workspace_bytes(int cell, int L, int T, int B, int I, int H) {
   if (gates_of(cell) == 0 || L <= 0 || T <= 0 || B <= 0 || I <= 0 || H <= 0) return 0;
-  const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
-  return p.H == d.H ? ws_total(cell, d) : rnn_pad_layout(cell, d, p).total;
+  const Dims d{L, T, B, I, H}, p = rnn_padded_rule(cell, d);
+  const size_t given = ws_total(cell, d);
+  return p.H == d.H ? given : std::max(given, rnn_pad_layout(cell, d, p).total);
 }
 
 int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, const float* h0, const float* W,
@@ -448,12 +451,12 @@ int rnn_forward(int cell, int L, int T, int B, int I, int H, const float* x, con
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
+  if (workspace_bytes < rnn_workspace_bytes(cell, L, T, B, I, H)) return LSTM_BUFFER_TOO_SMALL;
+  if (take_watchdog()) return LSTM_INTERNAL;  // an earlier call's persistent kernel gave up waiting: reported once, here
   if (p.H != d.H) {
-    if (workspace_bytes < rnn_pad_layout(cell, d, p).total) return LSTM_BUFFER_TOO_SMALL;
     return forward_padded(cell, d, p, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve),
                           reinterpret_cast<char*>(workspace), (hipStream_t)stream);
   }
-  if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return forward_impl(cell, d, x, h0, W, R, b, y, hT, reinterpret_cast<float*>(reserve), reinterpret_cast<char*>(workspace),
                       (hipStream_t)stream);
 }
@@ -467,12 +470,12 @@ int rnn_backward(int cell, int L, int T, int B, int I, int H, const float* x, co
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return LSTM_INVALID_ARG;
   const Dims d{L, T, B, I, H}, p = rnn_padded_dims(cell, d);
+  if (workspace_bytes < rnn_workspace_bytes(cell, L, T, B, I, H)) return LSTM_BUFFER_TOO_SMALL;
+  if (take_watchdog()) return LSTM_INTERNAL;  // an earlier call's persistent kernel gave up waiting: reported once, here
   if (p.H != d.H) {
-    if (workspace_bytes < rnn_pad_layout(cell, d, p).total) return LSTM_BUFFER_TOO_SMALL;
     return backward_padded(cell, d, p, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
                            reinterpret_cast<char*>(workspace), (hipStream_t)stream);
   }
-  if (workspace_bytes < ws_total(cell, d)) return LSTM_BUFFER_TOO_SMALL;
   return backward_impl(cell, d, x, h0, W, R, reinterpret_cast<const float*>(reserve), dy, dhT, dx, dh0, dW, dR, db,
                        reinterpret_cast<char*>(workspace), (hipStream_t)stream);
 }

@@ -51,6 +51,7 @@ struct BwdArgs {
 // persistent kernels exist for H = 128, 256 and 512, and any other hidden size below 512 runs faster (several times,
 // with more than one layer) padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
 int padded_hidden(const Dims& d);
+int padded_hidden_rule(const Dims& d);  // the same without looking at LSTM_NO_PAD (size queries cover both settings)
 inline Dims padded_dims(const Dims& d) { return Dims{d.L, d.T, d.B, d.I, padded_hidden(d)}; }
 // dst [outer][rd][cd] <- src [outer][rs][cs]: the common corner is copied, the rest of dst is zero (pads and crops).
 hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int cd, int rs, int cs, hipStream_t s);
@@ -75,6 +76,8 @@ int weight_gradients_layers(const BwdArgs& a, const float* dA_all, int l0, int l
 int run_forward(const FwdArgs& a, unsigned path);
 int run_backward(const BwdArgs& a, unsigned path);
 void release_helpers();
+hipError_t setup_persistent();  // creates, for the current device, what the persistent path otherwise creates on first use
+bool take_watchdog();  // true once after a bounded wait of a persistent kernel expired (clears the word)
 void set_trace(void* buf, size_t bytes, int block);
 hipError_t record(hipError_t e, const char* what);
 

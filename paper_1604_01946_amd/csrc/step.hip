@@ -21,6 +21,7 @@
 // Backward: workgroup = upw (8 or 16) hidden units x (16*NT) batch rows, K = 4H over the
 // transposed recurrent matrix; the epilogue is the point-wise gate-gradient computation.
 #include "internal.h"
+#include "knobs.h"
 
 namespace lstm {
 namespace {
@@ -331,8 +332,8 @@ hipError_t launch_bwd_nt(const StepBwdArgs& a, hipStream_t s) {
 // 16 halve them again (at H = 4096 they are otherwise twice the stream of R itself); fewer units per workgroup
 // where more would leave CUs idle.
 int step_fwd_mtiles(int H, int B) {
-  const char* e = getenv("LSTM_STEP_MT");
-  if (e && (*e == '1' || *e == '2' || *e == '4')) return *e - '0';
+  const int forced = knobs().step_mt;
+  if (forced == 1 || forced == 2 || forced == 4) return forced;
   if (((H + 15) / 16) * batch_tiles_y(B) >= 200) return 4;
   return (((H + 7) / 8) * batch_tiles_y(B) < 200) ? 1 : 2;
 }
@@ -363,6 +364,7 @@ hipError_t launch_pack_bwd(const float* R, float* RTp, int L, int H, int B, size
 hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
   const bool vec = (a.H % 4 == 0) && (a.h_prev == nullptr || aligned16(a.h_prev));
   const int MT = step_fwd_mtiles(a.H, a.B);
+  if (a.h_prev) prof_flops(2.0 * a.B * 4.0 * a.H * a.H, "step_fwd_kernel");
   if (MT == 1) return vec ? launch_fwd_mt<1, true>(a, stream) : launch_fwd_mt<1, false>(a, stream);
   if (MT == 4) return vec ? launch_fwd_mt<4, true>(a, stream) : launch_fwd_mt<4, false>(a, stream);
   return vec ? launch_fwd_mt<2, true>(a, stream) : launch_fwd_mt<2, false>(a, stream);
@@ -371,6 +373,7 @@ hipError_t launch_step_fwd(const StepFwdArgs& a, hipStream_t stream) {
 hipError_t launch_step_bwd(const StepBwdArgs& a0, hipStream_t stream) {
   StepBwdArgs a = a0;
   a.units_per_wg = step_bwd_units(a.H, a.B);
+  if (a.dA_next) prof_flops(2.0 * a.B * 4.0 * a.H * a.H, "step_bwd_kernel");
   const bool vec = (a.dA_next == nullptr || aligned16(a.dA_next));  // K = 4H is a multiple of 4
   return vec ? launch_bwd_nt<true>(a, stream) : launch_bwd_nt<false>(a, stream);
 }

@@ -14,6 +14,7 @@
 // contracts over K = H only; there the same scheme measured slower than step.hip's kernel and is
 // not used.)
 #include "internal.h"
+#include "knobs.h"
 
 #include <stdlib.h>
 
@@ -256,8 +257,7 @@ inline int pow2_floor(int v) {
 
 // Split-K is used when H is large and a multiple of 64 (the fix-up then needs no unit guards).
 bool splitk_supported(int H) {
-  const char* e = getenv("LSTM_SPLITK_MIN_H");  // tests lower the threshold to reach these kernels with small shapes
-  const int min_h = (e && *e) ? atoi(e) : 1024;
+  const int min_h = knobs().splitk_min_h > 0 ? knobs().splitk_min_h : 1024;  // tests lower the threshold to reach these kernels with small shapes
   return H >= min_h && (H % 64) == 0;
 }
 
@@ -285,6 +285,7 @@ hipError_t launch_pack_bwd_sk(const float* R, float* RTp, int L, int H, int B, s
 
 hipError_t launch_step_bwd_sk(const StepBwdArgs& a, float* partial, int* counters, hipStream_t s) {
   SplitK sk{partial, counters, splitk_bwd_slices(a.H, a.B), splitk_bwd_per(a.H, a.B)};
+  if (a.dA_next) prof_flops(2.0 * a.B * 4.0 * a.H * a.H, "step_bwd_sk_kernel");
   const dim3 grid(((a.H + 63) / 64) * sk.KS, batch_tiles_y(a.B));
   const bool vec = (a.dA_next == nullptr) || (reinterpret_cast<uintptr_t>(a.dA_next) & 15u) == 0;
   const int nt = tile_nt(a.B);

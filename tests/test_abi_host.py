@@ -72,9 +72,29 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     a = 4096
     ptrs = [a, None, None, a, a, a, a, None, None, None, a]
     assert B.lstm_forward(2, 5, 3, 8, 100, *ptrs, padded - 1, stream=0, flags=0) == B.LSTM_BUFFER_TOO_SMALL
+
+
+def test_buffer_sizes_do_not_depend_on_the_environment(monkeypatch):
+    """LSTM_NO_PAD / RNN_NO_PERSISTENT switch the zero-padding of hidden sizes off, which changes the layout of the
+    reserve; the size queries answer for both settings (the larger), so buffers sized under one setting can never
+    be overrun under the other.  The settings themselves are read once and again after lstm_shutdown()."""
+    shapes = [(2, 5, 3, 8, 100), (2, 5, 3, 8, 800), (4, 100, 64, 512, 512), (1, 8, 3, 8, 100), (2, 5, 3, 384, 384)]
+    B.lstm_shutdown()
+    ref = [(B.lstm_reserve_bytes(*s), B.lstm_workspace_bytes(*s)) for s in shapes]
+    rnn = [(B.rnn_reserve_bytes(c, *s), B.rnn_workspace_bytes(c, *s)) for s in shapes for c in (0, 1, 2)]
     monkeypatch.setenv("LSTM_NO_PAD", "1")
-    assert B.lstm_reserve_bytes(2, 5, 3, 8, 100) == 2 * 5 * 3 * 6 * 100 * 4
-    assert B.lstm_workspace_bytes(2, 5, 3, 8, 100) < padded
+    monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
+    B.lstm_shutdown()  # the settings are read again
+    assert ref == [(B.lstm_reserve_bytes(*s), B.lstm_workspace_bytes(*s)) for s in shapes]
+    assert rnn == [(B.rnn_reserve_bytes(c, *s), B.rnn_workspace_bytes(c, *s)) for s in shapes for c in (0, 1, 2)]
+    # as-given runs need no more than the padded ones were sized for
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 100) >= 2 * 5 * 3 * 6 * 100 * 4
+    a = 4096
+    ptrs = [a, None, None, a, a, a, a, None, None, None, a]
+    assert B.lstm_forward(2, 5, 3, 8, 100, *ptrs, ref[0][1] - 1, stream=0, flags=0) == B.LSTM_BUFFER_TOO_SMALL
+    monkeypatch.delenv("LSTM_NO_PAD")
+    monkeypatch.delenv("RNN_NO_PERSISTENT")
+    B.lstm_shutdown()
 
 
 def test_wavefront_chunks_setting_validates():

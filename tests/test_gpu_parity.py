@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from paper_1604_01946_amd.inputs import CONFIGS, Config, make_inputs
+import parity
 from parity import oracle_results, assert_close, FWD_TOL, BWD_TOL
 
 pytestmark = pytest.mark.gpu
@@ -38,6 +39,7 @@ def run_case(cfg, seed, flags, backward=True, with_states=True, with_dstates=Tru
         torch.cuda.synchronize()
         e.update(assert_close(r.bwd_outputs(), ref, BWD, BWD_TOL, f"bwd {cfg.dims} flags={flags}"))
     print("  errors:", {k: f"{v:.2e}" for k, v in e.items()}, flush=True)
+    print("  element-wise relative (floor 1e-6 of the scale):", {k: f"{parity.last_relerr[k]:.2e}" for k in e}, flush=True)
     return r, ref
 
 
@@ -79,8 +81,8 @@ def test_gemm_matches_numpy(M, N, K, layout):
 
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (6400, 2048, 512), (256, 384, 48), (100, 260, 32)])
 @pytest.mark.parametrize("layout", ["NT", "NN", "TN", "TT"])
-def test_gemm_register_staged_kernel(M, N, K, layout, monkeypatch):
-    monkeypatch.setenv("LSTM_GEMM_STAGED", "1")
+def test_gemm_register_staged_kernel(M, N, K, layout, knobs):
+    knobs(LSTM_GEMM_STAGED="1")
     _gemm_case(M, N, K, layout)
 
 
@@ -92,10 +94,10 @@ PATHS_ALL = [0, 1, 2, 3, 4, 5, 6]
 # every path; LSTM_NO_PAD=1 runs the shape as given, which is what exercises the ragged tiles of the per-step kernels.
 @pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
 @pytest.mark.parametrize("flags", PATHS_ALL)
-def test_cfg1_all_paths(flags, nopad, monkeypatch):
+def test_cfg1_all_paths(flags, nopad, knobs):
     _, binding, _ = _mods()
     if nopad:
-        monkeypatch.setenv("LSTM_NO_PAD", "1")
+        knobs(LSTM_NO_PAD="1")
     cfg = CONFIGS["cfg1"]
     if flags == 6 and binding.lstm_auto_path(*cfg.dims, 0) != 6:
         pytest.skip("persistent path does not take this shape")
@@ -111,6 +113,11 @@ def test_cfg2_forward(flags):
 @pytest.mark.parametrize("flags", [0, 4, 5, 6])
 def test_cfg3_forward_backward(flags):
     run_case(CONFIGS["cfg3"], 0, flags)
+
+
+def test_cfg3_second_seed():
+    """Guard against anything fitted to seed 0: the measured shape once more with other inputs."""
+    run_case(CONFIGS["cfg3"], 1, 0)
 
 
 @pytest.mark.parametrize("flags", [0, 4], ids=["auto", "step"])
@@ -219,17 +226,17 @@ VARIANTS = [
 
 @pytest.mark.parametrize("env", VARIANTS, ids=["narrow", "chains2", "fullfences", "batched_input", "wide"])
 @pytest.mark.parametrize("cfg", [PERS[3], PERS[4], PERS[5]], ids=["p256b20", "p512b33", "p512b64"])
-def test_persistent_variants(cfg, env, monkeypatch):
+def test_persistent_variants(cfg, env, knobs):
     """The alternative kernels and the fence-based protocol must give the oracle's answer too; the
     default path must give bit-identical results to the fence-based one (same arithmetic, only the
     synchronisation differs), which cross-checks the fast flag protocol."""
     torch, binding, runner = _mods()
     for k, v in env.items():
-        monkeypatch.setenv(k, v)
+        knobs(**{k: v})
     r, ref = run_case(cfg, 11, binding.LSTM_PATH_PERSISTENT)
     if "LSTM_FULL_FENCES" in env:
         slow = {k: getattr(r, k).clone() for k in FWD + BWD}
-        monkeypatch.delenv("LSTM_FULL_FENCES")
+        knobs(LSTM_FULL_FENCES=None)
         r.poison()
         binding.check(r.forward(flags=binding.LSTM_PATH_PERSISTENT))
         binding.check(r.backward(flags=binding.LSTM_PATH_PERSISTENT))
@@ -238,25 +245,28 @@ def test_persistent_variants(cfg, env, monkeypatch):
             assert torch.equal(slow[k], getattr(r, k)), k
 
 
-def test_watchdog_expires_and_reports(monkeypatch):
+@pytest.mark.parametrize("next_path", [6, 4], ids=["persistent", "step"])
+def test_watchdog_expires_and_reports(knobs, next_path):
     """A spin limit of 1 makes the waits of the persistent kernels give up at once (forced from the
-    host; the kernels still run to completion).  The library must report LSTM_INTERNAL on the next
-    call and work again after lstm_shutdown()."""
+    host; the kernels still run to completion).  The next call, on whatever path, must report
+    LSTM_INTERNAL once, launch nothing, and the call after it must work again."""
     torch, binding, runner = _mods()
     cfg = PERS[5]
     d, ref = oracle_results(cfg, 11)
     r = runner.LstmRunner(cfg.dims, d)
-    monkeypatch.setenv("LSTM_SPIN_LIMIT", "1")
+    knobs(LSTM_SPIN_LIMIT="1")
     st = r.forward(flags=binding.LSTM_PATH_PERSISTENT)
     torch.cuda.synchronize()          # the kernel drained
     assert st == binding.LSTM_OK      # the expiry is seen by the host only afterwards
-    monkeypatch.delenv("LSTM_SPIN_LIMIT")
-    st2 = r.forward(flags=binding.LSTM_PATH_PERSISTENT)
+    r.y.fill_(float("nan"))
+    st2 = r.forward(flags=next_path)
+    torch.cuda.synchronize()
     if st2 == binding.LSTM_OK:
         pytest.skip("no wait expired with a spin limit of 1 (every flag was already set when polled)")
     assert st2 == binding.LSTM_INTERNAL
-    binding.lstm_shutdown()
-    binding.check(r.forward(flags=binding.LSTM_PATH_PERSISTENT))
+    assert torch.isnan(r.y).all()     # the reporting call launched nothing
+    knobs(LSTM_SPIN_LIMIT=None)
+    binding.check(r.forward(flags=next_path))
     torch.cuda.synchronize()
     assert_close(r.fwd_outputs(), ref, FWD, FWD_TOL)
 
@@ -277,11 +287,11 @@ ODD = [
 @pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
 @pytest.mark.parametrize("cfg", ODD, ids=[c.name for c in ODD])
 @pytest.mark.parametrize("flags", [0, 1, 3, 4, 5])
-def test_odd_shapes(cfg, flags, nopad, monkeypatch):
+def test_odd_shapes(cfg, flags, nopad, knobs):
     if nopad:
         if cfg.H >= 512:
             pytest.skip("not a padded shape: same run as the other variant")
-        monkeypatch.setenv("LSTM_NO_PAD", "1")
+        knobs(LSTM_NO_PAD="1")
     run_case(cfg, 3, flags)
 
 
@@ -294,10 +304,10 @@ STEPK = [ODD[2], ODD[4], ODD[6],
 
 @pytest.mark.parametrize("mt", ["1", "2", "4"])
 @pytest.mark.parametrize("cfg", STEPK, ids=[c.name for c in STEPK])
-def test_step_kernel_units_per_workgroup(cfg, mt, monkeypatch):
+def test_step_kernel_units_per_workgroup(cfg, mt, knobs):
     _, binding, _ = _mods()
-    monkeypatch.setenv("LSTM_NO_PAD", "1")
-    monkeypatch.setenv("LSTM_STEP_MT", mt)
+    knobs(LSTM_NO_PAD="1")
+    knobs(LSTM_STEP_MT=mt)
     run_case(cfg, 19, binding.LSTM_PATH_STEP)
 
 
@@ -328,10 +338,10 @@ def test_padded_hidden_sizes(cfg, with_states):
 
 # ------------------------------------------------------------------ optional pointers, inference
 @pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
-def test_null_optionals_and_inference(nopad, monkeypatch):
+def test_null_optionals_and_inference(nopad, knobs):
     torch, binding, runner = _mods()
     if nopad:
-        monkeypatch.setenv("LSTM_NO_PAD", "1")
+        knobs(LSTM_NO_PAD="1")
     cfg = Config("opt", L=2, T=4, B=6, I=16, H=24)
     for flags in (0, 4):
         d, ref = oracle_results(cfg, 5, with_states=False, with_dstates=False)
@@ -360,6 +370,27 @@ def test_large_minibatch_takes_the_gemm_rung_forward():
     run_case(cfg, 13, 0)
 
 
+# ------------------------------------------------------------------ the large end of the hidden-size / minibatch sweep
+# Section 3.2 sweeps hidden sizes up to 4096 and minibatches up to 256; these are the kernels that the sweep times
+# there, compared with the oracle on two or three steps: the forward step kernel with 16 units per workgroup and the
+# split-K backward kernel (H = 4096), the grouped-GEMM rung that the automatic forward path takes once one step fills
+# the chip (B = 256), and the step kernels at H = 2048 with 256 rows (two waves per SIMD).
+SWEEP_END = [
+    (Config("s4096b32", L=1, T=2, B=32, I=64, H=4096, state_std=0.3, dstate_std=0.3), 0),
+    (Config("s4096L2b64", L=2, T=2, B=64, I=4096, H=4096, state_std=0.3, dstate_std=0.3), 0),
+    (Config("s4096b256", L=1, T=2, B=256, I=64, H=4096, state_std=0.3, dstate_std=0.3), 0),
+    (Config("s2048b256", L=2, T=2, B=256, I=128, H=2048, state_std=0.3, dstate_std=0.3), 4),
+]
+SWEEP_END += [(Config("s4096L2b32", L=2, T=3, B=32, I=64, H=4096, state_std=0.3, dstate_std=0.3), f) for f in (3, 4, 5)]
+SWEEP_END += [(Config("s4096b256", L=1, T=2, B=256, I=64, H=4096, state_std=0.3, dstate_std=0.3), f) for f in (3, 4, 5)]
+SWEEP_END += [(Config("s2048L1b256", L=1, T=3, B=256, I=64, H=2048, state_std=0.3, dstate_std=0.3), f) for f in (0, 3, 4, 5)]
+
+
+@pytest.mark.parametrize("cfg,flags", SWEEP_END, ids=[f"{c.name}-path{f}" for c, f in SWEEP_END])
+def test_large_end_of_the_sweep(cfg, flags):
+    run_case(cfg, 29, flags)
+
+
 # ------------------------------------------------------------------ determinism (doubles as a race detector)
 @pytest.mark.parametrize("name", ["cfg1", "cfg3", "cfg4", "cfg5"])
 def test_bitwise_repeatable(name):
@@ -380,7 +411,7 @@ def test_bitwise_repeatable(name):
 
 @pytest.mark.parametrize("launch", ["unchained", "chained", "cooperative"])
 @pytest.mark.parametrize("dims", [(4, 100, 16, 256), (8, 60, 32, 256)], ids=["b16", "b32"])
-def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, launch, monkeypatch):
+def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, launch, knobs):
     """Two calls on two streams: each must give exactly what it gives alone.  Unchained ordinary launches let the two
     persistent kernels run on the same CUs at once where both fit (small register footprint): this caught a 16-byte
     write-through store issued from inline assembly without the idle cycles a wide store needs before its data
@@ -388,7 +419,7 @@ def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, launch, mon
     the third mode."""
     torch, binding, runner = _mods()
     if launch != "chained":
-        monkeypatch.setenv("LSTM_PLAIN_LAUNCH" if launch == "unchained" else "LSTM_COOP_LAUNCH", "1")
+        knobs(**{"LSTM_PLAIN_LAUNCH" if launch == "unchained" else "LSTM_COOP_LAUNCH": "1"})
     L, T, B, H = dims
     cfg = Config("two", L=L, T=T, B=B, I=H, H=H, state_std=0.1)
     r1, r2 = runner.LstmRunner(cfg.dims, make_inputs(cfg, 1)), runner.LstmRunner(cfg.dims, make_inputs(cfg, 2))
@@ -415,10 +446,10 @@ def test_two_streams_sharing_the_cus_do_not_disturb_each_other(dims, launch, mon
 
 # ------------------------------------------------------------------ boundary identity on the GPU
 @pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
-def test_split_T_chaining_on_gpu(nopad, monkeypatch):
+def test_split_T_chaining_on_gpu(nopad, knobs):
     torch, binding, runner = _mods()
     if nopad:
-        monkeypatch.setenv("LSTM_NO_PAD", "1")
+        knobs(LSTM_NO_PAD="1")
     cfg = Config("chain", L=2, T=8, B=16, I=32, H=64, state_std=0.3)
     d = make_inputs(cfg, 7)
     full = runner.LstmRunner(cfg.dims, d)

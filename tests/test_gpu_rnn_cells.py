@@ -112,9 +112,9 @@ RAGGED = [(3, 5, 7, 24, 40), (2, 3, 3, 5, 7), (2, 4, 70, 36, 100), (2, 40, 9, 30
 @pytest.mark.parametrize("step_by_step", [False, True], ids=["padded", "as_given"])
 @pytest.mark.parametrize("cell", ["relu", "tanh", "gru"])
 @pytest.mark.parametrize("dims", RAGGED, ids=["x".join(map(str, s)) for s in RAGGED])
-def test_ragged_hidden_sizes(cell, dims, step_by_step, monkeypatch):
+def test_ragged_hidden_sizes(cell, dims, step_by_step, knobs):
     if step_by_step:
-        monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
+        knobs(RNN_NO_PERSISTENT="1")
     run(cell, *dims, seed=11)
 
 
@@ -168,6 +168,6 @@ def test_large_hidden_shapes(dims, cell, with_h0):
 
 
 @pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
-def test_step_by_step_path_at_a_persistent_shape(cell, monkeypatch):
-    monkeypatch.setenv("RNN_NO_PERSISTENT", "1")
+def test_step_by_step_path_at_a_persistent_shape(cell, knobs):
+    knobs(RNN_NO_PERSISTENT="1")
     run(cell, 2, 5, 40, 64, 128, seed=6)
