@@ -130,6 +130,38 @@ int lstm_forward(int L, int T, int B, int I, int H,
                  void* stream, unsigned flags);
 
 /*
+ * One-time set-up for the current device, for callers that want nothing created inside their calls:
+ * resolves the address of the library's static scratch array on this device and creates what the
+ * persistent path otherwise creates on first use (the host-visible watchdog word, pinned host memory,
+ * and the event that chains persistent launches).  Optional: every entry point does its own set-up on
+ * first use.  Call it again after lstm_shutdown().  Returns LSTM_OK or LSTM_HIP_ERROR.
+ */
+int lstm_init(void);
+
+/*
+ * lstm_forward for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * lstm_forward without `workspace` / `workspace_bytes`: the scratch is a static array in device memory,
+ * LSTM_NOALLOC_SCRATCH_BYTES (64 MiB) per GPU, held from library load until the process ends.
+ *   - shapes whose lstm_workspace_bytes() exceeds that size are rejected with LSTM_BUFFER_TOO_SMALL
+ *     (lstm_last_error() gives both numbers) before anything is launched;
+ *   - the call allocates and frees nothing and creates no stream or event once lstm_init() has run on
+ *     the device (without it the first call on a device performs that set-up itself);
+ *   - LSTM_PATH_WAVEFRONT is refused (LSTM_UNSUPPORTED), and where LSTM_PATH_AUTO would choose it the
+ *     step path runs instead: the wavefront's helper streams are created to the size of the shape;
+ *   - every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it and must be ordered by the caller.  Nothing is assumed about
+ *     what the previous call left there: counters that must start at zero are cleared by a fill kernel
+ *     inside the call (no memset node, so a captured call replays correctly).
+ */
+#define LSTM_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+int lstm_forward_noalloc(int L, int T, int B, int I, int H,
+                         const float* x, const float* h0, const float* c0,
+                         const float* W, const float* R, const float* b,
+                         float* y, float* hT, float* cT,
+                         void* reserve, void* stream, unsigned flags);
+
+/*
  * Backward pass: gradients of  <dy,y> + <dhT,hT> + <dcT,cT>  with respect to every input
  * of lstm_forward.  The paper gives no backward equations; this is the chain rule through
  * the Section 2 equations, with the data-gradient products grouped over the four gates

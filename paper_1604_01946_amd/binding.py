@@ -30,6 +30,7 @@ PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wa
 
 EXPORTS = [
     "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
+    "lstm_init", "lstm_forward_noalloc",
     "lstm_auto_path", "lstm_set_path", "lstm_set_wavefront_chunks", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
     "lstm_profile_enable", "lstm_profile_read", "lstm_profile_kernel", "lstm_phase_name", "lstm_debug_set_trace",
 ]
@@ -62,6 +63,10 @@ def library():
         lib.lstm_forward.argtypes = [i] * 5 + [p] * 11 + [z, p, u]
         lib.lstm_backward.restype = i
         lib.lstm_backward.argtypes = [i] * 5 + [p] * 16 + [z, p, u]
+        lib.lstm_init.restype = i
+        lib.lstm_init.argtypes = []
+        lib.lstm_forward_noalloc.restype = i
+        lib.lstm_forward_noalloc.argtypes = [i] * 5 + [p] * 10 + [p, u]
         lib.lstm_gemm_f32.restype = i
         lib.lstm_gemm_f32.argtypes = [i, i, i, p, l, l, p, l, l, p, l, i, p]
         lib.lstm_auto_path.restype = u
@@ -174,6 +179,15 @@ def lstm_forward(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, workspac
     return library().lstm_forward(L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(c0), _ptr(W), _ptr(R), _ptr(b),
                                   _ptr(y), _ptr(hT), _ptr(cT), _ptr(reserve), _ptr(workspace), workspace_bytes,
                                   _stream(stream), flags)
+
+
+def lstm_init():
+    return library().lstm_init()
+
+
+def lstm_forward_noalloc(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, stream=None, flags=0):
+    return library().lstm_forward_noalloc(L, T, B, I, H, _ptr(x), _ptr(h0), _ptr(c0), _ptr(W), _ptr(R), _ptr(b),
+                                          _ptr(y), _ptr(hT), _ptr(cT), _ptr(reserve), _stream(stream), flags)
 
 
 def lstm_backward(L, T, B, I, H, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0, dc0, dW, dR, db,

@@ -322,7 +322,42 @@ int backward_padded(const Dims& d, const Dims& p, const float* x, const float* h
 
 }  // namespace
 
+// ---------------------------------------------------------------- scratch of lstm_forward_noalloc
+// One array per GPU, held from the moment the library is loaded until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the device address is resolved once per device, with that device
+// current, and every later use goes through the resolved pointer.
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[64] = {};
+bool g_init_done[64] = {};   // set-up of the persistent path done on this device (undone by lstm_shutdown)
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (record(hipGetDevice(&dev), "hipGetDevice") != hipSuccess) return LSTM_HIP_ERROR;
+  if (dev < 0 || dev >= 64) {
+    g_last_error = "lstm_forward_noalloc: device index out of range";
+    return LSTM_HIP_ERROR;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (record(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)") != hipSuccess || !p) return LSTM_HIP_ERROR;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LSTM_OK;
+}
+
+bool lstm_init_needed() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  return g_scratch_ptr[dev] == nullptr || !g_init_done[dev];
+}
+
 int forward_call(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
                  const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
                  size_t workspace_bytes, void* stream, unsigned flags, bool no_new_resources);
@@ -360,6 +395,10 @@ const char* lstm_status_string(int status) {
 const char* lstm_last_error(void) { return g_last_error.c_str(); }
 
 void lstm_shutdown(void) {
+  {
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    for (bool& v : g_init_done) v = false;   // the watchdog word and the chain events are released below
+  }
   release_helpers();
   clear_path_overrides();
   reset_knobs();
@@ -430,6 +469,38 @@ int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const
   return LSTM_OK;
 }
 
+int lstm_init(void) {
+  g_last_error.clear();
+  void* p = nullptr;
+  if (scratch_of_current_device(&p) != LSTM_OK) return LSTM_HIP_ERROR;
+  if (record(setup_persistent(), "lstm_init: watchdog word / launch-chain event") != hipSuccess) return LSTM_HIP_ERROR;
+  int dev = -1;
+  if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    g_init_done[dev] = true;
+  }
+  return LSTM_OK;
+}
+
+int lstm_forward_noalloc(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0,
+                         const float* W, const float* R, const float* b, float* y, float* hT, float* cT, void* reserve,
+                         void* stream, unsigned flags) {
+  g_last_error.clear();
+  if (!dims_ok(L, T, B, I, H)) return LSTM_INVALID_ARG;
+  if ((flags & LSTM_PATH_MASK) == LSTM_PATH_WAVEFRONT) return LSTM_UNSUPPORTED;  // that path creates helper streams sized by the shape
+  const size_t need = lstm_workspace_bytes(L, T, B, I, H);
+  if (need > kScratchBytes) {
+    g_last_error = "lstm_forward_noalloc: this shape needs " + std::to_string(need) + " bytes of scratch, the static array holds " +
+                   std::to_string(kScratchBytes);
+    return LSTM_BUFFER_TOO_SMALL;
+  }
+  void* ws = nullptr;
+  const int st = lstm_init_needed() ? lstm_init() : LSTM_OK;
+  if (st != LSTM_OK) return st;
+  if (scratch_of_current_device(&ws) != LSTM_OK) return LSTM_HIP_ERROR;
+  return forward_call(L, T, B, I, H, x, h0, c0, W, R, b, y, hT, cT, reserve, ws, kScratchBytes, stream, flags, true);
+}
+
 int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
                  const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
                  size_t workspace_bytes, void* stream, unsigned flags) {
@@ -439,7 +510,7 @@ int lstm_forward(int L, int T, int B, int I, int H, const float* x, const float*
 }  // extern "C"
 
 namespace {
-// no_new_resources: the caller may create nothing; the stream wavefront, whose helper streams
+// no_new_resources: the caller may create nothing (lstm_forward_noalloc); the stream wavefront, whose helper streams
 // and events are created to the size of the shape, is then replaced by the step path.
 int forward_call(int L, int T, int B, int I, int H, const float* x, const float* h0, const float* c0, const float* W,
                  const float* R, const float* b, float* y, float* hT, float* cT, void* reserve, void* workspace,
