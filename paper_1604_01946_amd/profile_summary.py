@@ -90,9 +90,11 @@ def cmd_traffic(a):
     avg = lambda d, k: (sum(d[k]) / len(d[k])) if d.get(k) else 0.0
     if COPY_KERNEL not in f or COPY_KERNEL not in w:
         sys.exit("no calibration copy in the runs: use bench.py --copy-calibration")
-    # counters are in KiB; the copy read 1 GiB and wrote 1 GiB
-    kf = COPY_BYTES / 1024.0 / avg(f, COPY_KERNEL)
-    kw = COPY_BYTES / 1024.0 / avg(w, COPY_KERNEL)
+    # counters are in KiB; the copy read 1 GiB and wrote 1 GiB (the runtime's small staging copies run under the same
+    # kernel name: the calibration copy is the largest dispatch)
+    cf, cw = max(f[COPY_KERNEL]), max(w[COPY_KERNEL])
+    kf = COPY_BYTES / 1024.0 / cf
+    kw = COPY_BYTES / 1024.0 / cw
     kernels = {}
     rows = ["| kernel | launches | FETCH_SIZE avg (KiB, raw) | read MiB per launch | WRITE_SIZE avg (KiB, raw) | written MiB per launch |",
             "|---|---|---|---|---|---|"]
@@ -113,7 +115,7 @@ def cmd_traffic(a):
         md += [f"    {a.command.replace('COUNTER', c)}" for c in ("FETCH_SIZE", "WRITE_SIZE")]
         md.append("")
     md.append(f"Calibration: `--copy-calibration` makes one 1 GiB device-to-device copy (`{COPY_KERNEL}`).  The counters read "
-              f"FETCH_SIZE = {avg(f, COPY_KERNEL):.1f} KiB and WRITE_SIZE = {avg(w, COPY_KERNEL):.1f} KiB for it, so read bytes = "
+              f"FETCH_SIZE = {cf:.1f} KiB and WRITE_SIZE = {cw:.1f} KiB for it, so read bytes = "
               f"FETCH_SIZE x {kf:.3f} KiB and written bytes = WRITE_SIZE x {kw:.3f} KiB.\n")
     md += rows
     if a.notes and os.path.exists(a.notes):
