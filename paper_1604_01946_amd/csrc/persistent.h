@@ -47,6 +47,7 @@ struct PersFwdArgs {
   long long* trace;
   int trace_block;
   int keep;           // wide kernel: 0 = inference call (no reserve wanted): only y, hT, cT are written
+  float* dummy;       // pers_fwd_pp_kernel: 128 bytes of scratch that take the stores nobody wants
 };
 
 // ------------------------------------------------------------------ backward

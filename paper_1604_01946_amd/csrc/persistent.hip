@@ -574,6 +574,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   PersFwdArgs k;
   k.xin = x_in_kernel ? P0 : nullptr;
   k.keep = a.inference ? 0 : 1;
+  k.dummy = reinterpret_cast<float*>(a.ws + a.w.scratch);
   k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.h0 = a.h0; k.hx = hx; k.flags = flags; k.watchdog = g_watch_dev;
   k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.has_h0 = a.h0 != nullptr; k.spin_limit = spin_limit();

@@ -8,8 +8,9 @@
 // different batch rows are independent, so here the slice is two chains of 32 rows that alternate: while the
 // h_t of one chain is on its way to the other workgroups (store acknowledgement, counter, propagation, the
 // fetch of the operand), the wave multiplies for the other chain.  The acknowledgement of a chain's store is
-// awaited, and its counter bumped, a few groups of matrix instructions into the other chain's block, and the
-// fetch of a chain's next input operand is requested from its own epilogue, so that none of these round trips
+// awaited, and its counter bumped, some groups of matrix instructions into the other chain's block; a chain's gates
+// are computed in between the first matrix instructions of the other chain's next block; the whole input half of
+// a chain's next operand is requested during the other chain's block: none of these round trips
 // has the matrix core waiting.  Section 4 of arXiv 1604.01946 names the underlying idea (weights stay on chip
 // for the whole sequence); Section 2.4's wavefront over layers runs inside the grid through per-(layer, step,
 // chain) counters.
@@ -94,6 +95,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   constexpr int NYOUNG = pp_count(LAG, LAG + NK8 - 1, GA) + pp_count(PF, PF + NK8 - 1, GA);
   static_assert(NYOUNG >= 1 && NYOUNG < 60 && PF + NK8 <= NG && GA < NG, "schedule");
   __shared__ __attribute__((aligned(16))) float part[2][4][1024];  // [buffer][wave][gate][kk][n][4]
+  __shared__ __attribute__((aligned(16))) float stage[4][6 * 64];  // per wave: i, f, o, c', c, h of its 8 rows x 8 units
 
   int l, s;
   map_block(a.L, NS * a.nsl, l, s);
@@ -179,30 +181,15 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   // input half (requested during the other chain's block); slot i is refilled with recurrent group i as soon as
   // input group i has been consumed, LAG groups behind.
   floatx4 ring[2][NK8];
-  float o_gate[2][4], o_c[2], o_h[2];  // what the chain's last step produced, until it is written to the reserve
   int seen_rec = 1 << 30;              // the next block's own-layer counter, read during the block before it
 
   // ---- completes the publication of chain c's step t: the store is acknowledged once at most NYOUNG younger
-  //      requests are outstanding (none for the very last one); then the counter, then the reserve and the outputs
-  //      (nobody reads those before the kernel ends)
+  //      requests are outstanding (none for the very last one); then the counter
   auto complete = [&](const int c, const int t, const bool last) {
     if (last) drain_vmem();
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NYOUNG) : "memory");
     if (lane == 0) __hip_atomic_fetch_add(flag(l, t + 1, c) + arrive_line, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     tr.mark(c, t, 6);
-    if (!valid[c]) return;
-    const size_t e = ((size_t)t * B + bb[c]) * H + unit;
-    if (a.keep) {
-      float* const gp = res_gates + ((size_t)t * B + bb[c]) * 4 * H + unit;
-      gp[0] = o_gate[c][0]; gp[H] = o_gate[c][1]; gp[2 * H] = o_gate[c][2]; gp[3 * H] = o_gate[c][3];
-      res_c[e] = o_c[c];
-      res_h[e] = o_h[c];
-    }
-    if (l == a.L - 1) a.y[e] = o_h[c];
-    if (t == T - 1) {
-      if (a.hT) a.hT[((size_t)l * B + bb[c]) * H + unit] = o_h[c];
-      if (a.cT) a.cT[((size_t)l * B + bb[c]) * H + unit] = o_c[c];
-    }
   };
 
   // ---- one block: the matrix instructions of chain c's step t, then its reduction, gates and the store of h_t.
@@ -211,11 +198,17 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   //      else this chain's recurrent slot once more: valid memory, values unused, real fetch at the end of the
   //      block); the next block's own-layer counter; the store of h_t.  Nothing with a run-time count follows the
   //      store before the next block completes it.
-  auto block = [&](const int c, const int t) {
-    tr.mark(c, t, 0);
-    floatx16 acc[2];
+  floatx16 acc[2];
+  // ---- the first LAG groups of a block: operands long in registers, no memory request; issued together with the
+  //      other chain's gates (see fused below)
+  auto head = [&](const int c) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = 0.f;
+#pragma unroll
+    for (int g = 0; g < LAG; ++g) mma4(acc, wW[g], ring[c][g]);
+  };
+  auto block = [&](const int c, const int t) {
+    tr.mark(c, t, 0);
     const int tn = c == 0 ? t + 1 : t + 2;  // input slot of the other chain's next block: its step t (c == 0) or t + 1
     const bool other_next = tn <= T;        // that block exists
     int seen_in = PpWaiter<NL>::peek(in_flag(other_next ? tn : T, 1 - c));
@@ -224,7 +217,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     bool fetched = false;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
+    for (int g = LAG; g < NG; ++g) {
       if (g == LAG) {  // h_{l,t-1} of this chain must be published (slot 0 was written before the launch)
         PpWaiter<NL>::land(seen_rec);
         w.wait(flag(l, t, c), 8, t > 0 ? seen_rec : 8);
@@ -264,20 +257,78 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     tr.mark(c, t, 3);
     __syncthreads();
     tr.mark(c, t, 4);
+  };
+  // ---- after the barrier, first part (straight-line code): K-split sums, gates, the store of h_t, the six values
+  //      of the cell into the wave's corner of LDS
+  auto post_a = [&](const int c, const int t) {
     const float* const all = &part[(2 * t + c) & 1][0][0] + kk * 128 + 32 * q + p;
     float sg[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
       sg[g] = (all[g * 256] + all[1024 + g * 256]) + (all[2048 + g * 256] + all[3072 + g * 256]) + bias[g];
-    o_gate[c][0] = sigmoidf_dev(sg[0]); o_gate[c][1] = sigmoidf_dev(sg[1]); o_gate[c][2] = sigmoidf_dev(sg[2]);
-    o_gate[c][3] = tanhf_dev(sg[3]);
-    o_c[c] = o_gate[c][1] * c_state[c] + o_gate[c][0] * o_gate[c][3];
-    o_h[c] = o_gate[c][2] * tanhf_dev(o_c[c]);
-    c_state[c] = o_c[c];
+    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gc = tanhf_dev(sg[3]);
+    const float cn = gf * c_state[c] + gi * gc;
+    const float hn = go * tanhf_dev(cn);
+    c_state[c] = cn;
     // publish: the wave's 64 values are two whole 128-byte lines of the slot
-    __hip_atomic_store(slot(l, t + 1, c) + (size_t)s * 256 + kk * 128 + 32 * q + p, valid[c] ? o_h[c] : 0.f, __ATOMIC_RELAXED,
+    __hip_atomic_store(slot(l, t + 1, c) + (size_t)s * 256 + kk * 128 + 32 * q + p, valid[c] ? hn : 0.f, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
-    tr.mark(c, t, 5);
+    // The reserve and the outputs (nobody reads them before the kernel ends) go out right behind it, as 16-byte
+    // pieces: the wave's 8 rows x 8 units of each of the six arrays are transposed through a corner of LDS that only
+    // this wave touches.  Stores to memory retire slowly and in order with the loads: anywhere later they would sit
+    // in front of operands that the next block is about to need.
+    {
+      float* const st = &stage[q][0];
+      const int so = (p >> 2) * 8 + 2 * (p & 3) + kk;  // (row of the wave's eight, unit of the slice)
+      st[so] = gi; st[64 + so] = gf; st[128 + so] = go; st[192 + so] = gc; st[256 + so] = cn; st[320 + so] = hn;
+    }
+  };
+  // ---- second part: the reserve and the outputs as 16-byte pieces.  Every wave issues the same three stores in
+  //      every step, whatever its rows and the call want written: a piece that is not wanted goes to a scratch line.
+  //      With no branch around them the compiler knows how many requests are outstanding behind the counter that the
+  //      next block looks at, and waits for that counter alone instead of for these stores to reach memory.
+  auto post_b = [&](const int c, const int t) {
+    const float* const st = &stage[q][0];
+    const bool lastt = t == T - 1, top = l == a.L - 1;
+    float* const scratch_line = a.dummy + 4 * (lane & 7);
+    const int row = (lane >> 1) & 7, hf = lane & 1;
+    const int br = a.b0 + 64 * sl + 32 * c + 8 * q + row;
+    const bool in_batch = br < B;
+    const size_t e = ((size_t)t * B + br) * H + u0 + 4 * hf;
+    const size_t se = ((size_t)l * B + br) * H + u0 + 4 * hf;
+    {  // gates: piece (array lane/16, row, half)
+      const int arr = lane >> 4;
+      const floatx4 v = *reinterpret_cast<const floatx4*>(st + arr * 64 + row * 8 + 4 * hf);
+      float* const dst = (in_batch && a.keep) ? res_gates + ((size_t)t * B + br) * 4 * H + (size_t)arr * H + u0 + 4 * hf : scratch_line;
+      *reinterpret_cast<floatx4*>(dst) = v;
+    }
+    {  // lanes 0-15: c, lanes 16-31: h (upper lanes repeat them into the scratch line)
+      const int arr = 4 + ((lane >> 4) & 1);
+      const floatx4 v = *reinterpret_cast<const floatx4*>(st + arr * 64 + row * 8 + 4 * hf);
+      const bool mine = in_batch && lane < 32;
+      float* const dst = (mine && a.keep) ? (arr == 4 ? res_c : res_h) + e : scratch_line;
+      *reinterpret_cast<floatx4*>(dst) = v;
+      float* const dsty = (mine && top && arr == 5) ? a.y + e : scratch_line;
+      *reinterpret_cast<floatx4*>(dsty) = v;
+      if (lastt && mine) {
+        if (arr == 4 && a.cT) *reinterpret_cast<floatx4*>(a.cT + se) = v;
+        if (arr == 5 && a.hT) *reinterpret_cast<floatx4*>(a.hT + se) = v;
+      }
+    }
+  };
+  // ---- a chain's gates and stores have no matrix instruction of their own chain to hide behind, but the other
+  //      chain's next block has: its first LAG groups are issued in between (one matrix instruction, then a
+  //      handful of the other instructions, and so on)
+  auto fused = [&](const int cp, const int tp, const int cn) {
+    post_a(cp, tp);
+    head(cn);
+#pragma unroll
+    for (int i = 0; i < 4 * LAG; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one matrix instruction
+      __builtin_amdgcn_sched_group_barrier(0x7f7, 8, 0);   // up to eight of anything else
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    post_b(cp, tp);
   };
 
   // ---- chain 0's first input operand (chain 1's is requested by chain 0's first block)
@@ -287,11 +338,21 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
 #pragma unroll
     for (int i = 0; i < NK8; ++i) ring[0][i] = ldx(src, i);
   }
+  // (the loop is rotated so that every look at a counter follows the stores before it in straight-line code)
+  head(0);
+  hide(rv);
+  block(0, 0);
   for (int t = 0; t < T; ++t) {
-    hide(rv);
-    block(0, t);
+    fused(0, t, 1);
     block(1, t);
+    if (t + 1 < T) {
+      hide(rv);
+      fused(1, t, 0);
+      block(0, t + 1);
+    }
   }
+  post_a(1, T - 1);
+  post_b(1, T - 1);
   complete(1, T - 1, true);  // chain 0's last publication was completed inside chain 1's last block
 }
 
@@ -341,7 +402,7 @@ hipError_t launch_pp(int grid, const PersFwdArgs& a, hipStream_t s) {
   constexpr int NK8 = HH / 32;
   // the other chain's publication is completed a quarter of an operand half into a block, the fetch of its next
   // input starts half an operand half in (measured at H = 512: later completion or later fetch are 1-2 % slower)
-  const void* fn = (const void*)pers_fwd_pp_kernel<HH, NK8 / 4 + 1, NK8 / 2>;
+  const void* fn = (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2>;
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
   return launch_resident(fn, grid, params, 0, s);
 }
