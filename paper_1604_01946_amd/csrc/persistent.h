@@ -7,6 +7,7 @@
 //   persistent_narrow.hip pers_fwd_kernel / pers_bwd_kernel: tiles of 16 batch rows (B <= 32, slices of 16 / 32 rows)
 //   persistent_wide.hip   pers_fwd32_kernel / pers_bwd32_kernel: slices of 64 rows, 32x32x2 tiles, templated on the cell
 //   persistent_pp.hip     pers_fwd_pp_kernel: two half-slices of 32 rows alternating on the matrix cores
+//   persistent_bpp.hip    pers_bwd_pp_kernel: two quarter-slices of 16 rows alternating on the matrix cores
 //   persistent_large.hip  pers_fwdL_kernel / pers_bwdL_kernel: one layer per launch, H = 1024 / 2048
 //   persistent.hip        host side: residency, launches, which shapes run where, layer groups, batch slices
 #pragma once
@@ -88,6 +89,7 @@ struct PersBwdArgs {
   long long* trace;
   int trace_block;
   const float* h0;     // [L][B][H] or null: read by the GRU variant of the wide kernel
+  float* dummy;        // pers_bwd_pp_kernel: 128 bytes of scratch that take the stores nobody wants
 };
 
 // Exchange layout of a slot (H x 32 floats): for k = wave*H/4 + 8*k8 + 2*m + kk and batch row n,
@@ -166,6 +168,10 @@ hipError_t launch_pack_x32(const float* x, float* xin, int* flags, int L, int T,
 hipError_t launch_fwd_pp(int H, int grid, const PersFwdArgs& a, hipStream_t s);
 hipError_t launch_pack_state_pp(const float* h0, float* hx, int L, int T, int B, int H, int b0, int nsl, hipStream_t s);
 hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int b0, int nsl, hipStream_t s);
+
+// backward counterpart: two chains of 16 rows per workgroup (batch half), 16x16x4 tiles; counters of H/16 lines per
+// (layer, step, half, chain), see persistent_bpp.hip
+hipError_t launch_bwd_pp(int H, const PersBwdArgs& a, int nbh, hipStream_t s);
 
 hipError_t launch_fwdL_any(int H, int cell, const PersFwdLArgs& k, hipStream_t s);
 hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s);

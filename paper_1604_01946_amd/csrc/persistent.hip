@@ -699,7 +699,10 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
     k.db = a.db;
   }
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
-  k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+  // two alternating chains per workgroup (LSTM, slices of 64 rows): counters of H/16 lines per (layer, step, quarter)
+  const bool pp = wide && cell == 0 && knobs().pingpong != 0;
+  k.dummy = reinterpret_cast<float*>(a.ws + a.w.scratch);
+  k.trace = (g_trace_bytes >= (size_t)d.T * 64 * (pp ? 2 : 1)) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;
   const int grid = d.L * (d.H / 8);
   // slices of 64 batch rows side by side while the CUs last (see run_forward_persistent): for the wide kernel a
@@ -716,15 +719,17 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
     k.b0 = slice_rows * s0;
     {
       ProfScope ps(LSTM_PHASE_BWD_PACK, s);
-      CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * 2 * kFlagInts * 4, s), "zero step counters");
+      const size_t per_slot = pp ? (size_t)4 * (d.H / 16) * kFlagStride : (size_t)2 * kFlagInts;  // ints per (slice, layer, step)
+      CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 2) * per_slot * 4, s), "zero step counters");
     }
     ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
     {  // dh products of every layer, dx products of the layers above the first, and layer 0's when the kernel writes dx itself
       const double rows = std::min(slice_rows * nsl, d.B - k.b0), per = 2.0 * GW * rows * d.T;
-      prof_flops(per * d.H * (2 * d.L - 1) + (k.dx0 ? per * d.I : 0.0), wide ? "pers_bwd32_kernel" : "pers_bwd_kernel");
+      prof_flops(per * d.H * (2 * d.L - 1) + (k.dx0 ? per * d.I : 0.0), pp ? "pers_bwd_pp_kernel" : (wide ? "pers_bwd32_kernel" : "pers_bwd_kernel"));
     }
     hipError_t e = hipErrorInvalidValue;
-    if (wide) e = launch_bwd_wide(cell, d.H, k, 2 * nsl, s);
+    if (pp) e = launch_bwd_pp(d.H, k, 2 * nsl, s);
+    else if (wide) e = launch_bwd_wide(cell, d.H, k, 2 * nsl, s);
     else e = launch_bwd_narrow(d.H, bp, grid * nsl, k, s);
     CK(e, "persistent backward launch");
   }

@@ -155,6 +155,45 @@ __device__ __forceinline__ void signal(int* flag, int full) {
   if (threadIdx.x == 0) __hip_atomic_fetch_add(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Counter of NL lines: lane i polls line i % NL; every line must reach `each` arrivals.
+template <int NL>
+struct PpWaiter {
+  int* watchdog;
+  int limit;
+  bool dead;
+  static __device__ __forceinline__ int peek(int* flag) {
+    return __hip_atomic_load(flag + (threadIdx.x & (NL - 1)) * kFlagStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  static __device__ __forceinline__ void land(int& v) { asm volatile("" : "+v"(v)); }
+  // `seen`: a value peeked earlier.  A wait that has to poll ends with every outstanding memory operation complete.
+  __device__ __forceinline__ void wait(int* flag, int each, int seen) {
+    if (!dead && !__all(seen >= each)) {
+      int spins = 0;
+      while (!__all(peek(flag) >= each)) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > limit) {
+          dead = true;
+          __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          break;
+        }
+      }
+      drain_vmem();
+    }
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  }
+};
+
+struct PpTracer {
+  long long* buf;  // [2 chains][T][8]
+  int T;
+  __device__ __forceinline__ void mark(int c, int step, int slot) const {
+    if (buf && threadIdx.x == 0) {
+      buf[((size_t)c * T + step) * 8 + slot] = wall_clock64();
+      if (slot == 0) buf[((size_t)c * T + step) * 8 + 7] = clock64();
+    }
+  }
+};
+
 // blockIdx -> (layer, slice).  Workgroups are dealt round-robin to the 8 XCDs, each with its
 // own L2; keeping a layer on 8/L XCDs lets its exchange reads be served by few L2s.
 __device__ __forceinline__ void map_block(int L, int NS, int& l, int& s) {
