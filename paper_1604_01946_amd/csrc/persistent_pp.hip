@@ -44,7 +44,7 @@ namespace {
 
 constexpr int pp_count(int lo, int hi, int upto) { return upto < lo ? 0 : ((upto < hi ? upto : hi) - lo + 1); }
 
-template <int HH, int GA_, int PF_>
+template <int HH, int GA_, int PF_, bool TRACE>
 __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   constexpr int H = HH, G = 4 * H, NS = H / 8, NL = H / 16;
   constexpr int NK8 = H / 32;        // 8-k groups per wave and operand half (K-quarter of H)
@@ -68,7 +68,12 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   const int kk = lane >> 5, n = lane & 31;
   const int u0 = 8 * s;
   const size_t TB = (size_t)T * B;
-  const int rot = ((int)(blockIdx.x >> 3) + q) & (NK8 - 1);
+  // The waves of a layer read a slot in orders rotated against each other (all of them would otherwise ask the same
+  // L2 lines at the same time).  The rotation is a multiple of four groups, so that the address of a request is a scalar
+  // base plus the lane's fixed offset plus an immediate: scalar arithmetic costs a wave that runs matrix instructions
+  // back to back nothing, every vector instruction costs its full issue time (one wave per SIMD: nothing else to issue).
+  constexpr int NR4 = NK8 / 4 > 0 ? NK8 / 4 : 1;
+  const int rot = NK8 >= 4 ? 4 * (((int)(blockIdx.x >> 3) + q) & (NR4 - 1)) : 0;
 
   // ---- weights -> registers.  A operand of group register i (k8 = (i + rot) % NK8), k-pair j:
   //      row rho = lane % 32 = 8*gate + 4*par + cc holds unit 2*cc + par; k = q*H/4 + 8*k8 + 2*j + kk
@@ -116,7 +121,6 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * 2 * NL * kFlagStride;
   auto slot = [&](int layer, int st, int c) { return hx + (((size_t)layer * (T + 1) + st) * 2 + c) * H * 32; };
   auto flag = [&](int layer, int st, int c) { return flags + (((size_t)layer * (T + 1) + st) * 2 + c) * NL * kFlagStride; };
-  const size_t boff = (size_t)q * (H / 4) * 32 + lane * 4;  // this lane's offset inside a slot (first group of its K-quarter)
   const int arrive_line = ((4 * s + q) & (NL - 1)) * kFlagStride;
   // the layer below is, for layer 0, the input sequence itself: x in exchange layout, all of it there before the launch
   const bool in_is_x = l == 0;
@@ -125,17 +129,33 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   auto in_flag = [&](int st, int c) { return in_is_x ? flag(0, 0, c) : flag(l - 1, st, c); };  // x: never waited for
 
   PpWaiter<NL> w{a.watchdog, a.spin_limit, false};
-  const PpTracer tr{(a.trace && (int)blockIdx.x == a.trace_block) ? a.trace : nullptr, T};
+  // time stamps of one workgroup's phases (diagnostic hook; a kernel instance of its own, so that the normal one carries
+  // neither the branches nor the registers)
+  const PpTracer trc{(TRACE && a.trace && (int)blockIdx.x == a.trace_block) ? a.trace : nullptr, T};
+  struct {
+    const PpTracer& t;
+    __device__ __forceinline__ void mark(int c, int step, int slot) const {
+      if constexpr (TRACE) t.mark(c, step, slot);
+    }
+  } tr{trc};
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
 
-  int rv = rot;
-  auto ldx = [&](const float* src, int i) {
-    return *reinterpret_cast<const floatx4*>(src + (size_t)((i + rv) & (NK8 - 1)) * 256);
+  int rv = rot >> 2;
+  // The lane offset as a 32-bit register that the optimiser meets anew in every block (fresh_lo): next to the scalar
+  // base it then becomes the offset operand of the request instead of one 64-bit vector addition per request.
+  unsigned lo = lane * 16;
+  auto fresh_lo = [&]() {
+    lo = lane * 16;
+    asm volatile("" : "+v"(lo));
   };
-  // two accumulators, alternating, summed at the end of the block
-  auto mma4 = [&](floatx16 (&acc)[2], const float (&wgt)[4], const floatx4& bv) {
+  auto ldx = [&](const float* src, int i) {  // src: the slot (wave-uniform); group i of this wave's K quarter
+    const char* const sb = reinterpret_cast<const char*>(src) +
+                           ((size_t)q * NK8 + (NK8 >= 4 ? 4 * (((i >> 2) + rv) & (NR4 - 1)) : 0)) * 1024;
+    return *reinterpret_cast<const floatx4*>(sb + lo + (NK8 >= 4 ? (i & 3) : i) * 1024);
+  };
+  auto mma4 = [&](floatx16& acc, const float (&wgt)[4], const floatx4& bv) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j & 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(wgt[j], bv[j], acc[j & 1], 0, 0, 0);
+    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wgt[j], bv[j], acc, 0, 0, 0);
   };
 
   // Operands of a chain, one register quad per group: at the start of the chain's block its ring holds the whole
@@ -159,12 +179,12 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   //      else this chain's recurrent slot once more: valid memory, values unused, real fetch at the end of the
   //      block); the next block's own-layer counter; the store of h_t.  Nothing with a run-time count follows the
   //      store before the next block completes it.
-  floatx16 acc[2];
+  floatx16 acc;
   // ---- the first LAG groups of a block: operands long in registers, no memory request; issued together with the
   //      other chain's gates (see fused below)
   auto head = [&](const int c) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[0][r] = acc[1][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 #pragma unroll
     for (int g = 0; g < LAG; ++g) mma4(acc, wW[g], ring[c][g]);
   };
@@ -173,7 +193,8 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     const int tn = c == 0 ? t + 1 : t + 2;  // input slot of the other chain's next block: its step t (c == 0) or t + 1
     const bool other_next = tn <= T;        // that block exists
     int seen_in = PpWaiter<NL>::peek(in_flag(other_next ? tn : T, 1 - c));
-    const float* const rsrc = slot(l, t, c) + boff;
+    const float* const rsrc = slot(l, t, c);
+    fresh_lo();
     const float* nsrc = rsrc;
     bool fetched = false;
     __builtin_amdgcn_sched_barrier(0);
@@ -183,24 +204,28 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
         PpWaiter<NL>::land(seen_rec);
         w.wait(flag(l, t, c), 8, t > 0 ? seen_rec : 8);
         tr.mark(c, t, 2);
+        fresh_lo();  // (after every branch: the offset has to be defined in the basic block of the requests)
       }
       if (g == PF) {
         PpWaiter<NL>::land(seen_in);
         fetched = other_next && !w.dead && (in_is_x || __all(seen_in >= 8));
-        if (fetched) nsrc = in_slot(tn, 1 - c) + boff;
+        if (fetched) nsrc = in_slot(tn, 1 - c);
       }
       const floatx4 cur = ring[c][g % NK8];
       if (g >= LAG && g < LAG + NK8) ring[c][g - LAG] = ldx(rsrc, g - LAG);
       if (g >= PF && g < PF + NK8) ring[1 - c][g - PF] = ldx(nsrc, g - PF);
       if (g < NK8) mma4(acc, wW[g], cur);
       else mma4(acc, wR[g - NK8], cur);
-      if (g == GA && (c == 1 || t > 0)) complete(1 - c, c == 1 ? t : t - 1, false);  // the other chain's previous step
+      if (g == GA) {
+        if (c == 1 || t > 0) complete(1 - c, c == 1 ? t : t - 1, false);  // the other chain's previous step
+        fresh_lo();
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     tr.mark(c, t, 1);
     if (other_next && !fetched) {  // the layer below was late: wait for it now (before this chain's store)
       w.wait(in_flag(tn, 1 - c), 8, 0);
-      const float* src = in_slot(tn, 1 - c) + boff;
+      const float* src = in_slot(tn, 1 - c);
 #pragma unroll
       for (int i = 0; i < NK8; ++i) ring[1 - c][i] = ldx(src, i);
     }
@@ -208,8 +233,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
 #pragma unroll
     for (int g = 0; g < 4; ++g)
       *reinterpret_cast<floatx4*>(mine + ((g * 2 + kk) * 32 + n) * 4) =
-          floatx4{acc[0][4 * g] + acc[1][4 * g], acc[0][4 * g + 1] + acc[1][4 * g + 1], acc[0][4 * g + 2] + acc[1][4 * g + 2],
-                  acc[0][4 * g + 3] + acc[1][4 * g + 3]};
+          floatx4{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
     // the own-layer counter that the next block (the other chain's) waits for: read now, looked at LAG groups into it
     {
       const int st = c == 0 ? t : t + 1;  // that block is (1, t) or (0, t + 1): it needs h of step st - 1
@@ -295,7 +319,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   // ---- chain 0's first input operand (chain 1's is requested by chain 0's first block)
   {
     if (!in_is_x) w.wait(in_flag(1, 0), 8, 0);
-    const float* src = in_slot(1, 0) + boff;
+    const float* src = in_slot(1, 0);
 #pragma unroll
     for (int i = 0; i < NK8; ++i) ring[0][i] = ldx(src, i);
   }
@@ -363,7 +387,8 @@ hipError_t launch_pp(int grid, const PersFwdArgs& a, hipStream_t s) {
   constexpr int NK8 = HH / 32;
   // the other chain's publication is completed a quarter of an operand half into a block, the fetch of its next
   // input starts half an operand half in (measured at H = 512: later completion or later fetch are 1-2 % slower)
-  const void* fn = (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2>;
+  const void* fn = a.trace ? (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2, true>
+                           : (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2, false>;
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
   return launch_resident(fn, grid, params, 0, s);
 }
