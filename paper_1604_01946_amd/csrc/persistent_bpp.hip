@@ -76,7 +76,7 @@ __device__ __forceinline__ gfloat* pick(bool c, const float* p, const float* q) 
   return reinterpret_cast<gfloat*>(x);
 }
 
-template <int HH, int GA_, int PL_, int HB_, int KH_, int FUSE_N_, bool TRACE>
+template <int HH, int GA_, int PL_, int KH_, int FUSE_N_, bool TRACE>
 __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, const int NBH) {
   constexpr int H = HH, G = 4 * H, NS2 = H / 16, NL = NS2;
   constexpr int NU = H / 16;             // groups of four units per wave (its K quarter)
@@ -84,11 +84,10 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   constexpr int LG = NU - RG;            // groups whose weights live in LDS
   constexpr int GA = GA_;                // group of phase B at which the chain's publication is completed
   constexpr int PL = PL_;                // group of phase B from which the next phase A's operands are requested
-  constexpr int HB = HB_;                // operand groups of the next phase A requested in phase B (the rest in that phase A)
   constexpr int KH = KH_;                // groups of phase B that are issued in between the instructions of post()
   constexpr int FUSE_N = FUSE_N_;        // instructions of post() per matrix instruction there
   constexpr int KM = KH - 3;             // groups in between the arithmetic of the point-wise stage
-  static_assert(GA >= 1 && GA < NU && PL >= KH && PL < NU && HB >= 1 && HB <= NU && KH >= 4 && KH < NU && (LG == 0 ? KH <= RG : KH + 2 <= RG), "schedule");
+  static_assert(GA >= 1 && GA < NU && PL >= KH && PL < NU && KH >= 4 && KH < NU && (LG == 0 ? KH <= RG : KH + 2 <= RG), "schedule");
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float* const part = smem;          // [2 tiles: dh, dx][2 chains][4 waves][64 lanes][4]
   float* const stage = smem + 4096;  // [4 waves][256]
@@ -179,11 +178,20 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   float* const dx_out = l > 0 ? a.dxbuf + (size_t)l * TB * H : a.dx0;
   const bool dx_wanted = l > 0 || a.dx0;
   float* const dummy = a.dummy + (size_t)blockIdx.x * 32 + (lane & 31);  // a line of this workgroup's own
-  auto slot = [&](int t, int c) { return a.dAx + (((size_t)l * T + t) * NQ + 2 * bh + c) * G * 16; };
+  // (lq, bq: the layer and batch half as values that the optimiser meets anew in every phase -- the slot and counter
+  // addresses are then worked out where they are used, with scalar instructions that cost the wave nothing, instead of
+  // being kept in registers across the whole step: the kernel is short of scalar registers, and each one that spills
+  // comes back through a vector instruction)
+  int lq = l, bq = bh;
+  auto rehide = [&]() {
+    hide(lq);
+    hide(bq);
+  };
+  auto slot = [&](int t, int c) { return a.dAx + (((size_t)lq * T + t) * NQ + 2 * bq + c) * G * 16; };
   // a slot that no step uses (the exchange array holds T + 1 slots per layer, the steps use T)
-  auto spare = [&](int c) { return a.dAx + (((size_t)a.L * T + l) * NQ + 2 * bh + c) * G * 16; };
+  auto spare = [&](int c) { return a.dAx + (((size_t)a.L * T + lq) * NQ + 2 * bq + c) * G * 16; };
   auto flag = [&](int layer, int st, int c) {
-    return a.flags + ((((size_t)layer * (T + 2) + st) * NQ + 2 * bh + c) * NL) * kFlagStride;
+    return a.flags + ((((size_t)layer * (T + 2) + st) * NQ + 2 * bq + c) * NL) * kFlagStride;
   };
   const int arrive_line = ((4 * s2 + w) & (NL - 1)) * kFlagStride;
 
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
 
   // ---- reserve values and upstream gradient of a chain's next point-wise stage
   float gi[2], gf[2], go[2], gg[2], ct[2], cp[2], dpre[2];
-  bool cp_real[2], up_ok[2] = {false, false};
+  bool cp_real[2];
   auto fetch_res = [&](const int c, const int t) {
     const float* const pg = res_gates + (size_t)t * B * G + goff[c];
     gi[c] = pg[0];
@@ -260,12 +268,11 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
 
   // ---- arrival of this wave on the counter of chain c, slot st (its stores up to here are acknowledged)
   auto arrive = [&](const int c, const int st) {
-    if (lane == 0) __hip_atomic_fetch_add(flag(l, st, c) + arrive_line, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) __hip_atomic_fetch_add(flag(lq, st, c) + arrive_line, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
 
   int seen_next = 0, seen_up = 0;
   floatx4 op[2][NU];               // B operands of a chain's step: requested during the other chain's phase B, kept until its own
-  bool ready[2] = {false, false};  // the operands of the chain's next phase A have been requested
   int rv = rot >> 2;
   // The lane offset as a 32-bit register that the optimiser meets anew in every phase (fresh_lo): next to the scalar base
   // it then becomes the offset operand of the request instead of one 64-bit vector addition per request.
@@ -279,21 +286,13 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     return *reinterpret_cast<const floatx4*>(sb + lo + (i & 3) * 1024);
   };
   // counter that stands for "dx of (chain c, step t) of the layer above is published" (see the phases below)
-  auto up_flag = [&](const int c, const int t) { return c == 0 ? flag(l + 1, t + 1, 1) : flag(l + 1, t, 0); };
+  auto up_flag = [&](const int c, const int t) { return c == 0 ? flag(lq + 1, t + 1, 1) : flag(lq + 1, t, 0); };
 
   // ---- phase A of chain c, step t: the recurrent half of the product, dh_{t-1} = R_l^T dA_t for the workgroup's
   //      units (the half that the chain's next point-wise stage waits for); no memory request at all
   auto phaseA = [&](const int c, const int t) {
+    rehide();
     mark(c, t, 0);
-    const float* const asrc = slot(t, c);
-    fresh_lo();
-    if (!ready[c]) {  // the counter was not complete when the phase before this one looked
-      wt.wait(flag(l, t + 2, c), 4, 0);
-#pragma unroll
-      for (int i = 0; i < HB; ++i) op[c][i] = ldx(asrc, i);
-      drain_vmem();  // a branch that issues requests ends with none outstanding: the compiler's count of what is
-                     // outstanding behind a register is then the count of the straight path
-    }
     floatx4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};
     floatx4 al[NU > RG ? NU - RG : 1];
     auto ldw = [&](int g) {
@@ -306,7 +305,6 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     for (int g = 0; g < NU; ++g) {
       if (g + 2 >= RG) ldw(g + 2);  // LDS part of the weights, two groups ahead
       if (g == 0 && RG < 2) ldw(RG);
-      if (g + HB < NU) op[c][g + HB] = ldx(asrc, g + HB);  // the operand groups that phase B left, HB groups ahead
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float a0 = g < RG ? wreg[g % RG][j][0] : al[g < RG ? 0 : g - RG][j];
@@ -318,7 +316,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
         // requested: an operand that has arrived means those stores are acknowledged.
         asm volatile("" : "+v"(op[c][0]));
         if (lane == 0 && tb < T)
-          __hip_atomic_fetch_add(flag(l, tb + 1, o) + arrive_line, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(flag(lq, tb + 1, o) + arrive_line, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -327,8 +325,8 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     // so that looking at them does not wait for those stores to reach memory
     {
       const int o = 1 - c, tn = c == 0 ? t : t - 1;
-      seen_next = PpWaiter<NL>::peek(tn >= 0 ? flag(l, tn + 2, o) : flag(l, t + 2, c));
-      seen_up = PpWaiter<NL>::peek((has_up && t > 1) ? up_flag(c, t - 2) : flag(l, t + 2, c));
+      seen_next = PpWaiter<NL>::peek(tn >= 0 ? flag(lq, tn + 2, o) : flag(lq, t + 2, c));
+      seen_up = PpWaiter<NL>::peek((has_up && t > 1) ? up_flag(c, t - 2) : flag(lq, t + 2, c));
     }
     *reinterpret_cast<floatx4*>(part + (c * 4 + w) * 256 + lane * 4) = acc;
     mark(c, t, 2);
@@ -364,11 +362,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     }
   };
   auto fused = [&](const int c, const int t) {
-    if (t > 0 && !up_ok[c]) {  // the layer above was late (or never looked at): wait for its dx of step t-1 now
-      if (has_up) wt.wait(up_flag(c, t - 1), 4, 0);
-      fetch_dout(c, t - 1);
-      drain_vmem();
-    }
+    rehide();
     const int o = 1 - c;
     const bool real = t > 0;
     const int tdx = c == 0 ? t + 1 : t;  // step of the other chain's last phase B (none before the very first phase A)
@@ -407,14 +401,16 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     mark(c, t, 4);
   };
   auto b_rest = [&](const int c, const int t) {
+    rehide();
     const int o = 1 - c;
     const int tn = c == 0 ? t : t - 1;  // the next phase A is (o, tn)
     const bool has_next = tn >= 0;
     const int tq = t > 1 ? t - 2 : 0;   // step of this chain's next point-wise stage (in post(c, t-1)), if any
     const bool has_pw = t > 1;
     fetch_res(c, tq);
-    const float* nsrc = slot(t, c);
-    fresh_lo();  // valid and long complete: stands in when the next operands may not be read yet
+    // operands of the next phase A; when there is none, this chain's own slot once more (valid memory, values unused),
+    // so that every step issues the same requests
+    const float* const nsrc = has_next ? slot(tn, o) : slot(t, c);
     floatx4 al[NU > RG ? NU - RG : 1];
     auto ldw = [&](int g) {
       if (g >= RG && g < NU) al[g - RG] = *reinterpret_cast<const floatx4*>(wl + ((((size_t)w * LG + (g - RG)) * 2 + 1) * 64 + lane) * 4);
@@ -424,15 +420,19 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     for (int g = KH; g < NU; ++g) {
       if (g + 2 >= RG) ldw(g + 2);
       if (g == PL) {
+        // The counters were read before this chain's post(); they are almost always complete (the publications they
+        // count are two phases old).  When one is not, the wave polls right here: nothing that it could do instead
+        // would get it past the next barrier any sooner, and no other workgroup waits for this one meanwhile (every
+        // counter that it feeds was fed before this phase).
         PpWaiter<NL>::land(seen_next);
         PpWaiter<NL>::land(seen_up);
-        ready[o] = has_next && !wt.dead && __all(seen_next >= 4);
-        up_ok[c] = has_pw && !wt.dead && (!has_up || __all(seen_up >= 4));
-        if (ready[o]) nsrc = slot(tn, o);
-        fetch_dout(c, up_ok[c] ? tq : (t > 0 ? t - 1 : 0));  // else a row that this lane has read before
+        if (has_next) wt.wait(flag(lq, tn + 2, o), 4, seen_next);
+        if (has_up && has_pw) wt.wait(up_flag(c, tq), 4, seen_up);
+        fetch_dout(c, tq);
+        fresh_lo();
       }
-      if (g >= PL) {  // operand groups [lo, hi) of the next phase A: HB of them spread evenly over groups PL..NU-1
-        constexpr int span = NU - PL;
+      if (g >= PL) {  // operand groups [lo, hi) of the next phase A, spread evenly over groups PL..NU-1
+        constexpr int span = NU - PL, HB = NU;
         const int lo = ((g - PL) * HB) / span, hi = ((g - PL + 1) * HB) / span;
 #pragma unroll
         for (int j = lo; j < hi; ++j) op[o][j] = ldx(nsrc, j);
@@ -457,11 +457,22 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     if (has_up) wt.wait(up_flag(c, T - 1), 4, 0);
     fetch_dout(c, T - 1);
     pointwise(c, T - 1, true);
-    fetch_res(c, T > 1 ? T - 2 : 0);  // for the stage in the first post(); later ones are requested a step ahead in phase B
   }
   drain_vmem();
   arrive(0, T + 1);
   arrive(1, T + 1);
+  // what the first phases need and later ones find requested by the phase B before them: the reserve values and the
+  // upstream gradient of step T-2 (for the point-wise stage in the first post() of either chain), and chain 0's operands
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    fetch_res(c, T > 1 ? T - 2 : 0);
+    if (has_up && T > 1) wt.wait(up_flag(c, T - 2), 4, 0);
+    fetch_dout(c, T > 1 ? T - 2 : 0);
+  }
+  wt.wait(flag(lq, T + 1, 0), 4, 0);
+  fresh_lo();
+#pragma unroll
+  for (int i = 0; i < NU; ++i) op[0][i] = ldx(slot(T - 1, 0), i);
   for (int t = T - 1; t >= 0; --t) {
     hide(rv);
     phaseA(0, t);
@@ -519,8 +530,8 @@ hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
   // instruction; the next phase A's operands are all requested during the rest of phase B.
   constexpr int KH = NU / 4 < 4 ? 4 : NU / 4;
   const bool trace = a.trace != nullptr;
-  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, KH, NU, KH, 6, true>
-                         : (const void*)pers_bwd_pp_kernel<HH, 1, KH, NU, KH, 6, false>;
+  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, KH, KH, 6, true>
+                         : (const void*)pers_bwd_pp_kernel<HH, 1, KH, KH, 6, false>;
   static bool attr_set[2] = {false, false};
   if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set[trace ? 1 : 0]); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
