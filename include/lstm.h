@@ -196,6 +196,20 @@ int lstm_gemm_f32(int M, int N, int K,
                   const float* B, long sBk, long sBn,
                   float* C, long ldc, int accumulate, void* stream);
 
+/*
+ * The same product with a scratch buffer (device memory, 16-byte aligned, scratch_bytes long, NULL: none; it must
+ * stay untouched until the stream has passed the call).  A product whose 128 x 128 tiles do not fill the chip evenly --
+ * fewer tiles than the chip holds workgroups, or a last round with few tiles -- has the tile rows of that round cut
+ * along K into as many slices as fill the chip once more; the slices' partial tiles go to the scratch buffer and are
+ * added in a fixed order, so the result is repeatable and differs from lstm_gemm_f32's only by the order of the
+ * additions.  Too small a buffer means fewer slices or none (never an error).  This is how the LSTM calls run the
+ * time-batched products of Section 2.3 at large hidden sizes (M = T*B = 1600 rows leave 832 tiles for 768 places).
+ */
+int lstm_gemm_f32_ws(int M, int N, int K,
+                  const float* A, long sAm, long sAk,
+                  const float* B, long sBk, long sBn,
+                  float* C, long ldc, int accumulate, void* scratch, size_t scratch_bytes, void* stream);
+
 /* Which path LSTM_PATH_AUTO resolves to for this shape on the current device
  * (returns an LSTM_PATH_* value; LSTM_PATH_AUTO on invalid dimensions). */
 unsigned lstm_auto_path(int L, int T, int B, int I, int H, int backward);

@@ -29,7 +29,7 @@ LSTM_PATH_PERSISTENT = 6
 PATH_NAMES = {0: "auto", 1: "naive", 2: "grouped", 3: "fused", 4: "step", 5: "wavefront", 6: "persistent"}
 
 EXPORTS = [
-    "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32",
+    "lstm_reserve_bytes", "lstm_workspace_bytes", "lstm_forward", "lstm_backward", "lstm_gemm_f32", "lstm_gemm_f32_ws",
     "lstm_init", "lstm_forward_noalloc",
     "lstm_auto_path", "lstm_set_path", "lstm_set_wavefront_chunks", "lstm_status_string", "lstm_last_error", "lstm_shutdown",
     "lstm_profile_enable", "lstm_profile_read", "lstm_profile_kernel", "lstm_phase_name", "lstm_debug_set_trace",
@@ -69,6 +69,8 @@ def library():
         lib.lstm_forward_noalloc.argtypes = [i] * 5 + [p] * 10 + [p, u]
         lib.lstm_gemm_f32.restype = i
         lib.lstm_gemm_f32.argtypes = [i, i, i, p, l, l, p, l, l, p, l, i, p]
+        lib.lstm_gemm_f32_ws.restype = i
+        lib.lstm_gemm_f32_ws.argtypes = [i, i, i, p, l, l, p, l, l, p, l, i, p, ctypes.c_size_t, p]
         lib.lstm_auto_path.restype = u
         lib.lstm_auto_path.argtypes = [i] * 6
         lib.lstm_set_path.restype = i
@@ -201,6 +203,11 @@ def lstm_backward(L, T, B, I, H, x, h0, c0, W, R, reserve, dy, dhT, dcT, dx, dh0
 def lstm_gemm_f32(M, N, K, A, sAm, sAk, Bm, sBk, sBn, C, ldc, accumulate, stream=None):
     return library().lstm_gemm_f32(M, N, K, _ptr(A), sAm, sAk, _ptr(Bm), sBk, sBn, _ptr(C), ldc, int(accumulate),
                                    _stream(stream))
+
+
+def lstm_gemm_f32_ws(M, N, K, A, sAm, sAk, Bm, sBk, sBn, C, ldc, accumulate, scratch, scratch_bytes, stream=None):
+    return library().lstm_gemm_f32_ws(M, N, K, _ptr(A), sAm, sAk, _ptr(Bm), sBk, sBn, _ptr(C), ldc, int(accumulate),
+                                      _ptr(scratch), ctypes.c_size_t(scratch_bytes), _stream(stream))
 
 
 def lstm_profile_enable(on):

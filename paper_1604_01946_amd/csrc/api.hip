@@ -49,6 +49,7 @@ const Knobs& knobs() {
     Knobs k;
     k.no_pad = env_is("LSTM_NO_PAD", '1');
     k.gemm_staged = env_is("LSTM_GEMM_STAGED", '1');
+    k.gemm_split = !env_is("LSTM_GEMM_SPLIT", '0');
     k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
     const char* ff = getenv("LSTM_FULL_FENCES");
     k.full_fences = ff && *ff && *ff != '0';
@@ -466,6 +467,17 @@ int lstm_gemm_f32(int M, int N, int K, const float* A, long sAm, long sAk, const
   if ((sAm != 1 && sAk != 1) || (sBk != 1 && sBn != 1)) return LSTM_INVALID_ARG;
   GemmProblem p{A, B, C, M, N, K, sAm, sAk, sBk, sBn, ldc, accumulate};
   if (record(launch_gemm_group(&p, 1, (hipStream_t)stream), "gemm launch") != hipSuccess) return LSTM_HIP_ERROR;
+  return LSTM_OK;
+}
+
+int lstm_gemm_f32_ws(int M, int N, int K, const float* A, long sAm, long sAk, const float* B, long sBk, long sBn,
+                     float* C, long ldc, int accumulate, void* scratch, size_t scratch_bytes, void* stream) {
+  if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C || ldc < N) return LSTM_INVALID_ARG;
+  if ((sAm != 1 && sAk != 1) || (sBk != 1 && sBn != 1)) return LSTM_INVALID_ARG;
+  if (scratch && (reinterpret_cast<uintptr_t>(scratch) & 15u) != 0) return LSTM_INVALID_ARG;
+  GemmProblem p{A, B, C, M, N, K, sAm, sAk, sBk, sBn, ldc, accumulate};
+  if (record(launch_gemm_split(p, (float*)scratch, scratch ? scratch_bytes : 0, (hipStream_t)stream), "gemm launch") != hipSuccess)
+    return LSTM_HIP_ERROR;
   return LSTM_OK;
 }
 

@@ -15,6 +15,7 @@
 #include "knobs.h"
 
 #include <stdlib.h>
+#include <algorithm>
 #include <type_traits>
 
 namespace lstm {
@@ -27,7 +28,23 @@ struct GemmGroupArgs {
   GemmProblem p[kMaxGemmGroup];
   int tile_start[kMaxGemmGroup + 1];
   int nprob;
+  int n_main;  // tiles [0, n_main) are dispatched before the rest (launch_gemm_split: whole tiles before K slices)
 };
+
+// blockIdx -> tile index.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): remap so that one
+// XCD works on a contiguous run of tiles, which share operand panels -- separately for the tiles before and from
+// n_main on, so that the hardware's dispatch order (ascending blockIdx) still reaches every tile of the first part
+// before any of the second.
+__device__ __forceinline__ int tile_index(const GemmGroupArgs& g) {
+  int bid = blockIdx.x, lo = 0, n = g.n_main;
+  if (bid >= n) {
+    lo = n;
+    n = (int)gridDim.x - n;
+    bid -= lo;
+  }
+  if ((n & 7) == 0 && (lo & 7) == 0) bid = (bid & 7) * (n >> 3) + (bid >> 3);
+  return lo + bid;
+}
 
 enum LoadMode : int { LM_SCALAR = 0, LM_KCONTIG = 1, LM_RCONTIG = 2 };
 
@@ -133,11 +150,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmGroupArgs g) {
   __shared__ __attribute__((aligned(16))) float Bs[2][KT * IOB::LDS_STRIDE];
 
   // which problem, which tile
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): remap so that one XCD
-  // works on a contiguous run of tiles, which share operand panels.
   int pi = 0;
-  int bid = blockIdx.x;
-  if ((gridDim.x & 7) == 0) bid = (bid & 7) * (gridDim.x >> 3) + (bid >> 3);
+  const int bid = tile_index(g);
   while (pi + 1 < g.nprob && bid >= g.tile_start[pi + 1]) ++pi;
   const GemmProblem& P = g.p[pi];
   const int local = bid - g.tile_start[pi];
@@ -349,8 +363,7 @@ __global__ __launch_bounds__(256) void gemm_dl_kernel(const GemmGroupArgs g) {
   __shared__ __attribute__((aligned(16))) float Bs[DL_STAGES * OB::TILE];
 
   int pi = 0;
-  int bid = blockIdx.x;
-  if ((gridDim.x & 7) == 0) bid = (bid & 7) * (gridDim.x >> 3) + (bid >> 3);
+  const int bid = tile_index(g);
   while (pi + 1 < g.nprob && bid >= g.tile_start[pi + 1]) ++pi;
   const GemmProblem& P = g.p[pi];
   const int local = bid - g.tile_start[pi];
@@ -490,7 +503,125 @@ void launch_tile(int ma, int mb, int grid, const GemmGroupArgs& g, hipStream_t s
 // LSTM_GEMM_STAGED=1 keeps every product on the register-staged kernel (for comparison and tests).
 static bool gemm_force_staged() { return knobs().gemm_staged; }
 
+namespace {
+hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, bool split, hipStream_t stream);
+
+// C[r][c] = (accumulate ? C[r][c] : 0) + sum over s of part[s][r][c], s ascending
+__global__ void split_reduce_kernel(float* __restrict__ C, long ldc, const float* __restrict__ part, int rows, int cols, int S,
+                                    int accumulate) {
+  const long n4 = (long)rows * (cols / 4);
+  for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n4; e += (long)gridDim.x * blockDim.x) {
+    const int r = (int)(e / (cols / 4)), c = 4 * (int)(e % (cols / 4));
+    float* dst = C + (long)r * ldc + c;
+    floatx4 v = accumulate ? *reinterpret_cast<const floatx4*>(dst) : floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int s2 = 0; s2 < S; ++s2) v += *reinterpret_cast<const floatx4*>(part + ((long)s2 * rows + r) * cols + c);
+    *reinterpret_cast<floatx4*>(dst) = v;
+  }
+}
+
+// Workgroups of the 128 x 128 kernels that the chip holds at once.
+int gemm_resident_workgroups() {
+  static int cached = 0;
+  if (cached) return cached;
+  int per_cu = 0, dev = 0, cus = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)gemm_dl_kernel<2, 2, LM_KCONTIG, LM_KCONTIG>, 256, 0) !=
+          hipSuccess ||
+      per_cu < 1)
+    per_cu = 2;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      cus < 1)
+    cus = 256;
+  cached = per_cu * cus;
+  return cached;
+}
+}  // namespace
+
+// One product whose 128 x 128 tiles do not fill the chip evenly: fewer tiles than the chip holds workgroups, or a
+// last partial round of tiles (every tile takes the same time, so a round with a few tiles costs as much as a full
+// one: at M = 1600, N = 8192 there are 832 tiles for 768 places, and the last 64 tiles doubled the time).  The
+// tile rows of that last round (or all rows, if there is no full round) are cut along K into S slices, as many as fill
+// the chip once more; the slices write partial tiles to `part`, a small kernel adds them in fixed order.  Whole tiles
+// and slices run in one launch, whole tiles first.  Falls back to the plain launch whenever a condition is not met.
+hipError_t launch_gemm_split(const GemmProblem& p, float* part, size_t part_bytes, hipStream_t stream) {
+  const int tm = (p.M + 127) / 128, tn = (p.N + 127) / 128, tiles = tm * tn, nk = p.K / KT;
+  const bool ok = part && knobs().gemm_split && p.M >= 96 && p.N >= 96 && tiles >= 128 && p.K % KT == 0 && (p.N % 4) == 0 &&
+                  (p.ldc % 4) == 0 && (reinterpret_cast<uintptr_t>(p.C) & 15u) == 0 && (reinterpret_cast<uintptr_t>(part) & 15u) == 0;
+  if (!ok) return launch_gemm_group(&p, 1, stream);
+  const int room = gemm_resident_workgroups();
+  int rows_tail;
+  if (tiles <= room) {
+    rows_tail = tm;
+  } else {
+    const int tail = tiles % room;
+    if (tail == 0) return launch_gemm_group(&p, 1, stream);
+    rows_tail = (tail + tn - 1) / tn;
+  }
+  const int tail_tiles = rows_tail * tn;
+  const int row0 = (tm - rows_tail) * 128, mt = p.M - row0;
+  // Number of slices: the one with the shortest estimated time for the cut rows.  A CU works off the workgroups it
+  // holds at about the same total rate whether it holds two or three (per_cu: what it can hold), and at about two
+  // thirds of it when it holds one; the slices are dealt out in rounds of `room`; every slice more costs a little in
+  // the addition of the partial tiles.  (208 tiles, 768 places: 6 slices; 64 tiles left over: 8.)
+  int cus = 256, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  const int per_cu = room / cus > 0 ? room / cus : 1;
+  auto estimate = [&](int S2) {
+    const long items = (long)tail_tiles * S2;
+    const long full = items / room, rem = items % room;
+    const int last = (int)((rem + cus - 1) / cus);
+    const double cost_last = last == 0 ? 0.0 : (last == 1 ? 1.5 : (last == 2 ? 2.2 : (double)last));
+    return ((double)full * per_cu + cost_last) / S2 + 0.01 * (S2 - 1);
+  };
+  int S = 1;
+  double best = estimate(1) * 0.95;  // a cut has to promise at least 5 %
+  for (int S2 = 2; S2 <= 8; ++S2) {
+    if (nk / S2 < 8) break;  // at least eight k-tiles per slice
+    if ((size_t)S2 * mt * p.N * sizeof(float) > part_bytes) break;
+    const double e = estimate(S2);
+    if (e < best) {
+      best = e;
+      S = S2;
+    }
+  }
+  if (S < 2) return launch_gemm_group(&p, 1, stream);
+  GemmProblem g[kMaxGemmGroup];
+  int n = 0;
+  if (row0 > 0) {
+    g[n] = p;
+    g[n].M = row0;
+    ++n;
+  }
+  const int main_probs = n;
+  for (int s2 = 0; s2 < S; ++s2) {
+    const int k0 = (int)((long)nk * s2 / S) * KT, k1 = (int)((long)nk * (s2 + 1) / S) * KT;
+    GemmProblem q = p;
+    q.A = p.A + (long)row0 * p.sAm + (long)k0 * p.sAk;
+    q.B = p.B + (long)k0 * p.sBk;
+    q.C = part + (size_t)s2 * mt * p.N;
+    q.M = mt;
+    q.K = k1 - k0;
+    q.ldc = p.N;
+    q.accumulate = 0;
+    g[n++] = q;
+  }
+  prof_flops(2.0 * p.M * p.N * p.K, "gemm");
+  if (hipError_t e = launch_group(g, n, main_probs, true, stream); e != hipSuccess) return e;
+  const long n4 = (long)mt * (p.N / 4);
+  const unsigned blocks = (unsigned)std::min<long>((n4 + 255) / 256, 2048);
+  hipLaunchKernelGGL(split_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.C + (long)row0 * p.ldc, p.ldc, part, mt, p.N, S,
+                     p.accumulate);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream) {
+  return launch_group(probs, nprob, nprob, false, stream);
+}
+
+namespace {
+// split: the group is one product cut up by launch_gemm_split (128 x 128 tiles whatever the parts' heights; its FLOPs
+// are counted there)
+hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, bool split, hipStream_t stream) {
   if (nprob <= 0) return hipSuccess;
   if (nprob > kMaxGemmGroup) return hipErrorInvalidValue;
   GemmGroupArgs g;
@@ -510,7 +641,7 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   }
   if (ma == LM_SCALAR || mb == LM_SCALAR) ma = mb = LM_SCALAR;
   bool dl = ma != LM_SCALAR && !gemm_force_staged();
-  {
+  if (!split) {
     double fl = 0.0;
     for (int i = 0; i < nprob; ++i) fl += 2.0 * probs[i].M * probs[i].N * probs[i].K;
     prof_flops(fl, "gemm");
@@ -520,6 +651,7 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
          dl_operand_ok(mb, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);
   // Few large tiles leave most of the 256 CUs idle; fall back to 64x64 tiles then.
   if (total_big < 128) big = false;
+  if (split) big = true;
   const int mt = big ? 128 : 64;
   int start = 0;
   for (int i = 0; i < nprob; ++i) {
@@ -528,6 +660,7 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   }
   for (int i = nprob; i <= kMaxGemmGroup; ++i) g.tile_start[i] = start;
   g.nprob = nprob;
+  g.n_main = main_probs < nprob ? g.tile_start[main_probs] : start;
   if (start == 0) return hipSuccess;
   if (dl) {
     if (big)
@@ -541,5 +674,6 @@ hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t st
   }
   return hipGetLastError();
 }
+}  // namespace
 
 }  // namespace lstm

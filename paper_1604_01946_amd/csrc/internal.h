@@ -25,6 +25,10 @@ constexpr int kMaxGemmGroup = 16;
 // A group of independent products executed by one launch (Section 2.6: the weight
 // update products have no dependencies, so they can all be in flight together).
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream);
+// One product, with the tiles of its last partial round (or all of them, when they are fewer than the chip holds
+// workgroups) cut along K; `part` (16-byte aligned, part_bytes long, free until the stream has passed the call) takes
+// the partial tiles.  The same result as launch_gemm_group up to the order of the additions, which is fixed.
+hipError_t launch_gemm_split(const GemmProblem& p, float* part, size_t part_bytes, hipStream_t stream);
 
 // ---------------------------------------------------------------- point-wise / layout kernels (pointwise.hip)
 enum EwOp : int {

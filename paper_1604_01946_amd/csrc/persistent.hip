@@ -335,7 +335,8 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
     {
       ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
       GemmProblem p{in, Wl, P, (int)TB, (int)G, Il, Il, 1, 1, Il, (long)G, 0};
-      CK(launch_gemm_group(&p, 1, s), "input projection GEMM");
+      // (the exchange area is idle between two recurrences: it takes the partial tiles)
+      CK(launch_gemm_split(p, hx, a.w.flags - a.w.xchg, s), "input projection GEMM");
     }
    for (int s0 = 0; s0 < slices; s0 += cap) {
     const int nsl = slices - s0 < cap ? slices - s0 : cap;
@@ -457,7 +458,7 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
       ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
       const float* Wl = a.W + (l == 0 ? 0 : GW * d.I + (size_t)(l - 1) * GW * d.H);
       GemmProblem p{dA, Wl, din, (int)TB, Il, (int)GW, (long)G, 1, Il, 1, Il, 0};
-      CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM");
+      CK(launch_gemm_split(p, reinterpret_cast<float*>(a.ws + a.w.xchg), a.w.flags - a.w.xchg, s), "input-gradient GEMM");
     }
     if (overlap) pending = l;
   }
