@@ -8,6 +8,7 @@
 //   persistent_wide.hip   pers_fwd32_kernel / pers_bwd32_kernel: slices of 64 rows, 32x32x2 tiles, templated on the cell
 //   persistent_pp.hip     pers_fwd_pp_kernel: two half-slices of 32 rows alternating on the matrix cores
 //   persistent_bpp.hip    pers_bwd_pp_kernel: two quarter-slices of 16 rows alternating on the matrix cores
+//   persistent_tiny.hip   pers_fwd_tiny_kernel / pers_bwd_tiny_kernel: B = 1, no counters, no barriers
 //   persistent_large.hip  pers_fwdL_kernel / pers_bwdL_kernel: one layer per launch, H = 1024 / 2048
 //   persistent.hip        host side: residency, launches, which shapes run where, layer groups, batch slices
 #pragma once
@@ -172,6 +173,11 @@ hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int
 // backward counterpart: two chains of 16 rows per workgroup (batch half), 16x16x4 tiles; counters of H/16 lines per
 // (layer, step, half, chain), see persistent_bpp.hip
 hipError_t launch_bwd_pp(int H, const PersBwdArgs& a, int nbh, hipStream_t s);
+
+// a single sequence (B = 1): one wave per two hidden units, the exchanged values are their own flags
+// (persistent_tiny.hip); hx [L][T+1][H], dAx [L][T][4H], dxbuf [L][T][H]
+hipError_t launch_fwd_tiny(int H, const PersFwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_tiny(int H, const PersBwdArgs& a, hipStream_t s);
 
 hipError_t launch_fwdL_any(int H, int cell, const PersFwdLArgs& k, hipStream_t s);
 hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s);

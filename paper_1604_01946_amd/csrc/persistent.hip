@@ -203,6 +203,14 @@ bool fwd_wide(const Dims& d) {
 }
 
 
+// A single sequence: the kernels of persistent_tiny.hip (one wave per two hidden units, all of them resident).
+bool tiny_path(const Dims& d, int cell) {
+  if (cell != 0 || d.B != 1 || !knobs().tiny) return false;
+  if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
+  DeviceInfo di;
+  return device_info(di) && (long)d.L * (d.H / 2) <= 4L * di.cus;
+}
+
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
 bool bwd_wide(const Dims& d) {
   if (d.B > 64) return true;
@@ -553,6 +561,21 @@ int forward_layers(const FwdArgs& a, int cell) {
   float* hx = reinterpret_cast<float*>(a.ws + a.w.xchg);
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* P0 = reinterpret_cast<float*>(a.ws + a.w.P);
+  if (tiny_path(d, cell)) {
+    {
+      ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
+      GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
+      CK(launch_gemm_group(&p, 1, s), "input projection GEMM (layer 0)");
+    }
+    PersFwdArgs k{};
+    k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.h0 = a.h0; k.hx = hx; k.watchdog = g_watch_dev;
+    k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
+    k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit();
+    ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    prof_flops(2.0 * G * d.T * d.H * (2 * d.L - 1), "pers_fwd_tiny_kernel");
+    CK(launch_fwd_tiny(d.H, k, s), "persistent forward launch (single sequence)");
+    return LSTM_OK;
+  }
   // Wide kernel with I == H: layer 0 multiplies by W_0 inside the kernel like the layers above it (its workgroups
   // are otherwise idle half of every step), reading x from a copy in exchange layout that takes the place of the
   // projection in the workspace.  LSTM_FWD_BATCHED_INPUT=1 keeps the batched product of Section 2.3 instead.
@@ -686,6 +709,29 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   const bool wide = cell != 0 || (!narrow_slices && bwd_wide(d));
   int* flags = reinterpret_cast<int*>(a.ws + a.w.flags);
   float* dA = reinterpret_cast<float*>(a.ws + a.w.P);
+  if (tiny_path(d, cell)) {
+    PersBwdArgs k{};
+    k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
+    k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);
+    k.dh0 = a.dh0; k.dc0 = a.dc0; k.watchdog = g_watch_dev;
+    k.dx0 = (a.dx && d.I == d.H) ? a.dx : nullptr;
+    k.db = a.db;  // every element written by the one lane that owns the unit
+    k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit();
+    {
+      ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+      const double per = 2.0 * G * d.T;
+      prof_flops(per * d.H * (2 * d.L - 1) + (k.dx0 ? per * d.I : 0.0), "pers_bwd_tiny_kernel");
+      CK(launch_bwd_tiny(d.H, k, s), "persistent backward launch (single sequence)");
+    }
+    if (a.dx && !k.dx0) {  // layer 0's input gradient: all T steps in one product
+      ProfScope ps(LSTM_PHASE_BWD_INPUT_GEMM, s);
+      GemmProblem p{dA, a.W, a.dx, (int)TB, d.I, (int)GW, (long)G, 1, d.I, 1, d.I, 0};
+      CK(launch_gemm_group(&p, 1, s), "input-gradient GEMM (layer 0)");
+    }
+    if (bias_done) *bias_done = a.db != nullptr;
+    if (!with_weight_gradients) return LSTM_OK;
+    return weight_gradients(a, dA, true, a.db != nullptr);
+  }
   PersBwdArgs k;
   k.W = a.W; k.R = a.R; k.res = a.reserve; k.c0 = a.c0; k.h0 = a.h0; k.dy = a.dy; k.dhT = a.dhT; k.dcT = a.dcT;
   k.dA = dA; k.dAx = reinterpret_cast<float*>(a.ws + a.w.xchg); k.dxbuf = reinterpret_cast<float*>(a.ws + a.w.dx);

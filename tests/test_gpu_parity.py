@@ -157,6 +157,31 @@ def test_cfg5_small_batch_long_sequence(flags):
     run_case(CONFIGS["cfg5"], 0, flags, with_states=False, with_dstates=False)
 
 
+def test_cfg5_on_the_narrow_kernels(knobs):
+    """B = 1 runs on the kernels whose exchanged values are their own flags; LSTM_TINY=0 keeps the counter-based ones."""
+    knobs(LSTM_TINY="0")
+    run_case(CONFIGS["cfg5"], 0, 6, with_states=False, with_dstates=False)
+
+
+# a single sequence: every hidden size of the flag-in-data kernels, I != H (input product and input gradient as batched
+# products), one layer, one step, a stack of eight layers (512 waves), with and without initial / final states
+SINGLE = [
+    Config("s128", L=1, T=9, B=1, I=128, H=128, state_std=0.3, dstate_std=0.3),
+    Config("s128i", L=3, T=6, B=1, I=40, H=128, state_std=0.3, dstate_std=0.3),
+    Config("s256T1", L=2, T=1, B=1, I=256, H=256, state_std=0.3, dstate_std=0.3),
+    Config("s512", L=2, T=7, B=1, I=512, H=512, state_std=0.3, dstate_std=0.3),
+    Config("s512i", L=4, T=5, B=1, I=72, H=512, state_std=0.3, dstate_std=0.3),
+    Config("s128L8", L=8, T=4, B=1, I=128, H=128, state_std=0.3, dstate_std=0.3),
+]
+
+
+@pytest.mark.parametrize("cfg", SINGLE, ids=[c.name for c in SINGLE])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_single_sequence(cfg, with_states):
+    _, binding, _ = _mods()
+    run_case(cfg, 5, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
+
+
 # ------------------------------------------------------------------ persistent path: every shape class it takes
 PERS = [
     Config("p128", L=2, T=5, B=16, I=40, H=128, state_std=0.3, dstate_std=0.3),
