@@ -38,7 +38,10 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kk = lane >> 5, n = lane & 31;
   const size_t TB = (size_t)T * B;
-  const int rot = ((int)(blockIdx.x >> 3) * (NB8 / 32 > 0 ? NB8 / 32 : 1) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (NB8 - 1);
+  // the waves read the slot in orders rotated against each other, in steps of four groups: the address of a request is
+  // then a scalar base + the lane's fixed offset + an immediate (vector address arithmetic costs a wave that runs matrix
+  // instructions back to back its full issue time, scalar arithmetic nothing)
+  const int rot = 4 * (((int)(blockIdx.x >> 3) * (NB8 / 32 > 0 ? NB8 / 32 : 1) + 2 * __builtin_amdgcn_readfirstlane(wave)) & (NB8 / 4 - 1));
   float* const hx = a.hx + (size_t)sl * (T + 1) * H * 32;
   int* const flags = a.flags + (size_t)sl * (T + 1) * 16 * kFlagStride;
 
@@ -56,8 +59,8 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
       const float v = live ? src[8 * k8 + 2 * m] : 0.f;
       if (i < RP)
         wreg[i < RP ? i : 0] = v;
-      else
-        wl[((size_t)wave * LP + (i - RP)) * 64 + lane] = v;
+      else  // the four k-pairs of a group side by side: one 16-byte LDS read per group
+        wl[(((size_t)wave * (LP / 4) + ((i - RP) >> 2)) * 64 + lane) * 4 + (i & 3)] = v;
     }
   }
 
@@ -93,15 +96,17 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     float pnx[4];
     {
-      const float* src = slot(t) + (size_t)wave * NB8 * 256 + lane * 4;
+      const char* const src = reinterpret_cast<const char*>(slot(t) + (size_t)__builtin_amdgcn_readfirstlane(wave) * NB8 * 256);
       floatx4 bv[NB8];
-      float al[NB8][4];
-      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rv) & (NB8 - 1)) * 256); };
+      floatx4 al[NB8];
+      unsigned lo = lane * 16;  // met anew by the optimiser here and after every branch, so that it stays a 32-bit offset
+      asm volatile("" : "+v"(lo));
+      auto ldb = [&](int g) {
+        const char* const sb = src + (size_t)(4 * (((g >> 2) + (rv >> 2)) & (NB8 / 4 - 1))) * 1024;
+        bv[g] = *reinterpret_cast<const floatx4*>(sb + lo + (g & 3) * 1024);
+      };
       auto ldw = [&](int g) {
-        if (g * 4 >= RP) {
-#pragma unroll
-          for (int m = 0; m < 4; ++m) al[g][m] = wl[((size_t)wave * LP + (g * 4 + m - RP)) * 64 + lane];
-        }
+        if (g * 4 >= RP) al[g] = *reinterpret_cast<const floatx4*>(wl + (((size_t)wave * (LP / 4) + (g - RP / 4)) * 64 + lane) * 4);
       };
 #pragma unroll
       for (int g = 0; g < DEPTH; ++g) ldb(g);
@@ -116,6 +121,8 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
 #pragma unroll
           for (int q = 0; q < 4; ++q)
             pnx[q] = (valid && t + 1 < T && q < NG) ? a.P[((size_t)(t + 1) * B + bb) * G + q * H + u0 + uj] : 0.f;
+          lo = lane * 16;
+          asm volatile("" : "+v"(lo));
         }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
@@ -273,8 +280,8 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       const float v = live ? col[((size_t)gate * H + unit) * H] : 0.f;
       if (p < RP)
         wreg[p < RP ? p : 0] = v;
-      else
-        wl[((size_t)wave * LP + (p - RP)) * 64 + lane] = v;
+      else  // the four k-pairs of a group side by side: one 16-byte LDS read per group
+        wl[(((size_t)wave * (LP / 4) + ((p - RP) >> 2)) * 64 + lane) * 4 + (p & 3)] = v;
     }
   }
 
@@ -394,15 +401,18 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     {
-      const float* src = slotX(t, i) + lane * 4;
+      const char* const src = reinterpret_cast<const char*>(slotX(t, i));
       floatx4 bv[NG8];
-      float al[NG8][4];
-      auto ldb = [&](int g) { bv[g] = *reinterpret_cast<const floatx4*>(src + (size_t)((g + rv) & (NG8 - 1)) * 256); };
+      floatx4 al[NG8];
+      unsigned lo = lane * 16;  // met anew by the optimiser here and after every branch, so that it stays a 32-bit offset
+      asm volatile("" : "+v"(lo));
+      // (rot is a multiple of four groups: scalar base + lane offset + immediate)
+      auto ldb = [&](int g) {
+        const char* const sb = src + (size_t)(4 * (((g >> 2) + (rv >> 2)) & (NG8 / 4 - 1))) * 1024;
+        bv[g] = *reinterpret_cast<const floatx4*>(sb + lo + (g & 3) * 1024);
+      };
       auto ldw = [&](int g) {
-        if (g * 4 >= RP) {
-#pragma unroll
-          for (int m = 0; m < 4; ++m) al[g][m] = wl[((size_t)wave * LP + (g * 4 + m - RP)) * 64 + lane];
-        }
+        if (g * 4 >= RP) al[g] = *reinterpret_cast<const floatx4*>(wl + (((size_t)wave * (LP / 4) + (g - RP / 4)) * 64 + lane) * 4);
       };
 #pragma unroll
       for (int g = 0; g < DEPTH; ++g) ldb(g);

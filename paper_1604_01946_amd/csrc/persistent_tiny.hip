@@ -238,7 +238,12 @@ __global__ void tiny_prepare_fwd_kernel(float* __restrict__ hx, const float* __r
   const long n = (long)L * (T + 1) * H;
   for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long)gridDim.x * blockDim.x) {
     const int k = (int)(e % H), st = (int)((e / H) % (T + 1)), l = (int)(e / ((long)H * (T + 1)));
-    hx[e] = st == 0 ? (h0 ? h0[(size_t)l * H + k] : 0.f) : __uint_as_float(kEmpty);
+    float v = __uint_as_float(kEmpty);
+    if (st == 0) {  // (an initial state that carries the empty pattern would never be seen as written)
+      v = h0 ? h0[(size_t)l * H + k] : 0.f;
+      if (__float_as_uint(v) == kEmpty) v = __uint_as_float(0x7FC00000u);
+    }
+    hx[e] = v;
   }
 }
 
