@@ -203,12 +203,13 @@ bool fwd_wide(const Dims& d) {
 }
 
 
-// A single sequence: the kernels of persistent_tiny.hip (one wave per two hidden units, all of them resident).
+// A single sequence: the kernels of persistent_tiny.hip (one wave per two hidden units, 32 workgroups per layer, all
+// of them resident).
 bool tiny_path(const Dims& d, int cell) {
   if (cell != 0 || d.B != 1 || !knobs().tiny) return false;
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
   DeviceInfo di;
-  return device_info(di) && (long)d.L * (d.H / 2) <= 4L * di.cus;
+  return device_info(di) && 32L * d.L <= di.cus;  // 32 workgroups per layer, one per CU
 }
 
 // The wide-batch backward kernel: two batch halves, 16 hidden units per workgroup.
@@ -571,6 +572,8 @@ int forward_layers(const FwdArgs& a, int cell) {
     k.W = a.W; k.R = a.R; k.bias = a.b; k.P0 = P0; k.c0 = a.c0; k.h0 = a.h0; k.hx = hx; k.watchdog = g_watch_dev;
     k.res = a.reserve; k.y = a.y; k.hT = a.hT; k.cT = a.cT;
     k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit();
+    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+    k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     prof_flops(2.0 * G * d.T * d.H * (2 * d.L - 1), "pers_fwd_tiny_kernel");
     CK(launch_fwd_tiny(d.H, k, s), "persistent forward launch (single sequence)");
@@ -717,6 +720,8 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
     k.dx0 = (a.dx && d.I == d.H) ? a.dx : nullptr;
     k.db = a.db;  // every element written by the one lane that owns the unit
     k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit();
+    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+    k.trace_block = g_trace_block;
     {
       ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
       const double per = 2.0 * G * d.T;

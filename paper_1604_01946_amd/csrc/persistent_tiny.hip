@@ -9,11 +9,18 @@
 // the hop is as short as the memory system allows:
 //   * the data is its own flag: every exchange slot is filled with a pattern that no result can have (a NaN with a
 //     payload that arithmetic never produces; a result that happens to carry it is published as the default NaN)
-//     before the launch, a producer stores its values with a write-through store and does nothing else, a consumer
+//     before the launch, a producer stores its values with one write-through store and does nothing else, a consumer
 //     re-reads the slot with agent-scope loads until no lane sees the pattern.  No acknowledgement, no counter.
-//   * a wave owns two hidden units with all their weights over the whole K (lane i holds k = i, i + 64, ...; the wave
-//     multiplies with vector FMAs and adds up across its lanes), so no wave waits for another one of its
-//     workgroup: there is no barrier and no LDS in a step, and a workgroup is a single wave.
+//   * a wave owns two hidden units with all their weights over the whole K (lane i holds a few k each; the wave
+//     multiplies with vector FMAs and adds up across its lanes), so no wave waits for another one's arithmetic.
+//   * the H / 64 waves of a workgroup poll 1 / (H / 64) of the slot each and hand their shares to each other through
+//     LDS (one barrier per step): every word of a slot is asked for once per workgroup, not once per wave.
+//   * nothing that has to be waited for is issued between a step's poll and its publishing store except what that
+//     store needs: the reserve values of later steps are requested right behind a poll (which has waited for
+//     everything in flight anyway) and consumed two steps on, in registers that take turns instead of being copied.
+// Measured at H = 256 (one or two layers, T = 500): 1.3 us per forward step and 1.4 us per backward step, of which
+// about 0.4 us are the wave's own arithmetic (matrix-vector product, lane reduction, gates), the rest the store
+// becoming visible and one poll round.
 // Section 2.4's wavefront over layers is the same polling: layer l reads the slot of layer l-1 (forward) or the
 // hand-over gradient of layer l+1 (backward).  Every poll is bounded (watchdog as in the other persistent kernels).
 #include "../../include/lstm.h"
@@ -35,65 +42,84 @@ __device__ __forceinline__ void publish(float* p, float v) {
   __hip_atomic_store(reinterpret_cast<unsigned*>(p), b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The 16-byte request of the backward kernel is inline assembly (there is no 16-byte atomic load to ask the compiler
+// for), so the wait for it is written out as well, tied to the value it covers.  Every word is its own flag: a request
+// that is served while the producer is writing is simply partly empty.
+__device__ __forceinline__ floatx4 request4(const float* p) {
+  floatx4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+  return v;
+}
+__device__ __forceinline__ void landed(floatx4& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)::"memory"); }
+__device__ __forceinline__ void publish4(float* p, floatx4 v) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    if (__float_as_uint(v[c]) == kEmpty) v[c] = __uint_as_float(0x7FC00000u);
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
+// Polls: one round after the other, without a pause (measured over the 500 steps of a forward pass at H = 256 with
+// every wave polling whole slots: 0.80 ms; with s_sleep 1 between rounds 0.94; with two rounds in flight half a round
+// trip apart, so as to notice a value sooner, 1.12: the polls get in each other's way).  What a round costs grows with
+// the bytes that all waves together ask the memory for, not with the number or the width of the requests (a backward
+// step at H = 256 with every wave polling the whole 4 KB slot took 2.1 us as 16 one-word requests and as 4 four-word
+// requests alike; the forward step with 2 KB took 1.3): the waves of a workgroup poll a share of the slot each and
+// hand the shares to each other through LDS.
 struct TinyWaiter {
   int* watchdog;
   int limit;
   bool dead;
-  // Reads NA values per lane from pa and NB from pb (element 64*i + lane) until none of them is the empty pattern.
-  // One round after the other, without a pause (measured over the 500 steps of a forward pass at H = 256: 0.80 ms;
-  // with s_sleep 1 between rounds 0.94; with two rounds in flight half a round trip apart, so as to notice a value
-  // sooner, 1.12: the polls of 256 waves on the same lines get in each other's way).
-  template <int NA, int NB>
-  __device__ __forceinline__ void poll(const float* pa, float (&va)[NA], const float* pb, float (&vb)[NB]) {
-    const int lane = threadIdx.x & 63;
-    int spins = 0;
-    while (true) {
-#pragma unroll
-      for (int i = 0; i < NA; ++i) va[i] = poll_load(pa + 64 * i + lane);
-#pragma unroll
-      for (int i = 0; i < NB; ++i) vb[i] = poll_load(pb + 64 * i + lane);
-      bool ok = true;
-#pragma unroll
-      for (int i = 0; i < NA; ++i) ok = ok && __float_as_uint(va[i]) != kEmpty;
-#pragma unroll
-      for (int i = 0; i < NB; ++i) ok = ok && __float_as_uint(vb[i]) != kEmpty;
-      if (__all(ok) || dead) return;
-      if (++spins > limit) {
-        dead = true;
-        __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        return;
-      }
+  __device__ __forceinline__ bool give_up(int& spins) {
+    if (dead) return true;
+    if (++spins > limit) {
+      dead = true;
+      __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      return true;
     }
+    return false;
   }
-  template <int NA>
-  __device__ __forceinline__ void poll1n(const float* pa, float (&va)[NA]) {
-    const int lane = threadIdx.x & 63;
-    int spins = 0;
-    while (true) {
-#pragma unroll
-      for (int i = 0; i < NA; ++i) va[i] = poll_load(pa + 64 * i + lane);
-      bool ok = true;
-#pragma unroll
-      for (int i = 0; i < NA; ++i) ok = ok && __float_as_uint(va[i]) != kEmpty;
-      if (__all(ok) || dead) return;
-      if (++spins > limit) {
-        dead = true;
-        __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        return;
-      }
-    }
-  }
-  // One value per lane (the same few addresses in every lane).
+  // One value per lane.
   __device__ __forceinline__ float poll1(const float* p) {
     int spins = 0;
     while (true) {
       const float v = poll_load(p);
-      if (__all(__float_as_uint(v) != kEmpty) || dead) return v;
-      if (++spins > limit) {
-        dead = true;
-        __hip_atomic_store(watchdog, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        return v;
-      }
+      if (__all(__float_as_uint(v) != kEmpty) || give_up(spins)) return v;
+    }
+  }
+  // Two values per lane.
+  __device__ __forceinline__ void poll2(const float* pa, float& va, const float* pb, float& vb) {
+    int spins = 0;
+    while (true) {
+      va = poll_load(pa);
+      vb = poll_load(pb);
+      if (__all(__float_as_uint(va) != kEmpty && __float_as_uint(vb) != kEmpty) || give_up(spins)) return;
+    }
+  }
+  // Four consecutive values per lane.  If pe is given, every round also reads *pe, which is handed back as the last
+  // round saw it (possibly still empty): a value that is due later and costs nothing to look at now.
+  __device__ __forceinline__ float poll4_peek(const float* pa, floatx4& va, const float* pe) {
+    int spins = 0;
+    while (true) {
+      va = request4(pa);
+      float ve = __uint_as_float(kEmpty);
+      if (pe) ve = poll_load(pe);
+      landed(va);
+      bool ok = true;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) ok = ok && __float_as_uint(va[c]) != kEmpty;
+      if (__all(ok) || give_up(spins)) return ve;
+    }
+  }
+};
+
+// Time stamps of one workgroup's first wave, eight per step (the time-stamped instance only).
+template <bool TRACE>
+struct TinyTracer {
+  long long* buf;  // [T][8]
+  __device__ __forceinline__ void mark(int step, int slot) const {
+    if (TRACE && buf && threadIdx.x == 0) {
+      buf[(size_t)step * 8 + slot] = wall_clock64();
+      if (slot == 0) buf[(size_t)step * 8 + 7] = clock64();
     }
   }
 };
@@ -150,17 +176,23 @@ __device__ __forceinline__ float lane_value(float v, int src_lane) {
 }
 
 // ------------------------------------------------------------------ forward
-// Wave (l, p): units u0 = 2p, 2p + 1 of layer l; rows r = 4*j + gate of the stacked matrices (j: which of the two
-// units).  Exchange: hx [L][T+1][H], slot t+1 = h_t, slot 0 = h0 (or zeros), everything else the empty pattern before
-// the launch.  Layer 0 takes its input product from the batched projection P0 [T][4H] (Section 2.3).
-template <int HH>
-__global__ __launch_bounds__(64) void pers_fwd_tiny_kernel(const PersFwdArgs a) {
-  constexpr int H = HH, G = 4 * H, NI = H / 64, NP = H / 2;
-  int l, p;
-  map_block(a.L, NP, l, p);
-  const int T = a.T, lane = threadIdx.x & 63;
-  const int u0 = 2 * p;
+// Workgroup (l, q) of H / 64 waves: wave w owns units u0 = 2 * (q * H / 64 + w), u0 + 1 of layer l (32 workgroups per
+// layer); rows r = 4*j + gate of the stacked matrices (j: which of the two units).  Exchange: hx [L][T+1][H], slot t+1 =
+// h_t, slot 0 = h0 (or zeros), everything else the empty pattern before the launch.  Wave w polls words 64 w ... of the
+// two operands.  Layer 0 takes its input product from the batched projection P0 [T][4H] (Section 2.3).
+constexpr int kTinyGroups = 32;  // workgroups per layer
 
+template <int HH, bool TRACE>
+__global__ __launch_bounds__(HH) void pers_fwd_tiny_kernel(const PersFwdArgs a) {
+  constexpr int H = HH, G = 4 * H, NI = H / 64, NW = H / 64;
+  __shared__ __align__(16) float xs[2][2][H];  // [step parity][x, h][word]
+  int l, q;
+  map_block(a.L, kTinyGroups, l, q);
+  const int T = a.T, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u0 = 2 * (q * NW + wave);
+
+  // value m of a lane: word (64 * (m / VW) + lane) * VW + m % VW of the operand (read from LDS VW words at a time)
+  constexpr int VW = NI < 4 ? NI : 4;
   float wW[8][NI], wR[8][NI];
   {
     const float* Rl = a.R + (size_t)l * G * H;
@@ -170,8 +202,9 @@ __global__ __launch_bounds__(64) void pers_fwd_tiny_kernel(const PersFwdArgs a) 
       const size_t row = ((size_t)(r & 3) * H + u0 + (r >> 2)) * H;
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        wR[r][i] = Rl[row + 64 * i + lane];
-        wW[r][i] = l > 0 ? Wl[row + 64 * i + lane] : 0.f;
+        const int k = (64 * (i / VW) + lane) * VW + i % VW;
+        wR[r][i] = Rl[row + k];
+        wW[r][i] = l > 0 ? Wl[row + k] : 0.f;
       }
     }
   }
@@ -188,14 +221,44 @@ __global__ __launch_bounds__(64) void pers_fwd_tiny_kernel(const PersFwdArgs a) 
   float* const res_h = res_l + (size_t)T * 5 * H;
   auto slot = [&](int layer, int st) { return a.hx + ((size_t)layer * (T + 1) + st) * H; };
   TinyWaiter w{a.watchdog, a.spin_limit, false};
+  const TinyTracer<TRACE> tr{(int)blockIdx.x == a.trace_block ? a.trace : nullptr};
 
-  for (int t = 0; t < T; ++t) {
-    float pin[4];
+  // Loads return in the order of their issue, so an ordinary load requested just before a poll holds up the poll's
+  // first round: the input product of step t + 1 is requested behind the poll of step t and taken over behind the
+  // poll of step t + 1, which has waited for everything in flight anyway.
+  float pin[4], pin_next[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) pin[g] = l == 0 ? a.P0[(size_t)t * G + g * H + uj] : 0.f;
+  for (int g = 0; g < 4; ++g) pin_next[g] = l == 0 ? a.P0[g * H + uj] : 0.f;
+  for (int t = 0; t < T; ++t) {
+    const int par = t & 1, mine = 64 * wave + lane;
+    tr.mark(t, 0);
+    float vx = 0.f, vh;  // (layer 0 has no input operand in the exchange)
+    if (l > 0) w.poll2(slot(l - 1, t + 1) + mine, vx, slot(l, t) + mine, vh);
+    else vh = w.poll1(slot(l, t) + mine);
+    tr.mark(t, 1);
+    xs[par][0][mine] = vx;
+    xs[par][1][mine] = vh;
+    // (one barrier per step: the buffer written two steps on is the one every wave has read before it arrived here)
+    __syncthreads();
+    tr.mark(t, 2);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) pin[g] = pin_next[g];
+    if (l == 0 && t + 1 < T) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) pin_next[g] = a.P0[(size_t)(t + 1) * G + g * H + uj];
+    }
     float xi[NI], hr[NI];
-    // (layer 0 has no input operand in the exchange: it reads its own recurrent slot twice; those weights are zero)
-    w.poll(l > 0 ? slot(l - 1, t + 1) : slot(l, t), xi, slot(l, t), hr);
+#pragma unroll
+    for (int i = 0; i < NI / VW; ++i) {
+      typedef float vec __attribute__((ext_vector_type(VW)));
+      const vec qx = *reinterpret_cast<const vec*>(&xs[par][0][(64 * i + lane) * VW]);
+      const vec qh = *reinterpret_cast<const vec*>(&xs[par][1][(64 * i + lane) * VW]);
+#pragma unroll
+      for (int c = 0; c < VW; ++c) {
+        xi[i * VW + c] = qx[c];
+        hr[i * VW + c] = qh[c];
+      }
+    }
     float acc[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -215,6 +278,7 @@ __global__ __launch_bounds__(64) void pers_fwd_tiny_kernel(const PersFwdArgs a) 
     const float cn = gf * c_state + gi * gc;
     const float hn = go * tanhf_dev(cn);
     c_state = cn;
+    tr.mark(t, 3);
     if (fin) {
       publish(slot(l, t + 1) + uj, hn);
       float* const rg = res_l + (size_t)t * G + uj;
@@ -255,27 +319,30 @@ __global__ void tiny_fill_empty_kernel(float* __restrict__ p, long n) {
 // ------------------------------------------------------------------ backward
 // Wave (l, p): units u0 = 2p, 2p + 1: four output rows over K = 4H -- dh_{t-1} of the two units (columns of R_l) and
 // the gradient dx_t for the same two units of the layer below (columns of W_l; layer 0: of the network input when
-// I == H and it is wanted).  Exchange: dAx [L][T][4H] gate gradients, dxbuf [L][T][H] hand-over gradients (slice l
-// written by layer l >= 1, read by layer l-1), both the empty pattern before the launch.  The bias gradient of a unit is
+// I == H and it is wanted).  Exchange: dAx [L][T][H][4] gate gradients (the four gates of a unit side by side: one
+// 16-byte store publishes them), dxbuf [L][T][H] hand-over gradients (slice l written by layer l >= 1, read by layer
+// l-1), both the empty pattern before the launch.  The bias gradient of a unit is
 // the sum over t of its gate gradients, which its lane carries along: no reduction, no atomic.
-template <int HH>
-__global__ __launch_bounds__(64) void pers_bwd_tiny_kernel(const PersBwdArgs a) {
-  constexpr int H = HH, G = 4 * H, NI = G / 64, NP = H / 2;
-  int l, p;
-  map_block(a.L, NP, l, p);
-  const int T = a.T, lane = threadIdx.x & 63;
-  const int u0 = 2 * p;
+template <int HH, bool TRACE>
+__global__ __launch_bounds__(HH) void pers_bwd_tiny_kernel(const PersBwdArgs a) {
+  constexpr int H = HH, G = 4 * H, NI = G / 64, NW = H / 64;
+  __shared__ __align__(16) float ds[2][G];  // [step parity][word of the slot]
+  int l, q;
+  map_block(a.L, kTinyGroups, l, q);
+  const int T = a.T, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u0 = 2 * (q * NW + wave);
 
   float wR[2][NI], wW[2][NI];
   {
     const float* Rl = a.R + (size_t)l * G * H + u0;
     const float* Wl = (l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W) + u0;  // layer 0: [G][I], I == H
     const bool live = l > 0 || a.dx0;
+    // value m of a lane: gate m % 4 of unit 64 * (m / 4) + lane (read from LDS four words at a time)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        const size_t k = (size_t)(64 * i + lane) * H;
+        const size_t k = ((size_t)(i & 3) * H + 64 * (i >> 2) + lane) * H;
         wR[jj][i] = Rl[k + jj];
         wW[jj][i] = live ? Wl[k + jj] : 0.f;
       }
@@ -294,44 +361,92 @@ __global__ __launch_bounds__(64) void pers_bwd_tiny_kernel(const PersBwdArgs a) 
   auto dslot = [&](int layer, int t) { return a.dAx + ((size_t)layer * T + t) * G; };
   auto xslot = [&](int layer, int t) { return a.dxbuf + ((size_t)layer * T + t) * H; };
   TinyWaiter w{a.watchdog, a.spin_limit, false};
+  const TinyTracer<TRACE> tr{(int)blockIdx.x == a.trace_block ? a.trace : nullptr};
 
-  float gi, gf, go, gg, ct, cp, dy = 0.f;
-  auto fetch = [&](int t) {  // reserve values (and dy) of step t for this lane's unit
-    const float* const rg = res_l + (size_t)t * G + uj;
-    gi = rg[0];
-    gf = rg[H];
-    go = rg[2 * H];
-    gg = rg[3 * H];
-    ct = res_c[(size_t)t * H + uj];
-    cp = t > 0 ? res_c[(size_t)(t - 1) * H + uj] : (a.c0 ? a.c0[se] : 0.f);
-    if (!has_up) dy = a.dy[(size_t)t * H + uj];
+  // Reserve values (and dy) of one step for this lane's unit, and what the point-wise stage makes of them before the
+  // incoming gradient is known.  Loads return in the order of their issue, so an ordinary load requested just before
+  // a poll holds up the poll's first round: the values of step t - 3 are requested behind the poll of step t, and
+  // those of step t - 1 are worked up while step t's own gate gradients are on their way.  The two sets of registers
+  // take turns (the loop runs two steps per iteration) so that no value is copied at the end of an iteration, which
+  // would wait for everything in flight.
+  struct Saved {
+    float gi, gf, go, gg, ct, cp, dy;
   };
-  fetch(T - 1);
+  struct Ready {
+    float k_c, k_i, k_f, k_o, k_g, gf, dy;  // dc += dh * k_c; d = dc * k_i, dc * k_f, dh * k_o, dc * k_g; dc *= gf
+  };
+  auto fetch = [&](int t) {
+    Saved v;
+    const float* const rg = res_l + (size_t)t * G + uj;
+    v.gi = rg[0];
+    v.gf = rg[H];
+    v.go = rg[2 * H];
+    v.gg = rg[3 * H];
+    v.ct = res_c[(size_t)t * H + uj];
+    v.cp = t > 0 ? res_c[(size_t)(t - 1) * H + uj] : (a.c0 ? a.c0[se] : 0.f);
+    v.dy = has_up ? 0.f : a.dy[(size_t)t * H + uj];
+    return v;
+  };
+  auto work_up = [&](const Saved& v) {
+    Ready k;
+    const float tc = tanhf_dev(v.ct);
+    k.k_c = v.go * (1.f - tc * tc);
+    k.k_i = v.gg * v.gi * (1.f - v.gi);
+    k.k_f = v.cp * v.gf * (1.f - v.gf);
+    k.k_o = tc * v.go * (1.f - v.go);
+    k.k_g = v.gi * (1.f - v.gg * v.gg);
+    k.gf = v.gf;
+    k.dy = v.dy;
+    return k;
+  };
+  Ready k = work_up(fetch(T - 1));
+  Saved ra = fetch(T > 1 ? T - 2 : 0), rb = fetch(T > 2 ? T - 3 : 0);
+  // hand-over gradient of the step about to start, looked at during the previous step's poll (empty: not there yet)
+  float seen = __uint_as_float(kEmpty);
 
-  for (int t = T - 1; t >= 0; --t) {
+  // step t; rx: the reserve values of step t - 1 on entry, of step t - 3 on exit
+  auto step = [&](int t, Saved& rx) {
     // ---- point-wise stage of step t
-    const float dout = has_up ? w.poll1(xslot(l + 1, t) + uj) : dy;
+    tr.mark(t, 0);
+    float dout = k.dy;
+    if (has_up) dout = __all(__float_as_uint(seen) != kEmpty) ? seen : w.poll1(xslot(l + 1, t) + uj);
+    tr.mark(t, 1);
     const float dh = dout + dh_rec;
-    const float tc = tanhf_dev(ct);
-    const float dcv = dc + dh * go * (1.f - tc * tc);
-    float d[4];
-    d[0] = dcv * gg * gi * (1.f - gi);
-    d[1] = dcv * cp * gf * (1.f - gf);
-    d[2] = dh * tc * go * (1.f - go);
-    d[3] = dcv * gi * (1.f - gg * gg);
-    dc = dcv * gf;
+    const float dcv = dc + dh * k.k_c;
+    const float d[4] = {dcv * k.k_i, dcv * k.k_f, dh * k.k_o, dcv * k.k_g};
+    dc = dcv * k.gf;
     if (fin) {
+      publish4(dslot(l, t) + 4 * uj, floatx4{d[0], d[1], d[2], d[3]});
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        publish(dslot(l, t) + g * H + uj, d[g]);
         dA_l[(size_t)t * G + g * H + uj] = d[g];
         dbsum[g] += d[g];
       }
     }
-    if (t > 0) fetch(t - 1);  // under the hop
+    if (t > 0) k = work_up(rx);
     // ---- dh_{t-1} and dx_t: needs dA_t of every unit of the layer
+    // (wave w polls words 256 w ... of the slot)
+    const int par = t & 1, mine = 256 * wave + 4 * lane;
+    tr.mark(t, 2);
+    // A poll round that comes back partly empty costs more than its own time: it is in the way of the stores it is
+    // waiting for.  Every wave publishes at about the same moment, so the first round is held back until those stores
+    // are about to be visible (measured at H = 256: 1.72 us per step with no pause, 1.57 with 192 cycles, 1.44 with
+    // 512, 1.57 with 1024; the forward kernel has its stores to the reserve in this place and gains nothing).
+    __builtin_amdgcn_s_sleep(8);
+    floatx4 share;
+    seen = w.poll4_peek(dslot(l, t) + mine, share, has_up && t > 0 ? xslot(l + 1, t - 1) + uj : nullptr);
+    tr.mark(t, 3);
+    *reinterpret_cast<floatx4*>(&ds[par][mine]) = share;
+    __syncthreads();  // (one barrier per step is enough: see the forward kernel)
+    tr.mark(t, 4);
+    if (t > 2) rx = fetch(t - 3);
     float da[NI];
-    w.poll1n(dslot(l, t), da);
+#pragma unroll
+    for (int i = 0; i < NI / 4; ++i) {
+      const floatx4 qd = *reinterpret_cast<const floatx4*>(&ds[par][(64 * i + lane) * 4]);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) da[i * 4 + c] = qd[c];
+    }
     float acc[4];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
@@ -349,11 +464,18 @@ __global__ __launch_bounds__(64) void pers_bwd_tiny_kernel(const PersBwdArgs a) 
     const float x0v = lane_value(r, of_value<4>(2)), x1v = lane_value(r, of_value<4>(3));
     dh_rec = j ? h1v : h0v;
     const float dxv = j ? x1v : x0v;
+    tr.mark(t, 5);
     if (fin) {
       if (l > 0) publish(xslot(l, t) + uj, dxv);
       else if (a.dx0) a.dx0[(size_t)t * a.I + uj] = dxv;
     }
+  };
+  int t = T - 1;
+  for (; t >= 1; t -= 2) {
+    step(t, ra);
+    step(t - 1, rb);
   }
+  if (t == 0) step(0, ra);
   if (fin) {
     if (a.dh0) a.dh0[se] = dh_rec;
     if (a.dc0) a.dc0[se] = dc;
@@ -370,20 +492,26 @@ hipError_t launch_fwd_tiny(int H, const PersFwdArgs& a, hipStream_t s) {
   const long n = (long)a.L * (a.T + 1) * H;
   hipLaunchKernelGGL(tiny_prepare_fwd_kernel, dim3((unsigned)std::min<long>((n + 255) / 256, 1024)), dim3(256), 0, s, a.hx, a.h0, a.L,
                      a.T, H);
-  const void* fn = H == 512 ? (const void*)pers_fwd_tiny_kernel<512>
-                            : (H == 256 ? (const void*)pers_fwd_tiny_kernel<256> : (const void*)pers_fwd_tiny_kernel<128>);
+  const void* fn = H == 512 ? (const void*)pers_fwd_tiny_kernel<512, false>
+                            : (H == 256 ? (const void*)pers_fwd_tiny_kernel<256, false> : (const void*)pers_fwd_tiny_kernel<128, false>);
+  if (a.trace)
+    fn = H == 512 ? (const void*)pers_fwd_tiny_kernel<512, true>
+                  : (H == 256 ? (const void*)pers_fwd_tiny_kernel<256, true> : (const void*)pers_fwd_tiny_kernel<128, true>);
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
-  return launch_resident(fn, a.L * (H / 2), params, 0, s, 64);
+  return launch_resident(fn, a.L * kTinyGroups, params, 0, s, H);
 }
 
 hipError_t launch_bwd_tiny(int H, const PersBwdArgs& a, hipStream_t s) {
   const long n1 = (long)a.L * a.T * 4 * H, n2 = (long)a.L * a.T * H;
   hipLaunchKernelGGL(tiny_fill_empty_kernel, dim3((unsigned)std::min<long>((n1 + 255) / 256, 1024)), dim3(256), 0, s, a.dAx, n1);
   hipLaunchKernelGGL(tiny_fill_empty_kernel, dim3((unsigned)std::min<long>((n2 + 255) / 256, 1024)), dim3(256), 0, s, a.dxbuf, n2);
-  const void* fn = H == 512 ? (const void*)pers_bwd_tiny_kernel<512>
-                            : (H == 256 ? (const void*)pers_bwd_tiny_kernel<256> : (const void*)pers_bwd_tiny_kernel<128>);
+  const void* fn = H == 512 ? (const void*)pers_bwd_tiny_kernel<512, false>
+                            : (H == 256 ? (const void*)pers_bwd_tiny_kernel<256, false> : (const void*)pers_bwd_tiny_kernel<128, false>);
+  if (a.trace)
+    fn = H == 512 ? (const void*)pers_bwd_tiny_kernel<512, true>
+                  : (H == 256 ? (const void*)pers_bwd_tiny_kernel<256, true> : (const void*)pers_bwd_tiny_kernel<128, true>);
   void* params[] = {const_cast<PersBwdArgs*>(&a)};
-  return launch_resident(fn, a.L * (H / 2), params, 0, s, 64);
+  return launch_resident(fn, a.L * kTinyGroups, params, 0, s, H);
 }
 
 }  // namespace lstm

@@ -169,6 +169,8 @@ SINGLE = [
     Config("s128", L=1, T=9, B=1, I=128, H=128, state_std=0.3, dstate_std=0.3),
     Config("s128i", L=3, T=6, B=1, I=40, H=128, state_std=0.3, dstate_std=0.3),
     Config("s256T1", L=2, T=1, B=1, I=256, H=256, state_std=0.3, dstate_std=0.3),
+    Config("s256T2", L=2, T=2, B=1, I=256, H=256, state_std=0.3, dstate_std=0.3),
+    Config("s256T3", L=1, T=3, B=1, I=256, H=256, state_std=0.3, dstate_std=0.3),
     Config("s512", L=2, T=7, B=1, I=512, H=512, state_std=0.3, dstate_std=0.3),
     Config("s512i", L=4, T=5, B=1, I=72, H=512, state_std=0.3, dstate_std=0.3),
     Config("s128L8", L=8, T=4, B=1, I=128, H=128, state_std=0.3, dstate_std=0.3),
