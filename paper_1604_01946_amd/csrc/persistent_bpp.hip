@@ -22,8 +22,10 @@
 //   post  K-split sums, point-wise stage of step t-1, dA_{t-1} published (exchange slot, standard array).
 //   B     dx_t = W_l^T dA_t (tile 1) from the same operand registers.  Nothing waits for it soon (the layer below
 //         runs behind), so every round trip of the kernel happens under it: the counters of the other chain's
-//         next phase A and of the layer above are looked at, the reserve values of the next point-wise stage and
-//         all operands of that phase A are requested.  Its partial sums are added up after the next barrier
+//         next phase A and of the layer above are looked at, the reserve values of the next point-wise stage (the
+//         other chain's, half a period away: the layers of a stack finish one behind the other, each by as much as
+//         it has to see of the layer above ahead of time, so nothing is asked for earlier than its round trip needs)
+//         and all operands of that phase A are requested.  Its partial sums are added up after the next barrier
 //         (the other chain's).
 // Order in time: A0 post0 B0 A1 post1 B1 A0 ...: between the publication of a chain's dA_{t-1} and the first
 // matrix instruction that needs everybody's dA_{t-1} lie two phases B and one phase A of pure arithmetic, three
@@ -112,6 +114,9 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int u0 = 16 * s2;
+  if constexpr (TRACE) {  // (slots 1 and 5 of the first step processed: kernel entry, weights in place; of step 0: last step done, exit)
+    if (a.trace && (int)blockIdx.x == a.trace_block && threadIdx.x == 0) a.trace[(size_t)(T - 1) * 8 + 1] = wall_clock64();
+  }
   const size_t TB = (size_t)T * B;
   const int NQ = 2 * NBH;
   // The waves of a layer read a slot's K quarter in orders rotated against each other (all of them would otherwise ask
@@ -205,6 +210,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   };
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // once: drop whatever earlier launches left in L1/L2
   __syncthreads();                                    // LDS weights are in place
+  mark(0, T - 1, 5);
 
   // ---- reserve values and upstream gradient of a chain's next point-wise stage
   float gi[2], gf[2], go[2], gg[2], ct[2], cp[2], dpre[2];
@@ -326,7 +332,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     {
       const int o = 1 - c, tn = c == 0 ? t : t - 1;
       seen_next = PpWaiter<NL>::peek(tn >= 0 ? flag(lq, tn + 2, o) : flag(lq, t + 2, c));
-      seen_up = PpWaiter<NL>::peek((has_up && t > 1) ? up_flag(c, t - 2) : flag(lq, t + 2, c));
+      seen_up = PpWaiter<NL>::peek((has_up && tn > 0) ? up_flag(o, tn - 1) : flag(lq, t + 2, c));
     }
     *reinterpret_cast<floatx4*>(part + (c * 4 + w) * 256 + lane * 4) = acc;
     mark(c, t, 2);
@@ -338,8 +344,8 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   //      before that barrier) goes out; then the chain's point-wise stage of step t-1
   // ---- phase B of chain c, step t: the other half of the product, dx_t = W_l^T dA_t, from the operands still in
   //      registers.  Nothing waits for it soon, so everything with a round trip happens under it: the counters that
-  //      phase A read are looked at, the reserve values of the chain's next point-wise stage and the operands of the
-  //      next phase A (the other chain's) are requested.  Its first KH groups carry no request: they are issued in
+  //      phase A read are looked at, the reserve values and the upstream gradient of the next point-wise stage and the
+  //      operands of the next phase A (both the other chain's) are requested.  Its first KH groups carry no request: they are issued in
   //      between the pieces of post() -- the K-split sums of dh, dx of the other chain's last phase B (its partial sums
   //      were written before the barrier), the chain's point-wise stage of step t-1 -- which has no matrix instruction
   //      of its own to hide its LDS round trips and its arithmetic behind.
@@ -405,9 +411,11 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     const int o = 1 - c;
     const int tn = c == 0 ? t : t - 1;  // the next phase A is (o, tn)
     const bool has_next = tn >= 0;
-    const int tq = t > 1 ? t - 2 : 0;   // step of this chain's next point-wise stage (in post(c, t-1)), if any
-    const bool has_pw = t > 1;
-    fetch_res(c, tq);
+    // the next point-wise stage is the other chain's, in post(o, tn), of step tn - 1 (if any): what it needs from the
+    // reserve and from the layer above is requested here, half a period ahead of its use
+    const int tq = tn > 0 ? tn - 1 : 0;
+    const bool has_pw = tn > 0;
+    fetch_res(o, tq);
     // operands of the next phase A; when there is none, this chain's own slot once more (valid memory, values unused),
     // so that every step issues the same requests
     const float* const nsrc = has_next ? slot(tn, o) : slot(t, c);
@@ -427,8 +435,8 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
         PpWaiter<NL>::land(seen_next);
         PpWaiter<NL>::land(seen_up);
         if (has_next) wt.wait(flag(lq, tn + 2, o), 4, seen_next);
-        if (has_up && has_pw) wt.wait(up_flag(c, tq), 4, seen_up);
-        fetch_dout(c, tq);
+        if (has_up && has_pw) wt.wait(up_flag(o, tq), 4, seen_up);
+        fetch_dout(o, tq);
         fresh_lo();
       }
       if (g >= PL) {  // operand groups [lo, hi) of the next phase A, spread evenly over groups PL..NU-1
@@ -462,12 +470,11 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   arrive(0, T + 1);
   arrive(1, T + 1);
   // what the first phases need and later ones find requested by the phase B before them: the reserve values and the
-  // upstream gradient of step T-2 (for the point-wise stage in the first post() of either chain), and chain 0's operands
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    fetch_res(c, T > 1 ? T - 2 : 0);
-    if (has_up && T > 1) wt.wait(up_flag(c, T - 2), 4, 0);
-    fetch_dout(c, T > 1 ? T - 2 : 0);
+  // upstream gradient of step T-2 for the point-wise stage in chain 0's first post(), and chain 0's operands
+  {
+    fetch_res(0, T > 1 ? T - 2 : 0);
+    if (has_up && T > 1) wt.wait(up_flag(0, T - 2), 4, 0);
+    fetch_dout(0, T > 1 ? T - 2 : 0);
   }
   wt.wait(flag(lq, T + 1, 0), 4, 0);
   fresh_lo();
@@ -495,6 +502,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   }
   drain_vmem();
   arrive(0, 0);
+  mark(0, 0, 1);
 
 #pragma unroll
   for (int c = 0; c < 2; ++c) {
@@ -519,6 +527,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
       atomicAdd(a.db + (size_t)l * G + (threadIdx.x >> 4) * H + u0 + (threadIdx.x & 15), sum);
     }
   }
+  mark(0, 0, 5);
 }
 
 template <int HH>
