@@ -75,6 +75,9 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   constexpr int NR4 = NK8 / 4 > 0 ? NK8 / 4 : 1;
   const int rot = NK8 >= 4 ? 4 * (((int)(blockIdx.x >> 3) + q) & (NR4 - 1)) : 0;
 
+  if constexpr (TRACE) {  // (slot 5 of step 0: kernel entry under chain 1, weights in place under chain 0)
+    if (a.trace && (int)blockIdx.x == a.trace_block && threadIdx.x == 0) a.trace[((size_t)T + 0) * 8 + 5] = wall_clock64();
+  }
   // ---- weights -> registers.  A operand of group register i (k8 = (i + rot) % NK8), k-pair j:
   //      row rho = lane % 32 = 8*gate + 4*par + cc holds unit 2*cc + par; k = q*H/4 + 8*k8 + 2*j + kk
   float wR[NK8][4], wW[NK8][4];
@@ -316,6 +319,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     post_b(cp, tp);
   };
 
+  tr.mark(0, 0, 5);
   // ---- chain 0's first input operand (chain 1's is requested by chain 0's first block)
   {
     if (!in_is_x) w.wait(in_flag(1, 0), 8, 0);
