@@ -174,6 +174,7 @@ SINGLE = [
     Config("s512", L=2, T=7, B=1, I=512, H=512, state_std=0.3, dstate_std=0.3),
     Config("s512i", L=4, T=5, B=1, I=72, H=512, state_std=0.3, dstate_std=0.3),
     Config("s128L8", L=8, T=4, B=1, I=128, H=128, state_std=0.3, dstate_std=0.3),
+    Config("s512L8", L=8, T=3, B=1, I=512, H=512, state_std=0.3, dstate_std=0.3),  # every CU holds one workgroup of 8 waves
 ]
 
 
