@@ -286,6 +286,7 @@ template <int W, int ROWS, int MODE>
 struct DlOperand {
   static constexpr int TILE = ROWS * KT;           // floats per stage
   static constexpr int CPW = ROWS / 64;            // 1 KB chunks per wave and tile (4 waves)
+  static constexpr bool kInterleaved = MODE == LM_RCONTIG && W == 2;
   const char* sb;                                   // scalar: address of the next tile to request
   long step;                                        // bytes between k-tiles
   unsigned voff[CPW];                               // per-lane byte offset inside the tile, per chunk
@@ -318,8 +319,12 @@ struct DlOperand {
         const int ra = min(r0 + row, R - 4);
         voff[j] = (unsigned)(((long)k * s_k + ra) * 4);
       }
+      // Two tiles per wave: the tiles take every other row of the wave's 64 (tile i: rows 2 r + i), so that a lane's
+      // values for both tiles lie side by side in LDS and come with one 8-byte read (kInterleaved; the epilogue maps
+      // the rows back).
 #pragma unroll
-      for (int i = 0; i < W; ++i) rd[i][0] = rd[i][1] = (4 * (lane >> 5)) * ROWS + w0 + 32 * i + (lane & 31);
+      for (int i = 0; i < W; ++i)
+        rd[i][0] = rd[i][1] = (4 * (lane >> 5)) * ROWS + w0 + (kInterleaved ? 2 * (lane & 31) + i : 32 * i + (lane & 31));
     }
   }
 
@@ -347,11 +352,17 @@ struct DlOperand {
           const floatx4 x = *reinterpret_cast<const floatx4*>(lds + so + rd[i][blk]);
           f[i][0] = x[0]; f[i][1] = x[1]; f[i][2] = x[2]; f[i][3] = x[3];
         }
+    } else if (kInterleaved) {
+      const floatx2 x = *reinterpret_cast<const floatx2*>(lds + so + rd[0][0] + (8 * blk + q) * ROWS);
+      f[0][q] = x[0];
+      f[W - 1][q] = x[1];
     } else {
 #pragma unroll
       for (int i = 0; i < W; ++i) f[i][q] = lds[so + rd[i][0] + (8 * blk + q) * ROWS];
     }
   }
+  // row (or column) of the output that element rho of the wave's tile i stands for, relative to the wave's first
+  static __device__ __forceinline__ int out_index(int i, int rho) { return kInterleaved ? 2 * rho + i : 32 * i + rho; }
 };
 
 template <int WM, int WN, int MA, int MB>
@@ -445,14 +456,37 @@ __global__ __launch_bounds__(256) void gemm_dl_kernel(const GemmGroupArgs g) {
   }
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // no request may still be writing LDS when the workgroup ends
 
+  if constexpr (OB::kInterleaved) {
+    // a lane holds two neighbouring columns (2 c, 2 c + 1: tiles 0 and 1): one 8-byte store per row where C allows it
+    const bool pair_ok = (P.ldc & 1) == 0 && (reinterpret_cast<uintptr_t>(P.C) & 7u) == 0;
+    const int col = n0 + wn * 64 + 2 * (lane & 31);
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 32 * WM + OA::out_index(i, 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
+        if (row < P.M && col < P.N) {
+          float* c = P.C + (long)row * P.ldc + col;
+          if (pair_ok && col + 1 < P.N) {
+            floatx2 v = {acc[i][0][r], acc[i][1][r]};
+            if (P.accumulate) v += *reinterpret_cast<const floatx2*>(c);
+            *reinterpret_cast<floatx2*>(c) = v;
+          } else {
+            c[0] = P.accumulate ? (c[0] + acc[i][0][r]) : acc[i][0][r];
+            if (col + 1 < P.N) c[1] = P.accumulate ? (c[1] + acc[i][1][r]) : acc[i][1][r];
+          }
+        }
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
-      const int col = n0 + wn * 32 * WN + 32 * j + (lane & 31);
+      const int col = n0 + wn * 32 * WN + OB::out_index(j, lane & 31);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 32 * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int row = m0 + wm * 32 * WM + OA::out_index(i, 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
         if (row < P.M && col < P.N) {
           float* c = P.C + (long)row * P.ldc + col;
           *c = P.accumulate ? (*c + acc[i][j][r]) : acc[i][j][r];
