@@ -456,6 +456,59 @@ __global__ __launch_bounds__(256) void gemm_dl_kernel(const GemmGroupArgs g) {
   }
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);  // no request may still be writing LDS when the workgroup ends
 
+  // (only the instance that the launcher exchanges roles into carries the transposing epilogue: in the others its
+  // registers would cost the kernel a resident workgroup per CU)
+  if (MA == LM_RCONTIG && MB == LM_KCONTIG && P.ct) {
+    // element (r, c) -> C[c * ldc + r].  With the rows of the wave's two tiles interleaved a lane holds, for each of
+    // its columns and each group of four accumulator registers, eight consecutive rows: 32 contiguous bytes of C.
+    if constexpr (OA::kInterleaved) {
+      const bool vec_ok = (P.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(P.C) & 15u) == 0;
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        const int c = n0 + wn * 32 * WN + OB::out_index(j, lane & 31);
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int r0 = m0 + wm * 64 + 2 * (8 * gq + 4 * (lane >> 5));
+          if (c < P.N && r0 < P.M) {
+            float* dst = P.C + (long)c * P.ldc + r0;
+            if (vec_ok && r0 + 7 < P.M) {
+              floatx4 v0 = {acc[0][j][4 * gq], acc[1][j][4 * gq], acc[0][j][4 * gq + 1], acc[1][j][4 * gq + 1]};
+              floatx4 v1 = {acc[0][j][4 * gq + 2], acc[1][j][4 * gq + 2], acc[0][j][4 * gq + 3], acc[1][j][4 * gq + 3]};
+              if (P.accumulate) {
+                v0 += *reinterpret_cast<const floatx4*>(dst);
+                v1 += *reinterpret_cast<const floatx4*>(dst + 4);
+              }
+              *reinterpret_cast<floatx4*>(dst) = v0;
+              *reinterpret_cast<floatx4*>(dst + 4) = v1;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (r0 + e < P.M) {
+                  const float v = acc[e & 1][j][4 * gq + (e >> 1)];
+                  dst[e] = P.accumulate ? dst[e] + v : v;
+                }
+            }
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+          const int col = n0 + wn * 32 * WN + OB::out_index(j, lane & 31);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 32 * WM + OA::out_index(i, 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3));
+            if (row < P.M && col < P.N) {
+              float* c = P.C + (long)col * P.ldc + row;
+              *c = P.accumulate ? (*c + acc[i][j][r]) : acc[i][j][r];
+            }
+          }
+        }
+    }
+    return;
+  }
   if constexpr (OB::kInterleaved) {
     // a lane holds two neighbouring columns (2 c, 2 c + 1: tiles 0 and 1): one 8-byte store per row where C allows it
     const bool pair_ok = (P.ldc & 1) == 0 && (reinterpret_cast<uintptr_t>(P.C) & 7u) == 0;
@@ -686,11 +739,27 @@ hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, boo
   // Few large tiles leave most of the 256 CUs idle; fall back to 64x64 tiles then.
   if (total_big < 128) big = false;
   if (split) big = true;
+  // The 128 x 128 kernel is slower with a K-contiguous A operand than with a K-contiguous B operand (2048 x 2048 x 8192:
+  // A K- / B row-contiguous 121 TFLOP/s, both K-contiguous 134, A row- / B K-contiguous 142, both row-contiguous 143;
+  // neither the order of the tiles, of the waves, of the requests nor of the matrix instructions changes that).  A
+  // product with A K-contiguous and B row-contiguous is therefore computed as its transpose, B^T A^T, whose
+  // elements the epilogue writes to where C expects them.
+  if (dl && big && ma == LM_KCONTIG && mb == LM_RCONTIG && knobs().gemm_swap) {
+    for (int i = 0; i < nprob; ++i) {
+      GemmProblem& q = g.p[i];
+      std::swap(q.A, q.B);
+      std::swap(q.M, q.N);
+      std::swap(q.sAm, q.sBn);
+      std::swap(q.sAk, q.sBk);
+      q.ct = !q.ct;
+    }
+    std::swap(ma, mb);
+  }
   const int mt = big ? 128 : 64;
   int start = 0;
   for (int i = 0; i < nprob; ++i) {
     g.tile_start[i] = start;
-    start += ((probs[i].M + mt - 1) / mt) * ((probs[i].N + mt - 1) / mt);
+    start += ((g.p[i].M + mt - 1) / mt) * ((g.p[i].N + mt - 1) / mt);
   }
   for (int i = nprob; i <= kMaxGemmGroup; ++i) g.tile_start[i] = start;
   g.nprob = nprob;

@@ -21,6 +21,7 @@ struct GemmProblem {
   int M, N, K;
   long sAm, sAk, sBk, sBn, ldc;
   int accumulate;
+  int ct;  // element (r, c) of the product goes to C[c * ldc + r] (set by the launcher when it exchanges the operands' roles)
 };
 constexpr int kMaxGemmGroup = 16;
 // A group of independent products executed by one launch (Section 2.6: the weight
