@@ -52,6 +52,7 @@ const Knobs& knobs() {
     k.gemm_split = !env_is("LSTM_GEMM_SPLIT", '0');
     k.tiny = !env_is("LSTM_TINY", '0');
     k.gemm_swap = !env_is("LSTM_GEMM_SWAP", '0');
+    k.large_pp = !env_is("LSTM_LARGE_PP", '0');
     k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
     const char* ff = getenv("LSTM_FULL_FENCES");
     k.full_fences = ff && *ff && *ff != '0';

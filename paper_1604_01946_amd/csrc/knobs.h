@@ -9,6 +9,7 @@ struct Knobs {
   bool no_pad;               // LSTM_NO_PAD=1: hidden sizes run as given instead of zero-padded to a persistent kernel's
   bool gemm_staged;          // LSTM_GEMM_STAGED=1: register-staged GEMM kernel everywhere
   bool gemm_swap;            // LSTM_GEMM_SWAP=0: no exchange of the operands' roles in the large-tile GEMM
+  bool large_pp;             // LSTM_LARGE_PP=0: the one-chain forward kernel at H = 2048 instead of the alternating one
   bool tiny;                 // LSTM_TINY=0: a single sequence (B = 1) on the narrow kernels instead of the flag-in-data ones
   bool gemm_split;           // LSTM_GEMM_SPLIT=0: no K slices for a product's last partial round of tiles
   int spin_limit;            // LSTM_SPIN_LIMIT: polls before a persistent kernel's wait gives up

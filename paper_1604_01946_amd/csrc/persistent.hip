@@ -337,6 +337,7 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
   int cap = di.cus / (d.H / 8);
   if (cap < 1) cap = 1;
   if (cap > 4) cap = 4;
+  const bool lpp = cell == 0 && d.H == 2048 && knobs().large_pp;  // the LSTM at H = 2048: two alternating chains of 16 rows per slice
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const float* in = l == 0 ? a.x : a.reserve + (size_t)(l - 1) * rstride + res_h_offset(cell, TB, d.H);
@@ -351,8 +352,10 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
     const int nsl = slices - s0 < cap ? slices - s0 : cap;
     {
       ProfScope ps(LSTM_PHASE_FWD_PACK, s);
-      CK(launch_fill_zero(flags, (size_t)nsl * (d.T + 1) * 16 * kFlagStride * 4, s), "zero step counters");
-      CK(launch_pack_stateL(a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.T, d.B, d.H, 32 * s0, nsl, s), "pack h0");
+      const size_t counter_ints = lpp ? fwdLpp_flag_ints() : (size_t)16 * kFlagStride;
+      CK(launch_fill_zero(flags, (size_t)nsl * (d.T + 1) * counter_ints * 4, s), "zero step counters");
+      if (lpp) CK(launch_pack_stateLpp(a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.T, d.B, d.H, 32 * s0, nsl, s), "pack h0");
+      else CK(launch_pack_stateL(a.h0 ? a.h0 + (size_t)l * BH : nullptr, hx, d.T, d.B, d.H, 32 * s0, nsl, s), "pack h0");
     }
     PersFwdLArgs k;
     k.b0 = 32 * s0; k.nsl = nsl;
@@ -365,11 +368,12 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
     k.hT = a.hT ? a.hT + (size_t)l * BH : nullptr;
     k.cT = a.cT ? a.cT + (size_t)l * BH : nullptr;
     k.T = d.T; k.B = d.B; k.spin_limit = spin_limit(); k.full_fences = full_fences();
-    k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
+    k.trace = (g_trace_bytes >= (size_t)d.T * 64 * (lpp ? 2 : 1)) ? g_trace_buf : nullptr;
     k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
-    prof_flops(2.0 * G * d.H * std::min(32 * nsl, d.B - 32 * s0) * d.T, "pers_fwdL_kernel");
-    CK(launch_fwdL_any(d.H, cell, k, s), "persistent forward launch (large H)");
+    prof_flops(2.0 * G * d.H * std::min(32 * nsl, d.B - 32 * s0) * d.T, lpp ? "pers_fwdLpp_kernel" : "pers_fwdL_kernel");
+    if (lpp) CK(launch_fwdLpp(d.H, k, s), "persistent forward launch (large H, alternating chains)");
+    else CK(launch_fwdL_any(d.H, cell, k, s), "persistent forward launch (large H)");
    }
   }
   return LSTM_OK;
