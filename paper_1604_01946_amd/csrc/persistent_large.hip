@@ -89,6 +89,9 @@ __global__ __launch_bounds__(256) void pers_fwdL_kernel(const PersFwdLArgs a) {
   for (int t = 0; t < T; ++t) {
     tr.mark(t, 0);
     hide(rv);  // keeps the rotated offsets next to their loads
+    // (the first look at the counter is held back: a poll that comes too early is in the way of the arrivals it waits
+    // for.  L = 4, H = 1024, B = 32, T = 50: 1.31 ms without a pause, 1.23 with 512 cycles, 1.25 with 1024, 1.32 with 2048)
+    __builtin_amdgcn_s_sleep(8);
     if (t > 0) w.template wait_split<16>(flags + (size_t)16 * kFlagStride * t, NS / 16);  // slot 0 was written before the launch
     tr.mark(t, 2);
     floatx16 acc;
@@ -249,6 +252,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   constexpr int RP = UF == 16 ? 136 : 128;   // k-pairs with weights in registers (more where the staging arrays are larger)
   constexpr int LP = KP - RP;                // k-pairs with weights in LDS
   constexpr int DEPTH = 16;
+  constexpr int kPauseA = 16, kPauseP = 32;  // pauses before the first look at a counter, in units of 64 cycles
   static_assert(NBK % kFlagSub == 0, "arrivals must spread evenly over the counter lines");
   static_assert(UF == 8 || UF == 16, "one or two cells per thread");
   extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -395,6 +399,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   for (int t = T - 1; t >= 0; --t) {
     tr.mark(t, 0);
     hide(rv);
+    __builtin_amdgcn_s_sleep(kPauseA);
     w.wait(flagA(t, i), NBK);
     tr.mark(t, 1);
     floatx16 acc;
@@ -448,6 +453,11 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     }
     signal(flagP(t, j) + (i & (kFlagSub - 1)) * kFlagStride, a.full_fences);
     tr.mark(t, 3);
+    // A poll that comes too early is in the way of the arrivals it waits for (every wave of every workgroup polls):
+    // the first look at a counter is held back until the arrivals are about due.  cfg4 backward recurrence (ms) by
+    // pause before the poll for the dA slot / for the partial sums, in units of 64 cycles: none 2.84, 8 / 8 2.80,
+    // 16 / 16 2.74, 16 / 32 2.67, 16 / 24 2.70, 12 / 32 2.71, 20 / 32 2.69, 16 / 40 2.71, 24 / 48 2.73, 32 / 64 2.83.
+    __builtin_amdgcn_s_sleep(kPauseP);
     w.wait(flagP(t, j), NBK);
     tr.mark(t, 4);
 #pragma unroll
