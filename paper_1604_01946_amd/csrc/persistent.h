@@ -10,6 +10,7 @@
 //   persistent_bpp.hip    pers_bwd_pp_kernel: two quarter-slices of 16 rows alternating on the matrix cores
 //   persistent_tiny.hip   pers_fwd_tiny_kernel / pers_bwd_tiny_kernel: B = 1, no counters, no barriers
 //   persistent_large.hip  pers_fwdL_kernel / pers_bwdL_kernel: one layer per launch, H = 1024 / 2048
+//   persistent_large_pp.hip  pers_fwdLpp_kernel: the LSTM forward kernel of H = 2048 with two alternating chains per slice
 //   persistent.hip        host side: residency, launches, which shapes run where, layer groups, batch slices
 #pragma once
 #include "schedule.h"
