@@ -8,7 +8,7 @@
 //   persistent_wide.hip   pers_fwd32_kernel / pers_bwd32_kernel: slices of 64 rows, 32x32x2 tiles, templated on the cell
 //   persistent_pp.hip     pers_fwd_pp_kernel: two half-slices of 32 rows alternating on the matrix cores
 //   persistent_bpp.hip    pers_bwd_pp_kernel: two quarter-slices of 16 rows alternating on the matrix cores
-//   persistent_tiny.hip   pers_fwd_tiny_kernel / pers_bwd_tiny_kernel: B = 1, no counters, no barriers
+//   persistent_tiny.hip   pers_fwd_tiny_kernel / pers_bwd_tiny_kernel: B = 1, the exchanged values are their own flags
 //   persistent_large.hip  pers_fwdL_kernel / pers_bwdL_kernel: one layer per launch, H = 1024 / 2048
 //   persistent_large_pp.hip  pers_fwdLpp_kernel: the LSTM forward kernel of H = 2048 with two alternating chains per slice
 //   persistent.hip        host side: residency, launches, which shapes run where, layer groups, batch slices

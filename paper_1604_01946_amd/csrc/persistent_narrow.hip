@@ -428,7 +428,10 @@ __global__ __launch_bounds__(256) void pers_bwd_kernel(const PersBwdArgs a) {
         for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
       }
 
-      // ---- GEMM of step t: needs dA_t of every slice of this layer
+      // ---- GEMM of step t: needs dA_t of every slice of this layer.  (The first look at the counter is held back by
+      //      1024 cycles: a poll that comes before the arrivals is in their way.  L = 4, T = 100: H = 512, B = 32 backward
+      //      1.144 -> 1.105 ms, H = 256, B = 16 0.488 -> 0.449 ms; 1536 cycles 1.080 / 0.469, 2048 cycles 1.085 / 0.490.)
+      __builtin_amdgcn_s_sleep(16);
       w.wait(flag(l, t + 1, c), NS);
       if (c == 0) tr.mark(t, 4);
       // counter of the layer above for the next point-wise stage, read without a branch and consumed there

@@ -582,7 +582,10 @@ __global__ __launch_bounds__(256) void pers_bwd32_kernel(const PersBwdArgs a, co
       for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4*>(dA_l + g0 + (size_t)g * H) = dA4[g];
     }
 
-    // ---- GEMM of step t: needs dA_t of every slice of this layer and batch half
+    // ---- GEMM of step t: needs dA_t of every slice of this layer and batch half.  (The first look at the counter is
+    //      held back by 1024 cycles: a poll that comes before the arrivals is in their way; L = 4, H = 512, B = 64, T = 100
+    //      backward 1.309 -> 1.27 ms.)
+    __builtin_amdgcn_s_sleep(16);
     w.wait(flag(l, t + 1), NS2);
     tr.mark(t, 4);
     // counter of the layer above for the next point-wise stage: read now, looked at under the MFMAs
