@@ -242,6 +242,16 @@ def test_persistent_large_hidden(cfg, with_states):
     run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
+# H = 2048 runs forward on the kernel with two alternating chains of 16 rows per slice; LSTM_LARGE_PP=0 keeps the
+# one-chain kernel (the one the other cells and H = 1024 use)
+@pytest.mark.parametrize("name", ["l2048b32", "l2048b5", "l2048b40", "l2048T1"])
+def test_large_hidden_one_chain_forward(name, knobs):
+    _, binding, _ = _mods()
+    knobs(LSTM_LARGE_PP="0")
+    cfg = next(c for c in LARGE if c.name == name)
+    run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=True, with_dstates=True)
+
+
 # Stacks deeper than the chip holds at once (L * H/8 workgroups > CUs): groups of consecutive layers, one launch each
 DEEP = [
     Config("d512L8", L=8, T=5, B=64, I=512, H=512, state_std=0.3, dstate_std=0.3),      # 4 + 4, x multiplied in the kernel
