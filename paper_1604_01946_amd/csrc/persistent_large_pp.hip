@@ -184,10 +184,12 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
     hide(rv);
     mark(c, t, 0);
     floatx4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    // (the stores to the reserve wait for the finalising waves' other block, the one without a point-wise stage: the
-    // four waves then reach the barrier closer together)
-    if (have_prev && cf == o) post(tp);
-    if (cf == c && t > 0) post_b(t - 1);
+    // (the stores to the reserve right behind the stage, ahead of the operand requests of this block: requests retire
+    // in issue order, and stores issued behind those requests would be waited for with them)
+    if (have_prev && cf == o) {
+      post(tp);
+      post_b(tp);
+    }
     floatx4 alw[LG > 0 ? LG / 2 : 1];
     auto ldw = [&](int p) {
       if (p >= RQ && p < NQ) {
@@ -259,8 +261,10 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
     block(0, t, t > 0);
     block(1, t, true);
   }
-  if (cf == 1) post(T - 1);
-  post_b(T - 1);
+  if (cf == 1) {
+    post(T - 1);
+    post_b(T - 1);
+  }
 }
 
 // h0 [B][H] of one layer (zeros if null) -> slot 0 of both chains of every slice, in the layout above
