@@ -536,11 +536,15 @@ hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
   const size_t smem = (5120 + (size_t)4 * LG * 2 * 64 * 4) * sizeof(float);
   // Schedule (measured at H = 512; the alternatives within 1 %): the other chain's publication is counted one group
   // into phase A; a quarter of phase B runs in between the pieces of post(), six of its instructions per matrix
-  // instruction; the next phase A's operands are all requested during the rest of phase B.
+  // instruction; the next phase A's operands are requested during the rest of phase B, from group PL on.
+  // At H = 512 the counters are looked at, and the requests begin, at group 12 of the 32 (cfg3 backward recurrence by
+  // that group: 8 1.047 ms, 10 1.038, 12 1.032, 13 1.031, 14 1.042, 16 1.058: looking later also lets a layer follow
+  // the one above more closely).
   constexpr int KH = NU / 4 < 4 ? 4 : NU / 4;
+  constexpr int PL = HH == 512 ? 12 : KH;
   const bool trace = a.trace != nullptr;
-  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, KH, KH, 6, true>
-                         : (const void*)pers_bwd_pp_kernel<HH, 1, KH, KH, 6, false>;
+  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, true>
+                         : (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, false>;
   static bool attr_set[2] = {false, false};
   if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set[trace ? 1 : 0]); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};

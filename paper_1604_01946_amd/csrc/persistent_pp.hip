@@ -389,10 +389,12 @@ __global__ __launch_bounds__(256) void pack_x_pp_kernel(const float* __restrict_
 template <int HH>
 hipError_t launch_pp(int grid, const PersFwdArgs& a, hipStream_t s) {
   constexpr int NK8 = HH / 32;
-  // the other chain's publication is completed a quarter of an operand half into a block, the fetch of its next
-  // input starts half an operand half in (measured at H = 512: later completion or later fetch are 1-2 % slower)
-  const void* fn = a.trace ? (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2, true>
-                           : (const void*)pers_fwd_pp_kernel<HH, NK8 / 2 + NK8 / 4, NK8 / 2, false>;
+  // the other chain's publication is completed half an operand half into a block (H = 512, group 8; cfg3 forward
+  // recurrence by that group: 6 0.964 ms -- the acknowledgement is not there yet --, 7 0.902, 8 0.906, 9 0.910,
+  // 10 0.911, 12 0.921), the fetch of its next input starts there as well (from group 10 or 12 on: 0.953)
+  constexpr int GA = HH == 512 ? NK8 / 2 : NK8 / 2 + NK8 / 4;
+  const void* fn = a.trace ? (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, true>
+                           : (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, false>;
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
   return launch_resident(fn, grid, params, 0, s);
 }
