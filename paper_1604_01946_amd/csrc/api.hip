@@ -53,6 +53,7 @@ const Knobs& knobs() {
     k.tiny = !env_is("LSTM_TINY", '0');
     k.gemm_swap = !env_is("LSTM_GEMM_SWAP", '0');
     k.large_pp = !env_is("LSTM_LARGE_PP", '0');
+    k.micro = env_is("LSTM_MICRO", '0') ? 0 : (env_is("LSTM_MICRO", '2') ? 2 : 1);
     k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
     const char* ff = getenv("LSTM_FULL_FENCES");
     k.full_fences = ff && *ff && *ff != '0';
@@ -197,7 +198,7 @@ hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int c
   return hipGetLastError();
 }
 
-int padded_hidden(const Dims& d) { return knobs().no_pad ? d.H : padded_hidden_rule(d); }
+int padded_hidden(const Dims& d) { return (knobs().no_pad || micro_shape(d)) ? d.H : padded_hidden_rule(d); }
 
 int padded_hidden_rule(const Dims& d) {
   // 704 <= H < 1024 with up to 128 rows: the one-layer persistent kernels of H = 1024 are 5-40 % faster than the step

@@ -10,6 +10,7 @@ struct Knobs {
   bool gemm_staged;          // LSTM_GEMM_STAGED=1: register-staged GEMM kernel everywhere
   bool gemm_swap;            // LSTM_GEMM_SWAP=0: no exchange of the operands' roles in the large-tile GEMM
   bool large_pp;             // LSTM_LARGE_PP=0: the one-chain forward kernel at H = 2048 instead of the alternating one
+  int micro;                 // LSTM_MICRO=0: no pass runs as one workgroup; =2: every shape those kernels take does
   bool tiny;                 // LSTM_TINY=0: a single sequence (B = 1) on the narrow kernels instead of the flag-in-data ones
   bool gemm_split;           // LSTM_GEMM_SPLIT=0: no K slices for a product's last partial round of tiles
   int spin_limit;            // LSTM_SPIN_LIMIT: polls before a persistent kernel's wait gives up

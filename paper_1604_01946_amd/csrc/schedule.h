@@ -50,6 +50,10 @@ struct BwdArgs {
 // for every step and receive zero gradients, so a network padded that way computes exactly the given one; the
 // persistent kernels exist for H = 128, 256 and 512, and any other hidden size below 512 runs faster (several times,
 // with more than one layer) padded to the next of them than on the per-step paths.  LSTM_NO_PAD=1 in the environment disables it.
+// micro.hip: a whole pass in one workgroup, for the smallest networks (part of the step path)
+bool micro_shape(const Dims& d);
+hipError_t launch_micro_forward(const FwdArgs& a);
+hipError_t launch_micro_backward(const BwdArgs& a);
 int padded_hidden(const Dims& d);
 int padded_hidden_rule(const Dims& d);  // the same without looking at LSTM_NO_PAD (size queries cover both settings)
 inline Dims padded_dims(const Dims& d) { return Dims{d.L, d.T, d.B, d.I, padded_hidden(d)}; }

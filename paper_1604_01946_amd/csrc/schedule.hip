@@ -105,6 +105,7 @@ unsigned resolve_auto_path(const Dims& user, bool backward) {
     for (const PathOverride& o : g_path_table)
       if (same_shape(o.d, user) && o.backward == backward) return o.path;
   }
+  if (micro_shape(user)) return LSTM_PATH_STEP;  // one launch per pass, steps looped inside (micro.hip)
   const Dims d = padded_dims(user);  // what the kernels will run
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
   const int cus = device_cu_count();
@@ -141,6 +142,11 @@ int fwd_step(const FwdArgs& a) {
   const Dims& d = a.d;
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H;
   hipStream_t s = a.stream;
+  if (micro_shape(d)) {  // a launch per step would cost more than the step: all of them in one launch
+    ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
+    CK(launch_micro_forward(a), "forward pass in one workgroup");
+    return LSTM_OK;
+  }
   float* Rp = ws_f(a.ws, a.w.RT);
   const size_t pf = step_plan(d).pack_floats;
   {
@@ -317,6 +323,11 @@ int bwd_step(const BwdArgs& a) {
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, BH = (size_t)d.B * d.H, BG = (size_t)d.B * G;
   const int H = d.H, B = d.B, T = d.T;
   hipStream_t s = a.stream;
+  if (micro_shape(d)) {
+    ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);
+    CK(launch_micro_backward(a), "backward pass in one workgroup");
+    return LSTM_OK;
+  }
   float* dA_all = ws_f(a.ws, a.w.P);
   float* RT = ws_f(a.ws, a.w.RT);
   const StepPlan sp = step_plan(d);

@@ -114,12 +114,16 @@ PATHS_ALL = [0, 1, 2, 3, 4, 5, 6]
 
 # Hidden sizes below 512 that the persistent kernels do not take run zero-padded to the next one that they do, on
 # every path; LSTM_NO_PAD=1 runs the shape as given, which is what exercises the ragged tiles of the per-step kernels.
-@pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
+# cfg1 itself is among the shapes that run a whole pass in one workgroup (automatic choice and step path):
+# LSTM_MICRO=0 puts it back on the per-step kernels.
+@pytest.mark.parametrize("variant", ["default", "per_step", "as_given"])
 @pytest.mark.parametrize("flags", PATHS_ALL)
-def test_cfg1_all_paths(flags, nopad, knobs):
+def test_cfg1_all_paths(flags, variant, knobs):
     _, binding, _ = _mods()
-    if nopad:
-        knobs(LSTM_NO_PAD="1")
+    if variant == "per_step":
+        knobs(LSTM_MICRO="0")
+    if variant == "as_given":
+        knobs(LSTM_NO_PAD="1", LSTM_MICRO="0")
     cfg = CONFIGS["cfg1"]
     if flags == 6 and binding.lstm_auto_path(*cfg.dims, 0) != 6:
         # H = 32 as given has no persistent kernel: forcing that path must be refused, not run on something else
@@ -401,13 +405,38 @@ def test_padded_hidden_sizes(cfg, with_states):
     assert torch.equal(r.y, y_train)
 
 
+# The smallest networks: one workgroup runs a whole pass (H = 8, 16, 32; few rows, few layers).
+MICRO = [
+    Config("m8", L=2, T=5, B=3, I=5, H=8, state_std=0.5, dstate_std=0.5),
+    Config("m16", L=3, T=7, B=8, I=64, H=16, state_std=0.5, dstate_std=0.5),
+    Config("m32", L=4, T=9, B=8, I=32, H=32, state_std=0.5, dstate_std=0.5),
+    Config("m32b2", L=2, T=6, B=2, I=64, H=32, state_std=0.5, dstate_std=0.5),
+    Config("m32b1", L=1, T=40, B=1, I=20, H=32, state_std=0.5, dstate_std=0.5),
+    Config("m32T1", L=2, T=1, B=7, I=1, H=32, state_std=0.5, dstate_std=0.5),
+]
+
+
+@pytest.mark.parametrize("cfg", MICRO, ids=[c.name for c in MICRO])
+@pytest.mark.parametrize("with_states", [True, False])
+def test_one_workgroup_per_pass(cfg, with_states, knobs):
+    _, binding, _ = _mods()
+    knobs(LSTM_MICRO="2")  # every shape the kernels take, not only those where they are the automatic choice
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_STEP
+    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_STEP
+    run_case(cfg, 11, 0, with_states=with_states, with_dstates=with_states)
+    run_case(cfg, 12, binding.LSTM_PATH_STEP, with_states=with_states, with_dstates=with_states)
+
+
 # ------------------------------------------------------------------ optional pointers, inference
+@pytest.mark.parametrize("hidden", [24, 32], ids=["h24", "h32_one_workgroup"])
 @pytest.mark.parametrize("nopad", [False, True], ids=["padded", "as_given"])
-def test_null_optionals_and_inference(nopad, knobs):
+def test_null_optionals_and_inference(nopad, hidden, knobs):
     torch, binding, runner = _mods()
     if nopad:
         knobs(LSTM_NO_PAD="1")
-    cfg = Config("opt", L=2, T=4, B=6, I=16, H=24)
+    if hidden == 32:
+        knobs(LSTM_MICRO="2")
+    cfg = Config("opt", L=2, T=4, B=6, I=16, H=hidden)
     for flags in (0, 4):
         d, ref = oracle_results(cfg, 5, with_states=False, with_dstates=False)
         r = runner.LstmRunner(cfg.dims, d, with_states=False, with_dstates=False)
