@@ -97,10 +97,14 @@ extern "C" {
  * at every step and receives zero gradients.  The persistent kernels (Section 4) exist for those
  * sizes, and the padded run is faster than the per-step paths at the given size (three to
  * five times with four layers).  Reserve and workspace sizes are those of the padded network, and
- * the copies are part of the weight re-layout that Section 2.3 redoes every pass.  LSTM_NO_PAD=1 in the
+ * the copies are part of the weight re-layout that Section 2.3 redoes every pass.  The smallest
+ * networks (H = 8, 16 or 32 with I <= 64, B <= 8 and L (3 + B) <= 20) are not padded either: one
+ * workgroup runs a whole pass of theirs as given, steps looped inside one launch (the low end of
+ * Section 3.1's range, where a launch costs more than a step); LSTM_MICRO=0 in the environment
+ * switches that off.  LSTM_NO_PAD=1 in the
  * environment runs every shape as given; both size queries return the larger of the padded and the
  * as-given requirement, so a buffer sized under one setting is never too small under the other (the
- * reserve's layout still differs: forward and backward of one reserve must run under one setting, which
+ * reserve's layout still differs: forward and backward of one reserve must run under one setting of both variables, which
  * holds by itself because settings are only read again after lstm_shutdown). */
 size_t lstm_reserve_bytes(int L, int T, int B, int I, int H);
 
