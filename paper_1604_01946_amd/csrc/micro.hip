@@ -172,15 +172,15 @@ __device__ __forceinline__ void micro_fwd_layer(const MicroFwdArgs& a, const int
   }
   const bool cell = tid < BH;  // one cell per thread: batch row tid / H, unit tid % H
   float c_state = (cell && a.c0) ? a.c0[(size_t)l * BH + tid] : 0.f;
+  const float h0v = (cell && a.h0) ? a.h0[(size_t)l * BH + tid] : 0.f;
   const int xo = tid < BI ? (tid / Il) * KP + tid % Il : -1;  // where this thread's element of x_t goes in act
-  __syncthreads();  // the layer before has finished with the LDS arrays, and its hidden states are written
+  // The first layer's weights, states and first staged steps are all requested before anything waits: one trip.
+  if (l > 0) __syncthreads();  // the layer before has finished with the LDS arrays, and its hidden states are written
   for (int e = tid; e < kMicroMaxB * KP; e += kMicroThreads) m.act[e] = 0.f;
-  __syncthreads();
-  if (cell) m.act[(tid / H) * KP + Il + tid % H] = a.h0 ? a.h0[(size_t)l * BH + tid] : 0.f;
   const bool vec = (BI & 3) == 0 && aligned16_dev(in);
   for (int t0 = 0; t0 < T; t0 += a.C) {
     const int c = min(a.C, T - t0), n = c * BI;
-    __syncthreads();  // the steps before have finished with sx
+    if (t0 > 0) __syncthreads();  // the steps before have finished with sx
     if (vec) {
       Segs<1> s;
       s.src[0] = reinterpret_cast<const float4*>(in + (size_t)t0 * BI);
@@ -190,6 +190,7 @@ __device__ __forceinline__ void micro_fwd_layer(const MicroFwdArgs& a, const int
       stage_scalar<8>(sx, in + (size_t)t0 * BI, n, tid);
     }
     __syncthreads();
+    if (t0 == 0 && cell) m.act[(tid / H) * KP + Il + tid % H] = h0v;
     if (xo >= 0) m.act[xo] = sx[tid];
     lds_barrier();
     for (int tt = 0; tt < c; ++tt) {
@@ -307,10 +308,11 @@ __device__ __forceinline__ void micro_bwd_layer(const MicroBwdArgs& a, const int
   }
   const bool cell = tid < BH;
   float dc = (cell && a.dcT) ? a.dcT[(size_t)l * BH + tid] : 0.f;
+  const float dhv = (cell && a.dhT) ? a.dhT[(size_t)l * BH + tid] : 0.f;
   const int xo = tid < BI ? (tid / Il) * KP + tid % Il : -1;
-  __syncthreads();  // the layer above has finished with the LDS arrays
+  // The top layer's weights, states and first staged steps are all requested before anything waits: one trip.
+  if (l < a.L - 1) __syncthreads();  // the layer above has finished with the LDS arrays, and has written `hand`
   for (int e = tid; e < kMicroMaxB * KP; e += kMicroThreads) m.act[e] = 0.f;
-  if (cell) m.dhs[tid] = a.dhT ? a.dhT[(size_t)l * BH + tid] : 0.f;
   const bool vec = (BI & 3) == 0 && aligned16_dev(in);
   for (int t1 = T; t1 > 0;) {
     const int t0 = max(0, t1 - a.C), c = t1 - t0;
@@ -332,10 +334,11 @@ __device__ __forceinline__ void micro_bwd_layer(const MicroBwdArgs& a, const int
     s.end[5] = ox >> 2;
     s.src[6] = reinterpret_cast<const float4*>(in + (size_t)t0 * BI);
     s.end[6] = s.end[5] + (vec ? (c * BI) >> 2 : 0);
-    __syncthreads();  // the steps before have finished with the staged arrays; the layer above has written `hand`
+    if (t1 < T) __syncthreads();  // the steps before have finished with the staged arrays
     stage_segs<7, 8>(m.staged4, s, tid);
     if (!vec) stage_scalar<8>(staged + ox, in + (size_t)t0 * BI, c * BI, tid);
     __syncthreads();
+    if (t1 == T && cell) m.dhs[tid] = dhv;  // read back by this thread only, in the point-wise stage below
     for (int tt = c - 1; tt >= 0; --tt) {
       const int t = t0 + tt;
       // ---- point-wise stage: gate gradients of step t; [x_t | h_{t-1}] for the weight gradients
