@@ -22,7 +22,7 @@
  * as a wavefront inside one launch (2.4; as many layers per launch as L*H/8 workgroups fit the CUs,
  * deeper stacks as consecutive groups of layers): their 32-row tile per workgroup holds, for 8 hidden units,
  * r, z and the input and recurrent halves of n (GRU), or the one gate and three empty groups
- * (single gate); with H = 1024 (B <= 512; single gate 256) or H = 2048 (B <= 192; single gate 96) the one-layer persistent kernels
+ * (single gate); with H = 1024 (B <= 512; single gate 256) or H = 2048 (B <= 320; single gate 96) the one-layer persistent kernels
  * with the recurrent matrix spread over all CUs.  Every other shape runs on the rungs of the paper's ladder that do not depend on the
  * cell: the input products of a layer batched over all steps (Section 2.3), the gates grouped into
  * one recurrent product per step (2.1), one fused point-wise kernel per step (2.2.2).  Weight

@@ -713,7 +713,8 @@ hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, boo
   if (nprob > kMaxGemmGroup) return hipErrorInvalidValue;
   GemmGroupArgs g;
   bool big = true;
-  long total_big = 0;
+  long total_big = 0, total_small = 0;
+  double area = 0.0;
   // one kernel instance serves the whole group: operands that cannot all take the same vector
   // loader fall back to the scalar one
   int ma = -1, mb = -1;
@@ -721,6 +722,8 @@ hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, boo
     g.p[i] = probs[i];
     if (probs[i].M < 96 || probs[i].N < 96) big = false;
     total_big += (long)((probs[i].M + 127) / 128) * ((probs[i].N + 127) / 128);
+    total_small += (long)((probs[i].M + 63) / 64) * ((probs[i].N + 63) / 64);
+    area += (double)probs[i].M * probs[i].N;
     const int a = pick_mode(probs[i].A, probs[i].sAm, probs[i].sAk, probs[i].M, probs[i].K);
     const int b = pick_mode(probs[i].B, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);
     ma = (i == 0 || ma == a) ? a : LM_SCALAR;
@@ -736,8 +739,20 @@ hipError_t launch_group(const GemmProblem* probs, int nprob, int main_probs, boo
   for (int i = 0; i < nprob && dl; ++i)
     dl = probs[i].K % KT == 0 && probs[i].K >= KT && dl_operand_ok(ma, probs[i].sAm, probs[i].sAk, probs[i].M, probs[i].K) &&
          dl_operand_ok(mb, probs[i].sBn, probs[i].sBk, probs[i].N, probs[i].K);
-  // Few large tiles leave most of the 256 CUs idle; fall back to 64x64 tiles then.
-  if (total_big < 128) big = false;
+  // 128 x 128 or 64 x 64 tiles: whichever the counts of tiles promise more from.  Measured on 256 CUs (forward
+  // products of one step, K = 2H = 4096 ... 8192): one 128 x 128 workgroup per CU runs at 128 TFLOP/s, two on a CU
+  // take 1.85 times as long as one and three 2.7 times (142 TFLOP/s when every CU has three), so between those counts
+  // the rate follows the fullest CU: 288 tiles 80 TFLOP/s, 384 tiles 105.  The 64 x 64 kernel reaches 116 TFLOP/s from
+  // two tiles per CU on.  Both are scaled by the part of their tiles that the product really covers.
+  if (big && !split) {
+    const double cus = (double)std::max(device_cu_count(), 1);
+    const double nb = (double)total_big / cus, ns = (double)total_small / cus;
+    const double rate_big = nb <= 1.0 ? 128.0 * nb
+                          : (nb <= 2.0 ? 128.0 * nb / 1.85 : (nb <= 3.0 ? 128.0 * nb / 2.7 : 138.0));
+    const double rate_small = 116.0 * std::min(1.0, ns / 2.0);
+    const double use_big = area / ((double)total_big * 128.0 * 128.0), use_small = area / ((double)total_small * 64.0 * 64.0);
+    big = rate_big * use_big >= rate_small * use_small;
+  }
   if (split) big = true;
   // The 128 x 128 kernel is slower with a K-contiguous A operand than with a K-contiguous B operand (2048 x 2048 x 8192:
   // A K- / B row-contiguous 121 TFLOP/s, both K-contiguous 134, A row- / B K-contiguous 142, both row-contiguous 143;

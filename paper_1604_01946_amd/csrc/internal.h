@@ -26,6 +26,7 @@ struct GemmProblem {
 constexpr int kMaxGemmGroup = 16;
 // A group of independent products executed by one launch (Section 2.6: the weight
 // update products have no dependencies, so they can all be in flight together).
+int device_cu_count();  // compute units of the current device (0 if it cannot be read); persistent.hip
 hipError_t launch_gemm_group(const GemmProblem* probs, int nprob, hipStream_t stream);
 // One product, with the tiles of its last partial round (or all of them, when they are fewer than the chip holds
 // workgroups) cut along K; `part` (16-byte aligned, part_bytes long, free until the stream has passed the call) takes

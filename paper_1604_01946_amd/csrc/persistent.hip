@@ -184,12 +184,16 @@ BatchPlan batch_plan(int B) {
 // two layers at H = 512, up to four at H = 256; L = 1, H = 512, B = 64, T = 100: forward recurrence 0.40 ms on four
 // slices of 16 rows, 0.53 on two of 32, 0.74 on the wide kernel; backward 0.65 against 1.14).  `env` names the
 // setting that pins the choice (LSTM_FWD_NARROW / LSTM_BWD_NARROW): 1 = one slice on the narrow kernel (B <= 64), 0 = never slices.
-int narrow_slice_rows(const Dims& d, int cell, int pinned) {
+// Backward, from H = 256 on, slices of 32 rows lose to the kernel with two alternating chains per slice of 64 rows
+// (whole iterations, T = 100: L = 2, H = 512, B = 64 2.46 -> 2.28 ms; L = 4, H = 256, B = 64 1.46 -> 1.37; L = 2, H = 256,
+// B = 128 1.55 -> 1.44), while slices of 16 rows stay ahead of it (L = 1, H = 512, B = 64 1.40 against 2.02 ms).
+int narrow_slice_rows(const Dims& d, int cell, int pinned, bool backward) {
   if (cell != 0) return 0;  // the narrow kernels are LSTM kernels
   if (pinned >= 0 || knobs().two_chains) return 0;
   DeviceInfo di;
   if (!device_info(di)) return 0;
   for (int rows = 16; rows <= 32; rows *= 2) {
+    if (backward && rows == 32 && d.H >= 256) break;
     const int n = (d.B + rows - 1) / rows;
     if (d.B > rows && (long)d.L * (d.H / 8) * n <= di.cus && n <= 16 / d.L) return rows;  // 16 (slice, layer) counter blocks
   }
@@ -291,9 +295,11 @@ void release_persistent() {
 // Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward):
 // measured faster than the step kernels up to here (108 against 89 TFLOP/s at B = 512).
 constexpr int kLargeMaxBatch1024 = 512;
-// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice, at a constant 5.8 ms per slice
-// and 100 steps, which the step kernels (streaming R once per step for the whole batch) undercut from about 200 rows on.
-constexpr int kLargeMaxBatch2048 = 192;
+// At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice, at a constant 5.55 ms per slice
+// and 100 steps (116-119 TFLOP/s for forward, backward and weight gradients together).  The step kernels and GEMM
+// rungs, which stream R once per step for the whole batch, gain with the batch: 96 TFLOP/s at 192 rows, 110 at 256,
+// 107 at 384, 121 at 512.
+constexpr int kLargeMaxBatch2048 = 448;
 
 bool persistent_large(const Dims& d, bool backward) {
   if (knobs().no_large_persistent) return false;
@@ -558,7 +564,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
   DeviceInfo di;
   (void)device_info(di);
-  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().fwd_narrow);
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().fwd_narrow, false);
   const bool narrow_slices = slice_rows_narrow > 0;
   const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
   const int BP = 16 * bp.NT;
@@ -710,7 +716,7 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   const size_t TB = (size_t)d.T * d.B, G = 4 * (size_t)d.H, GW = (cell == 0 ? 4 : (cell == 1 ? 3 : 1)) * (size_t)d.H;
   hipStream_t s = a.stream;
   if (!ensure_watchdog()) return LSTM_HIP_ERROR;
-  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().bwd_narrow);
+  const int slice_rows_narrow = narrow_slice_rows(d, cell, knobs().bwd_narrow, true);
   const bool narrow_slices = slice_rows_narrow > 0;
   const BatchPlan bp = narrow_slices ? BatchPlan{slice_rows_narrow / 16, 1} : batch_plan(d.B);
   const bool wide = cell != 0 || (!narrow_slices && bwd_wide(d));

@@ -28,8 +28,6 @@ int run_forward_persistent(const FwdArgs& a, int cell = 0);
 int run_backward_persistent(const BwdArgs& a, int cell = 0, bool* bias_done = nullptr, LayerGradients* lg = nullptr);
 bool persistent_supported(const Dims& d, bool backward);
 
-int device_cu_count();
-
 // Per-shape overrides of the automatic choice (lstm_set_path), a few entries, guarded by a mutex.
 namespace {
 struct PathOverride {
@@ -110,11 +108,16 @@ unsigned resolve_auto_path(const Dims& user, bool backward) {
   if (persistent_supported(d, backward)) return LSTM_PATH_PERSISTENT;
   const int cus = device_cu_count();
   // Section 3.2 observes that at large minibatches the individual optimisations stop paying.  Here: once the plain
-  // [B x 4H] x [H] product of one step fills every CU with 128 x 128 tiles, the GEMM kernel (grouped gates, fused
-  // point-wise kernel) beats the forward step kernel by 15-20 % (H = 4096 with B >= 256, H = 2048 with B >= 512,
-  // H = 1024 with B >= 1024).  Backward the split-K step kernel stays ahead at every size measured (its contraction
-  // is four times longer, and it fuses the point-wise work that the GEMM rung runs as a second kernel).
-  if (!backward && cus > 0 && (long)((d.B + 127) / 128) * (4L * d.H / 128) >= cus) return LSTM_PATH_FUSED;
+  // [B x 4H] x [H] product of one step gives every CU three 64 x 64 tiles (or one of 128 x 128), the GEMM kernel
+  // (grouped gates, fused point-wise kernel) beats the forward step kernel and the stream wavefront by 5-20 %: H = 4096
+  // from B = 128 on (there already with two tiles per CU: 113 against 107 TFLOP/s), H = 3072 from 256 (115 against
+  // 109), H = 1536 from 512 (115 against 100), H = 1024 from 768 (110 against 93).  Backward the split-K step kernel
+  // stays ahead at every size measured (its contraction is four times longer, and it fuses the point-wise work that
+  // the GEMM rung runs as a second kernel).
+  if (!backward && cus > 0) {
+    const long small_tiles = (long)((d.B + 63) / 64) * (4L * d.H / 64);
+    if (small_tiles >= 3L * cus || (d.H >= 4096 && small_tiles >= 2L * cus)) return LSTM_PATH_FUSED;
+  }
   // Overlapping layers on streams pays when one step kernel leaves CUs idle (Section 2.4: the
   // gain is largest for small layers); a step that already fills the chip runs layer by layer.
   const long wgs = (long)((d.H + 3) / 4) * ((d.B + 63) / 64);
