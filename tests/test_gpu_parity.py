@@ -90,6 +90,14 @@ def test_gemm_matches_numpy(M, N, K, layout):
     _gemm_case(M, N, K, layout)
 
 
+# The tile (128 x 128 or 64 x 64) follows how the tiles fill the 256 CUs: half the CUs in large tiles, exactly one large
+# tile per CU, a CU in eight with two, two per CU, and large tiles of which a quarter is empty (M = 192).
+@pytest.mark.parametrize("M,N,K", [(256, 8192, 64), (256, 16384, 32), (384, 12288, 32), (512, 16384, 32), (192, 16384, 48)])
+@pytest.mark.parametrize("layout", ["NT", "TN"])
+def test_gemm_tile_choice(M, N, K, layout):
+    _gemm_case(M, N, K, layout)
+
+
 # Products whose tiles do not fill the chip evenly, with a scratch buffer for K slices: the shapes of the time-batched
 # products at T*B = 1600 rows (a last round of few tiles; fewer tiles than places), a ragged last tile row, a product
 # with whole rounds only (nothing to cut), too small a buffer (fewer slices, then none) and no buffer.
