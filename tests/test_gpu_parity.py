@@ -421,6 +421,10 @@ MICRO = [
     Config("m32b2", L=2, T=6, B=2, I=64, H=32, state_std=0.5, dstate_std=0.5),
     Config("m32b1", L=1, T=40, B=1, I=20, H=32, state_std=0.5, dstate_std=0.5),
     Config("m32T1", L=2, T=1, B=7, I=1, H=32, state_std=0.5, dstate_std=0.5),
+    # more steps than are staged in LDS at a time: two lots forward, six backward; with inputs of 5 floats (no
+    # 16-byte alignment: the scalar staging loop) two forward and nine backward
+    Config("m32long", L=2, T=60, B=8, I=64, H=32, state_std=0.5, dstate_std=0.5),
+    Config("m8long", L=1, T=400, B=8, I=5, H=8, state_std=0.5, dstate_std=0.5),
 ]
 
 
