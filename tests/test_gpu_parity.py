@@ -216,6 +216,15 @@ PERS = [
 ]
 
 
+def test_persistent_many_slices():
+    """A batch of many 64-row slices (beyond the 2048 rows that were once the limit of the persistent path), ragged last slice."""
+    _, binding, _ = _mods()
+    cfg = Config("p128b2100", L=2, T=3, B=2100, I=40, H=128, state_std=0.5, dstate_std=0.5)
+    assert binding.lstm_auto_path(*cfg.dims, 0) == binding.LSTM_PATH_PERSISTENT
+    assert binding.lstm_auto_path(*cfg.dims, 1) == binding.LSTM_PATH_PERSISTENT
+    run_case(cfg, 21, 0)
+
+
 @pytest.mark.parametrize("cfg", PERS, ids=[c.name for c in PERS])
 @pytest.mark.parametrize("with_states", [True, False])
 def test_persistent_shapes(cfg, with_states):
