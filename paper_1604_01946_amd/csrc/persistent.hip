@@ -502,7 +502,7 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
 bool gru_persistent_supported(const Dims& d) {
   if (persistent_large(d, false) && persistent_large(d, true)) return true;  // one-layer kernels, H = 1024 / 2048
   if (!(d.H == 128 || d.H == 256 || d.H == 512)) return false;
-  if (d.B > 2048) return false;
+  if (d.B > 16384) return false;  // (the cells' own limits are lower: rnn_cells.hip)
   DeviceInfo di;
   if (!device_info(di) || !di.coop) return false;
   return d.H / 8 <= di.cus;  // deeper stacks than the chip holds run as groups of layers
