@@ -88,8 +88,8 @@ extern "C" {
 /* Bytes of the opaque `reserve` buffer that lstm_forward fills for lstm_backward.
  * Returns 0 if any dimension is non-positive.
  *
- * Hidden sizes below 512 other than 128 and 256 (with B <= 512, and more than a few steps of one
- * layer) are computed at the next of 128, 256, 512, and sizes from 704 to 1023 (with B <= 128) at
+ * Hidden sizes below 512 other than 128 and 256 (with more than a few steps of one layer; above
+ * 512 rows not the sizes from 257 to 415) are computed at the next of 128, 256, 512, and sizes from 704 to 1023 (with B <= 128) at
  * 1024: the library copies W, R, b, the initial states
  * and, backward, the upstream gradients into zero-padded buffers inside the workspace, runs the
  * padded network on the chosen path and copies the results back.  The result is that of the

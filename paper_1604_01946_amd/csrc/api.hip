@@ -204,9 +204,15 @@ int padded_hidden_rule(const Dims& d) {
   // 704 <= H < 1024 with up to 128 rows: the one-layer persistent kernels of H = 1024 are 5-40 % faster than the step
   // kernels at the given size (with more rows, or sizes nearer 512, the extra arithmetic costs more than it saves)
   if (d.H >= 704 && d.H < 1024 && d.B <= 128) return 1024;
-  if (d.H >= 512 || d.B > 512) return d.H;  // B: the persistent kernels take up to 512 rows
+  if (d.H >= 512 || d.B > 16384) return d.H;  // B: the limit of the persistent kernels
   if (d.L == 1 && d.T < 32) return d.H;     // a few steps of one layer: the copies would cost more than they save
-  return d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);
+  const int p = d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);
+  // Above 512 rows the per-step kernels and the GEMM rung have enough to do at the given size, and padding to 512
+  // pays only while it adds little arithmetic (L = 4, B = 1024: H = 448 75 TFLOP/s padded against 62 as given,
+  // H = 384 55 against 55, H = 320 39 against 43; B = 2048: H = 384 56 against 72); padding to 128 or 256 pays at
+  // every batch size (H = 200, B = 2048: 47 against 38; H = 100: 26 against 18).
+  if (d.B > 512 && p == 512 && d.H < 416) return d.H;
+  return p;
 }
 
 }  // namespace lstm

@@ -66,7 +66,10 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 800) == 2 * 5 * 3 * 6 * 1024 * 4     # nearer 1024: the one-layer kernels
     assert B.lstm_reserve_bytes(2, 5, 200, 8, 800) == 2 * 5 * 200 * 6 * 800 * 4  # but only for small batches
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 1100) == 2 * 5 * 3 * 6 * 1100 * 4
-    assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 100 * 4  # and batches the persistent kernels do not take
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 128 * 4  # large batches: still padded up to 128 / 256
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 448) == 2 * 5 * 600 * 6 * 512 * 4  # ... and to 512 from H = 416 on
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 384) == 2 * 5 * 600 * 6 * 384 * 4  # ... in between the given size is the faster one
+    assert B.lstm_reserve_bytes(2, 5, 512, 8, 384) == 2 * 5 * 512 * 6 * 512 * 4  # (up to 512 rows every size below 512 is padded)
     padded = B.lstm_workspace_bytes(2, 5, 3, 8, 100)
     assert padded > B.lstm_workspace_bytes(2, 5, 3, 8, 128) and padded % 256 == 0
     a = 4096
