@@ -349,7 +349,9 @@ inline Dims rnn_padded_rule(int cell, const Dims& d) {  // what the environment 
   // point-wise kernel per step): 2.5-3 times at every size measured
   if (d.H > 512 && d.H < 1024 && gru_persistent_shape(cell, Dims{d.L, d.T, d.B, d.I, 1024}))
     return Dims{d.L, d.T, d.B, d.I, 1024};
-  return Dims{d.L, d.T, d.B, d.I, padded_hidden_rule(d)};
+  // the LSTM's rule, but only where these cells' persistent kernels take the padded shape (their batch limits are lower)
+  const Dims p{d.L, d.T, d.B, d.I, padded_hidden_rule(d)};
+  return (p.H == d.H || gru_persistent_shape(cell, p)) ? p : d;
 }
 inline Dims rnn_padded_dims(int cell, const Dims& d) {
   return (knobs().rnn_no_persistent || knobs().no_pad) ? d : rnn_padded_rule(cell, d);
