@@ -293,8 +293,9 @@ void release_persistent() {
 
 // Large hidden sizes: one layer per launch, the layer's recurrent matrix spread over all CUs.
 // Largest batch the one-layer kernels take at H = 1024 (slices of 32 rows: two side by side forward, four backward):
-// measured faster than the step kernels up to here (108 against 89 TFLOP/s at B = 512).
-constexpr int kLargeMaxBatch1024 = 512;
+// measured faster than the GEMM rung forward with the step kernels backward up to here (L = 1 / L = 4: 108 / 104 against
+// 106 / 102 TFLOP/s at B = 768; 108 / 103 against 116 / 110 at B = 1024).
+constexpr int kLargeMaxBatch1024 = 768;
 // At H = 2048 one slice of 32 rows fills the chip: larger batches run slice after slice, at a constant 5.55 ms per slice
 // and 100 steps (116-119 TFLOP/s for forward, backward and weight gradients together).  The step kernels and GEMM
 // rungs, which stream R once per step for the whole batch, gain with the batch: 96 TFLOP/s at 192 rows, 110 at 256,
