@@ -117,6 +117,36 @@ __global__ void colsum_partial_kernel(const float* __restrict__ in, int rows, in
   __syncthreads();
   if (ry == 0 && col < cols) partial[(long)blockIdx.y * cols + col] = (red[0][cx] + red[1][cx]) + (red[2][cx] + red[3][cx]);
 }
+// The same for cols % 4 == 0 and a 16-byte aligned matrix: grid (ceil(cols/256), kColsumChunks, matrices); a wave reads 1 KB
+// of a row per request (four columns per lane), the four waves take every fourth row, four requests in flight each.
+__global__ void colsum_partial4_kernel(const float* __restrict__ in, int rows, int cols, float* __restrict__ partial) {
+  __shared__ floatx4 red[4][64];
+  in += (size_t)blockIdx.z * rows * cols;
+  partial += (size_t)blockIdx.z * kColsumChunks * cols;
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = blockIdx.x * 256 + 4 * cx;
+  const int per = (rows + kColsumChunks - 1) / kColsumChunks;
+  const int rbeg = blockIdx.y * per, rend = min(rows, rbeg + per);
+  floatx4 s[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) s[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+  if (col < cols) {
+    const float* const base = in + col;
+    int r = rbeg + ry;
+    for (; r + 12 < rend; r += 16) {
+      floatx4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const floatx4*>(base + (long)(r + 4 * u) * cols);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s[u] += v[u];
+    }
+    for (; r < rend; r += 4) s[0] += *reinterpret_cast<const floatx4*>(base + (long)r * cols);
+  }
+  red[ry][cx] = (s[0] + s[1]) + (s[2] + s[3]);
+  __syncthreads();
+  if (ry == 0 && col < cols)
+    *reinterpret_cast<floatx4*>(partial + (long)blockIdx.y * cols + col) = (red[0][cx] + red[1][cx]) + (red[2][cx] + red[3][cx]);
+}
 __global__ void colsum_final_kernel(const float* __restrict__ partial, int cols, float* __restrict__ out) {
   const int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= cols) return;
@@ -176,8 +206,13 @@ hipError_t launch_colsum(const float* in, int rows, int cols, float* partial, fl
 // `count` matrices [rows][cols] one after the other -> out [count][cols]; partial: count * 64 * cols floats.
 hipError_t launch_colsum_batched(const float* in, int rows, int cols, int count, float* partial, float* out,
                                  hipStream_t stream) {
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3((cols + 63) / 64, kColsumChunks, count), dim3(256), 0, stream, in, rows,
-                     cols, partial);
+  const bool vec = cols % 4 == 0 && ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(partial)) & 15u) == 0;
+  if (vec)
+    hipLaunchKernelGGL(colsum_partial4_kernel, dim3((cols + 255) / 256, kColsumChunks, count), dim3(256), 0, stream, in,
+                       rows, cols, partial);
+  else
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3((cols + 63) / 64, kColsumChunks, count), dim3(256), 0, stream, in, rows,
+                       cols, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256, count), dim3(256), 0, stream, partial, cols, out);
