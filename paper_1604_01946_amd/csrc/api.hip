@@ -53,6 +53,7 @@ const Knobs& knobs() {
     k.tiny = !env_is("LSTM_TINY", '0');
     k.gemm_swap = !env_is("LSTM_GEMM_SWAP", '0');
     k.large_pp = !env_is("LSTM_LARGE_PP", '0');
+    k.large_ksplit = !env_is("LSTM_LARGE_KSPLIT", '0');
     k.micro = env_is("LSTM_MICRO", '0') ? 0 : (env_is("LSTM_MICRO", '2') ? 2 : 1);
     k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
     const char* ff = getenv("LSTM_FULL_FENCES");
@@ -157,7 +158,9 @@ WsLayout ws_layout(const Dims& d, bool wide_rows) {
   size_t xchg = L * ((size_t)d.T + 1) * G * Bp * 4;
   if (d.H == 2048 || d.H == 1024) {  // up to four slices of 32 batch rows side by side (one at H = 2048)
     const size_t nbk = d.H / 128, sl = std::min<size_t>(((size_t)d.B + 31) / 32, d.H == 2048 ? 1 : 4);
-    const size_t need = sl * d.T * (nbk * 4 * 128 * 32 + nbk * nbk * 128 * 32) * 4;
+    // (one or two slices at H = 1024 cut their tiles' K in four or two: as many partial sums as four slices)
+    const size_t psl = (d.H == 1024 && sl <= 2) ? 4 : sl;
+    const size_t need = d.T * (sl * nbk * 4 * 128 * 32 + psl * nbk * nbk * 128 * 32) * 4;
     if (need > xchg) xchg = need;
     const size_t fwd = sl * ((size_t)d.T + 1) * d.H * 32 * 4;
     if (fwd > xchg) xchg = fwd;

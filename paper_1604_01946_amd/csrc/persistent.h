@@ -127,7 +127,7 @@ struct PersBwdLArgs {
   const float* dcT;    // [B][H] or null
   float* dA;           // [T][B][4H] gate gradients (standard layout)
   float* X;            // [nsl][T][NBK][4*UB*32] exchange
-  float* Pp;           // [nsl][T][NBK][NBK][UB*32] partial sums
+  float* Pp;           // [nsl][T][NBK][NBK * ks][UB*32] partial sums
   float* dh0;          // [B][H] or null
   float* dc0;          // [B][H] or null
   float* db;           // [4H] or null (must be null when the batch has more than one slice: column sums follow instead)
@@ -136,7 +136,8 @@ struct PersBwdLArgs {
   int* watchdog;
   int T, B;
   int b0;              // first batch row of this launch (a multiple of 32)
-  int nsl;             // batch slices side by side in this launch (grid = nsl * NBK * NBK)
+  int nsl;             // batch slices side by side in this launch (grid = nsl * NBK * NBK * ks)
+  int ks;              // parts that a tile's K is cut into, each on a workgroup of its own: 1, or 4 (H = 1024, one slice)
   int spin_limit;
   int full_fences;
   long long* trace;

@@ -421,12 +421,16 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
   int* flagsA = reinterpret_cast<int*>(a.ws + a.w.flags);
   int* flagsP = flagsA + (size_t)maxsl * d.T * NBK * kFlagInts;
   const bool bias_in_kernel = slices == 1;
+  // A single slice at H = 1024 would occupy 64 CUs: the tiles' K is cut in four, 256 workgroups (LSTM_LARGE_KSPLIT=0:
+  // not); two slices of a single layer cut it in two (with more layers the idle CUs are used by the weight gradients
+  // of the layer above, which is worth more: L = 4, B = 64).
+  const int ks = (d.H != 1024 || !knobs().large_ksplit) ? 1 : (slices == 1 ? (d.L > 1 ? 2 : 4) : ((slices == 2 && d.L == 1) ? 2 : 1));
   // A launch that occupies at most half of the CUs (H = 1024 with one or two slices) leaves room for the weight
   // gradients of the layer above, which are complete once that layer's recurrence is: they run on a side stream
   // while this layer's recurrence runs (Section 2.6 wants them after the propagation of *their* layer, not of all
   // layers).  The side stream starts them behind the counter reset that precedes the persistent launch, so that the
   // launch gets its CUs first and the products fill the rest.  LSTM_NO_WGRAD_OVERLAP=1 keeps one stream.
-  bool overlap = (cell == 0 || lg) && d.L > 1 && 2 * maxsl * NBK * NBK <= di.cus && slices <= cap;
+  bool overlap = (cell == 0 || lg) && d.L > 1 && 2 * maxsl * NBK * NBK * ks <= di.cus && slices <= cap;
   // The side stream and its two events are process-wide: calls from several host threads take turns from the first
   // fork to the join (the enqueue only; the GPU work of different calls still overlaps as their streams allow).
   std::unique_lock<std::mutex> side_turn(g_side_mu, std::defer_lock);
@@ -469,7 +473,7 @@ int run_backward_persistent_large(const BwdArgs& a, int cell, bool* bias_done, L
       k.dc0 = a.dc0 ? a.dc0 + (size_t)l * BH : nullptr;
       k.db = bias_in_kernel ? a.db + (size_t)l * GW : nullptr;
       k.flagsA = flagsA; k.flagsP = flagsP; k.watchdog = g_watch_dev;
-      k.T = d.T; k.B = d.B; k.b0 = 32 * s0; k.nsl = nsl; k.spin_limit = spin_limit(); k.full_fences = full_fences();
+      k.T = d.T; k.B = d.B; k.b0 = 32 * s0; k.nsl = nsl; k.ks = ks; k.spin_limit = spin_limit(); k.full_fences = full_fences();
       k.trace = (g_trace_bytes >= (size_t)d.T * 64) ? g_trace_buf : nullptr;
       k.trace_block = g_trace_block;
       ProfScope ps(LSTM_PHASE_BWD_RECURRENCE, s);

@@ -241,17 +241,21 @@ __global__ void pack_stateL_kernel(const float* __restrict__ h0, float* __restri
 // pre-activations (LSTM); to the r and z pre-activations, W_n x + b_n and R_n h (GRU: the third has no weights here,
 // dh_{t-1} also receives dh_t o z_t); to the one pre-activation (single gate).  For the other cells `res` is that
 // cell's reserve, c0 carries h0, dcT / dc0 are unused, R and db have 3H or H rows.
-template <int HH, int CELL>
+// KS > 1 (a single slice at H = 1024, where NBK x NBK workgroups would leave three quarters of the CUs idle): the tile's
+// K = 4*UB is cut into KS parts, each on a workgroup of its own (ks, i, j); a block's partial sums are then NBK * KS, and
+// the workgroups with ks = 0 finalise as before while the others go straight on to wait for the next step's gradients.
+template <int HH, int CELL, int KS>
 __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   constexpr int H = HH, G = 4 * H, UB = 128, NBK = H / UB;
   constexpr int NG = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1);  // gate blocks of R and db
   constexpr int UF = UB / NBK;               // units a workgroup finalises: 8 or 16
   constexpr int CPT = UF / 8;                // cells per thread in the point-wise stage
-  constexpr int NG8 = 4 * UB / 8;            // 8-k groups of the tile's K = 4*UB
-  constexpr int KP = 4 * UB / 2;             // k-pairs; every wave runs all of them for its 32 output units
-  constexpr int RP = UF == 16 ? 136 : 128;   // k-pairs with weights in registers (more where the staging arrays are larger)
+  constexpr int NG8 = 4 * UB / 8 / KS;       // 8-k groups of this workgroup's part of the tile's K = 4*UB
+  constexpr int KP = 4 * UB / 2 / KS;        // k-pairs; every wave runs all of them for its 32 output units
+  constexpr int RP = KS > 1 ? KP : (UF == 16 ? 136 : 128);  // k-pairs with weights in registers (more where the staging arrays are larger)
   constexpr int LP = KP - RP;                // k-pairs with weights in LDS
-  constexpr int DEPTH = 16;
+  constexpr int DEPTH = NG8 < 16 ? NG8 : 16;
+  constexpr int NPART = NBK * KS;            // partial sums of an output block
   constexpr int kPauseA = 16, kPauseP = 32;  // pauses before the first look at a counter, in units of 64 cycles
   static_assert(NBK % kFlagSub == 0, "arrivals must spread evenly over the counter lines");
   static_assert(UF == 8 || UF == 16, "one or two cells per thread");
@@ -261,8 +265,10 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   float* const ro = xsA + 1024 * CPT;     // [4 gates][32 batch rows][UF units] the same in standard order
   float* const wl = ro + 128 * UF;        // [4 waves][LP][64 lanes]; 152 KB in all
 
-  const int sl = blockIdx.x / (NBK * NBK), bid = blockIdx.x % (NBK * NBK);
+  const int sl = blockIdx.x / (NBK * NBK * KS), bid = blockIdx.x % (NBK * NBK), ks = (blockIdx.x / (NBK * NBK)) % KS;
   const int i = bid / NBK, j = bid % NBK;
+  const bool fin = ks == 0;      // this workgroup finalises (adds the partial sums, point-wise stage, publication)
+  const int g0 = ks * NG8;       // first 8-k group of this workgroup's part
   const int T = a.T, B = a.B;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kk = lane >> 5, n = lane & 31;
@@ -276,7 +282,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     const float* col = a.R + UB * j + 32 * wave + n;
 #pragma unroll
     for (int p = 0; p < KP; ++p) {
-      const int k8 = ((p >> 2) + rot) & (NG8 - 1), m = p & 3;
+      const int k8 = g0 + (((p >> 2) + rot) & (NG8 - 1)), m = p & 3;
       const int unit = UB * i + 8 * (k8 >> 2) + 2 * m + kk;
       const int grp = k8 & 3;
       const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);
@@ -306,11 +312,11 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   const float* const res_gates = CELL == 0 ? a.res : a.res + TB * H;  // the four saved arrays [T][B][4H] (LSTM, GRU)
   const float* const res_c = CELL == 0 ? a.res + TB * 4 * H : a.res;   // c (LSTM) or h: the state array the step reads
   float* const Xs = a.X + (size_t)sl * T * NBK * (4 * UB * 32);
-  float* const Ps = a.Pp + (size_t)sl * T * NBK * NBK * (UB * 32);
+  float* const Ps = a.Pp + (size_t)sl * T * NBK * NPART * (UB * 32);
   int* const fA = a.flagsA + (size_t)sl * T * NBK * kFlagInts;
   int* const fP = a.flagsP + (size_t)sl * T * NBK * kFlagInts;
   auto slotX = [&](int t, int blk) { return Xs + ((size_t)t * NBK + blk) * (4 * UB * 32); };
-  auto slotP = [&](int t, int jb, int ib) { return Ps + (((size_t)t * NBK + jb) * NBK + ib) * (UB * 32); };
+  auto slotP = [&](int t, int jb, int ib) { return Ps + (((size_t)t * NBK + jb) * NPART + ib) * (UB * 32); };
   auto flagA = [&](int t, int blk) { return fA + ((size_t)t * NBK + blk) * kFlagInts; };
   auto flagP = [&](int t, int blk) { return fP + ((size_t)t * NBK + blk) * kFlagInts; };
 
@@ -392,8 +398,10 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
   };
 
   __syncthreads();  // LDS weights are in place
-  fetch_step(T - 1);
-  pointwise_publish(T - 1);
+  if (fin) {
+    fetch_step(T - 1);
+    pointwise_publish(T - 1);
+  }
 
   int rv = rot;
   for (int t = T - 1; t >= 0; --t) {
@@ -413,7 +421,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       asm volatile("" : "+v"(lo));
       // (rot is a multiple of four groups: scalar base + lane offset + immediate)
       auto ldb = [&](int g) {
-        const char* const sb = src + (size_t)(4 * (((g >> 2) + (rv >> 2)) & (NG8 / 4 - 1))) * 1024;
+        const char* const sb = src + (size_t)(g0 + 4 * (((g >> 2) + (rv >> 2)) & (NG8 / 4 - 1))) * 1024;
         bv[g] = *reinterpret_cast<const floatx4*>(sb + lo + (g & 3) * 1024);
       };
       auto ldw = [&](int g) {
@@ -428,7 +436,7 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
       for (int g = 0; g < NG8; ++g) {
         if (g + DEPTH < NG8) ldb(g + DEPTH);
         if (g + 2 < NG8) ldw(g + 2);
-        if (g == NG8 - DEPTH && t > 0) fetch_step(t - 1);  // behind the last exchange load of this step
+        if (g == NG8 - DEPTH && t > 0 && fin) fetch_step(t - 1);  // behind the last exchange load of this step
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           const int pr = g * 4 + m;
@@ -444,44 +452,45 @@ __global__ __launch_bounds__(256) void pers_bwdL_kernel(const PersBwdLArgs a) {
     tr.mark(t, 2);
     __syncthreads();
     {
-      float* const dst = slotP(t, j, i);
+      float* const dst = slotP(t, j, i * KS + ks);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int idx = threadIdx.x + 256 * q;
         xstore4(dst + 4 * idx, *reinterpret_cast<const floatx4*>(stage + 4 * idx));
       }
     }
-    signal(flagP(t, j) + (i & (kFlagSub - 1)) * kFlagStride, a.full_fences);
+    signal(flagP(t, j) + ((i * KS + ks) & (kFlagSub - 1)) * kFlagStride, a.full_fences);
     tr.mark(t, 3);
+    if (!fin) continue;
     // A poll that comes too early is in the way of the arrivals it waits for (every wave of every workgroup polls):
     // the first look at a counter is held back until the arrivals are about due.  cfg4 backward recurrence (ms) by
     // pause before the poll for the dA slot / for the partial sums, in units of 64 cycles: none 2.84, 8 / 8 2.80,
     // 16 / 16 2.74, 16 / 32 2.67, 16 / 24 2.70, 12 / 32 2.71, 20 / 32 2.69, 16 / 40 2.71, 24 / 48 2.73, 32 / 64 2.83.
     __builtin_amdgcn_s_sleep(kPauseP);
-    w.wait(flagP(t, j), NBK);
+    w.wait(flagP(t, j), NPART);
     tr.mark(t, 4);
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {  // dh_rec of this thread's cells: the NBK partial sums in fixed order
-      float pv[NBK];
+      float pv[NPART];
 #pragma unroll
-      for (int ib = 0; ib < NBK; ++ib) pv[ib] = slotP(t, j, ib)[(UF * i + 8 * c + j8) * 32 + n];
+      for (int ib = 0; ib < NPART; ++ib) pv[ib] = slotP(t, j, ib)[(UF * i + 8 * c + j8) * 32 + n];
       float sum = 0.f;
 #pragma unroll
-      for (int ib = 0; ib < NBK; ++ib) sum += pv[ib];
+      for (int ib = 0; ib < NPART; ++ib) sum += pv[ib];
       dh_rec[c] = CELL == 1 ? sum + dc[c] : sum;
     }
     tr.mark(t, 5);
     if (t > 0) pointwise_publish(t - 1);
     tr.mark(t, 6);
   }
-  if (valid) {
+  if (valid && fin) {
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       if (a.dh0) a.dh0[(size_t)bb * H + cu[c]] = dh_rec[c];
       if (CELL == 0 && a.dc0) a.dc0[(size_t)bb * H + cu[c]] = dc[c];
     }
   }
-  if (a.db) {  // single slice: this workgroup owns its units for every batch row, plain sums, no atomics
+  if (a.db && fin) {  // single slice: this workgroup owns its units for every batch row, plain sums, no atomics
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < CPT; ++c)
@@ -508,15 +517,15 @@ hipError_t launch_fwdL(const PersFwdLArgs& a, hipStream_t s) {
   return launch_resident(fn, a.nsl * (HH / 8), params, (unsigned)smem, s);
 }
 
-template <int HH, int CELL>
+template <int HH, int CELL, int KS = 1>
 hipError_t launch_bwdL(const PersBwdLArgs& a, hipStream_t s) {
-  constexpr int NBK = HH / 128, UF = 128 / NBK, LP = 256 - (UF == 16 ? 136 : 128);
+  constexpr int NBK = HH / 128, UF = 128 / NBK, LP = KS > 1 ? 0 : 256 - (UF == 16 ? 136 : 128);
   const size_t smem = (4096 + 128 * (size_t)UF + 128 * (size_t)UF + (size_t)4 * LP * 64) * sizeof(float);
-  const void* fn = (const void*)pers_bwdL_kernel<HH, CELL>;
+  const void* fn = (const void*)pers_bwdL_kernel<HH, CELL, KS>;
   static bool attr_set = false;
   if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdLArgs*>(&a)};
-  return launch_resident(fn, a.nsl * NBK * NBK, params, (unsigned)smem, s);
+  return launch_resident(fn, a.nsl * NBK * NBK * KS, params, (unsigned)smem, s);
 }
 
 }  // namespace
@@ -535,6 +544,14 @@ hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s
   if (H == 2048) {
     return cell == 0 ? launch_bwdL<2048, 0>(k, s) : (cell == 1 ? launch_bwdL<2048, 1>(k, s)
                      : (cell == 2 ? launch_bwdL<2048, 2>(k, s) : launch_bwdL<2048, 3>(k, s)));
+  }
+  if (k.ks == 4) {
+    return cell == 0 ? launch_bwdL<1024, 0, 4>(k, s) : (cell == 1 ? launch_bwdL<1024, 1, 4>(k, s)
+                     : (cell == 2 ? launch_bwdL<1024, 2, 4>(k, s) : launch_bwdL<1024, 3, 4>(k, s)));
+  }
+  if (k.ks == 2) {
+    return cell == 0 ? launch_bwdL<1024, 0, 2>(k, s) : (cell == 1 ? launch_bwdL<1024, 1, 2>(k, s)
+                     : (cell == 2 ? launch_bwdL<1024, 2, 2>(k, s) : launch_bwdL<1024, 3, 2>(k, s)));
   }
   return cell == 0 ? launch_bwdL<1024, 0>(k, s) : (cell == 1 ? launch_bwdL<1024, 1>(k, s)
                    : (cell == 2 ? launch_bwdL<1024, 2>(k, s) : launch_bwdL<1024, 3>(k, s)));

@@ -263,6 +263,14 @@ def test_persistent_large_hidden(cfg, with_states):
     run_case(cfg, 12, binding.LSTM_PATH_PERSISTENT, with_states=with_states, with_dstates=with_states)
 
 
+# H = 1024 with one or two slices cuts the backward tiles' K over the idle CUs; LSTM_LARGE_KSPLIT=0 keeps one workgroup
+# per tile covered there.
+@pytest.mark.parametrize("name", ["l1024b32", "l1024b7", "l1024b64", "l1024b33"])
+def test_large_hidden_whole_tiles_backward(name, knobs):
+    knobs(LSTM_LARGE_KSPLIT="0")
+    run_case(next(c for c in LARGE if c.name == name), 14, 0)
+
+
 # H = 2048 runs forward on the kernel with two alternating chains of 16 rows per slice; LSTM_LARGE_PP=0 keeps the
 # one-chain kernel (the one the other cells and H = 1024 use)
 @pytest.mark.parametrize("name", ["l2048b32", "l2048b5", "l2048b40", "l2048T1"])
