@@ -53,6 +53,12 @@ def library():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_1604_01946_amd.build`")
+        # PyTorch ships a HIP runtime of its own.  Loaded first, it is the one this library binds to as well; the
+        # other way round the process ends up with two runtimes, and the second one finds no device.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(LIB_PATH)
         i, p, z, u, l = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint, ctypes.c_long
         lib.lstm_reserve_bytes.restype = z
