@@ -204,9 +204,15 @@ hipError_t launch_resize(float* dst, const float* src, long outer, int rd, int c
 int padded_hidden(const Dims& d) { return (knobs().no_pad || micro_shape(d)) ? d.H : padded_hidden_rule(d); }
 
 int padded_hidden_rule(const Dims& d) {
-  // 704 <= H < 1024 with up to 128 rows: the one-layer persistent kernels of H = 1024 are 5-40 % faster than the step
-  // kernels at the given size (with more rows, or sizes nearer 512, the extra arithmetic costs more than it saves)
-  if (d.H >= 704 && d.H < 1024 && d.B <= 128) return 1024;
+  // 512 < H < 1024: the one-layer persistent kernels of H = 1024 against the step kernels at the given size (which
+  // have no weights on chip).  Padded, the rate in terms of the given network is about 105 (H/1024)^2 TFLOP/s at 64 rows
+  // and more, and better than that of the given size wherever the latter is short of rows or of arithmetic: with up
+  // to 64 rows everywhere (L = 4, B = 64: H = 544 17.5 ms as given, 12.8 padded), with up to 128 rows from H = 608 on,
+  // up to 256 from 640, up to 768 (the limit of those kernels) from 832.
+  if (d.H > 512 && d.H < 1024 && d.B <= 768) {
+    const int hmin = d.B <= 64 ? 513 : (d.B <= 128 ? 608 : (d.B <= 256 ? 640 : 832));
+    if (d.H >= hmin) return 1024;
+  }
   if (d.H >= 512 || d.B > 16384) return d.H;  // B: the limit of the persistent kernels
   if (d.L == 1 && d.T < 32) return d.H;     // a few steps of one layer: the copies would cost more than they save
   const int p = d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);

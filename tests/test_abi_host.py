@@ -62,9 +62,14 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_reserve_bytes(1, 40, 3, 8, 100) == 40 * 3 * 6 * 128 * 4
     assert B.lstm_reserve_bytes(1, 8, 3, 8, 100) == 8 * 3 * 6 * 100 * 4          # a few steps of one layer: not worth the copies
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 256) == 2 * 5 * 3 * 6 * 256 * 4      # native sizes stay as they are
-    assert B.lstm_reserve_bytes(2, 5, 3, 8, 640) == 2 * 5 * 3 * 6 * 640 * 4      # and so do sizes just above 512
-    assert B.lstm_reserve_bytes(2, 5, 3, 8, 800) == 2 * 5 * 3 * 6 * 1024 * 4     # nearer 1024: the one-layer kernels
-    assert B.lstm_reserve_bytes(2, 5, 200, 8, 800) == 2 * 5 * 200 * 6 * 800 * 4  # but only for small batches
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 520) == 2 * 5 * 3 * 6 * 1024 * 4     # between 512 and 1024: the one-layer kernels of 1024
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 800) == 2 * 5 * 3 * 6 * 1024 * 4
+    assert B.lstm_reserve_bytes(2, 5, 100, 8, 600) == 2 * 5 * 100 * 6 * 600 * 4  # with more rows only from a larger size on
+    assert B.lstm_reserve_bytes(2, 5, 100, 8, 608) == 2 * 5 * 100 * 6 * 1024 * 4
+    assert B.lstm_reserve_bytes(2, 5, 200, 8, 800) == 2 * 5 * 200 * 6 * 1024 * 4
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 800) == 2 * 5 * 600 * 6 * 800 * 4
+    assert B.lstm_reserve_bytes(2, 5, 600, 8, 832) == 2 * 5 * 600 * 6 * 1024 * 4
+    assert B.lstm_reserve_bytes(2, 5, 800, 8, 900) == 2 * 5 * 800 * 6 * 900 * 4  # beyond the batch those kernels take: as given
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 1100) == 2 * 5 * 3 * 6 * 1100 * 4
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 128 * 4  # large batches: still padded up to 128 / 256
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 448) == 2 * 5 * 600 * 6 * 512 * 4  # ... and to 512 from H = 416 on
