@@ -90,7 +90,8 @@ extern "C" {
  *
  * Hidden sizes below 512 other than 128 and 256 (with more than a few steps of one layer; above
  * 512 rows not the sizes from 257 to 415) are computed at the next of 128, 256, 512, and sizes between 512 and 1024 at 1024
- * (with up to 64 rows; up to 128 rows from 608, up to 256 from 640, up to 768 from 832): the library copies W, R, b, the initial states
+ * (with up to 64 rows; up to 128 rows from 608, up to 256 from 640, up to 768 from 832), sizes from 1472 (up to
+ * 32 rows) or 1664 (up to 64 rows) to 2047 at 2048: the library copies W, R, b, the initial states
  * and, backward, the upstream gradients into zero-padded buffers inside the workspace, runs the
  * padded network on the chosen path and copies the results back.  The result is that of the
  * given network: a hidden unit whose weights, bias and initial state are zero stays at h = c = 0

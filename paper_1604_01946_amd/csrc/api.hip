@@ -213,6 +213,10 @@ int padded_hidden_rule(const Dims& d) {
     const int hmin = d.B <= 64 ? 513 : (d.B <= 128 ? 608 : (d.B <= 256 ? 640 : 832));
     if (d.H >= hmin) return 1024;
   }
+  // 1024 < H < 2048 with few rows: the one-layer kernels of H = 2048 (L = 4, T = 100: 21.6 ms at 32 rows, 43.2 at 64, plus
+  // about 1 ms for the copies) against the step kernels at the given size (B = 32: H = 1536 24.5 ms, H = 1792 28.1;
+  // B = 64: H = 1536 43.0, H = 1792 48.7)
+  if (d.H > 1024 && d.H < 2048 && ((d.B <= 32 && d.H >= 1472) || (d.B <= 64 && d.H >= 1664))) return 2048;
   if (d.H >= 512 || d.B > 16384) return d.H;  // B: the limit of the persistent kernels
   if (d.L == 1 && d.T < 32) return d.H;     // a few steps of one layer: the copies would cost more than they save
   const int p = d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);

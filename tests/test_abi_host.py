@@ -71,6 +71,9 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 832) == 2 * 5 * 600 * 6 * 1024 * 4
     assert B.lstm_reserve_bytes(2, 5, 800, 8, 900) == 2 * 5 * 800 * 6 * 900 * 4  # beyond the batch those kernels take: as given
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 1100) == 2 * 5 * 3 * 6 * 1100 * 4
+    assert B.lstm_reserve_bytes(2, 5, 3, 8, 1500) == 2 * 5 * 3 * 6 * 2048 * 4    # nearer 2048 with few rows: the one-layer kernels of 2048
+    assert B.lstm_reserve_bytes(2, 5, 48, 8, 1500) == 2 * 5 * 48 * 6 * 1500 * 4
+    assert B.lstm_reserve_bytes(2, 5, 48, 8, 1700) == 2 * 5 * 48 * 6 * 2048 * 4
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 100) == 2 * 5 * 600 * 6 * 128 * 4  # large batches: still padded up to 128 / 256
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 448) == 2 * 5 * 600 * 6 * 512 * 4  # ... and to 512 from H = 416 on
     assert B.lstm_reserve_bytes(2, 5, 600, 8, 384) == 2 * 5 * 600 * 6 * 384 * 4  # ... in between the given size is the faster one

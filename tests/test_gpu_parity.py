@@ -413,6 +413,8 @@ PADDED = [
     Config("h300b130", L=2, T=3, B=130, I=40, H=300, state_std=0.3, dstate_std=0.3),  # three batch slices
     Config("h511", L=5, T=3, B=7, I=511, H=511, state_std=0.3, dstate_std=0.3),       # odd size, two groups of layers
     Config("h800", L=2, T=3, B=40, I=800, H=800, state_std=0.3, dstate_std=0.3),      # to 1024: the one-layer kernels
+    Config("h560", L=1, T=32, B=9, I=48, H=560, state_std=0.3, dstate_std=0.3),       # just above 512, few rows: to 1024 as well
+    Config("h1500", L=2, T=3, B=20, I=64, H=1500, state_std=0.3, dstate_std=0.3),     # to 2048 (few rows only)
 ]
 
 
