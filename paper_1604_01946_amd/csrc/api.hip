@@ -218,7 +218,9 @@ int padded_hidden_rule(const Dims& d) {
   // B = 64: H = 1536 43.0, H = 1792 48.7)
   if (d.H > 1024 && d.H < 2048 && ((d.B <= 32 && d.H >= 1472) || (d.B <= 64 && d.H >= 1664))) return 2048;
   if (d.H >= 512 || d.B > 16384) return d.H;  // B: the limit of the persistent kernels
-  if (d.L == 1 && d.T < 32) return d.H;     // a few steps of one layer: the copies would cost more than they save
+  // a few steps of one layer: the copies and the weights' way onto the chip cost more than they save (T = 8: 0.14 ms
+  // padded against 0.12 as given at 16 rows, but 0.16 against 0.20 at 64 rows; T = 16: 0.19 / 0.20 and 0.21 / 0.34)
+  if (d.L == 1 && (d.T < 8 || (d.T < 16 && d.B < 48))) return d.H;
   const int p = d.H <= 128 ? 128 : (d.H <= 256 ? 256 : 512);
   // Above 512 rows the per-step kernels and the GEMM rung have enough to do at the given size, and padding to 512
   // pays only while it adds little arithmetic (L = 4, B = 1024: H = 448 75 TFLOP/s padded against 62 as given,

@@ -61,6 +61,8 @@ def test_hidden_sizes_between_the_native_ones_are_padded(monkeypatch):
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 1) == 2 * 5 * 3 * 6 * 128 * 4
     assert B.lstm_reserve_bytes(1, 40, 3, 8, 100) == 40 * 3 * 6 * 128 * 4
     assert B.lstm_reserve_bytes(1, 8, 3, 8, 100) == 8 * 3 * 6 * 100 * 4          # a few steps of one layer: not worth the copies
+    assert B.lstm_reserve_bytes(1, 8, 64, 8, 100) == 8 * 64 * 6 * 128 * 4        # (with more rows they are, from 8 steps on)
+    assert B.lstm_reserve_bytes(1, 7, 64, 8, 100) == 7 * 64 * 6 * 100 * 4
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 256) == 2 * 5 * 3 * 6 * 256 * 4      # native sizes stay as they are
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 520) == 2 * 5 * 3 * 6 * 1024 * 4     # between 512 and 1024: the one-layer kernels of 1024
     assert B.lstm_reserve_bytes(2, 5, 3, 8, 800) == 2 * 5 * 3 * 6 * 1024 * 4
