@@ -28,7 +28,8 @@
  * one recurrent product per step (2.1), one fused point-wise kernel per step (2.2.2).  Weight
  * gradients are large products after propagation (2.6) in both cases, on the library's MFMA GEMM
  * kernels.  Hidden sizes below 512 other than 128 and 256 run zero-padded to the next of 128, 256, 512,
- * and sizes between 512 and 1024 padded to 1024, on those persistent kernels (same rule, same reasoning and same effect on the reserve and workspace
+ * sizes between 512 and 1024 padded to 1024, and sizes between 1024 and 2048 with few rows (GRU: up to 64, from 1472
+ * on up to 128; single gate: up to 64, from 1536 on up to 96) padded to 2048, on those persistent kernels (same rule, same reasoning and same effect on the reserve and workspace
  * sizes as in lstm.h: a padded unit stays at h = 0 and receives zero gradients, so the result is that of
  * the given network).  RNN_NO_PERSISTENT=1 in the environment keeps every shape, as given, on the
  * step-by-step path.

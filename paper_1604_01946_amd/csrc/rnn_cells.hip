@@ -349,6 +349,13 @@ inline Dims rnn_padded_rule(int cell, const Dims& d) {  // what the environment 
   // point-wise kernel per step): 2.5-3 times at every size measured
   if (d.H > 512 && d.H < 1024 && gru_persistent_shape(cell, Dims{d.L, d.T, d.B, d.I, 1024}))
     return Dims{d.L, d.T, d.B, d.I, 1024};
+  // between 1024 and 2048 likewise, with few rows (GRU, L = 4, T = 100, as given -> at 2048: B = 32 44-68 -> 19 ms, B = 64
+  // 48-78 -> 37.5, B = 128 82 (H = 1536) -> 75 but 55 (H = 1152) as given; single gate: B = 64 26-39 -> 24, B = 96 from 1536 on)
+  if (d.H > 1024 && d.H < 2048) {
+    const bool pad = cell == RNN_CELL_GRU ? (d.B <= 64 || (d.B <= 128 && d.H >= 1472)) : (d.B <= 64 || (d.B <= 96 && d.H >= 1536));
+    const Dims p{d.L, d.T, d.B, d.I, 2048};
+    return (pad && gru_persistent_shape(cell, p)) ? p : d;
+  }
   // the LSTM's rule, but only where these cells' persistent kernels take the padded shape (their batch limits are lower)
   const Dims p{d.L, d.T, d.B, d.I, padded_hidden_rule(d)};
   return (p.H == d.H || gru_persistent_shape(cell, p)) ? p : d;

@@ -106,7 +106,8 @@ def test_cells_match_oracle(cell, dims):
 
 # Hidden sizes below 512 without persistent kernels run zero-padded to 128 / 256 / 512 (as the LSTM's do);
 # RNN_NO_PERSISTENT=1 runs them as given on the step-by-step path, which keeps its ragged tiles covered.
-RAGGED = [(3, 5, 7, 24, 40), (2, 3, 3, 5, 7), (2, 4, 70, 36, 100), (2, 40, 9, 300, 300), (2, 3, 9, 64, 600)]
+# (between 1024 and 2048 with few rows: padded to 2048)
+RAGGED = [(3, 5, 7, 24, 40), (2, 3, 3, 5, 7), (2, 4, 70, 36, 100), (2, 40, 9, 300, 300), (2, 3, 9, 64, 600), (2, 2, 12, 48, 1500)]
 
 
 @pytest.mark.parametrize("step_by_step", [False, True], ids=["padded", "as_given"])
