@@ -168,7 +168,7 @@ hipError_t launch_pack_x32(const float* x, float* xin, int* flags, int L, int T,
 
 // two half-slices of 32 rows alternating on the matrix cores (512 threads per workgroup; exchange slots and counters
 // per chain, see persistent_pp.hip)
-hipError_t launch_fwd_pp(int H, int grid, const PersFwdArgs& a, hipStream_t s);
+hipError_t launch_fwd_pp(int cell, int H, int grid, const PersFwdArgs& a, hipStream_t s);  // cell 0: LSTM, 1: GRU
 hipError_t launch_pack_state_pp(const float* h0, float* hx, int L, int T, int B, int H, int b0, int nsl, hipStream_t s);
 hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int b0, int nsl, hipStream_t s);
 

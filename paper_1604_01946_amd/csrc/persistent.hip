@@ -610,7 +610,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   }
   // LSTM with every layer multiplying its input in the kernel: the two half-slices of 32 rows take turns inside the
   // waves (pers_fwd_pp_kernel); LSTM_PINGPONG=0 keeps the one-chain kernel
-  const bool pp = x_in_kernel && cell == 0 && knobs().pingpong != 0;
+  const bool pp = x_in_kernel && (cell == 0 || (cell == 1 && knobs().gru_pp)) && knobs().pingpong != 0;
   if (!x_in_kernel) {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
     GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
@@ -660,7 +660,7 @@ int forward_layers(const FwdArgs& a, int cell) {
                  pp ? "pers_fwd_pp_kernel" : (wide ? "pers_fwd32_kernel" : "pers_fwd_kernel"));
     }
     hipError_t e = hipErrorInvalidValue;
-    if (pp) e = launch_fwd_pp(d.H, grid * nsl, k, s);
+    if (pp) e = launch_fwd_pp(cell, d.H, grid * nsl, k, s);
     else if (wide) e = launch_fwd_wide(cell, d.H, grid * nsl, k, s);
     else e = launch_fwd_narrow(d.H, bp, grid * nsl, k, s);
     CK(e, "persistent forward launch");

@@ -44,9 +44,13 @@ namespace {
 
 constexpr int pp_count(int lo, int hi, int upto) { return upto < lo ? 0 : ((upto < hi ? upto : hi) - lo + 1); }
 
-template <int HH, int GA_, int PF_, bool TRACE>
+// CELL = 1 runs a GRU on the same machinery, as pers_fwd32_kernel does (convention of rnn.h: gates r, z, n; the reset
+// gate multiplies the recurrent product): the four row groups of a workgroup's tile are then r, z, the input half of
+// n (W_n x, no recurrent weights) and the recurrent half of n (R_n h, no input weights); its reserve is h [T][B][H]
+// followed by r, z, n, R_n h as [T][B][4H], and `c0` is not used (the carried state is h).
+template <int HH, int GA_, int PF_, bool TRACE, int CELL = 0>
 __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
-  constexpr int H = HH, G = 4 * H, NS = H / 8, NL = H / 16;
+  constexpr int H = HH, G = (CELL == 1 ? 3 : 4) * H, NS = H / 8, NL = H / 16;  // G: rows of W, R, b
   constexpr int NK8 = H / 32;        // 8-k groups per wave and operand half (K-quarter of H)
   constexpr int NG = 2 * NK8;        // groups of a block: input half, then recurrent half
   constexpr int LAG = NK8 / 4;       // group at which the recurrent operand's fetch begins (its counter is looked at there)
@@ -84,7 +88,9 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   {
     const float* Rl = a.R + (size_t)l * G * H;
     const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I] with I == H
-    const int gate = n >> 3, par = (n >> 2) & 1, cc = n & 3;
+    const int grp = n >> 3, par = (n >> 2) & 1, cc = n & 3;
+    const int gate = (CELL == 1 && grp == 3) ? 2 : grp;  // matrix row block behind tile row group grp
+    const bool useR = CELL == 0 || grp != 2, useW = CELL == 0 || grp != 3;
     const size_t row = ((size_t)gate * H + u0 + 2 * cc + par) * H;
 #pragma unroll
     for (int i = 0; i < NK8; ++i) {
@@ -92,8 +98,8 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int k = q * (H / 4) + 8 * k8 + 2 * j + kk;
-        wR[i][j] = Rl[row + k];
-        wW[i][j] = Wl[row + k];
+        wR[i][j] = useR ? Rl[row + k] : 0.f;
+        wW[i][j] = useW ? Wl[row + k] : 0.f;
       }
     }
   }
@@ -110,16 +116,17 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   for (int c = 0; c < 2; ++c) {
     bb[c] = a.b0 + 64 * sl + 32 * c + nr;
     valid[c] = bb[c] < B;
-    c_state[c] = (valid[c] && a.c0) ? a.c0[((size_t)l * B + bb[c]) * H + unit] : 0.f;
+    const float* const s0 = CELL == 0 ? a.c0 : a.h0;  // the carried state: c (LSTM), h (GRU)
+    c_state[c] = (valid[c] && s0) ? s0[((size_t)l * B + bb[c]) * H + unit] : 0.f;
   }
   float bias[4];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) bias[g] = a.bias[(size_t)l * G + g * H + unit];
+  for (int g = 0; g < 4; ++g) bias[g] = (CELL == 0 || g < 3) ? a.bias[(size_t)l * G + g * H + unit] : 0.f;
 
-  float* const res_l = a.res + (size_t)l * TB * 6 * H;
-  float* const res_gates = res_l;
-  float* const res_c = res_l + TB * 4 * H;
-  float* const res_h = res_l + TB * 5 * H;
+  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;
+  float* const res_c = res_l + TB * 4 * H;  // LSTM only
+  float* const res_h = CELL == 0 ? res_l + TB * 5 * H : res_l;
   float* const hx = a.hx + (size_t)sl * a.L * (T + 1) * H * 64;
   int* const flags = a.flags + (size_t)sl * a.L * (T + 1) * 2 * NL * kFlagStride;
   auto slot = [&](int layer, int st, int c) { return hx + (((size_t)layer * (T + 1) + st) * 2 + c) * H * 32; };
@@ -254,10 +261,20 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
 #pragma unroll
     for (int g = 0; g < 4; ++g)
       sg[g] = (all[g * 256] + all[1024 + g * 256]) + (all[2048 + g * 256] + all[3072 + g * 256]) + bias[g];
-    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gc = tanhf_dev(sg[3]);
-    const float cn = gf * c_state[c] + gi * gc;
-    const float hn = go * tanhf_dev(cn);
-    c_state[c] = cn;
+    float gi, gf, go, gc, cn, hn;
+    if (CELL == 0) {
+      gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gc = tanhf_dev(sg[3]);
+      cn = gf * c_state[c] + gi * gc;
+      hn = go * tanhf_dev(cn);
+      c_state[c] = cn;
+    } else {  // sg: r and z pre-activations, W_n x + b_n, R_n h; the four saved values: r, z, n, R_n h
+      gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]);
+      go = tanhf_dev(sg[2] + gi * sg[3]);
+      gc = sg[3];
+      hn = (1.f - gf) * go + gf * c_state[c];
+      cn = 0.f;
+      c_state[c] = hn;
+    }
     // publish: the wave's 64 values are two whole 128-byte lines of the slot
     __hip_atomic_store(slot(l, t + 1, c) + (size_t)s * 256 + kk * 128 + 32 * q + p, valid[c] ? hn : 0.f, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
@@ -294,12 +311,12 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
       const int arr = 4 + ((lane >> 4) & 1);
       const floatx4 v = *reinterpret_cast<const floatx4*>(st + arr * 64 + row * 8 + 4 * hf);
       const bool mine = in_batch && lane < 32;
-      float* const dst = (mine && a.keep) ? (arr == 4 ? res_c : res_h) + e : scratch_line;
+      float* const dst = (mine && a.keep && (CELL == 0 || arr == 5)) ? (arr == 4 ? res_c : res_h) + e : scratch_line;
       *reinterpret_cast<floatx4*>(dst) = v;
       float* const dsty = (mine && top && arr == 5) ? a.y + e : scratch_line;
       *reinterpret_cast<floatx4*>(dsty) = v;
       if (lastt && mine) {
-        if (arr == 4 && a.cT) *reinterpret_cast<floatx4*>(a.cT + se) = v;
+        if (CELL == 0 && arr == 4 && a.cT) *reinterpret_cast<floatx4*>(a.cT + se) = v;
         if (arr == 5 && a.hT) *reinterpret_cast<floatx4*>(a.hT + se) = v;
       }
     }
@@ -386,25 +403,32 @@ __global__ __launch_bounds__(256) void pack_x_pp_kernel(const float* __restrict_
   }
 }
 
-template <int HH>
+template <int HH, int CELL>
 hipError_t launch_pp(int grid, const PersFwdArgs& a, hipStream_t s) {
   constexpr int NK8 = HH / 32;
   // the other chain's publication is completed half an operand half into a block (H = 512, group 8; cfg3 forward
   // recurrence by that group: 6 0.964 ms -- the acknowledgement is not there yet --, 7 0.902, 8 0.906, 9 0.910,
   // 10 0.911, 12 0.921), the fetch of its next input starts there as well (from group 10 or 12 on: 0.953)
   constexpr int GA = HH == 512 ? NK8 / 2 : NK8 / 2 + NK8 / 4;
-  const void* fn = a.trace ? (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, true>
-                           : (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, false>;
+  const void* fn = a.trace ? (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, true, CELL>
+                           : (const void*)pers_fwd_pp_kernel<HH, GA, NK8 / 2, false, CELL>;
   void* params[] = {const_cast<PersFwdArgs*>(&a)};
   return launch_resident(fn, grid, params, 0, s);
 }
 
 }  // namespace
 
-hipError_t launch_fwd_pp(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
-  if (H == 512) return launch_pp<512>(grid, a, s);
-  if (H == 256) return launch_pp<256>(grid, a, s);
-  if (H == 128) return launch_pp<128>(grid, a, s);
+hipError_t launch_fwd_pp(int cell, int H, int grid, const PersFwdArgs& a, hipStream_t s) {  // cell 0: LSTM, 1: GRU
+  if (cell == 1) {
+    if (H == 512) return launch_pp<512, 1>(grid, a, s);
+    if (H == 256) return launch_pp<256, 1>(grid, a, s);
+    if (H == 128) return launch_pp<128, 1>(grid, a, s);
+    return hipErrorInvalidValue;
+  }
+  if (cell != 0) return hipErrorInvalidValue;
+  if (H == 512) return launch_pp<512, 0>(grid, a, s);
+  if (H == 256) return launch_pp<256, 0>(grid, a, s);
+  if (H == 128) return launch_pp<128, 0>(grid, a, s);
   return hipErrorInvalidValue;
 }
 
