@@ -17,7 +17,7 @@
  * layers stacked as Section 2.4 describes.  The reset gate multiplies the recurrent product, so the
  * three recurrent matrices run as one stacked product per step (the grouping of Section 2.1).
  *
- * What runs: with H = 128, 256 or 512 (H = 512: B <= 1024, single gate 512; H = 256: 4096 / 2048; H = 128: 8192) the
+ * What runs: with H = 128, 256 or 512 (H = 512: B <= 2048, single gate 512; H = 256: 4096 / 2048; H = 128: 8192) the
  * persistent kernels of lstm.h with the weights on chip for all T steps (Section 4) and the layers
  * as a wavefront inside one launch (2.4; as many layers per launch as L*H/8 workgroups fit the CUs,
  * deeper stacks as consecutive groups of layers): their 32-row tile per workgroup holds, for 8 hidden units,

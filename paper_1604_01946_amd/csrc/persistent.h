@@ -174,7 +174,7 @@ hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int
 
 // backward counterpart: two chains of 16 rows per workgroup (batch half), 16x16x4 tiles; counters of H/16 lines per
 // (layer, step, half, chain), see persistent_bpp.hip
-hipError_t launch_bwd_pp(int H, const PersBwdArgs& a, int nbh, hipStream_t s);
+hipError_t launch_bwd_pp(int cell, int H, const PersBwdArgs& a, int nbh, hipStream_t s);  // cell 0: LSTM, 1: GRU
 
 // a single sequence (B = 1): one wave per two hidden units, the exchanged values are their own flags
 // (persistent_tiny.hip); hx [L][T+1][H], dAx [L][T][4H], dxbuf [L][T][H]

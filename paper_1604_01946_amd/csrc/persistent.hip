@@ -770,7 +770,7 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   }
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
   // two alternating chains per workgroup (LSTM, slices of 64 rows): counters of H/16 lines per (layer, step, quarter)
-  const bool pp = wide && cell == 0 && knobs().pingpong != 0;
+  const bool pp = wide && (cell == 0 || (cell == 1 && knobs().gru_pp)) && knobs().pingpong != 0;
   k.dummy = reinterpret_cast<float*>(a.ws + a.w.scratch);
   k.trace = (g_trace_bytes >= (size_t)d.T * 64 * (pp ? 2 : 1)) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;
@@ -798,7 +798,7 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
       prof_flops(per * d.H * (2 * d.L - 1) + (k.dx0 ? per * d.I : 0.0), pp ? "pers_bwd_pp_kernel" : (wide ? "pers_bwd32_kernel" : "pers_bwd_kernel"));
     }
     hipError_t e = hipErrorInvalidValue;
-    if (pp) e = launch_bwd_pp(d.H, k, 2 * nsl, s);
+    if (pp) e = launch_bwd_pp(cell, d.H, k, 2 * nsl, s);
     else if (wide) e = launch_bwd_wide(cell, d.H, k, 2 * nsl, s);
     else e = launch_bwd_narrow(d.H, bp, grid * nsl, k, s);
     CK(e, "persistent backward launch");

@@ -78,9 +78,14 @@ __device__ __forceinline__ gfloat* pick(bool c, const float* p, const float* q) 
   return reinterpret_cast<gfloat*>(x);
 }
 
-template <int HH, int GA_, int PL_, int KH_, int FUSE_N_, bool TRACE>
+// CELL = 1: GRU, as in pers_bwd32_kernel.  The four K groups are then the gradients with respect to the r and z
+// pre-activations, to W_n x + b_n and to R_n h (the third has no recurrent weights, the fourth no input weights);
+// dh_{t-1} also receives the direct term dh_t o z_t (carried in `dc`); the reserve is h [T][B][H] followed by r, z, n,
+// R_n h as [T][B][4H]; `h0` takes the place of `c0`, dcT / dc0 are unused, R, W and db have 3H rows.
+template <int HH, int GA_, int PL_, int KH_, int FUSE_N_, bool TRACE, int CELL = 0>
 __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, const int NBH) {
   constexpr int H = HH, G = 4 * H, NS2 = H / 16, NL = NS2;
+  constexpr int NGW = CELL == 1 ? 3 : 4, GW = NGW * H;  // gate blocks and rows of R, W, db
   constexpr int NU = H / 16;             // groups of four units per wave (its K quarter)
   constexpr int RG = NU < 16 ? NU : 16;  // groups whose weights live in registers
   constexpr int LG = NU - RG;            // groups whose weights live in LDS
@@ -130,17 +135,18 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   float wreg[RG][4][2];
   {
     const int kq = lane >> 4, row = lane & 15;
-    const float* Rl = a.R + (size_t)l * G * H + u0 + row;
-    const float* Wl = (l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W) + u0 + row;  // layer 0: [G][I], I == H
+    const float* Rl = a.R + (size_t)l * GW * H + u0 + row;
+    const float* Wl = (l > 0 ? a.W + (size_t)GW * a.I + (size_t)(l - 1) * GW * H : a.W) + u0 + row;  // layer 0: [GW][I], I == H
     const bool live1 = l > 0 || a.dx0;
 #pragma unroll
     for (int i = 0; i < NU; ++i) {
       const int ug = w * NU + ((i + rot) & (NU - 1));
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const size_t k = (size_t)(g * H + 4 * ug + kq) * H;
-        const float v0 = Rl[k];
-        const float v1 = live1 ? Wl[k] : 0.f;
+        const int gm = (CELL == 1 && g == 3) ? 2 : g;  // matrix row block behind K group g
+        const size_t k = (size_t)(gm * H + 4 * ug + kq) * H;
+        const float v0 = (CELL == 0 || g != 2) ? Rl[k] : 0.f;
+        const float v1 = (live1 && (CELL == 0 || g != 3)) ? Wl[k] : 0.f;
         if (i < RG) {
           wreg[i < RG ? i : 0][g][0] = v0;
           wreg[i < RG ? i : 0][g][1] = v1;
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     eoff[c] = (size_t)bc * H + u;
     goff[c] = (size_t)bc * G + u;
     const size_t se = (size_t)l * B * H + eoff[c];
-    dc[c] = (valid[c] && a.dcT) ? a.dcT[se] : 0.f;
+    dc[c] = (CELL == 0 && valid[c] && a.dcT) ? a.dcT[se] : 0.f;  // GRU: the direct term dh_t o z_t
     dh_rec[c] = (valid[c] && a.dhT) ? a.dhT[se] : 0.f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) dbsum[c][g] = 0.f;
@@ -175,8 +181,10 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   // B operand role: lane (kq, nn) fetches piece (nn/4)*16 + kq*4 + nn%4 of every 4-unit group of its K quarter
   const unsigned loff = (unsigned)(((lane & 15) >> 2) * 16 + (lane >> 4) * 4 + (lane & 3)) * 16;  // bytes
 
-  const float* const res_gates = a.res + (size_t)l * TB * 6 * H;
-  const float* const res_c = res_gates + TB * 4 * H;
+  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  const float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;
+  const float* const res_c = CELL == 0 ? res_l + TB * 4 * H : res_l;  // c (LSTM) or h: the state array the step reads
+  const float* const s0 = CELL == 0 ? a.c0 : a.h0;
   float* const dA_l = a.dA + (size_t)l * TB * G;
   const bool has_up = l < a.L - 1;
   const float* const dout_base = has_up ? a.dxbuf + (size_t)(l + 1) * TB * H : a.dy;
@@ -221,11 +229,11 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     gf[c] = pg[H];
     go[c] = pg[2 * H];
     gg[c] = pg[3 * H];
-    ct[c] = res_c[(size_t)t * B * H + eoff[c]];
+    if (CELL == 0) ct[c] = res_c[(size_t)t * B * H + eoff[c]];
     const float* const pc = t > 0 ? res_c + (size_t)(t - 1) * B * H + eoff[c]
-                                  : (a.c0 ? a.c0 + (size_t)l * B * H + eoff[c] : res_c + eoff[c]);
+                                  : (s0 ? s0 + (size_t)l * B * H + eoff[c] : res_c + eoff[c]);
     cp[c] = *pc;
-    cp_real[c] = t > 0 || a.c0;
+    cp_real[c] = t > 0 || s0;
   };
   auto fetch_dout = [&](const int c, const int t) { dpre[c] = dout_base[(size_t)t * B * H + eoff[c]]; };
 
@@ -237,14 +245,23 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   float pw_d[4], pw_s[4];
   auto pw_math = [&](const int c, const bool real) {
     const float dh = dpre[c] + dh_rec[c];
-    const float tc = tanhf_dev(ct[c]);
-    const float dcv = dc[c] + dh * go[c] * (1.f - tc * tc);
     const float cpv = cp_real[c] ? cp[c] : 0.f;
-    pw_d[0] = dcv * gg[c] * gi[c] * (1.f - gi[c]);
-    pw_d[1] = dcv * cpv * gf[c] * (1.f - gf[c]);
-    pw_d[2] = dh * tc * go[c] * (1.f - go[c]);
-    pw_d[3] = dcv * gi[c] * (1.f - gg[c] * gg[c]);
-    dc[c] = real ? dcv * gf[c] : dc[c];
+    if (CELL == 0) {
+      const float tc = tanhf_dev(ct[c]);
+      const float dcv = dc[c] + dh * go[c] * (1.f - tc * tc);
+      pw_d[0] = dcv * gg[c] * gi[c] * (1.f - gi[c]);
+      pw_d[1] = dcv * cpv * gf[c] * (1.f - gf[c]);
+      pw_d[2] = dh * tc * go[c] * (1.f - go[c]);
+      pw_d[3] = dcv * gi[c] * (1.f - gg[c] * gg[c]);
+      dc[c] = real ? dcv * gf[c] : dc[c];
+    } else {  // gi, gf, go, gg hold r, z, n, R_n h; cpv is h_{t-1}
+      const float dn = dh * (1.f - gf[c]) * (1.f - go[c] * go[c]);
+      pw_d[0] = dn * gg[c] * gi[c] * (1.f - gi[c]);
+      pw_d[1] = dh * (cpv - go[c]) * gf[c] * (1.f - gf[c]);
+      pw_d[2] = dn;
+      pw_d[3] = dn * gi[c];
+      dc[c] = real ? dh * gf[c] : dc[c];
+    }
     const bool keep = valid[c] && real;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -385,7 +402,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     b_groups(c, 0, 1);
     __builtin_amdgcn_sched_barrier(0);
     // 2: sums, dx out, the arithmetic of the point-wise stage, its gate gradients into LDS -- in between KM groups
-    dh_rec[c] = (h0 + h1) + (h2 + h3);
+    dh_rec[c] = CELL == 1 ? ((h0 + h1) + (h2 + h3)) + dc[c] : (h0 + h1) + (h2 + h3);
     const float dxv = (x0 + x1) + (x2 + x3);
     // (every step issues the same requests, whatever is wanted: what is not goes to the workgroup's scratch line)
     __hip_atomic_store(pick(dx_wanted && valid[o] && tdx < T, dx_out + (size_t)tdx * B * H + eoff[o], dummy), dxv, __ATOMIC_RELAXED,
@@ -509,7 +526,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
     if (valid[c]) {
       const size_t se = (size_t)l * B * H + eoff[c];
       if (a.dh0) a.dh0[se] = dh_rec[c];
-      if (a.dc0) a.dc0[se] = dc[c];
+      if (CELL == 0 && a.dc0) a.dc0[se] = dc[c];
     }
   }
   // Bias gradient (Section 2.6 lists it with the weight update): the per-lane sums over t are added over the 32
@@ -520,17 +537,17 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
 #pragma unroll
     for (int g = 0; g < 4; ++g) part[(g * 16 + m) * 16 + n] = dbsum[0][g] + dbsum[1][g];
     __syncthreads();
-    if (threadIdx.x < 64) {
+    if (threadIdx.x < 16 * NGW) {
       float sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sum += part[threadIdx.x * 16 + ((i + threadIdx.x) & 15)];
-      atomicAdd(a.db + (size_t)l * G + (threadIdx.x >> 4) * H + u0 + (threadIdx.x & 15), sum);
+      atomicAdd(a.db + (size_t)l * GW + (threadIdx.x >> 4) * H + u0 + (threadIdx.x & 15), sum);
     }
   }
   mark(0, 0, 5);
 }
 
-template <int HH>
+template <int HH, int CELL>
 hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
   constexpr int NU = HH / 16, LG = NU > 16 ? NU - 16 : 0;
   const size_t smem = (5120 + (size_t)4 * LG * 2 * 64 * 4) * sizeof(float);
@@ -543,8 +560,8 @@ hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
   constexpr int KH = NU / 4 < 4 ? 4 : NU / 4;
   constexpr int PL = HH == 512 ? 12 : KH;
   const bool trace = a.trace != nullptr;
-  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, true>
-                         : (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, false>;
+  const void* fn = trace ? (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, true, CELL>
+                         : (const void*)pers_bwd_pp_kernel<HH, 1, PL, KH, 6, false, CELL>;
   static bool attr_set[2] = {false, false};
   if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set[trace ? 1 : 0]); e != hipSuccess) return e;
   void* params[] = {const_cast<PersBwdArgs*>(&a), &nbh};
@@ -554,10 +571,17 @@ hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_bwd_pp(int H, const PersBwdArgs& a, int nbh, hipStream_t s) {
-  if (H == 512) return launch_bpp<512>(a, nbh, s);
-  if (H == 256) return launch_bpp<256>(a, nbh, s);
-  if (H == 128) return launch_bpp<128>(a, nbh, s);
+hipError_t launch_bwd_pp(int cell, int H, const PersBwdArgs& a, int nbh, hipStream_t s) {  // cell 0: LSTM, 1: GRU
+  if (cell == 1) {
+    if (H == 512) return launch_bpp<512, 1>(a, nbh, s);
+    if (H == 256) return launch_bpp<256, 1>(a, nbh, s);
+    if (H == 128) return launch_bpp<128, 1>(a, nbh, s);
+    return hipErrorInvalidValue;
+  }
+  if (cell != 0) return hipErrorInvalidValue;
+  if (H == 512) return launch_bpp<512, 0>(a, nbh, s);
+  if (H == 256) return launch_bpp<256, 0>(a, nbh, s);
+  if (H == 128) return launch_bpp<128, 0>(a, nbh, s);
   return hipErrorInvalidValue;
 }
 

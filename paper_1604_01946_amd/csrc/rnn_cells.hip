@@ -129,9 +129,9 @@ inline bool gru_persistent_shape(int cell, const Dims& d) {
   if (d.H == 2048) return d.B <= (gru ? 320 : 96);  // GRU: 105 TFLOP/s at any number of slices; step by step 99 at 256 rows, 105 at 384, 120 at 512
   // H <= 512: the rate on chip does not depend on the batch (slices of 64 rows, one after the other once the chip is
   // full), the step-by-step path gains with it; measured break-even (L = 4; TFLOP/s on chip / step by step at the
-  // limit): GRU H = 512 73 / 72 at 1024 rows, H = 256 57 / 43 at 2048, H = 128 31 / 14 at 2048; single gate H = 512
+  // limit): GRU H = 512 92 / 92 at 2048 rows, H = 256 57 / 43 at 2048, H = 128 31 / 14 at 2048; single gate H = 512
   // 31 / 29 at 512 rows, H = 256 22 / 19 at 2048, H = 128 11 / 5.5 at 2048
-  if (d.H == 512) return d.B <= (gru ? 1024 : 512);
+  if (d.H == 512) return d.B <= (gru ? 2048 : 512);
   if (d.H == 256) return d.B <= (gru ? 4096 : 2048);
   return d.H == 128 && d.B <= 8192;
 }

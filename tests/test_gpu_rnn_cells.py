@@ -146,6 +146,15 @@ def test_persistent_shapes(dims, cell, with_h0):
     run(cell, *dims, seed=5, with_h0=with_h0)
 
 
+# The GRU runs these shapes on the kernels with two alternating chains per slice; RNN_GRU_PP=0 keeps the one-chain
+# kernels (the ones the single-gate cells use) covered for it.
+@pytest.mark.parametrize("dims", [PERSISTENT[0], PERSISTENT[1], PERSISTENT[3], PERSISTENT[7], PERSISTENT[9]],
+                         ids=["4x7x64x512x512", "2x5x33x72x256", "1x3x48x512x512", "4x5x1x512x512", "3x3x130x256x256"])
+def test_gru_on_the_one_chain_kernels(dims, knobs):
+    knobs(RNN_GRU_PP="0")
+    run("gru", *dims, seed=6)
+
+
 # Stacks deeper than the chip holds at once: groups of consecutive layers, one launch per group
 DEEP = [(5, 4, 64, 512, 512), (6, 3, 130, 512, 512), (9, 3, 20, 48, 256), (17, 2, 8, 128, 128)]
 
