@@ -54,7 +54,7 @@ const Knobs& knobs() {
     k.gemm_swap = !env_is("LSTM_GEMM_SWAP", '0');
     k.large_pp = !env_is("LSTM_LARGE_PP", '0');
     k.large_ksplit = !env_is("LSTM_LARGE_KSPLIT", '0');
-    k.gru_pp = !env_is("RNN_GRU_PP", '0');
+    k.rnn_pp = !env_is("RNN_PINGPONG", '0');
     k.micro = env_is("LSTM_MICRO", '0') ? 0 : (env_is("LSTM_MICRO", '2') ? 2 : 1);
     k.spin_limit = env_int("LSTM_SPIN_LIMIT", 1, (1L << 30) - 1, 1 << 21);
     const char* ff = getenv("LSTM_FULL_FENCES");

@@ -8,7 +8,7 @@ namespace lstm {
 struct Knobs {
   bool no_pad;               // LSTM_NO_PAD=1: hidden sizes run as given instead of zero-padded to a persistent kernel's
   bool gemm_staged;          // LSTM_GEMM_STAGED=1: register-staged GEMM kernel everywhere
-  bool gru_pp;               // RNN_GRU_PP=0: the GRU on the one-chain wide kernels instead of the alternating ones
+  bool rnn_pp;               // RNN_PINGPONG=0: the GRU and the single-gate cells on the one-chain wide kernels instead of the alternating ones
   bool large_ksplit;         // LSTM_LARGE_KSPLIT=0: a single slice at H = 1024 backward on 64 workgroups instead of 256
   bool gemm_swap;            // LSTM_GEMM_SWAP=0: no exchange of the operands' roles in the large-tile GEMM
   bool large_pp;             // LSTM_LARGE_PP=0: the one-chain forward kernel at H = 2048 instead of the alternating one

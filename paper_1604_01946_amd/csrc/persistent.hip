@@ -610,7 +610,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   }
   // LSTM with every layer multiplying its input in the kernel: the two half-slices of 32 rows take turns inside the
   // waves (pers_fwd_pp_kernel); LSTM_PINGPONG=0 keeps the one-chain kernel
-  const bool pp = x_in_kernel && (cell == 0 || (cell == 1 && knobs().gru_pp)) && knobs().pingpong != 0;
+  const bool pp = x_in_kernel && (cell == 0 || knobs().rnn_pp) && knobs().pingpong != 0;
   if (!x_in_kernel) {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
     GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
@@ -770,7 +770,7 @@ int backward_layers(const BwdArgs& a, int cell, bool* bias_done, bool with_weigh
   }
   k.L = d.L; k.T = d.T; k.B = d.B; k.I = d.I; k.H = d.H; k.spin_limit = spin_limit(); k.full_fences = full_fences();
   // two alternating chains per workgroup (LSTM, slices of 64 rows): counters of H/16 lines per (layer, step, quarter)
-  const bool pp = wide && (cell == 0 || (cell == 1 && knobs().gru_pp)) && knobs().pingpong != 0;
+  const bool pp = wide && (cell == 0 || knobs().rnn_pp) && knobs().pingpong != 0;
   k.dummy = reinterpret_cast<float*>(a.ws + a.w.scratch);
   k.trace = (g_trace_bytes >= (size_t)d.T * 64 * (pp ? 2 : 1)) ? g_trace_buf : nullptr;
   k.trace_block = g_trace_block;

@@ -82,10 +82,11 @@ __device__ __forceinline__ gfloat* pick(bool c, const float* p, const float* q) 
 // pre-activations, to W_n x + b_n and to R_n h (the third has no recurrent weights, the fourth no input weights);
 // dh_{t-1} also receives the direct term dh_t o z_t (carried in `dc`); the reserve is h [T][B][H] followed by r, z, n,
 // R_n h as [T][B][4H]; `h0` takes the place of `c0`, dcT / dc0 are unused, R, W and db have 3H rows.
+// CELL = 2 / 3: single-gate RNN (ReLU / tanh): only the first K group is non-zero; the reserve holds h alone.
 template <int HH, int GA_, int PL_, int KH_, int FUSE_N_, bool TRACE, int CELL = 0>
 __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, const int NBH) {
   constexpr int H = HH, G = 4 * H, NS2 = H / 16, NL = NS2;
-  constexpr int NGW = CELL == 1 ? 3 : 4, GW = NGW * H;  // gate blocks and rows of R, W, db
+  constexpr int NGW = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1), GW = NGW * H;  // gate blocks and rows of R, W, db
   constexpr int NU = H / 16;             // groups of four units per wave (its K quarter)
   constexpr int RG = NU < 16 ? NU : 16;  // groups whose weights live in registers
   constexpr int LG = NU - RG;            // groups whose weights live in LDS
@@ -143,10 +144,10 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
       const int ug = w * NU + ((i + rot) & (NU - 1));
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int gm = (CELL == 1 && g == 3) ? 2 : g;  // matrix row block behind K group g
+        const int gm = CELL >= 2 ? 0 : ((CELL == 1 && g == 3) ? 2 : g);  // matrix row block behind K group g
         const size_t k = (size_t)(gm * H + 4 * ug + kq) * H;
-        const float v0 = (CELL == 0 || g != 2) ? Rl[k] : 0.f;
-        const float v1 = (live1 && (CELL == 0 || g != 3)) ? Wl[k] : 0.f;
+        const float v0 = (CELL == 0 || (CELL == 1 ? g != 2 : g == 0)) ? Rl[k] : 0.f;
+        const float v1 = (live1 && (CELL == 0 || (CELL == 1 ? g != 3 : g == 0))) ? Wl[k] : 0.f;
         if (i < RG) {
           wreg[i < RG ? i : 0][g][0] = v0;
           wreg[i < RG ? i : 0][g][1] = v1;
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   // B operand role: lane (kq, nn) fetches piece (nn/4)*16 + kq*4 + nn%4 of every 4-unit group of its K quarter
   const unsigned loff = (unsigned)(((lane & 15) >> 2) * 16 + (lane >> 4) * 4 + (lane & 3)) * 16;  // bytes
 
-  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
+  const float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : (CELL == 1 ? 5 : 1)) * H;
   const float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;
   const float* const res_c = CELL == 0 ? res_l + TB * 4 * H : res_l;  // c (LSTM) or h: the state array the step reads
   const float* const s0 = CELL == 0 ? a.c0 : a.h0;
@@ -224,12 +225,14 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
   float gi[2], gf[2], go[2], gg[2], ct[2], cp[2], dpre[2];
   bool cp_real[2];
   auto fetch_res = [&](const int c, const int t) {
-    const float* const pg = res_gates + (size_t)t * B * G + goff[c];
-    gi[c] = pg[0];
-    gf[c] = pg[H];
-    go[c] = pg[2 * H];
-    gg[c] = pg[3 * H];
-    if (CELL == 0) ct[c] = res_c[(size_t)t * B * H + eoff[c]];
+    if (CELL <= 1) {
+      const float* const pg = res_gates + (size_t)t * B * G + goff[c];
+      gi[c] = pg[0];
+      gf[c] = pg[H];
+      go[c] = pg[2 * H];
+      gg[c] = pg[3 * H];
+    }
+    if (CELL != 1) ct[c] = res_c[(size_t)t * B * H + eoff[c]];  // c_t (LSTM), h_t (single gate)
     const float* const pc = t > 0 ? res_c + (size_t)(t - 1) * B * H + eoff[c]
                                   : (s0 ? s0 + (size_t)l * B * H + eoff[c] : res_c + eoff[c]);
     cp[c] = *pc;
@@ -254,6 +257,9 @@ __global__ __launch_bounds__(256) void pers_bwd_pp_kernel(const PersBwdArgs a, c
       pw_d[2] = dh * tc * go[c] * (1.f - go[c]);
       pw_d[3] = dcv * gi[c] * (1.f - gg[c] * gg[c]);
       dc[c] = real ? dcv * gf[c] : dc[c];
+    } else if (CELL >= 2) {  // ct holds h_t
+      pw_d[0] = CELL == 3 ? dh * (1.f - ct[c] * ct[c]) : (ct[c] > 0.f ? dh : 0.f);
+      pw_d[1] = pw_d[2] = pw_d[3] = 0.f;
     } else {  // gi, gf, go, gg hold r, z, n, R_n h; cpv is h_{t-1}
       const float dn = dh * (1.f - gf[c]) * (1.f - go[c] * go[c]);
       pw_d[0] = dn * gg[c] * gi[c] * (1.f - gi[c]);
@@ -571,13 +577,18 @@ hipError_t launch_bpp(const PersBwdArgs& a, int nbh, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_bwd_pp(int cell, int H, const PersBwdArgs& a, int nbh, hipStream_t s) {  // cell 0: LSTM, 1: GRU
-  if (cell == 1) {
-    if (H == 512) return launch_bpp<512, 1>(a, nbh, s);
-    if (H == 256) return launch_bpp<256, 1>(a, nbh, s);
-    if (H == 128) return launch_bpp<128, 1>(a, nbh, s);
-    return hipErrorInvalidValue;
-  }
+template <int CELL>
+hipError_t launch_bpp_h(int H, const PersBwdArgs& a, int nbh, hipStream_t s) {
+  if (H == 512) return launch_bpp<512, CELL>(a, nbh, s);
+  if (H == 256) return launch_bpp<256, CELL>(a, nbh, s);
+  if (H == 128) return launch_bpp<128, CELL>(a, nbh, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_pp(int cell, int H, const PersBwdArgs& a, int nbh, hipStream_t s) {  // cell 0: LSTM, 1: GRU, 2: ReLU, 3: tanh
+  if (cell == 1) return launch_bpp_h<1>(H, a, nbh, s);
+  if (cell == 2) return launch_bpp_h<2>(H, a, nbh, s);
+  if (cell == 3) return launch_bpp_h<3>(H, a, nbh, s);
   if (cell != 0) return hipErrorInvalidValue;
   if (H == 512) return launch_bpp<512, 0>(a, nbh, s);
   if (H == 256) return launch_bpp<256, 0>(a, nbh, s);

@@ -48,9 +48,11 @@ constexpr int pp_count(int lo, int hi, int upto) { return upto < lo ? 0 : ((upto
 // gate multiplies the recurrent product): the four row groups of a workgroup's tile are then r, z, the input half of
 // n (W_n x, no recurrent weights) and the recurrent half of n (R_n h, no input weights); its reserve is h [T][B][H]
 // followed by r, z, n, R_n h as [T][B][4H], and `c0` is not used (the carried state is h).
+// CELL = 2 / 3: single-gate RNN with ReLU / tanh: only the first row group carries weights; the reserve is h [T][B][H].
 template <int HH, int GA_, int PF_, bool TRACE, int CELL = 0>
 __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
-  constexpr int H = HH, G = (CELL == 1 ? 3 : 4) * H, NS = H / 8, NL = H / 16;  // G: rows of W, R, b
+  constexpr int NGT = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1);  // gate blocks of W, R, b
+  constexpr int H = HH, G = NGT * H, NS = H / 8, NL = H / 16;  // G: rows of W, R, b
   constexpr int NK8 = H / 32;        // 8-k groups per wave and operand half (K-quarter of H)
   constexpr int NG = 2 * NK8;        // groups of a block: input half, then recurrent half
   constexpr int LAG = NK8 / 4;       // group at which the recurrent operand's fetch begins (its counter is looked at there)
@@ -89,8 +91,8 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     const float* Rl = a.R + (size_t)l * G * H;
     const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I] with I == H
     const int grp = n >> 3, par = (n >> 2) & 1, cc = n & 3;
-    const int gate = (CELL == 1 && grp == 3) ? 2 : grp;  // matrix row block behind tile row group grp
-    const bool useR = CELL == 0 || grp != 2, useW = CELL == 0 || grp != 3;
+    const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);  // matrix row block behind tile row group grp
+    const bool useR = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0), useW = CELL == 0 || (CELL == 1 ? grp != 3 : grp == 0);
     const size_t row = ((size_t)gate * H + u0 + 2 * cc + par) * H;
 #pragma unroll
     for (int i = 0; i < NK8; ++i) {
@@ -116,15 +118,15 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   for (int c = 0; c < 2; ++c) {
     bb[c] = a.b0 + 64 * sl + 32 * c + nr;
     valid[c] = bb[c] < B;
-    const float* const s0 = CELL == 0 ? a.c0 : a.h0;  // the carried state: c (LSTM), h (GRU)
+    const float* const s0 = CELL == 0 ? a.c0 : (CELL == 1 ? a.h0 : nullptr);  // the carried state: c (LSTM), h (GRU)
     c_state[c] = (valid[c] && s0) ? s0[((size_t)l * B + bb[c]) * H + unit] : 0.f;
   }
   float bias[4];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) bias[g] = (CELL == 0 || g < 3) ? a.bias[(size_t)l * G + g * H + unit] : 0.f;
+  for (int g = 0; g < 4; ++g) bias[g] = g < NGT ? a.bias[(size_t)l * G + g * H + unit] : 0.f;
 
-  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : 5) * H;
-  float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;
+  float* const res_l = a.res + (size_t)l * TB * (CELL == 0 ? 6 : (CELL == 1 ? 5 : 1)) * H;
+  float* const res_gates = CELL == 0 ? res_l : res_l + TB * H;  // LSTM, GRU
   float* const res_c = res_l + TB * 4 * H;  // LSTM only
   float* const res_h = CELL == 0 ? res_l + TB * 5 * H : res_l;
   float* const hx = a.hx + (size_t)sl * a.L * (T + 1) * H * 64;
@@ -267,6 +269,9 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
       cn = gf * c_state[c] + gi * gc;
       hn = go * tanhf_dev(cn);
       c_state[c] = cn;
+    } else if (CELL >= 2) {
+      gi = gf = go = gc = cn = 0.f;
+      hn = CELL == 3 ? tanhf_dev(sg[0]) : fmaxf(sg[0], 0.f);
     } else {  // sg: r and z pre-activations, W_n x + b_n, R_n h; the four saved values: r, z, n, R_n h
       gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]);
       go = tanhf_dev(sg[2] + gi * sg[3]);
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
     {  // gates: piece (array lane/16, row, half)
       const int arr = lane >> 4;
       const floatx4 v = *reinterpret_cast<const floatx4*>(st + arr * 64 + row * 8 + 4 * hf);
-      float* const dst = (in_batch && a.keep) ? res_gates + ((size_t)t * B + br) * 4 * H + (size_t)arr * H + u0 + 4 * hf : scratch_line;
+      float* const dst = (in_batch && a.keep && CELL <= 1) ? res_gates + ((size_t)t * B + br) * 4 * H + (size_t)arr * H + u0 + 4 * hf : scratch_line;
       *reinterpret_cast<floatx4*>(dst) = v;
     }
     {  // lanes 0-15: c, lanes 16-31: h (upper lanes repeat them into the scratch line)
@@ -418,13 +423,18 @@ hipError_t launch_pp(int grid, const PersFwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_fwd_pp(int cell, int H, int grid, const PersFwdArgs& a, hipStream_t s) {  // cell 0: LSTM, 1: GRU
-  if (cell == 1) {
-    if (H == 512) return launch_pp<512, 1>(grid, a, s);
-    if (H == 256) return launch_pp<256, 1>(grid, a, s);
-    if (H == 128) return launch_pp<128, 1>(grid, a, s);
-    return hipErrorInvalidValue;
-  }
+template <int CELL>
+hipError_t launch_pp_h(int H, int grid, const PersFwdArgs& a, hipStream_t s) {
+  if (H == 512) return launch_pp<512, CELL>(grid, a, s);
+  if (H == 256) return launch_pp<256, CELL>(grid, a, s);
+  if (H == 128) return launch_pp<128, CELL>(grid, a, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_fwd_pp(int cell, int H, int grid, const PersFwdArgs& a, hipStream_t s) {  // cell 0: LSTM, 1: GRU, 2: ReLU, 3: tanh
+  if (cell == 1) return launch_pp_h<1>(H, grid, a, s);
+  if (cell == 2) return launch_pp_h<2>(H, grid, a, s);
+  if (cell == 3) return launch_pp_h<3>(H, grid, a, s);
   if (cell != 0) return hipErrorInvalidValue;
   if (H == 512) return launch_pp<512, 0>(grid, a, s);
   if (H == 256) return launch_pp<256, 0>(grid, a, s);

@@ -146,13 +146,14 @@ def test_persistent_shapes(dims, cell, with_h0):
     run(cell, *dims, seed=5, with_h0=with_h0)
 
 
-# The GRU runs these shapes on the kernels with two alternating chains per slice; RNN_GRU_PP=0 keeps the one-chain
-# kernels (the ones the single-gate cells use) covered for it.
+# These cells run on the kernels with two alternating chains per slice (where x is multiplied inside the kernel, I == H,
+# forward; always backward); RNN_PINGPONG=0 keeps the one-chain kernels covered at those shapes.
+@pytest.mark.parametrize("cell", ["gru", "tanh", "relu"])
 @pytest.mark.parametrize("dims", [PERSISTENT[0], PERSISTENT[1], PERSISTENT[3], PERSISTENT[7], PERSISTENT[9]],
                          ids=["4x7x64x512x512", "2x5x33x72x256", "1x3x48x512x512", "4x5x1x512x512", "3x3x130x256x256"])
-def test_gru_on_the_one_chain_kernels(dims, knobs):
-    knobs(RNN_GRU_PP="0")
-    run("gru", *dims, seed=6)
+def test_cells_on_the_one_chain_kernels(dims, cell, knobs):
+    knobs(RNN_PINGPONG="0")
+    run(cell, *dims, seed=6)
 
 
 # Stacks deeper than the chip holds at once: groups of consecutive layers, one launch per group
