@@ -170,7 +170,7 @@ hipError_t launch_pack_x32(const float* x, float* xin, int* flags, int L, int T,
 // per chain, see persistent_pp.hip)
 hipError_t launch_fwd_pp(int cell, int H, int grid, const PersFwdArgs& a, hipStream_t s);  // cell 0: LSTM, 1: GRU
 hipError_t launch_pack_state_pp(const float* h0, float* hx, int L, int T, int B, int H, int b0, int nsl, hipStream_t s);
-hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int b0, int nsl, hipStream_t s);
+hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int I, int H, int b0, int nsl, hipStream_t s);
 
 // backward counterpart: two chains of 16 rows per workgroup (batch half), 16x16x4 tiles; counters of H/16 lines per
 // (layer, step, half, chain), see persistent_bpp.hip

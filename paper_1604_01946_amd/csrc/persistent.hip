@@ -602,7 +602,9 @@ int forward_layers(const FwdArgs& a, int cell) {
   // projection in the workspace.  LSTM_FWD_BATCHED_INPUT=1 keeps the batched product of Section 2.3 instead.
   // (Section 2.3 notes that batching the input products pays at some sizes and not at others; here the batched
   // product only wins where nothing would be idle otherwise: one layer, one slice -- by about 4 %.)
-  bool x_in_kernel = wide && d.I == d.H && !(d.L == 1 && d.B <= 64);
+  // (the kernels with two alternating chains also take I < H: x zero-padded to H columns in that copy)
+  const bool pp_ok = (cell == 0 || knobs().rnn_pp) && knobs().pingpong != 0;
+  bool x_in_kernel = wide && (d.I == d.H || (pp_ok && d.I < d.H)) && !(d.L == 1 && d.B <= 64);
   if (x_in_kernel) {
     if (knobs().fwd_batched_input) x_in_kernel = false;
     const size_t rows = (size_t)(d.B + 63) / 64 * 64;  // the copy of x: T+1 slots of H x 64 per slice
@@ -610,7 +612,7 @@ int forward_layers(const FwdArgs& a, int cell) {
   }
   // LSTM with every layer multiplying its input in the kernel: the two half-slices of 32 rows take turns inside the
   // waves (pers_fwd_pp_kernel); LSTM_PINGPONG=0 keeps the one-chain kernel
-  const bool pp = x_in_kernel && (cell == 0 || knobs().rnn_pp) && knobs().pingpong != 0;
+  const bool pp = x_in_kernel && pp_ok;
   if (!x_in_kernel) {
     ProfScope ps(LSTM_PHASE_FWD_INPUT_GEMM, s);
     GemmProblem p{a.x, a.W, P0, (int)TB, (int)G, d.I, d.I, 1, 1, d.I, (long)G, 0};
@@ -643,7 +645,7 @@ int forward_layers(const FwdArgs& a, int cell) {
       CK(launch_fill_zero(flags, (size_t)nsl * d.L * (d.T + 1) * counter_ints * 4, s), "zero step counters");
       if (pp) {
         CK(launch_pack_state_pp(a.h0, hx, d.L, d.T, d.B, d.H, k.b0, nsl, s), "pack h0");
-        if (x_in_kernel) CK(launch_pack_x_pp(a.x, P0, d.T, d.B, d.H, k.b0, nsl, s), "pack x");
+        if (x_in_kernel) CK(launch_pack_x_pp(a.x, P0, d.T, d.B, d.I, d.H, k.b0, nsl, s), "pack x");
       } else if (wide) {
         CK(launch_pack_state32(a.h0, hx, d.L, d.T, d.B, d.H, k.b0, nsl, s), "pack h0");
         if (x_in_kernel) {

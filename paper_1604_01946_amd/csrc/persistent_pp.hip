@@ -89,11 +89,13 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
   float wR[NK8][4], wW[NK8][4];
   {
     const float* Rl = a.R + (size_t)l * G * H;
-    const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I] with I == H
+    const float* Wl = l > 0 ? a.W + (size_t)G * a.I + (size_t)(l - 1) * G * H : a.W;  // layer 0: [G][I] with I <= H
+    const int Il = l > 0 ? H : a.I;  // columns of Wl (x comes zero-padded to H columns)
     const int grp = n >> 3, par = (n >> 2) & 1, cc = n & 3;
     const int gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);  // matrix row block behind tile row group grp
     const bool useR = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0), useW = CELL == 0 || (CELL == 1 ? grp != 3 : grp == 0);
     const size_t row = ((size_t)gate * H + u0 + 2 * cc + par) * H;
+    const size_t rowW = ((size_t)gate * H + u0 + 2 * cc + par) * Il;
 #pragma unroll
     for (int i = 0; i < NK8; ++i) {
       const int k8 = (i + rot) & (NK8 - 1);
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(256) void pers_fwd_pp_kernel(const PersFwdArgs a) {
       for (int j = 0; j < 4; ++j) {
         const int k = q * (H / 4) + 8 * k8 + 2 * j + kk;
         wR[i][j] = useR ? Rl[row + k] : 0.f;
-        wW[i][j] = useW ? Wl[row + k] : 0.f;
+        wW[i][j] = (useW && k < Il) ? Wl[rowW + k] : 0.f;
       }
     }
   }
@@ -382,18 +384,19 @@ __global__ void pack_state_pp_kernel(const float* __restrict__ h0, float* __rest
   }
 }
 
-// x [T][B][H] (I == H) -> slots 1..T of xin [nsl][T+1][2][H*32] in the layout above, rows past the batch zero.
+// x [T][B][I] (I <= H) -> slots 1..T of xin [nsl][T+1][2][H*32] in the layout above, rows past the batch and columns
+// past I zero (layer 0 then multiplies H columns like every other layer; its weights beyond column I are zero as well).
 // Block (kb, t, sl) moves the 64 batch rows x 64 inputs [64*kb, 64*kb+64) of one step through LDS: whole rows in,
 // one contiguous 8 KB piece of each chain's slot out.
 __global__ __launch_bounds__(256) void pack_x_pp_kernel(const float* __restrict__ x, float* __restrict__ xin, int T, int B,
-                                                        int H, int b0, int nsl) {
+                                                        int I, int H, int b0, int nsl) {
   __shared__ float tile[64][65];
   const int kb = blockIdx.x, t = blockIdx.y, sl = blockIdx.z;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int e = threadIdx.x + 256 * i, lb = e >> 6, kc = e & 63;
     const int bb = b0 + 64 * sl + lb;
-    tile[lb][kc] = bb < B ? x[((size_t)t * B + bb) * H + 64 * kb + kc] : 0.f;
+    tile[lb][kc] = (bb < B && 64 * kb + kc < I) ? x[((size_t)t * B + bb) * I + 64 * kb + kc] : 0.f;
   }
   __syncthreads();
 #pragma unroll
@@ -448,8 +451,8 @@ hipError_t launch_pack_state_pp(const float* h0, float* hx, int L, int T, int B,
   return hipGetLastError();
 }
 
-hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int H, int b0, int nsl, hipStream_t s) {
-  hipLaunchKernelGGL(pack_x_pp_kernel, dim3(H / 64, T, nsl), dim3(256), 0, s, x, xin, T, B, H, b0, nsl);
+hipError_t launch_pack_x_pp(const float* x, float* xin, int T, int B, int I, int H, int b0, int nsl, hipStream_t s) {
+  hipLaunchKernelGGL(pack_x_pp_kernel, dim3(H / 64, T, nsl), dim3(256), 0, s, x, xin, T, B, I, H, b0, nsl);
   return hipGetLastError();
 }
 
