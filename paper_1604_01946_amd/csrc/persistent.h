@@ -185,7 +185,7 @@ hipError_t launch_fwdL_any(int H, int cell, const PersFwdLArgs& k, hipStream_t s
 hipError_t launch_bwdL_any(int H, int cell, const PersBwdLArgs& k, hipStream_t s);
 hipError_t launch_pack_stateL(const float* h0, float* hx, int T, int B, int H, int b0, int nsl, hipStream_t s);
 // persistent_large_pp.hip: the LSTM forward kernel of the same shapes with two alternating chains of 16 rows per slice
-hipError_t launch_fwdLpp(int H, const PersFwdLArgs& k, hipStream_t s);
+hipError_t launch_fwdLpp(int cell, int H, const PersFwdLArgs& k, hipStream_t s);  // cell: 0 LSTM, 1 GRU, 2 ReLU, 3 tanh
 hipError_t launch_pack_stateLpp(const float* h0, float* hx, int T, int B, int H, int b0, int nsl, hipStream_t s);
 size_t fwdLpp_flag_ints();  // counter ints per (slice, step)
 

@@ -347,7 +347,7 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
   int cap = di.cus / (d.H / 8);
   if (cap < 1) cap = 1;
   if (cap > 4) cap = 4;
-  const bool lpp = cell == 0 && d.H == 2048 && knobs().large_pp;  // the LSTM at H = 2048: two alternating chains of 16 rows per slice
+  const bool lpp = (cell == 0 || knobs().rnn_pp) && d.H == 2048 && knobs().large_pp;  // the LSTM at H = 2048: two alternating chains of 16 rows per slice
   for (int l = 0; l < d.L; ++l) {
     const int Il = in_dim(d, l);
     const float* in = l == 0 ? a.x : a.reserve + (size_t)(l - 1) * rstride + res_h_offset(cell, TB, d.H);
@@ -382,7 +382,7 @@ int run_forward_persistent_large(const FwdArgs& a, int cell) {
     k.trace_block = g_trace_block;
     ProfScope ps(LSTM_PHASE_FWD_RECURRENCE, s);
     prof_flops(2.0 * G * d.H * std::min(32 * nsl, d.B - 32 * s0) * d.T, lpp ? "pers_fwdLpp_kernel" : "pers_fwdL_kernel");
-    if (lpp) CK(launch_fwdLpp(d.H, k, s), "persistent forward launch (large H, alternating chains)");
+    if (lpp) CK(launch_fwdLpp(cell, d.H, k, s), "persistent forward launch (large H, alternating chains)");
     else CK(launch_fwdL_any(d.H, cell, k, s), "persistent forward launch (large H)");
    }
   }

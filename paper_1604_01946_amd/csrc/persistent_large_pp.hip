@@ -34,8 +34,12 @@
 namespace lstm {
 namespace {
 
-template <int HH, int GA_, int QP_, int RG_, bool TRACE>
+// CELL as in pers_fwdL_kernel (0 LSTM, 1 GRU, 2 / 3 single gate with ReLU / tanh): only recurrent weights live here, so
+// the GRU's third row of a unit (W_n x + b_n) has none and arrives with the batched projection P [T*B][3H], its fourth
+// (R_n h) has no projection; `c0` carries h0 for the GRU; reserve layouts as in that kernel.
+template <int HH, int GA_, int QP_, int RG_, bool TRACE, int CELL = 0>
 __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) {
+  constexpr int NGT = CELL == 0 ? 4 : (CELL == 1 ? 3 : 1), GP = NGT * HH;  // gate blocks and rows of R, bias, P
   constexpr int H = HH, G = 4 * H, NS = H / 8;
   constexpr int KQ = H / 4;                 // k per wave
   constexpr int NQ = KQ / 16;               // operand requests per wave and chain-step
@@ -76,7 +80,9 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
         const int i = 4 * p + j;
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-          const float v = a.R[((size_t)(row & 3) * H + u0 + 4 * m + (row >> 2)) * H + (size_t)w * KQ + 16 * Q + 4 * kq + j];
+          const int grp = row & 3, gate = CELL >= 2 ? 0 : ((CELL == 1 && grp == 3) ? 2 : grp);
+          const bool live = CELL == 0 || (CELL == 1 ? grp != 2 : grp == 0);
+          const float v = live ? a.R[((size_t)gate * H + u0 + 4 * m + (row >> 2)) * H + (size_t)w * KQ + 16 * Q + 4 * kq + j] : 0.f;
           if (i < RG)
             wreg[i < RG ? i : 0][m] = v;
           else
@@ -93,20 +99,21 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
   const int bb = b0 + 16 * cf + n;
   const bool valid = bb < B;
   const int bc = valid ? bb : B - 1;  // rows past the batch read the last row (their results are not stored)
-  float c_state = (valid && a.c0) ? a.c0[(size_t)bb * H + unit] : 0.f;
+  float c_state = (CELL <= 1 && valid && a.c0) ? a.c0[(size_t)bb * H + unit] : 0.f;  // c_{t-1} (LSTM), h_{t-1} (GRU)
   float bias[4], pin[4];  // pin: the input product of the chain's next point-wise stage
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    bias[g] = a.bias[g * H + unit];
-    pin[g] = a.P[(size_t)bc * G + g * H + unit];
+    bias[g] = g < NGT ? a.bias[g * H + unit] : 0.f;
+    pin[g] = g < NGT ? a.P[(size_t)bc * GP + g * H + unit] : 0.f;
   }
   // Addresses of the point-wise stage's requests: a scalar base per array and step (scalar arithmetic costs a wave that
   // runs matrix instructions back to back nothing) plus one of two per-lane 32-bit offsets.
   const unsigned off_g = (unsigned)(((size_t)bc * G + unit) * 4), off_h = (unsigned)(((size_t)bc * H + unit) * 4);
+  const unsigned off_p = (unsigned)(((size_t)bc * GP + unit) * 4);
   const char* const p_base = reinterpret_cast<const char*>(a.P);
-  char* const res_gates = reinterpret_cast<char*>(a.res);
-  char* const res_c = reinterpret_cast<char*>(a.res + TB * 4 * H);
-  char* const res_h = reinterpret_cast<char*>(a.res + TB * 5 * H);
+  char* const res_gates = reinterpret_cast<char*>(CELL == 0 ? a.res : a.res + TB * H);  // the four saved arrays (LSTM, GRU)
+  char* const res_c = reinterpret_cast<char*>(a.res + TB * 4 * H);                       // LSTM only
+  char* const res_h = reinterpret_cast<char*>(CELL == 0 ? a.res + TB * 5 * H : a.res);
   char* const y_base = reinterpret_cast<char*>(a.y);
 
   PpWaiter<16> wt{a.watchdog, a.spin_limit, false};
@@ -141,10 +148,23 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
     float sg[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) sg[g] = ((s0[g] + s1[g]) + (s2[g] + s3[g])) + pin[g] + bias[g];
-    const float gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gc = tanhf_dev(sg[3]);
-    const float cn = gf * c_state + gi * gc;
-    const float hn = go * tanhf_dev(cn);
-    c_state = cn;
+    float gi, gf, go, gc, cn, hn;
+    if (CELL == 0) {
+      gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]), go = sigmoidf_dev(sg[2]), gc = tanhf_dev(sg[3]);
+      cn = gf * c_state + gi * gc;
+      hn = go * tanhf_dev(cn);
+      c_state = cn;
+    } else if (CELL == 1) {  // sg: r, z pre-activations; W_n x + b_n (from P); R_n h.  Saved: r, z, n, R_n h
+      gi = sigmoidf_dev(sg[0]), gf = sigmoidf_dev(sg[1]);
+      go = tanhf_dev(sg[2] + gi * sg[3]);
+      gc = sg[3];
+      hn = (1.f - gf) * go + gf * c_state;
+      cn = 0.f;
+      c_state = hn;
+    } else {
+      gi = gf = go = gc = cn = 0.f;
+      hn = CELL == 3 ? tanhf_dev(sg[0]) : fmaxf(sg[0], 0.f);
+    }
     __hip_atomic_store(slot(t + 1, cf) + (size_t)s * 128 + (mf * 16 + n) * 4 + q4, valid ? hn : 0.f, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
     // A load requested behind the publication (a word that is in the L2 cache anyway): requests retire in issue order,
@@ -158,18 +178,20 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
     if (valid) {
       unsigned og = off_g, oh = off_h;
       asm volatile("" : "+v"(og), "+v"(oh));  // (32-bit offsets met anew here: they become the offset operands of the stores)
-      char* const rg = res_gates + (size_t)t * B * G * 4;
-      *reinterpret_cast<float*>(rg + og) = gi;
-      *reinterpret_cast<float*>(rg + (size_t)H * 4 + og) = gf;
-      *reinterpret_cast<float*>(rg + (size_t)2 * H * 4 + og) = go;
-      *reinterpret_cast<float*>(rg + (size_t)3 * H * 4 + og) = gc;
+      if (CELL <= 1) {
+        char* const rg = res_gates + (size_t)t * B * G * 4;
+        *reinterpret_cast<float*>(rg + og) = gi;
+        *reinterpret_cast<float*>(rg + (size_t)H * 4 + og) = gf;
+        *reinterpret_cast<float*>(rg + (size_t)2 * H * 4 + og) = go;
+        *reinterpret_cast<float*>(rg + (size_t)3 * H * 4 + og) = gc;
+      }
       const size_t eb = (size_t)t * B * H * 4;
-      *reinterpret_cast<float*>(res_c + eb + oh) = cn;
+      if (CELL == 0) *reinterpret_cast<float*>(res_c + eb + oh) = cn;
       *reinterpret_cast<float*>(res_h + eb + oh) = hn;
       if (a.y) *reinterpret_cast<float*>(y_base + eb + oh) = hn;
       if (t == T - 1) {
         if (a.hT) a.hT[(size_t)bb * H + unit] = hn;
-        if (a.cT) a.cT[(size_t)bb * H + unit] = cn;
+        if (CELL == 0 && a.cT) a.cT[(size_t)bb * H + unit] = cn;
       }
     }
   };
@@ -235,11 +257,11 @@ __global__ __launch_bounds__(256) void pers_fwdLpp_kernel(const PersFwdLArgs a) 
             __hip_atomic_fetch_add(flag(tp + 1, o) + (s & 15) * kFlagStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           // the input product of the chain's next point-wise stage, a whole step ahead of its use
           const size_t tq = tp + 1 < T ? tp + 1 : tp;
-          unsigned og = off_g;
+          unsigned og = off_p;
           asm volatile("" : "+v"(og));
-          const char* const pb = p_base + tq * B * G * 4;
+          const char* const pb = p_base + tq * B * GP * 4;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) pin[g] = *reinterpret_cast<const float*>(pb + (size_t)g * H * 4 + og);
+          for (int g = 0; g < NGT; ++g) pin[g] = *reinterpret_cast<const float*>(pb + (size_t)g * H * 4 + og);
         }
         fresh_lo();
       }
@@ -278,12 +300,12 @@ __global__ void pack_stateLpp_kernel(const float* __restrict__ h0, float* __rest
   }
 }
 
-template <int HH, int GA, int QP, int RG>
+template <int HH, int GA, int QP, int RG, int CELL>
 hipError_t launch_fwdLpp_t(const PersFwdLArgs& a, hipStream_t s) {
   constexpr int NGR = HH / 16, LG = NGR > RG ? NGR - RG : 0;
   const size_t smem = (4096 + (size_t)4 * (LG / 2) * 64 * 4) * sizeof(float);
   const bool trace = a.trace != nullptr;
-  const void* fn = trace ? (const void*)pers_fwdLpp_kernel<HH, GA, QP, RG, true> : (const void*)pers_fwdLpp_kernel<HH, GA, QP, RG, false>;
+  const void* fn = trace ? (const void*)pers_fwdLpp_kernel<HH, GA, QP, RG, true, CELL> : (const void*)pers_fwdLpp_kernel<HH, GA, QP, RG, false, CELL>;
   static bool attr_set[2] = {false, false};
   if (hipError_t e = allow_dynamic_lds(fn, smem, attr_set[trace ? 1 : 0]); e != hipSuccess) return e;
   void* params[] = {const_cast<PersFwdLArgs*>(&a)};
@@ -295,13 +317,16 @@ hipError_t launch_fwdLpp_t(const PersFwdLArgs& a, hipStream_t s) {
 // Counter ints per (slice, step): two chains x 16 lines
 size_t fwdLpp_flag_ints() { return (size_t)2 * 16 * kFlagStride; }
 
-hipError_t launch_fwdLpp(int H, const PersFwdLArgs& a, hipStream_t s) {
+hipError_t launch_fwdLpp(int cell, int H, const PersFwdLArgs& a, hipStream_t s) {  // cell: 0 LSTM, 1 GRU, 2 ReLU, 3 tanh
   // Schedule, measured at B = 32, T = 50 (ms per launch): (GA, QP) = (14, 22) 3.60, (10, 24) 2.97, (8, 26) 2.14,
   // (4, 26) 1.97, (4, 28) 1.98, (2, 26) 1.97 -- the earlier a publication is completed and the later its counter is
   // looked at, the fewer polls get in the way of the arrivals they wait for; 64 groups of weights in registers (96:
   // 2.08, all 128: 2.24; the one-chain kernel: 2.40).  At H = 1024 a block is too short to cover the exchange (best
   // schedule 1.44 ms against 1.31 for the one-chain kernel at L = 4, B = 32): that size stays on pers_fwdL_kernel.
-  if (H == 2048) return launch_fwdLpp_t<2048, 4, 26, 64>(a, s);
+  if (H == 2048) {
+    return cell == 0 ? launch_fwdLpp_t<2048, 4, 26, 64, 0>(a, s) : (cell == 1 ? launch_fwdLpp_t<2048, 4, 26, 64, 1>(a, s)
+                     : (cell == 2 ? launch_fwdLpp_t<2048, 4, 26, 64, 2>(a, s) : launch_fwdLpp_t<2048, 4, 26, 64, 3>(a, s)));
+  }
   return hipErrorInvalidValue;
 }
 
